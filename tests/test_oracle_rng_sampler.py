@@ -128,11 +128,11 @@ def test_sampler_limits_ties_and_gap(orc):
 def test_sampler_exact_ties_go_to_the_lowest_index(orc):
     # two entries so large that the fp32 sum z + g absorbs the noise: an exact tie
     z = np.zeros(32)
-    z[[9, 20]] = 1e30
+    z[[9, 20]] = 1e9
     for s in range(30):
         tok, lp, gap = orc.sample(z, 1.0, 5, 0, s)
         assert tok == 9 and gap == 0.0
-        assert lp == pytest.approx(-np.log(2.0), abs=1e-12)
+        assert lp == pytest.approx(-np.log(2.0), abs=1e-6)
 
 
 def test_sampler_decides_in_fp32_in_both_builds(orc, orc32):
