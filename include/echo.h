@@ -1,0 +1,149 @@
+/*
+ * echo.h -- C ABI of the MI355X rollout-generation library.
+ *
+ * The library is the GPU side of a rollout worker as ECHO-2 states the problem:
+ * a worker holds a locally installed policy snapshot of some version, draws
+ * responses y ~ pi_v(. | x) for prompts x, and emits them tagged with that version
+ * (Sec. 3.2 "Rollout generation"; Algorithm 1, rollout-plane loop); the learner's
+ * truncated importance ratio needs the sampler's own per-token probability
+ * (App. "GRPO-Style Policy Gradient Objective"); a worker switches to a new
+ * snapshot once it is completely installed (Sec. 3.3).  The policy is a dense
+ * decoder-only transformer (RMSNorm, grouped-query attention with rotary
+ * embeddings, SwiGLU, no biases); every step of the path runs in HIP kernels for
+ * gfx950.  One context drives one GPU.  There is no CPU fallback.
+ *
+ * Conventions: all functions return 0 on success or a negative echo_status; they
+ * never throw, abort or print.  "host" / "device" in a parameter comment says
+ * where the pointer must live.  The caller owns every buffer it passes in.
+ */
+#ifndef ECHO_H_
+#define ECHO_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct echo_ctx echo_ctx; /* opaque, one per GPU */
+
+typedef enum {
+  ECHO_OK = 0,
+  ECHO_EINVAL = -1, /* bad argument or shape */
+  ECHO_ENOMEM = -2, /* arena too small / request exceeds max_seqs or max_ctx */
+  ECHO_ESTATE = -3, /* no policy installed, version not increasing, swap never staged */
+  ECHO_EHIP = -4    /* a HIP runtime call failed */
+} echo_status;
+
+enum { ECHO_F32 = 0, ECHO_BF16 = 1 };
+
+/* Decoder shape and capacity.  dtype selects the storage type of weights and KV cache:
+ * ECHO_BF16 runs the MFMA kernels (bf16 operands, fp32 accumulation, fp32 residual stream);
+ * ECHO_F32 runs the all-fp32 debug kernels.  debug_naive = 1 with ECHO_BF16 keeps bf16
+ * weights but runs the debug kernels on them (fp32 activations and KV cache). */
+typedef struct {
+  int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+  float rms_eps, rope_base;
+  int32_t dtype;
+  int32_t qk_norm;        /* 1: per-head RMSNorm on q and k before the rotary embedding */
+  int32_t tie_embeddings; /* 1: lm_head is the embedding table (absent from the blob) */
+  int32_t max_seqs;       /* KV-cache capacity in sequences (P*G of the largest rollout) */
+  int32_t max_ctx;        /* KV-cache capacity in tokens per sequence (prompt + generated) */
+  int32_t n_weight_slots; /* 1, or 2 to install a snapshot while another is decoding */
+  int32_t debug_naive;
+} echo_model_desc;
+
+/* Optional rollout controls (a NULL opts means: none of them). */
+typedef struct {
+  const int32_t *stop_lens;    /* host [N] or NULL: sequence n ends after min(max_new, stop_lens[n]) tokens */
+  int32_t eos_id;              /* >= 0: a sequence also ends after emitting this token (kept); -1: none */
+  float top_p;                 /* nucleus mass; only 1.0 (no truncation) is implemented */
+  int32_t n_swaps;             /* snapshot switches pinned inside this rollout */
+  const int32_t *swap_at_step; /* host [n_swaps], ascending, >= 1: from generation step k on, the forward
+                                  passes use the snapshot staged by echo_load_policy (the call waits for it,
+                                  at most swap_timeout_ms); the KV cache built so far is kept */
+  int32_t swap_timeout_ms;     /* 0 = 10000 */
+  const int32_t *forced_tokens; /* host [N, max_new] or NULL: teacher forcing -- the sampled token and its
+                                   log-prob are still returned, the token fed back is the forced one */
+  float *debug_logits;         /* host [N, max_new, vocab] or NULL: also return the raw logits (uses the
+                                  unfused sampler; sizes the caller can afford only) */
+  int32_t unfused_sampler;     /* 1: write logits to HBM and sample from them with the fp32 debug sampler */
+  int32_t no_graph;            /* 1: launch decode steps kernel by kernel instead of replaying a HIP graph */
+  int32_t time_kernels;        /* 1: bracket decode-attention and GEMM launches with HIP events (implies
+                                  no_graph); durations are read back with echo_stats */
+} echo_rollout_opts;
+
+typedef struct {
+  int64_t active_version, staged_version; /* -1 when none */
+  int32_t decode_steps;                   /* decode forward passes of the last rollout */
+  float prefill_ms, decode_ms, total_ms;  /* wall time of the last rollout, by phase */
+  float swap_wait_ms;                     /* time the last rollout waited for staged snapshots */
+  /* filled by a rollout run with time_kernels = 1 (sums over all timed launches): */
+  int64_t attn_launches;
+  double attn_ms, attn_bytes; /* decode attention: HIP-event time, K/V bytes it had to read */
+  int64_t gemm_launches;
+  double gemm_ms, gemm_bytes; /* weight-streaming GEMMs: HIP-event time, weight bytes read */
+} echo_stats_t;
+
+/* Bytes of device memory a context of this shape needs (weights x slots, KV cache, activations);
+ * 0 if the shape is invalid. */
+size_t echo_arena_bytes(const echo_model_desc *desc);
+
+/* Bytes of one policy blob for this shape (see echo_load_policy); 0 if the shape is invalid. */
+size_t echo_blob_bytes(const echo_model_desc *desc);
+
+/* Create a context on `device`.  dev_arena (device, >= echo_arena_bytes, 256-byte aligned) is owned by the
+ * caller and must outlive the context; compute_stream / copy_stream are hipStream_t handles of default
+ * priority (the caller's; NULL = the null stream).  *out receives the context. */
+int echo_init(const echo_model_desc *desc, int device, void *dev_arena, size_t arena_bytes,
+              void *compute_stream, void *copy_stream, echo_ctx **out);
+
+/* Install policy snapshot `version` (Sec. 3.2-3.3: immutable snapshots, versions only advance).
+ * host_weights (host, nbytes = echo_blob_bytes) is a flat row-major [out,in] blob in the model dtype:
+ *   embed[V,d]; per layer attn_norm[d], wq[Hq*hd,d], wk[Hkv*hd,d], wv[Hkv*hd,d], (q_norm[hd], k_norm[hd]),
+ *   wo[d,Hq*hd], ffn_norm[d], w_gate[F,d], w_up[F,d], w_down[d,F]; final_norm[d]; lm_head[V,d] (if untied).
+ * The blob is copied and repacked on the GPU (copy stream) into the inactive weight slot; it may be freed
+ * when the call returns.  With no rollout running the snapshot becomes active at once; while a rollout runs
+ * (call from another thread; needs n_weight_slots = 2) it is staged and becomes active at the rollout's next
+ * pinned swap step, or when the rollout ends.  ECHO_ESTATE if version <= the newest installed version or if
+ * a staged snapshot is still waiting. */
+int echo_load_policy(echo_ctx *ctx, int64_t version, const void *host_weights, size_t nbytes);
+
+/* Generate G samples for each of n_prompts prompts (sequence n = p*G + g) by ancestral sampling from
+ * softmax(logits / temperature) (Algorithm 1, "sample and generate y ~ pi(.|x)"), up to max_new tokens each.
+ * The draw for vocabulary entry i of sequence n at step s is the Gumbel-max rule on a counter-based uniform
+ * keyed by (seed; n, s, i), so a sequence's result does not depend on what else is in the batch.
+ *   prompt_tokens  host [n_prompts, prompt_stride]; prompt_lens host [n_prompts], each in 1..prompt_stride
+ *   out_tokens     host [N, max_new], pad -1        out_logprobs host [N, max_new], pad 0
+ *   out_lens       host [N]                         out_versions host [N, max_new], pad -1 (nullable)
+ * out_logprobs[n][s] = log softmax(logits/temperature)[out_tokens[n][s]].
+ * ECHO_ENOMEM if N > max_seqs or prompt_len + max_new > max_ctx; ECHO_ESTATE without a policy. */
+int echo_rollout(echo_ctx *ctx, const int32_t *prompt_tokens, int32_t prompt_stride, const int32_t *prompt_lens,
+                 int32_t n_prompts, int32_t G, int32_t max_new, float temperature, uint64_t seed,
+                 const echo_rollout_opts *opts, int32_t *out_tokens, float *out_logprobs, int32_t *out_lens,
+                 int64_t *out_versions);
+
+/* Teacher-forced scoring under the active snapshot (the learner-side pi(y_t | x, y_<t) of the importance
+ * ratio): out[n][t] = log softmax(logits_{t-1}/temperature)[tokens[n][t]] for 1 <= t < lens[n], else 0.
+ *   tokens host [n_seqs, stride]; lens host [n_seqs]; out host [n_seqs, stride]. */
+int echo_logprobs(echo_ctx *ctx, const int32_t *tokens, int32_t stride, const int32_t *lens, int32_t n_seqs,
+                  float temperature, float *out_logprobs);
+
+/* Raw 32-bit draws of the sampler's generator for (seed; n, s, i = i0..i0+count-1), computed on the GPU
+ * (out: host [count]).  Exists so that the generator can be compared bit for bit with its definition. */
+int echo_debug_draw_bits(echo_ctx *ctx, uint64_t seed, uint32_t n, uint32_t s, uint32_t i0, int32_t count,
+                         uint32_t *out_bits);
+
+int echo_stats(echo_ctx *ctx, echo_stats_t *out);
+
+/* Message for the last error on this context (ctx-owned, valid until the next call); "" if none.
+ * With ctx == NULL: the message of the last failed echo_init on this thread. */
+const char *echo_last_error(const echo_ctx *ctx);
+
+void echo_destroy(echo_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ECHO_H_ */

@@ -1,0 +1,842 @@
+// Host engine behind the C ABI: arena planning, snapshot install and swap, prefill, the decode loop
+// (one HIP graph per snapshot, replayed per generation step), teacher-forced scoring, statistics.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <chrono>
+#include <condition_variable>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "../../include/echo.h"
+#include "echo_kernels.h"
+
+using namespace echo;
+
+namespace {
+
+thread_local std::string g_init_error;
+
+struct LayerW {
+  const void *attn_norm, *wqkv, *q_norm, *k_norm, *wo, *ffn_norm, *wgu, *wdown;
+};
+struct Slot {
+  int64_t version = -1;
+  char *base = nullptr;
+  const void *embed = nullptr, *final_norm = nullptr, *lm_head = nullptr;
+  std::vector<LayerW> layers;
+};
+
+struct Bump {  // plans offsets inside the caller's arena
+  size_t off = 0;
+  size_t take(size_t bytes) { size_t o = off; off += (bytes + 255) / 256 * 256; return o; }
+};
+
+struct Plan {
+  bool ok = false, fast = false;
+  int elt = 4;                  // bytes per weight element
+  int Mcap = 0;                 // row capacity of one pass
+  int Np_qkv, Np_d, Np_gu, Np_v, Kp_d, Kp_q, Kp_f;
+  size_t slot_bytes, o_slot[2], o_kv, kv_bytes;
+  size_t o_h, o_x, o_qkv, o_att, o_gu, o_ff, o_logits, o_q16, o_xa, o_xatt, o_xff, o_part, o_rope, o_lmpart;
+  size_t o_attn_o, o_attn_ml;
+  size_t o_rows, o_seq, o_samp, o_out_tok, o_out_lp, o_out_ver, o_forced, o_scal, o_first_h, o_stage, o_maps;
+  size_t stage_bytes, part_floats, total;
+  int attn_chunk, attn_max_splits;
+};
+
+constexpr int PREFILL_ROWS = 256;
+constexpr size_t STAGE_BYTES = (size_t)64 << 20;
+constexpr int MAX_GRID_SPLIT = 8;
+
+int pad_rows(int m) {  // 32 * pow2 up to 256, then multiples of 256
+  int p = 32;
+  while (p < m && p < 256) p *= 2;
+  if (m > 256) p = (int)round_up(m, 256);
+  return p;
+}
+
+size_t packed_bytes(int64_t N, int64_t K) { return (size_t)(round_up(N, 32) * round_up(K, 16) * 2); }
+
+bool valid_desc(const echo_model_desc *d, std::string *why) {
+  auto bad = [&](const char *m) { if (why) *why = m; return false; };
+  if (!d) return bad("desc is NULL");
+  if (d->n_layers < 1 || d->hidden < 1 || d->n_q_heads < 1 || d->n_kv_heads < 1 || d->head_dim < 2 || d->ffn < 1 || d->vocab < 1)
+    return bad("non-positive model dimension");
+  if (d->n_q_heads % d->n_kv_heads) return bad("n_q_heads must be a multiple of n_kv_heads");
+  if (d->head_dim % 2 || d->head_dim > 256) return bad("head_dim must be even and <= 256");
+  if (d->dtype != ECHO_F32 && d->dtype != ECHO_BF16) return bad("dtype must be ECHO_F32 or ECHO_BF16");
+  if (d->max_seqs < 1 || d->max_ctx < 2) return bad("max_seqs / max_ctx too small");
+  if (d->n_weight_slots != 1 && d->n_weight_slots != 2) return bad("n_weight_slots must be 1 or 2");
+  if (!(d->rms_eps >= 0.f) || !(d->rope_base > 0.f)) return bad("rms_eps / rope_base out of range");
+  bool fast = d->dtype == ECHO_BF16 && !d->debug_naive;
+  if (fast) {
+    if (d->hidden % 16 || d->ffn % 16 || (d->n_q_heads * d->head_dim) % 16) return bad("bf16 path needs hidden, ffn and Hq*head_dim multiples of 16");
+    if (d->hidden > 8192) return bad("bf16 path needs hidden <= 8192");
+    if (d->head_dim % 64) return bad("bf16 path needs head_dim a multiple of 64");
+    int grp = d->n_q_heads / d->n_kv_heads;
+    if (grp > 8 || (grp & (grp - 1))) return bad("bf16 path needs Hq/Hkv in {1,2,4,8}");
+  }
+  return true;
+}
+
+int64_t blob_numel(const echo_model_desc *d) {
+  int64_t h = d->hidden, hd = d->head_dim, q = (int64_t)d->n_q_heads * hd, kv = (int64_t)d->n_kv_heads * hd;
+  int64_t per = h + q * h + 2 * kv * h + (d->qk_norm ? 2 * hd : 0) + h * q + h + 3 * (int64_t)d->ffn * h;
+  return (int64_t)d->vocab * h + d->n_layers * per + h + (d->tie_embeddings ? 0 : (int64_t)d->vocab * h);
+}
+
+Plan make_plan(const echo_model_desc *d) {
+  Plan p;
+  if (!valid_desc(d, nullptr)) return p;
+  p.fast = d->dtype == ECHO_BF16 && !d->debug_naive;
+  p.elt = d->dtype == ECHO_BF16 ? 2 : 4;
+  int64_t H = d->hidden, hd = d->head_dim, Q = (int64_t)d->n_q_heads * hd, KV = (int64_t)d->n_kv_heads * hd, F = d->ffn, V = d->vocab;
+  p.Mcap = std::max(pad_rows(d->max_seqs), PREFILL_ROWS);
+  p.Np_qkv = (int)round_up(Q + 2 * KV, 32); p.Np_d = (int)round_up(H, 32); p.Np_gu = (int)round_up(2 * F, 32);
+  p.Np_v = (int)round_up(V, 32);
+  p.Kp_d = (int)round_up(H, 16); p.Kp_q = (int)round_up(Q, 16); p.Kp_f = (int)round_up(F, 16);
+  Bump b;
+  if (p.fast) {
+    size_t per = 2 * H * 2 + (d->qk_norm ? 2 * hd * 2 : 0) + 4 * 256 /*alignment slack*/ + packed_bytes(Q + 2 * KV, H) +
+                 packed_bytes(H, Q) + packed_bytes(2 * F, H) + packed_bytes(H, F);
+    p.slot_bytes = (size_t)V * H * 2 + 256 + H * 2 + 256 + packed_bytes(V, H) + d->n_layers * (per + 8 * 256);
+  } else {
+    p.slot_bytes = (size_t)blob_numel(d) * p.elt;
+  }
+  for (int s = 0; s < d->n_weight_slots; ++s) p.o_slot[s] = b.take(p.slot_bytes);
+  int kv_elt = p.fast ? 2 : 4;
+  p.kv_bytes = (size_t)d->max_seqs * d->n_layers * 2 * d->n_kv_heads * d->max_ctx * hd * kv_elt;
+  p.o_kv = b.take(p.kv_bytes);
+  size_t M = p.Mcap;
+  p.o_h = b.take(M * H * 4);
+  p.o_first_h = b.take((size_t)d->max_seqs * H * 4);
+  p.o_logits = b.take(M * (size_t)p.Np_v * 4);
+  p.o_rope = b.take(M * hd * 4);
+  if (p.fast) {
+    p.o_xa = b.take(M * p.Kp_d * 2);
+    p.o_xatt = b.take(M * p.Kp_q * 2);
+    p.o_xff = b.take(M * p.Kp_f * 2);
+    p.o_q16 = b.take(M * Q * 2);
+    p.part_floats = (size_t)MAX_GRID_SPLIT * std::max(p.Np_qkv, p.Np_d) * M;
+    p.o_part = b.take(p.part_floats * 4);
+    p.o_lmpart = b.take(fast_lmhead_partial_floats(p.Np_v, (int)M) * 4);
+    p.attn_chunk = 256;
+    p.attn_max_splits = (d->max_ctx + p.attn_chunk - 1) / p.attn_chunk;
+    p.o_attn_o = b.take(M * d->n_q_heads * (size_t)p.attn_max_splits * hd * 4);
+    p.o_attn_ml = b.take(M * d->n_q_heads * (size_t)p.attn_max_splits * 2 * 4);
+    p.stage_bytes = STAGE_BYTES;
+    p.o_stage = b.take(p.stage_bytes);
+  } else {
+    p.o_x = b.take(M * H * 4);
+    p.o_qkv = b.take(M * (Q + 2 * KV) * 4);
+    p.o_att = b.take(M * Q * 4);
+    p.o_gu = b.take(M * 2 * F * 4);
+    p.o_ff = b.take(M * F * 4);
+  }
+  p.o_rows = b.take(4 * M * 4);
+  p.o_maps = b.take(2 * M * 4 + (size_t)d->max_seqs * 4);
+  p.o_seq = b.take(3 * (size_t)d->max_seqs * 4);
+  p.o_samp = b.take(4 * M * 4);
+  size_t outn = (size_t)d->max_seqs * d->max_ctx;
+  p.o_out_tok = b.take(outn * 4);
+  p.o_out_lp = b.take(outn * 4);
+  p.o_out_ver = b.take(outn * 8);
+  p.o_forced = b.take(outn * 4);
+  p.o_scal = b.take(256);
+  p.total = b.off;
+  p.ok = true;
+  return p;
+}
+
+}  // namespace
+
+struct echo_ctx {
+  echo_model_desc d;
+  Plan p;
+  int device = 0;
+  char *arena = nullptr;
+  hipStream_t cs = nullptr, ks = nullptr;  // compute, copy
+  bool own_cs = false, own_ks = false;
+  Slot slots[2];
+  int active = -1, staged = -1;
+  hipEvent_t staged_ev = nullptr;
+  bool rollout_running = false;
+  std::mutex mu;
+  std::condition_variable cv;
+  std::string err;
+  echo_stats_t st;
+  // device views
+  RowState rows;
+  KvGeom kv;
+  int32_t *d_prompt_len_seq, *d_gen_len, *d_limit, *d_samp_tok, *d_target, *d_step, *d_n_active, *d_map_a, *d_map_b, *d_plen_p;
+  float *d_samp_lp, *d_target_lp;
+  hipGraphExec_t graph = nullptr;
+  // kernel timing (time_kernels)
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> ev_attn, ev_gemm;
+  bool timing = false;
+  double t_attn_bytes = 0, t_gemm_bytes = 0, cur_attn_bytes = 0;
+};
+
+namespace {
+
+int fail(echo_ctx *c, int code, const char *fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (c) c->err = buf; else g_init_error = buf;
+  return code;
+}
+
+#define HIPCHK(c, expr)                                                                      \
+  do {                                                                                       \
+    hipError_t e_ = (expr);                                                                  \
+    if (e_ != hipSuccess) return fail(c, ECHO_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+template <typename T> T *at(echo_ctx *c, size_t off) { return (T *)(c->arena + off); }
+
+void bind_slot(echo_ctx *c, int s) {
+  const echo_model_desc &d = c->d;
+  Slot &S = c->slots[s];
+  S.base = c->arena + c->p.o_slot[s];
+  S.layers.assign(d.n_layers, LayerW{});
+  int64_t H = d.hidden, hd = d.head_dim, Q = (int64_t)d.n_q_heads * hd, KV = (int64_t)d.n_kv_heads * hd, F = d.ffn, V = d.vocab;
+  if (!c->p.fast) {  // the raw blob itself
+    size_t e = c->p.elt;
+    char *p = S.base;
+    S.embed = p; p += V * H * e;
+    for (int l = 0; l < d.n_layers; ++l) {
+      LayerW &L = S.layers[l];
+      L.attn_norm = p; p += H * e;
+      L.wqkv = p; p += (Q + 2 * KV) * H * e;
+      if (d.qk_norm) { L.q_norm = p; p += hd * e; L.k_norm = p; p += hd * e; }
+      L.wo = p; p += H * Q * e;
+      L.ffn_norm = p; p += H * e;
+      L.wgu = p; p += 2 * F * H * e;
+      L.wdown = p; p += H * F * e;
+    }
+    S.final_norm = p; p += H * e;
+    S.lm_head = d.tie_embeddings ? S.embed : p;
+    return;
+  }
+  Bump b;
+  auto take = [&](size_t n) { return (const void *)(S.base + b.take(n)); };
+  S.embed = take((size_t)V * H * 2);
+  S.final_norm = take(H * 2);
+  S.lm_head = take(packed_bytes(V, H));
+  for (int l = 0; l < d.n_layers; ++l) {
+    LayerW &L = S.layers[l];
+    L.attn_norm = take(H * 2);
+    L.ffn_norm = take(H * 2);
+    if (d.qk_norm) { L.q_norm = take(hd * 2); L.k_norm = take(hd * 2); }
+    L.wqkv = take(packed_bytes(Q + 2 * KV, H));
+    L.wo = take(packed_bytes(H, Q));
+    L.wgu = take(packed_bytes(2 * F, H));
+    L.wdown = take(packed_bytes(H, F));
+  }
+}
+
+// Copy a row-major bf16 matrix from the host blob through the staging buffer into a packed weight.
+int stage_matrix(echo_ctx *c, const void *dst, const char *src, int64_t rows, int K, int64_t dst_row0, int stride) {
+  int Kp = (int)round_up(K, 16);
+  int64_t row_bytes = (int64_t)K * 2, rows_per = std::max<int64_t>(1, (int64_t)(c->p.stage_bytes / 2) / row_bytes);
+  static int flip = 0;
+  for (int64_t r = 0; r < rows; r += rows_per) {
+    int64_t n = std::min(rows_per, rows - r);
+    char *stg = c->arena + c->p.o_stage + (flip ? c->p.stage_bytes / 2 : 0);
+    flip ^= 1;
+    HIPCHK(c, hipMemcpyAsync(stg, src + r * row_bytes, (size_t)(n * row_bytes), hipMemcpyHostToDevice, c->ks));
+    fast_pack_weight((void *)dst, stg, dst_row0 + r * stride, stride, n, K, Kp, c->ks);
+  }
+  return 0;
+}
+
+int install(echo_ctx *c, int s, const char *blob) {
+  const echo_model_desc &d = c->d;
+  Slot &S = c->slots[s];
+  if (!c->p.fast) {
+    size_t total = c->p.slot_bytes, step = (size_t)256 << 20;
+    for (size_t o = 0; o < total; o += step)
+      HIPCHK(c, hipMemcpyAsync(S.base + o, blob + o, std::min(step, total - o), hipMemcpyHostToDevice, c->ks));
+    return 0;
+  }
+  int64_t H = d.hidden, hd = d.head_dim, Q = (int64_t)d.n_q_heads * hd, KV = (int64_t)d.n_kv_heads * hd, F = d.ffn, V = d.vocab;
+  HIPCHK(c, hipMemsetAsync(S.base, 0, c->p.slot_bytes, c->ks));  // zero rows/columns of padding
+  const char *p = blob;
+  auto raw = [&](const void *dst, size_t bytes) -> int {
+    HIPCHK(c, hipMemcpyAsync((void *)dst, p, bytes, hipMemcpyHostToDevice, c->ks));
+    p += bytes;
+    return 0;
+  };
+  int rc;
+  const char *embed_src = p;
+  if ((rc = raw(S.embed, (size_t)V * H * 2))) return rc;
+  for (int l = 0; l < d.n_layers; ++l) {
+    LayerW &L = S.layers[l];
+    if ((rc = raw(L.attn_norm, H * 2))) return rc;
+    if ((rc = stage_matrix(c, L.wqkv, p, Q + 2 * KV, (int)H, 0, 1))) return rc;
+    p += (Q + 2 * KV) * H * 2;
+    if (d.qk_norm) { if ((rc = raw(L.q_norm, hd * 2))) return rc; if ((rc = raw(L.k_norm, hd * 2))) return rc; }
+    if ((rc = stage_matrix(c, L.wo, p, H, (int)Q, 0, 1))) return rc;
+    p += H * Q * 2;
+    if ((rc = raw(L.ffn_norm, H * 2))) return rc;
+    if ((rc = stage_matrix(c, L.wgu, p, F, (int)H, 0, 2))) return rc;  // gate -> even rows
+    p += F * H * 2;
+    if ((rc = stage_matrix(c, L.wgu, p, F, (int)H, 1, 2))) return rc;  // up   -> odd rows
+    p += F * H * 2;
+    if ((rc = stage_matrix(c, L.wdown, p, H, (int)F, 0, 1))) return rc;
+    p += H * F * 2;
+  }
+  if ((rc = raw(S.final_norm, H * 2))) return rc;
+  if ((rc = stage_matrix(c, S.lm_head, d.tie_embeddings ? embed_src : p, V, (int)H, 0, 1))) return rc;
+  return 0;
+}
+
+// ---- one forward pass over M rows (row state already on the device) ----------------------------------------
+struct TimerScope {
+  echo_ctx *c; std::vector<std::pair<hipEvent_t, hipEvent_t>> *v; hipEvent_t a = nullptr, b = nullptr;
+  TimerScope(echo_ctx *c_, std::vector<std::pair<hipEvent_t, hipEvent_t>> *v_) : c(c_), v(v_) {
+    if (!c->timing) return;
+    if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { a = b = nullptr; return; }
+    hipEventRecord(a, c->cs);
+  }
+  ~TimerScope() { if (a && b) { hipEventRecord(b, c->cs); v->push_back({a, b}); } }
+};
+
+void gemm_fast(echo_ctx *c, void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, GemmEpilogue epi, int *nsplit_out) {
+  int ns, wk;
+  fast_gemm_pick(Np, Kp, Mp, &ns, &wk);
+  if (epi == EPI_SWIGLU) ns = 1;
+  if (ns > MAX_GRID_SPLIT) ns = MAX_GRID_SPLIT;
+  {
+    TimerScope t(c, &c->ev_gemm);
+    fast_gemm(out, Xp, Wp, Mp, Np, Kp, ns, wk, epi, c->cs);
+  }
+  if (c->timing) c->t_gemm_bytes += (double)Np * Kp * 2;
+  if (nsplit_out) *nsplit_out = ns;
+}
+
+void forward_layers(echo_ctx *c, const Slot &S, int M, bool use_splitk_attn) {
+  const echo_model_desc &d = c->d;
+  const Plan &p = c->p;
+  hipStream_t st = c->cs;
+  int Hq = d.n_q_heads, Hkv = d.n_kv_heads, hd = d.head_dim, H = d.hidden, F = d.ffn;
+  float *h = at<float>(c, p.o_h), *rope = at<float>(c, p.o_rope);
+  launch_rope_table(rope, c->rows.pos, M, hd, d.rope_base, st);
+  if (!p.fast) {
+    int bf = d.dtype == ECHO_BF16;
+    float *x = at<float>(c, p.o_x), *qkv = at<float>(c, p.o_qkv), *att = at<float>(c, p.o_att), *gu = at<float>(c, p.o_gu),
+          *ff = at<float>(c, p.o_ff);
+    dbg_embed(h, S.embed, bf, c->rows.token, M, H, st);
+    for (int l = 0; l < d.n_layers; ++l) {
+      const LayerW &L = S.layers[l];
+      dbg_rmsnorm(x, h, L.attn_norm, bf, M, H, d.rms_eps, st);
+      dbg_gemm(qkv, x, L.wqkv, bf, M, (Hq + 2 * Hkv) * hd, H, 0, st);
+      dbg_qkv_post(qkv, L.q_norm, L.k_norm, bf, d.qk_norm, d.rms_eps, rope, c->rows, c->kv, l, M, Hq, Hkv, st);
+      dbg_attention(att, qkv, c->rows, c->kv, l, M, Hq, Hkv, st);
+      dbg_gemm(h, att, L.wo, bf, M, H, Hq * hd, 1, st);
+      dbg_rmsnorm(x, h, L.ffn_norm, bf, M, H, d.rms_eps, st);
+      dbg_gemm(gu, x, L.wgu, bf, M, 2 * F, H, 0, st);
+      dbg_swiglu(ff, gu, M, F, st);
+      dbg_gemm(h, ff, L.wdown, bf, M, H, F, 1, st);
+    }
+    dbg_rmsnorm(x, h, S.final_norm, bf, M, H, d.rms_eps, st);
+    return;
+  }
+  int Mp = pad_rows(M), ns;
+  void *xa = at<void>(c, p.o_xa), *xatt = at<void>(c, p.o_xatt), *xff = at<void>(c, p.o_xff), *q16 = at<void>(c, p.o_q16);
+  float *part = at<float>(c, p.o_part);
+  fast_resid_norm(h, S.embed, c->rows.token, nullptr, 0, p.Np_d, xa, S.layers[0].attn_norm, M, Mp, H, d.rms_eps, st);
+  for (int l = 0; l < d.n_layers; ++l) {
+    const LayerW &L = S.layers[l];
+    gemm_fast(c, part, xa, L.wqkv, Mp, p.Np_qkv, p.Kp_d, EPI_PARTIAL, &ns);
+    fast_qkv_post(part, ns, p.Np_qkv, Mp, q16, L.q_norm, L.k_norm, d.qk_norm, d.rms_eps, rope, c->rows, c->kv, l, M, Hq, Hkv, st);
+    {
+      TimerScope t(c, &c->ev_attn);
+      if (use_splitk_attn)
+        fast_attention(xatt, q16, c->rows, c->kv, l, M, Mp, Hq, Hkv, p.attn_chunk, p.attn_max_splits, at<float>(c, p.o_attn_o),
+                       at<float>(c, p.o_attn_ml), st);
+      else
+        fast_attention_simple(xatt, q16, c->rows, c->kv, l, M, Mp, Hq, Hkv, st);
+    }
+    if (c->timing) c->t_attn_bytes += c->cur_attn_bytes;
+    gemm_fast(c, part, xatt, L.wo, Mp, p.Np_d, p.Kp_q, EPI_PARTIAL, &ns);
+    fast_resid_norm(h, nullptr, nullptr, part, ns, p.Np_d, xa, L.ffn_norm, M, Mp, H, d.rms_eps, st);
+    gemm_fast(c, xff, xa, L.wgu, Mp, p.Np_gu, p.Kp_d, EPI_SWIGLU, nullptr);
+    gemm_fast(c, part, xff, L.wdown, Mp, p.Np_d, p.Kp_f, EPI_PARTIAL, &ns);
+    const void *next_gain = l + 1 < d.n_layers ? S.layers[l + 1].attn_norm : S.final_norm;
+    fast_resid_norm(h, nullptr, nullptr, part, ns, p.Np_d, xa, next_gain, M, Mp, H, d.rms_eps, st);
+  }
+}
+
+// lm_head + sampler over the normed rows left by forward_layers (or by norm_only).
+void sample_rows(echo_ctx *c, const Slot &S, int M, float temperature, uint64_t seed, bool unfused, const int32_t *target) {
+  const echo_model_desc &d = c->d;
+  const Plan &p = c->p;
+  hipStream_t st = c->cs;
+  float *logits = at<float>(c, p.o_logits);
+  if (!p.fast) {
+    int bf = d.dtype == ECHO_BF16;
+    dbg_gemm(logits, at<float>(c, p.o_x), S.lm_head, bf, M, d.vocab, d.hidden, 0, st);
+    dbg_sample(c->d_samp_tok, c->d_samp_lp, logits, d.vocab, M, d.vocab, temperature, seed, c->d_step, nullptr, st);
+    if (target) dbg_target_logprob(c->d_target_lp, logits, d.vocab, M, d.vocab, temperature, target, st);
+    return;
+  }
+  int Mp = pad_rows(M);
+  if (unfused) {
+    {
+      TimerScope t(c, &c->ev_gemm);
+      fast_lmhead_logits(logits, p.Np_v, at<void>(c, p.o_xa), S.lm_head, Mp, p.Np_v, p.Kp_d, d.vocab, st);
+    }
+    dbg_sample(c->d_samp_tok, c->d_samp_lp, logits, p.Np_v, M, d.vocab, temperature, seed, c->d_step, nullptr, st);
+    if (target) dbg_target_logprob(c->d_target_lp, logits, p.Np_v, M, d.vocab, temperature, target, st);
+  } else {
+    TimerScope t(c, &c->ev_gemm);
+    fast_lmhead_sample(c->d_samp_tok, c->d_samp_lp, c->d_target_lp, at<void>(c, p.o_xa), S.lm_head, Mp, M, d.vocab, p.Np_v, p.Kp_d,
+                       temperature, seed, c->d_step, nullptr, target, at<float>(c, p.o_lmpart), st);
+  }
+  if (c->timing) c->t_gemm_bytes += (double)p.Np_v * p.Kp_d * 2;
+}
+
+int64_t logits_ld(echo_ctx *c) { return c->p.fast ? c->p.Np_v : c->d.vocab; }
+
+// h rows -> normed rows (no layers): used for the first sampled token of every sequence.
+void norm_only(echo_ctx *c, const Slot &S, int M) {
+  const echo_model_desc &d = c->d;
+  const Plan &p = c->p;
+  if (!p.fast) dbg_rmsnorm(at<float>(c, p.o_x), at<float>(c, p.o_h), S.final_norm, d.dtype == ECHO_BF16, M, d.hidden, d.rms_eps, c->cs);
+  else fast_resid_norm(at<float>(c, p.o_h), nullptr, nullptr, nullptr, 0, p.Np_d, at<void>(c, p.o_xa), S.final_norm, M, pad_rows(M),
+                       d.hidden, d.rms_eps, c->cs);
+}
+
+bool env_flag(const char *name) { const char *v = getenv(name); return v && v[0] && v[0] != '0'; }
+
+struct ChunkRow { int32_t token, slot, pos; };
+
+// Feed the token strings (one per cache slot slot0 + q*slot_step) through the decoder in chunks of rows.
+// After each chunk `after(chunk_rows, M)` runs (still on the compute stream).
+template <typename F>
+int run_chunks(echo_ctx *c, const Slot &S, const int32_t *tokens, int stride, const std::vector<int> &lens, int slot_step, F after) {
+  std::vector<ChunkRow> all;
+  for (size_t q = 0; q < lens.size(); ++q)
+    for (int t = 0; t < lens[q]; ++t) all.push_back({tokens[(int64_t)q * stride + t], (int32_t)(q * slot_step), t});
+  int R = std::min(PREFILL_ROWS, c->p.Mcap);
+  std::vector<int32_t> tok(R), slot(R), pos(R), act(R);
+  bool splitk = !env_flag("ECHO_ATTN_SIMPLE");
+  for (size_t a = 0; a < all.size(); a += R) {
+    int M = (int)std::min<size_t>(R, all.size() - a);
+    for (int i = 0; i < M; ++i) { tok[i] = all[a + i].token; slot[i] = all[a + i].slot; pos[i] = all[a + i].pos; act[i] = 1; }
+    HIPCHK(c, hipMemcpyAsync(c->rows.token, tok.data(), M * 4, hipMemcpyHostToDevice, c->cs));
+    HIPCHK(c, hipMemcpyAsync(c->rows.slot, slot.data(), M * 4, hipMemcpyHostToDevice, c->cs));
+    HIPCHK(c, hipMemcpyAsync(c->rows.pos, pos.data(), M * 4, hipMemcpyHostToDevice, c->cs));
+    HIPCHK(c, hipMemcpyAsync(c->rows.active, act.data(), M * 4, hipMemcpyHostToDevice, c->cs));
+    HIPCHK(c, hipStreamSynchronize(c->cs));  // the host vectors are reused by the next chunk
+    forward_layers(c, S, M, splitk);
+    int rc = after(&all[a], M);
+    if (rc) return rc;
+  }
+  return 0;
+}
+
+int capture_step(echo_ctx *c, const Slot &S, int N, int max_new, float temperature, uint64_t seed, bool unfused, const int32_t *forced,
+                 int eos) {
+  if (c->graph) { hipGraphExecDestroy(c->graph); c->graph = nullptr; }
+  hipGraph_t g = nullptr;
+  HIPCHK(c, hipStreamBeginCapture(c->cs, hipStreamCaptureModeThreadLocal));
+  forward_layers(c, S, N, !env_flag("ECHO_ATTN_SIMPLE"));
+  sample_rows(c, S, N, temperature, seed, unfused, nullptr);
+  launch_bookkeeping(N, max_new, c->d_step, c->d_samp_tok, c->d_samp_lp, forced, c->d_limit, eos, S.version, c->d_prompt_len_seq,
+                     c->d_gen_len, c->rows, at<int32_t>(c, c->p.o_out_tok), at<float>(c, c->p.o_out_lp), at<int64_t>(c, c->p.o_out_ver),
+                     c->d_n_active, c->cs);
+  HIPCHK(c, hipStreamEndCapture(c->cs, &g));
+  hipError_t e = hipGraphInstantiate(&c->graph, g, nullptr, nullptr, 0);
+  hipGraphDestroy(g);
+  if (e != hipSuccess) return fail(c, ECHO_EHIP, "hipGraphInstantiate: %s", hipGetErrorString(e));
+  return 0;
+}
+
+double drain_events(std::vector<std::pair<hipEvent_t, hipEvent_t>> &v, int64_t *count) {
+  double ms = 0;
+  for (auto &pr : v) {
+    float t = 0;
+    if (hipEventElapsedTime(&t, pr.first, pr.second) == hipSuccess) { ms += t; ++*count; }
+    hipEventDestroy(pr.first);
+    hipEventDestroy(pr.second);
+  }
+  v.clear();
+  return ms;
+}
+
+}  // namespace
+
+// =================================================================================================== C ABI
+extern "C" {
+
+size_t echo_arena_bytes(const echo_model_desc *desc) {
+  Plan p = make_plan(desc);
+  return p.ok ? p.total : 0;
+}
+
+size_t echo_blob_bytes(const echo_model_desc *desc) {
+  if (!valid_desc(desc, nullptr)) return 0;
+  return (size_t)blob_numel(desc) * (desc->dtype == ECHO_BF16 ? 2 : 4);
+}
+
+int echo_init(const echo_model_desc *desc, int device, void *dev_arena, size_t arena_bytes, void *compute_stream, void *copy_stream,
+              echo_ctx **out) {
+  if (!out) return fail(nullptr, ECHO_EINVAL, "out is NULL");
+  *out = nullptr;
+  std::string why;
+  if (!valid_desc(desc, &why)) return fail(nullptr, ECHO_EINVAL, "invalid model description: %s", why.c_str());
+  Plan p = make_plan(desc);
+  if (!dev_arena || ((uintptr_t)dev_arena & 255)) return fail(nullptr, ECHO_EINVAL, "dev_arena must be a 256-byte aligned device pointer");
+  if (arena_bytes < p.total) return fail(nullptr, ECHO_ENOMEM, "arena has %zu bytes, this shape needs %zu", arena_bytes, p.total);
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return fail(nullptr, ECHO_EHIP, "no HIP device %d", device);
+  echo_ctx *c = new echo_ctx();
+  c->d = *desc; c->p = p; c->device = device; c->arena = (char *)dev_arena;
+  memset(&c->st, 0, sizeof c->st);
+  c->st.active_version = c->st.staged_version = -1;
+  auto bail = [&](const char *what, hipError_t e) { int rc = fail(nullptr, ECHO_EHIP, "%s: %s", what, hipGetErrorString(e)); delete c; return rc; };
+  hipError_t e;
+  if ((e = hipSetDevice(device)) != hipSuccess) return bail("hipSetDevice", e);
+  // graph capture is not possible on the null stream, so it is replaced by a stream of the library's own
+  c->cs = (hipStream_t)compute_stream; c->ks = (hipStream_t)copy_stream;
+  if (!c->cs) { if ((e = hipStreamCreateWithFlags(&c->cs, hipStreamNonBlocking)) != hipSuccess) return bail("hipStreamCreate", e); c->own_cs = true; }
+  if (!c->ks) { if ((e = hipStreamCreateWithFlags(&c->ks, hipStreamNonBlocking)) != hipSuccess) return bail("hipStreamCreate", e); c->own_ks = true; }
+  if ((e = hipEventCreateWithFlags(&c->staged_ev, hipEventDisableTiming)) != hipSuccess) return bail("hipEventCreate", e);
+  for (int s = 0; s < desc->n_weight_slots; ++s) bind_slot(c, s);
+  int32_t *r = at<int32_t>(c, p.o_rows);
+  size_t M = p.Mcap;
+  c->rows = {r, r + M, r + 2 * M, r + 3 * M};
+  c->kv = {c->arena + p.o_kv, desc->n_layers, desc->n_kv_heads, desc->max_ctx, desc->head_dim, p.fast ? 2 : 4};
+  int32_t *q = at<int32_t>(c, p.o_seq);
+  c->d_prompt_len_seq = q; c->d_gen_len = q + desc->max_seqs; c->d_limit = q + 2 * (size_t)desc->max_seqs;
+  int32_t *sm = at<int32_t>(c, p.o_samp);
+  c->d_samp_tok = sm; c->d_samp_lp = (float *)(sm + M); c->d_target = sm + 2 * M; c->d_target_lp = (float *)(sm + 3 * M);
+  int32_t *mp = at<int32_t>(c, p.o_maps);
+  c->d_map_a = mp; c->d_map_b = mp + M; c->d_plen_p = mp + 2 * M;
+  c->d_step = at<int32_t>(c, p.o_scal); c->d_n_active = c->d_step + 1;
+  // activations, row state and scratch start from zero (padding rows and columns are never written)
+  size_t zero_from = p.o_h;
+  if ((e = hipMemsetAsync(c->arena + zero_from, 0, p.total - zero_from, c->cs)) != hipSuccess) return bail("hipMemsetAsync", e);
+  if ((e = hipStreamSynchronize(c->cs)) != hipSuccess) return bail("hipStreamSynchronize", e);
+  *out = c;
+  return ECHO_OK;
+}
+
+int echo_load_policy(echo_ctx *c, int64_t version, const void *host_weights, size_t nbytes) {
+  if (!c) return ECHO_EINVAL;
+  std::unique_lock<std::mutex> lk(c->mu);
+  if (!host_weights) return fail(c, ECHO_EINVAL, "host_weights is NULL");
+  if (nbytes != echo_blob_bytes(&c->d)) return fail(c, ECHO_EINVAL, "blob has %zu bytes, this shape needs %zu", nbytes, echo_blob_bytes(&c->d));
+  int64_t newest = std::max(c->active >= 0 ? c->slots[c->active].version : -1, c->staged >= 0 ? c->slots[c->staged].version : -1);
+  if (version <= newest || version < 0) return fail(c, ECHO_ESTATE, "version %lld does not advance past %lld", (long long)version, (long long)newest);
+  if (c->staged >= 0) return fail(c, ECHO_ESTATE, "a staged snapshot is still waiting to be switched in");
+  bool running = c->rollout_running;
+  int target;
+  if (c->active < 0) target = 0;
+  else if (c->d.n_weight_slots == 2) target = 1 - c->active;
+  else if (!running) target = c->active;
+  else return fail(c, ECHO_ESTATE, "installing during a rollout needs n_weight_slots = 2");
+  lk.unlock();
+  HIPCHK(c, hipSetDevice(c->device));
+  if (!running) HIPCHK(c, hipStreamSynchronize(c->cs));
+  int rc = install(c, target, (const char *)host_weights);
+  if (rc) return rc;
+  HIPCHK(c, hipEventRecord(c->staged_ev, c->ks));
+  HIPCHK(c, hipStreamSynchronize(c->ks));  // the host blob may be freed when this call returns
+  lk.lock();
+  c->slots[target].version = version;
+  if (c->rollout_running) {
+    c->staged = target;
+    c->st.staged_version = version;
+  } else {
+    c->active = target;
+    c->st.active_version = version;
+  }
+  c->cv.notify_all();
+  return ECHO_OK;
+}
+
+int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_stride, const int32_t *prompt_lens, int32_t P, int32_t G,
+                 int32_t max_new, float temperature, uint64_t seed, const echo_rollout_opts *opts, int32_t *out_tokens,
+                 float *out_logprobs, int32_t *out_lens, int64_t *out_versions) {
+  if (!c) return ECHO_EINVAL;
+  echo_rollout_opts o;
+  memset(&o, 0, sizeof o);
+  o.eos_id = -1; o.top_p = 1.0f;
+  if (opts) o = *opts;
+  if (!prompt_tokens || !prompt_lens || !out_tokens || !out_logprobs || !out_lens) return fail(c, ECHO_EINVAL, "NULL argument");
+  if (P < 1 || G < 1 || max_new < 1 || prompt_stride < 1) return fail(c, ECHO_EINVAL, "n_prompts, G, max_new and prompt_stride must be positive");
+  if (!(temperature > 0.f)) return fail(c, ECHO_EINVAL, "temperature must be positive");
+  if (o.top_p != 1.0f) return fail(c, ECHO_EINVAL, "top_p != 1 is not implemented");
+  int64_t N64 = (int64_t)P * G;
+  if (N64 > c->d.max_seqs) return fail(c, ECHO_ENOMEM, "%lld sequences exceed max_seqs = %d", (long long)N64, c->d.max_seqs);
+  int N = (int)N64, max_pl = 0;
+  for (int p = 0; p < P; ++p) {
+    if (prompt_lens[p] < 1 || prompt_lens[p] > prompt_stride) return fail(c, ECHO_EINVAL, "prompt_lens[%d] = %d out of range", p, prompt_lens[p]);
+    max_pl = std::max(max_pl, prompt_lens[p]);
+    for (int t = 0; t < prompt_lens[p]; ++t) {
+      int tk = prompt_tokens[(int64_t)p * prompt_stride + t];
+      if (tk < 0 || tk >= c->d.vocab) return fail(c, ECHO_EINVAL, "prompt token %d of prompt %d is outside the vocabulary", t, p);
+    }
+  }
+  if ((int64_t)max_pl + max_new > c->d.max_ctx) return fail(c, ECHO_ENOMEM, "prompt %d + max_new %d exceeds max_ctx = %d", max_pl, max_new, c->d.max_ctx);
+  if (o.n_swaps < 0 || (o.n_swaps > 0 && !o.swap_at_step)) return fail(c, ECHO_EINVAL, "bad swap schedule");
+  for (int j = 0; j < o.n_swaps; ++j)
+    if (o.swap_at_step[j] < 1 || (j && o.swap_at_step[j] <= o.swap_at_step[j - 1])) return fail(c, ECHO_EINVAL, "swap_at_step must be ascending and >= 1");
+  if (o.n_swaps > 0 && c->d.n_weight_slots < 2) return fail(c, ECHO_ESTATE, "snapshot swaps inside a rollout need n_weight_slots = 2");
+  if (o.forced_tokens)
+    for (int64_t i = 0; i < (int64_t)N * max_new; ++i)
+      if (o.forced_tokens[i] < 0 || o.forced_tokens[i] >= c->d.vocab) return fail(c, ECHO_EINVAL, "forced token outside the vocabulary");
+  {
+    std::lock_guard<std::mutex> lk(c->mu);
+    if (c->active < 0) return fail(c, ECHO_ESTATE, "no policy snapshot installed");
+    if (c->rollout_running) return fail(c, ECHO_ESTATE, "a rollout is already running on this context");
+    c->rollout_running = true;
+  }
+  struct Done { echo_ctx *c; ~Done() {
+    std::lock_guard<std::mutex> lk(c->mu);
+    c->rollout_running = false;
+    if (c->staged >= 0) { c->active = c->staged; c->staged = -1; c->st.active_version = c->slots[c->active].version; c->st.staged_version = -1; }
+  } } done{c};
+
+  HIPCHK(c, hipSetDevice(c->device));
+  const Plan &p = c->p;
+  hipStream_t st = c->cs;
+  auto t0 = std::chrono::steady_clock::now();
+  bool unfused = o.unfused_sampler || o.debug_logits;
+  bool want_timing = o.time_kernels != 0;
+  c->timing = false;
+  bool use_graph = !o.no_graph && !want_timing && !o.debug_logits;
+  c->t_attn_bytes = c->t_gemm_bytes = 0;
+
+  // per-sequence state
+  std::vector<int32_t> plen_seq(N), limit(N);
+  int steps = 0;
+  for (int n = 0; n < N; ++n) {
+    plen_seq[n] = prompt_lens[n / G];
+    limit[n] = o.stop_lens ? std::max(1, std::min(max_new, o.stop_lens[n])) : max_new;
+    steps = std::max(steps, limit[n]);
+  }
+  HIPCHK(c, hipMemcpyAsync(c->d_prompt_len_seq, plen_seq.data(), N * 4, hipMemcpyHostToDevice, st));
+  HIPCHK(c, hipMemcpyAsync(c->d_limit, limit.data(), N * 4, hipMemcpyHostToDevice, st));
+  HIPCHK(c, hipMemcpyAsync(c->d_plen_p, prompt_lens, P * 4, hipMemcpyHostToDevice, st));
+  int32_t *d_forced = nullptr;
+  if (o.forced_tokens) {
+    d_forced = at<int32_t>(c, p.o_forced);
+    HIPCHK(c, hipMemcpyAsync(d_forced, o.forced_tokens, (size_t)N * max_new * 4, hipMemcpyHostToDevice, st));
+  }
+  int64_t outn = (int64_t)N * max_new;
+  launch_fill_i32(at<int32_t>(c, p.o_out_tok), -1, outn, st);
+  launch_fill_i32(at<int32_t>(c, p.o_out_lp), 0, outn, st);
+  launch_fill_i32(at<int32_t>(c, p.o_out_ver), -1, outn * 2, st);
+  launch_fill_i32(c->d_gen_len, 0, N, st);
+  launch_fill_i32(c->d_step, 0, 1, st);
+  HIPCHK(c, hipStreamSynchronize(st));
+
+  int cur = c->active;
+  // ---- prefill the P unique prompts into cache slots p*G, keep each prompt's last hidden state
+  std::vector<int> lens(prompt_lens, prompt_lens + P);
+  std::vector<int32_t> map(std::max(P, N));
+  float *first_h = at<float>(c, p.o_first_h);
+  int rc = run_chunks(c, c->slots[cur], prompt_tokens, prompt_stride, lens, G, [&](const ChunkRow *rows, int M) -> int {
+    std::fill(map.begin(), map.begin() + P, -1);
+    bool any = false;
+    for (int i = 0; i < M; ++i) {
+      int pp = rows[i].slot / G;
+      if (rows[i].pos == prompt_lens[pp] - 1) { map[pp] = i; any = true; }
+    }
+    if (!any) return 0;
+    HIPCHK(c, hipMemcpyAsync(c->d_map_a, map.data(), P * 4, hipMemcpyHostToDevice, st));
+    launch_gather_rows_f32(first_h, at<float>(c, p.o_h), c->d_map_a, P, c->d.hidden, st);
+    HIPCHK(c, hipStreamSynchronize(st));
+    return 0;
+  });
+  if (rc) return rc;
+  // ---- first token of all N sequences from the shared prompt state; replicate the prompt K/V
+  for (int n = 0; n < N; ++n) map[n] = n / G;
+  HIPCHK(c, hipMemcpyAsync(c->d_map_a, map.data(), N * 4, hipMemcpyHostToDevice, st));
+  launch_gather_rows_f32(at<float>(c, p.o_h), first_h, c->d_map_a, N, c->d.hidden, st);
+  launch_fill_i32(c->rows.active, 1, N, st);
+  for (int n = 0; n < N; ++n) map[n] = n;
+  HIPCHK(c, hipMemcpyAsync(c->rows.slot, map.data(), N * 4, hipMemcpyHostToDevice, st));
+  norm_only(c, c->slots[cur], N);
+  sample_rows(c, c->slots[cur], N, temperature, seed, unfused, nullptr);
+  auto grab_logits = [&](int s) -> int {
+    if (!o.debug_logits) return 0;
+    HIPCHK(c, hipMemcpy2DAsync(o.debug_logits + (int64_t)s * c->d.vocab, (size_t)max_new * c->d.vocab * 4, at<float>(c, p.o_logits),
+                               (size_t)logits_ld(c) * 4, (size_t)c->d.vocab * 4, N, hipMemcpyDeviceToHost, st));
+    HIPCHK(c, hipStreamSynchronize(st));
+    return 0;
+  };
+  if ((rc = grab_logits(0))) return rc;
+  auto book = [&](int slot) {
+    launch_bookkeeping(N, max_new, c->d_step, c->d_samp_tok, c->d_samp_lp, d_forced, c->d_limit, o.eos_id, c->slots[slot].version,
+                       c->d_prompt_len_seq, c->d_gen_len, c->rows, at<int32_t>(c, p.o_out_tok), at<float>(c, p.o_out_lp),
+                       at<int64_t>(c, p.o_out_ver), c->d_n_active, st);
+  };
+  book(cur);
+  launch_kv_replicate(c->kv, c->d_plen_p, P, G, st);
+  HIPCHK(c, hipStreamSynchronize(st));
+  auto t1 = std::chrono::steady_clock::now();
+
+  // ---- decode
+  c->timing = want_timing;
+  double swap_wait = 0;
+  int next_swap = 0, decode_steps = 0;
+  bool have_graph = false;
+  bool splitk = !env_flag("ECHO_ATTN_SIMPLE");
+  for (int s = 1; s < steps; ++s) {
+    if (next_swap < o.n_swaps && o.swap_at_step[next_swap] == s) {
+      auto w0 = std::chrono::steady_clock::now();
+      std::unique_lock<std::mutex> lk(c->mu);
+      int tmo = o.swap_timeout_ms > 0 ? o.swap_timeout_ms : 10000;
+      if (!c->cv.wait_for(lk, std::chrono::milliseconds(tmo), [&] { return c->staged >= 0; }))
+        return fail(c, ECHO_ESTATE, "no snapshot was staged for the swap at step %d within %d ms", s, tmo);
+      cur = c->staged; c->active = cur; c->staged = -1;
+      c->st.active_version = c->slots[cur].version; c->st.staged_version = -1;
+      lk.unlock();
+      HIPCHK(c, hipStreamWaitEvent(st, c->staged_ev, 0));
+      swap_wait += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - w0).count();
+      have_graph = false;
+      ++next_swap;
+    }
+    if (o.eos_id >= 0 && (s % 16) == 0) {  // sequences may have ended early: look at the active count
+      int32_t na = 0;
+      HIPCHK(c, hipMemcpyAsync(&na, c->d_n_active, 4, hipMemcpyDeviceToHost, st));
+      HIPCHK(c, hipStreamSynchronize(st));
+      if (na == 0) break;
+    }
+    bool time_this = c->timing;
+    if (c->timing) {
+      c->timing = (s % 16) == 1;
+      double b = 0;
+      for (int n = 0; n < N; ++n) if (s < limit[n]) b += (double)(plen_seq[n] + s) * 2 * c->d.n_kv_heads * c->d.head_dim * 2;
+      c->cur_attn_bytes = b;
+    }
+    if (use_graph) {
+      if (!have_graph) {
+        if ((rc = capture_step(c, c->slots[cur], N, max_new, temperature, seed, unfused, d_forced, o.eos_id))) return rc;
+        have_graph = true;
+      }
+      HIPCHK(c, hipGraphLaunch(c->graph, st));
+    } else {
+      forward_layers(c, c->slots[cur], N, splitk);
+      sample_rows(c, c->slots[cur], N, temperature, seed, unfused, nullptr);
+      if ((rc = grab_logits(s))) return rc;
+      book(cur);
+    }
+    c->timing = time_this;
+    ++decode_steps;
+  }
+  HIPCHK(c, hipStreamSynchronize(st));
+  auto t2 = std::chrono::steady_clock::now();
+
+  // ---- results
+  HIPCHK(c, hipMemcpyAsync(out_tokens, at<int32_t>(c, p.o_out_tok), outn * 4, hipMemcpyDeviceToHost, st));
+  HIPCHK(c, hipMemcpyAsync(out_logprobs, at<float>(c, p.o_out_lp), outn * 4, hipMemcpyDeviceToHost, st));
+  if (out_versions) HIPCHK(c, hipMemcpyAsync(out_versions, at<int64_t>(c, p.o_out_ver), outn * 8, hipMemcpyDeviceToHost, st));
+  HIPCHK(c, hipMemcpyAsync(out_lens, c->d_gen_len, N * 4, hipMemcpyDeviceToHost, st));
+  HIPCHK(c, hipStreamSynchronize(st));
+  auto t3 = std::chrono::steady_clock::now();
+  c->st.decode_steps = decode_steps;
+  c->st.prefill_ms = std::chrono::duration<float, std::milli>(t1 - t0).count();
+  c->st.decode_ms = std::chrono::duration<float, std::milli>(t2 - t1).count();
+  c->st.total_ms = std::chrono::duration<float, std::milli>(t3 - t0).count();
+  c->st.swap_wait_ms = (float)swap_wait;
+  if (c->timing) {
+    c->st.attn_launches = c->st.gemm_launches = 0;
+    c->st.attn_ms = drain_events(c->ev_attn, &c->st.attn_launches);
+    c->st.gemm_ms = drain_events(c->ev_gemm, &c->st.gemm_launches);
+    c->st.attn_bytes = c->t_attn_bytes;
+    c->st.gemm_bytes = c->t_gemm_bytes;
+    c->timing = false;
+  }
+  return ECHO_OK;
+}
+
+int echo_logprobs(echo_ctx *c, const int32_t *tokens, int32_t stride, const int32_t *lens_in, int32_t n_seqs, float temperature,
+                  float *out) {
+  if (!c) return ECHO_EINVAL;
+  if (!tokens || !lens_in || !out || n_seqs < 1 || stride < 1) return fail(c, ECHO_EINVAL, "bad argument");
+  if (!(temperature > 0.f)) return fail(c, ECHO_EINVAL, "temperature must be positive");
+  if (n_seqs > c->d.max_seqs) return fail(c, ECHO_ENOMEM, "%d sequences exceed max_seqs = %d", n_seqs, c->d.max_seqs);
+  std::vector<int> lens(n_seqs);
+  for (int n = 0; n < n_seqs; ++n) {
+    if (lens_in[n] < 1 || lens_in[n] > stride || lens_in[n] > c->d.max_ctx) return fail(c, ECHO_ENOMEM, "lens[%d] = %d out of range", n, lens_in[n]);
+    lens[n] = lens_in[n] - 1;  // the last token is only a target
+    for (int t = 0; t < lens_in[n]; ++t) {
+      int tk = tokens[(int64_t)n * stride + t];
+      if (tk < 0 || tk >= c->d.vocab) return fail(c, ECHO_EINVAL, "token %d of sequence %d is outside the vocabulary", t, n);
+    }
+  }
+  {
+    std::lock_guard<std::mutex> lk(c->mu);
+    if (c->active < 0) return fail(c, ECHO_ESTATE, "no policy snapshot installed");
+    if (c->rollout_running) return fail(c, ECHO_ESTATE, "a rollout is running on this context");
+  }
+  HIPCHK(c, hipSetDevice(c->device));
+  memset(out, 0, (size_t)n_seqs * stride * sizeof(float));
+  hipStream_t st = c->cs;
+  launch_fill_i32(c->d_step, 0, 1, st);
+  std::vector<int32_t> tgt(c->p.Mcap);
+  std::vector<float> lp(c->p.Mcap);
+  const Slot &S = c->slots[c->active];
+  return run_chunks(c, S, tokens, stride, lens, 1, [&](const ChunkRow *rows, int M) -> int {
+    for (int i = 0; i < M; ++i) tgt[i] = tokens[(int64_t)rows[i].slot * stride + rows[i].pos + 1];
+    HIPCHK(c, hipMemcpyAsync(c->d_target, tgt.data(), M * 4, hipMemcpyHostToDevice, st));
+    sample_rows(c, S, M, temperature, 0, false, c->d_target);
+    HIPCHK(c, hipMemcpyAsync(lp.data(), c->d_target_lp, M * 4, hipMemcpyDeviceToHost, st));
+    HIPCHK(c, hipStreamSynchronize(st));
+    for (int i = 0; i < M; ++i) out[(int64_t)rows[i].slot * stride + rows[i].pos + 1] = lp[i];
+    return 0;
+  });
+}
+
+int echo_debug_draw_bits(echo_ctx *c, uint64_t seed, uint32_t n, uint32_t s, uint32_t i0, int32_t count, uint32_t *out_bits) {
+  if (!c || !out_bits || count < 1) return c ? fail(c, ECHO_EINVAL, "bad argument") : ECHO_EINVAL;
+  size_t cap = c->p.Mcap * (size_t)c->p.Np_v;  // the logits buffer is borrowed as scratch
+  if ((size_t)count > cap) return fail(c, ECHO_EINVAL, "count exceeds %zu", cap);
+  {
+    std::lock_guard<std::mutex> lk(c->mu);
+    if (c->rollout_running) return fail(c, ECHO_ESTATE, "a rollout is running on this context");
+  }
+  HIPCHK(c, hipSetDevice(c->device));
+  uint32_t *buf = at<uint32_t>(c, c->p.o_logits);
+  launch_draw_bits(buf, seed, n, s, i0, count, c->cs);
+  HIPCHK(c, hipMemcpyAsync(out_bits, buf, (size_t)count * 4, hipMemcpyDeviceToHost, c->cs));
+  HIPCHK(c, hipStreamSynchronize(c->cs));
+  return ECHO_OK;
+}
+
+int echo_stats(echo_ctx *c, echo_stats_t *out) {
+  if (!c || !out) return ECHO_EINVAL;
+  std::lock_guard<std::mutex> lk(c->mu);
+  *out = c->st;
+  return ECHO_OK;
+}
+
+const char *echo_last_error(const echo_ctx *c) { return c ? c->err.c_str() : g_init_error.c_str(); }
+
+void echo_destroy(echo_ctx *c) {
+  if (!c) return;
+  hipSetDevice(c->device);
+  hipStreamSynchronize(c->cs);
+  hipStreamSynchronize(c->ks);
+  if (c->graph) hipGraphExecDestroy(c->graph);
+  if (c->staged_ev) hipEventDestroy(c->staged_ev);
+  if (c->own_cs) hipStreamDestroy(c->cs);
+  if (c->own_ks) hipStreamDestroy(c->ks);
+  delete c;
+}
+
+}  // extern "C"

@@ -1,0 +1,97 @@
+// Internal launcher interface between the engine and the HIP kernels (not part of the C ABI).
+// Every launcher enqueues on `st` and returns; shapes are validated by the engine before the call.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace echo {
+
+// ------------------------------------------------------------------------------------------------
+// Layouts of the bf16 (MFMA) path.
+//   packed weight  Wp: rows padded to 32, K padded to 16.  Element (r,k) lives at
+//       ((((r/32)*(Kp/8) + k/8)*32 + r%32)*8 + k%8)            -- one 32-row block is contiguous over K,
+//       and a wavefront's MFMA A-operand load (32 rows x 16 k) is one contiguous 1 KiB read.
+//   packed activation Xp ("K8"): M padded to 32.  Element (m,k) lives at ((k/8)*Mp + m)*8 + k%8.
+//   split-K partials P: [split][Np/4][Mp][4] fp32.
+// ------------------------------------------------------------------------------------------------
+static inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
+
+struct RowState {        // device arrays, one entry per row of the current batch of rows
+  int32_t *token;        // token fed at this row (-1: padding row)
+  int32_t *slot;         // KV-cache sequence slot of the row
+  int32_t *pos;          // position of the token inside its sequence
+  int32_t *active;       // 0: row is skipped (finished sequence or padding)
+};
+
+struct KvGeom {          // KV cache: [slot][layer][K|V][kv_head][max_ctx][head_dim]
+  void *base;
+  int32_t n_layers, n_kv_heads, max_ctx, head_dim, elt_bytes;
+  __host__ __device__ int64_t head_stride() const { return (int64_t)max_ctx * head_dim; }
+  __host__ __device__ int64_t kv_stride() const { return head_stride() * n_kv_heads; }
+  __host__ __device__ int64_t layer_stride() const { return kv_stride() * 2; }
+  __host__ __device__ int64_t slot_stride() const { return layer_stride() * n_layers; }
+};
+
+// ---- shared small kernels (both paths) -----------------------------------------------------------
+void launch_rope_table(float *cs /*[M][hd/2][2]*/, const int32_t *pos, int M, int hd, float base, hipStream_t st);
+void launch_bookkeeping(int N, int max_new, int32_t *d_step, const int32_t *samp_tok, const float *samp_lp,
+                        const int32_t *forced, const int32_t *limit, int eos, int64_t version,
+                        const int32_t *prompt_len, int32_t *gen_len, RowState rows, int32_t *out_tok,
+                        float *out_lp, int64_t *out_ver, int32_t *n_active, hipStream_t st);
+void launch_kv_replicate(KvGeom kv, const int32_t *prompt_len /*[P]*/, int P, int G, hipStream_t st);
+void launch_draw_bits(uint32_t *out, uint64_t seed, uint32_t n, uint32_t s, uint32_t i0, int count, hipStream_t st);
+void launch_fill_i32(int32_t *p, int32_t v, int64_t n, hipStream_t st);
+void launch_gather_rows_f32(float *dst, const float *src, const int32_t *src_row /*[n_dst], -1 = skip*/,
+                            int n_dst, int width, hipStream_t st);
+
+// ---- debug path: row-major weights (fp32 or bf16), fp32 activations, fp32 KV cache ------------------
+void dbg_embed(float *h, const void *embed, int w_bf16, const int32_t *token, int M, int d, hipStream_t st);
+void dbg_rmsnorm(float *x, const float *h, const void *gain, int w_bf16, int M, int d, float eps, hipStream_t st);
+// Y[m][n] (+)= sum_k X[m][k] * W[n][k]
+void dbg_gemm(float *Y, const float *X, const void *W, int w_bf16, int M, int N, int K, int accumulate, hipStream_t st);
+void dbg_qkv_post(float *qkv /*[M][(Hq+2Hkv)*hd], q rotated in place*/, const void *q_gain, const void *k_gain,
+                  int w_bf16, int qk_norm, float eps, const float *rope_cs, RowState rows, KvGeom kv, int layer,
+                  int M, int Hq, int Hkv, hipStream_t st);
+void dbg_attention(float *out /*[M][Hq*hd]*/, const float *qkv, RowState rows, KvGeom kv, int layer, int M, int Hq,
+                   int Hkv, hipStream_t st);
+void dbg_swiglu(float *ff /*[M][F]*/, const float *gu /*[M][2F] = gate | up*/, int M, int F, hipStream_t st);
+// Unfused sampler over materialised logits [M][ld]: Gumbel-max token and its log-softmax, in fp32.
+void dbg_sample(int32_t *tok, float *lp, const float *logits, int64_t ld, int M, int V, float temperature,
+                uint64_t seed, const int32_t *d_step, const int32_t *row_active, hipStream_t st);
+// log softmax(logits/T)[target[m]] per row (teacher-forced scoring).
+void dbg_target_logprob(float *lp, const float *logits, int64_t ld, int M, int V, float temperature,
+                        const int32_t *target, hipStream_t st);
+
+// ---- bf16 MFMA path -------------------------------------------------------------------------------
+// Repack a row-major bf16 chunk `src` [n_rows][K] into the packed weight `dst`: source row i goes to
+// destination row dst_row0 + i*dst_row_stride (stride 2 interleaves gate and up rows).  K % 8 == 0.
+void fast_pack_weight(void *dst, const void *src, int64_t dst_row0, int dst_row_stride, int64_t n_rows, int K, int Kp,
+                      hipStream_t st);
+// h = embed[token] (first layer) or h += sum_s P[s] (+0); then x = rmsnorm(h)*gain -> Xp (bf16 K8).
+void fast_resid_norm(float *h, const void *embed_bf16, const int32_t *token, const float *partials, int nsplit,
+                     int Np, void *Xp, const void *gain_bf16, int M, int Mp, int d, float eps, hipStream_t st);
+enum GemmEpilogue { EPI_PARTIAL = 0, EPI_SWIGLU = 1 };
+// out = Xp[Mp x Kp] * Wp[Np x Kp]^T.  EPI_PARTIAL: fp32 partials [nsplit][Np/4][Mp][4];
+// EPI_SWIGLU (rows alternate gate_f, up_f): silu(gate)*up -> bf16 K8 [Mp][Np/2]; nsplit must be 1.
+void fast_gemm(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, int nsplit, int waves_k,
+               GemmEpilogue epi, hipStream_t st);
+int fast_gemm_pick(int Np, int Kp, int Mp, int *nsplit, int *waves_k); // heuristics for the two knobs
+void fast_qkv_post(const float *partials, int nsplit, int Np, int Mp, void *q_bf16 /*[M][Hq][hd]*/,
+                   const void *q_gain, const void *k_gain, int qk_norm, float eps, const float *rope_cs,
+                   RowState rows, KvGeom kv, int layer, int M, int Hq, int Hkv, hipStream_t st);
+// Plain one-wavefront-per-(row, head) attention over the bf16 KV cache (cross-check of the split-K kernel).
+void fast_attention_simple(void *Xp_out, const void *q_bf16, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq,
+                           int Hkv, hipStream_t st);
+// Split-K decode attention over the bf16 KV cache + combine; writes Xp (bf16 K8 [Mp][Hq*hd]).
+void fast_attention(void *Xp_out, const void *q_bf16, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq,
+                    int Hkv, int chunk_keys, int max_splits, float *part_o, float *part_ml, hipStream_t st);
+// lm_head with the sampler fused into the epilogue (partials per workgroup) + the combine kernel.
+void fast_lmhead_sample(int32_t *tok, float *lp, float *target_lp, const void *Xp, const void *Wp, int Mp, int M,
+                        int V, int Np, int Kp, float temperature, uint64_t seed, const int32_t *d_step,
+                        const int32_t *row_active, const int32_t *target, float *partials, hipStream_t st);
+size_t fast_lmhead_partial_floats(int Np, int Mp);
+// lm_head writing fp32 logits [Mp][ld] row-major (debug / unfused sampler).
+void fast_lmhead_logits(float *logits, int64_t ld, const void *Xp, const void *Wp, int Mp, int Np, int Kp, int V,
+                        hipStream_t st);
+
+}  // namespace echo

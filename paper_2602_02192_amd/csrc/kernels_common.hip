@@ -1,0 +1,119 @@
+// Small kernels used by both the debug (fp32) and the MFMA (bf16) path: rotary table, per-step
+// bookkeeping, KV replication across a group, generator read-out, fills and row gathers.
+#include "echo_device.h"
+#include "echo_kernels.h"
+
+namespace echo {
+
+// cos/sin of pos * base^(-2i/hd), evaluated in double and stored as fp32: cs[m][i] = (cos, sin).
+__global__ void rope_table_kernel(float2 *cs, const int32_t *pos, int M, int half, int hd, float base) {
+  int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= M * half) return;
+  int m = idx / half, i = idx % half;
+  int p = pos[m];
+  if (p < 0) p = 0;
+  double theta = pow((double)base, -2.0 * (double)i / (double)hd);
+  double ang = (double)p * theta, s, c;
+  sincos(ang, &s, &c);
+  cs[idx] = make_float2((float)c, (float)s);
+}
+
+void launch_rope_table(float *cs, const int32_t *pos, int M, int hd, float base, hipStream_t st) {
+  int half = hd / 2, n = M * half;
+  hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, st, (float2 *)cs, pos, M, half, hd, base);
+}
+
+// One block.  Records the token sampled at generation step *d_step for every active sequence, chooses the
+// token fed back (forced or sampled), applies the stop rules and prepares the rows of the next decode pass.
+__global__ void bookkeeping_kernel(int N, int max_new, int32_t *d_step, const int32_t *samp_tok, const float *samp_lp,
+                                   const int32_t *forced, const int32_t *limit, int eos, int64_t version,
+                                   const int32_t *prompt_len, int32_t *gen_len, RowState rows, int32_t *out_tok,
+                                   float *out_lp, int64_t *out_ver, int32_t *n_active) {
+  __shared__ int cnt;
+  if (threadIdx.x == 0) cnt = 0;
+  __syncthreads();
+  int s = *d_step;
+  int mine = 0;
+  for (int n = threadIdx.x; n < N; n += blockDim.x) {
+    if (!rows.active[n]) continue;
+    int tok = samp_tok[n];
+    int64_t o = (int64_t)n * max_new + s;
+    out_tok[o] = tok;
+    out_lp[o] = samp_lp[n];
+    out_ver[o] = version;
+    int fed = forced ? forced[o] : tok;
+    int len = s + 1;
+    gen_len[n] = len;
+    bool done = (len >= limit[n]) || (eos >= 0 && fed == eos);
+    rows.token[n] = fed;
+    rows.pos[n] = prompt_len[n] + s;
+    rows.active[n] = done ? 0 : 1;
+    mine += done ? 0 : 1;
+  }
+  if (mine) atomicAdd(&cnt, mine);
+  __syncthreads();
+  if (threadIdx.x == 0) { *d_step = s + 1; *n_active = cnt; }
+}
+
+void launch_bookkeeping(int N, int max_new, int32_t *d_step, const int32_t *samp_tok, const float *samp_lp,
+                        const int32_t *forced, const int32_t *limit, int eos, int64_t version,
+                        const int32_t *prompt_len, int32_t *gen_len, RowState rows, int32_t *out_tok, float *out_lp,
+                        int64_t *out_ver, int32_t *n_active, hipStream_t st) {
+  hipLaunchKernelGGL(bookkeeping_kernel, dim3(1), dim3(256), 0, st, N, max_new, d_step, samp_tok, samp_lp, forced,
+                     limit, eos, version, prompt_len, gen_len, rows, out_tok, out_lp, out_ver, n_active);
+}
+
+// Copy the prompt part of slot p*G into slots p*G+1 .. p*G+G-1.  grid = (chunks, L*2*Hkv, P*(G-1)).
+__global__ void kv_replicate_kernel(KvGeom kv, const int32_t *prompt_len, int G) {
+  int p = blockIdx.z / (G - 1), g = blockIdx.z % (G - 1) + 1;
+  int64_t bytes = (int64_t)prompt_len[p] * kv.head_dim * kv.elt_bytes;
+  int64_t head_bytes = kv.head_stride() * kv.elt_bytes;
+  const char *src = (const char *)kv.base + ((int64_t)p * G) * kv.slot_stride() * kv.elt_bytes + blockIdx.y * head_bytes;
+  char *dst = (char *)kv.base + ((int64_t)p * G + g) * kv.slot_stride() * kv.elt_bytes + blockIdx.y * head_bytes;
+  int64_t n16 = bytes / 16;  // head_dim * elt_bytes is a multiple of 16
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (int64_t)gridDim.x * blockDim.x)
+    ((uint4 *)dst)[i] = ((const uint4 *)src)[i];
+}
+
+void launch_kv_replicate(KvGeom kv, const int32_t *prompt_len, int P, int G, hipStream_t st) {
+  if (G <= 1 || P <= 0) return;
+  hipLaunchKernelGGL(kv_replicate_kernel, dim3(8, kv.n_layers * 2 * kv.n_kv_heads, P * (G - 1)), dim3(256), 0, st, kv,
+                     prompt_len, G);
+}
+
+__global__ void draw_bits_kernel(uint32_t *out, uint64_t seed, uint32_t n, uint32_t s, uint32_t i0, int count) {
+  int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= count) return;
+  uint32_t i = i0 + (uint32_t)j;
+  u32x4 r = draw4(seed, n, s, i >> 2);
+  uint32_t w[4] = {r.x, r.y, r.z, r.w};
+  out[j] = w[i & 3u];
+}
+
+void launch_draw_bits(uint32_t *out, uint64_t seed, uint32_t n, uint32_t s, uint32_t i0, int count, hipStream_t st) {
+  hipLaunchKernelGGL(draw_bits_kernel, dim3((count + 255) / 256), dim3(256), 0, st, out, seed, n, s, i0, count);
+}
+
+__global__ void fill_i32_kernel(int32_t *p, int32_t v, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+void launch_fill_i32(int32_t *p, int32_t v, int64_t n, hipStream_t st) {
+  if (n <= 0) return;
+  int64_t blocks = (n + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p, v, n);
+}
+
+__global__ void gather_rows_kernel(float *dst, const float *src, const int32_t *src_row, int width) {
+  int r = src_row[blockIdx.x];
+  if (r < 0) return;
+  for (int i = threadIdx.x; i < width; i += blockDim.x) dst[(int64_t)blockIdx.x * width + i] = src[(int64_t)r * width + i];
+}
+
+void launch_gather_rows_f32(float *dst, const float *src, const int32_t *src_row, int n_dst, int width, hipStream_t st) {
+  if (n_dst <= 0) return;
+  hipLaunchKernelGGL(gather_rows_kernel, dim3(n_dst), dim3(256), 0, st, dst, src, src_row, width);
+}
+
+}  // namespace echo

@@ -1,0 +1,297 @@
+// bf16 MFMA path, dense contractions: weight repacking, the weight-streaming GEMM (split-K over the
+// wavefronts of a workgroup and over the grid) with its epilogues, and the lm_head GEMM whose epilogue
+// is the sampler (temperature, Gumbel-max, running log-sum-exp), so logits never reach HBM.
+//
+// Operand roles of v_mfma_f32_32x32x16_bf16 here: A = 32 weight rows x 16 k, B = 16 k x 32 batch rows.
+// Lane l supplies A[row l%32][k 8*(l/32) .. +8] and B[k 8*(l/32) .. +8][col l%32]; it receives
+// D[row 8*g + 4*(l/32) + i][col l%32] in accumulator register 4*g + i (g, i in 0..3).
+#include "echo_device.h"
+#include "echo_kernels.h"
+
+namespace echo {
+
+// ---- weight repacking --------------------------------------------------------------------------------
+// src: row-major bf16 [n_rows][K]; destination row of source row i is dst_row0 + i*dst_row_stride.
+__global__ void pack_weight_kernel(uint4 *dst, const uint4 *src, int64_t dst_row0, int dst_row_stride, int64_t n_rows,
+                                   int K8, int Kp8) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n_rows * K8) return;
+  int64_t i = idx / K8;
+  int k8 = (int)(idx % K8);
+  int64_t r = dst_row0 + i * dst_row_stride;
+  dst[((r >> 5) * Kp8 + k8) * 32 + (r & 31)] = src[idx];
+}
+
+void fast_pack_weight(void *dst, const void *src, int64_t dst_row0, int dst_row_stride, int64_t n_rows, int K, int Kp,
+                      hipStream_t st) {
+  int64_t n = n_rows * (K / 8);
+  if (n <= 0) return;
+  hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (uint4 *)dst,
+                     (const uint4 *)src, dst_row0, dst_row_stride, n_rows, K / 8, Kp / 8);
+}
+
+// ---- the MFMA inner loop -------------------------------------------------------------------------------
+template <int MB>
+__device__ __forceinline__ void mma_range(f32x16 (&acc)[MB], const bf16x8 *__restrict__ Wnb,
+                                          const bf16x8 *__restrict__ Xp, int Mp, int ks0, int ks1, int lane) {
+  const bf16x8 *a_ptr = Wnb + (lane >> 5) * 32 + (lane & 31);
+  const bf16x8 *b_ptr = Xp + (int64_t)(lane >> 5) * Mp + (lane & 31);
+#pragma unroll 4
+  for (int ks = ks0; ks < ks1; ++ks) {
+    bf16x8 a = __builtin_nontemporal_load(a_ptr + (int64_t)ks * 64);
+    const bf16x8 *bp = b_ptr + (int64_t)ks * 2 * Mp;
+#pragma unroll
+    for (int j = 0; j < MB; ++j) {
+      bf16x8 b = bp[j * 32];
+      acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+    }
+  }
+}
+
+template <int MB>
+__device__ __forceinline__ void reduce_waves(f32x16 (&acc)[MB], float *red, int w, int waves, int lane) {
+  if (waves == 1) return;
+  if (w > 0) {
+#pragma unroll
+    for (int j = 0; j < MB; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) red[(((w - 1) * MB + j) * 16 + r) * 64 + lane] = acc[j][r];
+  }
+  __syncthreads();
+  if (w == 0) {
+    for (int ww = 1; ww < waves; ++ww)
+#pragma unroll
+      for (int j = 0; j < MB; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[j][r] += red[(((ww - 1) * MB + j) * 16 + r) * 64 + lane];
+  }
+}
+
+__device__ __forceinline__ float silu_f(float x) { return x / (1.0f + expf(-x)); }
+
+// grid (Np/32, nsplit, Mp/(32*MB)); block 64*waves.  One 32-row weight block per workgroup; the k-steps of
+// this grid split are divided among the workgroup's wavefronts and summed in LDS in wavefront order.
+template <int MB, int EPI>
+__global__ __launch_bounds__(512) void gemm_kernel(void *out, const bf16x8 *__restrict__ Xp, const bf16x8 *__restrict__ Wp,
+                                                   int Mp, int Np, int Kp, int ksteps_per_split) {
+  extern __shared__ float red[];
+  int waves = blockDim.x >> 6, w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  int nb = blockIdx.x, split = blockIdx.y, mblk0 = blockIdx.z * MB;
+  int ksteps = Kp >> 4;
+  int s0 = split * ksteps_per_split, s1 = min(ksteps, s0 + ksteps_per_split);
+  int per_wave = (s1 - s0 + waves - 1) / waves;
+  int k0 = min(s1, s0 + w * per_wave), k1 = min(s1, k0 + per_wave);
+  f32x16 acc[MB];
+#pragma unroll
+  for (int j = 0; j < MB; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+  mma_range<MB>(acc, Wp + (int64_t)nb * (Kp >> 3) * 32, Xp + mblk0 * 32, Mp, k0, k1, lane);
+  reduce_waves<MB>(acc, red, w, waves, lane);
+  if (w != 0) return;
+  int half = lane >> 5, col = lane & 31;
+  if (EPI == EPI_PARTIAL) {
+    f32x4 *P = (f32x4 *)out;
+#pragma unroll
+    for (int j = 0; j < MB; ++j) {
+      int m = (mblk0 + j) * 32 + col;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        int n4 = nb * 8 + half + 2 * g;
+        f32x4 v = {acc[j][4 * g], acc[j][4 * g + 1], acc[j][4 * g + 2], acc[j][4 * g + 3]};
+        P[((int64_t)split * (Np >> 2) + n4) * Mp + m] = v;
+      }
+    }
+  } else {  // EPI_SWIGLU: rows alternate gate_f, up_f
+    uint32_t *O = (uint32_t *)out;
+#pragma unroll
+    for (int j = 0; j < MB; ++j) {
+      int m = (mblk0 + j) * 32 + col;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        int f = nb * 16 + half * 2 + 4 * g;
+        float v0 = silu_f(acc[j][4 * g]) * acc[j][4 * g + 1];
+        float v1 = silu_f(acc[j][4 * g + 2]) * acc[j][4 * g + 3];
+        uint32_t pk = (uint32_t)f32_to_bf16_bits(v0) | ((uint32_t)f32_to_bf16_bits(v1) << 16);
+        O[(((int64_t)(f >> 3) * Mp + m) * 8 + (f & 7)) >> 1] = pk;
+      }
+    }
+  }
+}
+
+int fast_gemm_pick(int Np, int Kp, int Mp, int *nsplit, int *waves_k) {
+  int nblocks = Np / 32, ksteps = Kp / 16, mb = Mp / 32 > 8 ? 8 : Mp / 32;
+  int zblocks = Mp / (32 * mb);
+  int want = 2560 / (nblocks * zblocks);          // wavefronts per weight block to fill 256 CUs ~10 deep
+  int cap = ksteps / 8;                           // at least 8 k-steps per wavefront
+  if (want > cap) want = cap;
+  if (want < 1) want = 1;
+  int wmax = 8;
+  while (wmax > 1 && (wmax - 1) * mb * 4096 > 65536) --wmax;   // LDS for the in-workgroup reduction
+  int wk = want < wmax ? want : wmax;
+  int ns = (want + wk - 1) / wk;
+  *nsplit = ns;
+  *waves_k = wk;
+  return 0;
+}
+
+template <int EPI>
+static void gemm_dispatch(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, int nsplit, int waves_k,
+                          hipStream_t st) {
+  int mbt = Mp / 32;
+  int MB = mbt >= 8 ? 8 : mbt;
+  int ksteps = Kp / 16, kps = (ksteps + nsplit - 1) / nsplit;
+  dim3 grid(Np / 32, nsplit, mbt / MB), block(64 * waves_k);
+  size_t lds = (size_t)(waves_k - 1) * MB * 16 * 64 * sizeof(float);
+  const bf16x8 *X = (const bf16x8 *)Xp, *W = (const bf16x8 *)Wp;
+  switch (MB) {
+    case 1: hipLaunchKernelGGL((gemm_kernel<1, EPI>), grid, block, lds, st, out, X, W, Mp, Np, Kp, kps); break;
+    case 2: hipLaunchKernelGGL((gemm_kernel<2, EPI>), grid, block, lds, st, out, X, W, Mp, Np, Kp, kps); break;
+    case 4: hipLaunchKernelGGL((gemm_kernel<4, EPI>), grid, block, lds, st, out, X, W, Mp, Np, Kp, kps); break;
+    default: hipLaunchKernelGGL((gemm_kernel<8, EPI>), grid, block, lds, st, out, X, W, Mp, Np, Kp, kps); break;
+  }
+}
+
+void fast_gemm(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, int nsplit, int waves_k,
+               GemmEpilogue epi, hipStream_t st) {
+  if (epi == EPI_PARTIAL) gemm_dispatch<EPI_PARTIAL>(out, Xp, Wp, Mp, Np, Kp, nsplit, waves_k, st);
+  else gemm_dispatch<EPI_SWIGLU>(out, Xp, Wp, Mp, Np, Kp, 1, waves_k, st);
+}
+
+// ---- lm_head ---------------------------------------------------------------------------------------------
+// grid (ceil(Np/32 / (4*NBSEQ)), 1, Mp/(32*MB)); block 256.  Each wavefront runs NBSEQ weight blocks over the full
+// K and folds every logit into a running (max, sum-exp, best perturbed score, its index, its z) per batch row.
+constexpr int LM_NBSEQ = 2;
+
+template <int MB, bool LOGITS>
+__global__ __launch_bounds__(256) void lmhead_kernel(const bf16x8 *__restrict__ Xp, const bf16x8 *__restrict__ Wp, int Mp,
+                                                     int Np, int Kp, int V, float temperature, uint64_t seed,
+                                                     const int32_t *d_step, const int32_t *target, float *target_z,
+                                                     float *part, int n_wg, float *logits, int64_t ld) {
+  __shared__ SampleAcc sh[3][MB][32];
+  int w = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
+  int mblk0 = blockIdx.z * MB, nblocks = Np >> 5;
+  uint32_t step = LOGITS ? 0u : (uint32_t)*d_step;
+  SampleAcc sa[MB];
+#pragma unroll
+  for (int j = 0; j < MB; ++j) sa[j] = sample_acc_init();
+  for (int q = 0; q < LM_NBSEQ; ++q) {
+    int nb = (blockIdx.x * 4 + w) * LM_NBSEQ + q;
+    if (nb >= nblocks) break;
+    f32x16 acc[MB];
+#pragma unroll
+    for (int j = 0; j < MB; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+    mma_range<MB>(acc, Wp + (int64_t)nb * (Kp >> 3) * 32, Xp + mblk0 * 32, Mp, 0, Kp >> 4, lane);
+#pragma unroll
+    for (int j = 0; j < MB; ++j) {
+      int m = (mblk0 + j) * 32 + col;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        int v0 = nb * 32 + 8 * g + 4 * half;
+        if (v0 >= V) continue;
+        if (LOGITS) {
+          f32x4 o = {acc[j][4 * g], acc[j][4 * g + 1], acc[j][4 * g + 2], acc[j][4 * g + 3]};
+          *(f32x4 *)(logits + (int64_t)m * ld + v0) = o;
+        } else {
+          u32x4 r = draw4(seed, (uint32_t)m, step, (uint32_t)(v0 >> 2));
+          uint32_t bits[4] = {r.x, r.y, r.z, r.w};
+          int tgt = target ? target[m] : -1;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            if (v0 + i >= V) break;
+            float z = acc[j][4 * g + i] / temperature;
+            sample_acc_add(sa[j], z, z + gumbel_from_bits(bits[i]), v0 + i);
+            if (v0 + i == tgt) target_z[m] = z;
+          }
+        }
+      }
+    }
+  }
+  if (LOGITS) return;
+  // lanes l and l^32 hold the same batch row; then fold the four wavefronts in wavefront order
+#pragma unroll
+  for (int j = 0; j < MB; ++j) { SampleAcc b = sample_acc_shfl_xor(sa[j], 32); sample_acc_merge(sa[j], b); }
+  if (w > 0 && half == 0)
+#pragma unroll
+    for (int j = 0; j < MB; ++j) sh[w - 1][j][col] = sa[j];
+  __syncthreads();
+  if (w == 0 && half == 0) {
+#pragma unroll
+    for (int j = 0; j < MB; ++j) {
+      for (int ww = 0; ww < 3; ++ww) sample_acc_merge(sa[j], sh[ww][j][col]);
+      int m = (mblk0 + j) * 32 + col;
+      int64_t o = (int64_t)blockIdx.x * Mp + m, plane = (int64_t)n_wg * Mp;
+      part[o] = sa[j].zmax;
+      part[plane + o] = sa[j].zsum;
+      part[2 * plane + o] = sa[j].best;
+      part[3 * plane + o] = sa[j].zbest;
+      part[4 * plane + o] = __int_as_float(sa[j].idx);
+    }
+  }
+}
+
+// grid M rows, block 256: fold the per-workgroup partials of one row in workgroup order.
+__global__ void sample_combine_kernel(int32_t *tok, float *lp, float *target_lp, const float *part, int n_wg, int Mp,
+                                      const int32_t *row_active, const int32_t *target, const float *target_z) {
+  __shared__ SampleAcc sh[4];
+  int m = blockIdx.x;
+  if (row_active && !row_active[m]) return;
+  int64_t plane = (int64_t)n_wg * Mp;
+  SampleAcc a = sample_acc_init();
+  for (int g = threadIdx.x; g < n_wg; g += blockDim.x) {
+    int64_t o = (int64_t)g * Mp + m;
+    SampleAcc b = {part[o], part[plane + o], part[2 * plane + o], part[3 * plane + o], __float_as_int(part[4 * plane + o])};
+    sample_acc_merge(a, b);
+  }
+  for (int o = 32; o > 0; o >>= 1) { SampleAcc b = sample_acc_shfl_xor(a, o); sample_acc_merge(a, b); }
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = a;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w) sample_acc_merge(a, sh[w]);
+    float lse = a.zmax + logf(a.zsum);
+    tok[m] = a.idx;
+    lp[m] = a.zbest - lse;
+    if (target_lp) target_lp[m] = (target && target[m] >= 0) ? target_z[m] - lse : 0.f;
+  }
+}
+
+static int lm_wgs(int Np) { return (Np / 32 + 4 * LM_NBSEQ - 1) / (4 * LM_NBSEQ); }
+size_t fast_lmhead_partial_floats(int Np, int Mp) { return (size_t)5 * lm_wgs(Np) * Mp + Mp; }
+
+template <bool LOGITS>
+static void lmhead_dispatch(const void *Xp, const void *Wp, int Mp, int Np, int Kp, int V, float temperature, uint64_t seed,
+                            const int32_t *d_step, const int32_t *target, float *target_z, float *part, float *logits,
+                            int64_t ld, hipStream_t st) {
+  int mbt = Mp / 32, MB = mbt >= 8 ? 8 : mbt, n_wg = lm_wgs(Np);
+  dim3 grid(n_wg, 1, mbt / MB), block(256);
+  const bf16x8 *X = (const bf16x8 *)Xp, *W = (const bf16x8 *)Wp;
+#define LM_LAUNCH(MBV)                                                                                               \
+  hipLaunchKernelGGL((lmhead_kernel<MBV, LOGITS>), grid, block, 0, st, X, W, Mp, Np, Kp, V, temperature, seed, d_step, \
+                     target, target_z, part, n_wg, logits, ld)
+  switch (MB) {
+    case 1: LM_LAUNCH(1); break;
+    case 2: LM_LAUNCH(2); break;
+    case 4: LM_LAUNCH(4); break;
+    default: LM_LAUNCH(8); break;
+  }
+#undef LM_LAUNCH
+}
+
+void fast_lmhead_sample(int32_t *tok, float *lp, float *target_lp, const void *Xp, const void *Wp, int Mp, int M, int V,
+                        int Np, int Kp, float temperature, uint64_t seed, const int32_t *d_step, const int32_t *row_active,
+                        const int32_t *target, float *partials, hipStream_t st) {
+  int n_wg = lm_wgs(Np);
+  float *target_z = partials + (size_t)5 * n_wg * Mp;
+  lmhead_dispatch<false>(Xp, Wp, Mp, Np, Kp, V, temperature, seed, d_step, target, target_z, partials, nullptr, 0, st);
+  hipLaunchKernelGGL(sample_combine_kernel, dim3(M), dim3(256), 0, st, tok, lp, target_lp, partials, n_wg, Mp, row_active,
+                     target, target_z);
+}
+
+void fast_lmhead_logits(float *logits, int64_t ld, const void *Xp, const void *Wp, int Mp, int Np, int Kp, int V,
+                        hipStream_t st) {
+  lmhead_dispatch<true>(Xp, Wp, Mp, Np, Kp, V, 1.0f, 0, nullptr, nullptr, nullptr, nullptr, logits, ld, st);
+}
+
+}  // namespace echo

@@ -1,0 +1,203 @@
+"""ctypes binding of the C-ABI library (include/echo.h).  Argument marshalling only: every step of
+the rollout runs in the library's HIP kernels.  PyTorch provides the device arena and the streams.
+
+Importing this module loads paper_2602_02192_amd/libecho_hip.so and raises if it is missing:
+there is no CPU fallback."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libecho_hip.so")
+if not os.path.exists(_LIB_PATH):
+    raise ImportError(f"{_LIB_PATH} is not built; run `python -m paper_2602_02192_amd.build` "
+                      "(the rollout path has no fallback without the HIP library)")
+lib = C.CDLL(_LIB_PATH)
+
+ECHO_OK, ECHO_EINVAL, ECHO_ENOMEM, ECHO_ESTATE, ECHO_EHIP = 0, -1, -2, -3, -4
+ECHO_F32, ECHO_BF16 = 0, 1
+
+
+class ModelDesc(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_q_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("ffn", C.c_int32),
+                ("vocab", C.c_int32), ("rms_eps", C.c_float), ("rope_base", C.c_float),
+                ("dtype", C.c_int32), ("qk_norm", C.c_int32), ("tie_embeddings", C.c_int32),
+                ("max_seqs", C.c_int32), ("max_ctx", C.c_int32), ("n_weight_slots", C.c_int32),
+                ("debug_naive", C.c_int32)]
+
+
+class RolloutOpts(C.Structure):
+    _fields_ = [("stop_lens", C.c_void_p), ("eos_id", C.c_int32), ("top_p", C.c_float),
+                ("n_swaps", C.c_int32), ("swap_at_step", C.c_void_p), ("swap_timeout_ms", C.c_int32),
+                ("forced_tokens", C.c_void_p), ("debug_logits", C.c_void_p),
+                ("unfused_sampler", C.c_int32), ("no_graph", C.c_int32), ("time_kernels", C.c_int32)]
+
+
+class Stats(C.Structure):
+    _fields_ = [("active_version", C.c_int64), ("staged_version", C.c_int64),
+                ("decode_steps", C.c_int32), ("prefill_ms", C.c_float), ("decode_ms", C.c_float),
+                ("total_ms", C.c_float), ("swap_wait_ms", C.c_float),
+                ("attn_launches", C.c_int64), ("attn_ms", C.c_double), ("attn_bytes", C.c_double),
+                ("gemm_launches", C.c_int64), ("gemm_ms", C.c_double), ("gemm_bytes", C.c_double)]
+
+
+EXPORTS = ["echo_arena_bytes", "echo_blob_bytes", "echo_init", "echo_load_policy", "echo_rollout",
+           "echo_logprobs", "echo_debug_draw_bits", "echo_stats", "echo_last_error", "echo_destroy"]
+
+lib.echo_arena_bytes.restype = C.c_size_t
+lib.echo_arena_bytes.argtypes = [C.POINTER(ModelDesc)]
+lib.echo_blob_bytes.restype = C.c_size_t
+lib.echo_blob_bytes.argtypes = [C.POINTER(ModelDesc)]
+lib.echo_init.argtypes = [C.POINTER(ModelDesc), C.c_int, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p,
+                          C.POINTER(C.c_void_p)]
+lib.echo_load_policy.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t]
+lib.echo_rollout.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                             C.c_float, C.c_uint64, C.POINTER(RolloutOpts), C.c_void_p, C.c_void_p, C.c_void_p,
+                             C.c_void_p]
+lib.echo_logprobs.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_float, C.c_void_p]
+lib.echo_debug_draw_bits.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int32,
+                                     C.c_void_p]
+lib.echo_stats.argtypes = [C.c_void_p, C.POINTER(Stats)]
+lib.echo_last_error.restype = C.c_char_p
+lib.echo_last_error.argtypes = [C.c_void_p]
+lib.echo_destroy.argtypes = [C.c_void_p]
+
+
+class EchoError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"echo error {code}: {msg}")
+        self.code = code
+
+
+def desc_from_shape(shape, max_seqs: int, max_ctx: int, n_weight_slots: int = 1,
+                    debug_naive: bool = False) -> ModelDesc:
+    return ModelDesc(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                     shape.ffn, shape.vocab, shape.rms_eps, shape.rope_base,
+                     ECHO_F32 if shape.dtype == "fp32" else ECHO_BF16, int(shape.qk_norm),
+                     int(shape.tie_embeddings), max_seqs, max_ctx, n_weight_slots, int(debug_naive))
+
+
+def arena_bytes(desc: ModelDesc) -> int:
+    return int(lib.echo_arena_bytes(C.byref(desc)))
+
+
+def blob_bytes(desc: ModelDesc) -> int:
+    return int(lib.echo_blob_bytes(C.byref(desc)))
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return a.ctypes.data_as(C.c_void_p) if a is not None else None
+
+
+class Context:
+    """echo_init / echo_destroy plus the calls of include/echo.h with numpy marshalling."""
+
+    def __init__(self, desc: ModelDesc, device: int = 0, compute_stream=None, copy_stream=None):
+        import torch
+        need = arena_bytes(desc)
+        if need == 0:
+            h = C.c_void_p()
+            rc = lib.echo_init(C.byref(desc), device, None, 0, None, None, C.byref(h))
+            raise EchoError(rc, lib.echo_last_error(None).decode())
+        self.desc = desc
+        self.device = device
+        self.arena = torch.empty(need + 256, dtype=torch.uint8, device=f"cuda:{device}")
+        base = (self.arena.data_ptr() + 255) // 256 * 256
+        self._streams = (compute_stream, copy_stream)
+        cs = compute_stream.cuda_stream if compute_stream is not None else None
+        ks = copy_stream.cuda_stream if copy_stream is not None else None
+        h = C.c_void_p()
+        rc = lib.echo_init(C.byref(desc), device, C.c_void_p(base), need, cs, ks, C.byref(h))
+        if rc != 0:
+            raise EchoError(rc, lib.echo_last_error(None).decode())
+        self.h = h
+
+    def _chk(self, rc: int) -> None:
+        if rc != 0:
+            raise EchoError(rc, lib.echo_last_error(self.h).decode())
+
+    def close(self) -> None:
+        if getattr(self, "h", None):
+            lib.echo_destroy(self.h)
+            self.h = None
+            self.arena = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def load_policy(self, version: int, blob) -> None:
+        """blob: host torch tensor or numpy array holding the flat weights in the model dtype."""
+        import torch
+        if isinstance(blob, torch.Tensor):
+            if blob.device.type != "cpu":
+                raise ValueError("echo_load_policy takes a host blob")
+            blob = blob.contiguous()
+            ptr, nbytes = blob.data_ptr(), blob.numel() * blob.element_size()
+        else:
+            blob = np.ascontiguousarray(blob)
+            ptr, nbytes = blob.ctypes.data, blob.nbytes
+        self._chk(lib.echo_load_policy(self.h, version, C.c_void_p(ptr), nbytes))
+
+    def rollout(self, prompts, prompt_lens, G: int, max_new: int, temperature: float, seed: int,
+                stop_lens=None, eos_id: int = -1, top_p: float = 1.0, swap_at_step: Sequence[int] = (),
+                swap_timeout_ms: int = 0, forced=None, want_logits: bool = False, unfused_sampler: bool = False,
+                no_graph: bool = False, time_kernels: bool = False) -> dict:
+        prompts = np.ascontiguousarray(prompts, np.int32)
+        prompt_lens = np.ascontiguousarray(prompt_lens, np.int32)
+        P = prompts.shape[0]
+        N = P * G
+        o = RolloutOpts()
+        o.eos_id, o.top_p = eos_id, top_p
+        keep = []
+        if stop_lens is not None:
+            a = np.ascontiguousarray(stop_lens, np.int32)
+            assert a.shape == (N,)
+            keep.append(a)
+            o.stop_lens = a.ctypes.data
+        sw = np.ascontiguousarray(list(swap_at_step), np.int32)
+        keep.append(sw)
+        o.n_swaps = sw.size
+        o.swap_at_step = sw.ctypes.data if sw.size else None
+        o.swap_timeout_ms = swap_timeout_ms
+        if forced is not None:
+            f = np.ascontiguousarray(forced, np.int32)
+            assert f.shape == (N, max_new)
+            keep.append(f)
+            o.forced_tokens = f.ctypes.data
+        logits = None
+        if want_logits:
+            logits = np.zeros((N, max_new, self.desc.vocab), np.float32)
+            o.debug_logits = logits.ctypes.data
+        o.unfused_sampler, o.no_graph, o.time_kernels = int(unfused_sampler), int(no_graph), int(time_kernels)
+        toks = np.empty((N, max_new), np.int32)
+        lps = np.empty((N, max_new), np.float32)
+        lens = np.empty(N, np.int32)
+        vers = np.empty((N, max_new), np.int64)
+        self._chk(lib.echo_rollout(self.h, _ptr(prompts), prompts.shape[1], _ptr(prompt_lens), P, G, max_new,
+                                   temperature, seed, C.byref(o), _ptr(toks), _ptr(lps), _ptr(lens), _ptr(vers)))
+        return dict(tokens=toks, logprobs=lps, lens=lens, versions=vers, logits=logits)
+
+    def logprobs(self, tokens, lens, temperature: float = 1.0) -> np.ndarray:
+        tokens = np.ascontiguousarray(tokens, np.int32)
+        lens = np.ascontiguousarray(lens, np.int32)
+        out = np.zeros(tokens.shape, np.float32)
+        self._chk(lib.echo_logprobs(self.h, _ptr(tokens), tokens.shape[1], _ptr(lens), tokens.shape[0], temperature,
+                                    _ptr(out)))
+        return out
+
+    def draw_bits(self, seed: int, n: int, s: int, i0: int, count: int) -> np.ndarray:
+        out = np.empty(count, np.uint32)
+        self._chk(lib.echo_debug_draw_bits(self.h, seed, n, s, i0, count, _ptr(out)))
+        return out
+
+    def stats(self) -> Stats:
+        st = Stats()
+        self._chk(lib.echo_stats(self.h, C.byref(st)))
+        return st

@@ -1,0 +1,52 @@
+"""Shared helpers of the GPU parity tests: build a context for a shape, run the oracle on the same
+seeded inputs, and compare under the stated tolerances."""
+import numpy as np
+
+from oracle import oracle
+from paper_2602_02192_amd import synth
+
+# Tolerances (bf16 path, teacher-forced on the oracle's token stream): the workload statement's
+# max |logit diff| <= 3e-2, |logprob diff| <= 1e-2, argmax agreement >= 99.5 %.  The all-fp32 path
+# differs from the fp64 oracle only by fp32 rounding and summation order.
+BF16_LOGIT_TOL, BF16_LOGPROB_TOL, BF16_ARGMAX_RATE = 3e-2, 1e-2, 0.995
+F32_LOGIT_TOL, F32_LOGPROB_TOL = 2e-4, 2e-4
+NEAR_TIE_GAP = 1e-4      # fp32 sampler: a top-2 perturbed-score gap below this may resolve either way
+
+
+def make_ctx(shape, max_seqs, max_ctx, blob=None, version=0, slots=1, debug_naive=False):
+    from paper_2602_02192_amd import echo
+    desc = echo.desc_from_shape(shape, max_seqs, max_ctx, n_weight_slots=slots, debug_naive=debug_naive)
+    ctx = echo.Context(desc)
+    if blob is not None:
+        ctx.load_policy(version, blob)
+    return ctx
+
+
+def oracle_rollout(shape, blob_f32, prompts, lens, **kw):
+    orc = oracle.load("f64")
+    return orc.rollout(oracle.desc_from_shape(shape), blob_f32, prompts, lens, **kw)
+
+
+def valid_mask(lens, max_new):
+    return np.arange(max_new)[None, :] < np.asarray(lens)[:, None]
+
+
+def check_tokens_fp32_sampler(gpu_tokens, ref, mask=None):
+    """Tokens equal the oracle's wherever the oracle's top-2 perturbed-score gap is not a near-tie."""
+    m = valid_mask(ref["lens"], ref["tokens"].shape[1]) if mask is None else mask
+    bad = (gpu_tokens != ref["tokens"]) & m & (ref["gaps"] >= NEAR_TIE_GAP)
+    assert not bad.any(), f"{bad.sum()} token mismatches outside near-ties at {np.argwhere(bad)[:5]}"
+    return int(((gpu_tokens != ref["tokens"]) & m).sum())
+
+
+def argmax_agreement(gpu_logits, ref_logits, mask, tol):
+    """Rate over positions whose oracle top-1/top-2 logit gap exceeds 2*tol (inside the gap either
+    candidate is a correct argmax), and the raw rate over all positions."""
+    g = gpu_logits[mask]
+    r = ref_logits[mask]
+    ga, ra = g.argmax(-1), r.argmax(-1)
+    part = np.partition(r, -2, axis=-1)
+    gap = part[:, -1] - part[:, -2]
+    clear = gap > 2 * tol
+    rate_clear = float((ga[clear] == ra[clear]).mean()) if clear.any() else 1.0
+    return rate_clear, float((ga == ra).mean()), int(clear.sum())
