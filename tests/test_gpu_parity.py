@@ -75,3 +75,36 @@ def test_tiny_bf16_teacher_forced_matches_oracle(debug_naive):
         assert np.array_equal(fused["tokens"], tf["tokens"])
         assert np.abs(fused["logprobs"] - unf["logprobs"]).max() < 1e-5
     ctx.close()
+
+
+MID = synth.ModelShape(2, 512, 8, 2, 128, 1024, 2048, dtype="bf16")
+
+
+def test_mid_bf16_ragged_long_context_splitk_vs_oracle_and_simple(monkeypatch):
+    """head_dim 128, 4 query heads per KV head, ragged prompts that span several 256-key chunks and a
+    ragged tail tile; the split-K MFMA attention against the oracle and against the plain kernel."""
+    shape = MID
+    blob = synth.make_weights(shape, 3)
+    blob32 = synth.widen_to_f32(blob)
+    prompts, lens = synth.make_prompts(shape.vocab, 3, 333, seed=4, ragged=True)
+    lens[0] = 333                       # one prompt at full length: 2 chunks, last tile of 13 keys
+    prompts[0] = synth.make_prompts(shape.vocab, 1, 333, seed=5)[0][0]
+    stop = np.array([8, 3, 8, 5, 1, 8], np.int32)
+    ref = oracle_rollout(shape, blob32, prompts, lens, G=2, max_new=8, temperature=1.0, seed=7, stop_lens=stop,
+                         want_logits=True)
+    ctx = make_ctx(shape, 6, 352, blob)
+    tf = ctx.rollout(prompts, lens, 2, 8, 1.0, 7, stop_lens=stop, forced=np.maximum(ref["tokens"], 0), want_logits=True)
+    assert np.array_equal(tf["lens"], ref["lens"])
+    m = valid_mask(ref["lens"], 8)
+    err = np.abs(tf["logits"] - ref["logits"])[m].max()
+    assert err < BF16_LOGIT_TOL, err
+    assert (tf["tokens"][~m] == -1).all() and (tf["logprobs"][~m] == 0).all() and (tf["versions"][~m] == -1).all()
+    same = (tf["tokens"] == ref["tokens"]) & m
+    assert same[m].mean() > 0.9
+    assert np.abs(tf["logprobs"] - ref["logprobs"])[same].max() < BF16_LOGPROB_TOL
+    monkeypatch.setenv("ECHO_ATTN_SIMPLE", "1")
+    simple = ctx.rollout(prompts, lens, 2, 8, 1.0, 7, stop_lens=stop, forced=np.maximum(ref["tokens"], 0), want_logits=True)
+    monkeypatch.delenv("ECHO_ATTN_SIMPLE")
+    assert np.abs(simple["logits"] - ref["logits"])[m].max() < BF16_LOGIT_TOL
+    assert np.abs(simple["logits"] - tf["logits"])[m].max() < BF16_LOGIT_TOL
+    ctx.close()
