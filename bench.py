@@ -1,0 +1,150 @@
+"""Rollout-generation benchmark on one MI355X.
+
+A "step" is one whole rollout of the workload (prefill of the unique prompts, KV replication, every
+decode step with fused sampling, result read-back), with the policy already installed in HBM.
+Prints one JSON line: generated tokens/s, the HBM roofline of the decode-attention kernel measured
+with HIP events inside the library, and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+WORKLOADS = {
+    # name: (shape attr, prompts, G, prompt_len, max_new)
+    "tiny-fp32": ("TINY", 4, 2, 16, 32),
+    "dense4b-64x512+1024": ("DENSE_4B", 8, 8, 512, 1024),
+    "dense8b-128x512+2048": ("DENSE_8B", 16, 8, 512, 2048),
+}
+
+
+def algorithmic_bytes(shape, n_seqs, prompt_len, max_new):
+    """HBM bytes the decode steps must move: all decode-read weights once per step, every active
+    sequence's K/V once per step, and the new K/V written."""
+    e = 2 if shape.dtype == "bf16" else 4
+    hd, H = shape.head_dim, shape.hidden
+    per_layer = H * (shape.n_q_heads + 2 * shape.n_kv_heads) * hd + shape.n_q_heads * hd * H + 3 * H * shape.ffn
+    w_dec = (shape.n_layers * per_layer + shape.vocab * H) * e
+    kvb = 2 * shape.n_layers * shape.n_kv_heads * hd * e
+    total = 0
+    for s in range(1, max_new):          # decode pass s reads prompt_len + s keys per sequence
+        total += w_dec + n_seqs * (prompt_len + s) * kvb + n_seqs * kvb
+    return total, w_dec, kvb
+
+
+def cpu_baseline(shape, blob, seconds_budget=20.0):
+    """The oracle (fp32 build, as it stands) on one sequence of the same model: a short prompt and a
+    few generated tokens, all layers at full width."""
+    from oracle import oracle
+    from paper_2602_02192_amd import synth
+    orc = oracle.load("f32")
+    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")))
+    orc.set_threads(cores)
+    prompt_len, new = (16, 32) if shape.n_layers <= 2 else (8, 4)
+    prompts, lens = synth.make_prompts(shape.vocab, 1, prompt_len, seed=1)
+    b32 = synth.widen_to_f32(blob)
+    t0 = time.perf_counter()
+    r = orc.rollout(oracle.desc_from_shape(shape), b32, prompts, lens, G=1, max_new=new, temperature=1.0, seed=2)
+    dt = time.perf_counter() - t0
+    del b32
+    return {"value": float(r["lens"].sum() / dt), "unit": "generated tokens/s", "cores": orc.get_threads(),
+            "kind": "oracle", "sample": f"fp32 oracle, 1 sequence, prompt {prompt_len} + {new} new tokens, all "
+            f"{shape.n_layers} layers at full width, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="dense4b-64x512+1024", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py measures one GPU: rollout workers are independent (data parallel over prompts) and "
+                 "this build runs a single MI355X; run with --gpus 1")
+    import torch
+    from paper_2602_02192_amd import echo, synth
+
+    name, P, G, plen, max_new = WORKLOADS[a.workload]
+    shape = getattr(synth, name)
+    N = P * G
+    torch.cuda.set_device(0)
+    blob_dev = synth.make_weights(shape, 0, device="cuda")
+    blob = torch.empty(blob_dev.shape, dtype=blob_dev.dtype, pin_memory=True)
+    blob.copy_(blob_dev)
+    del blob_dev
+    torch.cuda.empty_cache()
+    prompts, lens = synth.make_prompts(shape.vocab, P, plen, seed=1)
+    ctx = echo.Context(echo.desc_from_shape(shape, N, plen + max_new))
+    t0 = time.perf_counter()
+    ctx.load_policy(0, blob)
+    load_s = time.perf_counter() - t0
+
+    for _ in range(a.warmup):
+        ctx.rollout(prompts, lens, G, max_new, 1.0, 2)
+    torch.cuda.synchronize()
+    times, toks, decode_ms, prefill_ms = [], 0, [], []
+    t_all = time.perf_counter()
+    for k in range(a.steps):
+        t0 = time.perf_counter()
+        out = ctx.rollout(prompts, lens, G, max_new, 1.0, 2 + k)
+        times.append(time.perf_counter() - t0)
+        toks += int(out["lens"].sum())
+        st = ctx.stats()
+        decode_ms.append(st.decode_ms)
+        prefill_ms.append(st.prefill_ms)
+    torch.cuda.synchronize()
+    total_s = time.perf_counter() - t_all
+    value = toks / total_s
+
+    bytes_decode, w_dec, kvb = algorithmic_bytes(shape, N, plen, max_new)
+    step_frac = bytes_decode / (np.mean(decode_ms) * 1e-3) / (HBM_PEAK_GBS * 1e9)
+
+    roofline = None
+    if not a.no_kernel_timing:
+        ctx.rollout(prompts, lens, G, max_new, 1.0, 2, time_kernels=True)
+        st = ctx.stats()
+        if st.attn_launches:
+            per_launch_bytes = st.attn_bytes / st.attn_launches
+            per_launch_s = st.attn_ms * 1e-3 / st.attn_launches
+            ach = per_launch_bytes / per_launch_s / 1e9
+            roofline = {"bound": "hbm", "kernel": "attn_splitk_kernel + attn_combine_kernel (one launch pair per layer)",
+                        "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                        "traffic": None, "launches_timed": int(st.attn_launches),
+                        "avg_launch_us": per_launch_s * 1e6, "bytes_per_launch": per_launch_bytes}
+            if st.gemm_launches:
+                g = st.gemm_bytes / (st.gemm_ms * 1e-3) / 1e9
+                roofline["gemm_weight_stream"] = {"achieved": g, "frac": g / HBM_PEAK_GBS,
+                                                  "avg_launch_us": st.gemm_ms * 1e3 / st.gemm_launches,
+                                                  "launches_timed": int(st.gemm_launches)}
+    cpu = None
+    if not a.no_cpu_baseline:
+        cpu = cpu_baseline(shape, blob)
+    ctx.close()
+    line = {
+        "metric": "rollout generated tokens/s on 1 MI355X", "value": value, "unit": "generated tokens/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": 1e3 * total_s / a.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": shape.dtype, "data": "synthetic (random N(0,0.02) weights, uniform random prompt tokens)",
+        "config": {"workload": a.workload, "model": name, "sequences": N, "prompts": P, "group": G,
+                   "prompt_len": plen, "max_new": max_new, "temperature": 1.0},
+        "decode_step": {"mean_ms": float(np.mean(decode_ms)) / max(1, max_new - 1),
+                        "hbm_frac_of_8TBps": step_frac, "algorithmic_bytes_per_rollout": bytes_decode,
+                        "prefill_ms": float(np.mean(prefill_ms)), "policy_install_s": load_s},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

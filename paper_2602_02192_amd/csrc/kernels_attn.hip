@@ -62,6 +62,8 @@ void fast_attention_simple(void *Xp_out, const void *q_bf16, RowState rows, KvGe
 // lane l receives, in accumulator registers 0..3, the scores of key l%32 for query rows 4*(l/32)+i.
 // PV: A = P (bf16, through LDS), B = V with column c of MFMA e standing for head dimension (HD/32)*c + e,
 // so that a lane's B operand is built from 8-byte (HD=128) or 4-byte (HD=64) LDS reads of 8 keys.
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+typedef uint32_t v2u __attribute__((ext_vector_type(2)));
 constexpr int ATT_TILE = 32;     // keys per tile
 constexpr int ATT_WAVES = 4;
 
@@ -72,6 +74,19 @@ template <int HD> struct AttLds {
   static constexpr int MERGE_PER_WAVE = 8 * HD * 4 + 64;    // O rows + (m, l)
   static constexpr int TOTAL = ATT_WAVES * PER_WAVE;
 };
+
+template <int HD>
+__device__ __forceinline__ void att_issue_loads(v4u (&rk)[HD / 16], v4u (&rv)[HD / 16], const uint16_t *__restrict__ Kg,
+                                                const uint16_t *__restrict__ Vg, int tk0, int n_keys, int lane) {
+#pragma unroll
+  for (int i = 0; i < HD / 16; ++i) {
+    int u = i * 64 + lane, key = tk0 + u / (HD / 8);
+    key = min(key, n_keys - 1);               // tail keys re-read the last valid row (masked by the caller)
+    int64_t off = (int64_t)key * HD + (u % (HD / 8)) * 8;
+    rk[i] = *(const v4u *)(Kg + off);
+    rv[i] = *(const v4u *)(Vg + off);
+  }
+}
 
 template <int HD>
 __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__ part_o, float *__restrict__ part_ml,
@@ -98,8 +113,8 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
     const uint16_t *qrow = q_bf16 + ((int64_t)m * Hq + kvh * grp + (col < grp ? col : 0)) * HD;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      uint4 v = *(const uint4 *)(qrow + ks * 16 + half * 8);
-      if (col >= grp) v = make_uint4(0, 0, 0, 0);
+      v4u v = *(const v4u *)(qrow + ks * 16 + half * 8);
+      if (col >= grp) v = v4u{0u, 0u, 0u, 0u};
       qa[ks] = __builtin_bit_cast(bf16x8, v);
     }
   }
@@ -114,29 +129,18 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
     for (int r = 0; r < 16; ++r) o[e][r] = 0.f;
 
   // global -> register staging of one tile: 16-byte unit u = i*64 + lane covers key u/(HD/8), byte (u%(HD/8))*16
-  uint4 rk[LD], rv[LD];
-  auto issue_loads = [&](int tile) {
-    int tk0 = key0 + tile * ATT_TILE;
-#pragma unroll
-    for (int i = 0; i < LD; ++i) {
-      int u = i * 64 + lane, key = tk0 + u / (HD / 8);
-      key = min(key, n_keys - 1);               // tail keys re-read the last valid row (masked below)
-      int64_t off = (int64_t)key * HD + (u % (HD / 8)) * 8;
-      rk[i] = *(const uint4 *)(Kg + off);
-      rv[i] = *(const uint4 *)(Vg + off);
-    }
-  };
+  v4u rk[LD], rv[LD];
   int tile = w;
-  if (tile < ntiles) issue_loads(tile);
+  if (tile < ntiles) att_issue_loads<HD>(rk, rv, Kg, Vg, key0 + tile * ATT_TILE, n_keys, lane);
   for (; tile < ntiles; tile += ATT_WAVES) {
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // earlier LDS reads of this wavefront are done
 #pragma unroll
     for (int i = 0; i < LD; ++i) {
       int u = i * 64 + lane, key = u / (HD / 8), b = (u % (HD / 8)) * 16;
-      *(uint4 *)(Ks + key * L::ROW + b) = rk[i];
-      *(uint4 *)(Vs + key * L::ROW + b) = rv[i];
+      *(v4u *)(Ks + key * L::ROW + b) = rk[i];
+      *(v4u *)(Vs + key * L::ROW + b) = rv[i];
     }
-    if (tile + ATT_WAVES < ntiles) issue_loads(tile + ATT_WAVES);
+    if (tile + ATT_WAVES < ntiles) att_issue_loads<HD>(rk, rv, Kg, Vg, key0 + (tile + ATT_WAVES) * ATT_TILE, n_keys, lane);
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     // ---- S = Q K^T
     f32x16 sacc;
@@ -144,7 +148,7 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
     for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      uint4 kb = *(const uint4 *)(Ks + col * L::ROW + (ks * 16 + half * 8) * 2);
+      v4u kb = *(const v4u *)(Ks + col * L::ROW + (ks * 16 + half * 8) * 2);
       sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[ks], __builtin_bit_cast(bf16x8, kb), sacc, 0, 0, 0);
     }
     // ---- online softmax over this tile's 32 keys (rows 4*half + i, key = col)
@@ -173,13 +177,13 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
     for (int k2 = 0; k2 < 2; ++k2) {
-      uint4 pa = make_uint4(0, 0, 0, 0);
-      if (col < 8) pa = *(const uint4 *)(Ps + col * L::PROW + (k2 * 16 + half * 8) * 2);
+      v4u pa = v4u{0u, 0u, 0u, 0u};
+      if (col < 8) pa = *(const v4u *)(Ps + col * L::PROW + (k2 * 16 + half * 8) * 2);
       bf16x8 pA = __builtin_bit_cast(bf16x8, pa);
       if (HD == 128) {
-        uint2 vr[8];
+        v2u vr[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) vr[j] = *(const uint2 *)(Vs + (k2 * 16 + half * 8 + j) * L::ROW + col * 8);
+        for (int j = 0; j < 8; ++j) vr[j] = *(const v2u *)(Vs + (k2 * 16 + half * 8 + j) * L::ROW + col * 8);
 #pragma unroll
         for (int e = 0; e < NE; ++e) {
           uint32_t d[4];
@@ -188,7 +192,7 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
             uint32_t a = (e < 2) ? vr[2 * jj].x : vr[2 * jj].y, b = (e < 2) ? vr[2 * jj + 1].x : vr[2 * jj + 1].y;
             d[jj] = (e & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
           }
-          uint4 vb = make_uint4(d[0], d[1], d[2], d[3]);
+          v4u vb = v4u{d[0], d[1], d[2], d[3]};
           o[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pA, __builtin_bit_cast(bf16x8, vb), o[e], 0, 0, 0);
         }
       } else {  // HD == 64: two dims per column
@@ -203,7 +207,7 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
             uint32_t a = vr[2 * jj], b = vr[2 * jj + 1];
             d[jj] = (e & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
           }
-          uint4 vb = make_uint4(d[0], d[1], d[2], d[3]);
+          v4u vb = v4u{d[0], d[1], d[2], d[3]};
           o[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pA, __builtin_bit_cast(bf16x8, vb), o[e], 0, 0, 0);
         }
       }

@@ -31,20 +31,54 @@ void fast_pack_weight(void *dst, const void *src, int64_t dst_row0, int dst_row_
 }
 
 // ---- the MFMA inner loop -------------------------------------------------------------------------------
+// Loads run two groups of U k-steps ahead of the MFMAs (register double buffer), so that a wavefront keeps
+// 2*U*(1+MB) KiB of weight and activation reads in flight instead of waiting for each k-step.
+template <int MB, int U>
+struct KGroup {
+  bf16x8 a[U];
+  bf16x8 b[U][MB];
+};
+
+template <int MB, int U>
+__device__ __forceinline__ void load_group(KGroup<MB, U> &g, const bf16x8 *__restrict__ a_ptr, const bf16x8 *__restrict__ b_ptr,
+                                           int Mp, int ks) {
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    g.a[u] = __builtin_nontemporal_load(a_ptr + (int64_t)(ks + u) * 64);
+    const bf16x8 *bp = b_ptr + (int64_t)(ks + u) * 2 * Mp;
+#pragma unroll
+    for (int j = 0; j < MB; ++j) g.b[u][j] = bp[j * 32];
+  }
+}
+
+template <int MB, int U>
+__device__ __forceinline__ void mma_group(f32x16 (&acc)[MB], const KGroup<MB, U> &g) {
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+#pragma unroll
+    for (int j = 0; j < MB; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g.a[u], g.b[u][j], acc[j], 0, 0, 0);
+}
+
 template <int MB>
 __device__ __forceinline__ void mma_range(f32x16 (&acc)[MB], const bf16x8 *__restrict__ Wnb,
                                           const bf16x8 *__restrict__ Xp, int Mp, int ks0, int ks1, int lane) {
+  constexpr int U = MB <= 2 ? 4 : (MB == 4 ? 2 : 1);
   const bf16x8 *a_ptr = Wnb + (lane >> 5) * 32 + (lane & 31);
   const bf16x8 *b_ptr = Xp + (int64_t)(lane >> 5) * Mp + (lane & 31);
-#pragma unroll 4
-  for (int ks = ks0; ks < ks1; ++ks) {
+  int ng = (ks1 - ks0) / U;
+  KGroup<MB, U> g0, g1;
+  if (ng > 0) load_group<MB, U>(g0, a_ptr, b_ptr, Mp, ks0);
+  for (int g = 0; g < ng; g += 2) {
+    if (g + 1 < ng) load_group<MB, U>(g1, a_ptr, b_ptr, Mp, ks0 + (g + 1) * U);
+    mma_group<MB, U>(acc, g0);
+    if (g + 2 < ng) load_group<MB, U>(g0, a_ptr, b_ptr, Mp, ks0 + (g + 2) * U);
+    if (g + 1 < ng) mma_group<MB, U>(acc, g1);
+  }
+  for (int ks = ks0 + ng * U; ks < ks1; ++ks) {   // remainder
     bf16x8 a = __builtin_nontemporal_load(a_ptr + (int64_t)ks * 64);
     const bf16x8 *bp = b_ptr + (int64_t)ks * 2 * Mp;
 #pragma unroll
-    for (int j = 0; j < MB; ++j) {
-      bf16x8 b = bp[j * 32];
-      acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
-    }
+    for (int j = 0; j < MB; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bp[j * 32], acc[j], 0, 0, 0);
   }
 }
 

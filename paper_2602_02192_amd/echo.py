@@ -10,6 +10,8 @@ import os
 from typing import Optional, Sequence
 
 import numpy as np
+import torch  # noqa: F401  -- first: the library must bind to the HIP runtime PyTorch has already loaded,
+#                              so that the arena and the streams belong to the runtime its kernels run on
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libecho_hip.so")
 if not os.path.exists(_LIB_PATH):
@@ -97,7 +99,6 @@ class Context:
     """echo_init / echo_destroy plus the calls of include/echo.h with numpy marshalling."""
 
     def __init__(self, desc: ModelDesc, device: int = 0, compute_stream=None, copy_stream=None):
-        import torch
         need = arena_bytes(desc)
         if need == 0:
             h = C.c_void_p()
@@ -134,7 +135,6 @@ class Context:
 
     def load_policy(self, version: int, blob) -> None:
         """blob: host torch tensor or numpy array holding the flat weights in the model dtype."""
-        import torch
         if isinstance(blob, torch.Tensor):
             if blob.device.type != "cpu":
                 raise ValueError("echo_load_policy takes a host blob")
