@@ -245,6 +245,7 @@ void bind_slot(echo_ctx *c, int s) {
 
 // Copy a row-major bf16 matrix from the host blob through the staging buffer into a packed weight.
 int stage_matrix(echo_ctx *c, const void *dst, const char *src, int64_t rows, int K, int64_t dst_row0, int stride) {
+  int Np = (int)round_up(rows * stride, 32);
   int Kp = (int)round_up(K, 16);
   int64_t row_bytes = (int64_t)K * 2, rows_per = std::max<int64_t>(1, (int64_t)(c->p.stage_bytes / 2) / row_bytes);
   static int flip = 0;
@@ -253,7 +254,7 @@ int stage_matrix(echo_ctx *c, const void *dst, const char *src, int64_t rows, in
     char *stg = c->arena + c->p.o_stage + (flip ? c->p.stage_bytes / 2 : 0);
     flip ^= 1;
     HIPCHK(c, hipMemcpyAsync(stg, src + r * row_bytes, (size_t)(n * row_bytes), hipMemcpyHostToDevice, c->ks));
-    fast_pack_weight((void *)dst, stg, dst_row0 + r * stride, stride, n, K, Kp, c->ks);
+    fast_pack_weight((void *)dst, stg, dst_row0 + r * stride, stride, n, K, Kp, Np, c->ks);
   }
   return 0;
 }

@@ -12,7 +12,7 @@ namespace echo {
 //       ((((r/32)*(Kp/8) + k/8)*32 + r%32)*8 + k%8)            -- one 32-row block is contiguous over K,
 //       and a wavefront's MFMA A-operand load (32 rows x 16 k) is one contiguous 1 KiB read.
 //   packed activation Xp ("K8"): M padded to 32.  Element (m,k) lives at ((k/8)*Mp + m)*8 + k%8.
-//   split-K partials P: [split][Np/4][Mp][4] fp32.
+//   split-K partials P: [split][Mp][Np] fp32, row-major.
 // ------------------------------------------------------------------------------------------------
 static inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
 
@@ -66,12 +66,12 @@ void dbg_target_logprob(float *lp, const float *logits, int64_t ld, int M, int V
 // Repack a row-major bf16 chunk `src` [n_rows][K] into the packed weight `dst`: source row i goes to
 // destination row dst_row0 + i*dst_row_stride (stride 2 interleaves gate and up rows).  K % 8 == 0.
 void fast_pack_weight(void *dst, const void *src, int64_t dst_row0, int dst_row_stride, int64_t n_rows, int K, int Kp,
-                      hipStream_t st);
+                      int Np, hipStream_t st);
 // h = embed[token] (first layer) or h += sum_s P[s] (+0); then x = rmsnorm(h)*gain -> Xp (bf16 K8).
 void fast_resid_norm(float *h, const void *embed_bf16, const int32_t *token, const float *partials, int nsplit,
                      int Np, void *Xp, const void *gain_bf16, int M, int Mp, int d, float eps, hipStream_t st);
 enum GemmEpilogue { EPI_PARTIAL = 0, EPI_SWIGLU = 1 };
-// out = Xp[Mp x Kp] * Wp[Np x Kp]^T.  EPI_PARTIAL: fp32 partials [nsplit][Np/4][Mp][4];
+// out = Xp[Mp x Kp] * Wp[Np x Kp]^T.  EPI_PARTIAL: fp32 partials [nsplit][Mp][Np];
 // EPI_SWIGLU (rows alternate gate_f, up_f): silu(gate)*up -> bf16 K8 [Mp][Np/2]; nsplit must be 1.
 void fast_gemm(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, int nsplit, int waves_k,
                GemmEpilogue epi, hipStream_t st);

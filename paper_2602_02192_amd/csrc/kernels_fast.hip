@@ -5,22 +5,28 @@
 
 namespace echo {
 
-// grid M rows, block 256.  h[m] = embed[token[m]]            (embed != null)
-//                          h[m] += sum_s partials[s][..][m]  (nsplit > 0)
+// grid M rows, block 1024.  h[m] = embed[token[m]]            (embed != null)
+//                           h[m] += sum_s partials[s][..][m]  (nsplit <= 8, summed in split order)
 // then Xp[m] = bf16(h[m] * rsqrt(mean(h[m]^2) + eps) * gain).  d % 8 == 0, d <= 8192.
-__global__ __launch_bounds__(256) void resid_norm_kernel(float *h, const uint16_t *embed, const int32_t *token,
-                                                         const f32x4 *partials, int nsplit, int Np, uint16_t *Xp,
-                                                         const uint16_t *gain, int Mp, int d, float eps) {
-  __shared__ float sh[4];
+// Every load of a thread (residual, up to 8 partials) is issued before the first use, so the kernel costs
+// one memory round trip whatever the split count.
+constexpr int RN_THREADS = 1024;
+__global__ __launch_bounds__(RN_THREADS) void resid_norm_kernel(float *h, const uint16_t *embed, const int32_t *token,
+                                                                const f32x4 *partials, int nsplit, int Np, uint16_t *Xp,
+                                                                const uint16_t *gain, int Mp, int d, float eps) {
+  __shared__ float sh[RN_THREADS / 64];
   int m = blockIdx.x, d4 = d >> 2;
-  f32x4 v[8];
+  f32x4 v[2];
   float ss = 0.f;
   int tok = embed ? token[m] : 0;
 #pragma unroll
-  for (int c = 0; c < 8; ++c) {
-    int n4 = threadIdx.x + c * 256;
+  for (int c = 0; c < 2; ++c) {
+    int n4 = threadIdx.x + c * RN_THREADS;
     if (n4 >= d4) break;
-    f32x4 a;
+    f32x4 a, pp[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+      pp[s] = s < nsplit ? partials[((int64_t)s * Mp + m) * (Np >> 2) + n4] : f32x4{0.f, 0.f, 0.f, 0.f};
     if (embed) {
       if (tok >= 0) {
         uint2 e = *(const uint2 *)(embed + (int64_t)tok * d + n4 * 4);
@@ -28,7 +34,8 @@ __global__ __launch_bounds__(256) void resid_norm_kernel(float *h, const uint16_
              __uint_as_float(e.y & 0xffff0000u)};
       } else a = {0.f, 0.f, 0.f, 0.f};
     } else a = *(const f32x4 *)(h + (int64_t)m * d + n4 * 4);
-    for (int s = 0; s < nsplit; ++s) a += partials[((int64_t)s * (Np >> 2) + n4) * Mp + m];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) a += pp[s];
     *(f32x4 *)(h + (int64_t)m * d + n4 * 4) = a;
     v[c] = a;
     ss += a[0] * a[0] + a[1] * a[1] + a[2] * a[2] + a[3] * a[3];
@@ -36,11 +43,13 @@ __global__ __launch_bounds__(256) void resid_norm_kernel(float *h, const uint16_
   ss = wave_sum(ss);
   if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = ss;
   __syncthreads();
-  ss = sh[0] + sh[1] + sh[2] + sh[3];
+  ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < RN_THREADS / 64; ++i) ss += sh[i];
   float inv = 1.0f / sqrtf(ss / (float)d + eps);
 #pragma unroll
-  for (int c = 0; c < 8; ++c) {
-    int n4 = threadIdx.x + c * 256;
+  for (int c = 0; c < 2; ++c) {
+    int n4 = threadIdx.x + c * RN_THREADS;
     if (n4 >= d4) break;
     int n = n4 * 4;
     uint2 g = *(const uint2 *)(gain + n);
@@ -56,7 +65,7 @@ __global__ __launch_bounds__(256) void resid_norm_kernel(float *h, const uint16_
 void fast_resid_norm(float *h, const void *embed_bf16, const int32_t *token, const float *partials, int nsplit, int Np,
                      void *Xp, const void *gain_bf16, int M, int Mp, int d, float eps, hipStream_t st) {
   if (M <= 0) return;
-  hipLaunchKernelGGL(resid_norm_kernel, dim3(M), dim3(256), 0, st, h, (const uint16_t *)embed_bf16, token,
+  hipLaunchKernelGGL(resid_norm_kernel, dim3(M), dim3(RN_THREADS), 0, st, h, (const uint16_t *)embed_bf16, token,
                      (const f32x4 *)partials, nsplit, Np, (uint16_t *)Xp, (const uint16_t *)gain_bf16, Mp, d, eps);
 }
 
@@ -70,11 +79,14 @@ __global__ void qkv_post_kernel(const float *partials, int nsplit, int Np, int M
   bool is_q = j < Hq, is_k = !is_q && j < Hq + Hkv;
   if (!is_q && !rows.active[m]) return;
   int n0 = j * hd + i, n1 = n0 + half;
-  float a = 0.f, b = 0.f;
-  for (int s = 0; s < nsplit; ++s) {
-    a += partials[(((int64_t)s * (Np >> 2) + (n0 >> 2)) * Mp + m) * 4 + (n0 & 3)];
-    b += partials[(((int64_t)s * (Np >> 2) + (n1 >> 2)) * Mp + m) * 4 + (n1 & 3)];
+  float a = 0.f, b = 0.f, pa[8], pb[8];
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {   // nsplit <= 8; all loads issued before the sums
+    pa[s] = s < nsplit ? partials[((int64_t)s * Mp + m) * Np + n0] : 0.f;
+    pb[s] = s < nsplit ? partials[((int64_t)s * Mp + m) * Np + n1] : 0.f;
   }
+#pragma unroll
+  for (int s = 0; s < 8; ++s) { a += pa[s]; b += pb[s]; }
   if (is_q || is_k) {
     if (qk_norm) {
       float ss = wave_sum(a * a + b * b);

@@ -10,24 +10,35 @@
 
 namespace echo {
 
+// Packed weight addressing, in units of 16 bytes (8 bf16).  ECHO_W_KSMAJOR = 0: one 32-row block is contiguous
+// over K.  ECHO_W_KSMAJOR = 1: k-step major -- all row blocks of one k-step are contiguous, so wavefronts that
+// advance together sweep HBM like one streaming copy.
+#ifndef ECHO_W_KSMAJOR
+#define ECHO_W_KSMAJOR 0
+#endif
+__host__ __device__ __forceinline__ int64_t w_block_base(int nb, int Kp) {
+  return ECHO_W_KSMAJOR ? (int64_t)nb * 64 : (int64_t)nb * (Kp >> 3) * 32;
+}
+__host__ __device__ __forceinline__ int64_t w_kstep_stride(int Np) { return ECHO_W_KSMAJOR ? (int64_t)(Np >> 5) * 64 : 64; }
+
 // ---- weight repacking --------------------------------------------------------------------------------
 // src: row-major bf16 [n_rows][K]; destination row of source row i is dst_row0 + i*dst_row_stride.
 __global__ void pack_weight_kernel(uint4 *dst, const uint4 *src, int64_t dst_row0, int dst_row_stride, int64_t n_rows,
-                                   int K8, int Kp8) {
+                                   int K8, int Kp8, int Np) {
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= n_rows * K8) return;
   int64_t i = idx / K8;
   int k8 = (int)(idx % K8);
   int64_t r = dst_row0 + i * dst_row_stride;
-  dst[((r >> 5) * Kp8 + k8) * 32 + (r & 31)] = src[idx];
+  dst[w_block_base((int)(r >> 5), Kp8 * 8) + (k8 >> 1) * w_kstep_stride(Np) + (k8 & 1) * 32 + (r & 31)] = src[idx];
 }
 
 void fast_pack_weight(void *dst, const void *src, int64_t dst_row0, int dst_row_stride, int64_t n_rows, int K, int Kp,
-                      hipStream_t st) {
+                      int Np, hipStream_t st) {
   int64_t n = n_rows * (K / 8);
   if (n <= 0) return;
   hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (uint4 *)dst,
-                     (const uint4 *)src, dst_row0, dst_row_stride, n_rows, K / 8, Kp / 8);
+                     (const uint4 *)src, dst_row0, dst_row_stride, n_rows, K / 8, Kp / 8, Np);
 }
 
 // ---- the MFMA inner loop -------------------------------------------------------------------------------
@@ -41,10 +52,10 @@ struct KGroup {
 
 template <int MB, int U>
 __device__ __forceinline__ void load_group(KGroup<MB, U> &g, const bf16x8 *__restrict__ a_ptr, const bf16x8 *__restrict__ b_ptr,
-                                           int Mp, int ks) {
+                                           int Mp, int ks, int64_t a_step) {
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    g.a[u] = __builtin_nontemporal_load(a_ptr + (int64_t)(ks + u) * 64);
+    g.a[u] = __builtin_nontemporal_load(a_ptr + (int64_t)(ks + u) * a_step);
     const bf16x8 *bp = b_ptr + (int64_t)(ks + u) * 2 * Mp;
 #pragma unroll
     for (int j = 0; j < MB; ++j) g.b[u][j] = bp[j * 32];
@@ -61,21 +72,22 @@ __device__ __forceinline__ void mma_group(f32x16 (&acc)[MB], const KGroup<MB, U>
 
 template <int MB>
 __device__ __forceinline__ void mma_range(f32x16 (&acc)[MB], const bf16x8 *__restrict__ Wnb,
-                                          const bf16x8 *__restrict__ Xp, int Mp, int ks0, int ks1, int lane) {
+                                          const bf16x8 *__restrict__ Xp, int Mp, int ks0, int ks1, int lane,
+                                          int64_t a_step) {
   constexpr int U = MB <= 2 ? 4 : (MB == 4 ? 2 : 1);
   const bf16x8 *a_ptr = Wnb + (lane >> 5) * 32 + (lane & 31);
   const bf16x8 *b_ptr = Xp + (int64_t)(lane >> 5) * Mp + (lane & 31);
   int ng = (ks1 - ks0) / U;
   KGroup<MB, U> g0, g1;
-  if (ng > 0) load_group<MB, U>(g0, a_ptr, b_ptr, Mp, ks0);
+  if (ng > 0) load_group<MB, U>(g0, a_ptr, b_ptr, Mp, ks0, a_step);
   for (int g = 0; g < ng; g += 2) {
-    if (g + 1 < ng) load_group<MB, U>(g1, a_ptr, b_ptr, Mp, ks0 + (g + 1) * U);
+    if (g + 1 < ng) load_group<MB, U>(g1, a_ptr, b_ptr, Mp, ks0 + (g + 1) * U, a_step);
     mma_group<MB, U>(acc, g0);
-    if (g + 2 < ng) load_group<MB, U>(g0, a_ptr, b_ptr, Mp, ks0 + (g + 2) * U);
+    if (g + 2 < ng) load_group<MB, U>(g0, a_ptr, b_ptr, Mp, ks0 + (g + 2) * U, a_step);
     if (g + 1 < ng) mma_group<MB, U>(acc, g1);
   }
   for (int ks = ks0 + ng * U; ks < ks1; ++ks) {   // remainder
-    bf16x8 a = __builtin_nontemporal_load(a_ptr + (int64_t)ks * 64);
+    bf16x8 a = __builtin_nontemporal_load(a_ptr + (int64_t)ks * a_step);
     const bf16x8 *bp = b_ptr + (int64_t)ks * 2 * Mp;
 #pragma unroll
     for (int j = 0; j < MB; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bp[j * 32], acc[j], 0, 0, 0);
@@ -120,7 +132,7 @@ __global__ __launch_bounds__(512) void gemm_kernel(void *out, const bf16x8 *__re
   for (int j = 0; j < MB; ++j)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
-  mma_range<MB>(acc, Wp + (int64_t)nb * (Kp >> 3) * 32, Xp + mblk0 * 32, Mp, k0, k1, lane);
+  mma_range<MB>(acc, Wp + w_block_base(nb, Kp), Xp + mblk0 * 32, Mp, k0, k1, lane, w_kstep_stride(Np));
   reduce_waves<MB>(acc, red, w, waves, lane);
   if (w != 0) return;
   int half = lane >> 5, col = lane & 31;
@@ -133,7 +145,7 @@ __global__ __launch_bounds__(512) void gemm_kernel(void *out, const bf16x8 *__re
       for (int g = 0; g < 4; ++g) {
         int n4 = nb * 8 + half + 2 * g;
         f32x4 v = {acc[j][4 * g], acc[j][4 * g + 1], acc[j][4 * g + 2], acc[j][4 * g + 3]};
-        P[((int64_t)split * (Np >> 2) + n4) * Mp + m] = v;
+        P[((int64_t)split * Mp + m) * (Np >> 2) + n4] = v;
       }
     }
   } else {  // EPI_SWIGLU: rows alternate gate_f, up_f
@@ -153,17 +165,19 @@ __global__ __launch_bounds__(512) void gemm_kernel(void *out, const bf16x8 *__re
   }
 }
 
+// Launch-shape heuristics, from sweeps on MI355X at the decode shapes: two wavefronts per workgroup share a
+// weight block's k-steps (deeper in-workgroup splits lose more in the LDS reduction than they gain), and the
+// grid split brings the launch to about 1536 wavefronts; a GEMM whose epilogue needs the whole K (nsplit = 1)
+// takes one wavefront per block once there are several hundred blocks.
 int fast_gemm_pick(int Np, int Kp, int Mp, int *nsplit, int *waves_k) {
   int nblocks = Np / 32, ksteps = Kp / 16, mb = Mp / 32 > 8 ? 8 : Mp / 32;
   int zblocks = Mp / (32 * mb);
-  int want = 2560 / (nblocks * zblocks);          // wavefronts per weight block to fill 256 CUs ~10 deep
-  int cap = ksteps / 8;                           // at least 8 k-steps per wavefront
-  if (want > cap) want = cap;
-  if (want < 1) want = 1;
-  int wmax = 8;
-  while (wmax > 1 && (wmax - 1) * mb * 4096 > 65536) --wmax;   // LDS for the in-workgroup reduction
-  int wk = want < wmax ? want : wmax;
-  int ns = (want + wk - 1) / wk;
+  int wk = 2;
+  while (wk > 1 && (ksteps / wk < 8 || (wk - 1) * mb * 4096 > 65536)) --wk;
+  int ns = (1536 + nblocks * zblocks * wk / 2) / (nblocks * zblocks * wk);
+  if (ns > 8) ns = 8;
+  while (ns > 1 && ksteps / (ns * wk) < 8) --ns;
+  if (ns < 1) ns = 1;
   *nsplit = ns;
   *waves_k = wk;
   return 0;
@@ -189,7 +203,7 @@ static void gemm_dispatch(void *out, const void *Xp, const void *Wp, int Mp, int
 void fast_gemm(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, int nsplit, int waves_k,
                GemmEpilogue epi, hipStream_t st) {
   if (epi == EPI_PARTIAL) gemm_dispatch<EPI_PARTIAL>(out, Xp, Wp, Mp, Np, Kp, nsplit, waves_k, st);
-  else gemm_dispatch<EPI_SWIGLU>(out, Xp, Wp, Mp, Np, Kp, 1, waves_k, st);
+  else gemm_dispatch<EPI_SWIGLU>(out, Xp, Wp, Mp, Np, Kp, 1, Np / 32 >= 384 ? 1 : waves_k, st);
 }
 
 // ---- lm_head ---------------------------------------------------------------------------------------------
@@ -217,7 +231,7 @@ __global__ __launch_bounds__(256) void lmhead_kernel(const bf16x8 *__restrict__ 
     for (int j = 0; j < MB; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
-    mma_range<MB>(acc, Wp + (int64_t)nb * (Kp >> 3) * 32, Xp + mblk0 * 32, Mp, 0, Kp >> 4, lane);
+    mma_range<MB>(acc, Wp + w_block_base(nb, Kp), Xp + mblk0 * 32, Mp, 0, Kp >> 4, lane, w_kstep_stride(Np));
 #pragma unroll
     for (int j = 0; j < MB; ++j) {
       int m = (mblk0 + j) * 32 + col;
