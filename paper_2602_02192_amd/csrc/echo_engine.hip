@@ -125,8 +125,8 @@ Plan make_plan(const echo_model_desc *d) {
     p.part_floats = (size_t)MAX_GRID_SPLIT * std::max(p.Np_qkv, p.Np_d) * M;
     p.o_part = b.take(p.part_floats * 4);
     p.o_lmpart = b.take(fast_lmhead_partial_floats(p.Np_v, (int)M) * 4);
-    p.attn_chunk = 256;
-    p.attn_max_splits = (d->max_ctx + p.attn_chunk - 1) / p.attn_chunk;
+    p.attn_chunk = 32;
+    p.attn_max_splits = 32;   // partial-buffer capacity in splits per (row, head)
     p.o_attn_o = b.take(M * d->n_q_heads * (size_t)p.attn_max_splits * hd * 4);
     p.o_attn_ml = b.take(M * d->n_q_heads * (size_t)p.attn_max_splits * 2 * 4);
     p.stage_bytes = STAGE_BYTES;
@@ -362,8 +362,8 @@ void forward_layers(echo_ctx *c, const Slot &S, int M, bool use_splitk_attn) {
     {
       TimerScope t(c, &c->ev_attn);
       if (use_splitk_attn)
-        fast_attention(xatt, q16, c->rows, c->kv, l, M, Mp, Hq, Hkv, p.attn_chunk, p.attn_max_splits, at<float>(c, p.o_attn_o),
-                       at<float>(c, p.o_attn_ml), st);
+        fast_attention(xatt, q16, c->rows, c->kv, l, M, Mp, Hq, Hkv, fast_attention_splits(M, Hkv, p.attn_max_splits),
+                       at<float>(c, p.o_attn_o), at<float>(c, p.o_attn_ml), st);
       else
         fast_attention_simple(xatt, q16, c->rows, c->kv, l, M, Mp, Hq, Hkv, st);
     }

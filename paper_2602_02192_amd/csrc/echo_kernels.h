@@ -83,8 +83,10 @@ void fast_qkv_post(const float *partials, int nsplit, int Np, int Mp, void *q_bf
 void fast_attention_simple(void *Xp_out, const void *q_bf16, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq,
                            int Hkv, hipStream_t st);
 // Split-K decode attention over the bf16 KV cache + combine; writes Xp (bf16 K8 [Mp][Hq*hd]).
+// nsplit = fast_attention_splits(M, Hkv, capacity); partial buffers hold M*Hq*nsplit*(hd + 2) floats.
 void fast_attention(void *Xp_out, const void *q_bf16, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq,
-                    int Hkv, int chunk_keys, int max_splits, float *part_o, float *part_ml, hipStream_t st);
+                    int Hkv, int nsplit, float *part_o, float *part_ml, hipStream_t st);
+int fast_attention_splits(int M, int Hkv, int max_splits);
 // lm_head with the sampler fused into the epilogue (partials per workgroup) + the combine kernel.
 void fast_lmhead_sample(int32_t *tok, float *lp, float *target_lp, const void *Xp, const void *Wp, int Mp, int M,
                         int V, int Np, int Kp, float temperature, uint64_t seed, const int32_t *d_step,

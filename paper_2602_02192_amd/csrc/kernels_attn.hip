@@ -88,22 +88,34 @@ __device__ __forceinline__ void att_issue_loads(v4u (&rk)[HD / 16], v4u (&rv)[HD
   }
 }
 
-template <int HD>
+// Keys per split of a row with n_keys keys cut into nsplit equal parts (whole tiles).
+__device__ __forceinline__ int att_split_len(int n_keys, int nsplit) {
+  return ((n_keys + nsplit - 1) / nsplit + ATT_TILE - 1) & ~(ATT_TILE - 1);
+}
+
+// grid (nsplit, Hkv, M).  Every row's keys are cut into nsplit equal chunks of that row's own length.  DIRECT
+// (nsplit == 1): the workgroup normalises and writes the bf16 output itself and no partials exist.
+template <int HD, bool DIRECT>
 __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__ part_o, float *__restrict__ part_ml,
+                                                             uint16_t *__restrict__ Xp, int Mp,
                                                              const uint16_t *__restrict__ q_bf16, RowState rows, KvGeom kv,
-                                                             int layer, int Hq, int Hkv, int chunk_keys, int max_splits) {
+                                                             int layer, int Hq, int Hkv, int nsplit) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   using L = AttLds<HD>;
   constexpr int KS = HD / 16;          // k-steps of QK^T
   constexpr int NE = HD / 32;          // PV MFMAs per 16 keys; also head dims per lane column
   constexpr int LD = HD / 16;          // 16-byte loads per lane per K (or V) tile
   const int c = blockIdx.x, kvh = blockIdx.y, m = blockIdx.z;
-  if (!rows.active[m]) return;
-  const int n_keys = rows.pos[m] + 1, key0 = c * chunk_keys;
+  const int grp = Hq / Hkv;
+  if (!rows.active[m]) {
+    if (DIRECT)
+      for (int idx = threadIdx.x; idx < grp * HD; idx += 256) Xp[k8_index(m, kvh * grp * HD + idx, Mp)] = 0;
+    return;
+  }
+  const int n_keys = rows.pos[m] + 1, chunk_keys = att_split_len(n_keys, nsplit), key0 = c * chunk_keys;
   if (key0 >= n_keys) return;
   const int key1 = min(n_keys, key0 + chunk_keys), ntiles = (key1 - key0 + ATT_TILE - 1) / ATT_TILE;
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
-  const int grp = Hq / Hkv;
   char *Ks = lds + w * L::PER_WAVE, *Vs = Ks + ATT_TILE * L::ROW, *Ps = Vs + ATT_TILE * L::ROW;
   const uint16_t *Kg = kv_head_ptr(kv, rows.slot[m], layer, kvh), *Vg = Kg + kv.kv_stride();
 
@@ -243,21 +255,25 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
       acc += mo[r * HD + dd] * f;
       lsum += mo[8 * HD + 8 + r] * f;
     }
-    int64_t pi = ((int64_t)m * Hq + kvh * grp + r) * max_splits + c;
-    part_o[pi * HD + dd] = acc;
-    if (dd == 0) { part_ml[pi * 2] = M; part_ml[pi * 2 + 1] = lsum; }
+    if (DIRECT) {
+      Xp[k8_index(m, (kvh * grp + r) * HD + dd, Mp)] = f32_to_bf16_bits(acc / lsum);
+    } else {
+      int64_t pi = ((int64_t)m * Hq + kvh * grp + r) * nsplit + c;
+      part_o[pi * HD + dd] = acc;
+      if (dd == 0) { part_ml[pi * 2] = M; part_ml[pi * 2 + 1] = lsum; }
+    }
   }
 }
 
 // grid (M, Hq), block HD: merge the chunk partials of one (row, head) in chunk order, normalise, write bf16 K8.
 template <int HD>
 __global__ void attn_combine_kernel(uint16_t *Xp, const float *__restrict__ part_o, const float *__restrict__ part_ml,
-                                    RowState rows, int Mp, int Hq, int chunk_keys, int max_splits) {
+                                    RowState rows, int Mp, int Hq, int nsplit) {
   int m = blockIdx.x, j = blockIdx.y, dd = threadIdx.x;
   int64_t xi = k8_index(m, j * HD + dd, Mp);
   if (!rows.active[m]) { Xp[xi] = 0; return; }
-  int ns = (rows.pos[m] + 1 + chunk_keys - 1) / chunk_keys;
-  int64_t pi = ((int64_t)m * Hq + j) * max_splits;
+  int n_keys = rows.pos[m] + 1, per = att_split_len(n_keys, nsplit), ns = (n_keys + per - 1) / per;
+  int64_t pi = ((int64_t)m * Hq + j) * nsplit;
   float M = -INFINITY;
   for (int c = 0; c < ns; ++c) M = fmaxf(M, part_ml[(pi + c) * 2]);
   float acc = 0.f, lsum = 0.f;
@@ -269,26 +285,41 @@ __global__ void attn_combine_kernel(uint16_t *Xp, const float *__restrict__ part
   Xp[xi] = f32_to_bf16_bits(acc / lsum);
 }
 
+// Splits per row: enough workgroups (rows x KV heads x splits) to put two on every compute unit, never more
+// than max_splits (the capacity of the partial buffers).  One split needs no partials and no combine launch.
+int fast_attention_splits(int M, int Hkv, int max_splits) {
+  int ns = (640 + M * Hkv - 1) / (M * Hkv);
+  if (ns < 1) ns = 1;
+  return ns < max_splits ? ns : max_splits;
+}
+
+template <int HD>
+static void attention_launch(void *Xp_out, const void *q_bf16, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq, int Hkv,
+                             int nsplit, float *part_o, float *part_ml, hipStream_t st) {
+  dim3 grid(nsplit, Hkv, M);
+  if (nsplit == 1) {
+    hipLaunchKernelGGL((attn_splitk_kernel<HD, true>), grid, dim3(256), AttLds<HD>::TOTAL, st, part_o, part_ml, (uint16_t *)Xp_out,
+                       Mp, (const uint16_t *)q_bf16, rows, kv, layer, Hq, Hkv, nsplit);
+  } else {
+    hipLaunchKernelGGL((attn_splitk_kernel<HD, false>), grid, dim3(256), AttLds<HD>::TOTAL, st, part_o, part_ml, (uint16_t *)Xp_out,
+                       Mp, (const uint16_t *)q_bf16, rows, kv, layer, Hq, Hkv, nsplit);
+    hipLaunchKernelGGL(attn_combine_kernel<HD>, dim3(M, Hq), dim3(HD), 0, st, (uint16_t *)Xp_out, part_o, part_ml, rows, Mp, Hq,
+                       nsplit);
+  }
+}
+
 void fast_attention(void *Xp_out, const void *q_bf16, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq, int Hkv,
-                    int chunk_keys, int max_splits, float *part_o, float *part_ml, hipStream_t st) {
+                    int nsplit, float *part_o, float *part_ml, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void *)attn_splitk_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, AttLds<128>::TOTAL);
-    (void)hipFuncSetAttribute((const void *)attn_splitk_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, AttLds<64>::TOTAL);
+    (void)hipFuncSetAttribute((const void *)attn_splitk_kernel<128, true>, hipFuncAttributeMaxDynamicSharedMemorySize, AttLds<128>::TOTAL);
+    (void)hipFuncSetAttribute((const void *)attn_splitk_kernel<128, false>, hipFuncAttributeMaxDynamicSharedMemorySize, AttLds<128>::TOTAL);
+    (void)hipFuncSetAttribute((const void *)attn_splitk_kernel<64, true>, hipFuncAttributeMaxDynamicSharedMemorySize, AttLds<64>::TOTAL);
+    (void)hipFuncSetAttribute((const void *)attn_splitk_kernel<64, false>, hipFuncAttributeMaxDynamicSharedMemorySize, AttLds<64>::TOTAL);
     attr_set = true;
   }
-  dim3 grid(max_splits, Hkv, M);
-  if (kv.head_dim == 128) {
-    hipLaunchKernelGGL(attn_splitk_kernel<128>, grid, dim3(256), AttLds<128>::TOTAL, st, part_o, part_ml, (const uint16_t *)q_bf16,
-                       rows, kv, layer, Hq, Hkv, chunk_keys, max_splits);
-    hipLaunchKernelGGL(attn_combine_kernel<128>, dim3(M, Hq), dim3(128), 0, st, (uint16_t *)Xp_out, part_o, part_ml, rows, Mp, Hq,
-                       chunk_keys, max_splits);
-  } else {
-    hipLaunchKernelGGL(attn_splitk_kernel<64>, grid, dim3(256), AttLds<64>::TOTAL, st, part_o, part_ml, (const uint16_t *)q_bf16,
-                       rows, kv, layer, Hq, Hkv, chunk_keys, max_splits);
-    hipLaunchKernelGGL(attn_combine_kernel<64>, dim3(M, Hq), dim3(64), 0, st, (uint16_t *)Xp_out, part_o, part_ml, rows, Mp, Hq,
-                       chunk_keys, max_splits);
-  }
+  if (kv.head_dim == 128) attention_launch<128>(Xp_out, q_bf16, rows, kv, layer, M, Mp, Hq, Hkv, nsplit, part_o, part_ml, st);
+  else attention_launch<64>(Xp_out, q_bf16, rows, kv, layer, M, Mp, Hq, Hkv, nsplit, part_o, part_ml, st);
 }
 
 }  // namespace echo
