@@ -98,13 +98,13 @@ Plan make_plan(const echo_model_desc *d) {
   int64_t H = d->hidden, hd = d->head_dim, Q = (int64_t)d->n_q_heads * hd, KV = (int64_t)d->n_kv_heads * hd, F = d->ffn, V = d->vocab;
   p.Mcap = std::max(pad_rows(d->max_seqs), PREFILL_ROWS);
   p.Np_qkv = (int)round_up(Q + 2 * KV, 32); p.Np_d = (int)round_up(H, 32); p.Np_gu = (int)round_up(2 * F, 32);
-  p.Np_v = (int)round_up(V, 32);
+  p.Np_v = (int)round_up(V, 64);   // an even number of 32-row blocks: lm_head wavefronts own two blocks
   p.Kp_d = (int)round_up(H, 16); p.Kp_q = (int)round_up(Q, 16); p.Kp_f = (int)round_up(F, 16);
   Bump b;
   if (p.fast) {
     size_t per = 2 * H * 2 + (d->qk_norm ? 2 * hd * 2 : 0) + 4 * 256 /*alignment slack*/ + packed_bytes(Q + 2 * KV, H) +
                  packed_bytes(H, Q) + packed_bytes(2 * F, H) + packed_bytes(H, F);
-    p.slot_bytes = (size_t)V * H * 2 + 256 + H * 2 + 256 + packed_bytes(V, H) + d->n_layers * (per + 8 * 256);
+    p.slot_bytes = (size_t)V * H * 2 + 256 + H * 2 + 256 + packed_bytes(round_up(V, 64), H) + d->n_layers * (per + 8 * 256);
   } else {
     p.slot_bytes = (size_t)blob_numel(d) * p.elt;
   }
@@ -230,7 +230,7 @@ void bind_slot(echo_ctx *c, int s) {
   auto take = [&](size_t n) { return (const void *)(S.base + b.take(n)); };
   S.embed = take((size_t)V * H * 2);
   S.final_norm = take(H * 2);
-  S.lm_head = take(packed_bytes(V, H));
+  S.lm_head = take(packed_bytes(round_up(V, 64), H));
   for (int l = 0; l < d.n_layers; ++l) {
     LayerW &L = S.layers[l];
     L.attn_norm = take(H * 2);
@@ -312,16 +312,15 @@ struct TimerScope {
 };
 
 void gemm_fast(echo_ctx *c, void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, GemmEpilogue epi, int *nsplit_out) {
-  int ns, wk;
-  fast_gemm_pick(Np, Kp, Mp, &ns, &wk);
-  if (epi == EPI_SWIGLU) ns = 1;
-  if (ns > MAX_GRID_SPLIT) ns = MAX_GRID_SPLIT;
+  GemmShape g;
+  fast_gemm_pick(Np, Kp, Mp, epi == EPI_SWIGLU, &g);
+  if (g.nsplit > MAX_GRID_SPLIT) g.nsplit = MAX_GRID_SPLIT;
   {
     TimerScope t(c, &c->ev_gemm);
-    fast_gemm(out, Xp, Wp, Mp, Np, Kp, ns, wk, epi, c->cs);
+    fast_gemm(out, Xp, Wp, Mp, Np, Kp, g, epi, c->cs);
   }
   if (c->timing) c->t_gemm_bytes += (double)Np * Kp * 2;
-  if (nsplit_out) *nsplit_out = ns;
+  if (nsplit_out) *nsplit_out = g.nsplit;
 }
 
 void forward_layers(echo_ctx *c, const Slot &S, int M, bool use_splitk_attn) {

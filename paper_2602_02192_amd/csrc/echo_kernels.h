@@ -73,9 +73,10 @@ void fast_resid_norm(float *h, const void *embed_bf16, const int32_t *token, con
 enum GemmEpilogue { EPI_PARTIAL = 0, EPI_SWIGLU = 1 };
 // out = Xp[Mp x Kp] * Wp[Np x Kp]^T.  EPI_PARTIAL: fp32 partials [nsplit][Mp][Np];
 // EPI_SWIGLU (rows alternate gate_f, up_f): silu(gate)*up -> bf16 K8 [Mp][Np/2]; nsplit must be 1.
-void fast_gemm(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, int nsplit, int waves_k,
-               GemmEpilogue epi, hipStream_t st);
-int fast_gemm_pick(int Np, int Kp, int Mp, int *nsplit, int *waves_k); // heuristics for the two knobs
+struct GemmShape { int nsplit, waves_k, waves_n, nbw; };   // launch shape, see fast_gemm_pick
+void fast_gemm(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, GemmShape g, GemmEpilogue epi,
+               hipStream_t st);
+void fast_gemm_pick(int Np, int Kp, int Mp, int full_k, GemmShape *g);
 void fast_qkv_post(const float *partials, int nsplit, int Np, int Mp, void *q_bf16 /*[M][Hq][hd]*/,
                    const void *q_gain, const void *k_gain, int qk_norm, float eps, const float *rope_cs,
                    RowState rows, KvGeom kv, int layer, int M, int Hq, int Hkv, hipStream_t st);

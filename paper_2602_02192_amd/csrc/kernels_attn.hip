@@ -288,7 +288,7 @@ __global__ void attn_combine_kernel(uint16_t *Xp, const float *__restrict__ part
 // Splits per row: enough workgroups (rows x KV heads x splits) to put two on every compute unit, never more
 // than max_splits (the capacity of the partial buffers).  One split needs no partials and no combine launch.
 int fast_attention_splits(int M, int Hkv, int max_splits) {
-  int ns = (640 + M * Hkv - 1) / (M * Hkv);
+  int ns = 640 / (M * Hkv);
   if (ns < 1) ns = 1;
   return ns < max_splits ? ns : max_splits;
 }

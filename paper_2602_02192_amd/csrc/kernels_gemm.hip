@@ -42,174 +42,211 @@ void fast_pack_weight(void *dst, const void *src, int64_t dst_row0, int dst_row_
 }
 
 // ---- the MFMA inner loop -------------------------------------------------------------------------------
-// Loads run two groups of U k-steps ahead of the MFMAs (register double buffer), so that a wavefront keeps
-// 2*U*(1+MB) KiB of weight and activation reads in flight instead of waiting for each k-step.
-template <int MB, int U>
+// A wavefront owns NBW consecutive 32-row weight blocks and all MB 32-row batch blocks of its launch slice:
+// per k-step it reads NBW KiB of weights and MB KiB of activations, so activation traffic from L2 per weight
+// byte falls with NBW.  Loads run two groups of U k-steps ahead of the MFMAs (register double buffer).
+template <int MB, int NBW, int U>
 struct KGroup {
-  bf16x8 a[U];
+  bf16x8 a[U][NBW];
   bf16x8 b[U][MB];
 };
 
-template <int MB, int U>
-__device__ __forceinline__ void load_group(KGroup<MB, U> &g, const bf16x8 *__restrict__ a_ptr, const bf16x8 *__restrict__ b_ptr,
-                                           int Mp, int ks, int64_t a_step) {
+template <int MB, int NBW, int U>
+__device__ __forceinline__ void load_group(KGroup<MB, NBW, U> &g, const bf16x8 *__restrict__ a_ptr, int64_t a_blk,
+                                           const bf16x8 *__restrict__ b_ptr, int Mp, int ks, int64_t a_step) {
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    g.a[u] = __builtin_nontemporal_load(a_ptr + (int64_t)(ks + u) * a_step);
+#pragma unroll
+    for (int n = 0; n < NBW; ++n) g.a[u][n] = __builtin_nontemporal_load(a_ptr + n * a_blk + (int64_t)(ks + u) * a_step);
     const bf16x8 *bp = b_ptr + (int64_t)(ks + u) * 2 * Mp;
 #pragma unroll
     for (int j = 0; j < MB; ++j) g.b[u][j] = bp[j * 32];
   }
 }
 
-template <int MB, int U>
-__device__ __forceinline__ void mma_group(f32x16 (&acc)[MB], const KGroup<MB, U> &g) {
+template <int MB, int NBW, int U>
+__device__ __forceinline__ void mma_group(f32x16 (&acc)[NBW][MB], const KGroup<MB, NBW, U> &g) {
 #pragma unroll
   for (int u = 0; u < U; ++u)
 #pragma unroll
-    for (int j = 0; j < MB; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g.a[u], g.b[u][j], acc[j], 0, 0, 0);
+    for (int n = 0; n < NBW; ++n)
+#pragma unroll
+      for (int j = 0; j < MB; ++j)
+        acc[n][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g.a[u][n], g.b[u][j], acc[n][j], 0, 0, 0);
 }
 
-template <int MB>
-__device__ __forceinline__ void mma_range(f32x16 (&acc)[MB], const bf16x8 *__restrict__ Wnb,
+// Wnb: first weight block of the wavefront; a_blk: distance between consecutive weight blocks (16-byte units).
+template <int MB, int NBW>
+__device__ __forceinline__ void mma_range(f32x16 (&acc)[NBW][MB], const bf16x8 *__restrict__ Wnb, int64_t a_blk,
                                           const bf16x8 *__restrict__ Xp, int Mp, int ks0, int ks1, int lane,
                                           int64_t a_step) {
-  constexpr int U = MB <= 2 ? 4 : (MB == 4 ? 2 : 1);
+  constexpr int U0 = 12 / (MB + NBW), U = U0 < 1 ? 1 : (U0 > 4 ? 4 : U0);
   const bf16x8 *a_ptr = Wnb + (lane >> 5) * 32 + (lane & 31);
   const bf16x8 *b_ptr = Xp + (int64_t)(lane >> 5) * Mp + (lane & 31);
   int ng = (ks1 - ks0) / U;
-  KGroup<MB, U> g0, g1;
-  if (ng > 0) load_group<MB, U>(g0, a_ptr, b_ptr, Mp, ks0, a_step);
+  KGroup<MB, NBW, U> g0, g1;
+  if (ng > 0) load_group<MB, NBW, U>(g0, a_ptr, a_blk, b_ptr, Mp, ks0, a_step);
   for (int g = 0; g < ng; g += 2) {
-    if (g + 1 < ng) load_group<MB, U>(g1, a_ptr, b_ptr, Mp, ks0 + (g + 1) * U, a_step);
-    mma_group<MB, U>(acc, g0);
-    if (g + 2 < ng) load_group<MB, U>(g0, a_ptr, b_ptr, Mp, ks0 + (g + 2) * U, a_step);
-    if (g + 1 < ng) mma_group<MB, U>(acc, g1);
+    if (g + 1 < ng) load_group<MB, NBW, U>(g1, a_ptr, a_blk, b_ptr, Mp, ks0 + (g + 1) * U, a_step);
+    mma_group<MB, NBW, U>(acc, g0);
+    if (g + 2 < ng) load_group<MB, NBW, U>(g0, a_ptr, a_blk, b_ptr, Mp, ks0 + (g + 2) * U, a_step);
+    if (g + 1 < ng) mma_group<MB, NBW, U>(acc, g1);
   }
   for (int ks = ks0 + ng * U; ks < ks1; ++ks) {   // remainder
-    bf16x8 a = __builtin_nontemporal_load(a_ptr + (int64_t)ks * a_step);
-    const bf16x8 *bp = b_ptr + (int64_t)ks * 2 * Mp;
-#pragma unroll
-    for (int j = 0; j < MB; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bp[j * 32], acc[j], 0, 0, 0);
-  }
-}
-
-template <int MB>
-__device__ __forceinline__ void reduce_waves(f32x16 (&acc)[MB], float *red, int w, int waves, int lane) {
-  if (waves == 1) return;
-  if (w > 0) {
-#pragma unroll
-    for (int j = 0; j < MB; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) red[(((w - 1) * MB + j) * 16 + r) * 64 + lane] = acc[j][r];
-  }
-  __syncthreads();
-  if (w == 0) {
-    for (int ww = 1; ww < waves; ++ww)
-#pragma unroll
-      for (int j = 0; j < MB; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[j][r] += red[(((ww - 1) * MB + j) * 16 + r) * 64 + lane];
+    KGroup<MB, NBW, 1> r;
+    load_group<MB, NBW, 1>(r, a_ptr, a_blk, b_ptr, Mp, ks, a_step);
+    mma_group<MB, NBW, 1>(acc, r);
   }
 }
 
 __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + expf(-x)); }
 
-// grid (Np/32, nsplit, Mp/(32*MB)); block 64*waves.  One 32-row weight block per workgroup; the k-steps of
-// this grid split are divided among the workgroup's wavefronts and summed in LDS in wavefront order.
-template <int MB, int EPI>
+// grid (ceil(Np/32 / (NBW*waves_n)), nsplit, Mp/(32*MB)); block 64 * waves_n * waves_k.
+// Wavefront w = wk*waves_n + wn: the waves_n wavefronts of one wk share a k-range (their activation reads hit
+// L1 together) and own different weight blocks; the waves_k k-ranges of a grid split are summed in LDS in wk order.
+template <int MB, int NBW, int EPI>
 __global__ __launch_bounds__(512) void gemm_kernel(void *out, const bf16x8 *__restrict__ Xp, const bf16x8 *__restrict__ Wp,
-                                                   int Mp, int Np, int Kp, int ksteps_per_split) {
+                                                   int Mp, int Np, int Kp, int ksteps_per_split, int waves_n) {
   extern __shared__ float red[];
-  int waves = blockDim.x >> 6, w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  int nb = blockIdx.x, split = blockIdx.y, mblk0 = blockIdx.z * MB;
-  int ksteps = Kp >> 4;
-  int s0 = split * ksteps_per_split, s1 = min(ksteps, s0 + ksteps_per_split);
-  int per_wave = (s1 - s0 + waves - 1) / waves;
-  int k0 = min(s1, s0 + w * per_wave), k1 = min(s1, k0 + per_wave);
-  f32x16 acc[MB];
+  const int waves = blockDim.x >> 6, w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wn = w % waves_n, wk = w / waves_n, nwk = waves / waves_n;
+  const int nblocks = Np >> 5, split = blockIdx.y, mblk0 = blockIdx.z * MB;
+  const int nb0 = (blockIdx.x * waves_n + wn) * NBW;
+  const int ksteps = Kp >> 4;
+  const int s0 = split * ksteps_per_split, s1 = min(ksteps, s0 + ksteps_per_split);
+  const int per_wave = (s1 - s0 + nwk - 1) / nwk;
+  const int k0 = min(s1, s0 + wk * per_wave), k1 = min(s1, k0 + per_wave);
+  f32x16 acc[NBW][MB];
 #pragma unroll
-  for (int j = 0; j < MB; ++j)
+  for (int n = 0; n < NBW; ++n)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
-  mma_range<MB>(acc, Wp + w_block_base(nb, Kp), Xp + mblk0 * 32, Mp, k0, k1, lane, w_kstep_stride(Np));
-  reduce_waves<MB>(acc, red, w, waves, lane);
-  if (w != 0) return;
-  int half = lane >> 5, col = lane & 31;
-  if (EPI == EPI_PARTIAL) {
-    f32x4 *P = (f32x4 *)out;
+    for (int j = 0; j < MB; ++j)
 #pragma unroll
-    for (int j = 0; j < MB; ++j) {
-      int m = (mblk0 + j) * 32 + col;
+      for (int r = 0; r < 16; ++r) acc[n][j][r] = 0.f;
+  // blocks past the end re-read the last block (their results are dropped)
+  const int nb_ld = min(nb0, nblocks - NBW);
+  if (nb0 < nblocks)
+    mma_range<MB, NBW>(acc, Wp + w_block_base(nb_ld, Kp), w_block_base(1, Kp), Xp + mblk0 * 32, Mp, k0, k1, lane,
+                       w_kstep_stride(Np));
+  if (nwk > 1) {
+    float *mine = red + (int64_t)((wk - 1) * waves_n + wn) * (NBW * MB * 16 * 64);
+    if (wk > 0) {
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        int n4 = nb * 8 + half + 2 * g;
-        f32x4 v = {acc[j][4 * g], acc[j][4 * g + 1], acc[j][4 * g + 2], acc[j][4 * g + 3]};
-        P[((int64_t)split * Mp + m) * (Np >> 2) + n4] = v;
+      for (int n = 0; n < NBW; ++n)
+#pragma unroll
+        for (int j = 0; j < MB; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mine[((n * MB + j) * 16 + r) * 64 + lane] = acc[n][j][r];
+    }
+    __syncthreads();
+    if (wk == 0) {
+      for (int ww = 1; ww < nwk; ++ww) {
+        const float *src = red + (int64_t)((ww - 1) * waves_n + wn) * (NBW * MB * 16 * 64);
+#pragma unroll
+        for (int n = 0; n < NBW; ++n)
+#pragma unroll
+          for (int j = 0; j < MB; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[n][j][r] += src[((n * MB + j) * 16 + r) * 64 + lane];
       }
     }
-  } else {  // EPI_SWIGLU: rows alternate gate_f, up_f
-    uint32_t *O = (uint32_t *)out;
+  }
+  if (wk != 0) return;
+  const int half = lane >> 5, col = lane & 31;
 #pragma unroll
-    for (int j = 0; j < MB; ++j) {
-      int m = (mblk0 + j) * 32 + col;
+  for (int n = 0; n < NBW; ++n) {
+    const int nb = nb0 + n;
+    if (nb >= nblocks) continue;
+    if (EPI == EPI_PARTIAL) {
+      f32x4 *P = (f32x4 *)out;
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        int f = nb * 16 + half * 2 + 4 * g;
-        float v0 = silu_f(acc[j][4 * g]) * acc[j][4 * g + 1];
-        float v1 = silu_f(acc[j][4 * g + 2]) * acc[j][4 * g + 3];
-        uint32_t pk = (uint32_t)f32_to_bf16_bits(v0) | ((uint32_t)f32_to_bf16_bits(v1) << 16);
-        O[(((int64_t)(f >> 3) * Mp + m) * 8 + (f & 7)) >> 1] = pk;
+      for (int j = 0; j < MB; ++j) {
+        int m = (mblk0 + j) * 32 + col;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          int n4 = nb * 8 + half + 2 * g;
+          f32x4 v = {acc[n][j][4 * g], acc[n][j][4 * g + 1], acc[n][j][4 * g + 2], acc[n][j][4 * g + 3]};
+          P[((int64_t)split * Mp + m) * (Np >> 2) + n4] = v;
+        }
+      }
+    } else {  // EPI_SWIGLU: rows alternate gate_f, up_f
+      uint32_t *O = (uint32_t *)out;
+#pragma unroll
+      for (int j = 0; j < MB; ++j) {
+        int m = (mblk0 + j) * 32 + col;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          int f = nb * 16 + half * 2 + 4 * g;
+          float v0 = silu_f(acc[n][j][4 * g]) * acc[n][j][4 * g + 1];
+          float v1 = silu_f(acc[n][j][4 * g + 2]) * acc[n][j][4 * g + 3];
+          uint32_t pk = (uint32_t)f32_to_bf16_bits(v0) | ((uint32_t)f32_to_bf16_bits(v1) << 16);
+          O[(((int64_t)(f >> 3) * Mp + m) * 8 + (f & 7)) >> 1] = pk;
+        }
       }
     }
   }
 }
 
-// Launch-shape heuristics, from sweeps on MI355X at the decode shapes: two wavefronts per workgroup share a
-// weight block's k-steps (deeper in-workgroup splits lose more in the LDS reduction than they gain), and the
-// grid split brings the launch to about 1536 wavefronts; a GEMM whose epilogue needs the whole K (nsplit = 1)
-// takes one wavefront per block once there are several hundred blocks.
-int fast_gemm_pick(int Np, int Kp, int Mp, int *nsplit, int *waves_k) {
+// Launch shape.  nbw: weight blocks per wavefront (2 halves the activation re-reads per weight byte, but on MI355X
+// at 64 batch rows the fewer, fatter wavefronts measured slower, so the decode GEMMs run nbw = 1; the lm_head
+// uses 2).  waves_k x nsplit wavefronts share a block's k-steps: the in-workgroup part costs an LDS reduction, the
+// grid part costs partial traffic; sweeps favour waves_k = 2 and a grid split that brings the launch to about
+// 1536 wavefronts.  A GEMM whose epilogue needs the whole K has nsplit = 1.
+void fast_gemm_pick(int Np, int Kp, int Mp, int full_k, GemmShape *g) {
   int nblocks = Np / 32, ksteps = Kp / 16, mb = Mp / 32 > 8 ? 8 : Mp / 32;
   int zblocks = Mp / (32 * mb);
+  g->nbw = 1;
+  g->waves_n = 1;
+  int tiles = nblocks / g->nbw * zblocks;
   int wk = 2;
-  while (wk > 1 && (ksteps / wk < 8 || (wk - 1) * mb * 4096 > 65536)) --wk;
-  int ns = (1536 + nblocks * zblocks * wk / 2) / (nblocks * zblocks * wk);
+  while (wk > 1 && (ksteps / wk < 8 || (size_t)(wk - 1) * g->nbw * mb * 4096 > 65536)) --wk;
+  if (full_k && tiles >= 256) wk = tiles >= 512 ? 1 : 2;
+  int ns = full_k ? 1 : (1536 + tiles * wk / 2) / (tiles * wk);
   if (ns > 8) ns = 8;
   while (ns > 1 && ksteps / (ns * wk) < 8) --ns;
   if (ns < 1) ns = 1;
-  *nsplit = ns;
-  *waves_k = wk;
-  return 0;
+  g->nsplit = ns;
+  g->waves_k = wk;
 }
 
 template <int EPI>
-static void gemm_dispatch(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, int nsplit, int waves_k,
-                          hipStream_t st) {
+static void gemm_dispatch(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, GemmShape g, hipStream_t st) {
   int mbt = Mp / 32;
   int MB = mbt >= 8 ? 8 : mbt;
-  int ksteps = Kp / 16, kps = (ksteps + nsplit - 1) / nsplit;
-  dim3 grid(Np / 32, nsplit, mbt / MB), block(64 * waves_k);
-  size_t lds = (size_t)(waves_k - 1) * MB * 16 * 64 * sizeof(float);
+  int ksteps = Kp / 16, kps = (ksteps + g.nsplit - 1) / g.nsplit;
+  int per_wg = g.nbw * g.waves_n, nblocks = Np / 32;
+  dim3 grid((nblocks + per_wg - 1) / per_wg, g.nsplit, mbt / MB), block(64 * g.waves_n * g.waves_k);
+  size_t lds = (size_t)(g.waves_k - 1) * g.waves_n * g.nbw * MB * 16 * 64 * sizeof(float);
   const bf16x8 *X = (const bf16x8 *)Xp, *W = (const bf16x8 *)Wp;
-  switch (MB) {
-    case 1: hipLaunchKernelGGL((gemm_kernel<1, EPI>), grid, block, lds, st, out, X, W, Mp, Np, Kp, kps); break;
-    case 2: hipLaunchKernelGGL((gemm_kernel<2, EPI>), grid, block, lds, st, out, X, W, Mp, Np, Kp, kps); break;
-    case 4: hipLaunchKernelGGL((gemm_kernel<4, EPI>), grid, block, lds, st, out, X, W, Mp, Np, Kp, kps); break;
-    default: hipLaunchKernelGGL((gemm_kernel<8, EPI>), grid, block, lds, st, out, X, W, Mp, Np, Kp, kps); break;
+#define GEMM_LAUNCH(MBV, NBWV) \
+  hipLaunchKernelGGL((gemm_kernel<MBV, NBWV, EPI>), grid, block, lds, st, out, X, W, Mp, Np, Kp, kps, g.waves_n)
+  if (g.nbw == 2) {
+    switch (MB) {
+      case 1: GEMM_LAUNCH(1, 2); break;
+      case 2: GEMM_LAUNCH(2, 2); break;
+      default: GEMM_LAUNCH(4, 2); break;
+    }
+  } else {
+    switch (MB) {
+      case 1: GEMM_LAUNCH(1, 1); break;
+      case 2: GEMM_LAUNCH(2, 1); break;
+      case 4: GEMM_LAUNCH(4, 1); break;
+      default: GEMM_LAUNCH(8, 1); break;
+    }
   }
+#undef GEMM_LAUNCH
 }
 
-void fast_gemm(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, int nsplit, int waves_k,
-               GemmEpilogue epi, hipStream_t st) {
-  if (epi == EPI_PARTIAL) gemm_dispatch<EPI_PARTIAL>(out, Xp, Wp, Mp, Np, Kp, nsplit, waves_k, st);
-  else gemm_dispatch<EPI_SWIGLU>(out, Xp, Wp, Mp, Np, Kp, 1, Np / 32 >= 384 ? 1 : waves_k, st);
+void fast_gemm(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, GemmShape g, GemmEpilogue epi,
+               hipStream_t st) {
+  if (epi == EPI_PARTIAL) gemm_dispatch<EPI_PARTIAL>(out, Xp, Wp, Mp, Np, Kp, g, st);
+  else { g.nsplit = 1; gemm_dispatch<EPI_SWIGLU>(out, Xp, Wp, Mp, Np, Kp, g, st); }
 }
 
 // ---- lm_head ---------------------------------------------------------------------------------------------
-// grid (ceil(Np/32 / (4*NBSEQ)), 1, Mp/(32*MB)); block 256.  Each wavefront runs NBSEQ weight blocks over the full
+// grid (ceil(Np/32 / (4*LM_NBW)), 1, Mp/(32*MB)); block 256.  Each wavefront runs LM_NBW weight blocks over the full
 // K and folds every logit into a running (max, sum-exp, best perturbed score, its index, its z) per batch row.
-constexpr int LM_NBSEQ = 2;
+constexpr int LM_NBW = 2;      // weight blocks per wavefront
 
 template <int MB, bool LOGITS>
 __global__ __launch_bounds__(256) void lmhead_kernel(const bf16x8 *__restrict__ Xp, const bf16x8 *__restrict__ Wp, int Mp,
@@ -223,15 +260,22 @@ __global__ __launch_bounds__(256) void lmhead_kernel(const bf16x8 *__restrict__ 
   SampleAcc sa[MB];
 #pragma unroll
   for (int j = 0; j < MB; ++j) sa[j] = sample_acc_init();
-  for (int q = 0; q < LM_NBSEQ; ++q) {
-    int nb = (blockIdx.x * 4 + w) * LM_NBSEQ + q;
-    if (nb >= nblocks) break;
-    f32x16 acc[MB];
+  const int nb0 = (blockIdx.x * 4 + w) * LM_NBW;
+  f32x16 accs[LM_NBW][MB];
+#pragma unroll
+  for (int n = 0; n < LM_NBW; ++n)
 #pragma unroll
     for (int j = 0; j < MB; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
-    mma_range<MB>(acc, Wp + w_block_base(nb, Kp), Xp + mblk0 * 32, Mp, 0, Kp >> 4, lane, w_kstep_stride(Np));
+      for (int r = 0; r < 16; ++r) accs[n][j][r] = 0.f;
+  if (nb0 < nblocks)   // blocks past the end re-read the last block; their results are dropped below
+    mma_range<MB, LM_NBW>(accs, Wp + w_block_base(min(nb0, nblocks - LM_NBW), Kp), w_block_base(1, Kp), Xp + mblk0 * 32, Mp, 0,
+                          Kp >> 4, lane, w_kstep_stride(Np));
+#pragma unroll
+  for (int q = 0; q < LM_NBW; ++q) {
+    const int nb = nb0 + q;
+    if (nb >= nblocks) break;
+    f32x16 (&acc)[MB] = accs[q];
 #pragma unroll
     for (int j = 0; j < MB; ++j) {
       int m = (mblk0 + j) * 32 + col;
@@ -305,7 +349,7 @@ __global__ void sample_combine_kernel(int32_t *tok, float *lp, float *target_lp,
   }
 }
 
-static int lm_wgs(int Np) { return (Np / 32 + 4 * LM_NBSEQ - 1) / (4 * LM_NBSEQ); }
+static int lm_wgs(int Np) { return (Np / 32 + 4 * LM_NBW - 1) / (4 * LM_NBW); }
 size_t fast_lmhead_partial_floats(int Np, int Mp) { return (size_t)5 * lm_wgs(Np) * Mp + Mp; }
 
 template <bool LOGITS>
