@@ -4,10 +4,10 @@
  * The library is the GPU side of a rollout worker as ECHO-2 states the problem:
  * a worker holds a locally installed policy snapshot of some version, draws
  * responses y ~ pi_v(. | x) for prompts x, and emits them tagged with that version
- * (Sec. 3.2 "Rollout generation"; Algorithm 1, rollout-plane loop); the learner's
+ * (Sec. 4.1 "Versioned Execution and Bounded Staleness"; Algorithm 1, rollout-plane loop); the learner's
  * truncated importance ratio needs the sampler's own per-token probability
  * (App. "GRPO-Style Policy Gradient Objective"); a worker switches to a new
- * snapshot once it is completely installed (Sec. 3.3).  The policy is a dense
+ * snapshot once it is completely installed (Sec. 4.2).  The policy is a dense
  * decoder-only transformer (RMSNorm, grouped-query attention with rotary
  * embeddings, SwiGLU, no biases); every step of the path runs in HIP kernels for
  * gfx950.  One context drives one GPU.  There is no CPU fallback.
@@ -99,7 +99,7 @@ size_t echo_blob_bytes(const echo_model_desc *desc);
 int echo_init(const echo_model_desc *desc, int device, void *dev_arena, size_t arena_bytes,
               void *compute_stream, void *copy_stream, echo_ctx **out);
 
-/* Install policy snapshot `version` (Sec. 3.2-3.3: immutable snapshots, versions only advance).
+/* Install policy snapshot `version` (Sec. 4.1-4.2: immutable snapshots, versions only advance).
  * host_weights (host, nbytes = echo_blob_bytes) is a flat row-major [out,in] blob in the model dtype:
  *   embed[V,d]; per layer attn_norm[d], wq[Hq*hd,d], wk[Hkv*hd,d], wv[Hkv*hd,d], (q_norm[hd], k_norm[hd]),
  *   wo[d,Hq*hd], ffn_norm[d], w_gate[F,d], w_up[F,d], w_down[d,F]; final_norm[d]; lm_head[V,d] (if untied).

@@ -3,12 +3,13 @@
  *
  * A plain, slow, definition-level implementation of what a rollout worker
  * computes: for a prompt x it draws y ~ pi_v(. | x) token by token from the
- * policy's autoregressive distribution (ECHO-2, Sec. 3.2 "Rollout generation";
+ * policy's autoregressive distribution (ECHO-2, Sec. 4.1 "Versioned Execution and
+ * Bounded Staleness";
  * Algorithm 1, rollout-plane loop) and records, for every sampled token, the
  * probability the sampler assigned to it (the denominator pi_sampler of the
  * truncated importance ratio, App. "GRPO-Style Policy Gradient Objective"),
- * tagged with the snapshot version in use (Sec. 3.2 "Policy publication",
- * Sec. 3.3: a worker switches version once a snapshot is fully installed).
+ * tagged with the snapshot version in use (Sec. 4.1: immutable snapshots;
+ * Sec. 4.2: a worker switches version once a snapshot is fully installed).
  *
  * The paper does not define the policy network; the decoder evaluated here is
  * the dense pre-norm transformer the workloads name (RMSNorm, grouped-query
