@@ -60,7 +60,7 @@ int pad_rows(int m) {  // 32 * pow2 up to 256, then multiples of 256
   return p;
 }
 
-size_t packed_bytes(int64_t N, int64_t K) { return (size_t)(round_up(N, 32) * round_up(K, 16) * 2); }
+size_t packed_bytes(int64_t N, int64_t K) { return (size_t)(round_up(N, 32) * round_up(K, GEMM_K_PAD) * 2); }
 
 bool valid_desc(const echo_model_desc *d, std::string *why) {
   auto bad = [&](const char *m) { if (why) *why = m; return false; };
@@ -99,7 +99,7 @@ Plan make_plan(const echo_model_desc *d) {
   p.Mcap = std::max(pad_rows(d->max_seqs), PREFILL_ROWS);
   p.Np_qkv = (int)round_up(Q + 2 * KV, 32); p.Np_d = (int)round_up(H, 32); p.Np_gu = (int)round_up(2 * F, 32);
   p.Np_v = (int)round_up(V, 64);   // an even number of 32-row blocks: lm_head wavefronts own two blocks
-  p.Kp_d = (int)round_up(H, 16); p.Kp_q = (int)round_up(Q, 16); p.Kp_f = (int)round_up(F, 16);
+  p.Kp_d = (int)round_up(H, GEMM_K_PAD); p.Kp_q = (int)round_up(Q, GEMM_K_PAD); p.Kp_f = (int)round_up(F, GEMM_K_PAD);
   Bump b;
   if (p.fast) {
     size_t per = 2 * H * 2 + (d->qk_norm ? 2 * hd * 2 : 0) + 4 * 256 /*alignment slack*/ + packed_bytes(Q + 2 * KV, H) +
@@ -246,7 +246,7 @@ void bind_slot(echo_ctx *c, int s) {
 // Copy a row-major bf16 matrix from the host blob through the staging buffer into a packed weight.
 int stage_matrix(echo_ctx *c, const void *dst, const char *src, int64_t rows, int K, int64_t dst_row0, int stride) {
   int Np = (int)round_up(rows * stride, 32);
-  int Kp = (int)round_up(K, 16);
+  int Kp = (int)round_up(K, GEMM_K_PAD);
   int64_t row_bytes = (int64_t)K * 2, rows_per = std::max<int64_t>(1, (int64_t)(c->p.stage_bytes / 2) / row_bytes);
   static int flip = 0;
   for (int64_t r = 0; r < rows; r += rows_per) {

@@ -8,7 +8,7 @@ namespace echo {
 
 // ------------------------------------------------------------------------------------------------
 // Layouts of the bf16 (MFMA) path.
-//   packed weight  Wp: rows padded to 32, K padded to 16.  Element (r,k) lives at
+//   packed weight  Wp: rows padded to 32, K padded to GEMM_K_PAD.  Element (r,k) lives at
 //       ((((r/32)*(Kp/8) + k/8)*32 + r%32)*8 + k%8)            -- one 32-row block is contiguous over K,
 //       and a wavefront's MFMA A-operand load (32 rows x 16 k) is one contiguous 1 KiB read.
 //   packed activation Xp ("K8"): M padded to 32.  Element (m,k) lives at ((k/8)*Mp + m)*8 + k%8.
@@ -73,7 +73,8 @@ void fast_resid_norm(float *h, const void *embed_bf16, const int32_t *token, con
 enum GemmEpilogue { EPI_PARTIAL = 0, EPI_SWIGLU = 1 };
 // out = Xp[Mp x Kp] * Wp[Np x Kp]^T.  EPI_PARTIAL: fp32 partials [nsplit][Mp][Np];
 // EPI_SWIGLU (rows alternate gate_f, up_f): silu(gate)*up -> bf16 K8 [Mp][Np/2]; nsplit must be 1.
-struct GemmShape { int nsplit, waves_k, waves_n, nbw; };   // launch shape, see fast_gemm_pick
+struct GemmShape { int nsplit, waves_k, waves_n, nbw, lds, stages; };   // launch shape, see fast_gemm_pick
+constexpr int GEMM_K_PAD = 128;   // packed weights and K8 activations pad K to this (whole LDS chunks of 8 k-steps)
 void fast_gemm(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, GemmShape g, GemmEpilogue epi,
                hipStream_t st);
 void fast_gemm_pick(int Np, int Kp, int Mp, int full_k, GemmShape *g);

@@ -187,14 +187,159 @@ __global__ __launch_bounds__(512) void gemm_kernel(void *out, const bf16x8 *__re
   }
 }
 
-// Launch shape.  nbw: weight blocks per wavefront (2 halves the activation re-reads per weight byte, but on MI355X
-// at 64 batch rows the fewer, fatter wavefronts measured slower, so the decode GEMMs run nbw = 1; the lm_head
-// uses 2).  waves_k x nsplit wavefronts share a block's k-steps: the in-workgroup part costs an LDS reduction, the
-// grid part costs partial traffic; sweeps favour waves_k = 2 and a grid split that brings the launch to about
-// 1536 wavefronts.  A GEMM whose epilogue needs the whole K has nsplit = 1.
+// ---- weight-streaming GEMM with the activations staged through LDS -----------------------------------------
+// Measured on MI355X: a compute unit sustains about 48 GB/s of vector-memory reads whether they come from HBM
+// (weights) or from L2 (activations), so activation re-reads cost as much as weight bytes.  Here the WN wavefronts
+// of a workgroup own WN consecutive 32-row weight blocks and walk the same k-range in chunks of KC k-steps; a
+// chunk of activations (KC x MB KiB) is fetched once per workgroup, coalesced, and shared through LDS, which cuts
+// the activation traffic per weight byte to MB/WN.  Weight loads run NSTAGE-1 chunks ahead in registers.  The
+// activation loads of a chunk are issued before the weight loads of the same chunk: the memory counter retires in
+// order, so waiting for them (to copy them into LDS) leaves every younger weight load in flight.
+// grid (ceil(Np/32 / WN), nsplit, Mp/(32*MB)); block 64*WN; chunks_per_split chunks of KC k-steps per grid split.
+typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
+
+template <int MB, int WN> struct GemmLds {
+  static constexpr int KC = 8;
+  static constexpr int CHUNK_UNITS = KC * 2 * 32 * MB;                  // 16-byte units of one activation chunk
+  static constexpr int X_BYTES = 2 * CHUNK_UNITS * 16;                   // double buffer
+  static constexpr int TILE_STRIDE = 33;                                 // floats per row of the transposed output tile
+  static constexpr int EPI_BYTES = WN * 32 * MB * TILE_STRIDE * 4;
+  static constexpr int BYTES = X_BYTES > EPI_BYTES ? X_BYTES : EPI_BYTES;
+};
+
+template <int MB, int WN, int NSTAGE, int EPI>
+__global__ __launch_bounds__(WN * 64) void gemm_lds_kernel(void *out, const u32x4v *__restrict__ Xp, const bf16x8 *__restrict__ Wp,
+                                                           int Mp, int Np, int Kp, int chunks_per_split) {
+  extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+  using L = GemmLds<MB, WN>;
+  constexpr int KC = L::KC, T = WN * 64, XU = L::CHUNK_UNITS, XL = (XU + T - 1) / T, ROWS = 32 * MB;
+  u32x4v *xs = (u32x4v *)lds_raw;
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, tid = threadIdx.x;
+  const int nblocks = Np >> 5, total_chunks = (Kp >> 4) / KC;
+  const int nb_own = blockIdx.x * WN + w, nb = min(nb_own, nblocks - 1);   // wavefronts past the end re-read the last block
+  const int c_begin = blockIdx.y * chunks_per_split, nchunks = min(chunks_per_split, total_chunks - c_begin);
+  const int mrow0 = blockIdx.z * ROWS;
+  const bf16x8 *a_ptr = Wp + w_block_base(nb, Kp) + (int64_t)c_begin * KC * w_kstep_stride(Np) + (lane >> 5) * 32 + (lane & 31);
+  const int64_t a_step = w_kstep_stride(Np);
+  f32x16 acc[MB];
+#pragma unroll
+  for (int j = 0; j < MB; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+  bf16x8 a[NSTAGE][KC];
+  u32x4v xr[NSTAGE][XL];
+  auto load_a = [&](int st, int c) {
+#pragma unroll
+    for (int u = 0; u < KC; ++u) a[st][u] = __builtin_nontemporal_load(a_ptr + (int64_t)(c * KC + u) * a_step);
+  };
+  // unit i of a chunk: k8 group i / ROWS (two per k-step), batch row i % ROWS
+  auto load_x = [&](int st, int c) {
+#pragma unroll
+    for (int i = 0; i < XL; ++i) {
+      int idx = i * T + tid;
+      if (XU % T == 0 || idx < XU)
+        xr[st][i] = Xp[(int64_t)((c_begin + c) * KC * 2 + idx / ROWS) * Mp + mrow0 + idx % ROWS];
+    }
+  };
+  auto store_x = [&](int st, int buf) {
+#pragma unroll
+    for (int i = 0; i < XL; ++i) {
+      int idx = i * T + tid;
+      if (XU % T == 0 || idx < XU) xs[buf * XU + idx] = xr[st][i];
+    }
+  };
+  auto compute = [&](int st, int buf) {
+    const u32x4v *bp = xs + buf * XU + (lane >> 5) * ROWS + (lane & 31);
+#pragma unroll
+    for (int u = 0; u < KC; ++u)
+#pragma unroll
+      for (int j = 0; j < MB; ++j)
+        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[st][u], __builtin_bit_cast(bf16x8, bp[u * 2 * ROWS + j * 32]), acc[j], 0, 0, 0);
+  };
+  if (nchunks > 0) {
+#pragma unroll
+    for (int s = 0; s < NSTAGE - 1; ++s)
+      if (s < nchunks) { load_x(s, s); load_a(s, s); }
+    store_x(0, 0);
+    __syncthreads();
+    for (int c0 = 0; c0 < nchunks; c0 += NSTAGE) {
+#pragma unroll
+      for (int s = 0; s < NSTAGE; ++s) {
+        const int c = c0 + s;
+        if (c < nchunks) {
+          if (c + NSTAGE - 1 < nchunks) { load_x((s + NSTAGE - 1) % NSTAGE, c + NSTAGE - 1); load_a((s + NSTAGE - 1) % NSTAGE, c + NSTAGE - 1); }
+          compute(s, c & 1);
+          if (c + 1 < nchunks) store_x((s + 1) % NSTAGE, (c + 1) & 1);
+          __syncthreads();   // chunk c+1 is visible; chunk c's buffer may be overwritten two iterations later
+        }
+      }
+    }
+  }
+  const int half = lane >> 5, col = lane & 31;
+  if (EPI == EPI_PARTIAL) {
+    // transpose the wavefront's 32 x ROWS tile through LDS so that every store is a whole 128-byte row segment
+    float *tile = (float *)lds_raw + (size_t)w * ROWS * L::TILE_STRIDE;
+#pragma unroll
+    for (int j = 0; j < MB; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) tile[(j * 32 + col) * L::TILE_STRIDE + 8 * g + 4 * half + i] = acc[j][4 * g + i];
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the tile is private to this wavefront
+    if (nb_own >= nblocks) return;
+    float *P = (float *)out + ((int64_t)blockIdx.y * Mp + mrow0) * Np + nb * 32;
+#pragma unroll
+    for (int q = 0; q < ROWS / 8; ++q) {
+      int r = q * 8 + (lane >> 3), n4 = (lane & 7) * 4;
+      const float *t = tile + r * L::TILE_STRIDE + n4;
+      f32x4 v = {t[0], t[1], t[2], t[3]};
+      *(f32x4 *)(P + (int64_t)r * Np + n4) = v;
+    }
+  } else {  // EPI_SWIGLU: weight rows alternate gate_f, up_f; a block of 32 rows yields 16 features = two K8 groups
+    if (nb_own >= nblocks) return;
+    uint32_t *O = (uint32_t *)out;
+#pragma unroll
+    for (int j = 0; j < MB; ++j) {
+      uint32_t pk[4];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {   // features 4g + 2*half + {0,1} of the block
+        float v0 = silu_f(acc[j][4 * g]) * acc[j][4 * g + 1];
+        float v1 = silu_f(acc[j][4 * g + 2]) * acc[j][4 * g + 3];
+        pk[g] = (uint32_t)f32_to_bf16_bits(v0) | ((uint32_t)f32_to_bf16_bits(v1) << 16);
+      }
+      // lane (half 0) assembles K8 group 0 (features 0..7), its partner (half 1) group 1 (features 8..15)
+      uint32_t give0 = half ? pk[0] : pk[2], give1 = half ? pk[1] : pk[3];
+      uint32_t got0 = __shfl_xor(give0, 32, 64), got1 = __shfl_xor(give1, 32, 64);
+      u32x4v o = half ? u32x4v{got0, pk[2], got1, pk[3]} : u32x4v{pk[0], got0, pk[1], got1};
+      int m = mrow0 + j * 32 + col;
+      *(u32x4v *)(O + (((int64_t)(nb * 2 + half) * Mp + m) * 4)) = o;
+    }
+  }
+}
+
+// Launch shape.  Up to 128 batch rows the LDS-staged kernel runs: three or four weight blocks per workgroup, and a
+// grid split over K that brings the launch to about one workgroup per compute unit (partials cost HBM writes, so
+// no more than that); a GEMM whose epilogue needs the whole K (SwiGLU) is not split.  Larger batches keep the
+// register-streaming kernel: waves_k wavefronts of a workgroup share a block's k-steps and are summed in LDS.
 void fast_gemm_pick(int Np, int Kp, int Mp, int full_k, GemmShape *g) {
   int nblocks = Np / 32, ksteps = Kp / 16, mb = Mp / 32 > 8 ? 8 : Mp / 32;
   int zblocks = Mp / (32 * mb);
+  g->lds = 0; g->stages = 0;
+  if (Mp <= 128 && Kp % (16 * GemmLds<1, 4>::KC) == 0) {
+    int total_chunks = ksteps / GemmLds<1, 4>::KC;
+    g->lds = 1; g->nbw = 1; g->waves_k = 1;
+    if (full_k) { g->waves_n = 3; g->stages = 4; g->nsplit = 1; return; }
+    g->waves_n = nblocks % 4 == 0 || nblocks > 96 ? 4 : 3;
+    g->stages = 3;
+    int strips = (nblocks + g->waves_n - 1) / g->waves_n;
+    int ns = (256 + strips / 2) / strips;
+    if (ns > total_chunks / 2) ns = total_chunks / 2;
+    if (ns > 8) ns = 8;
+    if (ns < 1) ns = 1;
+    int cps = (total_chunks + ns - 1) / ns;
+    g->nsplit = (total_chunks + cps - 1) / cps;
+    return;
+  }
   g->nbw = 1;
   g->waves_n = 1;
   int tiles = nblocks / g->nbw * zblocks;
@@ -209,8 +354,36 @@ void fast_gemm_pick(int Np, int Kp, int Mp, int full_k, GemmShape *g) {
   g->waves_k = wk;
 }
 
+template <int MB, int WN, int NSTAGE, int EPI>
+static void gemm_lds_launch(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, int nsplit, hipStream_t st) {
+  using L = GemmLds<MB, WN>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void *)gemm_lds_kernel<MB, WN, NSTAGE, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, L::BYTES);
+    attr_set = true;
+  }
+  int nblocks = Np / 32, total_chunks = (Kp / 16) / L::KC, cps = (total_chunks + nsplit - 1) / nsplit;
+  dim3 grid((nblocks + WN - 1) / WN, nsplit, Mp / (32 * MB)), block(64 * WN);
+  hipLaunchKernelGGL((gemm_lds_kernel<MB, WN, NSTAGE, EPI>), grid, block, L::BYTES, st, out, (const u32x4v *)Xp, (const bf16x8 *)Wp, Mp,
+                     Np, Kp, cps);
+}
+
+template <int EPI>
+static void gemm_lds_dispatch(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, GemmShape g, hipStream_t st) {
+  int mb = Mp / 32;   // 1, 2 or 4
+#define LDS_CASE(MBV)                                                                                              \
+  if (g.waves_n == 3 && g.stages == 4) gemm_lds_launch<MBV, 3, 4, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st);     \
+  else if (g.waves_n == 3) gemm_lds_launch<MBV, 3, 3, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st);                 \
+  else gemm_lds_launch<MBV, 4, 3, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st)
+  if (mb == 1) { LDS_CASE(1); }
+  else if (mb == 2) { LDS_CASE(2); }
+  else { LDS_CASE(4); }
+#undef LDS_CASE
+}
+
 template <int EPI>
 static void gemm_dispatch(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, GemmShape g, hipStream_t st) {
+  if (g.lds) { gemm_lds_dispatch<EPI>(out, Xp, Wp, Mp, Np, Kp, g, st); return; }
   int mbt = Mp / 32;
   int MB = mbt >= 8 ? 8 : mbt;
   int ksteps = Kp / 16, kps = (ksteps + g.nsplit - 1) / g.nsplit;
