@@ -68,6 +68,8 @@ def main():
     ap.add_argument("--workload", default="dense4b-64x512+1024", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="launch decode steps kernel by kernel (counter collection cannot follow graph replays)")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py measures one GPU: rollout workers are independent (data parallel over prompts) and "
@@ -91,13 +93,13 @@ def main():
     load_s = time.perf_counter() - t0
 
     for _ in range(a.warmup):
-        ctx.rollout(prompts, lens, G, max_new, 1.0, 2)
+        ctx.rollout(prompts, lens, G, max_new, 1.0, 2, no_graph=a.no_graph)
     torch.cuda.synchronize()
     times, toks, decode_ms, prefill_ms = [], 0, [], []
     t_all = time.perf_counter()
     for k in range(a.steps):
         t0 = time.perf_counter()
-        out = ctx.rollout(prompts, lens, G, max_new, 1.0, 2 + k)
+        out = ctx.rollout(prompts, lens, G, max_new, 1.0, 2 + k, no_graph=a.no_graph)
         times.append(time.perf_counter() - t0)
         toks += int(out["lens"].sum())
         st = ctx.stats()
