@@ -68,6 +68,7 @@ def main():
     ap.add_argument("--workload", default="dense4b-64x512+1024", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--ctx-pad", type=int, default=0, help="extra KV-cache tokens per sequence beyond prompt + max_new")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch decode steps kernel by kernel (counter collection cannot follow graph replays)")
     a = ap.parse_args()
@@ -87,7 +88,7 @@ def main():
     del blob_dev
     torch.cuda.empty_cache()
     prompts, lens = synth.make_prompts(shape.vocab, P, plen, seed=1)
-    ctx = echo.Context(echo.desc_from_shape(shape, N, plen + max_new))
+    ctx = echo.Context(echo.desc_from_shape(shape, N, plen + max_new + a.ctx_pad))
     t0 = time.perf_counter()
     ctx.load_policy(0, blob)
     load_s = time.perf_counter() - t0

@@ -110,7 +110,8 @@ Plan make_plan(const echo_model_desc *d) {
   }
   for (int s = 0; s < d->n_weight_slots; ++s) p.o_slot[s] = b.take(p.slot_bytes);
   int kv_elt = p.fast ? 2 : 4;
-  p.kv_bytes = (size_t)d->max_seqs * d->n_layers * 2 * d->n_kv_heads * d->max_ctx * hd * kv_elt;
+  int64_t ctx_cap = p.fast ? round_up(d->max_ctx, 32) : d->max_ctx;   // the tiled cache holds whole tiles of 32 keys
+  p.kv_bytes = (size_t)d->max_seqs * d->n_layers * 2 * d->n_kv_heads * ctx_cap * hd * kv_elt;
   p.o_kv = b.take(p.kv_bytes);
   size_t M = p.Mcap;
   p.o_h = b.take(M * H * 4);
@@ -516,7 +517,8 @@ int echo_init(const echo_model_desc *desc, int device, void *dev_arena, size_t a
   int32_t *r = at<int32_t>(c, p.o_rows);
   size_t M = p.Mcap;
   c->rows = {r, r + M, r + 2 * M, r + 3 * M};
-  c->kv = {c->arena + p.o_kv, desc->n_layers, desc->n_kv_heads, desc->max_ctx, desc->head_dim, p.fast ? 2 : 4};
+  c->kv = {c->arena + p.o_kv, desc->n_layers, desc->n_kv_heads, p.fast ? (int32_t)round_up(desc->max_ctx, 32) : desc->max_ctx, desc->head_dim,
+           p.fast ? 2 : 4, p.fast ? 1 : 0};
   int32_t *q = at<int32_t>(c, p.o_seq);
   c->d_prompt_len_seq = q; c->d_gen_len = q + desc->max_seqs; c->d_limit = q + 2 * (size_t)desc->max_seqs;
   int32_t *sm = at<int32_t>(c, p.o_samp);

@@ -23,13 +23,30 @@ struct RowState {        // device arrays, one entry per row of the current batc
   int32_t *active;       // 0: row is skipped (finished sequence or padding)
 };
 
-struct KvGeom {          // KV cache: [slot][layer][K|V][kv_head][max_ctx][head_dim]
+struct KvGeom {          // KV cache, plain form: [slot][layer][K|V][kv_head][max_ctx][head_dim]
   void *base;
   int32_t n_layers, n_kv_heads, max_ctx, head_dim, elt_bytes;
+  int32_t tiled;         // 1: the MFMA path's form (same size, max_ctx a multiple of 32), see below
   __host__ __device__ int64_t head_stride() const { return (int64_t)max_ctx * head_dim; }
   __host__ __device__ int64_t kv_stride() const { return head_stride() * n_kv_heads; }
   __host__ __device__ int64_t layer_stride() const { return kv_stride() * 2; }
   __host__ __device__ int64_t slot_stride() const { return layer_stride() * n_layers; }
+  // Tiled form: [slot][layer][kv_head][tile of 32 keys][K tile | V tile].  Both tiles are stored in the order the
+  // attention kernel's MFMA operands want them, so a wavefront reads a tile as head_dim/16 contiguous 1 KiB loads
+  // per operand, straight into registers.  In 16-byte units (8 bf16):
+  //   K tile: unit (dim/8)*32 + key%32 holds dims 8*(dim/8).. of one key            (A operand of K Q^T)
+  //   V tile: unit (((key%32)/16 * (hd/32) + dim/32)*2 + (key%16)/8)*32 + dim%32 holds 8 keys of one dim (A operand of V^T P^T)
+  __host__ __device__ int64_t tiled_head_off(int slot, int layer, int kvh) const {
+    return (int64_t)slot * slot_stride() + (int64_t)layer * layer_stride() + (int64_t)kvh * 2 * head_stride();
+  }
+  __host__ __device__ int64_t tiled_k_off(int key, int dim) const {
+    return (int64_t)(key >> 5) * 64 * head_dim + ((dim >> 3) * 32 + (key & 31)) * 8 + (dim & 7);
+  }
+  __host__ __device__ int64_t tiled_v_off(int key, int dim) const {
+    int k = key & 31;
+    return (int64_t)(key >> 5) * 64 * head_dim + 32 * head_dim +
+           ((((k >> 4) * (head_dim >> 5) + (dim >> 5)) * 2 + ((k >> 3) & 1)) * 32 + (dim & 31)) * 8 + (k & 7);
+  }
 };
 
 // ---- shared small kernels (both paths) -----------------------------------------------------------

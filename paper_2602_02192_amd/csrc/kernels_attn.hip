@@ -1,20 +1,19 @@
-// bf16 path: grouped-query decode attention over the contiguous per-sequence KV cache.
+// bf16 path: grouped-query decode attention over the tiled per-sequence KV cache.
 //
 // attn_simple_kernel: one wavefront per (row, query head), two passes, no split -- the plain form, kept as
 //   the on-GPU cross-check of the split-K kernel.
-// attn_splitk_kernel: one workgroup per (row, KV head, chunk of keys); the group's query heads share every
-//   K/V tile; tiles are staged in LDS from fully coalesced 16-byte loads; QK^T and PV run on MFMA with an
-//   online softmax per wavefront; partial (max, sum, acc) per chunk are merged by attn_combine_kernel in
-//   chunk order (deterministic, no atomics).
+// attn_splitk_kernel: one workgroup per (row, KV head, split of the keys).  Its wavefronts take tiles of 32 keys
+//   in turn.  A tile's K and V are stored in MFMA operand order (see KvGeom), so a wavefront streams them from
+//   HBM straight into operand registers with contiguous 1 KiB loads, one tile ahead of the one being computed; the
+//   loop touches no LDS.  The group's query heads share every tile.  S^T = K Q^T and O^T = V^T P^T run on MFMA
+//   (keys and head dims on the 32-row side, the group's query heads on the column side), with an online softmax
+//   whose state lives in the lanes of each query-head column.  Per-wavefront and per-split partial (max, sum,
+//   acc) are merged in a fixed order (no atomics): by the workgroup through LDS, by attn_combine_kernel across
+//   splits.
 #include "echo_device.h"
 #include "echo_kernels.h"
 
 namespace echo {
-
-__device__ __forceinline__ const uint16_t *kv_head_ptr(const KvGeom &kv, int slot, int layer, int kvh) {
-  return (const uint16_t *)kv.base + (int64_t)slot * kv.slot_stride() + (int64_t)layer * kv.layer_stride() +
-         (int64_t)kvh * kv.head_stride();
-}
 
 // Xp (bf16 K8 [Mp][Hq*hd]) element (m, n)
 __device__ __forceinline__ int64_t k8_index(int m, int n, int Mp) { return ((int64_t)(n >> 3) * Mp + m) * 8 + (n & 7); }
@@ -29,12 +28,12 @@ __global__ void attn_simple_kernel(uint16_t *Xp, const uint16_t *q_bf16, RowStat
     return;
   }
   int n_keys = rows.pos[m] + 1, kvh = j / (Hq / Hkv);
-  const uint16_t *K = kv_head_ptr(kv, rows.slot[m], layer, kvh), *V = K + kv.kv_stride();
+  const uint16_t *head = (const uint16_t *)kv.base + kv.tiled_head_off(rows.slot[m], layer, kvh);
   const uint16_t *q = q_bf16 + ((int64_t)m * Hq + j) * hd;
   float scale = 1.0f / sqrtf((float)hd), mx = -INFINITY;
   for (int t = lane; t < n_keys; t += 64) {
     float s = 0.f;
-    for (int i = 0; i < hd; ++i) s += bf16_bits_to_f32(q[i]) * bf16_bits_to_f32(K[(int64_t)t * hd + i]);
+    for (int i = 0; i < hd; ++i) s += bf16_bits_to_f32(q[i]) * bf16_bits_to_f32(head[kv.tiled_k_off(t, i)]);
     s *= scale;
     sc[t] = s;
     mx = fmaxf(mx, s);
@@ -46,7 +45,7 @@ __global__ void attn_simple_kernel(uint16_t *Xp, const uint16_t *q_bf16, RowStat
   __syncthreads();
   for (int i = lane; i < hd; i += 64) {
     float acc = 0.f;
-    for (int t = 0; t < n_keys; ++t) acc += sc[t] * bf16_bits_to_f32(V[(int64_t)t * hd + i]);
+    for (int t = 0; t < n_keys; ++t) acc += sc[t] * bf16_bits_to_f32(head[kv.tiled_v_off(t, i)]);
     Xp[k8_index(m, j * hd + i, Mp)] = f32_to_bf16_bits(acc / den);
   }
 }
@@ -58,53 +57,52 @@ void fast_attention_simple(void *Xp_out, const void *q_bf16, RowState rows, KvGe
 }
 
 // ---- split-K MFMA kernel -----------------------------------------------------------------------------
-// MFMA roles.  QK^T: A = Q (row = query head of the group, zero beyond the group), B = K^T (column = key);
-// lane l receives, in accumulator registers 0..3, the scores of key l%32 for query rows 4*(l/32)+i.
-// PV: A = P (bf16, through LDS), B = V with column c of MFMA e standing for head dimension (HD/32)*c + e,
-// so that a lane's B operand is built from 8-byte (HD=128) or 4-byte (HD=64) LDS reads of 8 keys.
+// MFMA roles (v_mfma_f32_32x32x16_bf16; lane l: half = l/32, col = l%32).
+// S^T = K Q^T: A = K tile (row = key of the tile, k = 16 head dims), B = Q^T (column = query head of the group, zero
+//   beyond the group); accumulator register 4g+i of a lane holds the score of key 8g + 4*half + i for head `col`.
+// O^T = V^T P^T: A = V tile (row = head dim 32e + row, k = 16 keys), B = P^T (column = query head); register 4g+i
+//   of accumulator e holds head dim 32e + 8g + 4*half + i for head `col`.
+// So everything a query head needs (running max, running sum, its column of O^T) sits in the two lanes of its column,
+// and rescaling is lane-local.
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
-typedef uint32_t v2u __attribute__((ext_vector_type(2)));
 constexpr int ATT_TILE = 32;     // keys per tile
 constexpr int ATT_WAVES = 4;
 
 template <int HD> struct AttLds {
-  static constexpr int ROW = HD * 2 + 16;                  // padded K/V row in bytes
-  static constexpr int PROW = ATT_TILE * 2 + 16;            // padded P row in bytes
-  static constexpr int PER_WAVE = 2 * ATT_TILE * ROW + 8 * PROW;
-  static constexpr int MERGE_PER_WAVE = 8 * HD * 4 + 64;    // O rows + (m, l)
-  static constexpr int TOTAL = ATT_WAVES * PER_WAVE;
+  static constexpr int MERGE_PER_WAVE = 8 * HD * 4 + 64;    // O rows of up to 8 query heads + (m, l)
+  static constexpr int Q_BYTES = 8 * HD * 2;                // the group's queries (B operands are re-read per tile)
+  static constexpr int TOTAL = ATT_WAVES * MERGE_PER_WAVE + Q_BYTES;
 };
-
-template <int HD>
-__device__ __forceinline__ void att_issue_loads(v4u (&rk)[HD / 16], v4u (&rv)[HD / 16], const uint16_t *__restrict__ Kg,
-                                                const uint16_t *__restrict__ Vg, int tk0, int n_keys, int lane) {
-#pragma unroll
-  for (int i = 0; i < HD / 16; ++i) {
-    int u = i * 64 + lane, key = tk0 + u / (HD / 8);
-    key = min(key, n_keys - 1);               // tail keys re-read the last valid row (masked by the caller)
-    int64_t off = (int64_t)key * HD + (u % (HD / 8)) * 8;
-    rk[i] = *(const v4u *)(Kg + off);
-    rv[i] = *(const v4u *)(Vg + off);
-  }
-}
 
 // Keys per split of a row with n_keys keys cut into nsplit equal parts (whole tiles).
 __device__ __forceinline__ int att_split_len(int n_keys, int nsplit) {
   return ((n_keys + nsplit - 1) / nsplit + ATT_TILE - 1) & ~(ATT_TILE - 1);
 }
 
+// A tile is 64*HD bf16 = HD*8 units of 16 bytes: the K tile, then the V tile; lane l of load i reads unit i*64 + l.
+template <int HD>
+__device__ __forceinline__ void att_issue_k(v4u (&rk)[HD / 16], const v4u *__restrict__ head, int tile, int lane) {
+  const v4u *t = head + (int64_t)tile * (HD * 8) + lane;
+#pragma unroll
+  for (int i = 0; i < HD / 16; ++i) rk[i] = __builtin_nontemporal_load(t + i * 64);
+}
+template <int HD>
+__device__ __forceinline__ void att_issue_v(v4u (&rv)[HD / 16], const v4u *__restrict__ head, int tile, int lane) {
+  const v4u *t = head + (int64_t)tile * (HD * 8) + HD * 4 + lane;
+#pragma unroll
+  for (int i = 0; i < HD / 16; ++i) rv[i] = __builtin_nontemporal_load(t + i * 64);
+}
+
 // grid (nsplit, Hkv, M).  Every row's keys are cut into nsplit equal chunks of that row's own length.  DIRECT
 // (nsplit == 1): the workgroup normalises and writes the bf16 output itself and no partials exist.
 template <int HD, bool DIRECT>
 __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__ part_o, float *__restrict__ part_ml,
-                                                             uint16_t *__restrict__ Xp, int Mp,
-                                                             const uint16_t *__restrict__ q_bf16, RowState rows, KvGeom kv,
-                                                             int layer, int Hq, int Hkv, int nsplit) {
+                                                          uint16_t *__restrict__ Xp, int Mp, const uint16_t *__restrict__ q_bf16,
+                                                          RowState rows, KvGeom kv, int layer, int Hq, int Hkv, int nsplit) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   using L = AttLds<HD>;
-  constexpr int KS = HD / 16;          // k-steps of QK^T
-  constexpr int NE = HD / 32;          // PV MFMAs per 16 keys; also head dims per lane column
-  constexpr int LD = HD / 16;          // 16-byte loads per lane per K (or V) tile
+  constexpr int KS = HD / 16;          // k-steps of K Q^T; also 1 KiB loads per K (or V) tile
+  constexpr int NE = HD / 32;          // 32-dim blocks of the head
   const int c = blockIdx.x, kvh = blockIdx.y, m = blockIdx.z;
   const int grp = Hq / Hkv;
   if (!rows.active[m]) {
@@ -114,132 +112,108 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
   }
   const int n_keys = rows.pos[m] + 1, chunk_keys = att_split_len(n_keys, nsplit), key0 = c * chunk_keys;
   if (key0 >= n_keys) return;
-  const int key1 = min(n_keys, key0 + chunk_keys), ntiles = (key1 - key0 + ATT_TILE - 1) / ATT_TILE;
+  const int key1 = min(n_keys, key0 + chunk_keys), ntiles = (key1 - key0 + ATT_TILE - 1) / ATT_TILE, tile0 = key0 / ATT_TILE;
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
-  char *Ks = lds + w * L::PER_WAVE, *Vs = Ks + ATT_TILE * L::ROW, *Ps = Vs + ATT_TILE * L::ROW;
-  const uint16_t *Kg = kv_head_ptr(kv, rows.slot[m], layer, kvh), *Vg = Kg + kv.kv_stride();
+  const v4u *head = (const v4u *)((const uint16_t *)kv.base + kv.tiled_head_off(rows.slot[m], layer, kvh));
 
-  // Q as MFMA A operand: row = col (query head within the group), dims ks*16 + half*8 .. +8
-  bf16x8 qa[KS];
-  {
-    const uint16_t *qrow = q_bf16 + ((int64_t)m * Hq + kvh * grp + (col < grp ? col : 0)) * HD;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      v4u v = *(const v4u *)(qrow + ks * 16 + half * 8);
-      if (col >= grp) v = v4u{0u, 0u, 0u, 0u};
-      qa[ks] = __builtin_bit_cast(bf16x8, v);
-    }
+  // One K and one V register tile per wavefront.  The next tile's K is requested as soon as K Q^T has consumed the
+  // current one, the next V as soon as V^T P^T has; loads return in order, so waiting for V leaves the next K in flight.
+  v4u rk[KS], rv[KS];
+  int tile = w;
+  if (tile < ntiles) { att_issue_k<HD>(rk, head, tile0 + tile, lane); att_issue_v<HD>(rv, head, tile0 + tile, lane); }
+
+  // the group's queries as B operands in LDS: unit (ks*2 + half)*8 + head holds dims ks*16 + half*8 .. +8 of one head
+  v4u *qs = (v4u *)(lds + ATT_WAVES * L::MERGE_PER_WAVE);
+  for (int idx = threadIdx.x; idx < 8 * (HD / 8); idx += 256) {
+    int hq = idx & 7, d8 = idx >> 3;
+    v4u v = v4u{0u, 0u, 0u, 0u};
+    if (hq < grp) v = *(const v4u *)(q_bf16 + ((int64_t)m * Hq + kvh * grp + hq) * HD + d8 * 8);
+    qs[idx] = v;
   }
+  __syncthreads();
+
   const float scale = 1.0f / sqrtf((float)HD);
-  float m_run[4], l_run[4];
+  float m_run = -INFINITY, l_run = 0.f;   // of query head `col` (lanes of one column agree on m_run; l_run is per half)
   f32x16 o[NE];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) { m_run[i] = -INFINITY; l_run[i] = 0.f; }
 #pragma unroll
   for (int e = 0; e < NE; ++e)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[e][r] = 0.f;
 
-  // global -> register staging of one tile: 16-byte unit u = i*64 + lane covers key u/(HD/8), byte (u%(HD/8))*16
-  v4u rk[LD], rv[LD];
-  int tile = w;
-  if (tile < ntiles) att_issue_loads<HD>(rk, rv, Kg, Vg, key0 + tile * ATT_TILE, n_keys, lane);
   for (; tile < ntiles; tile += ATT_WAVES) {
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // earlier LDS reads of this wavefront are done
+    const bool more = tile + ATT_WAVES < ntiles;
+    // ---- S^T = K Q^T
+    f32x16 s;
 #pragma unroll
-    for (int i = 0; i < LD; ++i) {
-      int u = i * 64 + lane, key = u / (HD / 8), b = (u % (HD / 8)) * 16;
-      *(v4u *)(Ks + key * L::ROW + b) = rk[i];
-      *(v4u *)(Vs + key * L::ROW + b) = rv[i];
-    }
-    if (tile + ATT_WAVES < ntiles) att_issue_loads<HD>(rk, rv, Kg, Vg, key0 + (tile + ATT_WAVES) * ATT_TILE, n_keys, lane);
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    // ---- S = Q K^T
-    f32x16 sacc;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      v4u kb = *(const v4u *)(Ks + col * L::ROW + (ks * 16 + half * 8) * 2);
-      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[ks], __builtin_bit_cast(bf16x8, kb), sacc, 0, 0, 0);
+      v4u qb = v4u{0u, 0u, 0u, 0u};
+      if (col < 8) qb = qs[(ks * 2 + half) * 8 + col];
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, rk[ks]), __builtin_bit_cast(bf16x8, qb), s, 0, 0, 0);
     }
-    // ---- online softmax over this tile's 32 keys (rows 4*half + i, key = col)
-    bool kvalid = key0 + tile * ATT_TILE + col < key1;
-    float p[4];
+    // the MFMAs above read rk when they issue; the loads below write rk when the data arrives, after them
+    if (more) att_issue_k<HD>(rk, head, tile0 + tile + ATT_WAVES, lane);
+    // ---- online softmax for head `col` over the tile's keys (register 4g+i: key 8g + 4*half + i)
+    const int kbase = key0 + tile * ATT_TILE + 4 * half;
+    float tm = -INFINITY;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      float sv = kvalid ? sacc[i] * scale : -INFINITY;
-      float tm = sv;
+    for (int g = 0; g < 4; ++g)
 #pragma unroll
-      for (int x = 16; x > 0; x >>= 1) tm = fmaxf(tm, __shfl_xor(tm, x, 64));
-      float mn = fmaxf(m_run[i], tm);
-      float alpha = __expf(m_run[i] - mn);
-      p[i] = __expf(sv - mn);
-      l_run[i] = l_run[i] * alpha + p[i];
-      m_run[i] = mn;
-#pragma unroll
-      for (int e = 0; e < NE; ++e) o[e][i] *= alpha;
-    }
-    // ---- P (bf16) through LDS into A-operand layout
-    {
-      int r0 = half * 4;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) *(uint16_t *)(Ps + (r0 + i) * L::PROW + col * 2) = f32_to_bf16_bits(p[i]);
-    }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-    for (int k2 = 0; k2 < 2; ++k2) {
-      v4u pa = v4u{0u, 0u, 0u, 0u};
-      if (col < 8) pa = *(const v4u *)(Ps + col * L::PROW + (k2 * 16 + half * 8) * 2);
-      bf16x8 pA = __builtin_bit_cast(bf16x8, pa);
-      if (HD == 128) {
-        v2u vr[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) vr[j] = *(const v2u *)(Vs + (k2 * 16 + half * 8 + j) * L::ROW + col * 8);
-#pragma unroll
-        for (int e = 0; e < NE; ++e) {
-          uint32_t d[4];
-#pragma unroll
-          for (int jj = 0; jj < 4; ++jj) {
-            uint32_t a = (e < 2) ? vr[2 * jj].x : vr[2 * jj].y, b = (e < 2) ? vr[2 * jj + 1].x : vr[2 * jj + 1].y;
-            d[jj] = (e & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
-          }
-          v4u vb = v4u{d[0], d[1], d[2], d[3]};
-          o[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pA, __builtin_bit_cast(bf16x8, vb), o[e], 0, 0, 0);
-        }
-      } else {  // HD == 64: two dims per column
-        uint32_t vr[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) vr[j] = *(const uint32_t *)(Vs + (k2 * 16 + half * 8 + j) * L::ROW + col * 4);
-#pragma unroll
-        for (int e = 0; e < NE; ++e) {
-          uint32_t d[4];
-#pragma unroll
-          for (int jj = 0; jj < 4; ++jj) {
-            uint32_t a = vr[2 * jj], b = vr[2 * jj + 1];
-            d[jj] = (e & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
-          }
-          v4u vb = v4u{d[0], d[1], d[2], d[3]};
-          o[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pA, __builtin_bit_cast(bf16x8, vb), o[e], 0, 0, 0);
-        }
+      for (int i = 0; i < 4; ++i) {
+        float sv = (kbase + 8 * g + i < key1) ? s[4 * g + i] * scale : -INFINITY;
+        s[4 * g + i] = sv;
+        tm = fmaxf(tm, sv);
       }
+    tm = fmaxf(tm, __shfl_xor(tm, 32, 64));
+    const float mn = fmaxf(m_run, tm);
+    const float alpha = __expf(m_run - mn);
+    m_run = mn;
+    float ls = 0.f;
+    uint32_t pk[8];   // bf16 pairs: pk[2g + i/2] = keys 8g + 4*half + {i, i+1}
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+      for (int i = 0; i < 4; i += 2) {
+        float p0 = __expf(s[4 * g + i] - mn), p1 = __expf(s[4 * g + i + 1] - mn);
+        ls += p0 + p1;
+        pk[2 * g + (i >> 1)] = (uint32_t)f32_to_bf16_bits(p0) | ((uint32_t)f32_to_bf16_bits(p1) << 16);
+      }
+    l_run = l_run * alpha + ls;
+    if (__any(alpha != 1.0f)) {
+#pragma unroll
+      for (int e = 0; e < NE; ++e)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[e][r] *= alpha;
     }
+    // ---- O^T += V^T P^T.  The B operand of k-step ks2 wants keys 16*ks2 + 8*half + 0..7 of head `col`: the first
+    // four sit in the half-0 lane of the column (its registers of group g = 2*ks2 + half), the last four in the half-1 lane.
+#pragma unroll
+    for (int ks2 = 0; ks2 < 2; ++ks2) {
+      const int ga = 2 * ks2, gb = 2 * ks2 + 1;   // half-0 lanes keep group ga and send gb; half-1 lanes the reverse
+      uint32_t s0 = half ? pk[2 * ga] : pk[2 * gb], s1 = half ? pk[2 * ga + 1] : pk[2 * gb + 1];
+      uint32_t r0 = __shfl_xor(s0, 32, 64), r1 = __shfl_xor(s1, 32, 64);
+      uint32_t m0 = half ? pk[2 * gb] : pk[2 * ga], m1 = half ? pk[2 * gb + 1] : pk[2 * ga + 1];
+      v4u pb = half ? v4u{r0, r1, m0, m1} : v4u{m0, m1, r0, r1};
+#pragma unroll
+      for (int e = 0; e < NE; ++e)
+        o[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, rv[ks2 * NE + e]), __builtin_bit_cast(bf16x8, pb), o[e], 0, 0, 0);
+    }
+    if (more) att_issue_v<HD>(rv, head, tile0 + tile + ATT_WAVES, lane);
   }
-  // ---- fold the wavefront's lanes (l), then the four wavefronts, in wavefront order
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int x = 16; x > 0; x >>= 1) l_run[i] += __shfl_xor(l_run[i], x, 64);
-  __syncthreads();   // every wavefront is past its last LDS tile; the staging area is reused for the merge
+  // ---- the two lanes of a column add their sums; then the four wavefronts are folded in wavefront order
+  l_run += __shfl_xor(l_run, 32, 64);
   {
     float *mo = (float *)(lds + w * L::MERGE_PER_WAVE);      // [8][HD] then m[8], l[8]
+    if (col < grp) {
 #pragma unroll
-    for (int e = 0; e < NE; ++e)
+      for (int e = 0; e < NE; ++e)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) mo[(half * 4 + i) * HD + NE * col + e] = o[e][i];
-    if (col == 0)
+        for (int g = 0; g < 4; ++g)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) { mo[8 * HD + half * 4 + i] = m_run[i]; mo[8 * HD + 8 + half * 4 + i] = l_run[i]; }
+          for (int i = 0; i < 4; ++i) mo[col * HD + 32 * e + 8 * g + 4 * half + i] = o[e][4 * g + i];
+      if (half == 0) { mo[8 * HD + col] = m_run; mo[8 * HD + 8 + col] = l_run; }
+    }
   }
   __syncthreads();
   for (int idx = threadIdx.x; idx < grp * HD; idx += 256) {
@@ -251,7 +225,7 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
 #pragma unroll
     for (int ww = 0; ww < ATT_WAVES; ++ww) {
       const float *mo = (const float *)(lds + ww * L::MERGE_PER_WAVE);
-      float f = __expf(mw[ww] - M);
+      float f = __expf(mw[ww] - M);   // a wavefront that saw no tile has max -inf and weight 0
       acc += mo[r * HD + dd] * f;
       lsum += mo[8 * HD + 8 + r] * f;
     }
@@ -310,14 +284,6 @@ static void attention_launch(void *Xp_out, const void *q_bf16, RowState rows, Kv
 
 void fast_attention(void *Xp_out, const void *q_bf16, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq, int Hkv,
                     int nsplit, float *part_o, float *part_ml, hipStream_t st) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute((const void *)attn_splitk_kernel<128, true>, hipFuncAttributeMaxDynamicSharedMemorySize, AttLds<128>::TOTAL);
-    (void)hipFuncSetAttribute((const void *)attn_splitk_kernel<128, false>, hipFuncAttributeMaxDynamicSharedMemorySize, AttLds<128>::TOTAL);
-    (void)hipFuncSetAttribute((const void *)attn_splitk_kernel<64, true>, hipFuncAttributeMaxDynamicSharedMemorySize, AttLds<64>::TOTAL);
-    (void)hipFuncSetAttribute((const void *)attn_splitk_kernel<64, false>, hipFuncAttributeMaxDynamicSharedMemorySize, AttLds<64>::TOTAL);
-    attr_set = true;
-  }
   if (kv.head_dim == 128) attention_launch<128>(Xp_out, q_bf16, rows, kv, layer, M, Mp, Hq, Hkv, nsplit, part_o, part_ml, st);
   else attention_launch<64>(Xp_out, q_bf16, rows, kv, layer, M, Mp, Hq, Hkv, nsplit, part_o, part_ml, st);
 }

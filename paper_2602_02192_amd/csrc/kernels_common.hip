@@ -63,13 +63,16 @@ void launch_bookkeeping(int N, int max_new, int32_t *d_step, const int32_t *samp
                      limit, eos, version, prompt_len, gen_len, rows, out_tok, out_lp, out_ver, n_active);
 }
 
-// Copy the prompt part of slot p*G into slots p*G+1 .. p*G+G-1.  grid = (chunks, L*2*Hkv, P*(G-1)).
+// Copy the prompt part of slot p*G into slots p*G+1 .. p*G+G-1.  grid = (chunks, regions per slot, P*(G-1)).
+// Plain form: a region is one head's K or V plane and the prompt is its first prompt_len rows.  Tiled form: a region
+// is one head's K and V tiles and the prompt is its first ceil(prompt_len/32) tiles.
 __global__ void kv_replicate_kernel(KvGeom kv, const int32_t *prompt_len, int G) {
   int p = blockIdx.z / (G - 1), g = blockIdx.z % (G - 1) + 1;
-  int64_t bytes = (int64_t)prompt_len[p] * kv.head_dim * kv.elt_bytes;
-  int64_t head_bytes = kv.head_stride() * kv.elt_bytes;
-  const char *src = (const char *)kv.base + ((int64_t)p * G) * kv.slot_stride() * kv.elt_bytes + blockIdx.y * head_bytes;
-  char *dst = (char *)kv.base + ((int64_t)p * G + g) * kv.slot_stride() * kv.elt_bytes + blockIdx.y * head_bytes;
+  int64_t region_bytes = kv.head_stride() * kv.elt_bytes * (kv.tiled ? 2 : 1);
+  int64_t bytes = kv.tiled ? (int64_t)((prompt_len[p] + 31) / 32) * 64 * kv.head_dim * kv.elt_bytes
+                           : (int64_t)prompt_len[p] * kv.head_dim * kv.elt_bytes;
+  const char *src = (const char *)kv.base + ((int64_t)p * G) * kv.slot_stride() * kv.elt_bytes + blockIdx.y * region_bytes;
+  char *dst = (char *)kv.base + ((int64_t)p * G + g) * kv.slot_stride() * kv.elt_bytes + blockIdx.y * region_bytes;
   int64_t n16 = bytes / 16;  // head_dim * elt_bytes is a multiple of 16
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (int64_t)gridDim.x * blockDim.x)
     ((uint4 *)dst)[i] = ((const uint4 *)src)[i];
@@ -77,8 +80,8 @@ __global__ void kv_replicate_kernel(KvGeom kv, const int32_t *prompt_len, int G)
 
 void launch_kv_replicate(KvGeom kv, const int32_t *prompt_len, int P, int G, hipStream_t st) {
   if (G <= 1 || P <= 0) return;
-  hipLaunchKernelGGL(kv_replicate_kernel, dim3(8, kv.n_layers * 2 * kv.n_kv_heads, P * (G - 1)), dim3(256), 0, st, kv,
-                     prompt_len, G);
+  int regions = kv.n_layers * kv.n_kv_heads * (kv.tiled ? 1 : 2);
+  hipLaunchKernelGGL(kv_replicate_kernel, dim3(8, regions, P * (G - 1)), dim3(256), 0, st, kv, prompt_len, G);
 }
 
 __global__ void draw_bits_kernel(uint32_t *out, uint64_t seed, uint32_t n, uint32_t s, uint32_t i0, int count) {

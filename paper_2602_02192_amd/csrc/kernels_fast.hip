@@ -104,15 +104,16 @@ __global__ void qkv_post_kernel(const float *partials, int nsplit, int Np, int M
     float ra = a * cs.x - b * cs.y, rb = a * cs.y + b * cs.x;
     a = ra; b = rb;
   }
-  uint16_t *dst;
-  if (is_q) dst = q_out + ((int64_t)m * Hq + j) * hd;
-  else {
-    int kvh = is_k ? j - Hq : j - Hq - Hkv;
-    dst = (uint16_t *)kv.base + (int64_t)rows.slot[m] * kv.slot_stride() + (int64_t)layer * kv.layer_stride() +
-          (is_k ? 0 : kv.kv_stride()) + (int64_t)kvh * kv.head_stride() + (int64_t)rows.pos[m] * hd;
+  if (is_q) {
+    uint16_t *dst = q_out + ((int64_t)m * Hq + j) * hd;
+    dst[i] = f32_to_bf16_bits(a);
+    dst[i + half] = f32_to_bf16_bits(b);
+  } else {   // append to the tiled cache
+    int kvh = is_k ? j - Hq : j - Hq - Hkv, pos = rows.pos[m];
+    uint16_t *head = (uint16_t *)kv.base + kv.tiled_head_off(rows.slot[m], layer, kvh);
+    if (is_k) { head[kv.tiled_k_off(pos, i)] = f32_to_bf16_bits(a); head[kv.tiled_k_off(pos, i + half)] = f32_to_bf16_bits(b); }
+    else { head[kv.tiled_v_off(pos, i)] = f32_to_bf16_bits(a); head[kv.tiled_v_off(pos, i + half)] = f32_to_bf16_bits(b); }
   }
-  dst[i] = f32_to_bf16_bits(a);
-  dst[i + half] = f32_to_bf16_bits(b);
 }
 
 void fast_qkv_post(const float *partials, int nsplit, int Np, int Mp, void *q_bf16, const void *q_gain, const void *k_gain,
