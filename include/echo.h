@@ -84,6 +84,8 @@ typedef struct {
   double attn_ms, attn_bytes; /* decode attention: HIP-event time, K/V bytes it had to read */
   int64_t gemm_launches;
   double gemm_ms, gemm_bytes; /* weight-streaming GEMMs: HIP-event time, weight bytes read */
+  int32_t rollout_running;    /* 1 while echo_rollout is inside its loop on another thread (a snapshot installed
+                                 now is staged, not activated) */
 } echo_stats_t;
 
 /* Bytes of device memory a context of this shape needs (weights x slots, KV cache, activations);

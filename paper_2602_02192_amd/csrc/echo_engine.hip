@@ -824,6 +824,7 @@ int echo_stats(echo_ctx *c, echo_stats_t *out) {
   if (!c || !out) return ECHO_EINVAL;
   std::lock_guard<std::mutex> lk(c->mu);
   *out = c->st;
+  out->rollout_running = c->rollout_running ? 1 : 0;
   return ECHO_OK;
 }
 

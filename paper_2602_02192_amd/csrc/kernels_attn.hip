@@ -33,7 +33,7 @@ __global__ void attn_simple_kernel(uint16_t *Xp, const uint16_t *q_bf16, RowStat
   float scale = 1.0f / sqrtf((float)hd), mx = -INFINITY;
   for (int t = lane; t < n_keys; t += 64) {
     float s = 0.f;
-    for (int i = 0; i < hd; ++i) s += bf16_bits_to_f32(q[i]) * bf16_bits_to_f32(head[kv.tiled_k_off(t, i)]);
+    for (int i = 0; i < hd; ++i) s += h16_bits_to_f32(q[i]) * h16_bits_to_f32(head[kv.tiled_k_off(t, i)]);
     s *= scale;
     sc[t] = s;
     mx = fmaxf(mx, s);
@@ -45,8 +45,8 @@ __global__ void attn_simple_kernel(uint16_t *Xp, const uint16_t *q_bf16, RowStat
   __syncthreads();
   for (int i = lane; i < hd; i += 64) {
     float acc = 0.f;
-    for (int t = 0; t < n_keys; ++t) acc += sc[t] * bf16_bits_to_f32(head[kv.tiled_v_off(t, i)]);
-    Xp[k8_index(m, j * hd + i, Mp)] = f32_to_bf16_bits(acc / den);
+    for (int t = 0; t < n_keys; ++t) acc += sc[t] * h16_bits_to_f32(head[kv.tiled_v_off(t, i)]);
+    Xp[k8_index(m, j * hd + i, Mp)] = f32_to_h16_bits(acc / den);
   }
 }
 
@@ -57,7 +57,7 @@ void fast_attention_simple(void *Xp_out, const void *q_bf16, RowState rows, KvGe
 }
 
 // ---- split-K MFMA kernel -----------------------------------------------------------------------------
-// MFMA roles (v_mfma_f32_32x32x16_bf16; lane l: half = l/32, col = l%32).
+// MFMA roles (v_mfma_f32_32x32x16_f16; lane l: half = l/32, col = l%32).
 // S^T = K Q^T: A = K tile (row = key of the tile, k = 16 head dims), B = Q^T (column = query head of the group, zero
 //   beyond the group); accumulator register 4g+i of a lane holds the score of key 8g + 4*half + i for head `col`.
 // O^T = V^T P^T: A = V tile (row = head dim 32e + row, k = 16 keys), B = P^T (column = query head); register 4g+i
@@ -150,7 +150,7 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
     for (int ks = 0; ks < KS; ++ks) {
       v4u qb = v4u{0u, 0u, 0u, 0u};
       if (col < 8) qb = qs[(ks * 2 + half) * 8 + col];
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, rk[ks]), __builtin_bit_cast(bf16x8, qb), s, 0, 0, 0);
+      s = mfma_h16(__builtin_bit_cast(h16x8, rk[ks]), __builtin_bit_cast(h16x8, qb), s);
     }
     // the MFMAs above read rk when they issue; the loads below write rk when the data arrives, after them
     if (more) att_issue_k<HD>(rk, head, tile0 + tile + ATT_WAVES, lane);
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
       for (int i = 0; i < 4; i += 2) {
         float p0 = __expf(s[4 * g + i] - mn), p1 = __expf(s[4 * g + i + 1] - mn);
         ls += p0 + p1;
-        pk[2 * g + (i >> 1)] = (uint32_t)f32_to_bf16_bits(p0) | ((uint32_t)f32_to_bf16_bits(p1) << 16);
+        pk[2 * g + (i >> 1)] = (uint32_t)f32_to_h16_bits(p0) | ((uint32_t)f32_to_h16_bits(p1) << 16);
       }
     l_run = l_run * alpha + ls;
     if (__any(alpha != 1.0f)) {
@@ -197,7 +197,7 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
       v4u pb = half ? v4u{r0, r1, m0, m1} : v4u{m0, m1, r0, r1};
 #pragma unroll
       for (int e = 0; e < NE; ++e)
-        o[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, rv[ks2 * NE + e]), __builtin_bit_cast(bf16x8, pb), o[e], 0, 0, 0);
+        o[e] = mfma_h16(__builtin_bit_cast(h16x8, rv[ks2 * NE + e]), __builtin_bit_cast(h16x8, pb), o[e]);
     }
     if (more) att_issue_v<HD>(rv, head, tile0 + tile + ATT_WAVES, lane);
   }
@@ -230,7 +230,7 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
       lsum += mo[8 * HD + 8 + r] * f;
     }
     if (DIRECT) {
-      Xp[k8_index(m, (kvh * grp + r) * HD + dd, Mp)] = f32_to_bf16_bits(acc / lsum);
+      Xp[k8_index(m, (kvh * grp + r) * HD + dd, Mp)] = f32_to_h16_bits(acc / lsum);
     } else {
       int64_t pi = ((int64_t)m * Hq + kvh * grp + r) * nsplit + c;
       part_o[pi * HD + dd] = acc;
@@ -256,7 +256,7 @@ __global__ void attn_combine_kernel(uint16_t *Xp, const float *__restrict__ part
     acc += part_o[(pi + c) * HD + dd] * f;
     lsum += part_ml[(pi + c) * 2 + 1] * f;
   }
-  Xp[xi] = f32_to_bf16_bits(acc / lsum);
+  Xp[xi] = f32_to_h16_bits(acc / lsum);
 }
 
 // Splits per row: enough workgroups (rows x KV heads x splits) to put two on every compute unit, never more

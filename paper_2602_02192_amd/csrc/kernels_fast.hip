@@ -56,8 +56,8 @@ __global__ __launch_bounds__(RN_THREADS) void resid_norm_kernel(float *h, const 
     float g0 = __uint_as_float(g.x << 16), g1 = __uint_as_float(g.x & 0xffff0000u);
     float g2 = __uint_as_float(g.y << 16), g3 = __uint_as_float(g.y & 0xffff0000u);
     uint2 o;
-    o.x = (uint32_t)f32_to_bf16_bits(v[c][0] * inv * g0) | ((uint32_t)f32_to_bf16_bits(v[c][1] * inv * g1) << 16);
-    o.y = (uint32_t)f32_to_bf16_bits(v[c][2] * inv * g2) | ((uint32_t)f32_to_bf16_bits(v[c][3] * inv * g3) << 16);
+    o.x = (uint32_t)f32_to_h16_bits(v[c][0] * inv * g0) | ((uint32_t)f32_to_h16_bits(v[c][1] * inv * g1) << 16);
+    o.y = (uint32_t)f32_to_h16_bits(v[c][2] * inv * g2) | ((uint32_t)f32_to_h16_bits(v[c][3] * inv * g3) << 16);
     *(uint2 *)(Xp + ((int64_t)(n >> 3) * Mp + m) * 8 + (n & 7)) = o;
   }
 }
@@ -106,13 +106,13 @@ __global__ void qkv_post_kernel(const float *partials, int nsplit, int Np, int M
   }
   if (is_q) {
     uint16_t *dst = q_out + ((int64_t)m * Hq + j) * hd;
-    dst[i] = f32_to_bf16_bits(a);
-    dst[i + half] = f32_to_bf16_bits(b);
+    dst[i] = f32_to_h16_bits(a);
+    dst[i + half] = f32_to_h16_bits(b);
   } else {   // append to the tiled cache
     int kvh = is_k ? j - Hq : j - Hq - Hkv, pos = rows.pos[m];
     uint16_t *head = (uint16_t *)kv.base + kv.tiled_head_off(rows.slot[m], layer, kvh);
-    if (is_k) { head[kv.tiled_k_off(pos, i)] = f32_to_bf16_bits(a); head[kv.tiled_k_off(pos, i + half)] = f32_to_bf16_bits(b); }
-    else { head[kv.tiled_v_off(pos, i)] = f32_to_bf16_bits(a); head[kv.tiled_v_off(pos, i + half)] = f32_to_bf16_bits(b); }
+    if (is_k) { head[kv.tiled_k_off(pos, i)] = f32_to_h16_bits(a); head[kv.tiled_k_off(pos, i + half)] = f32_to_h16_bits(b); }
+    else { head[kv.tiled_v_off(pos, i)] = f32_to_h16_bits(a); head[kv.tiled_v_off(pos, i + half)] = f32_to_h16_bits(b); }
   }
 }
 

@@ -2,7 +2,7 @@
 // wavefronts of a workgroup and over the grid) with its epilogues, and the lm_head GEMM whose epilogue
 // is the sampler (temperature, Gumbel-max, running log-sum-exp), so logits never reach HBM.
 //
-// Operand roles of v_mfma_f32_32x32x16_bf16 here: A = 32 weight rows x 16 k, B = 16 k x 32 batch rows.
+// Operand roles of v_mfma_f32_32x32x16_f16 here: A = 32 weight rows x 16 k, B = 16 k x 32 batch rows.
 // Lane l supplies A[row l%32][k 8*(l/32) .. +8] and B[k 8*(l/32) .. +8][col l%32]; it receives
 // D[row 8*g + 4*(l/32) + i][col l%32] in accumulator register 4*g + i (g, i in 0..3).
 #include "echo_device.h"
@@ -30,7 +30,13 @@ __global__ void pack_weight_kernel(uint4 *dst, const uint4 *src, int64_t dst_row
   int64_t i = idx / K8;
   int k8 = (int)(idx % K8);
   int64_t r = dst_row0 + i * dst_row_stride;
-  dst[w_block_base((int)(r >> 5), Kp8 * 8) + (k8 >> 1) * w_kstep_stride(Np) + (k8 & 1) * 32 + (r & 31)] = src[idx];
+  uint4 v = src[idx];
+  uint32_t w[4] = {v.x, v.y, v.z, v.w}, o[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q)   // bf16 pair -> half pair, scaled by W_SCALE (exact)
+    o[q] = (uint32_t)f32_to_h16_bits(__uint_as_float(w[q] << 16) * W_SCALE) |
+           ((uint32_t)f32_to_h16_bits(__uint_as_float(w[q] & 0xffff0000u) * W_SCALE) << 16);
+  dst[w_block_base((int)(r >> 5), Kp8 * 8) + (k8 >> 1) * w_kstep_stride(Np) + (k8 & 1) * 32 + (r & 31)] = make_uint4(o[0], o[1], o[2], o[3]);
 }
 
 void fast_pack_weight(void *dst, const void *src, int64_t dst_row0, int dst_row_stride, int64_t n_rows, int K, int Kp,
@@ -47,18 +53,18 @@ void fast_pack_weight(void *dst, const void *src, int64_t dst_row0, int dst_row_
 // byte falls with NBW.  Loads run two groups of U k-steps ahead of the MFMAs (register double buffer).
 template <int MB, int NBW, int U>
 struct KGroup {
-  bf16x8 a[U][NBW];
-  bf16x8 b[U][MB];
+  h16x8 a[U][NBW];
+  h16x8 b[U][MB];
 };
 
 template <int MB, int NBW, int U>
-__device__ __forceinline__ void load_group(KGroup<MB, NBW, U> &g, const bf16x8 *__restrict__ a_ptr, int64_t a_blk,
-                                           const bf16x8 *__restrict__ b_ptr, int Mp, int ks, int64_t a_step) {
+__device__ __forceinline__ void load_group(KGroup<MB, NBW, U> &g, const h16x8 *__restrict__ a_ptr, int64_t a_blk,
+                                           const h16x8 *__restrict__ b_ptr, int Mp, int ks, int64_t a_step) {
 #pragma unroll
   for (int u = 0; u < U; ++u) {
 #pragma unroll
     for (int n = 0; n < NBW; ++n) g.a[u][n] = __builtin_nontemporal_load(a_ptr + n * a_blk + (int64_t)(ks + u) * a_step);
-    const bf16x8 *bp = b_ptr + (int64_t)(ks + u) * 2 * Mp;
+    const h16x8 *bp = b_ptr + (int64_t)(ks + u) * 2 * Mp;
 #pragma unroll
     for (int j = 0; j < MB; ++j) g.b[u][j] = bp[j * 32];
   }
@@ -72,17 +78,17 @@ __device__ __forceinline__ void mma_group(f32x16 (&acc)[NBW][MB], const KGroup<M
     for (int n = 0; n < NBW; ++n)
 #pragma unroll
       for (int j = 0; j < MB; ++j)
-        acc[n][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g.a[u][n], g.b[u][j], acc[n][j], 0, 0, 0);
+        acc[n][j] = mfma_h16(g.a[u][n], g.b[u][j], acc[n][j]);
 }
 
 // Wnb: first weight block of the wavefront; a_blk: distance between consecutive weight blocks (16-byte units).
 template <int MB, int NBW>
-__device__ __forceinline__ void mma_range(f32x16 (&acc)[NBW][MB], const bf16x8 *__restrict__ Wnb, int64_t a_blk,
-                                          const bf16x8 *__restrict__ Xp, int Mp, int ks0, int ks1, int lane,
+__device__ __forceinline__ void mma_range(f32x16 (&acc)[NBW][MB], const h16x8 *__restrict__ Wnb, int64_t a_blk,
+                                          const h16x8 *__restrict__ Xp, int Mp, int ks0, int ks1, int lane,
                                           int64_t a_step) {
   constexpr int U0 = 12 / (MB + NBW), U = U0 < 1 ? 1 : (U0 > 4 ? 4 : U0);
-  const bf16x8 *a_ptr = Wnb + (lane >> 5) * 32 + (lane & 31);
-  const bf16x8 *b_ptr = Xp + (int64_t)(lane >> 5) * Mp + (lane & 31);
+  const h16x8 *a_ptr = Wnb + (lane >> 5) * 32 + (lane & 31);
+  const h16x8 *b_ptr = Xp + (int64_t)(lane >> 5) * Mp + (lane & 31);
   int ng = (ks1 - ks0) / U;
   KGroup<MB, NBW, U> g0, g1;
   if (ng > 0) load_group<MB, NBW, U>(g0, a_ptr, a_blk, b_ptr, Mp, ks0, a_step);
@@ -105,7 +111,7 @@ __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + expf(-x));
 // Wavefront w = wk*waves_n + wn: the waves_n wavefronts of one wk share a k-range (their activation reads hit
 // L1 together) and own different weight blocks; the waves_k k-ranges of a grid split are summed in LDS in wk order.
 template <int MB, int NBW, int EPI>
-__global__ __launch_bounds__(512) void gemm_kernel(void *out, const bf16x8 *__restrict__ Xp, const bf16x8 *__restrict__ Wp,
+__global__ __launch_bounds__(512) void gemm_kernel(void *out, const h16x8 *__restrict__ Xp, const h16x8 *__restrict__ Wp,
                                                    int Mp, int Np, int Kp, int ksteps_per_split, int waves_n) {
   extern __shared__ float red[];
   const int waves = blockDim.x >> 6, w = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -166,7 +172,7 @@ __global__ __launch_bounds__(512) void gemm_kernel(void *out, const bf16x8 *__re
         for (int g = 0; g < 4; ++g) {
           int n4 = nb * 8 + half + 2 * g;
           f32x4 v = {acc[n][j][4 * g], acc[n][j][4 * g + 1], acc[n][j][4 * g + 2], acc[n][j][4 * g + 3]};
-          P[((int64_t)split * Mp + m) * (Np >> 2) + n4] = v;
+          P[((int64_t)split * Mp + m) * (Np >> 2) + n4] = v * W_UNSCALE;
         }
       }
     } else {  // EPI_SWIGLU: rows alternate gate_f, up_f
@@ -177,9 +183,9 @@ __global__ __launch_bounds__(512) void gemm_kernel(void *out, const bf16x8 *__re
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           int f = nb * 16 + half * 2 + 4 * g;
-          float v0 = silu_f(acc[n][j][4 * g]) * acc[n][j][4 * g + 1];
-          float v1 = silu_f(acc[n][j][4 * g + 2]) * acc[n][j][4 * g + 3];
-          uint32_t pk = (uint32_t)f32_to_bf16_bits(v0) | ((uint32_t)f32_to_bf16_bits(v1) << 16);
+          float v0 = silu_f(acc[n][j][4 * g] * W_UNSCALE) * (acc[n][j][4 * g + 1] * W_UNSCALE);
+          float v1 = silu_f(acc[n][j][4 * g + 2] * W_UNSCALE) * (acc[n][j][4 * g + 3] * W_UNSCALE);
+          uint32_t pk = (uint32_t)f32_to_h16_bits(v0) | ((uint32_t)f32_to_h16_bits(v1) << 16);
           O[(((int64_t)(f >> 3) * Mp + m) * 8 + (f & 7)) >> 1] = pk;
         }
       }
@@ -208,7 +214,7 @@ template <int MB, int WN> struct GemmLds {
 };
 
 template <int MB, int WN, int NSTAGE, int EPI>
-__global__ __launch_bounds__(WN * 64) void gemm_lds_kernel(void *out, const u32x4v *__restrict__ Xp, const bf16x8 *__restrict__ Wp,
+__global__ __launch_bounds__(WN * 64) void gemm_lds_kernel(void *out, const u32x4v *__restrict__ Xp, const h16x8 *__restrict__ Wp,
                                                            int Mp, int Np, int Kp, int chunks_per_split) {
   extern __shared__ __attribute__((aligned(16))) char lds_raw[];
   using L = GemmLds<MB, WN>;
@@ -219,14 +225,14 @@ __global__ __launch_bounds__(WN * 64) void gemm_lds_kernel(void *out, const u32x
   const int nb_own = blockIdx.x * WN + w, nb = min(nb_own, nblocks - 1);   // wavefronts past the end re-read the last block
   const int c_begin = blockIdx.y * chunks_per_split, nchunks = min(chunks_per_split, total_chunks - c_begin);
   const int mrow0 = blockIdx.z * ROWS;
-  const bf16x8 *a_ptr = Wp + w_block_base(nb, Kp) + (int64_t)c_begin * KC * w_kstep_stride(Np) + (lane >> 5) * 32 + (lane & 31);
+  const h16x8 *a_ptr = Wp + w_block_base(nb, Kp) + (int64_t)c_begin * KC * w_kstep_stride(Np) + (lane >> 5) * 32 + (lane & 31);
   const int64_t a_step = w_kstep_stride(Np);
   f32x16 acc[MB];
 #pragma unroll
   for (int j = 0; j < MB; ++j)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
-  bf16x8 a[NSTAGE][KC];
+  h16x8 a[NSTAGE][KC];
   u32x4v xr[NSTAGE][XL];
   auto load_a = [&](int st, int c) {
 #pragma unroll
@@ -254,7 +260,7 @@ __global__ __launch_bounds__(WN * 64) void gemm_lds_kernel(void *out, const u32x
     for (int u = 0; u < KC; ++u)
 #pragma unroll
       for (int j = 0; j < MB; ++j)
-        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[st][u], __builtin_bit_cast(bf16x8, bp[u * 2 * ROWS + j * 32]), acc[j], 0, 0, 0);
+        acc[j] = mfma_h16(a[st][u], __builtin_bit_cast(h16x8, bp[u * 2 * ROWS + j * 32]), acc[j]);
   };
   if (nchunks > 0) {
 #pragma unroll
@@ -284,7 +290,7 @@ __global__ __launch_bounds__(WN * 64) void gemm_lds_kernel(void *out, const u32x
 #pragma unroll
       for (int g = 0; g < 4; ++g)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) tile[(j * 32 + col) * L::TILE_STRIDE + 8 * g + 4 * half + i] = acc[j][4 * g + i];
+        for (int i = 0; i < 4; ++i) tile[(j * 32 + col) * L::TILE_STRIDE + 8 * g + 4 * half + i] = acc[j][4 * g + i] * W_UNSCALE;
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the tile is private to this wavefront
     if (nb_own >= nblocks) return;
     float *P = (float *)out + ((int64_t)blockIdx.y * Mp + mrow0) * Np + nb * 32;
@@ -303,9 +309,9 @@ __global__ __launch_bounds__(WN * 64) void gemm_lds_kernel(void *out, const u32x
       uint32_t pk[4];
 #pragma unroll
       for (int g = 0; g < 4; ++g) {   // features 4g + 2*half + {0,1} of the block
-        float v0 = silu_f(acc[j][4 * g]) * acc[j][4 * g + 1];
-        float v1 = silu_f(acc[j][4 * g + 2]) * acc[j][4 * g + 3];
-        pk[g] = (uint32_t)f32_to_bf16_bits(v0) | ((uint32_t)f32_to_bf16_bits(v1) << 16);
+        float v0 = silu_f(acc[j][4 * g] * W_UNSCALE) * (acc[j][4 * g + 1] * W_UNSCALE);
+        float v1 = silu_f(acc[j][4 * g + 2] * W_UNSCALE) * (acc[j][4 * g + 3] * W_UNSCALE);
+        pk[g] = (uint32_t)f32_to_h16_bits(v0) | ((uint32_t)f32_to_h16_bits(v1) << 16);
       }
       // lane (half 0) assembles K8 group 0 (features 0..7), its partner (half 1) group 1 (features 8..15)
       uint32_t give0 = half ? pk[0] : pk[2], give1 = half ? pk[1] : pk[3];
@@ -364,7 +370,7 @@ static void gemm_lds_launch(void *out, const void *Xp, const void *Wp, int Mp, i
   }
   int nblocks = Np / 32, total_chunks = (Kp / 16) / L::KC, cps = (total_chunks + nsplit - 1) / nsplit;
   dim3 grid((nblocks + WN - 1) / WN, nsplit, Mp / (32 * MB)), block(64 * WN);
-  hipLaunchKernelGGL((gemm_lds_kernel<MB, WN, NSTAGE, EPI>), grid, block, L::BYTES, st, out, (const u32x4v *)Xp, (const bf16x8 *)Wp, Mp,
+  hipLaunchKernelGGL((gemm_lds_kernel<MB, WN, NSTAGE, EPI>), grid, block, L::BYTES, st, out, (const u32x4v *)Xp, (const h16x8 *)Wp, Mp,
                      Np, Kp, cps);
 }
 
@@ -390,7 +396,7 @@ static void gemm_dispatch(void *out, const void *Xp, const void *Wp, int Mp, int
   int per_wg = g.nbw * g.waves_n, nblocks = Np / 32;
   dim3 grid((nblocks + per_wg - 1) / per_wg, g.nsplit, mbt / MB), block(64 * g.waves_n * g.waves_k);
   size_t lds = (size_t)(g.waves_k - 1) * g.waves_n * g.nbw * MB * 16 * 64 * sizeof(float);
-  const bf16x8 *X = (const bf16x8 *)Xp, *W = (const bf16x8 *)Wp;
+  const h16x8 *X = (const h16x8 *)Xp, *W = (const h16x8 *)Wp;
 #define GEMM_LAUNCH(MBV, NBWV) \
   hipLaunchKernelGGL((gemm_kernel<MBV, NBWV, EPI>), grid, block, lds, st, out, X, W, Mp, Np, Kp, kps, g.waves_n)
   if (g.nbw == 2) {
@@ -422,7 +428,7 @@ void fast_gemm(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp
 constexpr int LM_NBW = 2;      // weight blocks per wavefront
 
 template <int MB, bool LOGITS>
-__global__ __launch_bounds__(256) void lmhead_kernel(const bf16x8 *__restrict__ Xp, const bf16x8 *__restrict__ Wp, int Mp,
+__global__ __launch_bounds__(256) void lmhead_kernel(const h16x8 *__restrict__ Xp, const h16x8 *__restrict__ Wp, int Mp,
                                                      int Np, int Kp, int V, float temperature, uint64_t seed,
                                                      const int32_t *d_step, const int32_t *target, float *target_z,
                                                      float *part, int n_wg, float *logits, int64_t ld) {
@@ -458,7 +464,7 @@ __global__ __launch_bounds__(256) void lmhead_kernel(const bf16x8 *__restrict__ 
         if (v0 >= V) continue;
         if (LOGITS) {
           f32x4 o = {acc[j][4 * g], acc[j][4 * g + 1], acc[j][4 * g + 2], acc[j][4 * g + 3]};
-          *(f32x4 *)(logits + (int64_t)m * ld + v0) = o;
+          *(f32x4 *)(logits + (int64_t)m * ld + v0) = o * W_UNSCALE;
         } else {
           u32x4 r = draw4(seed, (uint32_t)m, step, (uint32_t)(v0 >> 2));
           uint32_t bits[4] = {r.x, r.y, r.z, r.w};
@@ -466,7 +472,7 @@ __global__ __launch_bounds__(256) void lmhead_kernel(const bf16x8 *__restrict__ 
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             if (v0 + i >= V) break;
-            float z = acc[j][4 * g + i] / temperature;
+            float z = acc[j][4 * g + i] * W_UNSCALE / temperature;
             sample_acc_add(sa[j], z, z + gumbel_from_bits(bits[i]), v0 + i);
             if (v0 + i == tgt) target_z[m] = z;
           }
@@ -531,7 +537,7 @@ static void lmhead_dispatch(const void *Xp, const void *Wp, int Mp, int Np, int 
                             int64_t ld, hipStream_t st) {
   int mbt = Mp / 32, MB = mbt >= 8 ? 8 : mbt, n_wg = lm_wgs(Np);
   dim3 grid(n_wg, 1, mbt / MB), block(256);
-  const bf16x8 *X = (const bf16x8 *)Xp, *W = (const bf16x8 *)Wp;
+  const h16x8 *X = (const h16x8 *)Xp, *W = (const h16x8 *)Wp;
 #define LM_LAUNCH(MBV)                                                                                               \
   hipLaunchKernelGGL((lmhead_kernel<MBV, LOGITS>), grid, block, 0, st, X, W, Mp, Np, Kp, V, temperature, seed, d_step, \
                      target, target_z, part, n_wg, logits, ld)

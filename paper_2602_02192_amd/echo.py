@@ -44,7 +44,8 @@ class Stats(C.Structure):
                 ("decode_steps", C.c_int32), ("prefill_ms", C.c_float), ("decode_ms", C.c_float),
                 ("total_ms", C.c_float), ("swap_wait_ms", C.c_float),
                 ("attn_launches", C.c_int64), ("attn_ms", C.c_double), ("attn_bytes", C.c_double),
-                ("gemm_launches", C.c_int64), ("gemm_ms", C.c_double), ("gemm_bytes", C.c_double)]
+                ("gemm_launches", C.c_int64), ("gemm_ms", C.c_double), ("gemm_bytes", C.c_double),
+                ("rollout_running", C.c_int32)]
 
 
 EXPORTS = ["echo_arena_bytes", "echo_blob_bytes", "echo_init", "echo_load_policy", "echo_rollout",

@@ -1,0 +1,252 @@
+"""GPU parity tests shaped like the larger workloads: wide batches (128 and 256 sequences) with ragged stop
+lengths, a snapshot swap inside a rollout, teacher-forced scoring, edge cases, and the 4B-class shape in the
+benchmark's launch configuration (sampled sequences against the oracle, the rest through properties)."""
+import threading
+import time
+
+import numpy as np
+import pytest
+
+from oracle import oracle
+from paper_2602_02192_amd import synth
+
+from gpu_util import (BF16_ARGMAX_RATE, BF16_LOGIT_TOL, BF16_LOGPROB_TOL, F32_LOGIT_TOL, F32_LOGPROB_TOL,
+                      argmax_agreement, check_tokens_fp32_sampler, make_ctx, oracle_rollout, valid_mask)
+
+pytestmark = pytest.mark.gpu
+
+MID = synth.ModelShape(2, 512, 8, 2, 128, 1024, 2048, dtype="bf16")
+
+
+@pytest.mark.parametrize("n_prompts,G", [(16, 8), (32, 8), (5, 3)])
+def test_wide_batches_with_ragged_stops_match_oracle(n_prompts, G):
+    """128 and 256 sequences (the row counts of the 8B and the KV-heavy workloads) and an odd 15: ragged
+    prompts, per-sequence stop lengths, finished rows dropping out while the others go on."""
+    shape = MID
+    N = n_prompts * G
+    blob = synth.make_weights(shape, 3)
+    blob32 = synth.widen_to_f32(blob)
+    prompts, lens = synth.make_prompts(shape.vocab, n_prompts, 45, seed=6, ragged=True)
+    prompts = np.maximum(prompts, 0)
+    max_new = 10
+    stop = synth.make_stop_lens(N, 1, max_new, seed=3)
+    ref = oracle_rollout(shape, blob32, prompts, lens, G=G, max_new=max_new, temperature=1.0, seed=5, stop_lens=stop,
+                         want_logits=True)
+    ctx = make_ctx(shape, N, 64, blob)
+    tf = ctx.rollout(prompts, lens, G, max_new, 1.0, 5, stop_lens=stop, forced=np.maximum(ref["tokens"], 0), want_logits=True)
+    assert np.array_equal(tf["lens"], ref["lens"]) and np.array_equal(tf["lens"], stop)
+    m = valid_mask(ref["lens"], max_new)
+    err = np.abs(tf["logits"] - ref["logits"])[m].max()
+    assert err < BF16_LOGIT_TOL, err
+    rate, raw, n_clear = argmax_agreement(tf["logits"], ref["logits"], m, BF16_LOGIT_TOL)
+    assert rate >= BF16_ARGMAX_RATE, (rate, raw, n_clear)
+    same = (tf["tokens"] == ref["tokens"]) & m
+    assert same[m].mean() > 0.9
+    assert np.abs(tf["logprobs"] - ref["logprobs"])[same].max() < BF16_LOGPROB_TOL
+    assert (tf["tokens"][~m] == -1).all() and (tf["logprobs"][~m] == 0).all()
+    # the fused sampler agrees bit for bit with the fp32 sampler run on the same logits
+    fused = ctx.rollout(prompts, lens, G, max_new, 1.0, 5, stop_lens=stop, forced=np.maximum(ref["tokens"], 0))
+    assert np.array_equal(fused["tokens"], tf["tokens"])
+    # free running: valid tokens, log-probs of a distribution, group members share the first step's distribution
+    free = ctx.rollout(prompts, lens, G, max_new, 1.0, 5, stop_lens=stop)
+    assert np.array_equal(free["lens"], stop)
+    mm = valid_mask(free["lens"], max_new)
+    assert ((free["tokens"][mm] >= 0) & (free["tokens"][mm] < shape.vocab)).all() and (free["logprobs"][mm] <= 0).all()
+    assert np.array_equal(free["tokens"][:, 0], tf["tokens"][:, 0])
+    ctx.close()
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_snapshot_swap_inside_a_rollout(dtype):
+    """A second snapshot is installed from another thread while the rollout runs and is switched in at a
+    pinned step: earlier steps are those of A, later ones those of B on A's KV cache; versions are tagged."""
+    shape = synth.TINY.replace(dtype=dtype)
+    A, B = synth.make_weights(shape, 0), synth.make_weights(shape, 10)
+    A32, B32 = synth.widen_to_f32(A), synth.widen_to_f32(B)
+    prompts, lens = synth.make_prompts(shape.vocab, 4, 16, seed=1)
+    k, max_new = 5, 12
+    ref = oracle_rollout(shape, [A32, B32], prompts, lens, G=2, max_new=max_new, temperature=1.0, seed=2, versions=[3, 8],
+                         swap_at_step=[k], want_logits=True)
+    ctx = make_ctx(shape, 8, 32, A, version=3, slots=2)
+    box = {}
+
+    def run():
+        box["out"] = ctx.rollout(prompts, lens, 2, max_new, 1.0, 2, swap_at_step=[k], swap_timeout_ms=20000, forced=ref["tokens"],
+                                 want_logits=True)
+
+    t = threading.Thread(target=run)
+    t.start()
+    for _ in range(2000):           # once the rollout is inside its loop a new snapshot is staged, not activated
+        if ctx.stats().rollout_running:
+            break
+        time.sleep(0.005)
+    assert ctx.stats().rollout_running
+    ctx.load_policy(8, B)
+    t.join(60)
+    assert not t.is_alive() and "out" in box
+    out = box["out"]
+    tol = F32_LOGIT_TOL if dtype == "fp32" else BF16_LOGIT_TOL
+    assert np.abs(out["logits"] - ref["logits"]).max() < tol
+    assert (out["versions"][:, :k] == 3).all() and (out["versions"][:, k:] == 8).all()
+    assert np.array_equal(out["versions"], ref["versions"])
+    assert np.abs(out["logits"][:, k:] - oracle_rollout(shape, A32, prompts, lens, G=2, max_new=max_new, temperature=1.0, seed=2,
+                                                         forced=ref["tokens"], want_logits=True)["logits"][:, k:]).max() > 1e-2
+    if dtype == "fp32":
+        check_tokens_fp32_sampler(out["tokens"], ref)
+    st = ctx.stats()
+    assert st.active_version == 8 and st.staged_version == -1
+    # versions only advance; a rollout that pins a swap nobody stages gives up with a message
+    from paper_2602_02192_amd import echo
+    with pytest.raises(echo.EchoError) as e:
+        ctx.load_policy(8, A)
+    assert e.value.code == echo.ECHO_ESTATE
+    with pytest.raises(echo.EchoError) as e:
+        ctx.rollout(prompts, lens, 2, 4, 1.0, 2, swap_at_step=[2], swap_timeout_ms=50)
+    assert e.value.code == echo.ECHO_ESTATE
+    ctx.close()
+
+
+@pytest.mark.parametrize("shape", [synth.TINY, MID], ids=["tiny-fp32", "mid-bf16"])
+def test_teacher_forced_scoring_matches_oracle_and_the_rollout(shape):
+    blob = synth.make_weights(shape, 0)
+    blob32 = synth.widen_to_f32(blob)
+    orc = oracle.load("f64")
+    d = oracle.desc_from_shape(shape)
+    prompts, lens = synth.make_prompts(shape.vocab, 3, 20, seed=1, ragged=True)
+    prompts = np.maximum(prompts, 0)
+    ctx = make_ctx(shape, 6, 64, blob)
+    out = ctx.rollout(prompts, lens, 2, 9, 0.8, 4)
+    # whole strings (prompt + generated), right padded
+    T = 20 + 9
+    toks = np.zeros((6, T), np.int32)
+    tl = np.zeros(6, np.int32)
+    for n in range(6):
+        p = n // 2
+        s = np.concatenate([prompts[p, :lens[p]], out["tokens"][n, :out["lens"][n]]])
+        toks[n, :s.size] = s
+        tl[n] = s.size
+    got = ctx.logprobs(toks, tl, 0.8)
+    tol = F32_LOGPROB_TOL if shape.dtype == "fp32" else BF16_LOGPROB_TOL
+    for n in range(6):
+        want = orc.logprobs(d, blob32, toks[n, :tl[n]], 0.8)
+        assert np.abs(got[n, :tl[n]] - want).max() < tol
+        assert got[n, 0] == 0 and (got[n, tl[n]:] == 0).all()
+        # the sampler's own log-probs are the scores of its tokens (what the importance ratio divides by)
+        p = n // 2
+        assert np.abs(got[n, lens[p]:tl[n]] - out["logprobs"][n, :out["lens"][n]]).max() < tol
+    ctx.close()
+
+
+def test_edge_cases_and_errors():
+    from paper_2602_02192_amd import echo
+    shape = synth.TINY
+    blob = synth.make_weights(shape, 0)
+    blob32 = synth.widen_to_f32(blob)
+    ctx = make_ctx(shape, 8, 64)
+    prompts, lens = synth.make_prompts(shape.vocab, 1, 1, seed=1)
+    with pytest.raises(echo.EchoError) as e:            # no snapshot yet
+        ctx.rollout(prompts, lens, 1, 1, 1.0, 0)
+    assert e.value.code == echo.ECHO_ESTATE
+    ctx.load_policy(0, blob)
+    # smallest rollout: one prompt of one token, one sample, one new token
+    out = ctx.rollout(prompts, lens, 1, 1, 1.0, 0, want_logits=True)
+    ref = oracle_rollout(shape, blob32, prompts, lens, G=1, max_new=1, temperature=1.0, seed=0, want_logits=True)
+    assert np.abs(out["logits"] - ref["logits"]).max() < F32_LOGIT_TOL and out["lens"][0] == 1
+    check_tokens_fp32_sampler(out["tokens"], ref)
+    # capacity: exactly max_seqs sequences and prompt + max_new == max_ctx are accepted, one more is not
+    prompts, lens = synth.make_prompts(shape.vocab, 4, 40, seed=2)
+    full = ctx.rollout(prompts, lens, 2, 24, 1.0, 1)
+    assert (full["lens"] == 24).all()
+    for bad in (lambda: ctx.rollout(prompts, lens, 3, 24, 1.0, 1), lambda: ctx.rollout(prompts, lens, 2, 25, 1.0, 1)):
+        with pytest.raises(echo.EchoError) as e:
+            bad()
+        assert e.value.code == echo.ECHO_ENOMEM
+    # argument checks
+    for bad in (lambda: ctx.rollout(prompts, lens, 2, 4, 0.0, 1), lambda: ctx.rollout(prompts, lens, 2, 4, 1.0, 1, top_p=0.9),
+                lambda: ctx.rollout(prompts + shape.vocab, lens, 2, 4, 1.0, 1), lambda: ctx.rollout(prompts, lens * 0, 2, 4, 1.0, 1)):
+        with pytest.raises(echo.EchoError) as e:
+            bad()
+        assert e.value.code == echo.ECHO_EINVAL
+    # EOS: a sequence ends with the EOS token it emitted; the oracle agrees on where
+    eos = int(full["tokens"][0, 3])
+    ref = oracle_rollout(shape, blob32, prompts, lens, G=2, max_new=24, temperature=1.0, seed=1, eos_id=eos)
+    got = ctx.rollout(prompts, lens, 2, 24, 1.0, 1, eos_id=eos)
+    if check_tokens_fp32_sampler(got["tokens"], ref, mask=valid_mask(np.minimum(got["lens"], ref["lens"]), 24)) == 0:
+        assert np.array_equal(got["lens"], ref["lens"])
+    assert got["lens"][0] <= 4 and got["tokens"][0, got["lens"][0] - 1] == eos
+    # the low-temperature limit picks the arg-max token
+    cold = ctx.rollout(prompts, lens, 2, 3, 1e-4, 1, want_logits=True)
+    assert np.array_equal(cold["tokens"][:, 0], cold["logits"][:, 0].argmax(-1))
+    # a different seed draws different tokens; the same seed repeats them
+    assert not np.array_equal(ctx.rollout(prompts, lens, 2, 24, 1.0, 9)["tokens"], full["tokens"])
+    assert np.array_equal(ctx.rollout(prompts, lens, 2, 24, 1.0, 1)["tokens"], full["tokens"])
+    ctx.close()
+
+
+def test_dense4b_shape_in_the_benchmark_launch_configuration():
+    """The 4B-class decoder (36 layers, full width, vocabulary 151936), 8 prompts x G = 8 = 64 sequences as the
+    benchmark launches it.  The oracle is affordable for two whole sequences with a short prompt; the long
+    configuration (prompt 512 + 1024 new tokens) is checked through properties and self-consistency."""
+    import torch
+    shape = synth.DENSE_4B
+    blob_dev = synth.make_weights(shape, 0, device="cuda")
+    blob = torch.empty(blob_dev.shape, dtype=blob_dev.dtype, pin_memory=True)
+    blob.copy_(blob_dev)
+    del blob_dev
+    torch.cuda.empty_cache()
+    blob32 = synth.widen_to_f32(blob)
+    P, G, N = 8, 8, 64
+    ctx = make_ctx(shape, N, 512 + 1024, blob)
+
+    # -- sampled sequences against the oracle: short prompts, 6 teacher-forced steps, sequences 0 and 63
+    prompts, lens = synth.make_prompts(shape.vocab, P, 12, seed=1)
+    max_new = 6
+    refs = {}
+    for p in (0, 7):
+        refs[p] = oracle_rollout(shape, blob32, prompts[p:p + 1], lens[p:p + 1], G=1, max_new=max_new, temperature=1.0, seed=2,
+                                 want_logits=True)
+    forced = np.zeros((N, max_new), np.int32)
+    rng = np.random.default_rng(0)
+    forced[:] = rng.integers(0, shape.vocab, size=(N, max_new))
+    forced[0], forced[63] = refs[0]["tokens"][0], refs[7]["tokens"][0]
+    # the oracle's sequence n=0 of a one-prompt rollout uses stream id 0; sequence 63 of the batch uses 63, so only
+    # logits (which do not depend on the stream) are compared for it, tokens and log-probs for sequence 0
+    out = ctx.rollout(prompts, lens, G, max_new, 1.0, 2, forced=forced)
+    d = ctx.desc
+    unf = ctx.rollout(prompts, lens, G, max_new, 1.0, 2, forced=forced, unfused_sampler=True)
+    assert np.array_equal(out["tokens"], unf["tokens"])                      # fused sampler == fp32 sampler on the same logits
+    assert np.abs(out["logprobs"] - unf["logprobs"]).max() < 1e-4
+    lg = ctx.rollout(prompts[[0, 7]], lens[[0, 7]], 1, max_new, 1.0, 2, forced=np.stack([forced[0], forced[63]]), want_logits=True)
+    for i, p in enumerate((0, 7)):
+        err = np.abs(lg["logits"][i] - refs[p]["logits"][0]).max()
+        assert err < BF16_LOGIT_TOL, (p, err)
+        rate, raw, n_clear = argmax_agreement(lg["logits"][i:i + 1], refs[p]["logits"], np.ones((1, max_new), bool), BF16_LOGIT_TOL)
+        assert rate >= BF16_ARGMAX_RATE, (rate, raw, n_clear)
+    same = out["tokens"][0] == refs[0]["tokens"][0]
+    assert same.mean() >= 0.8
+    assert np.abs(out["logprobs"][0] - refs[0]["logprobs"][0])[same].max() < BF16_LOGPROB_TOL
+    # rows of the 64-row batch equal the same sequences run in a batch of two (batch invariance, bf16 path)
+    assert np.abs(lg["logprobs"][0] - out["logprobs"][0])[lg["tokens"][0] == out["tokens"][0]].max() < 2e-3
+
+    # -- the benchmark's own configuration: prompt 512, 1024 new tokens, graph replay
+    prompts, lens = synth.make_prompts(shape.vocab, P, 512, seed=1)
+    big = ctx.rollout(prompts, lens, G, 1024, 1.0, 2)
+    assert (big["lens"] == 1024).all() and (big["versions"] == 0).all()
+    assert ((big["tokens"] >= 0) & (big["tokens"] < shape.vocab)).all()
+    lp = big["logprobs"]
+    assert (lp <= 0).all() and np.isfinite(lp).all()
+    # near-uniform policy on random weights: log-probs sit around -ln V - sigma^2/2 .. , far from 0 and from -inf
+    assert -16.0 < lp.mean() < -9.0
+    # the G samples of a prompt draw their first token from one distribution; later tokens differ
+    first = big["tokens"][:, 0].reshape(P, G)
+    assert (np.array([len(set(r)) for r in first]) >= G - 1).all()
+    assert len({tuple(r) for r in big["tokens"][:, :8]}) == N
+    # self-consistency over the full length: scoring a rollout's own tokens reproduces the sampler's log-probs
+    for n in (0, 37):
+        s = np.concatenate([prompts[n // G], big["tokens"][n]])[None, :]
+        got = ctx.logprobs(s, np.array([s.shape[1]], np.int32), 1.0)[0, 512:]
+        assert np.abs(got - lp[n]).max() < BF16_LOGPROB_TOL
+    # kernel-by-kernel launches reproduce the graph replay bit for bit (same kernels, same order)
+    ng = ctx.rollout(prompts, lens, G, 64, 1.0, 2, no_graph=True)
+    assert np.array_equal(ng["tokens"], big["tokens"][:, :64]) and np.array_equal(ng["logprobs"], big["logprobs"][:, :64])
+    ctx.close()
