@@ -39,7 +39,8 @@ typedef enum {
 enum { ECHO_F32 = 0, ECHO_BF16 = 1 };
 
 /* Decoder shape and capacity.  dtype selects the storage type of weights and KV cache:
- * ECHO_BF16 runs the MFMA kernels (bf16 operands, fp32 accumulation, fp32 residual stream);
+ * ECHO_BF16 (weights are bf16 values) runs the MFMA kernels: half-precision operands -- the weights converted
+ * exactly, activations and the KV cache rounded to half -- fp32 accumulation, fp32 residual stream;
  * ECHO_F32 runs the all-fp32 debug kernels.  debug_naive = 1 with ECHO_BF16 keeps bf16
  * weights but runs the debug kernels on them (fp32 activations and KV cache). */
 typedef struct {

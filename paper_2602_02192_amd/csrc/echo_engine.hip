@@ -49,7 +49,7 @@ struct Plan {
   int attn_chunk, attn_max_splits;
 };
 
-constexpr int PREFILL_ROWS = 256;
+constexpr int PREFILL_ROWS = 1024;   // rows per pass of prefill and of teacher-forced scoring
 constexpr size_t STAGE_BYTES = (size_t)64 << 20;
 constexpr int MAX_GRID_SPLIT = 8;
 

@@ -7,11 +7,11 @@
 namespace echo {
 
 // ------------------------------------------------------------------------------------------------
-// Layouts of the bf16 (MFMA) path.
+// Layouts of the MFMA path (model dtype bf16; MFMA operands are half precision, see echo_device.h).
 //   packed weight  Wp: rows padded to 32, K padded to GEMM_K_PAD.  Element (r,k) lives at
 //       ((((r/32)*(Kp/8) + k/8)*32 + r%32)*8 + k%8)            -- one 32-row block is contiguous over K,
 //       and a wavefront's MFMA A-operand load (32 rows x 16 k) is one contiguous 1 KiB read.
-//   packed activation Xp ("K8"): M padded to 32.  Element (m,k) lives at ((k/8)*Mp + m)*8 + k%8.
+//   packed activation Xp ("K8", halves): M padded to 32.  Element (m,k) lives at ((k/8)*Mp + m)*8 + k%8.
 //   split-K partials P: [split][Mp][Np] fp32, row-major.
 // ------------------------------------------------------------------------------------------------
 static inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
@@ -33,7 +33,7 @@ struct KvGeom {          // KV cache, plain form: [slot][layer][K|V][kv_head][ma
   __host__ __device__ int64_t slot_stride() const { return layer_stride() * n_layers; }
   // Tiled form: [slot][layer][kv_head][tile of 32 keys][K tile | V tile].  Both tiles are stored in the order the
   // attention kernel's MFMA operands want them, so a wavefront reads a tile as head_dim/16 contiguous 1 KiB loads
-  // per operand, straight into registers.  In 16-byte units (8 bf16):
+  // per operand, straight into registers.  In 16-byte units (8 halves):
   //   K tile: unit (dim/8)*32 + key%32 holds dims 8*(dim/8).. of one key            (A operand of K Q^T)
   //   V tile: unit (((key%32)/16 * (hd/32) + dim/32)*2 + (key%16)/8)*32 + dim%32 holds 8 keys of one dim (A operand of V^T P^T)
   __host__ __device__ int64_t tiled_head_off(int slot, int layer, int kvh) const {
@@ -79,31 +79,31 @@ void dbg_sample(int32_t *tok, float *lp, const float *logits, int64_t ld, int M,
 void dbg_target_logprob(float *lp, const float *logits, int64_t ld, int M, int V, float temperature,
                         const int32_t *target, hipStream_t st);
 
-// ---- bf16 MFMA path -------------------------------------------------------------------------------
-// Repack a row-major bf16 chunk `src` [n_rows][K] into the packed weight `dst`: source row i goes to
+// ---- MFMA path -------------------------------------------------------------------------------
+// Repack a row-major bf16 chunk `src` [n_rows][K] into the packed weight `dst` (halves, scaled by W_SCALE): source row i goes to
 // destination row dst_row0 + i*dst_row_stride (stride 2 interleaves gate and up rows).  K % 8 == 0.
 void fast_pack_weight(void *dst, const void *src, int64_t dst_row0, int dst_row_stride, int64_t n_rows, int K, int Kp,
                       int Np, hipStream_t st);
-// h = embed[token] (first layer) or h += sum_s P[s] (+0); then x = rmsnorm(h)*gain -> Xp (bf16 K8).
+// h = embed[token] (first layer) or h += sum_s P[s] (+0); then x = rmsnorm(h)*gain -> Xp (half K8).
 void fast_resid_norm(float *h, const void *embed_bf16, const int32_t *token, const float *partials, int nsplit,
                      int Np, void *Xp, const void *gain_bf16, int M, int Mp, int d, float eps, hipStream_t st);
 enum GemmEpilogue { EPI_PARTIAL = 0, EPI_SWIGLU = 1 };
 // out = Xp[Mp x Kp] * Wp[Np x Kp]^T.  EPI_PARTIAL: fp32 partials [nsplit][Mp][Np];
-// EPI_SWIGLU (rows alternate gate_f, up_f): silu(gate)*up -> bf16 K8 [Mp][Np/2]; nsplit must be 1.
+// EPI_SWIGLU (rows alternate gate_f, up_f): silu(gate)*up -> half K8 [Mp][Np/2]; nsplit must be 1.
 struct GemmShape { int nsplit, waves_k, waves_n, nbw, lds, stages; };   // launch shape, see fast_gemm_pick
 constexpr int GEMM_K_PAD = 128;   // packed weights and K8 activations pad K to this (whole LDS chunks of 8 k-steps)
 void fast_gemm(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, GemmShape g, GemmEpilogue epi,
                hipStream_t st);
 void fast_gemm_pick(int Np, int Kp, int Mp, int full_k, GemmShape *g);
-void fast_qkv_post(const float *partials, int nsplit, int Np, int Mp, void *q_bf16 /*[M][Hq][hd]*/,
+void fast_qkv_post(const float *partials, int nsplit, int Np, int Mp, void *q_h16 /*[M][Hq][hd]*/,
                    const void *q_gain, const void *k_gain, int qk_norm, float eps, const float *rope_cs,
                    RowState rows, KvGeom kv, int layer, int M, int Hq, int Hkv, hipStream_t st);
-// Plain one-wavefront-per-(row, head) attention over the bf16 KV cache (cross-check of the split-K kernel).
-void fast_attention_simple(void *Xp_out, const void *q_bf16, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq,
+// Plain one-wavefront-per-(row, head) attention over the half-precision KV cache (cross-check of the split-K kernel).
+void fast_attention_simple(void *Xp_out, const void *q_h16, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq,
                            int Hkv, hipStream_t st);
-// Split-K decode attention over the bf16 KV cache + combine; writes Xp (bf16 K8 [Mp][Hq*hd]).
+// Split-K decode attention over the half-precision KV cache + combine; writes Xp (half K8 [Mp][Hq*hd]).
 // nsplit = fast_attention_splits(M, Hkv, capacity); partial buffers hold M*Hq*nsplit*(hd + 2) floats.
-void fast_attention(void *Xp_out, const void *q_bf16, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq,
+void fast_attention(void *Xp_out, const void *q_h16, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq,
                     int Hkv, int nsplit, float *part_o, float *part_ml, hipStream_t st);
 int fast_attention_splits(int M, int Hkv, int max_splits);
 // lm_head with the sampler fused into the epilogue (partials per workgroup) + the combine kernel.

@@ -1,4 +1,4 @@
-// bf16 path: grouped-query decode attention over the tiled per-sequence KV cache.
+// MFMA path: grouped-query decode attention over the tiled per-sequence KV cache.
 //
 // attn_simple_kernel: one wavefront per (row, query head), two passes, no split -- the plain form, kept as
 //   the on-GPU cross-check of the split-K kernel.
@@ -15,11 +15,11 @@
 
 namespace echo {
 
-// Xp (bf16 K8 [Mp][Hq*hd]) element (m, n)
+// Xp (half K8 [Mp][Hq*hd]) element (m, n)
 __device__ __forceinline__ int64_t k8_index(int m, int n, int Mp) { return ((int64_t)(n >> 3) * Mp + m) * 8 + (n & 7); }
 
 // grid (M, Hq), block 64, dynamic LDS max_ctx floats; hd <= 256, hd % 64 == 0.
-__global__ void attn_simple_kernel(uint16_t *Xp, const uint16_t *q_bf16, RowState rows, KvGeom kv, int layer, int Mp, int Hq,
+__global__ void attn_simple_kernel(uint16_t *Xp, const uint16_t *q_h16, RowState rows, KvGeom kv, int layer, int Mp, int Hq,
                                    int Hkv) {
   extern __shared__ float sc[];
   int m = blockIdx.x, j = blockIdx.y, lane = threadIdx.x, hd = kv.head_dim;
@@ -29,7 +29,7 @@ __global__ void attn_simple_kernel(uint16_t *Xp, const uint16_t *q_bf16, RowStat
   }
   int n_keys = rows.pos[m] + 1, kvh = j / (Hq / Hkv);
   const uint16_t *head = (const uint16_t *)kv.base + kv.tiled_head_off(rows.slot[m], layer, kvh);
-  const uint16_t *q = q_bf16 + ((int64_t)m * Hq + j) * hd;
+  const uint16_t *q = q_h16 + ((int64_t)m * Hq + j) * hd;
   float scale = 1.0f / sqrtf((float)hd), mx = -INFINITY;
   for (int t = lane; t < n_keys; t += 64) {
     float s = 0.f;
@@ -50,10 +50,10 @@ __global__ void attn_simple_kernel(uint16_t *Xp, const uint16_t *q_bf16, RowStat
   }
 }
 
-void fast_attention_simple(void *Xp_out, const void *q_bf16, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq,
+void fast_attention_simple(void *Xp_out, const void *q_h16, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq,
                            int Hkv, hipStream_t st) {
   hipLaunchKernelGGL(attn_simple_kernel, dim3(M, Hq), dim3(64), (size_t)kv.max_ctx * sizeof(float), st, (uint16_t *)Xp_out,
-                     (const uint16_t *)q_bf16, rows, kv, layer, Mp, Hq, Hkv);
+                     (const uint16_t *)q_h16, rows, kv, layer, Mp, Hq, Hkv);
 }
 
 // ---- split-K MFMA kernel -----------------------------------------------------------------------------
@@ -79,7 +79,7 @@ __device__ __forceinline__ int att_split_len(int n_keys, int nsplit) {
   return ((n_keys + nsplit - 1) / nsplit + ATT_TILE - 1) & ~(ATT_TILE - 1);
 }
 
-// A tile is 64*HD bf16 = HD*8 units of 16 bytes: the K tile, then the V tile; lane l of load i reads unit i*64 + l.
+// A tile is 64*HD halves = HD*8 units of 16 bytes: the K tile, then the V tile; lane l of load i reads unit i*64 + l.
 template <int HD>
 __device__ __forceinline__ void att_issue_k(v4u (&rk)[HD / 16], const v4u *__restrict__ head, int tile, int lane) {
   const v4u *t = head + (int64_t)tile * (HD * 8) + lane;
@@ -94,10 +94,10 @@ __device__ __forceinline__ void att_issue_v(v4u (&rv)[HD / 16], const v4u *__res
 }
 
 // grid (nsplit, Hkv, M).  Every row's keys are cut into nsplit equal chunks of that row's own length.  DIRECT
-// (nsplit == 1): the workgroup normalises and writes the bf16 output itself and no partials exist.
+// (nsplit == 1): the workgroup normalises and writes the half-precision output itself and no partials exist.
 template <int HD, bool DIRECT>
 __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__ part_o, float *__restrict__ part_ml,
-                                                          uint16_t *__restrict__ Xp, int Mp, const uint16_t *__restrict__ q_bf16,
+                                                          uint16_t *__restrict__ Xp, int Mp, const uint16_t *__restrict__ q_h16,
                                                           RowState rows, KvGeom kv, int layer, int Hq, int Hkv, int nsplit) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   using L = AttLds<HD>;
@@ -127,7 +127,7 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
   for (int idx = threadIdx.x; idx < 8 * (HD / 8); idx += 256) {
     int hq = idx & 7, d8 = idx >> 3;
     v4u v = v4u{0u, 0u, 0u, 0u};
-    if (hq < grp) v = *(const v4u *)(q_bf16 + ((int64_t)m * Hq + kvh * grp + hq) * HD + d8 * 8);
+    if (hq < grp) v = *(const v4u *)(q_h16 + ((int64_t)m * Hq + kvh * grp + hq) * HD + d8 * 8);
     qs[idx] = v;
   }
   __syncthreads();
@@ -239,7 +239,7 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
   }
 }
 
-// grid (M, Hq), block HD: merge the chunk partials of one (row, head) in chunk order, normalise, write bf16 K8.
+// grid (M, Hq), block HD: merge the chunk partials of one (row, head) in chunk order, normalise, write half K8.
 template <int HD>
 __global__ void attn_combine_kernel(uint16_t *Xp, const float *__restrict__ part_o, const float *__restrict__ part_ml,
                                     RowState rows, int Mp, int Hq, int nsplit) {
@@ -268,24 +268,24 @@ int fast_attention_splits(int M, int Hkv, int max_splits) {
 }
 
 template <int HD>
-static void attention_launch(void *Xp_out, const void *q_bf16, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq, int Hkv,
+static void attention_launch(void *Xp_out, const void *q_h16, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq, int Hkv,
                              int nsplit, float *part_o, float *part_ml, hipStream_t st) {
   dim3 grid(nsplit, Hkv, M);
   if (nsplit == 1) {
     hipLaunchKernelGGL((attn_splitk_kernel<HD, true>), grid, dim3(256), AttLds<HD>::TOTAL, st, part_o, part_ml, (uint16_t *)Xp_out,
-                       Mp, (const uint16_t *)q_bf16, rows, kv, layer, Hq, Hkv, nsplit);
+                       Mp, (const uint16_t *)q_h16, rows, kv, layer, Hq, Hkv, nsplit);
   } else {
     hipLaunchKernelGGL((attn_splitk_kernel<HD, false>), grid, dim3(256), AttLds<HD>::TOTAL, st, part_o, part_ml, (uint16_t *)Xp_out,
-                       Mp, (const uint16_t *)q_bf16, rows, kv, layer, Hq, Hkv, nsplit);
+                       Mp, (const uint16_t *)q_h16, rows, kv, layer, Hq, Hkv, nsplit);
     hipLaunchKernelGGL(attn_combine_kernel<HD>, dim3(M, Hq), dim3(HD), 0, st, (uint16_t *)Xp_out, part_o, part_ml, rows, Mp, Hq,
                        nsplit);
   }
 }
 
-void fast_attention(void *Xp_out, const void *q_bf16, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq, int Hkv,
+void fast_attention(void *Xp_out, const void *q_h16, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq, int Hkv,
                     int nsplit, float *part_o, float *part_ml, hipStream_t st) {
-  if (kv.head_dim == 128) attention_launch<128>(Xp_out, q_bf16, rows, kv, layer, M, Mp, Hq, Hkv, nsplit, part_o, part_ml, st);
-  else attention_launch<64>(Xp_out, q_bf16, rows, kv, layer, M, Mp, Hq, Hkv, nsplit, part_o, part_ml, st);
+  if (kv.head_dim == 128) attention_launch<128>(Xp_out, q_h16, rows, kv, layer, M, Mp, Hq, Hkv, nsplit, part_o, part_ml, st);
+  else attention_launch<64>(Xp_out, q_h16, rows, kv, layer, M, Mp, Hq, Hkv, nsplit, part_o, part_ml, st);
 }
 
 }  // namespace echo

@@ -1,4 +1,4 @@
-// bf16 MFMA path, everything that is not a dense contraction: residual + RMSNorm (with the split-K
+// MFMA path, everything that is not a dense contraction: residual + RMSNorm (with the split-K
 // reduction folded in), QKV post-processing (reduction, per-head norm, rotary embedding, KV append).
 #include "echo_device.h"
 #include "echo_kernels.h"
@@ -7,7 +7,7 @@ namespace echo {
 
 // grid M rows, block 1024.  h[m] = embed[token[m]]            (embed != null)
 //                           h[m] += sum_s partials[s][..][m]  (nsplit <= 8, summed in split order)
-// then Xp[m] = bf16(h[m] * rsqrt(mean(h[m]^2) + eps) * gain).  d % 8 == 0, d <= 8192.
+// then Xp[m] = half(h[m] * rsqrt(mean(h[m]^2) + eps) * gain).  d % 8 == 0, d <= 8192.
 // Every load of a thread (residual, up to 8 partials) is issued before the first use, so the kernel costs
 // one memory round trip whatever the split count.
 constexpr int RN_THREADS = 1024;
@@ -70,7 +70,7 @@ void fast_resid_norm(float *h, const void *embed_bf16, const int32_t *token, con
 }
 
 // grid (M, Hq + 2*Hkv), block hd/2.  Sums the split-K partials of one head of one row, applies the optional
-// per-head RMSNorm and the rotary embedding, writes q (bf16 [M][Hq][hd]) or appends k / v to the bf16 cache.
+// per-head RMSNorm and the rotary embedding, writes q (half [M][Hq][hd]) or appends k / v to the half-precision cache.
 __global__ void qkv_post_kernel(const float *partials, int nsplit, int Np, int Mp, uint16_t *q_out, const uint16_t *q_gain,
                                 const uint16_t *k_gain, int qk_norm, float eps, const float2 *rope_cs, RowState rows,
                                 KvGeom kv, int layer, int Hq, int Hkv) {
@@ -116,11 +116,11 @@ __global__ void qkv_post_kernel(const float *partials, int nsplit, int Np, int M
   }
 }
 
-void fast_qkv_post(const float *partials, int nsplit, int Np, int Mp, void *q_bf16, const void *q_gain, const void *k_gain,
+void fast_qkv_post(const float *partials, int nsplit, int Np, int Mp, void *q_h16, const void *q_gain, const void *k_gain,
                    int qk_norm, float eps, const float *rope_cs, RowState rows, KvGeom kv, int layer, int M, int Hq, int Hkv,
                    hipStream_t st) {
   hipLaunchKernelGGL(qkv_post_kernel, dim3(M, Hq + 2 * Hkv), dim3(kv.head_dim / 2), 0, st, partials, nsplit, Np, Mp,
-                     (uint16_t *)q_bf16, (const uint16_t *)q_gain, (const uint16_t *)k_gain, qk_norm, eps,
+                     (uint16_t *)q_h16, (const uint16_t *)q_gain, (const uint16_t *)k_gain, qk_norm, eps,
                      (const float2 *)rope_cs, rows, kv, layer, Hq, Hkv);
 }
 

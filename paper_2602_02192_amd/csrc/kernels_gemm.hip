@@ -1,4 +1,4 @@
-// bf16 MFMA path, dense contractions: weight repacking, the weight-streaming GEMM (split-K over the
+// MFMA path, dense contractions: weight repacking, the weight-streaming GEMM (split-K over the
 // wavefronts of a workgroup and over the grid) with its epilogues, and the lm_head GEMM whose epilogue
 // is the sampler (temperature, Gumbel-max, running log-sum-exp), so logits never reach HBM.
 //
@@ -10,7 +10,7 @@
 
 namespace echo {
 
-// Packed weight addressing, in units of 16 bytes (8 bf16).  ECHO_W_KSMAJOR = 0: one 32-row block is contiguous
+// Packed weight addressing, in units of 16 bytes (8 halves).  ECHO_W_KSMAJOR = 0: one 32-row block is contiguous
 // over K.  ECHO_W_KSMAJOR = 1: k-step major -- all row blocks of one k-step are contiguous, so wavefronts that
 // advance together sweep HBM like one streaming copy.
 #ifndef ECHO_W_KSMAJOR
@@ -204,12 +204,13 @@ __global__ __launch_bounds__(512) void gemm_kernel(void *out, const h16x8 *__res
 // grid (ceil(Np/32 / WN), nsplit, Mp/(32*MB)); block 64*WN; chunks_per_split chunks of KC k-steps per grid split.
 typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
 
+constexpr int GEMM_KC_SMALL = 8, GEMM_KC_WIDE = 4;   // k-steps per chunk for up to 128 / for 256 batch rows per workgroup
 template <int MB, int WN> struct GemmLds {
-  static constexpr int KC = 8;
+  static constexpr int KC = MB >= 8 ? GEMM_KC_WIDE : GEMM_KC_SMALL;
   static constexpr int CHUNK_UNITS = KC * 2 * 32 * MB;                  // 16-byte units of one activation chunk
   static constexpr int X_BYTES = 2 * CHUNK_UNITS * 16;                   // double buffer
   static constexpr int TILE_STRIDE = 33;                                 // floats per row of the transposed output tile
-  static constexpr int EPI_BYTES = WN * 32 * MB * TILE_STRIDE * 4;
+  static constexpr int EPI_BYTES = WN * 32 * TILE_STRIDE * 4;            // one 32 x 32 tile per wavefront at a time
   static constexpr int BYTES = X_BYTES > EPI_BYTES ? X_BYTES : EPI_BYTES;
 };
 
@@ -283,23 +284,27 @@ __global__ __launch_bounds__(WN * 64) void gemm_lds_kernel(void *out, const u32x
   }
   const int half = lane >> 5, col = lane & 31;
   if (EPI == EPI_PARTIAL) {
-    // transpose the wavefront's 32 x ROWS tile through LDS so that every store is a whole 128-byte row segment
-    float *tile = (float *)lds_raw + (size_t)w * ROWS * L::TILE_STRIDE;
+    // transpose the wavefront's tile through LDS, 32 batch rows at a time, so that every store is a whole 128-byte
+    // row segment (the LDS tile is private to the wavefront: only its own LDS traffic has to be waited for)
+    float *tile = (float *)lds_raw + (size_t)w * 32 * L::TILE_STRIDE;
+    float *P = (float *)out + ((int64_t)blockIdx.y * Mp + mrow0) * Np + nb * 32;
 #pragma unroll
-    for (int j = 0; j < MB; ++j)
+    for (int j = 0; j < MB; ++j) {
 #pragma unroll
       for (int g = 0; g < 4; ++g)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) tile[(j * 32 + col) * L::TILE_STRIDE + 8 * g + 4 * half + i] = acc[j][4 * g + i] * W_UNSCALE;
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the tile is private to this wavefront
-    if (nb_own >= nblocks) return;
-    float *P = (float *)out + ((int64_t)blockIdx.y * Mp + mrow0) * Np + nb * 32;
+        for (int i = 0; i < 4; ++i) tile[col * L::TILE_STRIDE + 8 * g + 4 * half + i] = acc[j][4 * g + i] * W_UNSCALE;
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      if (nb_own < nblocks) {
 #pragma unroll
-    for (int q = 0; q < ROWS / 8; ++q) {
-      int r = q * 8 + (lane >> 3), n4 = (lane & 7) * 4;
-      const float *t = tile + r * L::TILE_STRIDE + n4;
-      f32x4 v = {t[0], t[1], t[2], t[3]};
-      *(f32x4 *)(P + (int64_t)r * Np + n4) = v;
+        for (int q = 0; q < 4; ++q) {
+          int r = q * 8 + (lane >> 3), n4 = (lane & 7) * 4;
+          const float *t = tile + r * L::TILE_STRIDE + n4;
+          f32x4 v = {t[0], t[1], t[2], t[3]};
+          *(f32x4 *)(P + (int64_t)(j * 32 + r) * Np + n4) = v;
+        }
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the reads are done before the next pass overwrites the tile
     }
   } else {  // EPI_SWIGLU: weight rows alternate gate_f, up_f; a block of 32 rows yields 16 features = two K8 groups
     if (nb_own >= nblocks) return;
@@ -331,13 +336,15 @@ void fast_gemm_pick(int Np, int Kp, int Mp, int full_k, GemmShape *g) {
   int nblocks = Np / 32, ksteps = Kp / 16, mb = Mp / 32 > 8 ? 8 : Mp / 32;
   int zblocks = Mp / (32 * mb);
   g->lds = 0; g->stages = 0;
-  if (Mp <= 128 && Kp % (16 * GemmLds<1, 4>::KC) == 0) {
-    int total_chunks = ksteps / GemmLds<1, 4>::KC;
+  if (Kp % (16 * GEMM_KC_SMALL) == 0 && (Mp <= 128 || Mp % 256 == 0)) {
+    const bool wide = Mp > 128;   // 256 batch rows per workgroup, Mp/256 workgroups per weight strip
+    int total_chunks = ksteps / (wide ? GEMM_KC_WIDE : GEMM_KC_SMALL);
     g->lds = 1; g->nbw = 1; g->waves_k = 1;
-    if (full_k) { g->waves_n = 3; g->stages = 4; g->nsplit = 1; return; }
-    g->waves_n = nblocks % 4 == 0 || nblocks > 96 ? 4 : 3;
-    g->stages = 3;
-    int strips = (nblocks + g->waves_n - 1) / g->waves_n;
+    if (full_k && !wide) { g->waves_n = 3; g->stages = 4; g->nsplit = 1; return; }
+    g->waves_n = wide || nblocks % 4 == 0 || nblocks > 96 ? 4 : 3;
+    g->stages = wide ? 2 : 3;
+    int strips = (nblocks + g->waves_n - 1) / g->waves_n * (wide ? Mp / 256 : 1);
+    if (full_k) { g->nsplit = 1; return; }
     int ns = (256 + strips / 2) / strips;
     if (ns > total_chunks / 2) ns = total_chunks / 2;
     if (ns > 8) ns = 8;
@@ -376,7 +383,8 @@ static void gemm_lds_launch(void *out, const void *Xp, const void *Wp, int Mp, i
 
 template <int EPI>
 static void gemm_lds_dispatch(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, GemmShape g, hipStream_t st) {
-  int mb = Mp / 32;   // 1, 2 or 4
+  int mb = Mp / 32;   // 1, 2, 4 or a multiple of 8
+  if (mb >= 8) { gemm_lds_launch<8, 4, 2, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st); return; }
 #define LDS_CASE(MBV)                                                                                              \
   if (g.waves_n == 3 && g.stages == 4) gemm_lds_launch<MBV, 3, 4, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st);     \
   else if (g.waves_n == 3) gemm_lds_launch<MBV, 3, 3, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st);                 \
