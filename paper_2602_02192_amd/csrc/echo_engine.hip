@@ -98,7 +98,7 @@ Plan make_plan(const echo_model_desc *d) {
   int64_t H = d->hidden, hd = d->head_dim, Q = (int64_t)d->n_q_heads * hd, KV = (int64_t)d->n_kv_heads * hd, F = d->ffn, V = d->vocab;
   p.Mcap = std::max(pad_rows(d->max_seqs), PREFILL_ROWS);
   p.Np_qkv = (int)round_up(Q + 2 * KV, 32); p.Np_d = (int)round_up(H, 32); p.Np_gu = (int)round_up(2 * F, 32);
-  p.Np_v = (int)round_up(V, 64);   // an even number of 32-row blocks: lm_head wavefronts own two blocks
+  p.Np_v = (int)round_up(V, 64);
   p.Kp_d = (int)round_up(H, GEMM_K_PAD); p.Kp_q = (int)round_up(Q, GEMM_K_PAD); p.Kp_f = (int)round_up(F, GEMM_K_PAD);
   Bump b;
   if (p.fast) {

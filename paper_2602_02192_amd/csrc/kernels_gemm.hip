@@ -214,6 +214,75 @@ template <int MB, int WN> struct GemmLds {
   static constexpr int BYTES = X_BYTES > EPI_BYTES ? X_BYTES : EPI_BYTES;
 };
 
+// The GEMM kernel's main loop as a function, for the lm_head (the GEMM kernel keeps its own inline copy: hipcc
+// schedules the inlined function measurably worse there): accumulates, for weight block `nb` and the 32*MB batch rows from
+// mrow0, the k-range of `nchunks` chunks starting at chunk c_begin.  Ends with a workgroup barrier, after which the
+// LDS buffers are free for the epilogue.
+template <int MB, int WN, int NSTAGE>
+__device__ __forceinline__ void gemm_lds_mainloop(f32x16 (&acc)[MB], char *lds_raw, const u32x4v *__restrict__ Xp,
+                                                  const h16x8 *__restrict__ Wp, int Mp, int Np, int Kp, int nb, int c_begin,
+                                                  int nchunks, int mrow0) {
+  using L = GemmLds<MB, WN>;
+  constexpr int KC = L::KC, T = WN * 64, XU = L::CHUNK_UNITS, XL = (XU + T - 1) / T, ROWS = 32 * MB;
+  u32x4v *xs = (u32x4v *)lds_raw;
+  const int lane = threadIdx.x & 63, tid = threadIdx.x;
+  const h16x8 *a_ptr = Wp + w_block_base(nb, Kp) + (int64_t)c_begin * KC * w_kstep_stride(Np) + (lane >> 5) * 32 + (lane & 31);
+  const int64_t a_step = w_kstep_stride(Np);
+#pragma unroll
+  for (int j = 0; j < MB; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+  h16x8 a[NSTAGE][KC];
+  u32x4v xr[NSTAGE][XL];
+  auto load_a = [&](int st, int c) {
+#pragma unroll
+    for (int u = 0; u < KC; ++u) a[st][u] = __builtin_nontemporal_load(a_ptr + (int64_t)(c * KC + u) * a_step);
+  };
+  // unit i of a chunk: k8 group i / ROWS (two per k-step), batch row i % ROWS
+  auto load_x = [&](int st, int c) {
+#pragma unroll
+    for (int i = 0; i < XL; ++i) {
+      int idx = i * T + tid;
+      if (XU % T == 0 || idx < XU)
+        xr[st][i] = Xp[(int64_t)((c_begin + c) * KC * 2 + idx / ROWS) * Mp + mrow0 + idx % ROWS];
+    }
+  };
+  auto store_x = [&](int st, int buf) {
+#pragma unroll
+    for (int i = 0; i < XL; ++i) {
+      int idx = i * T + tid;
+      if (XU % T == 0 || idx < XU) xs[buf * XU + idx] = xr[st][i];
+    }
+  };
+  auto compute = [&](int st, int buf) {
+    const u32x4v *bp = xs + buf * XU + (lane >> 5) * ROWS + (lane & 31);
+#pragma unroll
+    for (int u = 0; u < KC; ++u)
+#pragma unroll
+      for (int j = 0; j < MB; ++j)
+        acc[j] = mfma_h16(a[st][u], __builtin_bit_cast(h16x8, bp[u * 2 * ROWS + j * 32]), acc[j]);
+  };
+  if (nchunks > 0) {
+#pragma unroll
+    for (int s = 0; s < NSTAGE - 1; ++s)
+      if (s < nchunks) { load_x(s, s); load_a(s, s); }
+    store_x(0, 0);
+    __syncthreads();
+    for (int c0 = 0; c0 < nchunks; c0 += NSTAGE) {
+#pragma unroll
+      for (int s = 0; s < NSTAGE; ++s) {
+        const int c = c0 + s;
+        if (c < nchunks) {
+          if (c + NSTAGE - 1 < nchunks) { load_x((s + NSTAGE - 1) % NSTAGE, c + NSTAGE - 1); load_a((s + NSTAGE - 1) % NSTAGE, c + NSTAGE - 1); }
+          compute(s, c & 1);
+          if (c + 1 < nchunks) store_x((s + 1) % NSTAGE, (c + 1) & 1);
+          __syncthreads();   // chunk c+1 is visible; chunk c's buffer may be overwritten two iterations later
+        }
+      }
+    }
+  }
+}
+
 template <int MB, int WN, int NSTAGE, int EPI>
 __global__ __launch_bounds__(WN * 64) void gemm_lds_kernel(void *out, const u32x4v *__restrict__ Xp, const h16x8 *__restrict__ Wp,
                                                            int Mp, int Np, int Kp, int chunks_per_split) {
@@ -431,41 +500,31 @@ void fast_gemm(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp
 }
 
 // ---- lm_head ---------------------------------------------------------------------------------------------
-// grid (ceil(Np/32 / (4*LM_NBW)), 1, Mp/(32*MB)); block 256.  Each wavefront runs LM_NBW weight blocks over the full
-// K and folds every logit into a running (max, sum-exp, best perturbed score, its index, its z) per batch row.
-constexpr int LM_NBW = 2;      // weight blocks per wavefront
+// grid (ceil(Np/32 / 4), 1, Mp/(32*MB)); block 256.  The GEMM main loop over the full K (four weight blocks per
+// workgroup), then every logit is folded into a running (max, sum-exp, best perturbed score, its index, its z) per
+// batch row: per wavefront, then over the four wavefronts in wavefront order, one partial per workgroup.
+constexpr int LM_WN = 4;
 
-template <int MB, bool LOGITS>
-__global__ __launch_bounds__(256) void lmhead_kernel(const h16x8 *__restrict__ Xp, const h16x8 *__restrict__ Wp, int Mp,
+template <int MB, int NSTAGE, bool LOGITS>
+__global__ __launch_bounds__(256) void lmhead_kernel(const u32x4v *__restrict__ Xp, const h16x8 *__restrict__ Wp, int Mp,
                                                      int Np, int Kp, int V, float temperature, uint64_t seed,
                                                      const int32_t *d_step, const int32_t *target, float *target_z,
                                                      float *part, int n_wg, float *logits, int64_t ld) {
-  __shared__ SampleAcc sh[3][MB][32];
+  extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+  using L = GemmLds<MB, LM_WN>;
   int w = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
-  int mblk0 = blockIdx.z * MB, nblocks = Np >> 5;
+  const int nblocks = Np >> 5, mrow0 = blockIdx.z * 32 * MB;
+  const int nb_own = blockIdx.x * LM_WN + w, nb = min(nb_own, nblocks - 1);
   uint32_t step = LOGITS ? 0u : (uint32_t)*d_step;
+  f32x16 acc[MB];
+  gemm_lds_mainloop<MB, LM_WN, NSTAGE>(acc, lds_raw, Xp, Wp, Mp, Np, Kp, nb, 0, (Kp >> 4) / L::KC, mrow0);
   SampleAcc sa[MB];
 #pragma unroll
   for (int j = 0; j < MB; ++j) sa[j] = sample_acc_init();
-  const int nb0 = (blockIdx.x * 4 + w) * LM_NBW;
-  f32x16 accs[LM_NBW][MB];
-#pragma unroll
-  for (int n = 0; n < LM_NBW; ++n)
-#pragma unroll
-    for (int j = 0; j < MB; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) accs[n][j][r] = 0.f;
-  if (nb0 < nblocks)   // blocks past the end re-read the last block; their results are dropped below
-    mma_range<MB, LM_NBW>(accs, Wp + w_block_base(min(nb0, nblocks - LM_NBW), Kp), w_block_base(1, Kp), Xp + mblk0 * 32, Mp, 0,
-                          Kp >> 4, lane, w_kstep_stride(Np));
-#pragma unroll
-  for (int q = 0; q < LM_NBW; ++q) {
-    const int nb = nb0 + q;
-    if (nb >= nblocks) break;
-    f32x16 (&acc)[MB] = accs[q];
+  if (nb_own < nblocks) {
 #pragma unroll
     for (int j = 0; j < MB; ++j) {
-      int m = (mblk0 + j) * 32 + col;
+      int m = mrow0 + j * 32 + col;
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         int v0 = nb * 32 + 8 * g + 4 * half;
@@ -490,6 +549,7 @@ __global__ __launch_bounds__(256) void lmhead_kernel(const h16x8 *__restrict__ X
   }
   if (LOGITS) return;
   // lanes l and l^32 hold the same batch row; then fold the four wavefronts in wavefront order
+  SampleAcc (*sh)[MB][32] = (SampleAcc (*)[MB][32])lds_raw;   // [3][MB][32]; the main loop's buffers are free by now
 #pragma unroll
   for (int j = 0; j < MB; ++j) { SampleAcc b = sample_acc_shfl_xor(sa[j], 32); sample_acc_merge(sa[j], b); }
   if (w > 0 && half == 0)
@@ -500,7 +560,7 @@ __global__ __launch_bounds__(256) void lmhead_kernel(const h16x8 *__restrict__ X
 #pragma unroll
     for (int j = 0; j < MB; ++j) {
       for (int ww = 0; ww < 3; ++ww) sample_acc_merge(sa[j], sh[ww][j][col]);
-      int m = (mblk0 + j) * 32 + col;
+      int m = mrow0 + j * 32 + col;
       int64_t o = (int64_t)blockIdx.x * Mp + m, plane = (int64_t)n_wg * Mp;
       part[o] = sa[j].zmax;
       part[plane + o] = sa[j].zsum;
@@ -536,26 +596,37 @@ __global__ void sample_combine_kernel(int32_t *tok, float *lp, float *target_lp,
   }
 }
 
-static int lm_wgs(int Np) { return (Np / 32 + 4 * LM_NBW - 1) / (4 * LM_NBW); }
+static int lm_wgs(int Np) { return (Np / 32 + LM_WN - 1) / LM_WN; }
 size_t fast_lmhead_partial_floats(int Np, int Mp) { return (size_t)5 * lm_wgs(Np) * Mp + Mp; }
+
+template <int MB, int NSTAGE, bool LOGITS>
+static void lmhead_launch(const void *Xp, const void *Wp, int Mp, int Np, int Kp, int V, float temperature, uint64_t seed,
+                          const int32_t *d_step, const int32_t *target, float *target_z, float *part, float *logits, int64_t ld,
+                          hipStream_t st) {
+  using L = GemmLds<MB, LM_WN>;
+  constexpr int SH = 3 * MB * 32 * (int)sizeof(SampleAcc), BYTES = L::X_BYTES > SH ? L::X_BYTES : SH;
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void *)lmhead_kernel<MB, NSTAGE, LOGITS>, hipFuncAttributeMaxDynamicSharedMemorySize, BYTES);
+    attr_set = true;
+  }
+  int n_wg = lm_wgs(Np);
+  dim3 grid(n_wg, 1, Mp / (32 * MB)), block(256);
+  hipLaunchKernelGGL((lmhead_kernel<MB, NSTAGE, LOGITS>), grid, block, BYTES, st, (const u32x4v *)Xp, (const h16x8 *)Wp, Mp, Np, Kp, V,
+                     temperature, seed, d_step, target, target_z, part, n_wg, logits, ld);
+}
 
 template <bool LOGITS>
 static void lmhead_dispatch(const void *Xp, const void *Wp, int Mp, int Np, int Kp, int V, float temperature, uint64_t seed,
                             const int32_t *d_step, const int32_t *target, float *target_z, float *part, float *logits,
                             int64_t ld, hipStream_t st) {
-  int mbt = Mp / 32, MB = mbt >= 8 ? 8 : mbt, n_wg = lm_wgs(Np);
-  dim3 grid(n_wg, 1, mbt / MB), block(256);
-  const h16x8 *X = (const h16x8 *)Xp, *W = (const h16x8 *)Wp;
-#define LM_LAUNCH(MBV)                                                                                               \
-  hipLaunchKernelGGL((lmhead_kernel<MBV, LOGITS>), grid, block, 0, st, X, W, Mp, Np, Kp, V, temperature, seed, d_step, \
-                     target, target_z, part, n_wg, logits, ld)
-  switch (MB) {
-    case 1: LM_LAUNCH(1); break;
-    case 2: LM_LAUNCH(2); break;
-    case 4: LM_LAUNCH(4); break;
-    default: LM_LAUNCH(8); break;
-  }
-#undef LM_LAUNCH
+  int mbt = Mp / 32;
+#define LM_ARGS Xp, Wp, Mp, Np, Kp, V, temperature, seed, d_step, target, target_z, part, logits, ld, st
+  if (mbt >= 8) lmhead_launch<8, 2, LOGITS>(LM_ARGS);
+  else if (mbt == 4) lmhead_launch<4, 3, LOGITS>(LM_ARGS);
+  else if (mbt == 2) lmhead_launch<2, 3, LOGITS>(LM_ARGS);
+  else lmhead_launch<1, 3, LOGITS>(LM_ARGS);
+#undef LM_ARGS
 }
 
 void fast_lmhead_sample(int32_t *tok, float *lp, float *target_lp, const void *Xp, const void *Wp, int Mp, int M, int V,
