@@ -242,17 +242,13 @@ __device__ __forceinline__ void gemm_lds_mainloop(f32x16 (&acc)[MB], char *lds_r
   auto load_x = [&](int st, int c) {
 #pragma unroll
     for (int i = 0; i < XL; ++i) {
-      int idx = i * T + tid;
-      if (XU % T == 0 || idx < XU)
-        xr[st][i] = Xp[(int64_t)((c_begin + c) * KC * 2 + idx / ROWS) * Mp + mrow0 + idx % ROWS];
+      int idx = min(i * T + tid, XU - 1);   // surplus threads repeat the last unit: no divergent branch around a load
+      xr[st][i] = Xp[(int64_t)((c_begin + c) * KC * 2 + idx / ROWS) * Mp + mrow0 + idx % ROWS];
     }
   };
   auto store_x = [&](int st, int buf) {
 #pragma unroll
-    for (int i = 0; i < XL; ++i) {
-      int idx = i * T + tid;
-      if (XU % T == 0 || idx < XU) xs[buf * XU + idx] = xr[st][i];
-    }
+    for (int i = 0; i < XL; ++i) xs[buf * XU + min(i * T + tid, XU - 1)] = xr[st][i];
   };
   auto compute = [&](int st, int buf) {
     const u32x4v *bp = xs + buf * XU + (lane >> 5) * ROWS + (lane & 31);
@@ -268,7 +264,23 @@ __device__ __forceinline__ void gemm_lds_mainloop(f32x16 (&acc)[MB], char *lds_r
       if (s < nchunks) { load_x(s, s); load_a(s, s); }
     store_x(0, 0);
     __syncthreads();
-    for (int c0 = 0; c0 < nchunks; c0 += NSTAGE) {
+    // Steady state, NSTAGE chunks per trip, every load unconditional: the compiler's wait counts are then exact and
+    // the younger chunks stay in flight while a chunk is computed.  (Behind a condition a load may not have been
+    // issued, so the waits that follow assume it was not and drain the queue.)
+    int c0 = 0;
+    for (; c0 + 2 * NSTAGE - 2 < nchunks; c0 += NSTAGE) {
+#pragma unroll
+      for (int s = 0; s < NSTAGE; ++s) {
+        const int c = c0 + s;
+        load_x((s + NSTAGE - 1) % NSTAGE, c + NSTAGE - 1);
+        load_a((s + NSTAGE - 1) % NSTAGE, c + NSTAGE - 1);
+        compute(s, c & 1);
+        store_x((s + 1) % NSTAGE, (c + 1) & 1);
+        __syncthreads();
+      }
+    }
+    // the last chunks (fewer than 2*NSTAGE - 1), loads guarded
+    for (; c0 < nchunks; c0 += NSTAGE) {
 #pragma unroll
       for (int s = 0; s < NSTAGE; ++s) {
         const int c = c0 + s;
@@ -312,17 +324,13 @@ __global__ __launch_bounds__(WN * 64) void gemm_lds_kernel(void *out, const u32x
   auto load_x = [&](int st, int c) {
 #pragma unroll
     for (int i = 0; i < XL; ++i) {
-      int idx = i * T + tid;
-      if (XU % T == 0 || idx < XU)
-        xr[st][i] = Xp[(int64_t)((c_begin + c) * KC * 2 + idx / ROWS) * Mp + mrow0 + idx % ROWS];
+      int idx = min(i * T + tid, XU - 1);   // surplus threads repeat the last unit: no divergent branch around a load
+      xr[st][i] = Xp[(int64_t)((c_begin + c) * KC * 2 + idx / ROWS) * Mp + mrow0 + idx % ROWS];
     }
   };
   auto store_x = [&](int st, int buf) {
 #pragma unroll
-    for (int i = 0; i < XL; ++i) {
-      int idx = i * T + tid;
-      if (XU % T == 0 || idx < XU) xs[buf * XU + idx] = xr[st][i];
-    }
+    for (int i = 0; i < XL; ++i) xs[buf * XU + min(i * T + tid, XU - 1)] = xr[st][i];
   };
   auto compute = [&](int st, int buf) {
     const u32x4v *bp = xs + buf * XU + (lane >> 5) * ROWS + (lane & 31);
@@ -338,7 +346,23 @@ __global__ __launch_bounds__(WN * 64) void gemm_lds_kernel(void *out, const u32x
       if (s < nchunks) { load_x(s, s); load_a(s, s); }
     store_x(0, 0);
     __syncthreads();
-    for (int c0 = 0; c0 < nchunks; c0 += NSTAGE) {
+    // Steady state, NSTAGE chunks per trip, every load unconditional: the compiler's wait counts are then exact and
+    // the younger chunks stay in flight while a chunk is computed.  (Behind a condition a load may not have been
+    // issued, so the waits that follow assume it was not and drain the queue.)
+    int c0 = 0;
+    for (; c0 + 2 * NSTAGE - 2 < nchunks; c0 += NSTAGE) {
+#pragma unroll
+      for (int s = 0; s < NSTAGE; ++s) {
+        const int c = c0 + s;
+        load_x((s + NSTAGE - 1) % NSTAGE, c + NSTAGE - 1);
+        load_a((s + NSTAGE - 1) % NSTAGE, c + NSTAGE - 1);
+        compute(s, c & 1);
+        store_x((s + 1) % NSTAGE, (c + 1) & 1);
+        __syncthreads();
+      }
+    }
+    // the last chunks (fewer than 2*NSTAGE - 1), loads guarded
+    for (; c0 < nchunks; c0 += NSTAGE) {
 #pragma unroll
       for (int s = 0; s < NSTAGE; ++s) {
         const int c = c0 + s;
