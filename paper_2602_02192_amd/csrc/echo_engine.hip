@@ -51,7 +51,7 @@ struct Plan {
 
 constexpr int PREFILL_ROWS = 1024;   // rows per pass of prefill and of teacher-forced scoring
 constexpr size_t STAGE_BYTES = (size_t)64 << 20;
-constexpr int MAX_GRID_SPLIT = 8;
+constexpr int MAX_GRID_SPLIT = REDUCE_MAX_SPLIT;
 
 int pad_rows(int m) {  // 32 * pow2 up to 256, then multiples of 256
   int p = 32;

@@ -91,6 +91,7 @@ enum GemmEpilogue { EPI_PARTIAL = 0, EPI_SWIGLU = 1 };
 // out = Xp[Mp x Kp] * Wp[Np x Kp]^T.  EPI_PARTIAL: fp32 partials [nsplit][Mp][Np];
 // EPI_SWIGLU (rows alternate gate_f, up_f): silu(gate)*up -> half K8 [Mp][Np/2]; nsplit must be 1.
 struct GemmShape { int nsplit, waves_k, waves_n, nbw, lds, stages; };   // launch shape, see fast_gemm_pick
+constexpr int REDUCE_MAX_SPLIT = 12;   // most grid splits over K whose partials the reducing kernels sum
 constexpr int GEMM_K_PAD = 128;   // packed weights and K8 activations pad K to this (whole LDS chunks of 8 k-steps)
 void fast_gemm(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, GemmShape g, GemmEpilogue epi,
                hipStream_t st);

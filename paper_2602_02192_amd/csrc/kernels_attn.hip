@@ -10,6 +10,8 @@
 //   whose state lives in the lanes of each query-head column.  Per-wavefront and per-split partial (max, sum,
 //   acc) are merged in a fixed order (no atomics): by the workgroup through LDS, by attn_combine_kernel across
 //   splits.
+#include <type_traits>
+
 #include "echo_device.h"
 #include "echo_kernels.h"
 
@@ -140,8 +142,8 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[e][r] = 0.f;
 
-  for (; tile < ntiles; tile += ATT_WAVES) {
-    const bool more = tile + ATT_WAVES < ntiles;
+  auto step = [&](auto more_tag) {
+    constexpr bool more = decltype(more_tag)::value;
     // ---- S^T = K Q^T
     f32x16 s;
 #pragma unroll
@@ -200,7 +202,11 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
         o[e] = mfma_h16(__builtin_bit_cast(h16x8, rv[ks2 * NE + e]), __builtin_bit_cast(h16x8, pb), o[e]);
     }
     if (more) att_issue_v<HD>(rv, head, tile0 + tile + ATT_WAVES, lane);
-  }
+  };
+  // every tile but the wavefront's last requests its successor unconditionally: a load behind a condition would make
+  // the compiler's wait counts assume it was not issued, and the waits that follow would drain the queue
+  for (; tile + ATT_WAVES < ntiles; tile += ATT_WAVES) step(std::true_type{});
+  if (tile < ntiles) step(std::false_type{});
   // ---- the two lanes of a column add their sums; then the four wavefronts are folded in wavefront order
   l_run += __shfl_xor(l_run, 32, 64);
   {

@@ -6,9 +6,9 @@
 namespace echo {
 
 // grid M rows, block 1024.  h[m] = embed[token[m]]            (embed != null)
-//                           h[m] += sum_s partials[s][..][m]  (nsplit <= 8, summed in split order)
+//                           h[m] += sum_s partials[s][..][m]  (nsplit <= REDUCE_MAX_SPLIT, summed in split order)
 // then Xp[m] = half(h[m] * rsqrt(mean(h[m]^2) + eps) * gain).  d % 8 == 0, d <= 8192.
-// Every load of a thread (residual, up to 8 partials) is issued before the first use, so the kernel costs
+// Every load of a thread (residual, all partials) is issued before the first use, so the kernel costs
 // one memory round trip whatever the split count.
 constexpr int RN_THREADS = 1024;
 __global__ __launch_bounds__(RN_THREADS) void resid_norm_kernel(float *h, const uint16_t *embed, const int32_t *token,
@@ -23,9 +23,9 @@ __global__ __launch_bounds__(RN_THREADS) void resid_norm_kernel(float *h, const 
   for (int c = 0; c < 2; ++c) {
     int n4 = threadIdx.x + c * RN_THREADS;
     if (n4 >= d4) break;
-    f32x4 a, pp[8];
+    f32x4 a, pp[REDUCE_MAX_SPLIT];
 #pragma unroll
-    for (int s = 0; s < 8; ++s)
+    for (int s = 0; s < REDUCE_MAX_SPLIT; ++s)
       pp[s] = s < nsplit ? partials[((int64_t)s * Mp + m) * (Np >> 2) + n4] : f32x4{0.f, 0.f, 0.f, 0.f};
     if (embed) {
       if (tok >= 0) {
@@ -35,7 +35,7 @@ __global__ __launch_bounds__(RN_THREADS) void resid_norm_kernel(float *h, const 
       } else a = {0.f, 0.f, 0.f, 0.f};
     } else a = *(const f32x4 *)(h + (int64_t)m * d + n4 * 4);
 #pragma unroll
-    for (int s = 0; s < 8; ++s) a += pp[s];
+    for (int s = 0; s < REDUCE_MAX_SPLIT; ++s) a += pp[s];
     *(f32x4 *)(h + (int64_t)m * d + n4 * 4) = a;
     v[c] = a;
     ss += a[0] * a[0] + a[1] * a[1] + a[2] * a[2] + a[3] * a[3];
@@ -79,14 +79,14 @@ __global__ void qkv_post_kernel(const float *partials, int nsplit, int Np, int M
   bool is_q = j < Hq, is_k = !is_q && j < Hq + Hkv;
   if (!is_q && !rows.active[m]) return;
   int n0 = j * hd + i, n1 = n0 + half;
-  float a = 0.f, b = 0.f, pa[8], pb[8];
+  float a = 0.f, b = 0.f, pa[REDUCE_MAX_SPLIT], pb[REDUCE_MAX_SPLIT];
 #pragma unroll
-  for (int s = 0; s < 8; ++s) {   // nsplit <= 8; all loads issued before the sums
+  for (int s = 0; s < REDUCE_MAX_SPLIT; ++s) {   // all loads issued before the sums
     pa[s] = s < nsplit ? partials[((int64_t)s * Mp + m) * Np + n0] : 0.f;
     pb[s] = s < nsplit ? partials[((int64_t)s * Mp + m) * Np + n1] : 0.f;
   }
 #pragma unroll
-  for (int s = 0; s < 8; ++s) { a += pa[s]; b += pb[s]; }
+  for (int s = 0; s < REDUCE_MAX_SPLIT; ++s) { a += pa[s]; b += pb[s]; }
   if (is_q || is_k) {
     if (qk_norm) {
       float ss = wave_sum(a * a + b * b);

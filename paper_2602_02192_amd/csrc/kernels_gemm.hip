@@ -433,14 +433,14 @@ void fast_gemm_pick(int Np, int Kp, int Mp, int full_k, GemmShape *g) {
     const bool wide = Mp > 128;   // 256 batch rows per workgroup, Mp/256 workgroups per weight strip
     int total_chunks = ksteps / (wide ? GEMM_KC_WIDE : GEMM_KC_SMALL);
     g->lds = 1; g->nbw = 1; g->waves_k = 1;
-    if (full_k && !wide) { g->waves_n = 3; g->stages = 4; g->nsplit = 1; return; }
+    if (full_k && !wide) { g->waves_n = 3; g->stages = 3; g->nsplit = 1; return; }
     g->waves_n = wide || nblocks % 4 == 0 || nblocks > 96 ? 4 : 3;
     g->stages = wide ? 2 : 3;
     int strips = (nblocks + g->waves_n - 1) / g->waves_n * (wide ? Mp / 256 : 1);
     if (full_k) { g->nsplit = 1; return; }
-    int ns = (256 + strips / 2) / strips;
+    int ns = (240 + strips / 2) / strips;
     if (ns > total_chunks / 2) ns = total_chunks / 2;
-    if (ns > 8) ns = 8;
+    if (ns > 10) ns = 10;
     if (ns < 1) ns = 1;
     int cps = (total_chunks + ns - 1) / ns;
     g->nsplit = (total_chunks + cps - 1) / cps;
@@ -479,8 +479,7 @@ static void gemm_lds_dispatch(void *out, const void *Xp, const void *Wp, int Mp,
   int mb = Mp / 32;   // 1, 2, 4 or a multiple of 8
   if (mb >= 8) { gemm_lds_launch<8, 4, 2, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st); return; }
 #define LDS_CASE(MBV)                                                                                              \
-  if (g.waves_n == 3 && g.stages == 4) gemm_lds_launch<MBV, 3, 4, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st);     \
-  else if (g.waves_n == 3) gemm_lds_launch<MBV, 3, 3, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st);                 \
+  if (g.waves_n == 3) gemm_lds_launch<MBV, 3, 3, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st);                      \
   else gemm_lds_launch<MBV, 4, 3, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st)
   if (mb == 1) { LDS_CASE(1); }
   else if (mb == 2) { LDS_CASE(2); }
