@@ -5,6 +5,8 @@
 // Operand roles of v_mfma_f32_32x32x16_f16 here: A = 32 weight rows x 16 k, B = 16 k x 32 batch rows.
 // Lane l supplies A[row l%32][k 8*(l/32) .. +8] and B[k 8*(l/32) .. +8][col l%32]; it receives
 // D[row 8*g + 4*(l/32) + i][col l%32] in accumulator register 4*g + i (g, i in 0..3).
+#include <type_traits>
+
 #include "echo_device.h"
 #include "echo_kernels.h"
 
@@ -250,23 +252,44 @@ __device__ __forceinline__ void gemm_lds_mainloop(f32x16 (&acc)[MB], char *lds_r
 #pragma unroll
     for (int i = 0; i < XL; ++i) xs[buf * XU + min(i * T + tid, XU - 1)] = xr[st][i];
   };
+  // The B operands of GU k-steps are read from LDS in one batch ahead of their MFMAs: with one wavefront per SIMD
+  // nothing else hides the LDS latency, and a read issued right before each MFMA would expose it every time.
   auto compute = [&](int st, int buf) {
+    constexpr int GU = MB >= 8 ? 2 : (MB == 4 ? 4 : KC);
     const u32x4v *bp = xs + buf * XU + (lane >> 5) * ROWS + (lane & 31);
 #pragma unroll
-    for (int u = 0; u < KC; ++u)
+    for (int u0 = 0; u0 < KC; u0 += GU) {
+      u32x4v b[GU][MB];
 #pragma unroll
-      for (int j = 0; j < MB; ++j)
-        acc[j] = mfma_h16(a[st][u], __builtin_bit_cast(h16x8, bp[u * 2 * ROWS + j * 32]), acc[j]);
+      for (int u = 0; u < GU; ++u)
+#pragma unroll
+        for (int j = 0; j < MB; ++j) b[u][j] = bp[(u0 + u) * 2 * ROWS + j * 32];
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int u = 0; u < GU; ++u)
+#pragma unroll
+        for (int j = 0; j < MB; ++j) acc[j] = mfma_h16(a[st][u0 + u], __builtin_bit_cast(h16x8, b[u][j]), acc[j]);
+    }
   };
-  if (nchunks > 0) {
+  // Every load that the compiler sees behind a condition makes its wait counts assume the load was not issued, and
+  // the waits that follow drain the queue.  So the pipeline is written without conditions around loads: prologue,
+  // steady trips of NSTAGE chunks, and one straight-line tail per possible number of remaining chunks.
+  auto tail = [&](auto r_tag) {
+    constexpr int R = decltype(r_tag)::value;   // chunks left; chunk i of them sits in register stage i % NSTAGE
+    const int cb = nchunks - R;
 #pragma unroll
-    for (int s = 0; s < NSTAGE - 1; ++s)
-      if (s < nchunks) { load_x(s, s); load_a(s, s); }
+    for (int i = 0; i < R; ++i) {
+      if (i + NSTAGE - 1 < R) { load_x((i + NSTAGE - 1) % NSTAGE, cb + i + NSTAGE - 1); load_a((i + NSTAGE - 1) % NSTAGE, cb + i + NSTAGE - 1); }
+      compute(i % NSTAGE, (cb + i) & 1);
+      if (i + 1 < R) store_x((i + 1) % NSTAGE, (cb + i + 1) & 1);
+      __syncthreads();
+    }
+  };
+  if (nchunks >= NSTAGE - 1) {
+#pragma unroll
+    for (int s = 0; s < NSTAGE - 1; ++s) { load_x(s, s); load_a(s, s); }
     store_x(0, 0);
     __syncthreads();
-    // Steady state, NSTAGE chunks per trip, every load unconditional: the compiler's wait counts are then exact and
-    // the younger chunks stay in flight while a chunk is computed.  (Behind a condition a load may not have been
-    // issued, so the waits that follow assume it was not and drain the queue.)
     int c0 = 0;
     for (; c0 + 2 * NSTAGE - 2 < nchunks; c0 += NSTAGE) {
 #pragma unroll
@@ -279,8 +302,24 @@ __device__ __forceinline__ void gemm_lds_mainloop(f32x16 (&acc)[MB], char *lds_r
         __syncthreads();
       }
     }
-    // the last chunks (fewer than 2*NSTAGE - 1), loads guarded
-    for (; c0 < nchunks; c0 += NSTAGE) {
+    // NSTAGE-1 .. 2*NSTAGE-2 chunks are left and c0 is a multiple of NSTAGE, so their register stages are static
+    static_assert(NSTAGE >= 2 && NSTAGE <= 4, "one tail per remaining count");
+    switch (nchunks - c0) {
+      case 1: if (NSTAGE == 2) tail(std::integral_constant<int, 1>{}); break;
+      case 2: if (NSTAGE <= 3) tail(std::integral_constant<int, 2>{}); break;
+      case 3: if (NSTAGE >= 3) tail(std::integral_constant<int, 3>{}); break;
+      case 4: if (NSTAGE >= 3) tail(std::integral_constant<int, 4>{}); break;
+      case 5: if (NSTAGE == 4) tail(std::integral_constant<int, 5>{}); break;
+      case 6: if (NSTAGE == 4) tail(std::integral_constant<int, 6>{}); break;
+      default: break;
+    }
+  } else if (nchunks > 0) {   // a K range shorter than the pipeline: guarded loads
+#pragma unroll
+    for (int s = 0; s < NSTAGE - 1; ++s)
+      if (s < nchunks) { load_x(s, s); load_a(s, s); }
+    store_x(0, 0);
+    __syncthreads();
+    for (int c0 = 0; c0 < nchunks; c0 += NSTAGE) {
 #pragma unroll
       for (int s = 0; s < NSTAGE; ++s) {
         const int c = c0 + s;
@@ -288,7 +327,7 @@ __device__ __forceinline__ void gemm_lds_mainloop(f32x16 (&acc)[MB], char *lds_r
           if (c + NSTAGE - 1 < nchunks) { load_x((s + NSTAGE - 1) % NSTAGE, c + NSTAGE - 1); load_a((s + NSTAGE - 1) % NSTAGE, c + NSTAGE - 1); }
           compute(s, c & 1);
           if (c + 1 < nchunks) store_x((s + 1) % NSTAGE, (c + 1) & 1);
-          __syncthreads();   // chunk c+1 is visible; chunk c's buffer may be overwritten two iterations later
+          __syncthreads();
         }
       }
     }
@@ -332,23 +371,44 @@ __global__ __launch_bounds__(WN * 64) void gemm_lds_kernel(void *out, const u32x
 #pragma unroll
     for (int i = 0; i < XL; ++i) xs[buf * XU + min(i * T + tid, XU - 1)] = xr[st][i];
   };
+  // The B operands of GU k-steps are read from LDS in one batch ahead of their MFMAs: with one wavefront per SIMD
+  // nothing else hides the LDS latency, and a read issued right before each MFMA would expose it every time.
   auto compute = [&](int st, int buf) {
+    constexpr int GU = MB >= 8 ? 2 : (MB == 4 ? 4 : KC);
     const u32x4v *bp = xs + buf * XU + (lane >> 5) * ROWS + (lane & 31);
 #pragma unroll
-    for (int u = 0; u < KC; ++u)
+    for (int u0 = 0; u0 < KC; u0 += GU) {
+      u32x4v b[GU][MB];
 #pragma unroll
-      for (int j = 0; j < MB; ++j)
-        acc[j] = mfma_h16(a[st][u], __builtin_bit_cast(h16x8, bp[u * 2 * ROWS + j * 32]), acc[j]);
+      for (int u = 0; u < GU; ++u)
+#pragma unroll
+        for (int j = 0; j < MB; ++j) b[u][j] = bp[(u0 + u) * 2 * ROWS + j * 32];
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int u = 0; u < GU; ++u)
+#pragma unroll
+        for (int j = 0; j < MB; ++j) acc[j] = mfma_h16(a[st][u0 + u], __builtin_bit_cast(h16x8, b[u][j]), acc[j]);
+    }
   };
-  if (nchunks > 0) {
+  // Every load that the compiler sees behind a condition makes its wait counts assume the load was not issued, and
+  // the waits that follow drain the queue.  So the pipeline is written without conditions around loads: prologue,
+  // steady trips of NSTAGE chunks, and one straight-line tail per possible number of remaining chunks.
+  auto tail = [&](auto r_tag) {
+    constexpr int R = decltype(r_tag)::value;   // chunks left; chunk i of them sits in register stage i % NSTAGE
+    const int cb = nchunks - R;
 #pragma unroll
-    for (int s = 0; s < NSTAGE - 1; ++s)
-      if (s < nchunks) { load_x(s, s); load_a(s, s); }
+    for (int i = 0; i < R; ++i) {
+      if (i + NSTAGE - 1 < R) { load_x((i + NSTAGE - 1) % NSTAGE, cb + i + NSTAGE - 1); load_a((i + NSTAGE - 1) % NSTAGE, cb + i + NSTAGE - 1); }
+      compute(i % NSTAGE, (cb + i) & 1);
+      if (i + 1 < R) store_x((i + 1) % NSTAGE, (cb + i + 1) & 1);
+      __syncthreads();
+    }
+  };
+  if (nchunks >= NSTAGE - 1) {
+#pragma unroll
+    for (int s = 0; s < NSTAGE - 1; ++s) { load_x(s, s); load_a(s, s); }
     store_x(0, 0);
     __syncthreads();
-    // Steady state, NSTAGE chunks per trip, every load unconditional: the compiler's wait counts are then exact and
-    // the younger chunks stay in flight while a chunk is computed.  (Behind a condition a load may not have been
-    // issued, so the waits that follow assume it was not and drain the queue.)
     int c0 = 0;
     for (; c0 + 2 * NSTAGE - 2 < nchunks; c0 += NSTAGE) {
 #pragma unroll
@@ -361,8 +421,24 @@ __global__ __launch_bounds__(WN * 64) void gemm_lds_kernel(void *out, const u32x
         __syncthreads();
       }
     }
-    // the last chunks (fewer than 2*NSTAGE - 1), loads guarded
-    for (; c0 < nchunks; c0 += NSTAGE) {
+    // NSTAGE-1 .. 2*NSTAGE-2 chunks are left and c0 is a multiple of NSTAGE, so their register stages are static
+    static_assert(NSTAGE >= 2 && NSTAGE <= 4, "one tail per remaining count");
+    switch (nchunks - c0) {
+      case 1: if (NSTAGE == 2) tail(std::integral_constant<int, 1>{}); break;
+      case 2: if (NSTAGE <= 3) tail(std::integral_constant<int, 2>{}); break;
+      case 3: if (NSTAGE >= 3) tail(std::integral_constant<int, 3>{}); break;
+      case 4: if (NSTAGE >= 3) tail(std::integral_constant<int, 4>{}); break;
+      case 5: if (NSTAGE == 4) tail(std::integral_constant<int, 5>{}); break;
+      case 6: if (NSTAGE == 4) tail(std::integral_constant<int, 6>{}); break;
+      default: break;
+    }
+  } else if (nchunks > 0) {   // a K range shorter than the pipeline: guarded loads
+#pragma unroll
+    for (int s = 0; s < NSTAGE - 1; ++s)
+      if (s < nchunks) { load_x(s, s); load_a(s, s); }
+    store_x(0, 0);
+    __syncthreads();
+    for (int c0 = 0; c0 < nchunks; c0 += NSTAGE) {
 #pragma unroll
       for (int s = 0; s < NSTAGE; ++s) {
         const int c = c0 + s;
@@ -370,7 +446,7 @@ __global__ __launch_bounds__(WN * 64) void gemm_lds_kernel(void *out, const u32x
           if (c + NSTAGE - 1 < nchunks) { load_x((s + NSTAGE - 1) % NSTAGE, c + NSTAGE - 1); load_a((s + NSTAGE - 1) % NSTAGE, c + NSTAGE - 1); }
           compute(s, c & 1);
           if (c + 1 < nchunks) store_x((s + 1) % NSTAGE, (c + 1) & 1);
-          __syncthreads();   // chunk c+1 is visible; chunk c's buffer may be overwritten two iterations later
+          __syncthreads();
         }
       }
     }
@@ -435,7 +511,7 @@ void fast_gemm_pick(int Np, int Kp, int Mp, int full_k, GemmShape *g) {
     g->lds = 1; g->nbw = 1; g->waves_k = 1;
     if (full_k && !wide) { g->waves_n = 3; g->stages = 3; g->nsplit = 1; return; }
     g->waves_n = wide || nblocks % 4 == 0 || nblocks > 96 ? 4 : 3;
-    g->stages = wide ? 2 : 3;
+    g->stages = 2;   // deeper register pipelines measured no faster once the wait counts are exact
     int strips = (nblocks + g->waves_n - 1) / g->waves_n * (wide ? Mp / 256 : 1);
     if (full_k) { g->nsplit = 1; return; }
     int ns = (240 + strips / 2) / strips;
@@ -480,7 +556,7 @@ static void gemm_lds_dispatch(void *out, const void *Xp, const void *Wp, int Mp,
   if (mb >= 8) { gemm_lds_launch<8, 4, 2, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st); return; }
 #define LDS_CASE(MBV)                                                                                              \
   if (g.waves_n == 3) gemm_lds_launch<MBV, 3, 3, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st);                      \
-  else gemm_lds_launch<MBV, 4, 3, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st)
+  else gemm_lds_launch<MBV, 4, 2, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st)
   if (mb == 1) { LDS_CASE(1); }
   else if (mb == 2) { LDS_CASE(2); }
   else { LDS_CASE(4); }
