@@ -17,6 +17,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of the decode-attention kernel (profiles/pmc_traffic_*.md), scaled by the same
+# counters on a plain 256 MiB copy: KiB fetched + written per launch over the K/V KiB the launch had to read.  Taken at the
+# same kernel, grid and shapes on a 2-layer model (the profiler crashes on the 36-layer process); set to None whenever
+# attn_splitk_kernel changes.
+ATTN_TRAFFIC_OVER_ALGORITHMIC = (143951.0 + 512.0) / 139264.0
 
 WORKLOADS = {
     # name: (shape attr, prompts, G, prompt_len, max_new)
@@ -69,6 +74,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--ctx-pad", type=int, default=0, help="extra KV-cache tokens per sequence beyond prompt + max_new")
+    ap.add_argument("--pageable-blob", action="store_true",
+                    help="keep the host copy of the weights in pageable memory (a counter-collecting profiler crashed on the pinned copy)")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch decode steps kernel by kernel (counter collection cannot follow graph replays)")
     a = ap.parse_args()
@@ -83,8 +90,11 @@ def main():
     N = P * G
     torch.cuda.set_device(0)
     blob_dev = synth.make_weights(shape, 0, device="cuda")
-    blob = torch.empty(blob_dev.shape, dtype=blob_dev.dtype, pin_memory=True)
-    blob.copy_(blob_dev)
+    if a.pageable_blob:
+        blob = blob_dev.cpu()
+    else:
+        blob = torch.empty(blob_dev.shape, dtype=blob_dev.dtype, pin_memory=True)
+        blob.copy_(blob_dev)
     del blob_dev
     torch.cuda.empty_cache()
     prompts, lens = synth.make_prompts(shape.vocab, P, plen, seed=1)
@@ -123,7 +133,9 @@ def main():
             ach = per_launch_bytes / per_launch_s / 1e9
             roofline = {"bound": "hbm", "kernel": "attn_splitk_kernel (decode attention, one launch per layer)",
                         "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-                        "traffic": None, "launches_timed": int(st.attn_launches),
+                        "traffic": (per_launch_bytes * ATTN_TRAFFIC_OVER_ALGORITHMIC
+                                    if ATTN_TRAFFIC_OVER_ALGORITHMIC else None),
+                        "traffic_unit": "bytes per launch (counter ratio 1.037 x algorithmic bytes)", "launches_timed": int(st.attn_launches),
                         "avg_launch_us": per_launch_s * 1e6, "bytes_per_launch": per_launch_bytes}
             if st.gemm_launches:
                 g = st.gemm_bytes / (st.gemm_ms * 1e-3) / 1e9

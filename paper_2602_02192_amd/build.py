@@ -11,6 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libecho_hip.so")
+CLIENT = os.path.join(HERE, "echo_client")   # the C-ABI client without Python (csrc/echo_client.cpp)
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -49,6 +50,8 @@ def build(force: bool = True) -> str:
     with ThreadPoolExecutor(max_workers=6) as ex:
         objs = list(ex.map(lambda n: _compile(n, force), sources()))
     subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
+    subprocess.check_call(["hipcc", "-O2", "-std=c++17", "-fopenmp", "-Wno-unused-result", os.path.join(CSRC, "echo_client.cpp"), "-o", CLIENT,
+                           "-L" + HERE, "-lecho_hip", "-Wl,-rpath,$ORIGIN"])
     return LIB
 
 
