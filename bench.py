@@ -24,24 +24,29 @@ HBM_PEAK_GBS = 8000.0
 ATTN_TRAFFIC_OVER_ALGORITHMIC = (143951.0 + 512.0) / 139264.0
 
 WORKLOADS = {
-    # name: (shape attr, prompts, G, prompt_len, max_new)
-    "tiny-fp32": ("TINY", 4, 2, 16, 32),
-    "dense4b-64x512+1024": ("DENSE_4B", 8, 8, 512, 1024),
-    "dense8b-128x512+2048": ("DENSE_8B", 16, 8, 512, 2048),
+    # name: shape, prompts, G, prompt_len, max_new [, stop = (lo, hi) per-sequence stop lengths, swap_every = decode
+    # steps between snapshot swaps, score = teacher-forced log-prob pass over all generated strings afterwards]
+    "tiny-fp32": dict(shape="TINY", P=4, G=2, plen=16, max_new=32),
+    "dense4b-64x512+1024": dict(shape="DENSE_4B", P=8, G=8, plen=512, max_new=1024),
+    "dense4b-kvheavy-256x1024+4096": dict(shape="DENSE_4B", P=32, G=8, plen=1024, max_new=4096, stop=(512, 4096)),
+    "dense8b-128x512+2048-swap256": dict(shape="DENSE_8B", P=16, G=8, plen=512, max_new=2048, swap_every=256),
+    "dense32b-64x1024+4096-score": dict(shape="DENSE_32B", P=8, G=8, plen=1024, max_new=4096, score=True),
 }
 
 
-def algorithmic_bytes(shape, n_seqs, prompt_len, max_new):
+def algorithmic_bytes(shape, gen_lens, prompt_len):
     """HBM bytes the decode steps must move: all decode-read weights once per step, every active
-    sequence's K/V once per step, and the new K/V written."""
+    sequence's K/V once per step, and the new K/V written.  gen_lens: tokens generated per sequence."""
     e = 2 if shape.dtype == "bf16" else 4
     hd, H = shape.head_dim, shape.hidden
     per_layer = H * (shape.n_q_heads + 2 * shape.n_kv_heads) * hd + shape.n_q_heads * hd * H + 3 * H * shape.ffn
     w_dec = (shape.n_layers * per_layer + shape.vocab * H) * e
     kvb = 2 * shape.n_layers * shape.n_kv_heads * hd * e
-    total = 0
-    for s in range(1, max_new):          # decode pass s reads prompt_len + s keys per sequence
-        total += w_dec + n_seqs * (prompt_len + s) * kvb + n_seqs * kvb
+    gen = np.asarray(gen_lens, np.int64)
+    steps = int(gen.max())
+    active = np.array([(gen > s).sum() for s in range(1, steps)], np.int64)   # decode pass s serves sequences with gen > s
+    s_idx = np.arange(1, steps, dtype=np.int64)
+    total = int((w_dec + active * (prompt_len + s_idx) * kvb + active * kvb).sum())
     return total, w_dec, kvb
 
 
@@ -85,47 +90,105 @@ def main():
     import torch
     from paper_2602_02192_amd import echo, synth
 
-    name, P, G, plen, max_new = WORKLOADS[a.workload]
+    wl = WORKLOADS[a.workload]
+    name, P, G, plen, max_new = wl["shape"], wl["P"], wl["G"], wl["plen"], wl["max_new"]
     shape = getattr(synth, name)
     N = P * G
     torch.cuda.set_device(0)
-    blob_dev = synth.make_weights(shape, 0, device="cuda")
-    if a.pageable_blob:
-        blob = blob_dev.cpu()
-    else:
-        blob = torch.empty(blob_dev.shape, dtype=blob_dev.dtype, pin_memory=True)
-        blob.copy_(blob_dev)
-    del blob_dev
-    torch.cuda.empty_cache()
+
+    def host_blob(seed):
+        dev = synth.make_weights(shape, seed, device="cuda")
+        if a.pageable_blob:
+            host = dev.cpu()
+        else:
+            host = torch.empty(dev.shape, dtype=dev.dtype, pin_memory=True)
+            host.copy_(dev)
+        del dev
+        torch.cuda.empty_cache()
+        return host
+
+    blob = host_blob(0)
+    swap_every = wl.get("swap_every")
+    blob_b = host_blob(10) if swap_every else None
     prompts, lens = synth.make_prompts(shape.vocab, P, plen, seed=1)
-    ctx = echo.Context(echo.desc_from_shape(shape, N, plen + max_new + a.ctx_pad))
+    stop = synth.make_stop_lens(N, wl["stop"][0], wl["stop"][1], seed=3) if wl.get("stop") else None
+    swaps = list(range(swap_every, max_new, swap_every)) if swap_every else []
+    ctx = echo.Context(echo.desc_from_shape(shape, N, plen + max_new + a.ctx_pad, n_weight_slots=2 if swap_every else 1))
     t0 = time.perf_counter()
     ctx.load_policy(0, blob)
     load_s = time.perf_counter() - t0
+    version = [0]
+
+    def rollout(seed, **kw):
+        """One rollout; with a swap schedule a second thread installs the next snapshot (alternating two weight
+        sets) as soon as the previous one has been switched in, as a worker's receiver thread would."""
+        if not swaps:
+            return ctx.rollout(prompts, lens, G, max_new, 1.0, seed, stop_lens=stop, no_graph=a.no_graph, **kw)
+        import threading
+        done = threading.Event()
+
+        def feeder():
+            for j in range(len(swaps)):
+                while not done.is_set():
+                    st = ctx.stats()
+                    if st.rollout_running and st.staged_version < 0:
+                        break
+                    time.sleep(0.002)
+                if done.is_set():
+                    return
+                version[0] += 1
+                ctx.load_policy(version[0], blob_b if version[0] % 2 else blob)
+
+        th = threading.Thread(target=feeder)
+        th.start()
+        try:
+            return ctx.rollout(prompts, lens, G, max_new, 1.0, seed, stop_lens=stop, swap_at_step=swaps, swap_timeout_ms=60000,
+                               no_graph=a.no_graph, **kw)
+        finally:
+            done.set()
+            th.join()
 
     for _ in range(a.warmup):
-        ctx.rollout(prompts, lens, G, max_new, 1.0, 2, no_graph=a.no_graph)
+        rollout(2)
     torch.cuda.synchronize()
-    times, toks, decode_ms, prefill_ms = [], 0, [], []
+    times, toks, decode_ms, prefill_ms, swap_wait_ms = [], 0, [], [], []
     t_all = time.perf_counter()
     for k in range(a.steps):
         t0 = time.perf_counter()
-        out = ctx.rollout(prompts, lens, G, max_new, 1.0, 2 + k, no_graph=a.no_graph)
+        out = rollout(2 + k)
         times.append(time.perf_counter() - t0)
         toks += int(out["lens"].sum())
         st = ctx.stats()
         decode_ms.append(st.decode_ms)
         prefill_ms.append(st.prefill_ms)
+        swap_wait_ms.append(st.swap_wait_ms)
     torch.cuda.synchronize()
     total_s = time.perf_counter() - t_all
     value = toks / total_s
 
-    bytes_decode, w_dec, kvb = algorithmic_bytes(shape, N, plen, max_new)
+    bytes_decode, w_dec, kvb = algorithmic_bytes(shape, out["lens"], plen)
     step_frac = bytes_decode / (np.mean(decode_ms) * 1e-3) / (HBM_PEAK_GBS * 1e9)
+    n_decode_steps = max(1, int(out["lens"].max()) - 1)
+
+    score = None
+    if wl.get("score"):       # teacher-forced log-probs of every generated string (prompt + response) under the active snapshot
+        full = np.concatenate([np.repeat(prompts, G, axis=0), np.maximum(out["tokens"], 0)], axis=1)
+        flen = (plen + out["lens"]).astype(np.int32)
+        t0 = time.perf_counter()
+        lp = ctx.logprobs(full, flen, 1.0)
+        score_s = time.perf_counter() - t0
+        hd, H = shape.head_dim, shape.hidden
+        per_layer = H * (shape.n_q_heads + 2 * shape.n_kv_heads) * hd + shape.n_q_heads * hd * H + 3 * H * shape.ffn
+        rows = int((flen - 1).sum())
+        flops = 2.0 * rows * (shape.n_layers * per_layer + shape.vocab * H)
+        m = np.arange(max_new)[None, :] < out["lens"][:, None]
+        dev = float(np.abs(lp[:, plen:][m] - out["logprobs"][m]).max())
+        score = {"rows": rows, "seconds": score_s, "gemm_tflops": flops / score_s / 1e12, "mfma_frac_of_2.5PFLOPs": flops / score_s / 2.5e15,
+                 "max_abs_diff_vs_sampler_logprobs": dev}
 
     roofline = None
     if not a.no_kernel_timing:
-        ctx.rollout(prompts, lens, G, max_new, 1.0, 2, time_kernels=True)
+        rollout(2, time_kernels=True)
         st = ctx.stats()
         if st.attn_launches:
             per_launch_bytes = st.attn_bytes / st.attn_launches
@@ -143,7 +206,7 @@ def main():
                                                   "avg_launch_us": st.gemm_ms * 1e3 / st.gemm_launches,
                                                   "launches_timed": int(st.gemm_launches)}
     cpu = None
-    if not a.no_cpu_baseline:
+    if not a.no_cpu_baseline and blob.numel() < 6e9:   # the oracle needs an fp32 copy of the weights: 4B-class and smaller
         cpu = cpu_baseline(shape, blob)
     ctx.close()
     line = {
@@ -152,10 +215,13 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16 MFMA operands, f32 accumulate (bf16 weights)" if shape.dtype == "bf16" else "f32", "data": "synthetic (random N(0,0.02) weights, uniform random prompt tokens)",
         "config": {"workload": a.workload, "model": name, "sequences": N, "prompts": P, "group": G,
-                   "prompt_len": plen, "max_new": max_new, "temperature": 1.0},
-        "decode_step": {"mean_ms": float(np.mean(decode_ms)) / max(1, max_new - 1),
+                   "prompt_len": plen, "max_new": max_new, "temperature": 1.0,
+                   "stop_lens": list(wl["stop"]) if wl.get("stop") else None},
+        "decode_step": {"mean_ms": float(np.mean(decode_ms)) / n_decode_steps,
                         "hbm_frac_of_8TBps": step_frac, "algorithmic_bytes_per_rollout": bytes_decode,
-                        "prefill_ms": float(np.mean(prefill_ms)), "policy_install_s": load_s},
+                        "prefill_ms": float(np.mean(prefill_ms)), "policy_install_s": load_s,
+                        "swaps_per_rollout": len(swaps), "swap_wait_ms": float(np.mean(swap_wait_ms))},
+        "scoring_pass": score,
         "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(line))
