@@ -44,12 +44,12 @@ struct Plan {
   size_t slot_bytes, o_slot[2], o_kv, kv_bytes;
   size_t o_h, o_x, o_qkv, o_att, o_gu, o_ff, o_logits, o_q16, o_xa, o_xatt, o_xff, o_part, o_rope, o_lmpart;
   size_t o_attn_o, o_attn_ml;
-  size_t o_rows, o_seq, o_samp, o_out_tok, o_out_lp, o_out_ver, o_forced, o_scal, o_first_h, o_stage, o_maps;
-  size_t stage_bytes, part_floats, total;
+  size_t o_blocks, o_rows, o_seq, o_samp, o_out_tok, o_out_lp, o_out_ver, o_forced, o_scal, o_first_h, o_stage, o_maps;
+  size_t stage_bytes, part_floats, logit_rows = 0, total;
   int attn_chunk, attn_max_splits;
 };
 
-constexpr int PREFILL_ROWS = 1024;   // rows per pass of prefill and of teacher-forced scoring
+constexpr int PREFILL_ROWS = 4096;   // rows per pass of prefill and of teacher-forced scoring
 constexpr size_t STAGE_BYTES = (size_t)64 << 20;
 constexpr int MAX_GRID_SPLIT = REDUCE_MAX_SPLIT;
 
@@ -77,7 +77,7 @@ bool valid_desc(const echo_model_desc *d, std::string *why) {
   if (fast) {
     if (d->hidden % 16 || d->ffn % 16 || (d->n_q_heads * d->head_dim) % 16) return bad("bf16 path needs hidden, ffn and Hq*head_dim multiples of 16");
     if (d->hidden > 8192) return bad("bf16 path needs hidden <= 8192");
-    if (d->head_dim % 64) return bad("bf16 path needs head_dim a multiple of 64");
+    if (d->head_dim != 64 && d->head_dim != 128) return bad("bf16 path needs head_dim 64 or 128");
     int grp = d->n_q_heads / d->n_kv_heads;
     if (grp > 8 || (grp & (grp - 1))) return bad("bf16 path needs Hq/Hkv in {1,2,4,8}");
   }
@@ -113,23 +113,25 @@ Plan make_plan(const echo_model_desc *d) {
   int64_t ctx_cap = p.fast ? round_up(d->max_ctx, 32) : d->max_ctx;   // the tiled cache holds whole tiles of 32 keys
   p.kv_bytes = (size_t)d->max_seqs * d->n_layers * 2 * d->n_kv_heads * ctx_cap * hd * kv_elt;
   p.o_kv = b.take(p.kv_bytes);
-  size_t M = p.Mcap;
+  size_t M = p.Mcap, Md = pad_rows(d->max_seqs);   // rows of a prefill / scoring pass, rows of a decode step
   p.o_h = b.take(M * H * 4);
   p.o_first_h = b.take((size_t)d->max_seqs * H * 4);
-  p.o_logits = b.take(M * (size_t)p.Np_v * 4);
+  p.logit_rows = p.fast ? Md : M;   // the MFMA path never writes logits of a scoring pass
+  p.o_logits = b.take(p.logit_rows * (size_t)p.Np_v * 4);
   p.o_rope = b.take(M * hd * 4);
   if (p.fast) {
     p.o_xa = b.take(M * p.Kp_d * 2);
     p.o_xatt = b.take(M * p.Kp_q * 2);
     p.o_xff = b.take(M * p.Kp_f * 2);
     p.o_q16 = b.take(M * Q * 2);
-    p.part_floats = (size_t)MAX_GRID_SPLIT * std::max(p.Np_qkv, p.Np_d) * M;
+    // split-K partials: every split count the reducers take for a decode step, fewer for the long passes
+    p.part_floats = std::max((size_t)MAX_GRID_SPLIT * Md, (size_t)2 * M) * std::max(p.Np_qkv, p.Np_d);
     p.o_part = b.take(p.part_floats * 4);
     p.o_lmpart = b.take(fast_lmhead_partial_floats(p.Np_v, (int)M) * 4);
     p.attn_chunk = 32;
     p.attn_max_splits = 32;   // partial-buffer capacity in splits per (row, head)
-    p.o_attn_o = b.take(M * d->n_q_heads * (size_t)p.attn_max_splits * hd * 4);
-    p.o_attn_ml = b.take(M * d->n_q_heads * (size_t)p.attn_max_splits * 2 * 4);
+    p.o_attn_o = b.take(Md * d->n_q_heads * (size_t)p.attn_max_splits * hd * 4);   // decode rows only
+    p.o_attn_ml = b.take(Md * d->n_q_heads * (size_t)p.attn_max_splits * 2 * 4);
     p.stage_bytes = STAGE_BYTES;
     p.o_stage = b.take(p.stage_bytes);
   } else {
@@ -139,6 +141,7 @@ Plan make_plan(const echo_model_desc *d) {
     p.o_gu = b.take(M * 2 * F * 4);
     p.o_ff = b.take(M * F * 4);
   }
+  p.o_blocks = b.take(M * sizeof(PrefillBlock));   // at worst every row of a pass is a block of its own
   p.o_rows = b.take(4 * M * 4);
   p.o_maps = b.take(2 * M * 4 + (size_t)d->max_seqs * 4);
   p.o_seq = b.take(3 * (size_t)d->max_seqs * 4);
@@ -316,6 +319,10 @@ void gemm_fast(echo_ctx *c, void *out, const void *Xp, const void *Wp, int Mp, i
   GemmShape g;
   fast_gemm_pick(Np, Kp, Mp, epi == EPI_SWIGLU, &g);
   if (g.nsplit > MAX_GRID_SPLIT) g.nsplit = MAX_GRID_SPLIT;
+  if (epi == EPI_PARTIAL) {   // the partial buffer holds part_floats
+    int room = (int)(c->p.part_floats / ((size_t)Np * Mp));
+    if (g.nsplit > room) g.nsplit = room;
+  }
   {
     TimerScope t(c, &c->ev_gemm);
     fast_gemm(out, Xp, Wp, Mp, Np, Kp, g, epi, c->cs);
@@ -324,7 +331,7 @@ void gemm_fast(echo_ctx *c, void *out, const void *Xp, const void *Wp, int Mp, i
   if (nsplit_out) *nsplit_out = g.nsplit;
 }
 
-void forward_layers(echo_ctx *c, const Slot &S, int M, bool use_splitk_attn) {
+void forward_layers(echo_ctx *c, const Slot &S, int M, bool use_splitk_attn, int n_prefill_blocks = 0) {
   const echo_model_desc &d = c->d;
   const Plan &p = c->p;
   hipStream_t st = c->cs;
@@ -361,7 +368,9 @@ void forward_layers(echo_ctx *c, const Slot &S, int M, bool use_splitk_attn) {
     fast_qkv_post(part, ns, p.Np_qkv, Mp, q16, L.q_norm, L.k_norm, d.qk_norm, d.rms_eps, rope, c->rows, c->kv, l, M, Hq, Hkv, st);
     {
       TimerScope t(c, &c->ev_attn);
-      if (use_splitk_attn)
+      if (n_prefill_blocks > 0)
+        fast_attention_prefill(xatt, q16, at<PrefillBlock>(c, p.o_blocks), n_prefill_blocks, c->kv, l, Mp, Hq, Hkv, st);
+      else if (use_splitk_attn)
         fast_attention(xatt, q16, c->rows, c->kv, l, M, Mp, Hq, Hkv, fast_attention_splits(M, Hkv, p.attn_max_splits),
                        at<float>(c, p.o_attn_o), at<float>(c, p.o_attn_ml), st);
       else
@@ -430,7 +439,9 @@ int run_chunks(echo_ctx *c, const Slot &S, const int32_t *tokens, int stride, co
     for (int t = 0; t < lens[q]; ++t) all.push_back({tokens[(int64_t)q * stride + t], (int32_t)(q * slot_step), t});
   int R = std::min(PREFILL_ROWS, c->p.Mcap);
   std::vector<int32_t> tok(R), slot(R), pos(R), act(R);
-  bool splitk = !env_flag("ECHO_ATTN_SIMPLE");
+  std::vector<PrefillBlock> blocks;
+  const int block_rows = ATT_PREFILL_COLS / (c->d.n_q_heads / c->d.n_kv_heads);
+  bool splitk = !env_flag("ECHO_ATTN_SIMPLE"), causal_blocks = c->p.fast && splitk;
   for (size_t a = 0; a < all.size(); a += R) {
     int M = (int)std::min<size_t>(R, all.size() - a);
     for (int i = 0; i < M; ++i) { tok[i] = all[a + i].token; slot[i] = all[a + i].slot; pos[i] = all[a + i].pos; act[i] = 1; }
@@ -438,8 +449,18 @@ int run_chunks(echo_ctx *c, const Slot &S, const int32_t *tokens, int stride, co
     HIPCHK(c, hipMemcpyAsync(c->rows.slot, slot.data(), M * 4, hipMemcpyHostToDevice, c->cs));
     HIPCHK(c, hipMemcpyAsync(c->rows.pos, pos.data(), M * 4, hipMemcpyHostToDevice, c->cs));
     HIPCHK(c, hipMemcpyAsync(c->rows.active, act.data(), M * 4, hipMemcpyHostToDevice, c->cs));
+    blocks.clear();
+    if (causal_blocks) {   // runs of consecutive positions of one slot, cut every block_rows rows
+      for (int i = 0; i < M; ++i) {
+        bool extend = !blocks.empty() && blocks.back().nrows < block_rows && blocks.back().slot == slot[i] &&
+                      blocks.back().pos0 + blocks.back().nrows == pos[i];
+        if (extend) ++blocks.back().nrows; else blocks.push_back({i, 1, slot[i], pos[i]});
+      }
+      HIPCHK(c, hipMemcpyAsync(at<PrefillBlock>(c, c->p.o_blocks), blocks.data(), blocks.size() * sizeof(PrefillBlock),
+                               hipMemcpyHostToDevice, c->cs));
+    }
     HIPCHK(c, hipStreamSynchronize(c->cs));  // the host vectors are reused by the next chunk
-    forward_layers(c, S, M, splitk);
+    forward_layers(c, S, M, splitk, (int)blocks.size());
     int rc = after(&all[a], M);
     if (rc) return rc;
   }
@@ -526,8 +547,10 @@ int echo_init(const echo_model_desc *desc, int device, void *dev_arena, size_t a
   int32_t *mp = at<int32_t>(c, p.o_maps);
   c->d_map_a = mp; c->d_map_b = mp + M; c->d_plen_p = mp + 2 * M;
   c->d_step = at<int32_t>(c, p.o_scal); c->d_n_active = c->d_step + 1;
-  // activations, row state and scratch start from zero (padding rows and columns are never written)
-  size_t zero_from = p.o_h;
+  // activations, row state and scratch start from zero (padding rows and columns are never written); so does the
+  // KV cache: the keys of a sequence's last tile that lie beyond its length get weight zero, which only cancels
+  // a finite value
+  size_t zero_from = p.o_kv;
   if ((e = hipMemsetAsync(c->arena + zero_from, 0, p.total - zero_from, c->cs)) != hipSuccess) return bail("hipMemsetAsync", e);
   if ((e = hipStreamSynchronize(c->cs)) != hipSuccess) return bail("hipStreamSynchronize", e);
   *out = c;
@@ -806,7 +829,7 @@ int echo_logprobs(echo_ctx *c, const int32_t *tokens, int32_t stride, const int3
 
 int echo_debug_draw_bits(echo_ctx *c, uint64_t seed, uint32_t n, uint32_t s, uint32_t i0, int32_t count, uint32_t *out_bits) {
   if (!c || !out_bits || count < 1) return c ? fail(c, ECHO_EINVAL, "bad argument") : ECHO_EINVAL;
-  size_t cap = c->p.Mcap * (size_t)c->p.Np_v;  // the logits buffer is borrowed as scratch
+  size_t cap = c->p.logit_rows * (size_t)c->p.Np_v;  // the logits buffer is borrowed as scratch
   if ((size_t)count > cap) return fail(c, ECHO_EINVAL, "count exceeds %zu", cap);
   {
     std::lock_guard<std::mutex> lk(c->mu);

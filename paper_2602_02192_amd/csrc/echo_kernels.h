@@ -107,7 +107,15 @@ void fast_attention_simple(void *Xp_out, const void *q_h16, RowState rows, KvGeo
 void fast_attention(void *Xp_out, const void *q_h16, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq,
                     int Hkv, int nsplit, float *part_o, float *part_ml, hipStream_t st);
 int fast_attention_splits(int M, int Hkv, int max_splits);
-// lm_head with the sampler fused into the epilogue (partials per workgroup) + the combine kernel.
+// Causal attention for runs of consecutive positions (prefill, teacher-forced scoring).  A block is up to
+// ATT_PREFILL_COLS / (Hq/Hkv) rows m0 .. m0 + nrows - 1 holding positions pos0 .. of one cache slot, whose keys
+// and values (positions 0 .. pos0 + nrows - 1) are already in the cache.  The blocks must cover every row once.
+struct PrefillBlock { int32_t m0, nrows, slot, pos0; };
+constexpr int ATT_PREFILL_COLS = 64;    // (row, query head) pairs of one KV head that one wavefront carries
+void fast_attention_prefill(void *Xp_out, const void *q_h16, const PrefillBlock *blocks, int nblocks, KvGeom kv, int layer,
+                            int Mp, int Hq, int Hkv, hipStream_t st);
+// lm_head with the sampler fused into the epilogue (partials per workgroup) + the combine kernel.  With `target` set
+// (scoring) only target_lp is meaningful: no noise is drawn and tok / lp describe the plain argmax.
 void fast_lmhead_sample(int32_t *tok, float *lp, float *target_lp, const void *Xp, const void *Wp, int Mp, int M,
                         int V, int Np, int Kp, float temperature, uint64_t seed, const int32_t *d_step,
                         const int32_t *row_active, const int32_t *target, float *partials, hipStream_t st);

@@ -288,6 +288,151 @@ static void attention_launch(void *Xp_out, const void *q_h16, RowState rows, KvG
   }
 }
 
+// ---- causal kernel for runs of consecutive positions ---------------------------------------------------
+// grid (blocks, Hkv), one wavefront per workgroup.  The wavefront carries NQ tiles of 32 columns, a column being a
+// (row, query head of the KV head's group) pair: column index t*32 + col = row_in_block * grp + head.  Every K / V
+// tile of the slot is streamed once into A-operand registers and used by all NQ column tiles (same MFMA roles as the
+// split-K kernel), so the cache traffic per row falls by the block height.  The queries wait in LDS as B operands,
+// each lane reading back exactly the units it wrote.  Keys after a column's own position are masked; only the tiles
+// that reach past the block's first position need the mask.
+template <int HD, int NQ>
+__global__ __launch_bounds__(64, 2) void attn_prefill_kernel(uint16_t *__restrict__ Xp, int Mp, const uint16_t *__restrict__ q_h16,
+                                                          const PrefillBlock *__restrict__ blocks, KvGeom kv, int layer, int Hq,
+                                                          int Hkv) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  constexpr int KS = HD / 16, NE = HD / 32;
+  const PrefillBlock b = blocks[blockIdx.x];
+  const int kvh = blockIdx.y, grp = Hq / Hkv, lane = threadIdx.x, half = lane >> 5, col = lane & 31;
+  const v4u *head = (const v4u *)((const uint16_t *)kv.base + kv.tiled_head_off(b.slot, layer, kvh));
+  const int n_keys = b.pos0 + b.nrows, ntiles = (n_keys + ATT_TILE - 1) / ATT_TILE;
+  v4u rk[KS], rv[KS];
+  att_issue_k<HD>(rk, head, 0, lane);
+  att_issue_v<HD>(rv, head, 0, lane);
+
+  v4u *qs = (v4u *)lds + lane;   // unit (t*KS + ks)*64 + lane: dims ks*16 + half*8 .. +8 of column t*32 + col
+  int pcol[NQ];                  // the column's position; a column beyond the block's rows is all zero and unmasked
+#pragma unroll
+  for (int t = 0; t < NQ; ++t) pcol[t] = (t * 32 + col) / grp < b.nrows ? b.pos0 + (t * 32 + col) / grp : 0x7fffffff;
+#pragma unroll 1
+  for (int t = 0; t < NQ; ++t) {
+    const int idx = t * 32 + col, r = idx / grp, hh = idx % grp;
+    const bool valid = r < b.nrows;
+    const uint16_t *src = q_h16 + ((int64_t)(b.m0 + (valid ? r : 0)) * Hq + kvh * grp + hh) * HD + half * 8;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qs[(t * KS + ks) * 64] = valid ? *(const v4u *)(src + ks * 16) : v4u{0u, 0u, 0u, 0u};
+  }
+
+  const float scale = 1.0f / sqrtf((float)HD);
+  float m_run[NQ], l_run[NQ];
+  f32x16 o[NQ][NE];
+#pragma unroll
+  for (int t = 0; t < NQ; ++t) {
+    m_run[t] = -INFINITY; l_run[t] = 0.f;
+#pragma unroll
+    for (int e = 0; e < NE; ++e)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[t][e][r] = 0.f;
+  }
+
+  int tile = 0;
+  auto step = [&](auto mask_tag, auto more_tag) {
+    constexpr bool mask = decltype(mask_tag)::value, more = decltype(more_tag)::value;
+    const int kbase = tile * ATT_TILE + 4 * half;
+    asm volatile("" ::: "memory");   // the queries are re-read from LDS every tile, not kept in registers
+#pragma unroll
+    for (int t = 0; t < NQ; ++t) {
+      f32x16 sa;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sa[r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        sa = mfma_h16(__builtin_bit_cast(h16x8, rk[ks]), __builtin_bit_cast(h16x8, qs[(t * KS + ks) * 64]), sa);
+      if (more && t == NQ - 1) att_issue_k<HD>(rk, head, tile + 1, lane);
+      float tm = -INFINITY;
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          float sv = sa[4 * g + i] * scale;
+          if (mask && kbase + 8 * g + i > pcol[t]) sv = -INFINITY;
+          sa[4 * g + i] = sv;
+          tm = fmaxf(tm, sv);
+        }
+      tm = fmaxf(tm, __shfl_xor(tm, 32, 64));
+      const float mn = fmaxf(m_run[t], tm);   // finite from the first tile on: key 0 is visible to every column
+      const float alpha = __expf(m_run[t] - mn);
+      m_run[t] = mn;
+      float ls = 0.f;
+      uint32_t pk[8];
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int i = 0; i < 4; i += 2) {
+          float p0 = __expf(sa[4 * g + i] - mn), p1 = __expf(sa[4 * g + i + 1] - mn);
+          ls += p0 + p1;
+          pk[2 * g + (i >> 1)] = (uint32_t)f32_to_h16_bits(p0) | ((uint32_t)f32_to_h16_bits(p1) << 16);
+        }
+      l_run[t] = l_run[t] * alpha + ls;
+      if (__any(alpha != 1.0f)) {
+#pragma unroll
+        for (int e = 0; e < NE; ++e)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[t][e][r] *= alpha;
+      }
+#pragma unroll
+      for (int ks2 = 0; ks2 < 2; ++ks2) {   // P^T as B operand: see the split-K kernel
+        const int ga = 2 * ks2, gb = 2 * ks2 + 1;
+        uint32_t s0 = half ? pk[2 * ga] : pk[2 * gb], s1 = half ? pk[2 * ga + 1] : pk[2 * gb + 1];
+        uint32_t r0 = __shfl_xor(s0, 32, 64), r1 = __shfl_xor(s1, 32, 64);
+        uint32_t m0 = half ? pk[2 * gb] : pk[2 * ga], m1 = half ? pk[2 * gb + 1] : pk[2 * ga + 1];
+        v4u pb = half ? v4u{r0, r1, m0, m1} : v4u{m0, m1, r0, r1};
+#pragma unroll
+        for (int e = 0; e < NE; ++e)
+          o[t][e] = mfma_h16(__builtin_bit_cast(h16x8, rv[ks2 * NE + e]), __builtin_bit_cast(h16x8, pb), o[t][e]);
+      }
+    }
+    if (more) att_issue_v<HD>(rv, head, tile + 1, lane);
+  };
+  // tiles wholly at or before the block's first position need no mask; the last tile requests no successor
+  const int nfull = min((b.pos0 + 1) / ATT_TILE, ntiles - 1);
+  for (; tile < nfull; ++tile) step(std::false_type{}, std::true_type{});
+  for (; tile < ntiles - 1; ++tile) step(std::true_type{}, std::true_type{});
+  step(std::true_type{}, std::false_type{});
+
+#pragma unroll
+  for (int t = 0; t < NQ; ++t) {
+    const float l = l_run[t] + __shfl_xor(l_run[t], 32, 64);
+    const int idx = t * 32 + col, r = idx / grp, hh = idx % grp;
+    if (r < b.nrows) {
+      const float inv = 1.0f / l;
+#pragma unroll
+      for (int e = 0; e < NE; ++e)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          uint2 w;
+          w.x = (uint32_t)f32_to_h16_bits(o[t][e][4 * g] * inv) | ((uint32_t)f32_to_h16_bits(o[t][e][4 * g + 1] * inv) << 16);
+          w.y = (uint32_t)f32_to_h16_bits(o[t][e][4 * g + 2] * inv) | ((uint32_t)f32_to_h16_bits(o[t][e][4 * g + 3] * inv) << 16);
+          *(uint2 *)(Xp + k8_index(b.m0 + r, (kvh * grp + hh) * HD + 32 * e + 8 * g + 4 * half, Mp)) = w;
+        }
+    }
+  }
+}
+
+template <int HD>
+static void attention_prefill_launch(void *Xp_out, const void *q_h16, const PrefillBlock *blocks, int nblocks, KvGeom kv, int layer,
+                                     int Mp, int Hq, int Hkv, hipStream_t st) {
+  constexpr int NQ = ATT_PREFILL_COLS / 32;
+  hipLaunchKernelGGL((attn_prefill_kernel<HD, NQ>), dim3(nblocks, Hkv), dim3(64), NQ * (HD / 16) * 64 * 16, st, (uint16_t *)Xp_out, Mp,
+                     (const uint16_t *)q_h16, blocks, kv, layer, Hq, Hkv);
+}
+
+void fast_attention_prefill(void *Xp_out, const void *q_h16, const PrefillBlock *blocks, int nblocks, KvGeom kv, int layer, int Mp,
+                            int Hq, int Hkv, hipStream_t st) {
+  if (nblocks <= 0) return;
+  if (kv.head_dim == 128) attention_prefill_launch<128>(Xp_out, q_h16, blocks, nblocks, kv, layer, Mp, Hq, Hkv, st);
+  else attention_prefill_launch<64>(Xp_out, q_h16, blocks, nblocks, kv, layer, Mp, Hq, Hkv, st);
+}
+
 void fast_attention(void *Xp_out, const void *q_h16, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq, int Hkv,
                     int nsplit, float *part_o, float *part_ml, hipStream_t st) {
   if (kv.head_dim == 128) attention_launch<128>(Xp_out, q_h16, rows, kv, layer, M, Mp, Hq, Hkv, nsplit, part_o, part_ml, st);

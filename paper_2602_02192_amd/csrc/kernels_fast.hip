@@ -5,7 +5,7 @@
 
 namespace echo {
 
-// grid M rows, block 1024.  h[m] = embed[token[m]]            (embed != null)
+// grid M rows, block <= 1024 (a multiple of 64 covering d/4 or d/8 lanes).  h[m] = embed[token[m]]            (embed != null)
 //                           h[m] += sum_s partials[s][..][m]  (nsplit <= REDUCE_MAX_SPLIT, summed in split order)
 // then Xp[m] = half(h[m] * rsqrt(mean(h[m]^2) + eps) * gain).  d % 8 == 0, d <= 8192.
 // Every load of a thread (residual, all partials) is issued before the first use, so the kernel costs
@@ -21,7 +21,7 @@ __global__ __launch_bounds__(RN_THREADS) void resid_norm_kernel(float *h, const 
   int tok = embed ? token[m] : 0;
 #pragma unroll
   for (int c = 0; c < 2; ++c) {
-    int n4 = threadIdx.x + c * RN_THREADS;
+    int n4 = threadIdx.x + c * (int)blockDim.x;
     if (n4 >= d4) break;
     f32x4 a, pp[REDUCE_MAX_SPLIT];
 #pragma unroll
@@ -44,12 +44,11 @@ __global__ __launch_bounds__(RN_THREADS) void resid_norm_kernel(float *h, const 
   if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = ss;
   __syncthreads();
   ss = 0.f;
-#pragma unroll
-  for (int i = 0; i < RN_THREADS / 64; ++i) ss += sh[i];
+  for (int i = 0; i < (int)blockDim.x / 64; ++i) ss += sh[i];
   float inv = 1.0f / sqrtf(ss / (float)d + eps);
 #pragma unroll
   for (int c = 0; c < 2; ++c) {
-    int n4 = threadIdx.x + c * RN_THREADS;
+    int n4 = threadIdx.x + c * (int)blockDim.x;
     if (n4 >= d4) break;
     int n = n4 * 4;
     uint2 g = *(const uint2 *)(gain + n);
@@ -65,17 +64,22 @@ __global__ __launch_bounds__(RN_THREADS) void resid_norm_kernel(float *h, const 
 void fast_resid_norm(float *h, const void *embed_bf16, const int32_t *token, const float *partials, int nsplit, int Np,
                      void *Xp, const void *gain_bf16, int M, int Mp, int d, float eps, hipStream_t st) {
   if (M <= 0) return;
-  hipLaunchKernelGGL(resid_norm_kernel, dim3(M), dim3(RN_THREADS), 0, st, h, (const uint16_t *)embed_bf16, token,
+  int threads = ((d >> 2) + 63) / 64 * 64;   // one float4 per thread when the row fits, else two
+  if (threads > RN_THREADS) threads = ((d >> 3) + 63) / 64 * 64;
+  hipLaunchKernelGGL(resid_norm_kernel, dim3(M), dim3(threads), 0, st, h, (const uint16_t *)embed_bf16, token,
                      (const f32x4 *)partials, nsplit, Np, (uint16_t *)Xp, (const uint16_t *)gain_bf16, Mp, d, eps);
 }
 
-// grid (M, Hq + 2*Hkv), block hd/2.  Sums the split-K partials of one head of one row, applies the optional
-// per-head RMSNorm and the rotary embedding, writes q (half [M][Hq][hd]) or appends k / v to the half-precision cache.
+// grid (M, ceil((Hq + 2*Hkv) / QP_HEADS)), block QP_HEADS * hd/2 with hd/2 <= 64: each group of hd/2 lanes sums the
+// split-K partials of one head of one row, applies the optional per-head RMSNorm and the rotary embedding, and writes
+// q (half [M][Hq][hd]) or appends k / v to the half-precision cache.
+constexpr int QP_HEADS = 8;
 __global__ void qkv_post_kernel(const float *partials, int nsplit, int Np, int Mp, uint16_t *q_out, const uint16_t *q_gain,
                                 const uint16_t *k_gain, int qk_norm, float eps, const float2 *rope_cs, RowState rows,
                                 KvGeom kv, int layer, int Hq, int Hkv) {
-  __shared__ float sh[2];
-  int m = blockIdx.x, j = blockIdx.y, hd = kv.head_dim, half = hd / 2, i = threadIdx.x;
+  int hd = kv.head_dim, half = hd / 2;
+  int m = blockIdx.x, j = blockIdx.y * QP_HEADS + threadIdx.x / half, i = threadIdx.x % half;
+  if (j >= Hq + 2 * Hkv) return;
   bool is_q = j < Hq, is_k = !is_q && j < Hq + Hkv;
   if (!is_q && !rows.active[m]) return;
   int n0 = j * hd + i, n1 = n0 + half;
@@ -89,12 +93,8 @@ __global__ void qkv_post_kernel(const float *partials, int nsplit, int Np, int M
   for (int s = 0; s < REDUCE_MAX_SPLIT; ++s) { a += pa[s]; b += pb[s]; }
   if (is_q || is_k) {
     if (qk_norm) {
-      float ss = wave_sum(a * a + b * b);
-      if (blockDim.x > 64) {
-        if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = ss;
-        __syncthreads();
-        ss = sh[0] + sh[1];
-      }
+      float ss = a * a + b * b;   // the head's lanes are an aligned power-of-two group within the wave
+      for (int off = half >> 1; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
       float inv = 1.0f / sqrtf(ss / (float)hd + eps);
       const uint16_t *g = is_q ? q_gain : k_gain;
       a = a * inv * bf16_bits_to_f32(g[i]);
@@ -119,7 +119,7 @@ __global__ void qkv_post_kernel(const float *partials, int nsplit, int Np, int M
 void fast_qkv_post(const float *partials, int nsplit, int Np, int Mp, void *q_h16, const void *q_gain, const void *k_gain,
                    int qk_norm, float eps, const float *rope_cs, RowState rows, KvGeom kv, int layer, int M, int Hq, int Hkv,
                    hipStream_t st) {
-  hipLaunchKernelGGL(qkv_post_kernel, dim3(M, Hq + 2 * Hkv), dim3(kv.head_dim / 2), 0, st, partials, nsplit, Np, Mp,
+  hipLaunchKernelGGL(qkv_post_kernel, dim3(M, (Hq + 2 * Hkv + QP_HEADS - 1) / QP_HEADS), dim3(QP_HEADS * kv.head_dim / 2), 0, st, partials, nsplit, Np, Mp,
                      (uint16_t *)q_h16, (const uint16_t *)q_gain, (const uint16_t *)k_gain, qk_norm, eps,
                      (const float2 *)rope_cs, rows, kv, layer, Hq, Hkv);
 }

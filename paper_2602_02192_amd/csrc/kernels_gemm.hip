@@ -497,6 +497,155 @@ __global__ __launch_bounds__(WN * 64) void gemm_lds_kernel(void *out, const u32x
   }
 }
 
+// ---- 256 x 256 tiles for batches of 256 rows and more ------------------------------------------------------
+// Prefill and scoring are bound by the matrix cores, and what a compute unit can pull from L2 per cycle caps them:
+// a workgroup that computes Tn x Tm outputs per k loads Tn + Tm operand rows, so the tile has to be large in both
+// directions.  Four wavefronts, each with two weight blocks (64 output columns) against 256 batch rows: every
+// activation operand read from LDS feeds two MFMAs, which halves the LDS traffic of the one-block kernel (that one
+// runs at the LDS limit).  The 256 accumulator registers per lane live in the accumulation half of the register file.
+struct GemmWide {
+  static constexpr int MB = 8, WN = 4, NBW = 2, NSTAGE = 8, ROWS = 32 * MB, T = WN * 64;
+  static constexpr int CHUNK_UNITS = 2 * ROWS, XL = CHUNK_UNITS / T;   // a chunk is one k-step
+  static constexpr int X_BYTES = 2 * CHUNK_UNITS * 16, TILE_STRIDE = 33, EPI_BYTES = WN * 32 * TILE_STRIDE * 4;
+  static constexpr int BYTES = X_BYTES > EPI_BYTES ? X_BYTES : EPI_BYTES;
+};
+
+// One k-step per chunk, operands requested seven chunks ahead: with one wavefront per SIMD only the depth of the
+// register pipeline hides the load latency, and measured throughput kept rising with it.  Kp is a multiple of
+// GEMM_K_PAD, so the k-step count is a multiple of the eight stages and the loop needs neither tails nor conditions
+// (a load behind a condition makes the compiler's wait counts drain the queue): the prefetches of the last trips
+// are clamped to the last k-step, loaded again and never used.
+// ZFAST: the row blocks of one weight strip are neighbours in launch order, so a strip is fetched from HBM once and
+// found in cache by the other row blocks; pays when the weight matrix is far larger than the last-level cache.
+template <int EPI, bool ZFAST>
+__global__ __launch_bounds__(256) void gemm_wide_kernel(void *out, const u32x4v *__restrict__ Xp, const h16x8 *__restrict__ Wp, int Mp,
+                                                        int Np, int Kp) {
+  extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+  using L = GemmWide;
+  constexpr int MB = L::MB, NBW = L::NBW, T = L::T, XU = L::CHUNK_UNITS, XL = L::XL, ROWS = L::ROWS, NSTAGE = L::NSTAGE;
+  static_assert((GEMM_K_PAD / 16) % NSTAGE == 0, "k-step count must be a multiple of the stage count");
+  u32x4v *xs = (u32x4v *)lds_raw;
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, tid = threadIdx.x;
+  const int nblocks = Np >> 5, nchunks = Kp >> 4, nz = Mp / ROWS;
+  const int bx = ZFAST ? blockIdx.x / nz : blockIdx.x, bz = ZFAST ? blockIdx.x % nz : blockIdx.z;
+  const int nb0 = (bx * L::WN + w) * NBW, mrow0 = bz * ROWS;
+  const int64_t a_step = w_kstep_stride(Np);
+  const h16x8 *a_ptr[NBW];
+#pragma unroll
+  for (int n = 0; n < NBW; ++n)   // blocks past the end re-read the last one and are not stored
+    a_ptr[n] = Wp + w_block_base(min(nb0 + n, nblocks - 1), Kp) + (lane >> 5) * 32 + (lane & 31);
+  f32x16 acc[NBW][MB];
+#pragma unroll
+  for (int n = 0; n < NBW; ++n)
+#pragma unroll
+    for (int j = 0; j < MB; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[n][j][r] = 0.f;
+  h16x8 a[NSTAGE][NBW];
+  u32x4v xr[NSTAGE][XL];
+  auto load_a = [&](int st, int c) {
+#pragma unroll
+    for (int n = 0; n < NBW; ++n) a[st][n] = __builtin_nontemporal_load(a_ptr[n] + (int64_t)c * a_step);
+  };
+  auto load_x = [&](int st, int c) {   // unit i of a k-step: k8 group i / ROWS, batch row i % ROWS
+#pragma unroll
+    for (int i = 0; i < XL; ++i) {
+      int idx = i * T + tid;
+      xr[st][i] = Xp[(int64_t)(c * 2 + idx / ROWS) * Mp + mrow0 + idx % ROWS];
+    }
+  };
+  auto store_x = [&](int st, int buf) {
+#pragma unroll
+    for (int i = 0; i < XL; ++i) xs[buf * XU + i * T + tid] = xr[st][i];
+  };
+  auto compute = [&](int st, int buf) {
+    const u32x4v *bp = xs + buf * XU + (lane >> 5) * ROWS + (lane & 31);
+    u32x4v b[MB];
+#pragma unroll
+    for (int j = 0; j < MB; ++j) b[j] = bp[j * 32];
+#pragma unroll
+    for (int j = 0; j < MB; ++j)
+#pragma unroll
+      for (int n = 0; n < NBW; ++n) acc[n][j] = mfma_h16(a[st][n], __builtin_bit_cast(h16x8, b[j]), acc[n][j]);
+  };
+#pragma unroll
+  for (int s = 0; s < NSTAGE - 1; ++s) { load_x(s, s); load_a(s, s); }
+  store_x(0, 0);
+  __syncthreads();
+  for (int c0 = 0; c0 < nchunks; c0 += NSTAGE) {
+#pragma unroll
+    for (int s = 0; s < NSTAGE; ++s) {
+      const int c = c0 + s, cn = min(c + NSTAGE - 1, nchunks - 1);
+      load_x((s + NSTAGE - 1) % NSTAGE, cn);
+      load_a((s + NSTAGE - 1) % NSTAGE, cn);
+      compute(s, c & 1);
+      store_x((s + 1) % NSTAGE, (c + 1) & 1);
+      __syncthreads();
+    }
+  }
+  const int half = lane >> 5, col = lane & 31;
+  if (EPI == EPI_PARTIAL) {   // 32 x 32 tiles transposed through LDS so that every store is a whole 128-byte row segment
+    float *tile = (float *)lds_raw + (size_t)w * 32 * L::TILE_STRIDE;
+#pragma unroll
+    for (int n = 0; n < NBW; ++n) {
+      float *P = (float *)out + (int64_t)mrow0 * Np + (nb0 + n) * 32;
+#pragma unroll
+      for (int j = 0; j < MB; ++j) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) tile[col * L::TILE_STRIDE + 8 * g + 4 * half + i] = acc[n][j][4 * g + i] * W_UNSCALE;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        if (nb0 + n < nblocks) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            int r = q * 8 + (lane >> 3), n4 = (lane & 7) * 4;
+            const float *t = tile + r * L::TILE_STRIDE + n4;
+            f32x4 v = {t[0], t[1], t[2], t[3]};
+            *(f32x4 *)(P + (int64_t)(j * 32 + r) * Np + n4) = v;
+          }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      }
+    }
+  } else {  // EPI_SWIGLU, as in the kernel above
+    uint32_t *O = (uint32_t *)out;
+#pragma unroll
+    for (int n = 0; n < NBW; ++n) {
+      if (nb0 + n >= nblocks) break;
+#pragma unroll
+      for (int j = 0; j < MB; ++j) {
+        uint32_t pk[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          float v0 = silu_f(acc[n][j][4 * g] * W_UNSCALE) * (acc[n][j][4 * g + 1] * W_UNSCALE);
+          float v1 = silu_f(acc[n][j][4 * g + 2] * W_UNSCALE) * (acc[n][j][4 * g + 3] * W_UNSCALE);
+          pk[g] = (uint32_t)f32_to_h16_bits(v0) | ((uint32_t)f32_to_h16_bits(v1) << 16);
+        }
+        uint32_t give0 = half ? pk[0] : pk[2], give1 = half ? pk[1] : pk[3];
+        uint32_t got0 = __shfl_xor(give0, 32, 64), got1 = __shfl_xor(give1, 32, 64);
+        u32x4v o = half ? u32x4v{got0, pk[2], got1, pk[3]} : u32x4v{pk[0], got0, pk[1], got1};
+        int m = mrow0 + j * 32 + col;
+        *(u32x4v *)(O + (((int64_t)((nb0 + n) * 2 + half) * Mp + m) * 4)) = o;
+      }
+    }
+  }
+}
+
+template <int EPI, bool ZFAST>
+static void gemm_wide_launch(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, hipStream_t st) {
+  using L = GemmWide;
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void *)gemm_wide_kernel<EPI, ZFAST>, hipFuncAttributeMaxDynamicSharedMemorySize, L::BYTES);
+    attr_set = true;
+  }
+  int nblocks = Np / 32, per_wg = L::WN * L::NBW, strips = (nblocks + per_wg - 1) / per_wg, nz = Mp / L::ROWS;
+  dim3 grid = ZFAST ? dim3(strips * nz, 1, 1) : dim3(strips, 1, nz);
+  hipLaunchKernelGGL((gemm_wide_kernel<EPI, ZFAST>), grid, dim3(L::T), L::BYTES, st, out, (const u32x4v *)Xp, (const h16x8 *)Wp, Mp, Np,
+                     Kp);
+}
+
 // Launch shape.  Up to 128 batch rows the LDS-staged kernel runs: three or four weight blocks per workgroup, and a
 // grid split over K that brings the launch to about one workgroup per compute unit (partials cost HBM writes, so
 // no more than that); a GEMM whose epilogue needs the whole K (SwiGLU) is not split.  Larger batches keep the
@@ -505,6 +654,10 @@ void fast_gemm_pick(int Np, int Kp, int Mp, int full_k, GemmShape *g) {
   int nblocks = Np / 32, ksteps = Kp / 16, mb = Mp / 32 > 8 ? 8 : Mp / 32;
   int zblocks = Mp / (32 * mb);
   g->lds = 0; g->stages = 0;
+  if (Kp % GEMM_K_PAD == 0 && Mp % 256 == 0 && (nblocks + 7) / 8 * (Mp / 256) >= 128) {   // 256 x 256 tiles fill the chip
+    g->lds = 2; g->nbw = 2; g->waves_k = 1; g->waves_n = 4; g->stages = 8; g->nsplit = 1;
+    return;
+  }
   if (Kp % (16 * GEMM_KC_SMALL) == 0 && (Mp <= 128 || Mp % 256 == 0)) {
     const bool wide = Mp > 128;   // 256 batch rows per workgroup, Mp/256 workgroups per weight strip
     int total_chunks = ksteps / (wide ? GEMM_KC_WIDE : GEMM_KC_SMALL);
@@ -565,6 +718,11 @@ static void gemm_lds_dispatch(void *out, const void *Xp, const void *Wp, int Mp,
 
 template <int EPI>
 static void gemm_dispatch(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, GemmShape g, hipStream_t st) {
+  if (g.lds == 2) {   // row blocks fastest once the weights are far larger than the last-level cache
+    if ((size_t)Np * Kp * 2 >= ((size_t)256 << 20)) gemm_wide_launch<EPI, true>(out, Xp, Wp, Mp, Np, Kp, st);
+    else gemm_wide_launch<EPI, false>(out, Xp, Wp, Mp, Np, Kp, st);
+    return;
+  }
   if (g.lds) { gemm_lds_dispatch<EPI>(out, Xp, Wp, Mp, Np, Kp, g, st); return; }
   int mbt = Mp / 32;
   int MB = mbt >= 8 ? 8 : mbt;
@@ -603,6 +761,10 @@ void fast_gemm(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp
 // workgroup), then every logit is folded into a running (max, sum-exp, best perturbed score, its index, its z) per
 // batch row: per wavefront, then over the four wavefronts in wavefront order, one partial per workgroup.
 constexpr int LM_WN = 4;
+template <int MB> struct LmLds {   // epilogue of the 256-row kernel: accumulators of four wavefronts + their partial results
+  static constexpr int DUMP_PER_WAVE = MB * 16 * 64 * 4;
+  static constexpr int BYTES = LM_WN * DUMP_PER_WAVE + LM_WN * MB * 32 * (int)sizeof(SampleAcc);
+};
 
 template <int MB, int NSTAGE, bool LOGITS>
 __global__ __launch_bounds__(256) void lmhead_kernel(const u32x4v *__restrict__ Xp, const h16x8 *__restrict__ Wp, int Mp,
@@ -617,55 +779,113 @@ __global__ __launch_bounds__(256) void lmhead_kernel(const u32x4v *__restrict__ 
   uint32_t step = LOGITS ? 0u : (uint32_t)*d_step;
   f32x16 acc[MB];
   gemm_lds_mainloop<MB, LM_WN, NSTAGE>(acc, lds_raw, Xp, Wp, Mp, Np, Kp, nb, 0, (Kp >> 4) / L::KC, mrow0);
-  SampleAcc sa[MB];
+  // One logit: temperature, running (max, sum-exp), perturbed-score argmax, the target's z.
+  auto fold = [&](SampleAcc &sa, float a, uint32_t bits, int v, int m, int tgt) {
+    if (v < V) {
+      float z = a * W_UNSCALE / temperature;
+      sample_acc_add(sa, z, z + gumbel_from_bits(bits), v);
+      if (v == tgt) target_z[m] = z;
+    }
+  };
+  auto fold_plain = [&](SampleAcc &sa, float a, int v, int m, int tgt) {
+    if (v < V) {
+      float z = a * W_UNSCALE / temperature;
+      sample_acc_add(sa, z, z, v);
+      if (v == tgt) target_z[m] = z;
+    }
+  };
+  auto fold4 = [&](SampleAcc &sa, f32x4 a, int v0, int m, int tgt) {
+    if (target) {   // scoring: only the target's log-prob is wanted, so no noise is drawn (the token output is the plain argmax)
+      fold_plain(sa, a[0], v0, m, tgt); fold_plain(sa, a[1], v0 + 1, m, tgt);
+      fold_plain(sa, a[2], v0 + 2, m, tgt); fold_plain(sa, a[3], v0 + 3, m, tgt);
+    } else {
+      u32x4 r = draw4(seed, (uint32_t)m, step, (uint32_t)(v0 >> 2));
+      fold(sa, a[0], r.x, v0, m, tgt); fold(sa, a[1], r.y, v0 + 1, m, tgt);
+      fold(sa, a[2], r.z, v0 + 2, m, tgt); fold(sa, a[3], r.w, v0 + 3, m, tgt);
+    }
+  };
+  auto write_partial = [&](const SampleAcc &sa, int m) {
+    int64_t o = (int64_t)blockIdx.x * Mp + m, plane = (int64_t)n_wg * Mp;
+    part[o] = sa.zmax;
+    part[plane + o] = sa.zsum;
+    part[2 * plane + o] = sa.best;
+    part[3 * plane + o] = sa.zbest;
+    part[4 * plane + o] = __int_as_float(sa.idx);
+  };
+  if constexpr (LOGITS) {
+    if (nb_own < nblocks) {
 #pragma unroll
-  for (int j = 0; j < MB; ++j) sa[j] = sample_acc_init();
-  if (nb_own < nblocks) {
+      for (int j = 0; j < MB; ++j) {
+        int m = mrow0 + j * 32 + col;
 #pragma unroll
-    for (int j = 0; j < MB; ++j) {
-      int m = mrow0 + j * 32 + col;
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        int v0 = nb * 32 + 8 * g + 4 * half;
-        if (v0 >= V) continue;
-        if (LOGITS) {
+        for (int g = 0; g < 4; ++g) {
+          int v0 = nb * 32 + 8 * g + 4 * half;
           f32x4 o = {acc[j][4 * g], acc[j][4 * g + 1], acc[j][4 * g + 2], acc[j][4 * g + 3]};
-          *(f32x4 *)(logits + (int64_t)m * ld + v0) = o * W_UNSCALE;
-        } else {
-          u32x4 r = draw4(seed, (uint32_t)m, step, (uint32_t)(v0 >> 2));
-          uint32_t bits[4] = {r.x, r.y, r.z, r.w};
-          int tgt = target ? target[m] : -1;
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            if (v0 + i >= V) break;
-            float z = acc[j][4 * g + i] * W_UNSCALE / temperature;
-            sample_acc_add(sa[j], z, z + gumbel_from_bits(bits[i]), v0 + i);
-            if (v0 + i == tgt) target_z[m] = z;
-          }
+          if (v0 < V) *(f32x4 *)(logits + (int64_t)m * ld + v0) = o * W_UNSCALE;
         }
       }
     }
-  }
-  if (LOGITS) return;
-  // lanes l and l^32 hold the same batch row; then fold the four wavefronts in wavefront order
-  SampleAcc (*sh)[MB][32] = (SampleAcc (*)[MB][32])lds_raw;   // [3][MB][32]; the main loop's buffers are free by now
+  } else if constexpr (MB >= 8) {
+    // Unrolling the sampler over eight row tiles is more code than the compiler will unroll, and a rolled loop over
+    // the accumulator array would move it out of the registers for the whole kernel.  So the accumulators are parked
+    // in LDS with static indices (each lane reads back only what it wrote) and the row tiles are folded in a loop.
+    using LM = LmLds<MB>;
+    __syncthreads();   // the main loop's buffers are free once every wavefront has left it
+    f32x4 *dump = (f32x4 *)(lds_raw + w * LM::DUMP_PER_WAVE) + lane;
 #pragma unroll
-  for (int j = 0; j < MB; ++j) { SampleAcc b = sample_acc_shfl_xor(sa[j], 32); sample_acc_merge(sa[j], b); }
-  if (w > 0 && half == 0)
+    for (int j = 0; j < MB; ++j)
 #pragma unroll
-    for (int j = 0; j < MB; ++j) sh[w - 1][j][col] = sa[j];
-  __syncthreads();
-  if (w == 0 && half == 0) {
-#pragma unroll
+      for (int g = 0; g < 4; ++g) dump[(j * 4 + g) * 64] = f32x4{acc[j][4 * g], acc[j][4 * g + 1], acc[j][4 * g + 2], acc[j][4 * g + 3]};
+    SampleAcc (*sh)[MB][32] = (SampleAcc (*)[MB][32])(lds_raw + LM_WN * LM::DUMP_PER_WAVE);   // [4][MB][32]
+#pragma unroll 1
     for (int j = 0; j < MB; ++j) {
-      for (int ww = 0; ww < 3; ++ww) sample_acc_merge(sa[j], sh[ww][j][col]);
-      int m = mrow0 + j * 32 + col;
-      int64_t o = (int64_t)blockIdx.x * Mp + m, plane = (int64_t)n_wg * Mp;
-      part[o] = sa[j].zmax;
-      part[plane + o] = sa[j].zsum;
-      part[2 * plane + o] = sa[j].best;
-      part[3 * plane + o] = sa[j].zbest;
-      part[4 * plane + o] = __int_as_float(sa[j].idx);
+      SampleAcc sa = sample_acc_init();
+      if (nb_own < nblocks) {
+        int m = mrow0 + j * 32 + col, tgt = target ? target[m] : -1;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) fold4(sa, dump[(j * 4 + g) * 64], nb * 32 + 8 * g + 4 * half, m, tgt);
+      }
+      SampleAcc o = sample_acc_shfl_xor(sa, 32);
+      sample_acc_merge(sa, o);
+      if (half == 0) sh[w][j][col] = sa;
+    }
+    __syncthreads();
+    if (w == 0 && half == 0) {
+#pragma unroll 1
+      for (int j = 0; j < MB; ++j) {
+        SampleAcc sa = sh[0][j][col];
+        for (int ww = 1; ww < LM_WN; ++ww) sample_acc_merge(sa, sh[ww][j][col]);
+        write_partial(sa, mrow0 + j * 32 + col);
+      }
+    }
+  } else {
+    SampleAcc sa[MB];
+#pragma unroll
+    for (int j = 0; j < MB; ++j) sa[j] = sample_acc_init();
+    if (nb_own < nblocks) {
+#pragma unroll
+      for (int j = 0; j < MB; ++j) {
+        int m = mrow0 + j * 32 + col, tgt = target ? target[m] : -1;
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          fold4(sa[j], f32x4{acc[j][4 * g], acc[j][4 * g + 1], acc[j][4 * g + 2], acc[j][4 * g + 3]}, nb * 32 + 8 * g + 4 * half, m, tgt);
+      }
+    }
+    // lanes l and l^32 hold the same batch row; then fold the four wavefronts in wavefront order
+    SampleAcc (*sh)[MB][32] = (SampleAcc (*)[MB][32])lds_raw;   // [3][MB][32]; the main loop's buffers are free by now
+#pragma unroll
+    for (int j = 0; j < MB; ++j) { SampleAcc b = sample_acc_shfl_xor(sa[j], 32); sample_acc_merge(sa[j], b); }
+    __syncthreads();   // every wavefront has left the main loop before its buffers are overwritten
+    if (w > 0 && half == 0)
+#pragma unroll
+      for (int j = 0; j < MB; ++j) sh[w - 1][j][col] = sa[j];
+    __syncthreads();
+    if (w == 0 && half == 0) {
+#pragma unroll
+      for (int j = 0; j < MB; ++j) {
+        for (int ww = 0; ww < 3; ++ww) sample_acc_merge(sa[j], sh[ww][j][col]);
+        write_partial(sa[j], mrow0 + j * 32 + col);
+      }
     }
   }
 }
@@ -703,7 +923,8 @@ static void lmhead_launch(const void *Xp, const void *Wp, int Mp, int Np, int Kp
                           const int32_t *d_step, const int32_t *target, float *target_z, float *part, float *logits, int64_t ld,
                           hipStream_t st) {
   using L = GemmLds<MB, LM_WN>;
-  constexpr int SH = 3 * MB * 32 * (int)sizeof(SampleAcc), BYTES = L::X_BYTES > SH ? L::X_BYTES : SH;
+  constexpr int SH = (MB >= 8 && !LOGITS) ? LmLds<MB>::BYTES : 3 * MB * 32 * (int)sizeof(SampleAcc);
+  constexpr int BYTES = L::X_BYTES > SH ? L::X_BYTES : SH;
   static bool attr_set = false;
   if (!attr_set) {
     (void)hipFuncSetAttribute((const void *)lmhead_kernel<MB, NSTAGE, LOGITS>, hipFuncAttributeMaxDynamicSharedMemorySize, BYTES);

@@ -68,6 +68,7 @@ def test_mfma_path_shape_limits_are_reported(echo):
     ok = synth.TINY.replace(dtype="bf16")
     assert echo.arena_bytes(echo.desc_from_shape(ok, 8, 64)) > 0
     for bad in (ok.replace(hidden=250), ok.replace(head_dim=32, n_q_heads=8, n_kv_heads=4),
+                ok.replace(head_dim=192, n_q_heads=4, n_kv_heads=2),
                 ok.replace(n_q_heads=32, n_kv_heads=2, hidden=2048)):
         d = echo.desc_from_shape(bad, 8, 64)
         assert echo.arena_bytes(d) == 0
