@@ -440,7 +440,7 @@ int run_chunks(echo_ctx *c, const Slot &S, const int32_t *tokens, int stride, co
   int R = std::min(PREFILL_ROWS, c->p.Mcap);
   std::vector<int32_t> tok(R), slot(R), pos(R), act(R);
   std::vector<PrefillBlock> blocks;
-  const int block_rows = ATT_PREFILL_COLS / (c->d.n_q_heads / c->d.n_kv_heads);
+  const int block_rows = ATT_PREFILL_WAVES * ATT_PREFILL_COLS / (c->d.n_q_heads / c->d.n_kv_heads);
   bool splitk = !env_flag("ECHO_ATTN_SIMPLE"), causal_blocks = c->p.fast && splitk;
   for (size_t a = 0; a < all.size(); a += R) {
     int M = (int)std::min<size_t>(R, all.size() - a);

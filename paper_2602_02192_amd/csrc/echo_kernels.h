@@ -108,10 +108,12 @@ void fast_attention(void *Xp_out, const void *q_h16, RowState rows, KvGeom kv, i
                     int Hkv, int nsplit, float *part_o, float *part_ml, hipStream_t st);
 int fast_attention_splits(int M, int Hkv, int max_splits);
 // Causal attention for runs of consecutive positions (prefill, teacher-forced scoring).  A block is up to
-// ATT_PREFILL_COLS / (Hq/Hkv) rows m0 .. m0 + nrows - 1 holding positions pos0 .. of one cache slot, whose keys
-// and values (positions 0 .. pos0 + nrows - 1) are already in the cache.  The blocks must cover every row once.
+// ATT_PREFILL_WAVES * ATT_PREFILL_COLS / (Hq/Hkv) rows m0 .. m0 + nrows - 1 holding positions pos0 .. of one cache
+// slot, whose keys and values (positions 0 .. pos0 + nrows - 1) are already in the cache.  The blocks must cover
+// every row once.
 struct PrefillBlock { int32_t m0, nrows, slot, pos0; };
-constexpr int ATT_PREFILL_COLS = 64;    // (row, query head) pairs of one KV head that one wavefront carries
+constexpr int ATT_PREFILL_COLS = 32;    // (row, query head) pairs of one KV head that one wavefront carries
+constexpr int ATT_PREFILL_WAVES = 8;    // wavefronts of a workgroup, which share the block's K / V tiles
 void fast_attention_prefill(void *Xp_out, const void *q_h16, const PrefillBlock *blocks, int nblocks, KvGeom kv, int layer,
                             int Mp, int Hq, int Hkv, hipStream_t st);
 // lm_head with the sampler fused into the epilogue (partials per workgroup) + the combine kernel.  With `target` set

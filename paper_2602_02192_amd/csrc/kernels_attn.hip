@@ -82,17 +82,19 @@ __device__ __forceinline__ int att_split_len(int n_keys, int nsplit) {
 }
 
 // A tile is 64*HD halves = HD*8 units of 16 bytes: the K tile, then the V tile; lane l of load i reads unit i*64 + l.
-template <int HD>
+// STREAM: the tile is read once (decode) and should not displace anything in the caches; the causal block kernel
+// reads every tile from many wavefronts and wants it cached.
+template <int HD, bool STREAM = true>
 __device__ __forceinline__ void att_issue_k(v4u (&rk)[HD / 16], const v4u *__restrict__ head, int tile, int lane) {
   const v4u *t = head + (int64_t)tile * (HD * 8) + lane;
 #pragma unroll
-  for (int i = 0; i < HD / 16; ++i) rk[i] = __builtin_nontemporal_load(t + i * 64);
+  for (int i = 0; i < HD / 16; ++i) rk[i] = STREAM ? __builtin_nontemporal_load(t + i * 64) : t[i * 64];
 }
-template <int HD>
+template <int HD, bool STREAM = true>
 __device__ __forceinline__ void att_issue_v(v4u (&rv)[HD / 16], const v4u *__restrict__ head, int tile, int lane) {
   const v4u *t = head + (int64_t)tile * (HD * 8) + HD * 4 + lane;
 #pragma unroll
-  for (int i = 0; i < HD / 16; ++i) rv[i] = __builtin_nontemporal_load(t + i * 64);
+  for (int i = 0; i < HD / 16; ++i) rv[i] = STREAM ? __builtin_nontemporal_load(t + i * 64) : t[i * 64];
 }
 
 // grid (nsplit, Hkv, M).  Every row's keys are cut into nsplit equal chunks of that row's own length.  DIRECT
@@ -289,40 +291,71 @@ static void attention_launch(void *Xp_out, const void *q_h16, RowState rows, KvG
 }
 
 // ---- causal kernel for runs of consecutive positions ---------------------------------------------------
-// grid (blocks, Hkv), one wavefront per workgroup.  The wavefront carries NQ tiles of 32 columns, a column being a
-// (row, query head of the KV head's group) pair: column index t*32 + col = row_in_block * grp + head.  Every K / V
-// tile of the slot is streamed once into A-operand registers and used by all NQ column tiles (same MFMA roles as the
-// split-K kernel), so the cache traffic per row falls by the block height.  The queries wait in LDS as B operands,
-// each lane reading back exactly the units it wrote.  Keys after a column's own position are masked; only the tiles
-// that reach past the block's first position need the mask.
-template <int HD, int NQ>
-__global__ __launch_bounds__(64, 2) void attn_prefill_kernel(uint16_t *__restrict__ Xp, int Mp, const uint16_t *__restrict__ q_h16,
-                                                          const PrefillBlock *__restrict__ blocks, KvGeom kv, int layer, int Hq,
-                                                          int Hkv) {
-  extern __shared__ __attribute__((aligned(16))) char lds[];
-  constexpr int KS = HD / 16, NE = HD / 32;
-  const PrefillBlock b = blocks[blockIdx.x];
-  const int kvh = blockIdx.y, grp = Hq / Hkv, lane = threadIdx.x, half = lane >> 5, col = lane & 31;
-  const v4u *head = (const v4u *)((const uint16_t *)kv.base + kv.tiled_head_off(b.slot, layer, kvh));
-  const int n_keys = b.pos0 + b.nrows, ntiles = (n_keys + ATT_TILE - 1) / ATT_TILE;
-  v4u rk[KS], rv[KS];
-  att_issue_k<HD>(rk, head, 0, lane);
-  att_issue_v<HD>(rv, head, 0, lane);
+// grid (blocks, Hkv), eight wavefronts per workgroup (two per SIMD, so one's MFMAs run under the other's softmax).
+// A block is up to 8 * 32 / grp consecutive rows of one cache slot; wavefront w carries rows w * 32/grp .. as one tile
+// of 32 columns, a column being a (row, query head of the KV head's group) pair: column index = row_in_wavefront * grp
+// + head.  The wavefronts need the same K / V tiles, so the workgroup fetches every tile once: all threads load it
+// two tiles ahead into staging
+// registers, store it one tile ahead into an LDS double buffer, and the wavefronts read their MFMA A operands from
+// there (same MFMA roles as the split-K kernel: S^T = K Q^T, O^T = V^T P^T).  The queries stay in registers as B
+// operands.  Keys after a column's own position are masked; only the tiles
+// that reach past a wavefront's first position need the mask, and a wavefront skips the tiles past its last row.
+// Blocks are taken longest first (the builder emits them by ascending position).
+constexpr int ATT_PF_NQ = ATT_PREFILL_COLS / 32;
+constexpr float ATT_PF_SLACK = 8.0f;
+template <int HD> struct AttPfLds {
+  static constexpr int TILE_UNITS = HD * 8;                     // 16-byte units: K tile then V tile
+  static constexpr int BYTES = 2 * TILE_UNITS * 16;
+};
 
-  v4u *qs = (v4u *)lds + lane;   // unit (t*KS + ks)*64 + lane: dims ks*16 + half*8 .. +8 of column t*32 + col
-  int pcol[NQ];                  // the column's position; a column beyond the block's rows is all zero and unmasked
+template <int HD>
+__global__ __launch_bounds__(ATT_PREFILL_WAVES * 64) void attn_prefill_kernel(uint16_t *__restrict__ Xp, int Mp, const uint16_t *__restrict__ q_h16,
+                                                           const PrefillBlock *__restrict__ blocks, int nblocks, KvGeom kv, int layer,
+                                                           int Hq, int Hkv) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  using L = AttPfLds<HD>;
+  constexpr int KS = HD / 16, NE = HD / 32, NQ = ATT_PF_NQ, TU = L::TILE_UNITS, NT = ATT_PREFILL_WAVES * 64, PER_T = TU / NT;
+  const PrefillBlock b = blocks[nblocks - 1 - blockIdx.x];
+  const int kvh = blockIdx.y, grp = Hq / Hkv, rb = ATT_PREFILL_COLS / grp;
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, half = lane >> 5, col = lane & 31;
+  const int r0 = w * rb, rows_w = max(0, min(rb, b.nrows - r0));   // this wavefront's rows: r0 .. r0 + rows_w - 1 of the block
+  const int ntiles = (b.pos0 + b.nrows + ATT_TILE - 1) / ATT_TILE;            // of the workgroup
+  const int ntiles_w = rows_w > 0 ? (b.pos0 + r0 + rows_w + ATT_TILE - 1) / ATT_TILE : 0;
+  const int nfull_w = rows_w > 0 ? min((b.pos0 + r0 + 1) / ATT_TILE, ntiles_w - 1) : 0;   // tiles that need no mask
+  const v4u *head = (const v4u *)((const uint16_t *)kv.base + kv.tiled_head_off(b.slot, layer, kvh));
+  v4u *ring = (v4u *)lds;
+
+  v4u stg[2][PER_T];
+  auto gload = [&](int st, int tile) {
+    const v4u *t = head + (int64_t)min(tile, ntiles - 1) * TU + tid;   // past the end: the last tile again, never used
 #pragma unroll
-  for (int t = 0; t < NQ; ++t) pcol[t] = (t * 32 + col) / grp < b.nrows ? b.pos0 + (t * 32 + col) / grp : 0x7fffffff;
-#pragma unroll 1
+    for (int j = 0; j < PER_T; ++j) stg[st][j] = t[j * NT];
+  };
+  auto lstore = [&](int st, int buf) {
+#pragma unroll
+    for (int j = 0; j < PER_T; ++j) ring[buf * TU + j * NT + tid] = stg[st][j];
+  };
+  gload(0, 0);
+  gload(1, 1);
+
+  int pcol[NQ];   // the column's position; a column beyond the wavefront's rows is all zero and unmasked
+#pragma unroll
+  for (int t = 0; t < NQ; ++t) pcol[t] = (t * 32 + col) / grp < rows_w ? b.pos0 + r0 + (t * 32 + col) / grp : 0x7fffffff;
+  v4u qs[NQ * KS];   // qs[t*KS + ks]: dims ks*16 + half*8 .. +8 of column t*32 + col
+#pragma unroll
   for (int t = 0; t < NQ; ++t) {
     const int idx = t * 32 + col, r = idx / grp, hh = idx % grp;
-    const bool valid = r < b.nrows;
-    const uint16_t *src = q_h16 + ((int64_t)(b.m0 + (valid ? r : 0)) * Hq + kvh * grp + hh) * HD + half * 8;
+    const bool valid = r < rows_w;
+    const uint16_t *src = q_h16 + ((int64_t)(b.m0 + r0 + (valid ? r : 0)) * Hq + kvh * grp + hh) * HD + half * 8;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qs[(t * KS + ks) * 64] = valid ? *(const v4u *)(src + ks * 16) : v4u{0u, 0u, 0u, 0u};
+    for (int ks = 0; ks < KS; ++ks) qs[t * KS + ks] = valid ? *(const v4u *)(src + ks * 16) : v4u{0u, 0u, 0u, 0u};
   }
+  lstore(0, 0);
+  gload(0, 2);
+  __syncthreads();
 
-  const float scale = 1.0f / sqrtf((float)HD);
+  // scores are kept in units of log2(e) / sqrt(HD), so the exponentials are bare v_exp_f32 (2^x) instructions
+  const float scale2 = 1.44269504088896f / sqrtf((float)HD);
   float m_run[NQ], l_run[NQ];
   f32x16 o[NQ][NE];
 #pragma unroll
@@ -333,44 +366,54 @@ __global__ __launch_bounds__(64, 2) void attn_prefill_kernel(uint16_t *__restric
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[t][e][r] = 0.f;
   }
+  typedef _Float16 h16x2 __attribute__((ext_vector_type(2)));
 
-  int tile = 0;
-  auto step = [&](auto mask_tag, auto more_tag) {
-    constexpr bool mask = decltype(mask_tag)::value, more = decltype(more_tag)::value;
+  auto compute = [&](int tile, int buf, auto mask_tag) {
+    constexpr bool mask = decltype(mask_tag)::value;
+    const v4u *kt = ring + buf * TU + lane, *vt = kt + HD * 4;
     const int kbase = tile * ATT_TILE + 4 * half;
-    asm volatile("" ::: "memory");   // the queries are re-read from LDS every tile, not kept in registers
+    v4u rk[KS], rv[KS];
+#pragma unroll
+    for (int i = 0; i < KS; ++i) rk[i] = kt[i * 64];
+#pragma unroll
+    for (int i = 0; i < KS; ++i) rv[i] = vt[i * 64];
 #pragma unroll
     for (int t = 0; t < NQ; ++t) {
-      f32x16 sa;
+      f32x16 sa, sb;   // two chains of HD/32 dependent MFMAs instead of one of HD/16
 #pragma unroll
-      for (int r = 0; r < 16; ++r) sa[r] = 0.f;
+      for (int r = 0; r < 16; ++r) { sa[r] = 0.f; sb[r] = 0.f; }
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-        sa = mfma_h16(__builtin_bit_cast(h16x8, rk[ks]), __builtin_bit_cast(h16x8, qs[(t * KS + ks) * 64]), sa);
-      if (more && t == NQ - 1) att_issue_k<HD>(rk, head, tile + 1, lane);
+      for (int ks = 0; ks < KS; ks += 2) {
+        sa = mfma_h16(__builtin_bit_cast(h16x8, rk[ks]), __builtin_bit_cast(h16x8, qs[t * KS + ks]), sa);
+        sb = mfma_h16(__builtin_bit_cast(h16x8, rk[ks + 1]), __builtin_bit_cast(h16x8, qs[t * KS + ks + 1]), sb);
+      }
       float tm = -INFINITY;
 #pragma unroll
       for (int g = 0; g < 4; ++g)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          float sv = sa[4 * g + i] * scale;
+          float sv = (sa[4 * g + i] + sb[4 * g + i]) * scale2;
           if (mask && kbase + 8 * g + i > pcol[t]) sv = -INFINITY;
           sa[4 * g + i] = sv;
           tm = fmaxf(tm, sv);
         }
       tm = fmaxf(tm, __shfl_xor(tm, 32, 64));
-      const float mn = fmaxf(m_run[t], tm);   // finite from the first tile on: key 0 is visible to every column
-      const float alpha = __expf(m_run[t] - mn);
+      // The reference exponent only follows the running maximum when that has grown by more than ATT_PF_SLACK (in
+      // powers of two): softmax does not depend on the reference, p stays below 2^ATT_PF_SLACK (exact in fp32 sums
+      // and well inside the half range), and the accumulators are rescaled a few times per row instead of at almost
+      // every tile.  Finite from the first tile on: key 0 is visible to every column.
+      const float mn = tm > m_run[t] + ATT_PF_SLACK ? tm : m_run[t];
+      const float alpha = __builtin_amdgcn_exp2f(m_run[t] - mn);
       m_run[t] = mn;
       float ls = 0.f;
-      uint32_t pk[8];
+      uint32_t pk[8];   // half pairs: pk[2g + i/2] = keys 8g + 4*half + {i, i+1}; p <= 1, so the conversion cannot overflow
 #pragma unroll
       for (int g = 0; g < 4; ++g)
 #pragma unroll
         for (int i = 0; i < 4; i += 2) {
-          float p0 = __expf(sa[4 * g + i] - mn), p1 = __expf(sa[4 * g + i + 1] - mn);
+          float p0 = __builtin_amdgcn_exp2f(sa[4 * g + i] - mn), p1 = __builtin_amdgcn_exp2f(sa[4 * g + i + 1] - mn);
           ls += p0 + p1;
-          pk[2 * g + (i >> 1)] = (uint32_t)f32_to_h16_bits(p0) | ((uint32_t)f32_to_h16_bits(p1) << 16);
+          pk[2 * g + (i >> 1)] = __builtin_bit_cast(uint32_t, h16x2{(_Float16)p0, (_Float16)p1});
         }
       l_run[t] = l_run[t] * alpha + ls;
       if (__any(alpha != 1.0f)) {
@@ -379,40 +422,50 @@ __global__ __launch_bounds__(64, 2) void attn_prefill_kernel(uint16_t *__restric
 #pragma unroll
           for (int r = 0; r < 16; ++r) o[t][e][r] *= alpha;
       }
+      // P^T as B operand of k-step ks2: keys 16*ks2 + 8*half + 0..7 of the column.  Register group 2*ks2 of the half-0
+      // lane and group 2*ks2+1 of the half-1 lane stay; the other two cross to the partner lane: v_permlane32_swap
+      // exchanges the upper half of its first operand with the lower half of its second, which is exactly that.
 #pragma unroll
-      for (int ks2 = 0; ks2 < 2; ++ks2) {   // P^T as B operand: see the split-K kernel
+      for (int ks2 = 0; ks2 < 2; ++ks2) {
         const int ga = 2 * ks2, gb = 2 * ks2 + 1;
-        uint32_t s0 = half ? pk[2 * ga] : pk[2 * gb], s1 = half ? pk[2 * ga + 1] : pk[2 * gb + 1];
-        uint32_t r0 = __shfl_xor(s0, 32, 64), r1 = __shfl_xor(s1, 32, 64);
-        uint32_t m0 = half ? pk[2 * gb] : pk[2 * ga], m1 = half ? pk[2 * gb + 1] : pk[2 * ga + 1];
-        v4u pb = half ? v4u{r0, r1, m0, m1} : v4u{m0, m1, r0, r1};
+        auto x0 = __builtin_amdgcn_permlane32_swap(pk[2 * ga], pk[2 * gb], false, false);
+        auto x1 = __builtin_amdgcn_permlane32_swap(pk[2 * ga + 1], pk[2 * gb + 1], false, false);
+        v4u pb = v4u{x0[0], x1[0], x0[1], x1[1]};
 #pragma unroll
         for (int e = 0; e < NE; ++e)
           o[t][e] = mfma_h16(__builtin_bit_cast(h16x8, rv[ks2 * NE + e]), __builtin_bit_cast(h16x8, pb), o[t][e]);
       }
     }
-    if (more) att_issue_v<HD>(rv, head, tile + 1, lane);
   };
-  // tiles wholly at or before the block's first position need no mask; the last tile requests no successor
-  const int nfull = min((b.pos0 + 1) / ATT_TILE, ntiles - 1);
-  for (; tile < nfull; ++tile) step(std::false_type{}, std::true_type{});
-  for (; tile < ntiles - 1; ++tile) step(std::true_type{}, std::true_type{});
-  step(std::true_type{}, std::false_type{});
+  // Trip i: tile i+1 (loaded two trips ago) goes to the LDS buffer that tile i-1 occupied, its staging registers are
+  // refilled with tile i+3, tile i is consumed, and the barrier both publishes tile i+1 and retires tile i.  Loads,
+  // stores and barriers are unconditional and the same for every wavefront; only the arithmetic is skipped.
+  for (int i0 = 0; i0 < ntiles; i0 += 2) {
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      const int i = i0 + s;
+      lstore((s + 1) & 1, (s + 1) & 1);
+      gload((s + 1) & 1, i + 3);
+      if (i < nfull_w) compute(i, s, std::false_type{});
+      else if (i < ntiles_w) compute(i, s, std::true_type{});
+      __syncthreads();
+    }
+  }
 
 #pragma unroll
   for (int t = 0; t < NQ; ++t) {
     const float l = l_run[t] + __shfl_xor(l_run[t], 32, 64);
     const int idx = t * 32 + col, r = idx / grp, hh = idx % grp;
-    if (r < b.nrows) {
+    if (r < rows_w) {
       const float inv = 1.0f / l;
 #pragma unroll
       for (int e = 0; e < NE; ++e)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          uint2 w;
-          w.x = (uint32_t)f32_to_h16_bits(o[t][e][4 * g] * inv) | ((uint32_t)f32_to_h16_bits(o[t][e][4 * g + 1] * inv) << 16);
-          w.y = (uint32_t)f32_to_h16_bits(o[t][e][4 * g + 2] * inv) | ((uint32_t)f32_to_h16_bits(o[t][e][4 * g + 3] * inv) << 16);
-          *(uint2 *)(Xp + k8_index(b.m0 + r, (kvh * grp + hh) * HD + 32 * e + 8 * g + 4 * half, Mp)) = w;
+          uint2 wv;
+          wv.x = (uint32_t)f32_to_h16_bits(o[t][e][4 * g] * inv) | ((uint32_t)f32_to_h16_bits(o[t][e][4 * g + 1] * inv) << 16);
+          wv.y = (uint32_t)f32_to_h16_bits(o[t][e][4 * g + 2] * inv) | ((uint32_t)f32_to_h16_bits(o[t][e][4 * g + 3] * inv) << 16);
+          *(uint2 *)(Xp + k8_index(b.m0 + r0 + r, (kvh * grp + hh) * HD + 32 * e + 8 * g + 4 * half, Mp)) = wv;
         }
     }
   }
@@ -421,9 +474,13 @@ __global__ __launch_bounds__(64, 2) void attn_prefill_kernel(uint16_t *__restric
 template <int HD>
 static void attention_prefill_launch(void *Xp_out, const void *q_h16, const PrefillBlock *blocks, int nblocks, KvGeom kv, int layer,
                                      int Mp, int Hq, int Hkv, hipStream_t st) {
-  constexpr int NQ = ATT_PREFILL_COLS / 32;
-  hipLaunchKernelGGL((attn_prefill_kernel<HD, NQ>), dim3(nblocks, Hkv), dim3(64), NQ * (HD / 16) * 64 * 16, st, (uint16_t *)Xp_out, Mp,
-                     (const uint16_t *)q_h16, blocks, kv, layer, Hq, Hkv);
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void *)attn_prefill_kernel<HD>, hipFuncAttributeMaxDynamicSharedMemorySize, AttPfLds<HD>::BYTES);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(attn_prefill_kernel<HD>, dim3(nblocks, Hkv), dim3(ATT_PREFILL_WAVES * 64), AttPfLds<HD>::BYTES, st, (uint16_t *)Xp_out, Mp,
+                     (const uint16_t *)q_h16, blocks, nblocks, kv, layer, Hq, Hkv);
 }
 
 void fast_attention_prefill(void *Xp_out, const void *q_h16, const PrefillBlock *blocks, int nblocks, KvGeom kv, int layer, int Mp,
