@@ -95,6 +95,7 @@ def main():
     shape = getattr(synth, name)
     N = P * G
     torch.cuda.set_device(0)
+    t_start = time.perf_counter()
 
     def host_blob(seed):
         dev = synth.make_weights(shape, seed, device="cuda")
@@ -118,6 +119,11 @@ def main():
     ctx.load_policy(0, blob)
     load_s = time.perf_counter() - t0
     version = [0]
+
+    def progress(msg):   # stage marks on stderr: the long workloads run minutes between two lines of output otherwise
+        print(f"[bench] {msg} (+{time.perf_counter() - t_start:.1f} s)", file=sys.stderr, flush=True)
+
+    progress(f"policy installed in {load_s:.2f} s")
 
     def rollout(seed, **kw):
         """One rollout; with a swap schedule a second thread installs the next snapshot (alternating two weight
@@ -150,6 +156,7 @@ def main():
 
     for _ in range(a.warmup):
         rollout(2)
+        progress("warm-up rollout done")
     torch.cuda.synchronize()
     times, toks, decode_ms, prefill_ms, swap_wait_ms = [], 0, [], [], []
     t_all = time.perf_counter()
@@ -162,6 +169,7 @@ def main():
         decode_ms.append(st.decode_ms)
         prefill_ms.append(st.prefill_ms)
         swap_wait_ms.append(st.swap_wait_ms)
+        progress(f"timed rollout {k + 1} of {a.steps} done")
     torch.cuda.synchronize()
     total_s = time.perf_counter() - t_all
     value = toks / total_s
@@ -177,6 +185,7 @@ def main():
         t0 = time.perf_counter()
         lp = ctx.logprobs(full, flen, 1.0)
         score_s = time.perf_counter() - t0
+        progress("scoring pass done")
         hd, H = shape.head_dim, shape.hidden
         per_layer = H * (shape.n_q_heads + 2 * shape.n_kv_heads) * hd + shape.n_q_heads * hd * H + 3 * H * shape.ffn
         rows = int((flen - 1).sum())
@@ -189,6 +198,7 @@ def main():
     roofline = None
     if not a.no_kernel_timing:
         rollout(2, time_kernels=True)
+        progress("rollout with per-kernel event timing done")
         st = ctx.stats()
         if st.attn_launches:
             per_launch_bytes = st.attn_bytes / st.attn_launches
