@@ -160,6 +160,33 @@ def test_causal_block_attention_scores_every_position_like_the_oracle(heads):
     ctx.close()
 
 
+def test_full_4096_row_pass_with_wide_tiles_and_a_pass_boundary_matches_the_oracle():
+    """Ten strings, 4306 rows: the first scoring pass is a full 4096 rows, which puts the QKV and gate/up projections
+    on the 256 x 256-tile GEMM (256 and 128 tiles); one string straddles the pass boundary.  The short strings sit
+    in different 256-row blocks of the pass and are compared with the oracle at every position."""
+    shape = synth.ModelShape(2, 512, 16, 8, 128, 1024, 1024, dtype="bf16")
+    blob = synth.make_weights(shape, 21)
+    blob32 = synth.widen_to_f32(blob)
+    orc = oracle.load("f64")
+    d = oracle.desc_from_shape(shape)
+    tl = np.array([128, 1000, 96, 1200, 64, 1300, 80, 178, 100, 160], np.int32)
+    assert tl[:8].sum() == 4046 and tl.sum() == 4306
+    rng = np.random.default_rng(9)
+    toks = rng.integers(0, shape.vocab, size=(tl.size, int(tl.max()))).astype(np.int32)
+    ctx = make_ctx(shape, tl.size, 1312, blob)
+    got = ctx.logprobs(toks, tl, 1.0)
+    assert np.isfinite(got).all()
+    for n in (0, 2, 4, 6, 8, 9):
+        want = orc.logprobs(d, blob32, toks[n, :tl[n]], 1.0)
+        assert np.abs(got[n, :tl[n]] - want).max() < BF16_LOGPROB_TOL, n
+    # the long strings: scoring twice in a different order (other row blocks, other passes) gives the same numbers
+    order = np.array([5, 3, 1, 7, 0, 2, 4, 6, 9, 8])
+    again = ctx.logprobs(toks[order], tl[order], 1.0)
+    for i, n in enumerate(order):
+        assert np.abs(again[i, :tl[n]] - got[n, :tl[n]]).max() < 2e-3, n
+    ctx.close()
+
+
 def test_edge_cases_and_errors():
     from paper_2602_02192_amd import echo
     shape = synth.TINY
