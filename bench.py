@@ -18,10 +18,27 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of the decode-attention kernel (profiles/pmc_traffic_*.md), scaled by the same
-# counters on a plain 256 MiB copy: KiB fetched + written per launch over the K/V KiB the launch had to read.  Taken at the
-# same kernel, grid and shapes on a 2-layer model (the profiler crashes on the 36-layer process); set to None whenever
-# attn_splitk_kernel changes.
-ATTN_TRAFFIC_OVER_ALGORITHMIC = (143951.0 + 512.0) / 139264.0
+# counters on a plain 256 MiB copy: KiB fetched + written per launch over the KiB of the K/V tiles the launch touches
+# (shared prompt tiles once per group, a sequence's last tile whole).  Taken at the same kernel and grid on a 2-layer
+# model generating 64 tokens (the profiler crashes on the 36-layer process); set to None whenever attn_splitk_kernel changes.
+ATTN_TRAFFIC_OVER_TILE_BYTES = (29291.0 + 512.0) / (28608.0 + 512.0)
+
+
+def attn_kv_bytes_per_launch(shape, gen_lens, prompt_len, group, steps, whole_tiles):
+    """K/V bytes one decode-attention launch (one layer) reads, averaged over the decode passes `steps`: the whole
+    32-key tiles of a prompt once per group with an active sequence, everything else per active sequence.
+    whole_tiles: count the tiles the kernel touches (a sequence's last tile is fetched whole) instead of the keys."""
+    gen = np.asarray(gen_lens, np.int64)
+    shared = (prompt_len // 32) * 32 if group > 1 else 0
+    group_len = gen.reshape(-1, group).max(axis=1)
+    per_key = 2 * shape.n_kv_heads * shape.head_dim * 2
+    tot = 0.0
+    for st in steps:
+        own = prompt_len - shared + st
+        if whole_tiles:
+            own = -(-own // 32) * 32
+        tot += (int((group_len > st).sum()) * shared + int((gen > st).sum()) * own) * per_key
+    return tot / max(1, len(steps))
 
 WORKLOADS = {
     # name: shape, prompts, G, prompt_len, max_new [, stop = (lo, hi) per-sequence stop lengths, swap_every = decode
@@ -34,9 +51,12 @@ WORKLOADS = {
 }
 
 
-def algorithmic_bytes(shape, gen_lens, prompt_len):
-    """HBM bytes the decode steps must move: all decode-read weights once per step, every active
-    sequence's K/V once per step, and the new K/V written.  gen_lens: tokens generated per sequence."""
+def algorithmic_bytes(shape, gen_lens, prompt_len, group=1):
+    """HBM bytes the decode steps must move: all decode-read weights once per step, the K/V of every active
+    sequence once per step, and the new K/V written.  gen_lens: tokens generated per sequence (prompt-major,
+    `group` sequences per prompt).  The whole 32-key tiles of a prompt are read from one copy per group by the
+    decode attention kernel, so they count once per group that still has an active sequence; group=1 gives the
+    per-sequence figure (every sequence reads its own copy of everything)."""
     e = 2 if shape.dtype == "bf16" else 4
     hd, H = shape.head_dim, shape.hidden
     per_layer = H * (shape.n_q_heads + 2 * shape.n_kv_heads) * hd + shape.n_q_heads * hd * H + 3 * H * shape.ffn
@@ -44,9 +64,13 @@ def algorithmic_bytes(shape, gen_lens, prompt_len):
     kvb = 2 * shape.n_layers * shape.n_kv_heads * hd * e
     gen = np.asarray(gen_lens, np.int64)
     steps = int(gen.max())
-    active = np.array([(gen > s).sum() for s in range(1, steps)], np.int64)   # decode pass s serves sequences with gen > s
+    shared = (prompt_len // 32) * 32 if group > 1 else 0
+    group_len = gen.reshape(-1, group).max(axis=1)
     s_idx = np.arange(1, steps, dtype=np.int64)
-    total = int((w_dec + active * (prompt_len + s_idx) * kvb + active * kvb).sum())
+    active = np.array([(gen > s).sum() for s in range(1, steps)], np.int64)   # decode pass s serves sequences with gen > s
+    groups = np.array([(group_len > s).sum() for s in range(1, steps)], np.int64)
+    kv_read = groups * shared + active * (prompt_len - shared + s_idx)
+    total = int((w_dec + kv_read * kvb + active * kvb).sum())
     return total, w_dec, kvb
 
 
@@ -174,8 +198,10 @@ def main():
     total_s = time.perf_counter() - t_all
     value = toks / total_s
 
-    bytes_decode, w_dec, kvb = algorithmic_bytes(shape, out["lens"], plen)
+    bytes_decode, w_dec, kvb = algorithmic_bytes(shape, out["lens"], plen, G)
     step_frac = bytes_decode / (np.mean(decode_ms) * 1e-3) / (HBM_PEAK_GBS * 1e9)
+    bytes_per_seq = algorithmic_bytes(shape, out["lens"], plen, 1)[0]   # every sequence reading a prompt copy of its own
+    step_frac_per_seq = bytes_per_seq / (np.mean(decode_ms) * 1e-3) / (HBM_PEAK_GBS * 1e9)
     n_decode_steps = max(1, int(out["lens"].max()) - 1)
 
     score = None
@@ -204,11 +230,17 @@ def main():
             per_launch_bytes = st.attn_bytes / st.attn_launches
             per_launch_s = st.attn_ms * 1e-3 / st.attn_launches
             ach = per_launch_bytes / per_launch_s / 1e9
+            timed = [t for t in range(1, int(out["lens"].max())) if t % 16 == 1]   # the passes the library times
+            model = attn_kv_bytes_per_launch(shape, out["lens"], plen, G, timed, whole_tiles=False)
+            traffic = None
+            if ATTN_TRAFFIC_OVER_TILE_BYTES and abs(model - per_launch_bytes) <= 1e-3 * per_launch_bytes:
+                traffic = attn_kv_bytes_per_launch(shape, out["lens"], plen, G, timed, whole_tiles=True) * ATTN_TRAFFIC_OVER_TILE_BYTES
             roofline = {"bound": "hbm", "kernel": "attn_splitk_kernel (decode attention, one launch per layer)",
                         "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-                        "traffic": (per_launch_bytes * ATTN_TRAFFIC_OVER_ALGORITHMIC
-                                    if ATTN_TRAFFIC_OVER_ALGORITHMIC else None),
-                        "traffic_unit": "bytes per launch (counter ratio 1.037 x algorithmic bytes)", "launches_timed": int(st.attn_launches),
+                        "traffic": traffic,
+                        "traffic_unit": "bytes per launch: whole K/V tiles of the timed launches x 1.0235 (FETCH_SIZE + WRITE_SIZE over "
+                                        "whole-tile bytes, same kernel and grid, profiles/pmc_traffic_*.md)",
+                        "launches_timed": int(st.attn_launches),
                         "avg_launch_us": per_launch_s * 1e6, "bytes_per_launch": per_launch_bytes}
             if st.gemm_launches:
                 g = st.gemm_bytes / (st.gemm_ms * 1e-3) / 1e9
@@ -229,6 +261,7 @@ def main():
                    "stop_lens": list(wl["stop"]) if wl.get("stop") else None},
         "decode_step": {"mean_ms": float(np.mean(decode_ms)) / n_decode_steps,
                         "hbm_frac_of_8TBps": step_frac, "algorithmic_bytes_per_rollout": bytes_decode,
+                        "hbm_frac_if_every_sequence_read_its_own_prompt_copy": step_frac_per_seq,
                         "prefill_ms": float(np.mean(prefill_ms)), "policy_install_s": load_s,
                         "swaps_per_rollout": len(swaps), "swap_wait_ms": float(np.mean(swap_wait_ms))},
         "scoring_pass": score,

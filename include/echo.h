@@ -82,7 +82,7 @@ typedef struct {
   float swap_wait_ms;                     /* time the last rollout waited for staged snapshots */
   /* filled by a rollout run with time_kernels = 1 (sums over all timed launches): */
   int64_t attn_launches;
-  double attn_ms, attn_bytes; /* decode attention: HIP-event time, K/V bytes it had to read */
+  double attn_ms, attn_bytes; /* decode attention: HIP-event time, K/V bytes it had to read (whole prompt tiles once per group) */
   int64_t gemm_launches;
   double gemm_ms, gemm_bytes; /* weight-streaming GEMMs: HIP-event time, weight bytes read */
   int32_t rollout_running;    /* 1 while echo_rollout is inside its loop on another thread (a snapshot installed

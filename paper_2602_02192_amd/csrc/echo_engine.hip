@@ -142,7 +142,7 @@ Plan make_plan(const echo_model_desc *d) {
     p.o_ff = b.take(M * F * 4);
   }
   p.o_blocks = b.take(M * sizeof(PrefillBlock));   // at worst every row of a pass is a block of its own
-  p.o_rows = b.take(4 * M * 4);
+  p.o_rows = b.take(6 * M * 4);
   p.o_maps = b.take(2 * M * 4 + (size_t)d->max_seqs * 4);
   p.o_seq = b.take(3 * (size_t)d->max_seqs * 4);
   p.o_samp = b.take(4 * M * 4);
@@ -449,6 +449,7 @@ int run_chunks(echo_ctx *c, const Slot &S, const int32_t *tokens, int stride, co
     HIPCHK(c, hipMemcpyAsync(c->rows.slot, slot.data(), M * 4, hipMemcpyHostToDevice, c->cs));
     HIPCHK(c, hipMemcpyAsync(c->rows.pos, pos.data(), M * 4, hipMemcpyHostToDevice, c->cs));
     HIPCHK(c, hipMemcpyAsync(c->rows.active, act.data(), M * 4, hipMemcpyHostToDevice, c->cs));
+    launch_fill_i32(c->rows.ptiles, 0, M, c->cs);   // rows of a pass share no prefix tiles
     blocks.clear();
     if (causal_blocks) {   // runs of consecutive positions of one slot, cut every block_rows rows
       for (int i = 0; i < M; ++i) {
@@ -537,7 +538,7 @@ int echo_init(const echo_model_desc *desc, int device, void *dev_arena, size_t a
   for (int s = 0; s < desc->n_weight_slots; ++s) bind_slot(c, s);
   int32_t *r = at<int32_t>(c, p.o_rows);
   size_t M = p.Mcap;
-  c->rows = {r, r + M, r + 2 * M, r + 3 * M};
+  c->rows = {r, r + M, r + 2 * M, r + 3 * M, r + 4 * M, r + 5 * M};
   c->kv = {c->arena + p.o_kv, desc->n_layers, desc->n_kv_heads, p.fast ? (int32_t)round_up(desc->max_ctx, 32) : desc->max_ctx, desc->head_dim,
            p.fast ? 2 : 4, p.fast ? 1 : 0};
   int32_t *q = at<int32_t>(c, p.o_seq);
@@ -669,6 +670,7 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
   HIPCHK(c, hipStreamSynchronize(st));
 
   int cur = c->active;
+  const bool share_prefix = p.fast && !env_flag("ECHO_NO_PREFIX_SHARING") && !env_flag("ECHO_ATTN_SIMPLE");
   // ---- prefill the P unique prompts into cache slots p*G, keep each prompt's last hidden state
   std::vector<int> lens(prompt_lens, prompt_lens + P);
   std::vector<int32_t> map(std::max(P, N));
@@ -694,6 +696,13 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
   launch_fill_i32(c->rows.active, 1, N, st);
   for (int n = 0; n < N; ++n) map[n] = n;
   HIPCHK(c, hipMemcpyAsync(c->rows.slot, map.data(), N * 4, hipMemcpyHostToDevice, st));
+  {   // decode attention reads the whole tiles of a group's prompt from the group's first slot
+    std::vector<int32_t> pslot(N), ptiles(N);
+    for (int n = 0; n < N; ++n) { pslot[n] = n / G * G; ptiles[n] = share_prefix ? prompt_lens[n / G] / 32 : 0; }
+    HIPCHK(c, hipMemcpyAsync(c->rows.pslot, pslot.data(), N * 4, hipMemcpyHostToDevice, st));
+    HIPCHK(c, hipMemcpyAsync(c->rows.ptiles, ptiles.data(), N * 4, hipMemcpyHostToDevice, st));
+    HIPCHK(c, hipStreamSynchronize(st));   // the host vectors go out of scope
+  }
   norm_only(c, c->slots[cur], N);
   sample_rows(c, c->slots[cur], N, temperature, seed, unfused, nullptr);
   auto grab_logits = [&](int s) -> int {
@@ -744,9 +753,15 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
     bool time_this = c->timing;
     if (c->timing) {
       c->timing = (s % 16) == 1;
-      double b = 0;
-      for (int n = 0; n < N; ++n) if (s < limit[n]) b += (double)(plen_seq[n] + s) * 2 * c->d.n_kv_heads * c->d.head_dim * 2;
-      c->cur_attn_bytes = b;
+      // K/V bytes one attention launch has to read: a group's whole prompt tiles once, the rest per active sequence
+      double keys = 0;
+      for (int g0 = 0; g0 < N; g0 += G) {
+        int shared = share_prefix ? plen_seq[g0] / 32 * 32 : 0;
+        bool any = false;
+        for (int n = g0; n < g0 + G; ++n) if (s < limit[n]) { keys += plen_seq[n] - shared + s; any = true; }
+        if (any) keys += shared;
+      }
+      c->cur_attn_bytes = keys * 2 * c->d.n_kv_heads * c->d.head_dim * 2;
     }
     if (use_graph) {
       if (!have_graph) {

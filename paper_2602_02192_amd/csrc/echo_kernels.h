@@ -21,6 +21,8 @@ struct RowState {        // device arrays, one entry per row of the current batc
   int32_t *slot;         // KV-cache sequence slot of the row
   int32_t *pos;          // position of the token inside its sequence
   int32_t *active;       // 0: row is skipped (finished sequence or padding)
+  int32_t *pslot;        // slot whose first ptiles key tiles equal this row's (its group's prompt); read by the split-K
+  int32_t *ptiles;       //   attention kernel only, which takes those tiles from pslot so that a group shares them in cache
 };
 
 struct KvGeom {          // KV cache, plain form: [slot][layer][K|V][kv_head][max_ctx][head_dim]

@@ -119,12 +119,20 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
   const int key1 = min(n_keys, key0 + chunk_keys), ntiles = (key1 - key0 + ATT_TILE - 1) / ATT_TILE, tile0 = key0 / ATT_TILE;
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
   const v4u *head = (const v4u *)((const uint16_t *)kv.base + kv.tiled_head_off(rows.slot[m], layer, kvh));
+  // The whole tiles of the group's prompt are identical in every sequence of the group; all of them read the copy of
+  // one slot, so the tiles reach HBM once per group and the other sequences find them in L2 (workgroups of one KV head
+  // land on one XCD, i.e. behind one L2).
+  const v4u *head_sh = (const v4u *)((const uint16_t *)kv.base + kv.tiled_head_off(rows.pslot[m], layer, kvh));
+  const int ptiles = rows.ptiles[m];
 
   // One K and one V register tile per wavefront.  The next tile's K is requested as soon as K Q^T has consumed the
   // current one, the next V as soon as V^T P^T has; loads return in order, so waiting for V leaves the next K in flight.
   v4u rk[KS], rv[KS];
+  // (streaming loads for the shared tiles too: measured faster than cached loads, the concurrent misses of a group merge)
+  auto issue_k = [&](int t) { att_issue_k<HD, true>(rk, t < ptiles ? head_sh : head, t, lane); };
+  auto issue_v = [&](int t) { att_issue_v<HD, true>(rv, t < ptiles ? head_sh : head, t, lane); };
   int tile = w;
-  if (tile < ntiles) { att_issue_k<HD>(rk, head, tile0 + tile, lane); att_issue_v<HD>(rv, head, tile0 + tile, lane); }
+  if (tile < ntiles) { issue_k(tile0 + tile); issue_v(tile0 + tile); }
 
   // the group's queries as B operands in LDS: unit (ks*2 + half)*8 + head holds dims ks*16 + half*8 .. +8 of one head
   v4u *qs = (v4u *)(lds + ATT_WAVES * L::MERGE_PER_WAVE);
@@ -157,7 +165,7 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
       s = mfma_h16(__builtin_bit_cast(h16x8, rk[ks]), __builtin_bit_cast(h16x8, qb), s);
     }
     // the MFMAs above read rk when they issue; the loads below write rk when the data arrives, after them
-    if (more) att_issue_k<HD>(rk, head, tile0 + tile + ATT_WAVES, lane);
+    if (more) issue_k(tile0 + tile + ATT_WAVES);
     // ---- online softmax for head `col` over the tile's keys (register 4g+i: key 8g + 4*half + i)
     const int kbase = key0 + tile * ATT_TILE + 4 * half;
     float tm = -INFINITY;
@@ -203,7 +211,7 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
       for (int e = 0; e < NE; ++e)
         o[e] = mfma_h16(__builtin_bit_cast(h16x8, rv[ks2 * NE + e]), __builtin_bit_cast(h16x8, pb), o[e]);
     }
-    if (more) att_issue_v<HD>(rv, head, tile0 + tile + ATT_WAVES, lane);
+    if (more) issue_v(tile0 + tile + ATT_WAVES);
   };
   // every tile but the wavefront's last requests its successor unconditionally: a load behind a condition would make
   // the compiler's wait counts assume it was not issued, and the waits that follow would drain the queue

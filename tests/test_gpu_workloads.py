@@ -187,6 +187,32 @@ def test_full_4096_row_pass_with_wide_tiles_and_a_pass_boundary_matches_the_orac
     ctx.close()
 
 
+def test_group_shared_prompt_tiles_change_no_bit(monkeypatch):
+    """Decode attention reads the whole 32-key tiles of a prompt from the group's first cache slot.  With that switched
+    off every sequence reads its own replicated copy: tokens and log-probs must be identical bit for bit.  Prompt lengths
+    below, at and between tile boundaries; sequences of a group stop at different lengths (the first one earliest)."""
+    shape = MID
+    blob = synth.make_weights(shape, 5)
+    prompts, lens = synth.make_prompts(shape.vocab, 5, 100, seed=8)
+    lens[:] = [31, 32, 33, 64, 100]
+    G, max_new = 4, 40
+    stop = np.tile(np.array([3, 40, 17, 29], np.int32), 5)
+    ctx = make_ctx(shape, 5 * G, 160, blob)
+    a = ctx.rollout(prompts, lens, G, max_new, 1.0, 11, stop_lens=stop)
+    monkeypatch.setenv("ECHO_NO_PREFIX_SHARING", "1")
+    b = ctx.rollout(prompts, lens, G, max_new, 1.0, 11, stop_lens=stop)
+    monkeypatch.delenv("ECHO_NO_PREFIX_SHARING")
+    assert np.array_equal(a["lens"], stop) and np.array_equal(b["lens"], stop)
+    assert np.array_equal(a["tokens"], b["tokens"])
+    assert np.array_equal(a["logprobs"], b["logprobs"])
+    # and the shared path against the oracle (teacher-forced on the oracle's tokens)
+    blob32 = synth.widen_to_f32(blob)
+    ref = oracle_rollout(shape, blob32, prompts, lens, G=G, max_new=12, temperature=1.0, seed=11, want_logits=True)
+    tf = ctx.rollout(prompts, lens, G, 12, 1.0, 11, forced=np.maximum(ref["tokens"], 0), want_logits=True)
+    assert np.abs(tf["logits"] - ref["logits"]).max() < BF16_LOGIT_TOL
+    ctx.close()
+
+
 def test_edge_cases_and_errors():
     from paper_2602_02192_amd import echo
     shape = synth.TINY
