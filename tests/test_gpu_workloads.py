@@ -187,17 +187,22 @@ def test_full_4096_row_pass_with_wide_tiles_and_a_pass_boundary_matches_the_orac
     ctx.close()
 
 
-def test_group_shared_prompt_tiles_change_no_bit(monkeypatch):
-    """Decode attention reads the whole 32-key tiles of a prompt from the group's first cache slot.  With that switched
-    off every sequence reads its own replicated copy: tokens and log-probs must be identical bit for bit.  Prompt lengths
-    below, at and between tile boundaries; sequences of a group stop at different lengths (the first one earliest)."""
-    shape = MID
+GRP8 = synth.ModelShape(2, 512, 16, 2, 64, 1024, 2048, dtype="bf16")
+
+
+@pytest.mark.parametrize("shape,G,P", [(MID, 8, 21), (GRP8, 8, 21), (MID, 3, 54), (MID, 4, 5)],
+                         ids=["grp4-G8", "grp8-G8", "grp4-G3", "grp4-G4-keys-split-over-workgroups"])
+def test_group_shared_prompt_tiles(monkeypatch, shape, G, P):
+    """Decode attention reads the whole 32-key tiles of a prompt from the group's first cache slot (three cases with
+    enough rows that every row's keys stay in one workgroup, one small batch whose keys are split over workgroups).  Prompt lengths below, at and between tile boundaries;
+    sequences of a group stop at different lengths."""
     blob = synth.make_weights(shape, 5)
-    prompts, lens = synth.make_prompts(shape.vocab, 5, 100, seed=8)
-    lens[:] = [31, 32, 33, 64, 100]
-    G, max_new = 4, 40
-    stop = np.tile(np.array([3, 40, 17, 29], np.int32), 5)
-    ctx = make_ctx(shape, 5 * G, 160, blob)
+    prompts, lens = synth.make_prompts(shape.vocab, P, 100, seed=8)
+    lens[:] = np.resize(np.array([31, 32, 33, 64, 100, 7, 96], np.int32), P)
+    N, max_new = P * G, 40
+    stop = np.resize(np.array([3, 40, 17, 29, 40, 1, 36, 22], np.int32), N)
+    ctx = make_ctx(shape, N, 160, blob)
+    # 1. every row reading the group's copy of the prompt tiles against every row reading its own replicated copy: bit for bit
     a = ctx.rollout(prompts, lens, G, max_new, 1.0, 11, stop_lens=stop)
     monkeypatch.setenv("ECHO_NO_PREFIX_SHARING", "1")
     b = ctx.rollout(prompts, lens, G, max_new, 1.0, 11, stop_lens=stop)
@@ -205,11 +210,17 @@ def test_group_shared_prompt_tiles_change_no_bit(monkeypatch):
     assert np.array_equal(a["lens"], stop) and np.array_equal(b["lens"], stop)
     assert np.array_equal(a["tokens"], b["tokens"])
     assert np.array_equal(a["logprobs"], b["logprobs"])
-    # and the shared path against the oracle (teacher-forced on the oracle's tokens)
+    # 2. against the oracle, teacher-forced on the oracle's tokens, for three prompts spread over the batch
     blob32 = synth.widen_to_f32(blob)
-    ref = oracle_rollout(shape, blob32, prompts, lens, G=G, max_new=12, temperature=1.0, seed=11, want_logits=True)
-    tf = ctx.rollout(prompts, lens, G, 12, 1.0, 11, forced=np.maximum(ref["tokens"], 0), want_logits=True)
-    assert np.abs(tf["logits"] - ref["logits"]).max() < BF16_LOGIT_TOL
+    pick = [0, P // 2, P - 1]
+    forced12 = np.zeros((N, 12), np.int32)
+    refs = {}
+    for p in pick:
+        refs[p] = oracle_rollout(shape, blob32, prompts[p:p + 1], lens[p:p + 1], G=G, max_new=12, temperature=1.0, seed=11, want_logits=True)
+        forced12[p * G:(p + 1) * G] = np.maximum(refs[p]["tokens"], 0)
+    tf = ctx.rollout(prompts, lens, G, 12, 1.0, 11, forced=forced12, want_logits=True)
+    for p in pick:
+        assert np.abs(tf["logits"][p * G:(p + 1) * G] - refs[p]["logits"]).max() < BF16_LOGIT_TOL, p
     ctx.close()
 
 
