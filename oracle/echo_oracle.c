@@ -383,6 +383,68 @@ void orc_sample(const real *logits, int V, float temperature, uint64_t seed, uin
   if (gap_out) *gap_out = best - second;
 }
 
+/* Nucleus (top-p) sampling, the paper's rollout setting (Sec. 5.1: temperature 1.0, top-p 0.95): with
+ * p = softmax(logits / temperature), order the tokens by probability, highest first and the lower index
+ * first among equals, keep the shortest prefix of that order whose probabilities sum to at least top_p,
+ * and sample from the kept set in proportion to p -- here again by the Gumbel-max rule with the same
+ * noise g_i per vocabulary index, restricted to the kept set.  The returned log-prob is that of the
+ * distribution actually sampled, i.e. renormalised over the kept set (the sampler's probability is what
+ * the importance ratio of App. "GRPO-Style Policy Gradient Objective" divides by).  top_p >= 1 keeps
+ * everything and is orc_sample.  kept_out: size of the kept set; margin_out: how far the cumulative
+ * probability is from top_p on either side of the cut (a margin near zero marks a cut that rounding
+ * could move by one token). */
+typedef struct { real z; int32_t i; } orc_zi;
+static int zi_desc(const void *a, const void *b) {
+  const orc_zi *x = (const orc_zi *)a, *y = (const orc_zi *)b;
+  if (x->z > y->z) return -1;
+  if (x->z < y->z) return 1;
+  return x->i < y->i ? -1 : (x->i > y->i ? 1 : 0);
+}
+void orc_sample_top_p(const real *logits, int V, float temperature, float top_p, uint64_t seed, uint32_t n,
+                      uint32_t s, int32_t *tok_out, double *logprob_out, float *gap_out, int32_t *kept_out,
+                      double *margin_out) {
+  if (!(top_p < 1.0f)) {
+    orc_sample(logits, V, temperature, seed, n, s, tok_out, logprob_out, gap_out);
+    if (kept_out) *kept_out = V;
+    if (margin_out) *margin_out = 1.0;
+    return;
+  }
+  orc_zi *zs = (orc_zi *)malloc(sizeof(orc_zi) * (size_t)V);
+  real mx = logits[0] / (real)temperature;
+  for (int i = 0; i < V; ++i) { zs[i].z = logits[i] / (real)temperature; zs[i].i = i; if (zs[i].z > mx) mx = zs[i].z; }
+  real den = 0;
+  for (int i = 0; i < V; ++i) den += (real)exp((double)(zs[i].z - mx));
+  qsort(zs, (size_t)V, sizeof(orc_zi), zi_desc);
+  real cum = 0, before = 0;
+  int k = 0;
+  while (k < V) {   /* shortest prefix with cumulative probability >= top_p */
+    before = cum;
+    cum += (real)exp((double)(zs[k].z - mx)) / den;
+    ++k;
+    if (cum >= (real)top_p) break;
+  }
+  float best = 0.f, second = -INFINITY;
+  int32_t bi = -1;
+  real bz = 0, den_kept = 0;
+  for (int j = 0; j < k; ++j) {
+    int i = zs[j].i;
+    float z = (float)logits[i] / temperature;
+    float sc = z + orc_gumbel(orc_uniform(orc_draw_bits(seed, n, s, (uint32_t)i)));
+    if (bi < 0 || sc > best || (sc == best && i < bi)) { if (bi >= 0) second = best > second ? best : second; best = sc; bi = i; bz = zs[j].z; }
+    else if (sc > second) second = sc;
+    den_kept += (real)exp((double)(zs[j].z - mx));
+  }
+  *tok_out = bi;
+  *logprob_out = (double)(bz - (mx + (real)log((double)den_kept)));
+  if (gap_out) *gap_out = best - second;
+  if (kept_out) *kept_out = k;
+  if (margin_out) {
+    double lo = (double)top_p - (double)before, hi = (double)cum - (double)top_p;
+    *margin_out = k < V ? (lo < hi ? lo : hi) : lo;
+  }
+  free(zs);
+}
+
 /* Rollout of P prompts x G samples (sequence n = p*G + g), each sequence on its own.
  *   blobs[j], versions[j], j < n_models: policy snapshots; snapshot j+1 replaces j
  *     for every forward pass that produces the logits of generation step >=
@@ -394,12 +456,13 @@ void orc_sample(const real *logits, int V, float temperature, uint64_t seed, uin
  *     log-prob are still recorded, but the token fed back is forced[n][s].
  * Outputs: tokens [N][max_new] (pad -1), logprobs [N][max_new] (pad 0), lens [N],
  *   versions [N][max_new] (pad -1); optional logits [N][max_new][V] and gaps. */
-int orc_rollout(const orc_desc *d, int n_models, const float *const *blobs, const int64_t *versions,
-                const int32_t *swap_at_step, const int32_t *prompts, int prompt_stride,
-                const int32_t *prompt_lens, int P, int G, int max_new, float temperature, uint64_t seed,
-                const int32_t *stop_lens, int eos_id, const int32_t *forced, int32_t *out_tokens,
-                double *out_logprobs, int32_t *out_lens, int64_t *out_versions, double *out_logits,
-                float *out_gaps) {
+int orc_rollout_top_p(const orc_desc *d, int n_models, const float *const *blobs, const int64_t *versions,
+                      const int32_t *swap_at_step, const int32_t *prompts, int prompt_stride,
+                      const int32_t *prompt_lens, int P, int G, int max_new, float temperature, float top_p,
+                      uint64_t seed, const int32_t *stop_lens, int eos_id, const int32_t *forced,
+                      int32_t *out_tokens, double *out_logprobs, int32_t *out_lens, int64_t *out_versions,
+                      double *out_logits, float *out_gaps, double *out_margins) {
+  if (!(top_p > 0.f)) return -1;
   if (n_models < 1 || P < 0 || G < 1 || max_new < 0 || !(temperature > 0.f)) return -1;
   orc_model **ms = (orc_model **)calloc((size_t)n_models, sizeof(orc_model *));
   for (int j = 0; j < n_models; ++j) ms[j] = model_bind(d, blobs[j]);
@@ -423,8 +486,9 @@ int orc_rollout(const orc_desc *d, int n_models, const float *const *blobs, cons
         int32_t fed = forced ? forced[(int64_t)n * max_new + s - 1] : out_tokens[(int64_t)n * max_new + s - 1];
         decode_token(ms[cur], sq, fed, lg);
       }
-      int32_t tok; double lp; float gap;
-      orc_sample(lg, V, temperature, seed, (uint32_t)n, (uint32_t)s, &tok, &lp, &gap);
+      int32_t tok; double lp, margin; float gap;
+      orc_sample_top_p(lg, V, temperature, top_p, seed, (uint32_t)n, (uint32_t)s, &tok, &lp, &gap, NULL, &margin);
+      if (out_margins) out_margins[(int64_t)n * max_new + s] = margin;
       out_tokens[(int64_t)n * max_new + s] = tok;
       out_logprobs[(int64_t)n * max_new + s] = lp;
       out_versions[(int64_t)n * max_new + s] = versions[s == 0 ? 0 : cur];
@@ -441,6 +505,17 @@ int orc_rollout(const orc_desc *d, int n_models, const float *const *blobs, cons
   for (int j = 0; j < n_models; ++j) model_free(ms[j]);
   free(ms);
   return 0;
+}
+
+int orc_rollout(const orc_desc *d, int n_models, const float *const *blobs, const int64_t *versions,
+                const int32_t *swap_at_step, const int32_t *prompts, int prompt_stride,
+                const int32_t *prompt_lens, int P, int G, int max_new, float temperature, uint64_t seed,
+                const int32_t *stop_lens, int eos_id, const int32_t *forced, int32_t *out_tokens,
+                double *out_logprobs, int32_t *out_lens, int64_t *out_versions, double *out_logits,
+                float *out_gaps) {
+  return orc_rollout_top_p(d, n_models, blobs, versions, swap_at_step, prompts, prompt_stride, prompt_lens, P, G, max_new,
+                           temperature, 1.0f, seed, stop_lens, eos_id, forced, out_tokens, out_logprobs, out_lens,
+                           out_versions, out_logits, out_gaps, NULL);
 }
 
 /* Teacher-forced scoring of one token string under one snapshot:
@@ -495,6 +570,14 @@ void orc_log_softmax_d(double *out, const double *logits, int n, float temperatu
   orc_log_softmax(lo, li, n, temperature);
   for (int i = 0; i < n; ++i) out[i] = (double)lo[i];
   free(li); free(lo);
+}
+
+void orc_sample_top_p_d(const double *logits, int V, float temperature, float top_p, uint64_t seed, uint32_t n, uint32_t s,
+                        int32_t *tok_out, double *logprob_out, float *gap_out, int32_t *kept_out, double *margin_out) {
+  real *li = (real *)malloc(sizeof(real) * (size_t)V);
+  for (int i = 0; i < V; ++i) li[i] = (real)logits[i];
+  orc_sample_top_p(li, V, temperature, top_p, seed, n, s, tok_out, logprob_out, gap_out, kept_out, margin_out);
+  free(li);
 }
 
 void orc_sample_d(const double *logits, int V, float temperature, uint64_t seed, uint32_t n, uint32_t s,

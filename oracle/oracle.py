@@ -111,6 +111,17 @@ class Oracle:
         self.lib.orc_sample_d(z, z.size, temperature, seed, n, s, C.byref(tok), C.byref(lp), C.byref(gap))
         return tok.value, lp.value, gap.value
 
+    def sample_top_p(self, logits, temperature: float, top_p: float, seed: int, n: int, s: int):
+        """(token, log-prob under the renormalised kept set, gap, size of the kept set, margin of the cut)."""
+        z = np.ascontiguousarray(logits, np.float64)
+        tok, lp, gap, kept, margin = C.c_int32(), C.c_double(), C.c_float(), C.c_int32(), C.c_double()
+        self.lib.orc_sample_top_p_d.argtypes = [_f64p, C.c_int, C.c_float, C.c_float, C.c_uint64, C.c_uint32, C.c_uint32,
+                                                C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_float),
+                                                C.POINTER(C.c_int32), C.POINTER(C.c_double)]
+        self.lib.orc_sample_top_p_d(z, z.size, temperature, top_p, seed, n, s, C.byref(tok), C.byref(lp), C.byref(gap),
+                                    C.byref(kept), C.byref(margin))
+        return tok.value, lp.value, gap.value, kept.value, margin.value
+
     # -- model-level --------------------------------------------------------------------
     def blob_numel(self, desc: Desc) -> int:
         return int(self.lib.orc_blob_numel(C.byref(desc)))
@@ -145,7 +156,7 @@ class Oracle:
     def rollout(self, desc: Desc, blobs, prompts, prompt_lens, G: int, max_new: int,
                 temperature: float, seed: int, versions: Optional[Sequence[int]] = None,
                 swap_at_step: Optional[Sequence[int]] = None, stop_lens=None, eos_id: int = -1,
-                forced=None, want_logits: bool = False) -> dict:
+                forced=None, want_logits: bool = False, top_p: float = 1.0) -> dict:
         if isinstance(blobs, np.ndarray):
             blobs = [blobs]
         blobs = [self._check_blob(desc, b) for b in blobs]
@@ -170,14 +181,17 @@ class Oracle:
         frc = np.ascontiguousarray(forced, np.int32) if forced is not None else None
         if frc is not None and frc.shape != (N, max_new):
             raise ValueError("forced must be [N, max_new]")
-        self.lib.orc_rollout.argtypes = None
-        rc = self.lib.orc_rollout(C.byref(desc), C.c_int(nm), bp, vp(versions), vp(swaps if swaps.size else np.zeros(1, np.int32)),
-                                  vp(prompts), C.c_int(prompts.shape[1]), vp(prompt_lens), C.c_int(P), C.c_int(G),
-                                  C.c_int(max_new), C.c_float(temperature), C.c_uint64(seed), vp(stop),
-                                  C.c_int(eos_id), vp(frc), vp(toks), vp(lps), vp(lens), vp(vers), vp(logits), vp(gaps))
+        margins = np.ones((N, max_new), np.float64)
+        self.lib.orc_rollout_top_p.argtypes = None
+        self.lib.orc_rollout_top_p.restype = C.c_int
+        rc = self.lib.orc_rollout_top_p(C.byref(desc), C.c_int(nm), bp, vp(versions), vp(swaps if swaps.size else np.zeros(1, np.int32)),
+                                        vp(prompts), C.c_int(prompts.shape[1]), vp(prompt_lens), C.c_int(P), C.c_int(G),
+                                        C.c_int(max_new), C.c_float(temperature), C.c_float(top_p), C.c_uint64(seed), vp(stop),
+                                        C.c_int(eos_id), vp(frc), vp(toks), vp(lps), vp(lens), vp(vers), vp(logits), vp(gaps),
+                                        vp(margins))
         if rc != 0:
-            raise RuntimeError(f"orc_rollout failed: {rc}")
-        return dict(tokens=toks, logprobs=lps, lens=lens, versions=vers, gaps=gaps, logits=logits)
+            raise RuntimeError(f"orc_rollout_top_p failed: {rc}")
+        return dict(tokens=toks, logprobs=lps, lens=lens, versions=vers, gaps=gaps, logits=logits, margins=margins)
 
     def set_threads(self, n: int) -> None:
         self.lib.orc_set_threads(n)
