@@ -45,6 +45,8 @@ WORKLOADS = {
     # steps between snapshot swaps, score = teacher-forced log-prob pass over all generated strings afterwards]
     "tiny-fp32": dict(shape="TINY", P=4, G=2, plen=16, max_new=32),
     "dense4b-64x512+1024": dict(shape="DENSE_4B", P=8, G=8, plen=512, max_new=1024),
+    # the same with the paper's sampling setting (Sec. 5.1: top-p 0.95): logits are materialised and cut per step
+    "dense4b-64x512+1024-top_p0.95": dict(shape="DENSE_4B", P=8, G=8, plen=512, max_new=1024, top_p=0.95),
     "dense4b-kvheavy-256x1024+4096": dict(shape="DENSE_4B", P=32, G=8, plen=1024, max_new=4096, stop=(512, 4096)),
     "dense8b-128x512+2048-swap256": dict(shape="DENSE_8B", P=16, G=8, plen=512, max_new=2048, swap_every=256),
     "dense32b-64x1024+4096-score": dict(shape="DENSE_32B", P=8, G=8, plen=1024, max_new=4096, score=True),
@@ -152,6 +154,7 @@ def main():
     def rollout(seed, **kw):
         """One rollout; with a swap schedule a second thread installs the next snapshot (alternating two weight
         sets) as soon as the previous one has been switched in, as a worker's receiver thread would."""
+        kw.setdefault("top_p", wl.get("top_p", 1.0))
         if not swaps:
             return ctx.rollout(prompts, lens, G, max_new, 1.0, seed, stop_lens=stop, no_graph=a.no_graph, **kw)
         import threading
@@ -257,7 +260,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16 MFMA operands, f32 accumulate (bf16 weights)" if shape.dtype == "bf16" else "f32", "data": "synthetic (random N(0,0.02) weights, uniform random prompt tokens)",
         "config": {"workload": a.workload, "model": name, "sequences": N, "prompts": P, "group": G,
-                   "prompt_len": plen, "max_new": max_new, "temperature": 1.0,
+                   "prompt_len": plen, "max_new": max_new, "temperature": 1.0, "top_p": wl.get("top_p", 1.0),
                    "stop_lens": list(wl["stop"]) if wl.get("stop") else None},
         "decode_step": {"mean_ms": float(np.mean(decode_ms)) / n_decode_steps,
                         "hbm_frac_of_8TBps": step_frac, "algorithmic_bytes_per_rollout": bytes_decode,

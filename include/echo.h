@@ -59,7 +59,9 @@ typedef struct {
 typedef struct {
   const int32_t *stop_lens;    /* host [N] or NULL: sequence n ends after min(max_new, stop_lens[n]) tokens */
   int32_t eos_id;              /* >= 0: a sequence also ends after emitting this token (kept); -1: none */
-  float top_p;                 /* nucleus mass; only 1.0 (no truncation) is implemented */
+  float top_p;                 /* in (0, 1]; 1.0: no truncation.  Below 1 (Sec. 5.1 runs rollouts at 0.95): sample from the
+                                  shortest descending-probability prefix reaching top_p; out_logprobs are then renormalised
+                                  over that kept set (the distribution actually sampled); logits are materialised per step */
   int32_t n_swaps;             /* snapshot switches pinned inside this rollout */
   const int32_t *swap_at_step; /* host [n_swaps], ascending, >= 1: from generation step k on, the forward
                                   passes use the snapshot staged by echo_load_policy (the call waits for it,

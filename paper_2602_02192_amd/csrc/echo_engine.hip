@@ -43,7 +43,7 @@ struct Plan {
   int Np_qkv, Np_d, Np_gu, Np_v, Kp_d, Kp_q, Kp_f;
   size_t slot_bytes, o_slot[2], o_kv, kv_bytes;
   size_t o_h, o_x, o_qkv, o_att, o_gu, o_ff, o_logits, o_q16, o_xa, o_xatt, o_xff, o_part, o_rope, o_lmpart;
-  size_t o_attn_o, o_attn_ml;
+  size_t o_attn_o, o_attn_ml, o_topp;
   size_t o_blocks, o_rows, o_seq, o_samp, o_out_tok, o_out_lp, o_out_ver, o_forced, o_scal, o_first_h, o_stage, o_maps;
   size_t stage_bytes, part_floats, logit_rows = 0, total;
   int attn_chunk, attn_max_splits;
@@ -142,6 +142,7 @@ Plan make_plan(const echo_model_desc *d) {
     p.o_ff = b.take(M * F * 4);
   }
   p.o_blocks = b.take(M * sizeof(PrefillBlock));   // at worst every row of a pass is a block of its own
+  p.o_topp = b.take(fast_topp_scratch_floats((int)pad_rows(d->max_seqs)) * 4);
   p.o_rows = b.take(6 * M * 4);
   p.o_maps = b.take(2 * M * 4 + (size_t)d->max_seqs * 4);
   p.o_seq = b.take(3 * (size_t)d->max_seqs * 4);
@@ -387,7 +388,16 @@ void forward_layers(echo_ctx *c, const Slot &S, int M, bool use_splitk_attn, int
 }
 
 // lm_head + sampler over the normed rows left by forward_layers (or by norm_only).
-void sample_rows(echo_ctx *c, const Slot &S, int M, float temperature, uint64_t seed, bool unfused, const int32_t *target) {
+// top_p < 1: cut, slice partials, combine -> d_samp_tok / d_samp_lp
+void nucleus(echo_ctx *c, const float *logits, int64_t ld, int M, float temperature, float top_p, uint64_t seed) {
+  int Mp = pad_rows(M);
+  float *scratch = at<float>(c, c->p.o_topp);
+  fast_topp_cut_and_draw(scratch, logits, ld, M, Mp, c->d.vocab, temperature, top_p, seed, c->d_step, nullptr, c->cs);
+  fast_sample_combine(c->d_samp_tok, c->d_samp_lp, scratch, TOPP_CHUNKS_PER_ROW, M, Mp, nullptr, c->cs);
+}
+
+void sample_rows(echo_ctx *c, const Slot &S, int M, float temperature, uint64_t seed, bool unfused, const int32_t *target,
+                 float top_p = 1.0f) {
   const echo_model_desc &d = c->d;
   const Plan &p = c->p;
   hipStream_t st = c->cs;
@@ -395,7 +405,8 @@ void sample_rows(echo_ctx *c, const Slot &S, int M, float temperature, uint64_t 
   if (!p.fast) {
     int bf = d.dtype == ECHO_BF16;
     dbg_gemm(logits, at<float>(c, p.o_x), S.lm_head, bf, M, d.vocab, d.hidden, 0, st);
-    dbg_sample(c->d_samp_tok, c->d_samp_lp, logits, d.vocab, M, d.vocab, temperature, seed, c->d_step, nullptr, st);
+    if (top_p < 1.0f) nucleus(c, logits, d.vocab, M, temperature, top_p, seed);
+    else dbg_sample(c->d_samp_tok, c->d_samp_lp, logits, d.vocab, M, d.vocab, temperature, seed, c->d_step, nullptr, st);
     if (target) dbg_target_logprob(c->d_target_lp, logits, d.vocab, M, d.vocab, temperature, target, st);
     return;
   }
@@ -405,7 +416,8 @@ void sample_rows(echo_ctx *c, const Slot &S, int M, float temperature, uint64_t 
       TimerScope t(c, &c->ev_gemm);
       fast_lmhead_logits(logits, p.Np_v, at<void>(c, p.o_xa), S.lm_head, Mp, p.Np_v, p.Kp_d, d.vocab, st);
     }
-    dbg_sample(c->d_samp_tok, c->d_samp_lp, logits, p.Np_v, M, d.vocab, temperature, seed, c->d_step, nullptr, st);
+    if (top_p < 1.0f) nucleus(c, logits, p.Np_v, M, temperature, top_p, seed);
+    else dbg_sample(c->d_samp_tok, c->d_samp_lp, logits, p.Np_v, M, d.vocab, temperature, seed, c->d_step, nullptr, st);
     if (target) dbg_target_logprob(c->d_target_lp, logits, p.Np_v, M, d.vocab, temperature, target, st);
   } else {
     TimerScope t(c, &c->ev_gemm);
@@ -469,12 +481,12 @@ int run_chunks(echo_ctx *c, const Slot &S, const int32_t *tokens, int stride, co
 }
 
 int capture_step(echo_ctx *c, const Slot &S, int N, int max_new, float temperature, uint64_t seed, bool unfused, const int32_t *forced,
-                 int eos) {
+                 int eos, float top_p) {
   if (c->graph) { hipGraphExecDestroy(c->graph); c->graph = nullptr; }
   hipGraph_t g = nullptr;
   HIPCHK(c, hipStreamBeginCapture(c->cs, hipStreamCaptureModeThreadLocal));
   forward_layers(c, S, N, !env_flag("ECHO_ATTN_SIMPLE"));
-  sample_rows(c, S, N, temperature, seed, unfused, nullptr);
+  sample_rows(c, S, N, temperature, seed, unfused, nullptr, top_p);
   launch_bookkeeping(N, max_new, c->d_step, c->d_samp_tok, c->d_samp_lp, forced, c->d_limit, eos, S.version, c->d_prompt_len_seq,
                      c->d_gen_len, c->rows, at<int32_t>(c, c->p.o_out_tok), at<float>(c, c->p.o_out_lp), at<int64_t>(c, c->p.o_out_ver),
                      c->d_n_active, c->cs);
@@ -603,7 +615,7 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
   if (!prompt_tokens || !prompt_lens || !out_tokens || !out_logprobs || !out_lens) return fail(c, ECHO_EINVAL, "NULL argument");
   if (P < 1 || G < 1 || max_new < 1 || prompt_stride < 1) return fail(c, ECHO_EINVAL, "n_prompts, G, max_new and prompt_stride must be positive");
   if (!(temperature > 0.f)) return fail(c, ECHO_EINVAL, "temperature must be positive");
-  if (o.top_p != 1.0f) return fail(c, ECHO_EINVAL, "top_p != 1 is not implemented");
+  if (!(o.top_p > 0.f) || o.top_p > 1.0f) return fail(c, ECHO_EINVAL, "top_p must be in (0, 1]");
   int64_t N64 = (int64_t)P * G;
   if (N64 > c->d.max_seqs) return fail(c, ECHO_ENOMEM, "%lld sequences exceed max_seqs = %d", (long long)N64, c->d.max_seqs);
   int N = (int)N64, max_pl = 0;
@@ -639,7 +651,7 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
   const Plan &p = c->p;
   hipStream_t st = c->cs;
   auto t0 = std::chrono::steady_clock::now();
-  bool unfused = o.unfused_sampler || o.debug_logits;
+  bool unfused = o.unfused_sampler || o.debug_logits || o.top_p < 1.0f;   // the nucleus cut needs the whole row of logits
   bool want_timing = o.time_kernels != 0;
   c->timing = false;
   bool use_graph = !o.no_graph && !want_timing && !o.debug_logits;
@@ -704,7 +716,7 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
     HIPCHK(c, hipStreamSynchronize(st));   // the host vectors go out of scope
   }
   norm_only(c, c->slots[cur], N);
-  sample_rows(c, c->slots[cur], N, temperature, seed, unfused, nullptr);
+  sample_rows(c, c->slots[cur], N, temperature, seed, unfused, nullptr, o.top_p);
   auto grab_logits = [&](int s) -> int {
     if (!o.debug_logits) return 0;
     HIPCHK(c, hipMemcpy2DAsync(o.debug_logits + (int64_t)s * c->d.vocab, (size_t)max_new * c->d.vocab * 4, at<float>(c, p.o_logits),
@@ -765,13 +777,13 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
     }
     if (use_graph) {
       if (!have_graph) {
-        if ((rc = capture_step(c, c->slots[cur], N, max_new, temperature, seed, unfused, d_forced, o.eos_id))) return rc;
+        if ((rc = capture_step(c, c->slots[cur], N, max_new, temperature, seed, unfused, d_forced, o.eos_id, o.top_p))) return rc;
         have_graph = true;
       }
       HIPCHK(c, hipGraphLaunch(c->graph, st));
     } else {
       forward_layers(c, c->slots[cur], N, splitk);
-      sample_rows(c, c->slots[cur], N, temperature, seed, unfused, nullptr);
+      sample_rows(c, c->slots[cur], N, temperature, seed, unfused, nullptr, o.top_p);
       if ((rc = grab_logits(s))) return rc;
       book(cur);
     }

@@ -124,6 +124,14 @@ void fast_lmhead_sample(int32_t *tok, float *lp, float *target_lp, const void *X
                         int V, int Np, int Kp, float temperature, uint64_t seed, const int32_t *d_step,
                         const int32_t *row_active, const int32_t *target, float *partials, hipStream_t st);
 size_t fast_lmhead_partial_floats(int Np, int Mp);
+// Nucleus sampling over fp32 logits [M][ld] (top_p < 1): finds every row's cut and leaves the sampler's partials of
+// TOPP_CHUNKS vocabulary slices per row in scratch (fast_topp_scratch_floats(Mp) floats), in the layout that
+// fast_sample_combine merges into the token and its log-prob under the renormalised kept set.
+constexpr int TOPP_CHUNKS_PER_ROW = 16;
+size_t fast_topp_scratch_floats(int Mp);
+void fast_topp_cut_and_draw(float *scratch, const float *logits, int64_t ld, int M, int Mp, int V, float temperature, float top_p,
+                            uint64_t seed, const int32_t *d_step, const int32_t *row_active, hipStream_t st);
+void fast_sample_combine(int32_t *tok, float *lp, const float *part, int n_parts, int M, int Mp, const int32_t *row_active, hipStream_t st);
 // lm_head writing fp32 logits [Mp][ld] row-major (debug / unfused sampler).
 void fast_lmhead_logits(float *logits, int64_t ld, const void *Xp, const void *Wp, int Mp, int Np, int Kp, int V,
                         hipStream_t st);

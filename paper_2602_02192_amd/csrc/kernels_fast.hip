@@ -124,4 +124,222 @@ void fast_qkv_post(const float *partials, int nsplit, int Np, int Mp, void *q_h1
                      (const float2 *)rope_cs, rows, kv, layer, Hq, Hkv);
 }
 
+// ---- nucleus (top-p) sampling over materialised logits ---------------------------------------------------------
+// With p = softmax(logits / T): keep the shortest prefix of the tokens in descending order of p (lower index first
+// among equals) whose probabilities reach top_p, draw by Gumbel-max over the kept set with the usual per-index noise,
+// return the log-prob renormalised over the kept set (Sec. 5.1 runs rollouts at top-p 0.95).  Three launches:
+// 1. topp_cut_kernel, one workgroup per row, finds the cut without sorting: a radix select over the order-preserving
+//    integer image of the logit, most significant byte first; each round histograms the probability mass of the
+//    candidates by their next byte and walks the 256 bins from the top until the running mass reaches the target.
+//    Mass is summed in integers, q_i = floor(exp(z_i - max) * 2^40), so the sums do not depend on the order of the
+//    additions and the kept set is the same on every run.  Equal keys have equal mass; of the keys equal
+//    to the cut the lowest indices are kept until the target is met, so the kernel also returns the last kept index
+//    among them.  Seven passes over the row, which stays in L2.
+// 2. topp_draw_kernel, TOPP_CHUNKS workgroups per row: the sampler's running (max, sum-exp, best perturbed score) over
+//    the kept tokens of one slice of the vocabulary, in the partial layout of the fused sampler;
+// 3. sample_combine_kernel merges the slices.
+constexpr int TOPP_THREADS = 1024, TOPP_CHUNKS = TOPP_CHUNKS_PER_ROW;
+__device__ __forceinline__ uint32_t float_order_key(float f) {   // a < b  <=>  key(a) < key(b)
+  uint32_t u = __float_as_uint(f);
+  return u ^ ((u >> 31) ? 0xffffffffu : 0x80000000u);
+}
+__global__ __launch_bounds__(TOPP_THREADS) void topp_cut_kernel(uint32_t *cut_key, int32_t *cut_last, const float *logits, int64_t ld,
+                                                                 int V, float temperature, float top_p, const int32_t *row_active) {
+  __shared__ unsigned long long hist[4];        // mass of the bins of each of the first four wavefronts
+  __shared__ unsigned long long sub[16][256];   // lanes that meet in one bin are spread over 16 copies of it
+  __shared__ unsigned long long sh_u64[TOPP_THREADS / 64];
+  __shared__ float sh_f[TOPP_THREADS / 64];
+  __shared__ int sh_i[TOPP_THREADS / 64];
+  __shared__ unsigned long long sel_above;
+  __shared__ uint32_t sel_digit;
+  const int m = blockIdx.x, tid = threadIdx.x, wv = tid >> 6;
+  if (row_active && !row_active[m]) return;
+  const float *lg = logits + (int64_t)m * ld;
+  // Every pass visits the row with a stride of the block, two 16-byte loads in flight per thread (a plain loop waits out
+  // one memory latency per element); an index past the end yields -inf: mass 0, no maximum, never above a cut.
+  const int n4 = (ld & 3) == 0 ? V >> 2 : 0;   // 16-byte loads need aligned rows
+  auto visit = [&](auto &&f) {
+    const f32x4 *lg4 = (const f32x4 *)lg;
+    constexpr int B = 2;   // more copies of the body than this and the kernel outgrows the instruction cache
+    for (int i = tid; i < n4; i += B * TOPP_THREADS) {
+      f32x4 v[B];
+#pragma unroll
+      for (int u = 0; u < B; ++u) { int j = i + u * TOPP_THREADS; v[u] = j < n4 ? lg4[j] : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY}; }
+#pragma unroll
+      for (int u = 0; u < B; ++u) { f(v[u][0]); f(v[u][1]); f(v[u][2]); f(v[u][3]); }
+    }
+    for (int i = n4 * 4 + tid; i < V; i += TOPP_THREADS) f(lg[i]);
+  };
+  // max of z and sum of exp(z - max), one pass (running maximum, the sum rescaled whenever it moves); 1/T instead of the
+  // division: nothing here is returned, the kept set only needs the same arithmetic in every pass
+  const float inv_t = 1.0f / temperature;
+  float mx = -INFINITY, zs = 0.f;
+  visit([&](float v) {
+    float z = v * inv_t;
+    if (z > mx) { zs = zs * __expf(mx - z) + 1.f; mx = z; }
+    else zs += __expf(z - mx);
+  });
+  for (int o = 32; o > 0; o >>= 1) {
+    float om = __shfl_xor(mx, o, 64), os = __shfl_xor(zs, o, 64), nm = fmaxf(mx, om);
+    zs = (mx > -INFINITY ? zs * __expf(mx - nm) : 0.f) + (om > -INFINITY ? os * __expf(om - nm) : 0.f);
+    mx = nm;
+  }
+  if ((tid & 63) == 0) { sh_f[wv] = mx; sh_u64[wv] = (unsigned long long)__float_as_uint(zs); }
+  __syncthreads();
+  mx = sh_f[0];
+  for (int w = 1; w < TOPP_THREADS / 64; ++w) mx = fmaxf(mx, sh_f[w]);
+  zs = 0.f;
+  for (int w = 0; w < TOPP_THREADS / 64; ++w) zs += __uint_as_float((uint32_t)sh_u64[w]) * __expf(sh_f[w] - mx);
+  // probability mass in units of 2^-40 of the largest one, as an integer: sums of it do not depend on the order of the
+  // additions.  (Two 32-bit conversions; a float -> 64-bit integer conversion is a long instruction sequence.)
+  auto mass = [&](float logit) {
+    float e = __expf(logit * inv_t - mx) * 256.0f;          // <= 256
+    uint32_t hi = (uint32_t)e;
+    uint32_t lo = (uint32_t)((e - (float)hi) * 4294967296.0f);
+    return ((unsigned long long)hi << 32) | lo;
+  };
+  unsigned long long target = (unsigned long long)ceil((double)zs * 1099511627776.0 * (double)top_p);
+  if (target < 1) target = 1;
+  // radix select of the cut key: the largest key K with mass{key >= K} >= target
+  uint32_t prefix = 0;
+  unsigned long long above = 0;   // mass of the keys above the current prefix range
+  for (int round = 0; round < 4; ++round) {
+    const int shift = 24 - 8 * round;
+    __syncthreads();
+    for (int j = tid; j < 16 * 256; j += TOPP_THREADS) (&sub[0][0])[j] = 0;
+    __syncthreads();
+    visit([&](float v) {
+      uint32_t key = float_order_key(v);
+      if (round == 0 || (key >> (shift + 8)) == prefix) {
+        unsigned long long q = mass(v);
+        if (q) atomicAdd(&sub[tid & 15][(key >> shift) & 255u], q);
+      }
+    });
+    __syncthreads();
+    // walk the bins from the top: thread t of the first four wavefronts owns bin 255 - t, so an inclusive prefix sum
+    // over t is the mass of the bins at or above its own; exactly one bin takes the running mass across the target
+    unsigned long long h = 0, incl = 0;
+    if (tid < 256) {
+      for (int j = 0; j < 16; ++j) h += sub[j][255 - tid];
+      incl = h;
+      for (int o = 1; o < 64; o <<= 1) { unsigned long long v = __shfl_up(incl, o, 64); if ((tid & 63) >= o) incl += v; }
+      if ((tid & 63) == 63) hist[wv] = incl;
+    }
+    __syncthreads();
+    if (tid < 256) {
+      for (int w = 0; w < wv; ++w) incl += hist[w];
+      const unsigned long long at = above + incl, before = at - h;
+      if ((at >= target && before < target) || (tid == 255 && at < target)) { sel_digit = (uint32_t)(255 - tid); sel_above = before; }
+    }
+    __syncthreads();
+    prefix = (prefix << 8) | sel_digit;
+    above = sel_above;
+  }
+  const uint32_t cut = prefix;
+  // keys equal to the cut share one mass; the first `take` of them in index order are kept
+  int ties = 0;
+  unsigned long long q_cut = 0;
+  visit([&](float v) { if (float_order_key(v) == cut) { ++ties; q_cut = mass(v); } });
+  for (int o = 32; o > 0; o >>= 1) {
+    ties += __shfl_xor(ties, o, 64);
+    unsigned long long v = __shfl_xor(q_cut, o, 64);
+    q_cut = q_cut > v ? q_cut : v;
+  }
+  __syncthreads();
+  if ((tid & 63) == 0) { sh_i[wv] = ties; sh_u64[wv] = q_cut; }
+  __syncthreads();
+  int n_ties = 0;
+  unsigned long long qc = 0;
+  for (int w = 0; w < TOPP_THREADS / 64; ++w) { n_ties += sh_i[w]; qc = qc > sh_u64[w] ? qc : sh_u64[w]; }
+  const unsigned long long need = target - above;   // > 0: mass still missing once every key above the cut is kept
+  const long long take = qc ? (long long)((need + qc - 1) / qc) : (long long)V;   // >= 1
+  if (tid == 0) { cut_key[m] = cut; cut_last[m] = V; }   // V: every key equal to the cut is kept
+  if (take >= n_ties) return;
+  // Only some of the equal keys are kept (exact ties at the cut: rare): their indices are collected and the take-th
+  // smallest one closes the kept set.  More ties than the list holds (flat logits): ranks by a scan over contiguous runs.
+  __shared__ int tie_list[TOPP_THREADS];
+  __shared__ int tie_n;
+  if (tid == 0) tie_n = 0;
+  __syncthreads();
+  if (n_ties <= TOPP_THREADS) {
+    for (int i = tid; i < V; i += TOPP_THREADS)
+      if (float_order_key(lg[i]) == cut) tie_list[atomicAdd(&tie_n, 1)] = i;
+    __syncthreads();
+    if (tid < n_ties) {
+      const int mine = tie_list[tid];
+      int smaller = 0;
+      for (int u = 0; u < n_ties; ++u) smaller += tie_list[u] < mine;
+      if (smaller == take - 1) cut_last[m] = mine;
+    }
+    return;
+  }
+  const int chunk = (V + TOPP_THREADS - 1) / TOPP_THREADS, i0 = tid * chunk, i1 = min(V, i0 + chunk);
+  int mine = 0;
+  for (int i = i0; i < i1; ++i) mine += float_order_key(lg[i]) == cut;
+  int incl = mine;
+  for (int o = 1; o < 64; o <<= 1) { int v = __shfl_up(incl, o, 64); if ((tid & 63) >= o) incl += v; }
+  __syncthreads();
+  if ((tid & 63) == 63) sh_i[wv] = incl;
+  __syncthreads();
+  int rank = incl - mine;   // ties before this thread's run
+  for (int w = 0; w < wv; ++w) rank += sh_i[w];
+  if (rank < take && take <= rank + mine) {   // the take-th tie lies in this thread's run
+    for (int i = i0; i < i1; ++i)
+      if (float_order_key(lg[i]) == cut && ++rank == take) cut_last[m] = i;
+  }
+}
+
+// grid (TOPP_CHUNKS, M), block 256: slice c of row m.
+__global__ void topp_draw_kernel(float *part, int Mp, const uint32_t *cut_key, const int32_t *cut_last, const float *logits, int64_t ld,
+                                 int V, float temperature, uint64_t seed, const int32_t *d_step, const int32_t *row_active) {
+  __shared__ SampleAcc sh[4];
+  const int c = blockIdx.x, m = blockIdx.y;
+  if (row_active && !row_active[m]) return;
+  const uint32_t step = (uint32_t)*d_step, cut = cut_key[m];
+  const int last = cut_last[m];
+  const int v4 = (V + 3) / 4, per = (v4 + TOPP_CHUNKS - 1) / TOPP_CHUNKS, b4 = c * per, e4 = min(v4, b4 + per);
+  const float *lg = logits + (int64_t)m * ld;
+  SampleAcc a = sample_acc_init();
+  for (int i4 = b4 + threadIdx.x; i4 < e4; i4 += blockDim.x) {
+    u32x4 r = draw4(seed, (uint32_t)m, step, (uint32_t)i4);
+    uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      int i = i4 * 4 + e;
+      if (i < V) {
+        float v = lg[i];
+        uint32_t key = float_order_key(v);
+        if (key > cut || (key == cut && i <= last)) {
+          float z = v / temperature;
+          sample_acc_add(a, z, z + gumbel_from_bits(w[e]), i);
+        }
+      }
+    }
+  }
+  for (int o = 32; o > 0; o >>= 1) { SampleAcc b = sample_acc_shfl_xor(a, o); sample_acc_merge(a, b); }
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = a;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w) sample_acc_merge(a, sh[w]);
+    int64_t o = (int64_t)c * Mp + m, plane = (int64_t)TOPP_CHUNKS * Mp;
+    part[o] = a.zmax;
+    part[plane + o] = a.zsum;
+    part[2 * plane + o] = a.best;
+    part[3 * plane + o] = a.zbest;
+    part[4 * plane + o] = __int_as_float(a.idx);
+  }
+}
+
+size_t fast_topp_scratch_floats(int Mp) { return (size_t)5 * TOPP_CHUNKS * Mp + 2 * (size_t)Mp; }
+
+void fast_topp_cut_and_draw(float *scratch, const float *logits, int64_t ld, int M, int Mp, int V, float temperature, float top_p,
+                            uint64_t seed, const int32_t *d_step, const int32_t *row_active, hipStream_t st) {
+  if (M <= 0) return;
+  uint32_t *cut_key = (uint32_t *)(scratch + (size_t)5 * TOPP_CHUNKS * Mp);
+  int32_t *cut_last = (int32_t *)cut_key + Mp;
+  hipLaunchKernelGGL(topp_cut_kernel, dim3(M), dim3(TOPP_THREADS), 0, st, cut_key, cut_last, logits, ld, V, temperature, top_p, row_active);
+  hipLaunchKernelGGL(topp_draw_kernel, dim3(TOPP_CHUNKS, M), dim3(256), 0, st, scratch, Mp, cut_key, cut_last, logits, ld, V, temperature,
+                     seed, d_step, row_active);
+}
+
 }  // namespace echo

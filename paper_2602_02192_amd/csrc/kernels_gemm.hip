@@ -959,6 +959,11 @@ void fast_lmhead_sample(int32_t *tok, float *lp, float *target_lp, const void *X
                      target, target_z);
 }
 
+void fast_sample_combine(int32_t *tok, float *lp, const float *part, int n_parts, int M, int Mp, const int32_t *row_active, hipStream_t st) {
+  hipLaunchKernelGGL(sample_combine_kernel, dim3(M), dim3(256), 0, st, tok, lp, (float *)nullptr, part, n_parts, Mp, row_active,
+                     (const int32_t *)nullptr, (const float *)nullptr);
+}
+
 void fast_lmhead_logits(float *logits, int64_t ld, const void *Xp, const void *Wp, int Mp, int Np, int Kp, int V,
                         hipStream_t st) {
   lmhead_dispatch<true>(Xp, Wp, Mp, Np, Kp, V, 1.0f, 0, nullptr, nullptr, nullptr, nullptr, logits, ld, st);

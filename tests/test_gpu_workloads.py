@@ -10,7 +10,7 @@ import pytest
 from oracle import oracle
 from paper_2602_02192_amd import synth
 
-from gpu_util import (BF16_ARGMAX_RATE, BF16_LOGIT_TOL, BF16_LOGPROB_TOL, F32_LOGIT_TOL, F32_LOGPROB_TOL,
+from gpu_util import (BF16_ARGMAX_RATE, BF16_LOGIT_TOL, BF16_LOGPROB_TOL, F32_LOGIT_TOL, F32_LOGPROB_TOL, NEAR_TIE_GAP,
                       argmax_agreement, check_tokens_fp32_sampler, make_ctx, oracle_rollout, valid_mask)
 
 pytestmark = pytest.mark.gpu
@@ -224,6 +224,82 @@ def test_group_shared_prompt_tiles(monkeypatch, shape, G, P):
     ctx.close()
 
 
+@pytest.mark.parametrize("shape,top_p,temperature", [(synth.TINY, 0.9, 1.0), (synth.TINY, 0.3, 0.7), (MID, 0.95, 1.0)],
+                         ids=["tiny-fp32-p0.9", "tiny-fp32-p0.3-T0.7", "mid-bf16-p0.95"])
+def test_nucleus_sampling_matches_the_oracle(shape, top_p, temperature):
+    """top_p < 1: teacher-forced on the oracle's own nucleus rollout, so every step's draw is compared on its own.
+    Where the oracle's cut is not within rounding of top_p and its draw is no near-tie, the all-fp32 path returns the
+    oracle's token; log-probs are those of the renormalised kept set.  The sampled token is always inside the kept set
+    that the returned logits define, and its log-prob is its renormalised log-probability there."""
+    blob = synth.make_weights(shape, 2)
+    blob32 = synth.widen_to_f32(blob)
+    P, G, max_new = 3, 4, 10
+    prompts, lens = synth.make_prompts(shape.vocab, P, 24, seed=6, ragged=True)
+    prompts = np.maximum(prompts, 0)
+    ref = oracle_rollout(shape, blob32, prompts, lens, G=G, max_new=max_new, temperature=temperature, seed=13, top_p=top_p,
+                         want_logits=True)
+    ctx = make_ctx(shape, P * G, 24 + max_new, blob)
+    got = ctx.rollout(prompts, lens, G, max_new, temperature, 13, top_p=top_p, forced=ref["tokens"], want_logits=True)
+    again = ctx.rollout(prompts, lens, G, max_new, temperature, 13, top_p=top_p, forced=ref["tokens"])
+    assert np.array_equal(got["tokens"], again["tokens"]) and np.array_equal(got["logprobs"], again["logprobs"])
+    fp32 = shape.dtype == "fp32"
+    assert np.abs(got["logits"] - ref["logits"]).max() < (F32_LOGIT_TOL if fp32 else BF16_LOGIT_TOL)
+    clear = (ref["margins"] > 1e-4) & (ref["gaps"] > NEAR_TIE_GAP)
+    same = got["tokens"] == ref["tokens"]
+    if fp32:
+        assert clear.mean() > 0.5 and same[clear].all()      # near-uniform p over 1024 tokens: a fifth of the cuts sit within 1e-4
+        assert np.abs(got["logprobs"] - ref["logprobs"])[same & clear].max() < F32_LOGPROB_TOL
+    else:
+        assert same.mean() > 0.8
+        assert np.abs(got["logprobs"] - ref["logprobs"])[same].max() < BF16_LOGPROB_TOL
+    # self-consistency on the GPU's own logits (fp64 arithmetic here): token inside the kept set, log-prob renormalised
+    T32 = float(np.float32(temperature))
+    for n in range(P * G):
+        for s in range(max_new):
+            z = got["logits"][n, s].astype(np.float64) / T32
+            p = np.exp(z - z.max())
+            p /= p.sum()
+            order = np.lexsort((np.arange(p.size), -p))
+            cum = np.cumsum(p[order])
+            k = int(np.argmax(cum >= top_p)) + 1
+            tok = int(got["tokens"][n, s])
+            pos = int(np.nonzero(order == tok)[0][0])
+            slack = 1e-4                                  # the kernel sums quantised fp32 masses: the cut may sit a hair off
+            k_lo = int(np.argmax(cum >= top_p - slack)) + 1
+            k_hi = int(np.argmax(cum >= min(top_p + slack, cum[-1]))) + 1
+            assert pos < k_hi, (n, s)
+            lo, hi = np.log(p[tok] / cum[k_hi - 1]), np.log(p[tok] / cum[k_lo - 1])
+            assert lo - 2e-4 <= got["logprobs"][n, s] <= hi + 2e-4, (n, s, k, got["logprobs"][n, s], lo, hi)
+    # top_p = 1 through the same unfused path is the plain sampler
+    a = ctx.rollout(prompts, lens, G, max_new, temperature, 13, unfused_sampler=True)
+    b = ctx.rollout(prompts, lens, G, max_new, temperature, 13)
+    if fp32:
+        assert np.array_equal(a["tokens"], b["tokens"])
+    ctx.close()
+
+
+@pytest.mark.parametrize("shape", [synth.TINY, MID], ids=["tiny-fp32-V1024", "mid-bf16-V2048"])
+def test_nucleus_cut_inside_exact_ties(shape):
+    """A zero lm_head makes every logit exactly 0: all V tokens tie, the kept set is the lowest ceil(top_p * V) indices
+    (lower index first among equals), every kept token has probability 1/k, and the token is the kept index with the
+    largest uniform draw -- the oracle and the GPU must agree on every token.  V = 1024 resolves the ties through the
+    index list, V = 2048 through the scan over contiguous runs."""
+    blob = synth.make_weights(shape, 4)
+    off, shp = synth.blob_offsets(shape)["lm_head"]
+    blob[off:off + int(np.prod(shp))] = 0
+    blob32 = synth.widen_to_f32(blob)
+    prompts, lens = synth.make_prompts(shape.vocab, 2, 9, seed=3)
+    top_p, G, max_new = 0.3, 3, 6
+    k = int(np.ceil(np.float32(top_p) * shape.vocab))
+    ref = oracle_rollout(shape, blob32, prompts, lens, G=G, max_new=max_new, temperature=1.0, seed=21, top_p=top_p)
+    assert (ref["tokens"] < k).all() and np.allclose(ref["logprobs"], -np.log(k))
+    ctx = make_ctx(shape, 2 * G, 9 + max_new, blob)
+    got = ctx.rollout(prompts, lens, G, max_new, 1.0, 21, top_p=top_p)
+    assert np.array_equal(got["tokens"], ref["tokens"])
+    assert np.abs(got["logprobs"] + np.log(k)).max() < 1e-5
+    ctx.close()
+
+
 def test_edge_cases_and_errors():
     from paper_2602_02192_amd import echo
     shape = synth.TINY
@@ -249,7 +325,8 @@ def test_edge_cases_and_errors():
             bad()
         assert e.value.code == echo.ECHO_ENOMEM
     # argument checks
-    for bad in (lambda: ctx.rollout(prompts, lens, 2, 4, 0.0, 1), lambda: ctx.rollout(prompts, lens, 2, 4, 1.0, 1, top_p=0.9),
+    for bad in (lambda: ctx.rollout(prompts, lens, 2, 4, 0.0, 1), lambda: ctx.rollout(prompts, lens, 2, 4, 1.0, 1, top_p=0.0),
+                lambda: ctx.rollout(prompts, lens, 2, 4, 1.0, 1, top_p=1.5),
                 lambda: ctx.rollout(prompts + shape.vocab, lens, 2, 4, 1.0, 1), lambda: ctx.rollout(prompts, lens * 0, 2, 4, 1.0, 1)):
         with pytest.raises(echo.EchoError) as e:
             bad()
