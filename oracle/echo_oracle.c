@@ -518,6 +518,40 @@ int orc_rollout(const orc_desc *d, int n_models, const float *const *blobs, cons
                            out_versions, out_logits, out_gaps, NULL);
 }
 
+/* Learner-side tensors of a batch of records (App. "Turn-Aware Masking" and "Outcome-Based Returns and
+ * Group-wise Normalization").
+ *   Turn index c[n][t] = number of positions k <= t with tokens[n][k] == turn_start; the response mask
+ *   selects the tokens of the odd turns after the first: m[n][t] = [c > 1][c odd]; positions >= lens[n]
+ *   are 0.
+ *   Advantage of sequence n within its group of G consecutive sequences:
+ *   A_n = (R_n - mean) / (std + eps), std the sample standard deviation (divisor G - 1), which is what the
+ *   paper's listing computes; adv_tok[n][t] = A_n * m[n][t].  G >= 2. */
+int orc_grpo_tensors(const int32_t *tokens, int stride, const int32_t *lens, int n_seqs, int G, int32_t turn_start,
+                     const double *rewards, double eps, uint8_t *out_mask, double *out_adv, double *out_adv_tok) {
+  if (n_seqs < 0 || G < 2 || n_seqs % G) return -1;
+  for (int g0 = 0; g0 < n_seqs; g0 += G) {
+    double mean = 0, ss = 0;
+    for (int j = 0; j < G; ++j) mean += rewards[g0 + j];
+    mean /= G;
+    for (int j = 0; j < G; ++j) ss += (rewards[g0 + j] - mean) * (rewards[g0 + j] - mean);
+    double sd = sqrt(ss / (G - 1));
+    for (int j = 0; j < G; ++j) out_adv[g0 + j] = (rewards[g0 + j] - mean) / (sd + eps);
+  }
+  for (int n = 0; n < n_seqs; ++n) {
+    int c = 0;
+    for (int t = 0; t < stride; ++t) {
+      uint8_t m = 0;
+      if (t < lens[n]) {
+        if (tokens[(int64_t)n * stride + t] == turn_start) ++c;
+        m = (uint8_t)(c > 1 && (c & 1));
+      }
+      out_mask[(int64_t)n * stride + t] = m;
+      if (out_adv_tok) out_adv_tok[(int64_t)n * stride + t] = m ? out_adv[n] : 0.0;
+    }
+  }
+  return 0;
+}
+
 /* Teacher-forced scoring of one token string under one snapshot:
  * out[t] = log softmax(logits_{t-1} / temperature)[tokens[t]] for t >= 1, out[0] = 0. */
 int orc_logprobs(const orc_desc *d, const float *blob, const int32_t *tokens, int T, float temperature, double *out) {

@@ -193,6 +193,24 @@ class Oracle:
             raise RuntimeError(f"orc_rollout_top_p failed: {rc}")
         return dict(tokens=toks, logprobs=lps, lens=lens, versions=vers, gaps=gaps, logits=logits, margins=margins)
 
+    def grpo_tensors(self, tokens, lens, G: int, turn_start: int, rewards, eps: float = 1e-6):
+        """(response mask uint8 [N, T], advantages [N], per-token advantages [N, T])."""
+        tokens = np.ascontiguousarray(tokens, np.int32)
+        lens = np.ascontiguousarray(lens, np.int32)
+        rewards = np.ascontiguousarray(rewards, np.float64)
+        N, T = tokens.shape
+        mask = np.zeros((N, T), np.uint8)
+        adv = np.zeros(N, np.float64)
+        adv_tok = np.zeros((N, T), np.float64)
+        vp = lambda a: a.ctypes.data_as(C.c_void_p)
+        self.lib.orc_grpo_tensors.argtypes = None
+        self.lib.orc_grpo_tensors.restype = C.c_int
+        rc = self.lib.orc_grpo_tensors(vp(tokens), C.c_int(T), vp(lens), C.c_int(N), C.c_int(G), C.c_int32(turn_start), vp(rewards),
+                                       C.c_double(eps), vp(mask), vp(adv), vp(adv_tok))
+        if rc != 0:
+            raise ValueError("orc_grpo_tensors: bad arguments")
+        return mask, adv, adv_tok
+
     def set_threads(self, n: int) -> None:
         self.lib.orc_set_threads(n)
 
