@@ -135,6 +135,21 @@ int echo_rollout(echo_ctx *ctx, const int32_t *prompt_tokens, int32_t prompt_str
 int echo_logprobs(echo_ctx *ctx, const int32_t *tokens, int32_t stride, const int32_t *lens, int32_t n_seqs,
                   float temperature, float *out_logprobs);
 
+/* Learner-side tensors of a batch of finished records (App. "Turn-Aware Masking", App. "Outcome-Based Returns and
+ * Group-wise Normalization"), computed on the GPU; sequence n belongs to group n / G.
+ *   c[n][t]          = number of k <= t with tokens[n][k] == turn_start_id         (turn index)
+ *   out_mask[n][t]   = 1 if t < lens[n], c > 1 and c odd, else 0                   (response tokens)
+ *   out_adv[n]       = (rewards[n] - mean) / (std + eps), mean and std over the group's G returns, std the
+ *                      sample standard deviation (divisor G - 1), sums in f64, result rounded to f32
+ *   out_adv_tok[n][t] = out_adv[n] * out_mask[n][t]                                (nullable)
+ *   tokens host [n_seqs, stride]; lens host [n_seqs], each in 0..stride; rewards host [n_seqs];
+ *   out_mask host u8 [n_seqs, stride]; out_adv host [n_seqs]; out_adv_tok host [n_seqs, stride].
+ * Needs no policy.  ECHO_EINVAL if G < 2, n_seqs is not a positive multiple of G or eps < 0; ECHO_ENOMEM if one
+ * group of G rows does not fit the context's staging buffer (9 bytes per token); ECHO_ESTATE during a rollout. */
+int echo_grpo_tensors(echo_ctx *ctx, const int32_t *tokens, int32_t stride, const int32_t *lens, int32_t n_seqs,
+                      int32_t G, int32_t turn_start_id, const float *rewards, float eps, uint8_t *out_mask,
+                      float *out_adv, float *out_adv_tok);
+
 /* Raw 32-bit draws of the sampler's generator for (seed; n, s, i = i0..i0+count-1), computed on the GPU
  * (out: host [count]).  Exists so that the generator can be compared bit for bit with its definition. */
 int echo_debug_draw_bits(echo_ctx *ctx, uint64_t seed, uint32_t n, uint32_t s, uint32_t i0, int32_t count,

@@ -854,6 +854,52 @@ int echo_logprobs(echo_ctx *c, const int32_t *tokens, int32_t stride, const int3
   });
 }
 
+int echo_grpo_tensors(echo_ctx *c, const int32_t *tokens, int32_t stride, const int32_t *lens, int32_t n_seqs, int32_t G,
+                      int32_t turn_start_id, const float *rewards, float eps, uint8_t *out_mask, float *out_adv, float *out_adv_tok) {
+  if (!c) return ECHO_EINVAL;
+  if (!tokens || !lens || !rewards || !out_mask || !out_adv || stride < 1) return fail(c, ECHO_EINVAL, "bad argument");
+  if (G < 2) return fail(c, ECHO_EINVAL, "a group needs at least 2 samples for a standard deviation (G = %d)", G);
+  if (n_seqs < G || n_seqs % G) return fail(c, ECHO_EINVAL, "n_seqs = %d is not a positive multiple of G = %d", n_seqs, G);
+  if (!(eps >= 0.f)) return fail(c, ECHO_EINVAL, "eps must be >= 0");
+  for (int n = 0; n < n_seqs; ++n)
+    if (lens[n] < 0 || lens[n] > stride) return fail(c, ECHO_EINVAL, "lens[%d] = %d outside 0..%d", n, lens[n], stride);
+  {
+    std::lock_guard<std::mutex> lk(c->mu);
+    if (c->rollout_running) return fail(c, ECHO_ESTATE, "a rollout is running on this context");
+  }
+  // The logits buffer is borrowed as staging, whole groups at a time:
+  // tokens i32 [ns, stride] | adv_tok f32 [ns, stride] | mask u8 [ns, stride] | lens i32 [ns] | rewards f32 [ns] | adv f32 [ns]
+  auto up16 = [](size_t x) { return (x + 15) & ~(size_t)15; };
+  size_t cap = c->p.logit_rows * (size_t)c->p.Np_v * 4;
+  auto need = [&](size_t ns) { return 2 * up16(ns * stride * 4) + up16(ns * stride) + 3 * up16(ns * 4); };
+  if (need(G) > cap) return fail(c, ECHO_ENOMEM, "one group (%d x %d tokens) needs %zu bytes of staging, the context has %zu", G, stride, need(G), cap);
+  size_t groups_per_pass = 1;
+  while (need((groups_per_pass * 2) * G) <= cap && groups_per_pass * G < (size_t)n_seqs) groups_per_pass *= 2;
+  HIPCHK(c, hipSetDevice(c->device));
+  hipStream_t st = c->cs;
+  char *base = at<char>(c, c->p.o_logits);
+  for (int n0 = 0; n0 < n_seqs; n0 += (int)(groups_per_pass * G)) {
+    size_t ns = std::min<size_t>(groups_per_pass * G, n_seqs - n0);
+    size_t cells = ns * stride;
+    int32_t *d_tok = (int32_t *)base;
+    float *d_at = (float *)(base + up16(cells * 4));
+    uint8_t *d_mask = (uint8_t *)(base + 2 * up16(cells * 4));
+    int32_t *d_len = (int32_t *)((char *)d_mask + up16(cells));
+    float *d_rew = (float *)((char *)d_len + up16(ns * 4));
+    float *d_adv = (float *)((char *)d_rew + up16(ns * 4));
+    HIPCHK(c, hipMemcpyAsync(d_tok, tokens + (int64_t)n0 * stride, cells * 4, hipMemcpyHostToDevice, st));
+    HIPCHK(c, hipMemcpyAsync(d_len, lens + n0, ns * 4, hipMemcpyHostToDevice, st));
+    HIPCHK(c, hipMemcpyAsync(d_rew, rewards + n0, ns * 4, hipMemcpyHostToDevice, st));
+    launch_grpo_tensors(d_mask, d_adv, out_adv_tok ? d_at : nullptr, d_tok, d_len, d_rew, (int)ns, G, stride, turn_start_id, eps, st);
+    HIPCHK(c, hipGetLastError());
+    HIPCHK(c, hipMemcpyAsync(out_mask + (int64_t)n0 * stride, d_mask, cells, hipMemcpyDeviceToHost, st));
+    HIPCHK(c, hipMemcpyAsync(out_adv + n0, d_adv, ns * 4, hipMemcpyDeviceToHost, st));
+    if (out_adv_tok) HIPCHK(c, hipMemcpyAsync(out_adv_tok + (int64_t)n0 * stride, d_at, cells * 4, hipMemcpyDeviceToHost, st));
+    HIPCHK(c, hipStreamSynchronize(st));
+  }
+  return ECHO_OK;
+}
+
 int echo_debug_draw_bits(echo_ctx *c, uint64_t seed, uint32_t n, uint32_t s, uint32_t i0, int32_t count, uint32_t *out_bits) {
   if (!c || !out_bits || count < 1) return c ? fail(c, ECHO_EINVAL, "bad argument") : ECHO_EINVAL;
   size_t cap = c->p.logit_rows * (size_t)c->p.Np_v;  // the logits buffer is borrowed as scratch

@@ -60,6 +60,10 @@ void launch_bookkeeping(int N, int max_new, int32_t *d_step, const int32_t *samp
 void launch_kv_replicate(KvGeom kv, const int32_t *prompt_len /*[P]*/, int P, int G, hipStream_t st);
 void launch_draw_bits(uint32_t *out, uint64_t seed, uint32_t n, uint32_t s, uint32_t i0, int count, hipStream_t st);
 void launch_fill_i32(int32_t *p, int32_t v, int64_t n, hipStream_t st);
+// Learner-side tensors of n_seqs records in groups of G (n_seqs a multiple of G, G >= 2): adv[n] from rewards[n],
+// mask[n][t] and adv_tok[n][t] (nullable) from tokens[n][t], lens[n].  tokens, adv_tok 16-byte aligned, mask 4-byte.
+void launch_grpo_tensors(uint8_t *mask, float *adv, float *adv_tok, const int32_t *tokens, const int32_t *lens, const float *rewards,
+                         int n_seqs, int G, int stride, int32_t turn_start, float eps, hipStream_t st);
 void launch_gather_rows_f32(float *dst, const float *src, const int32_t *src_row /*[n_dst], -1 = skip*/,
                             int n_dst, int width, hipStream_t st);
 

@@ -119,4 +119,100 @@ void launch_gather_rows_f32(float *dst, const float *src, const int32_t *src_row
   hipLaunchKernelGGL(gather_rows_kernel, dim3(n_dst), dim3(256), 0, st, dst, src, src_row, width);
 }
 
+// Group-wise normalised advantages (App. "Outcome-Based Returns and Group-wise Normalization"): one wave per group of
+// G consecutive returns; mean and sample standard deviation (divisor G - 1) in double, A = (R - mean) / (std + eps).
+__global__ void grpo_advantage_kernel(float *adv, const float *rewards, int G, float eps) {
+  const float *r = rewards + (int64_t)blockIdx.x * G;
+  int lane = threadIdx.x;
+  double sum = 0;
+  for (int j = lane; j < G; j += 64) sum += (double)r[j];
+  for (int o = 32; o; o >>= 1) sum += __shfl_xor(sum, o);
+  double mean = sum / G, ss = 0;
+  for (int j = lane; j < G; j += 64) {
+    double dv = (double)r[j] - mean;
+    ss += dv * dv;
+  }
+  for (int o = 32; o; o >>= 1) ss += __shfl_xor(ss, o);
+  double den = sqrt(ss / (G - 1)) + (double)eps;
+  for (int j = lane; j < G; j += 64) adv[(int64_t)blockIdx.x * G + j] = (float)(((double)r[j] - mean) / den);
+}
+
+// Turn-aware response mask (App. "Turn-Aware Masking") and per-token advantages: one workgroup of 256 threads per
+// sequence walks the row in tiles of 1024 tokens, 4 consecutive tokens per thread; the turn index of a token is the
+// carried count of turn starts plus a prefix sum over the tile (shuffles within a wave, LDS across the 4 waves).
+// VEC: rows start 16-byte aligned (stride % 4 == 0), so the 4 tokens travel as one vector.
+template <bool VEC>
+__global__ void __launch_bounds__(256) grpo_mask_kernel(uint8_t *mask, float *adv_tok, const int32_t *tokens, const int32_t *lens,
+                                                        const float *adv, int stride, int32_t turn_start) {
+  __shared__ int wave_tot[4];
+  int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int32_t *row = tokens + (int64_t)n * stride;
+  uint8_t *mrow = mask + (int64_t)n * stride;
+  float *arow = adv_tok ? adv_tok + (int64_t)n * stride : nullptr;
+  int len = lens[n];
+  float a = adv[n];
+  int carry = 0;
+  for (int base = 0; base < stride; base += 1024) {
+    int t0 = base + 4 * tid;
+    int32_t tk[4];
+    if (VEC && t0 + 3 < stride) {
+      int4 v = *(const int4 *)(row + t0);
+      tk[0] = v.x, tk[1] = v.y, tk[2] = v.z, tk[3] = v.w;
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) tk[j] = t0 + j < stride ? row[t0 + j] : turn_start - 1;
+    }
+    int hit[4], cnt = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      hit[j] = (t0 + j < len && tk[j] == turn_start) ? 1 : 0;
+      cnt += hit[j];
+    }
+    int inc = cnt;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      int up = __shfl_up(inc, o);
+      if (lane >= o) inc += up;
+    }
+    if (lane == 63) wave_tot[w] = inc;
+    __syncthreads();
+    int before = carry + inc - cnt, total = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (k < w) before += wave_tot[k];
+      total += wave_tot[k];
+    }
+    carry += total;
+    __syncthreads();
+    int c = before;
+    uint8_t m[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      c += hit[j];
+      m[j] = (t0 + j < len && c > 1 && (c & 1)) ? 1 : 0;
+    }
+    if (VEC && t0 + 3 < stride) {
+      *(uchar4 *)(mrow + t0) = make_uchar4(m[0], m[1], m[2], m[3]);
+      if (arow) *(float4 *)(arow + t0) = make_float4(m[0] ? a : 0.f, m[1] ? a : 0.f, m[2] ? a : 0.f, m[3] ? a : 0.f);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (t0 + j < stride) {
+          mrow[t0 + j] = m[j];
+          if (arow) arow[t0 + j] = m[j] ? a : 0.f;
+        }
+    }
+  }
+}
+
+void launch_grpo_tensors(uint8_t *mask, float *adv, float *adv_tok, const int32_t *tokens, const int32_t *lens, const float *rewards,
+                         int n_seqs, int G, int stride, int32_t turn_start, float eps, hipStream_t st) {
+  if (n_seqs <= 0) return;
+  hipLaunchKernelGGL(grpo_advantage_kernel, dim3(n_seqs / G), dim3(64), 0, st, adv, rewards, G, eps);
+  if (stride % 4 == 0)
+    hipLaunchKernelGGL(grpo_mask_kernel<true>, dim3(n_seqs), dim3(256), 0, st, mask, adv_tok, tokens, lens, adv, stride, turn_start);
+  else
+    hipLaunchKernelGGL(grpo_mask_kernel<false>, dim3(n_seqs), dim3(256), 0, st, mask, adv_tok, tokens, lens, adv, stride, turn_start);
+}
+
 }  // namespace echo

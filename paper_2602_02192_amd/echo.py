@@ -49,7 +49,7 @@ class Stats(C.Structure):
 
 
 EXPORTS = ["echo_arena_bytes", "echo_blob_bytes", "echo_init", "echo_load_policy", "echo_rollout",
-           "echo_logprobs", "echo_debug_draw_bits", "echo_stats", "echo_last_error", "echo_destroy"]
+           "echo_logprobs", "echo_grpo_tensors", "echo_debug_draw_bits", "echo_stats", "echo_last_error", "echo_destroy"]
 
 lib.echo_arena_bytes.restype = C.c_size_t
 lib.echo_arena_bytes.argtypes = [C.POINTER(ModelDesc)]
@@ -62,6 +62,8 @@ lib.echo_rollout.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_
                              C.c_float, C.c_uint64, C.POINTER(RolloutOpts), C.c_void_p, C.c_void_p, C.c_void_p,
                              C.c_void_p]
 lib.echo_logprobs.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_float, C.c_void_p]
+lib.echo_grpo_tensors.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                  C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
 lib.echo_debug_draw_bits.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int32,
                                      C.c_void_p]
 lib.echo_stats.argtypes = [C.c_void_p, C.POINTER(Stats)]
@@ -192,6 +194,17 @@ class Context:
         self._chk(lib.echo_logprobs(self.h, _ptr(tokens), tokens.shape[1], _ptr(lens), tokens.shape[0], temperature,
                                     _ptr(out)))
         return out
+
+    def grpo_tensors(self, tokens, lens, G: int, turn_start_id: int, rewards, eps: float = 1e-6, per_token: bool = True):
+        tokens = np.ascontiguousarray(tokens, np.int32)
+        lens = np.ascontiguousarray(lens, np.int32)
+        rewards = np.ascontiguousarray(rewards, np.float32)
+        mask = np.empty(tokens.shape, np.uint8)
+        adv = np.empty(tokens.shape[0], np.float32)
+        adv_tok = np.empty(tokens.shape, np.float32) if per_token else None
+        self._chk(lib.echo_grpo_tensors(self.h, _ptr(tokens), tokens.shape[1], _ptr(lens), tokens.shape[0], G, turn_start_id,
+                                        _ptr(rewards), eps, _ptr(mask), _ptr(adv), _ptr(adv_tok) if per_token else None))
+        return mask, adv, adv_tok
 
     def draw_bits(self, seed: int, n: int, s: int, i0: int, count: int) -> np.ndarray:
         out = np.empty(count, np.uint32)

@@ -148,3 +148,39 @@ def make_stop_lens(n_seqs: int, lo: int, hi: int, seed: int) -> np.ndarray:
     """Per-sequence stop lengths iid uniform over {lo..hi} (stand-in for EOS)."""
     rng = np.random.default_rng(seed)
     return rng.integers(lo, hi + 1, size=n_seqs).astype(np.int32)
+
+
+def make_turn_records(n_seqs: int, stride: int, vocab: int, turn_start_id: int, seed: int,
+                      max_turns: int = 9, binary_rewards: bool = True) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Finished multi-turn records for the learner-side tensors: tokens int32 [N, stride], lens [N], rewards f32 [N].
+
+    Lengths are uniform in [0, stride]; tokens are iid uniform over the vocabulary without the turn-start id, which is
+    then planted at the first position and at up to max_turns - 1 further uniform positions (about one record in
+    eight gets no turn start at all, one in eight a single one).  The padding beyond a record's length holds random
+    tokens, turn starts included, so that a reader that ignores the length is caught.  Rewards are 0/1 outcomes
+    (about one group-sized run in ten all equal) or, with binary_rewards off, normal with mean 3 and deviation 40."""
+    rng = np.random.default_rng(seed)
+    toks = rng.integers(0, vocab - 1, size=(n_seqs, stride), dtype=np.int64)
+    toks[toks >= turn_start_id] += 1
+    lens = rng.integers(0, stride + 1, size=n_seqs).astype(np.int32)
+    for n in range(n_seqs):
+        kind = rng.integers(0, 8)
+        if kind == 0 or lens[n] == 0:
+            pass
+        else:
+            toks[n, 0] = turn_start_id
+            if kind > 1:
+                k = int(rng.integers(1, max_turns))
+                toks[n, rng.integers(0, lens[n], size=k)] = turn_start_id
+        pad = stride - lens[n]
+        if pad:
+            toks[n, lens[n]:] = rng.integers(0, vocab, size=pad)
+            toks[n, lens[n]:][rng.random(pad) < 0.01] = turn_start_id
+    if binary_rewards:
+        rewards = (rng.random(n_seqs) < 0.4).astype(np.float32)
+        for g0 in range(0, n_seqs, 16):
+            if rng.random() < 0.1:
+                rewards[g0:g0 + 16] = rewards[g0]
+    else:
+        rewards = rng.normal(3.0, 40.0, n_seqs).astype(np.float32)
+    return toks.astype(np.int32), lens, rewards
