@@ -137,14 +137,14 @@ __global__ void grpo_advantage_kernel(float *adv, const float *rewards, int G, f
   for (int j = lane; j < G; j += 64) adv[(int64_t)blockIdx.x * G + j] = (float)(((double)r[j] - mean) / den);
 }
 
-// Turn-aware response mask (App. "Turn-Aware Masking") and per-token advantages: one workgroup of 256 threads per
-// sequence walks the row in tiles of 1024 tokens, 4 consecutive tokens per thread; the turn index of a token is the
-// carried count of turn starts plus a prefix sum over the tile (shuffles within a wave, LDS across the 4 waves).
+// Turn-aware response mask (App. "Turn-Aware Masking") and per-token advantages: one workgroup of 1024 threads per
+// sequence walks the row in tiles of 4096 tokens, 4 consecutive tokens per thread; the turn index of a token is the
+// carried count of turn starts plus a prefix sum over the tile (shuffles within a wave, LDS across the 16 waves).
 // VEC: rows start 16-byte aligned (stride % 4 == 0), so the 4 tokens travel as one vector.
 template <bool VEC>
-__global__ void __launch_bounds__(256) grpo_mask_kernel(uint8_t *mask, float *adv_tok, const int32_t *tokens, const int32_t *lens,
+__global__ void __launch_bounds__(1024) grpo_mask_kernel(uint8_t *mask, float *adv_tok, const int32_t *tokens, const int32_t *lens,
                                                         const float *adv, int stride, int32_t turn_start) {
-  __shared__ int wave_tot[4];
+  __shared__ int wave_tot[16];
   int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int32_t *row = tokens + (int64_t)n * stride;
   uint8_t *mrow = mask + (int64_t)n * stride;
@@ -152,7 +152,7 @@ __global__ void __launch_bounds__(256) grpo_mask_kernel(uint8_t *mask, float *ad
   int len = lens[n];
   float a = adv[n];
   int carry = 0;
-  for (int base = 0; base < stride; base += 1024) {
+  for (int base = 0; base < stride; base += 4096) {
     int t0 = base + 4 * tid;
     int32_t tk[4];
     if (VEC && t0 + 3 < stride) {
@@ -178,7 +178,7 @@ __global__ void __launch_bounds__(256) grpo_mask_kernel(uint8_t *mask, float *ad
     __syncthreads();
     int before = carry + inc - cnt, total = 0;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
+    for (int k = 0; k < 16; ++k) {
       if (k < w) before += wave_tot[k];
       total += wave_tot[k];
     }
@@ -210,9 +210,9 @@ void launch_grpo_tensors(uint8_t *mask, float *adv, float *adv_tok, const int32_
   if (n_seqs <= 0) return;
   hipLaunchKernelGGL(grpo_advantage_kernel, dim3(n_seqs / G), dim3(64), 0, st, adv, rewards, G, eps);
   if (stride % 4 == 0)
-    hipLaunchKernelGGL(grpo_mask_kernel<true>, dim3(n_seqs), dim3(256), 0, st, mask, adv_tok, tokens, lens, adv, stride, turn_start);
+    hipLaunchKernelGGL(grpo_mask_kernel<true>, dim3(n_seqs), dim3(1024), 0, st, mask, adv_tok, tokens, lens, adv, stride, turn_start);
   else
-    hipLaunchKernelGGL(grpo_mask_kernel<false>, dim3(n_seqs), dim3(256), 0, st, mask, adv_tok, tokens, lens, adv, stride, turn_start);
+    hipLaunchKernelGGL(grpo_mask_kernel<false>, dim3(n_seqs), dim3(1024), 0, st, mask, adv_tok, tokens, lens, adv, stride, turn_start);
 }
 
 }  // namespace echo

@@ -28,7 +28,7 @@ def check(ctx, orc, toks, lens, G, rewards, eps=1e-6, per_token=True):
 
 
 @pytest.mark.parametrize("N,G,stride,binary", [(48, 16, 5000, True), (6, 3, 1027, False), (64, 2, 1000, True),
-                                              (2, 2, 1, True), (4, 4, 3, False), (130, 65, 4096, False)])
+                                              (2, 2, 1, True), (4, 4, 3, False), (130, 65, 4096, False), (8, 4, 12290, True)])
 def test_learner_tensors_match_the_oracle(orc, N, G, stride, binary):
     ctx = make_ctx(synth.TINY, 8, 64)       # no policy: the call needs none
     toks, lens, rewards = synth.make_turn_records(N, stride, 1024, TAU, seed=N + stride, binary_rewards=binary)
