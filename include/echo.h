@@ -115,6 +115,26 @@ int echo_init(const echo_model_desc *desc, int device, void *dev_arena, size_t a
  * a staged snapshot is still waiting. */
 int echo_load_policy(echo_ctx *ctx, int64_t version, const void *host_weights, size_t nbytes);
 
+/* The same install for a snapshot that arrives in pieces (Sec. 4.2: snapshots travel as chunks that a worker
+ * forwards and consumes as they land, and generation under the new version starts once the last one is in).
+ *   echo_load_policy_begin(version, nbytes)  opens the load: same checks, same choice of weight slot and same
+ *                                            errors as echo_load_policy; nbytes = echo_blob_bytes
+ *   echo_load_policy_chunk(data, nbytes)     the next nbytes of the blob (host), in blob order, any sizes, cut at any
+ *                                            byte; copied and repacked on the copy stream while a rollout keeps
+ *                                            decoding; data may be freed when the call returns.  After an error
+ *                                            the load must be aborted
+ *   echo_load_policy_commit()                all bytes are in (ECHO_ESTATE otherwise): the snapshot becomes active
+ *                                            or staged exactly as after echo_load_policy
+ *   echo_load_policy_abort()                 drops the load; the version may be offered again
+ * The calls of one load come from one thread at a time; a rollout may run, start and end meanwhile, except that
+ * with n_weight_slots = 1 the load overwrites the active snapshot: echo_rollout and echo_logprobs return
+ * ECHO_ESTATE until the commit, and after an abort no snapshot is installed.  The result is bit for bit the
+ * one echo_load_policy leaves for the same bytes. */
+int echo_load_policy_begin(echo_ctx *ctx, int64_t version, size_t nbytes);
+int echo_load_policy_chunk(echo_ctx *ctx, const void *data, size_t nbytes);
+int echo_load_policy_commit(echo_ctx *ctx);
+int echo_load_policy_abort(echo_ctx *ctx);
+
 /* Generate G samples for each of n_prompts prompts (sequence n = p*G + g) by ancestral sampling from
  * softmax(logits / temperature) (Algorithm 1, "sample and generate y ~ pi(.|x)"), up to max_new tokens each.
  * The draw for vocabulary entry i of sequence n at step s is the Gumbel-max rule on a counter-based uniform

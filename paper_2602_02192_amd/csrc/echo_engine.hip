@@ -160,6 +160,27 @@ Plan make_plan(const echo_model_desc *d) {
 
 }  // namespace
 
+// A byte range of a snapshot blob and where it goes: a plain copy to dst (rows == 0), or rows x K bf16 values that are
+// packed into the weight at dst, blob row r becoming packed row dst_row0 + r * stride.
+struct BlobSeg {
+  size_t off, bytes;
+  char *dst;
+  int64_t rows = 0;
+  int K = 0;
+  int64_t dst_row0 = 0;
+  int stride = 1;
+  std::vector<char> carry;
+};
+
+// A snapshot that is arriving piece by piece (echo_load_policy_begin .. _commit).
+struct Loading {
+  bool open = false;
+  int64_t version = -1;
+  int target = -1;
+  size_t received = 0, total = 0;
+  std::vector<BlobSeg> segs;
+};
+
 struct echo_ctx {
   echo_model_desc d;
   Plan p;
@@ -170,6 +191,9 @@ struct echo_ctx {
   Slot slots[2];
   int active = -1, staged = -1;
   hipEvent_t staged_ev = nullptr;
+  Loading load;
+  int64_t newest_version = -1;
+  int stage_flip = 0;
   bool rollout_running = false;
   std::mutex mu;
   std::condition_variable cv;
@@ -248,60 +272,91 @@ void bind_slot(echo_ctx *c, int s) {
   }
 }
 
-// Copy a row-major bf16 matrix from the host blob through the staging buffer into a packed weight.
-int stage_matrix(echo_ctx *c, const void *dst, const char *src, int64_t rows, int K, int64_t dst_row0, int stride) {
-  int Np = (int)round_up(rows * stride, 32);
-  int Kp = (int)round_up(K, GEMM_K_PAD);
-  int64_t row_bytes = (int64_t)K * 2, rows_per = std::max<int64_t>(1, (int64_t)(c->p.stage_bytes / 2) / row_bytes);
-  static int flip = 0;
-  for (int64_t r = 0; r < rows; r += rows_per) {
-    int64_t n = std::min(rows_per, rows - r);
-    char *stg = c->arena + c->p.o_stage + (flip ? c->p.stage_bytes / 2 : 0);
-    flip ^= 1;
+// Upload rows r0 .. r0+n-1 of a row-major bf16 matrix through the staging buffer and pack them into its weight.
+int stage_rows(echo_ctx *c, const BlobSeg &g, const char *src, int64_t r0, int64_t n_rows) {
+  int Np = (int)round_up(g.rows * g.stride, 32);
+  int Kp = (int)round_up(g.K, GEMM_K_PAD);
+  int64_t row_bytes = (int64_t)g.K * 2, rows_per = std::max<int64_t>(1, (int64_t)(c->p.stage_bytes / 2) / row_bytes);
+  for (int64_t r = 0; r < n_rows; r += rows_per) {
+    int64_t n = std::min(rows_per, n_rows - r);
+    char *stg = c->arena + c->p.o_stage + (c->stage_flip ? c->p.stage_bytes / 2 : 0);
+    c->stage_flip ^= 1;
     HIPCHK(c, hipMemcpyAsync(stg, src + r * row_bytes, (size_t)(n * row_bytes), hipMemcpyHostToDevice, c->ks));
-    fast_pack_weight((void *)dst, stg, dst_row0 + r * stride, stride, n, K, Kp, Np, c->ks);
+    fast_pack_weight(g.dst, stg, g.dst_row0 + (r0 + r) * g.stride, g.stride, n, g.K, Kp, Np, c->ks);
   }
   return 0;
 }
 
-int install(echo_ctx *c, int s, const char *blob) {
+// The byte ranges of a snapshot blob for weight slot s, each with the place its bytes go to.
+std::vector<BlobSeg> blob_segments(echo_ctx *c, int s) {
   const echo_model_desc &d = c->d;
   Slot &S = c->slots[s];
-  if (!c->p.fast) {
-    size_t total = c->p.slot_bytes, step = (size_t)256 << 20;
-    for (size_t o = 0; o < total; o += step)
-      HIPCHK(c, hipMemcpyAsync(S.base + o, blob + o, std::min(step, total - o), hipMemcpyHostToDevice, c->ks));
-    return 0;
+  std::vector<BlobSeg> v;
+  if (!c->p.fast) {  // the slot holds the blob as it is
+    v.push_back(BlobSeg{0, c->p.slot_bytes, S.base});
+    return v;
   }
   int64_t H = d.hidden, hd = d.head_dim, Q = (int64_t)d.n_q_heads * hd, KV = (int64_t)d.n_kv_heads * hd, F = d.ffn, V = d.vocab;
-  HIPCHK(c, hipMemsetAsync(S.base, 0, c->p.slot_bytes, c->ks));  // zero rows/columns of padding
-  const char *p = blob;
-  auto raw = [&](const void *dst, size_t bytes) -> int {
-    HIPCHK(c, hipMemcpyAsync((void *)dst, p, bytes, hipMemcpyHostToDevice, c->ks));
-    p += bytes;
-    return 0;
+  size_t off = 0;
+  auto raw = [&](const void *dst, size_t bytes) { v.push_back(BlobSeg{off, bytes, (char *)dst}); off += bytes; };
+  auto mat = [&](const void *dst, int64_t rows, int64_t K, int64_t row0, int stride, size_t at_off, bool advance) {
+    BlobSeg g{at_off, (size_t)(rows * K * 2), (char *)dst};
+    g.rows = rows; g.K = (int)K; g.dst_row0 = row0; g.stride = stride;
+    v.push_back(g);
+    if (advance) off += g.bytes;
   };
-  int rc;
-  const char *embed_src = p;
-  if ((rc = raw(S.embed, (size_t)V * H * 2))) return rc;
+  size_t embed_off = off;
+  raw(S.embed, (size_t)V * H * 2);
   for (int l = 0; l < d.n_layers; ++l) {
     LayerW &L = S.layers[l];
-    if ((rc = raw(L.attn_norm, H * 2))) return rc;
-    if ((rc = stage_matrix(c, L.wqkv, p, Q + 2 * KV, (int)H, 0, 1))) return rc;
-    p += (Q + 2 * KV) * H * 2;
-    if (d.qk_norm) { if ((rc = raw(L.q_norm, hd * 2))) return rc; if ((rc = raw(L.k_norm, hd * 2))) return rc; }
-    if ((rc = stage_matrix(c, L.wo, p, H, (int)Q, 0, 1))) return rc;
-    p += H * Q * 2;
-    if ((rc = raw(L.ffn_norm, H * 2))) return rc;
-    if ((rc = stage_matrix(c, L.wgu, p, F, (int)H, 0, 2))) return rc;  // gate -> even rows
-    p += F * H * 2;
-    if ((rc = stage_matrix(c, L.wgu, p, F, (int)H, 1, 2))) return rc;  // up   -> odd rows
-    p += F * H * 2;
-    if ((rc = stage_matrix(c, L.wdown, p, H, (int)F, 0, 1))) return rc;
-    p += H * F * 2;
+    raw(L.attn_norm, H * 2);
+    mat(L.wqkv, Q + 2 * KV, H, 0, 1, off, true);
+    if (d.qk_norm) { raw(L.q_norm, hd * 2); raw(L.k_norm, hd * 2); }
+    mat(L.wo, H, Q, 0, 1, off, true);
+    raw(L.ffn_norm, H * 2);
+    mat(L.wgu, F, H, 0, 2, off, true);  // gate -> even rows
+    mat(L.wgu, F, H, 1, 2, off, true);  // up   -> odd rows
+    mat(L.wdown, H, F, 0, 1, off, true);
   }
-  if ((rc = raw(S.final_norm, H * 2))) return rc;
-  if ((rc = stage_matrix(c, S.lm_head, d.tie_embeddings ? embed_src : p, V, (int)H, 0, 1))) return rc;
+  raw(S.final_norm, H * 2);
+  if (d.tie_embeddings) mat(S.lm_head, V, H, 0, 1, embed_off, false);  // a second consumer of the embedding's bytes
+  else mat(S.lm_head, V, H, 0, 1, off, true);
+  return v;
+}
+
+// Bytes [lo, lo + n) of the blob have arrived at `data`: send the part of every segment they cover on its way.
+// A matrix moves in whole rows; the bytes of a row cut by the end of a piece wait in the segment's carry buffer.
+int feed_segments(echo_ctx *c, std::vector<BlobSeg> &segs, const char *data, size_t lo, size_t n) {
+  size_t hi = lo + n;
+  for (BlobSeg &g : segs) {
+    size_t a = std::max(lo, g.off), b = std::min(hi, g.off + g.bytes);
+    if (a >= b) continue;
+    const char *src = data + (a - lo);
+    size_t rel = a - g.off, len = b - a;
+    if (g.rows == 0) {
+      for (size_t o = 0; o < len; o += (size_t)256 << 20)
+        HIPCHK(c, hipMemcpyAsync(g.dst + rel + o, src + o, std::min((size_t)256 << 20, len - o), hipMemcpyHostToDevice, c->ks));
+      continue;
+    }
+    size_t row_bytes = (size_t)g.K * 2;
+    if (!g.carry.empty()) {  // finish the row the last piece left open
+      size_t take = std::min(row_bytes - g.carry.size(), len);
+      int64_t row = (int64_t)((rel - g.carry.size()) / row_bytes);
+      g.carry.insert(g.carry.end(), src, src + take);
+      src += take; rel += take; len -= take;
+      if (g.carry.size() < row_bytes) continue;
+      int rc = stage_rows(c, g, g.carry.data(), row, 1);
+      if (rc) return rc;
+      HIPCHK(c, hipStreamSynchronize(c->ks));  // the carry buffer is reused below
+      g.carry.clear();
+    }
+    size_t whole = len / row_bytes;
+    if (whole) {
+      int rc = stage_rows(c, g, src, (int64_t)(rel / row_bytes), (int64_t)whole);
+      if (rc) return rc;
+    }
+    g.carry.assign(src + whole * row_bytes, src + len);
+  }
   return 0;
 }
 
@@ -570,12 +625,12 @@ int echo_init(const echo_model_desc *desc, int device, void *dev_arena, size_t a
   return ECHO_OK;
 }
 
-int echo_load_policy(echo_ctx *c, int64_t version, const void *host_weights, size_t nbytes) {
+int echo_load_policy_begin(echo_ctx *c, int64_t version, size_t nbytes) {
   if (!c) return ECHO_EINVAL;
   std::unique_lock<std::mutex> lk(c->mu);
-  if (!host_weights) return fail(c, ECHO_EINVAL, "host_weights is NULL");
   if (nbytes != echo_blob_bytes(&c->d)) return fail(c, ECHO_EINVAL, "blob has %zu bytes, this shape needs %zu", nbytes, echo_blob_bytes(&c->d));
-  int64_t newest = std::max(c->active >= 0 ? c->slots[c->active].version : -1, c->staged >= 0 ? c->slots[c->staged].version : -1);
+  if (c->load.open) return fail(c, ECHO_ESTATE, "snapshot %lld is still arriving (commit or abort it first)", (long long)c->load.version);
+  int64_t newest = c->newest_version;  // of the snapshots committed so far
   if (version <= newest || version < 0) return fail(c, ECHO_ESTATE, "version %lld does not advance past %lld", (long long)version, (long long)newest);
   if (c->staged >= 0) return fail(c, ECHO_ESTATE, "a staged snapshot is still waiting to be switched in");
   bool running = c->rollout_running;
@@ -584,24 +639,88 @@ int echo_load_policy(echo_ctx *c, int64_t version, const void *host_weights, siz
   else if (c->d.n_weight_slots == 2) target = 1 - c->active;
   else if (!running) target = c->active;
   else return fail(c, ECHO_ESTATE, "installing during a rollout needs n_weight_slots = 2");
+  c->load.open = true;  // from here on a rollout cannot start on the target slot
+  c->load.version = version; c->load.target = target; c->load.received = 0; c->load.total = nbytes;
   lk.unlock();
+  auto undo = [&](int rc) { lk.lock(); c->load.open = false; if (target == c->active) { c->active = -1; c->st.active_version = -1; } return rc; };
+  if (hipSetDevice(c->device) != hipSuccess) return undo(fail(c, ECHO_EHIP, "hipSetDevice failed"));
+  if (!running && hipStreamSynchronize(c->cs) != hipSuccess) return undo(fail(c, ECHO_EHIP, "hipStreamSynchronize failed"));
+  c->load.segs = blob_segments(c, target);
+  // zero rows and columns of padding in the packed weights
+  if (c->p.fast && hipMemsetAsync(c->slots[target].base, 0, c->p.slot_bytes, c->ks) != hipSuccess) return undo(fail(c, ECHO_EHIP, "hipMemsetAsync failed"));
+  return ECHO_OK;
+}
+
+int echo_load_policy_chunk(echo_ctx *c, const void *data, size_t nbytes) {
+  if (!c) return ECHO_EINVAL;
+  {
+    std::lock_guard<std::mutex> lk(c->mu);
+    if (!c->load.open) return fail(c, ECHO_ESTATE, "no snapshot is being loaded");
+    if (!data && nbytes) return fail(c, ECHO_EINVAL, "data is NULL");
+    if (nbytes > c->load.total - c->load.received)
+      return fail(c, ECHO_EINVAL, "%zu bytes after %zu overrun the blob of %zu", nbytes, c->load.received, c->load.total);
+  }
   HIPCHK(c, hipSetDevice(c->device));
-  if (!running) HIPCHK(c, hipStreamSynchronize(c->cs));
-  int rc = install(c, target, (const char *)host_weights);
+  int rc = feed_segments(c, c->load.segs, (const char *)data, c->load.received, nbytes);
   if (rc) return rc;
+  HIPCHK(c, hipStreamSynchronize(c->ks));  // the piece may be freed when this call returns
+  c->load.received += nbytes;
+  return ECHO_OK;
+}
+
+int echo_load_policy_commit(echo_ctx *c) {
+  if (!c) return ECHO_EINVAL;
+  {
+    std::lock_guard<std::mutex> lk(c->mu);
+    if (!c->load.open) return fail(c, ECHO_ESTATE, "no snapshot is being loaded");
+    if (c->load.received != c->load.total) return fail(c, ECHO_ESTATE, "%zu of %zu bytes have arrived", c->load.received, c->load.total);
+  }
+  HIPCHK(c, hipSetDevice(c->device));
   HIPCHK(c, hipEventRecord(c->staged_ev, c->ks));
-  HIPCHK(c, hipStreamSynchronize(c->ks));  // the host blob may be freed when this call returns
-  lk.lock();
-  c->slots[target].version = version;
+  HIPCHK(c, hipStreamSynchronize(c->ks));
+  std::lock_guard<std::mutex> lk(c->mu);
+  int target = c->load.target;
+  c->slots[target].version = c->load.version;
+  c->newest_version = c->load.version;
   if (c->rollout_running) {
     c->staged = target;
-    c->st.staged_version = version;
+    c->st.staged_version = c->load.version;
   } else {
     c->active = target;
-    c->st.active_version = version;
+    c->st.active_version = c->load.version;
   }
+  c->load.open = false;
+  c->load.segs.clear();
   c->cv.notify_all();
   return ECHO_OK;
+}
+
+int echo_load_policy_abort(echo_ctx *c) {
+  if (!c) return ECHO_EINVAL;
+  hipSetDevice(c->device);
+  hipStreamSynchronize(c->ks);
+  std::lock_guard<std::mutex> lk(c->mu);
+  if (!c->load.open) return fail(c, ECHO_ESTATE, "no snapshot is being loaded");
+  if (c->load.target == c->active) {  // the only slot now holds part of two snapshots
+    c->active = -1;
+    c->st.active_version = -1;
+  }
+  c->load.open = false;
+  c->load.segs.clear();
+  return ECHO_OK;
+}
+
+int echo_load_policy(echo_ctx *c, int64_t version, const void *host_weights, size_t nbytes) {
+  if (!c) return ECHO_EINVAL;
+  if (!host_weights) return fail(c, ECHO_EINVAL, "host_weights is NULL");
+  int rc = echo_load_policy_begin(c, version, nbytes);
+  if (rc) return rc;
+  if ((rc = echo_load_policy_chunk(c, host_weights, nbytes)) || (rc = echo_load_policy_commit(c))) {
+    std::string msg = c->err;
+    echo_load_policy_abort(c);
+    c->err = msg;
+  }
+  return rc;
 }
 
 int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_stride, const int32_t *prompt_lens, int32_t P, int32_t G,
@@ -638,6 +757,7 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
   {
     std::lock_guard<std::mutex> lk(c->mu);
     if (c->active < 0) return fail(c, ECHO_ESTATE, "no policy snapshot installed");
+    if (c->load.open && c->load.target == c->active) return fail(c, ECHO_ESTATE, "a snapshot is arriving in the only weight slot");
     if (c->rollout_running) return fail(c, ECHO_ESTATE, "a rollout is already running on this context");
     c->rollout_running = true;
   }
@@ -834,6 +954,7 @@ int echo_logprobs(echo_ctx *c, const int32_t *tokens, int32_t stride, const int3
   {
     std::lock_guard<std::mutex> lk(c->mu);
     if (c->active < 0) return fail(c, ECHO_ESTATE, "no policy snapshot installed");
+    if (c->load.open && c->load.target == c->active) return fail(c, ECHO_ESTATE, "a snapshot is arriving in the only weight slot");
     if (c->rollout_running) return fail(c, ECHO_ESTATE, "a rollout is running on this context");
   }
   HIPCHK(c, hipSetDevice(c->device));

@@ -48,7 +48,8 @@ class Stats(C.Structure):
                 ("rollout_running", C.c_int32)]
 
 
-EXPORTS = ["echo_arena_bytes", "echo_blob_bytes", "echo_init", "echo_load_policy", "echo_rollout",
+EXPORTS = ["echo_arena_bytes", "echo_blob_bytes", "echo_init", "echo_load_policy", "echo_load_policy_begin",
+           "echo_load_policy_chunk", "echo_load_policy_commit", "echo_load_policy_abort", "echo_rollout",
            "echo_logprobs", "echo_grpo_tensors", "echo_debug_draw_bits", "echo_stats", "echo_last_error", "echo_destroy"]
 
 lib.echo_arena_bytes.restype = C.c_size_t
@@ -58,6 +59,10 @@ lib.echo_blob_bytes.argtypes = [C.POINTER(ModelDesc)]
 lib.echo_init.argtypes = [C.POINTER(ModelDesc), C.c_int, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p,
                           C.POINTER(C.c_void_p)]
 lib.echo_load_policy.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t]
+lib.echo_load_policy_begin.argtypes = [C.c_void_p, C.c_int64, C.c_size_t]
+lib.echo_load_policy_chunk.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
+lib.echo_load_policy_commit.argtypes = [C.c_void_p]
+lib.echo_load_policy_abort.argtypes = [C.c_void_p]
 lib.echo_rollout.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                              C.c_float, C.c_uint64, C.POINTER(RolloutOpts), C.c_void_p, C.c_void_p, C.c_void_p,
                              C.c_void_p]
@@ -147,6 +152,43 @@ class Context:
             blob = np.ascontiguousarray(blob)
             ptr, nbytes = blob.ctypes.data, blob.nbytes
         self._chk(lib.echo_load_policy(self.h, version, C.c_void_p(ptr), nbytes))
+
+    def load_policy_chunked(self, version: int, blob, chunk_sizes, between=None) -> None:
+        """The same blob handed over in pieces of the given byte sizes (cycled until the blob ends); `between`,
+        if given, is called after every piece."""
+        if isinstance(blob, torch.Tensor):
+            blob = blob.contiguous()
+            ptr, nbytes = blob.data_ptr(), blob.numel() * blob.element_size()
+        else:
+            blob = np.ascontiguousarray(blob)
+            ptr, nbytes = blob.ctypes.data, blob.nbytes
+        self._chk(lib.echo_load_policy_begin(self.h, version, nbytes))
+        try:
+            off, k = 0, 0
+            while off < nbytes:
+                n = min(int(chunk_sizes[k % len(chunk_sizes)]), nbytes - off)
+                self._chk(lib.echo_load_policy_chunk(self.h, C.c_void_p(ptr + off), n))
+                off += n
+                k += 1
+                if between is not None:
+                    between()
+            self._chk(lib.echo_load_policy_commit(self.h))
+        except Exception:
+            lib.echo_load_policy_abort(self.h)
+            raise
+
+    def load_policy_begin(self, version: int, nbytes: int) -> None:
+        self._chk(lib.echo_load_policy_begin(self.h, version, nbytes))
+
+    def load_policy_chunk(self, data: np.ndarray) -> None:
+        data = np.ascontiguousarray(data)
+        self._chk(lib.echo_load_policy_chunk(self.h, C.c_void_p(data.ctypes.data), data.nbytes))
+
+    def load_policy_commit(self) -> None:
+        self._chk(lib.echo_load_policy_commit(self.h))
+
+    def load_policy_abort(self) -> None:
+        self._chk(lib.echo_load_policy_abort(self.h))
 
     def rollout(self, prompts, prompt_lens, G: int, max_new: int, temperature: float, seed: int,
                 stop_lens=None, eos_id: int = -1, top_p: float = 1.0, swap_at_step: Sequence[int] = (),
