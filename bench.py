@@ -107,6 +107,8 @@ def main():
     ap.add_argument("--ctx-pad", type=int, default=0, help="extra KV-cache tokens per sequence beyond prompt + max_new")
     ap.add_argument("--pageable-blob", action="store_true",
                     help="keep the host copy of the weights in pageable memory (a counter-collecting profiler crashed on the pinned copy)")
+    ap.add_argument("--install-chunk-mb", type=int, default=0,
+                    help="snapshot swaps inside a rollout hand the blob over in pieces of this size (0 = one call)")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch decode steps kernel by kernel (counter collection cannot follow graph replays)")
     a = ap.parse_args()
@@ -170,7 +172,11 @@ def main():
                 if done.is_set():
                     return
                 version[0] += 1
-                ctx.load_policy(version[0], blob_b if version[0] % 2 else blob)
+                nxt = blob_b if version[0] % 2 else blob
+                if a.install_chunk_mb > 0:
+                    ctx.load_policy_chunked(version[0], nxt, [a.install_chunk_mb << 20])
+                else:
+                    ctx.load_policy(version[0], nxt)
 
         th = threading.Thread(target=feeder)
         th.start()
@@ -266,7 +272,7 @@ def main():
                         "hbm_frac_of_8TBps": step_frac, "algorithmic_bytes_per_rollout": bytes_decode,
                         "hbm_frac_if_every_sequence_read_its_own_prompt_copy": step_frac_per_seq,
                         "prefill_ms": float(np.mean(prefill_ms)), "policy_install_s": load_s,
-                        "swaps_per_rollout": len(swaps), "swap_wait_ms": float(np.mean(swap_wait_ms))},
+                        "swaps_per_rollout": len(swaps), "install_chunk_mb": a.install_chunk_mb, "swap_wait_ms": float(np.mean(swap_wait_ms))},
         "scoring_pass": score,
         "roofline": roofline, "cpu_baseline": cpu,
     }
