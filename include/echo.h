@@ -149,6 +149,22 @@ int echo_rollout(echo_ctx *ctx, const int32_t *prompt_tokens, int32_t prompt_str
                  const echo_rollout_opts *opts, int32_t *out_tokens, float *out_logprobs, int32_t *out_lens,
                  int64_t *out_versions);
 
+/* The same rollout for more prompts than the KV cache holds at once: the worker's generate-continuously loop
+ * (Algorithm 1, rollout side).  max_seqs / G groups decode together; when all G sequences of a group have
+ * ended its records are handed over and the next waiting prompt takes its cache slots, so the batch stays
+ * full until the prompts run out.  Arguments, output layout (sequence n = p*G + g over ALL n_prompts), sampling
+ * rule and per-sequence results are those of echo_rollout -- the draw of sequence n at its own step s is keyed
+ * (seed; n, s, i) whenever it runs -- with these differences:
+ *   - n_prompts * G may exceed max_seqs (G may not: ECHO_ENOMEM); prompt_len + max_new <= max_ctx as before;
+ *   - a snapshot staged by echo_load_policy / _commit while the call runs is switched in between two decode
+ *     steps as soon as it is there (out_versions tags every token); pinned swaps (n_swaps), debug_logits and
+ *     time_kernels are refused with ECHO_EINVAL;
+ *   - echo_stats: prefill_ms is the time spent admitting prompts, decode_ms the rest. */
+int echo_rollout_continuous(echo_ctx *ctx, const int32_t *prompt_tokens, int32_t prompt_stride,
+                            const int32_t *prompt_lens, int32_t n_prompts, int32_t G, int32_t max_new,
+                            float temperature, uint64_t seed, const echo_rollout_opts *opts, int32_t *out_tokens,
+                            float *out_logprobs, int32_t *out_lens, int64_t *out_versions);
+
 /* Teacher-forced scoring under the active snapshot (the learner-side pi(y_t | x, y_<t) of the importance
  * ratio): out[n][t] = log softmax(logits_{t-1}/temperature)[tokens[n][t]] for 1 <= t < lens[n], else 0.
  *   tokens host [n_seqs, stride]; lens host [n_seqs]; out host [n_seqs, stride]. */

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "echo_kernels.h"
+
 namespace echo {
 
 // MFMA operands are IEEE half precision (11-bit significand): activations, the KV cache and the attention
@@ -59,6 +61,10 @@ __device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_
 __device__ __forceinline__ u32x4 draw4(uint64_t seed, uint32_t n, uint32_t s, uint32_t i4) {
   return philox4x32_10(i4, s, n, 0u, (uint32_t)seed, (uint32_t)(seed >> 32));
 }
+
+// Step and stream words of row m's draws.
+__device__ __forceinline__ uint32_t draw_step(const DrawIds &d, int m) { return (uint32_t)(d.row_step ? d.row_step[m] : *d.d_step); }
+__device__ __forceinline__ uint32_t draw_stream(const DrawIds &d, int m) { return (uint32_t)(d.row_stream ? d.row_stream[m] : m); }
 
 // 23 random bits -> u = (2k+1) 2^-24, then the standard Gumbel variate -log(-log u) in fp32.
 __device__ __forceinline__ float gumbel_from_bits(uint32_t bits) {

@@ -145,7 +145,7 @@ Plan make_plan(const echo_model_desc *d) {
   p.o_topp = b.take(fast_topp_scratch_floats((int)pad_rows(d->max_seqs)) * 4);
   p.o_rows = b.take(6 * M * 4);
   p.o_maps = b.take(2 * M * 4 + (size_t)d->max_seqs * 4);
-  p.o_seq = b.take(3 * (size_t)d->max_seqs * 4);
+  p.o_seq = b.take(4 * (size_t)pad_rows(d->max_seqs) * 4);   // samplers read the step and stream of padding rows too
   p.o_samp = b.take(4 * M * 4);
   size_t outn = (size_t)d->max_seqs * d->max_ctx;
   p.o_out_tok = b.take(outn * 4);
@@ -204,6 +204,8 @@ struct echo_ctx {
   KvGeom kv;
   int32_t *d_prompt_len_seq, *d_gen_len, *d_limit, *d_samp_tok, *d_target, *d_step, *d_n_active, *d_map_a, *d_map_b, *d_plen_p;
   float *d_samp_lp, *d_target_lp;
+  int32_t *d_stream;  // per-row stream ids of a continuous rollout
+  DrawIds ids{nullptr, nullptr, nullptr};
   hipGraphExec_t graph = nullptr;
   // kernel timing (time_kernels)
   std::vector<std::pair<hipEvent_t, hipEvent_t>> ev_attn, ev_gemm;
@@ -447,7 +449,7 @@ void forward_layers(echo_ctx *c, const Slot &S, int M, bool use_splitk_attn, int
 void nucleus(echo_ctx *c, const float *logits, int64_t ld, int M, float temperature, float top_p, uint64_t seed) {
   int Mp = pad_rows(M);
   float *scratch = at<float>(c, c->p.o_topp);
-  fast_topp_cut_and_draw(scratch, logits, ld, M, Mp, c->d.vocab, temperature, top_p, seed, c->d_step, nullptr, c->cs);
+  fast_topp_cut_and_draw(scratch, logits, ld, M, Mp, c->d.vocab, temperature, top_p, seed, c->ids, nullptr, c->cs);
   fast_sample_combine(c->d_samp_tok, c->d_samp_lp, scratch, TOPP_CHUNKS_PER_ROW, M, Mp, nullptr, c->cs);
 }
 
@@ -461,7 +463,7 @@ void sample_rows(echo_ctx *c, const Slot &S, int M, float temperature, uint64_t 
     int bf = d.dtype == ECHO_BF16;
     dbg_gemm(logits, at<float>(c, p.o_x), S.lm_head, bf, M, d.vocab, d.hidden, 0, st);
     if (top_p < 1.0f) nucleus(c, logits, d.vocab, M, temperature, top_p, seed);
-    else dbg_sample(c->d_samp_tok, c->d_samp_lp, logits, d.vocab, M, d.vocab, temperature, seed, c->d_step, nullptr, st);
+    else dbg_sample(c->d_samp_tok, c->d_samp_lp, logits, d.vocab, M, d.vocab, temperature, seed, c->ids, nullptr, st);
     if (target) dbg_target_logprob(c->d_target_lp, logits, d.vocab, M, d.vocab, temperature, target, st);
     return;
   }
@@ -472,12 +474,12 @@ void sample_rows(echo_ctx *c, const Slot &S, int M, float temperature, uint64_t 
       fast_lmhead_logits(logits, p.Np_v, at<void>(c, p.o_xa), S.lm_head, Mp, p.Np_v, p.Kp_d, d.vocab, st);
     }
     if (top_p < 1.0f) nucleus(c, logits, p.Np_v, M, temperature, top_p, seed);
-    else dbg_sample(c->d_samp_tok, c->d_samp_lp, logits, p.Np_v, M, d.vocab, temperature, seed, c->d_step, nullptr, st);
+    else dbg_sample(c->d_samp_tok, c->d_samp_lp, logits, p.Np_v, M, d.vocab, temperature, seed, c->ids, nullptr, st);
     if (target) dbg_target_logprob(c->d_target_lp, logits, p.Np_v, M, d.vocab, temperature, target, st);
   } else {
     TimerScope t(c, &c->ev_gemm);
     fast_lmhead_sample(c->d_samp_tok, c->d_samp_lp, c->d_target_lp, at<void>(c, p.o_xa), S.lm_head, Mp, M, d.vocab, p.Np_v, p.Kp_d,
-                       temperature, seed, c->d_step, nullptr, target, at<float>(c, p.o_lmpart), st);
+                       temperature, seed, c->ids, nullptr, target, at<float>(c, p.o_lmpart), st);
   }
   if (c->timing) c->t_gemm_bytes += (double)p.Np_v * p.Kp_d * 2;
 }
@@ -499,11 +501,13 @@ struct ChunkRow { int32_t token, slot, pos; };
 
 // Feed the token strings (one per cache slot slot0 + q*slot_step) through the decoder in chunks of rows.
 // After each chunk `after(chunk_rows, M)` runs (still on the compute stream).
+struct ChunkSeq { const int32_t *tokens; int len, slot; };
+
 template <typename F>
-int run_chunks(echo_ctx *c, const Slot &S, const int32_t *tokens, int stride, const std::vector<int> &lens, int slot_step, F after) {
+int run_chunk_seqs(echo_ctx *c, const Slot &S, const std::vector<ChunkSeq> &seqs, F after) {
   std::vector<ChunkRow> all;
-  for (size_t q = 0; q < lens.size(); ++q)
-    for (int t = 0; t < lens[q]; ++t) all.push_back({tokens[(int64_t)q * stride + t], (int32_t)(q * slot_step), t});
+  for (const ChunkSeq &q : seqs)
+    for (int t = 0; t < q.len; ++t) all.push_back({q.tokens[t], (int32_t)q.slot, t});
   int R = std::min(PREFILL_ROWS, c->p.Mcap);
   std::vector<int32_t> tok(R), slot(R), pos(R), act(R);
   std::vector<PrefillBlock> blocks;
@@ -535,14 +539,21 @@ int run_chunks(echo_ctx *c, const Slot &S, const int32_t *tokens, int stride, co
   return 0;
 }
 
+template <typename F>
+int run_chunks(echo_ctx *c, const Slot &S, const int32_t *tokens, int stride, const std::vector<int> &lens, int slot_step, F after) {
+  std::vector<ChunkSeq> seqs;
+  for (size_t q = 0; q < lens.size(); ++q) seqs.push_back({tokens + (int64_t)q * stride, lens[q], (int)(q * slot_step)});
+  return run_chunk_seqs(c, S, seqs, after);
+}
+
 int capture_step(echo_ctx *c, const Slot &S, int N, int max_new, float temperature, uint64_t seed, bool unfused, const int32_t *forced,
-                 int eos, float top_p) {
+                 int eos, float top_p, int per_row = 0) {
   if (c->graph) { hipGraphExecDestroy(c->graph); c->graph = nullptr; }
   hipGraph_t g = nullptr;
   HIPCHK(c, hipStreamBeginCapture(c->cs, hipStreamCaptureModeThreadLocal));
   forward_layers(c, S, N, !env_flag("ECHO_ATTN_SIMPLE"));
   sample_rows(c, S, N, temperature, seed, unfused, nullptr, top_p);
-  launch_bookkeeping(N, max_new, c->d_step, c->d_samp_tok, c->d_samp_lp, forced, c->d_limit, eos, S.version, c->d_prompt_len_seq,
+  launch_bookkeeping(N, max_new, per_row, c->d_step, c->d_samp_tok, c->d_samp_lp, forced, c->d_limit, eos, S.version, c->d_prompt_len_seq,
                      c->d_gen_len, c->rows, at<int32_t>(c, c->p.o_out_tok), at<float>(c, c->p.o_out_lp), at<int64_t>(c, c->p.o_out_ver),
                      c->d_n_active, c->cs);
   HIPCHK(c, hipStreamEndCapture(c->cs, &g));
@@ -609,12 +620,14 @@ int echo_init(const echo_model_desc *desc, int device, void *dev_arena, size_t a
   c->kv = {c->arena + p.o_kv, desc->n_layers, desc->n_kv_heads, p.fast ? (int32_t)round_up(desc->max_ctx, 32) : desc->max_ctx, desc->head_dim,
            p.fast ? 2 : 4, p.fast ? 1 : 0};
   int32_t *q = at<int32_t>(c, p.o_seq);
-  c->d_prompt_len_seq = q; c->d_gen_len = q + desc->max_seqs; c->d_limit = q + 2 * (size_t)desc->max_seqs;
+  size_t Ms = pad_rows(desc->max_seqs);
+  c->d_prompt_len_seq = q; c->d_gen_len = q + Ms; c->d_limit = q + 2 * Ms; c->d_stream = q + 3 * Ms;
   int32_t *sm = at<int32_t>(c, p.o_samp);
   c->d_samp_tok = sm; c->d_samp_lp = (float *)(sm + M); c->d_target = sm + 2 * M; c->d_target_lp = (float *)(sm + 3 * M);
   int32_t *mp = at<int32_t>(c, p.o_maps);
   c->d_map_a = mp; c->d_map_b = mp + M; c->d_plen_p = mp + 2 * M;
   c->d_step = at<int32_t>(c, p.o_scal); c->d_n_active = c->d_step + 1;
+  c->ids = DrawIds{c->d_step, nullptr, nullptr};
   // activations, row state and scratch start from zero (padding rows and columns are never written); so does the
   // KV cache: the keys of a sequence's last tile that lie beyond its length get weight zero, which only cancels
   // a finite value
@@ -846,7 +859,7 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
   };
   if ((rc = grab_logits(0))) return rc;
   auto book = [&](int slot) {
-    launch_bookkeeping(N, max_new, c->d_step, c->d_samp_tok, c->d_samp_lp, d_forced, c->d_limit, o.eos_id, c->slots[slot].version,
+    launch_bookkeeping(N, max_new, 0, c->d_step, c->d_samp_tok, c->d_samp_lp, d_forced, c->d_limit, o.eos_id, c->slots[slot].version,
                        c->d_prompt_len_seq, c->d_gen_len, c->rows, at<int32_t>(c, p.o_out_tok), at<float>(c, p.o_out_lp),
                        at<int64_t>(c, p.o_out_ver), c->d_n_active, st);
   };
@@ -933,6 +946,196 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
     c->st.gemm_bytes = c->t_gemm_bytes;
     c->timing = false;
   }
+  return ECHO_OK;
+}
+
+int echo_rollout_continuous(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_stride, const int32_t *prompt_lens, int32_t P,
+                            int32_t G, int32_t max_new, float temperature, uint64_t seed, const echo_rollout_opts *opts,
+                            int32_t *out_tokens, float *out_logprobs, int32_t *out_lens, int64_t *out_versions) {
+  if (!c) return ECHO_EINVAL;
+  echo_rollout_opts o;
+  memset(&o, 0, sizeof o);
+  o.eos_id = -1; o.top_p = 1.0f;
+  if (opts) o = *opts;
+  if (!prompt_tokens || !prompt_lens || !out_tokens || !out_logprobs || !out_lens) return fail(c, ECHO_EINVAL, "NULL argument");
+  if (P < 1 || G < 1 || max_new < 1 || prompt_stride < 1) return fail(c, ECHO_EINVAL, "n_prompts, G, max_new and prompt_stride must be positive");
+  if (!(temperature > 0.f)) return fail(c, ECHO_EINVAL, "temperature must be positive");
+  if (!(o.top_p > 0.f) || o.top_p > 1.0f) return fail(c, ECHO_EINVAL, "top_p must be in (0, 1]");
+  if (o.n_swaps || o.debug_logits || o.time_kernels)
+    return fail(c, ECHO_EINVAL, "a continuous rollout takes no pinned swaps (it switches when a snapshot is staged), no debug_logits and no time_kernels");
+  if (G > c->d.max_seqs) return fail(c, ECHO_ENOMEM, "one group of %d sequences exceeds max_seqs = %d", G, c->d.max_seqs);
+  if ((int64_t)P * G * max_new > INT32_MAX) return fail(c, ECHO_EINVAL, "n_prompts * G * max_new exceeds 2^31 - 1");
+  int max_pl = 0;
+  for (int p = 0; p < P; ++p) {
+    if (prompt_lens[p] < 1 || prompt_lens[p] > prompt_stride) return fail(c, ECHO_EINVAL, "prompt_lens[%d] = %d out of range", p, prompt_lens[p]);
+    max_pl = std::max(max_pl, prompt_lens[p]);
+    for (int t = 0; t < prompt_lens[p]; ++t) {
+      int tk = prompt_tokens[(int64_t)p * prompt_stride + t];
+      if (tk < 0 || tk >= c->d.vocab) return fail(c, ECHO_EINVAL, "prompt token %d of prompt %d is outside the vocabulary", t, p);
+    }
+  }
+  if ((int64_t)max_pl + max_new > c->d.max_ctx) return fail(c, ECHO_ENOMEM, "prompt %d + max_new %d exceeds max_ctx = %d", max_pl, max_new, c->d.max_ctx);
+  const int N = P * G;
+  if (o.forced_tokens)
+    for (int64_t i = 0; i < (int64_t)N * max_new; ++i)
+      if (o.forced_tokens[i] < 0 || o.forced_tokens[i] >= c->d.vocab) return fail(c, ECHO_EINVAL, "forced token outside the vocabulary");
+  {
+    std::lock_guard<std::mutex> lk(c->mu);
+    if (c->active < 0) return fail(c, ECHO_ESTATE, "no policy snapshot installed");
+    if (c->load.open && c->load.target == c->active) return fail(c, ECHO_ESTATE, "a snapshot is arriving in the only weight slot");
+    if (c->rollout_running) return fail(c, ECHO_ESTATE, "a rollout is already running on this context");
+    c->rollout_running = true;
+  }
+  struct Done { echo_ctx *c; ~Done() {
+    std::lock_guard<std::mutex> lk(c->mu);
+    c->rollout_running = false;
+    c->ids = DrawIds{c->d_step, nullptr, nullptr};
+    if (c->staged >= 0) { c->active = c->staged; c->staged = -1; c->st.active_version = c->slots[c->active].version; c->st.staged_version = -1; }
+  } } done{c};
+
+  HIPCHK(c, hipSetDevice(c->device));
+  const Plan &p = c->p;
+  hipStream_t st = c->cs;
+  auto t0 = std::chrono::steady_clock::now();
+  const bool unfused = o.unfused_sampler || o.top_p < 1.0f;
+  const bool use_graph = !o.no_graph;
+  const bool share_prefix = p.fast && !env_flag("ECHO_NO_PREFIX_SHARING") && !env_flag("ECHO_ATTN_SIMPLE");
+  const bool splitk = !env_flag("ECHO_ATTN_SIMPLE");
+  const int B = std::min(P, c->d.max_seqs / G), R = B * G;   // group slots and rows of the batch
+  // host mirrors of the per-row state; token, pos, active and gen are read back at every check
+  std::vector<int32_t> tok(R, 0), pos(R, 0), act(R, 0), slot(R), pslot(R, 0), ptiles(R, 0), plen(R, 1), gen(R, 0), lim(R, 1), stream(R, 0);
+  std::vector<int> group_prompt(B, -1);
+  for (int r = 0; r < R; ++r) slot[r] = r;
+  int32_t *d_forced = o.forced_tokens ? at<int32_t>(c, p.o_forced) : nullptr;
+  int32_t *d_out_tok = at<int32_t>(c, p.o_out_tok);
+  float *d_out_lp = at<float>(c, p.o_out_lp);
+  int64_t *d_out_ver = at<int64_t>(c, p.o_out_ver);
+  auto upload_rows = [&]() -> int {
+    struct { int32_t *dst; std::vector<int32_t> *src; } cp[] = {
+        {c->rows.token, &tok}, {c->rows.pos, &pos}, {c->rows.active, &act}, {c->rows.slot, &slot}, {c->rows.pslot, &pslot},
+        {c->rows.ptiles, &ptiles}, {c->d_prompt_len_seq, &plen}, {c->d_gen_len, &gen}, {c->d_limit, &lim}, {c->d_stream, &stream}};
+    for (auto &x : cp) HIPCHK(c, hipMemcpyAsync(x.dst, x.src->data(), (size_t)R * 4, hipMemcpyHostToDevice, st));
+    return 0;
+  };
+  launch_fill_i32(c->d_step, 0, 1, st);
+  c->ids = DrawIds{c->d_step, c->d_gen_len, c->d_stream};
+
+  int cur = c->active, next_prompt = 0, done_prompts = 0, decode_steps = 0, until_check = 0;
+  bool have_graph = false, first = true;
+  double admit_ms = 0, swap_wait = 0;
+  int rc;
+  for (;;) {
+    if (until_check <= 0) {
+      if (!first) {
+        HIPCHK(c, hipMemcpyAsync(tok.data(), c->rows.token, (size_t)R * 4, hipMemcpyDeviceToHost, st));
+        HIPCHK(c, hipMemcpyAsync(pos.data(), c->rows.pos, (size_t)R * 4, hipMemcpyDeviceToHost, st));
+        HIPCHK(c, hipMemcpyAsync(act.data(), c->rows.active, (size_t)R * 4, hipMemcpyDeviceToHost, st));
+        HIPCHK(c, hipMemcpyAsync(gen.data(), c->d_gen_len, (size_t)R * 4, hipMemcpyDeviceToHost, st));
+        HIPCHK(c, hipStreamSynchronize(st));
+      }
+      first = false;
+      // groups whose sequences have all ended hand their records over and free their slots
+      for (int b = 0; b < B; ++b) {
+        if (group_prompt[b] < 0) continue;
+        bool busy = false;
+        for (int g = 0; g < G; ++g) busy |= act[b * G + g] != 0;
+        if (busy) continue;
+        int64_t r0 = (int64_t)b * G * max_new, n0 = (int64_t)group_prompt[b] * G * max_new, cells = (int64_t)G * max_new;
+        HIPCHK(c, hipMemcpyAsync(out_tokens + n0, d_out_tok + r0, cells * 4, hipMemcpyDeviceToHost, st));
+        HIPCHK(c, hipMemcpyAsync(out_logprobs + n0, d_out_lp + r0, cells * 4, hipMemcpyDeviceToHost, st));
+        if (out_versions) HIPCHK(c, hipMemcpyAsync(out_versions + n0, d_out_ver + r0, cells * 8, hipMemcpyDeviceToHost, st));
+        for (int g = 0; g < G; ++g) out_lens[group_prompt[b] * G + g] = gen[b * G + g];
+        group_prompt[b] = -1;
+        ++done_prompts;
+      }
+      if (done_prompts == P) break;
+      // waiting prompts take the free group slots
+      std::vector<int> admitted;
+      for (int b = 0; b < B && next_prompt < P; ++b)
+        if (group_prompt[b] < 0) { group_prompt[b] = next_prompt++; admitted.push_back(b); }
+      if (!admitted.empty()) {
+        auto a0 = std::chrono::steady_clock::now();
+        // all of a prompt but its last token goes through the causal-block pass into the group's first slot; the
+        // last token is the group's first decode input, so the first sampled token comes out of an ordinary step
+        std::vector<ChunkSeq> seqs;
+        std::vector<int32_t> plen_b(B, 0);
+        for (int b : admitted) {
+          int pp = group_prompt[b], L = prompt_lens[pp];
+          if (L > 1) seqs.push_back({prompt_tokens + (int64_t)pp * prompt_stride, L - 1, b * G});
+          plen_b[b] = L - 1;
+        }
+        if (!seqs.empty()) {
+          if ((rc = run_chunk_seqs(c, c->slots[cur], seqs, [&](const ChunkRow *, int) { return 0; }))) return rc;
+          HIPCHK(c, hipMemcpyAsync(c->d_plen_p, plen_b.data(), (size_t)B * 4, hipMemcpyHostToDevice, st));
+          launch_kv_replicate(c->kv, c->d_plen_p, B, G, st);
+        }
+        for (int b : admitted) {
+          int pp = group_prompt[b], L = prompt_lens[pp];
+          for (int g = 0; g < G; ++g) {
+            int r = b * G + g, n = pp * G + g;
+            tok[r] = prompt_tokens[(int64_t)pp * prompt_stride + L - 1];
+            pos[r] = L - 1; act[r] = 1; pslot[r] = b * G; ptiles[r] = share_prefix ? (L - 1) / 32 : 0;
+            plen[r] = L; gen[r] = 0; stream[r] = n;
+            lim[r] = o.stop_lens ? std::max(1, std::min(max_new, o.stop_lens[n])) : max_new;
+          }
+          int64_t r0 = (int64_t)b * G * max_new, cells = (int64_t)G * max_new;
+          launch_fill_i32(d_out_tok + r0, -1, cells, st);
+          launch_fill_i32((int32_t *)(d_out_lp + r0), 0, cells, st);
+          launch_fill_i32((int32_t *)(d_out_ver + r0), -1, cells * 2, st);
+          if (d_forced)
+            HIPCHK(c, hipMemcpyAsync(d_forced + r0, o.forced_tokens + (int64_t)pp * G * max_new, cells * 4, hipMemcpyHostToDevice, st));
+        }
+        if ((rc = upload_rows())) return rc;   // also restores the rows the prefill pass used as its own
+        HIPCHK(c, hipStreamSynchronize(st));
+        admit_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - a0).count();
+      }
+      // the next event: with stop lengths only, the step at which the first group runs out is known
+      until_check = 8;
+      if (o.eos_id < 0) {
+        int soonest = INT32_MAX;
+        for (int b = 0; b < B; ++b) {
+          if (group_prompt[b] < 0) continue;
+          int longest = 0;
+          for (int g = 0; g < G; ++g) if (act[b * G + g]) longest = std::max(longest, lim[b * G + g] - gen[b * G + g]);
+          soonest = std::min(soonest, std::max(longest, 1));
+        }
+        until_check = soonest;
+      }
+    }
+    {   // a snapshot that has been staged meanwhile is switched in between two steps
+      std::unique_lock<std::mutex> lk(c->mu);
+      if (c->staged >= 0) {
+        auto w0 = std::chrono::steady_clock::now();
+        cur = c->staged; c->active = cur; c->staged = -1;
+        c->st.active_version = c->slots[cur].version; c->st.staged_version = -1;
+        lk.unlock();
+        HIPCHK(c, hipStreamWaitEvent(st, c->staged_ev, 0));
+        swap_wait += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - w0).count();
+        have_graph = false;
+      }
+    }
+    if (use_graph) {
+      if (!have_graph) {
+        if ((rc = capture_step(c, c->slots[cur], R, max_new, temperature, seed, unfused, d_forced, o.eos_id, o.top_p, 1))) return rc;
+        have_graph = true;
+      }
+      HIPCHK(c, hipGraphLaunch(c->graph, st));
+    } else {
+      forward_layers(c, c->slots[cur], R, splitk);
+      sample_rows(c, c->slots[cur], R, temperature, seed, unfused, nullptr, o.top_p);
+      launch_bookkeeping(R, max_new, 1, c->d_step, c->d_samp_tok, c->d_samp_lp, d_forced, c->d_limit, o.eos_id, c->slots[cur].version,
+                         c->d_prompt_len_seq, c->d_gen_len, c->rows, d_out_tok, d_out_lp, d_out_ver, c->d_n_active, st);
+    }
+    ++decode_steps;
+    --until_check;
+  }
+  HIPCHK(c, hipStreamSynchronize(st));
+  auto t1 = std::chrono::steady_clock::now();
+  c->st.decode_steps = decode_steps;
+  c->st.prefill_ms = (float)admit_ms;
+  c->st.total_ms = std::chrono::duration<float, std::milli>(t1 - t0).count();
+  c->st.decode_ms = c->st.total_ms - (float)admit_ms;
+  c->st.swap_wait_ms = (float)swap_wait;
   return ECHO_OK;
 }
 

@@ -53,13 +53,21 @@ struct KvGeom {          // KV cache, plain form: [slot][layer][K|V][kv_head][ma
 
 // ---- shared small kernels (both paths) -----------------------------------------------------------
 void launch_rope_table(float *cs /*[M][hd/2][2]*/, const int32_t *pos, int M, int hd, float base, hipStream_t st);
-void launch_bookkeeping(int N, int max_new, int32_t *d_step, const int32_t *samp_tok, const float *samp_lp,
+void launch_bookkeeping(int N, int max_new, int per_row /*1: a row's step is its gen_len*/, int32_t *d_step, const int32_t *samp_tok, const float *samp_lp,
                         const int32_t *forced, const int32_t *limit, int eos, int64_t version,
                         const int32_t *prompt_len, int32_t *gen_len, RowState rows, int32_t *out_tok,
                         float *out_lp, int64_t *out_ver, int32_t *n_active, hipStream_t st);
 void launch_kv_replicate(KvGeom kv, const int32_t *prompt_len /*[P]*/, int P, int G, hipStream_t st);
 void launch_draw_bits(uint32_t *out, uint64_t seed, uint32_t n, uint32_t s, uint32_t i0, int count, hipStream_t st);
 void launch_fill_i32(int32_t *p, int32_t v, int64_t n, hipStream_t st);
+// Which draw of the generator a row takes (the step and stream words of its counter).  In a rollout whose sequences
+// all start together every row sits at the step *d_step and row m is stream m; with row_step / row_stream set the
+// two are read per row (sequences that join a running batch).
+struct DrawIds {
+  const int32_t *d_step;      // device scalar
+  const int32_t *row_step;    // device [rows], or null
+  const int32_t *row_stream;  // device [rows], or null
+};
 // Learner-side tensors of n_seqs records in groups of G (n_seqs a multiple of G, G >= 2): adv[n] from rewards[n],
 // mask[n][t] and adv_tok[n][t] (nullable) from tokens[n][t], lens[n].  tokens, adv_tok 16-byte aligned, mask 4-byte.
 void launch_grpo_tensors(uint8_t *mask, float *adv, float *adv_tok, const int32_t *tokens, const int32_t *lens, const float *rewards,
@@ -80,7 +88,7 @@ void dbg_attention(float *out /*[M][Hq*hd]*/, const float *qkv, RowState rows, K
 void dbg_swiglu(float *ff /*[M][F]*/, const float *gu /*[M][2F] = gate | up*/, int M, int F, hipStream_t st);
 // Unfused sampler over materialised logits [M][ld]: Gumbel-max token and its log-softmax, in fp32.
 void dbg_sample(int32_t *tok, float *lp, const float *logits, int64_t ld, int M, int V, float temperature,
-                uint64_t seed, const int32_t *d_step, const int32_t *row_active, hipStream_t st);
+                uint64_t seed, DrawIds ids, const int32_t *row_active, hipStream_t st);
 // log softmax(logits/T)[target[m]] per row (teacher-forced scoring).
 void dbg_target_logprob(float *lp, const float *logits, int64_t ld, int M, int V, float temperature,
                         const int32_t *target, hipStream_t st);
@@ -125,7 +133,7 @@ void fast_attention_prefill(void *Xp_out, const void *q_h16, const PrefillBlock 
 // lm_head with the sampler fused into the epilogue (partials per workgroup) + the combine kernel.  With `target` set
 // (scoring) only target_lp is meaningful: no noise is drawn and tok / lp describe the plain argmax.
 void fast_lmhead_sample(int32_t *tok, float *lp, float *target_lp, const void *Xp, const void *Wp, int Mp, int M,
-                        int V, int Np, int Kp, float temperature, uint64_t seed, const int32_t *d_step,
+                        int V, int Np, int Kp, float temperature, uint64_t seed, DrawIds ids,
                         const int32_t *row_active, const int32_t *target, float *partials, hipStream_t st);
 size_t fast_lmhead_partial_floats(int Np, int Mp);
 // Nucleus sampling over fp32 logits [M][ld] (top_p < 1): finds every row's cut and leaves the sampler's partials of
@@ -134,7 +142,7 @@ size_t fast_lmhead_partial_floats(int Np, int Mp);
 constexpr int TOPP_CHUNKS_PER_ROW = 16;
 size_t fast_topp_scratch_floats(int Mp);
 void fast_topp_cut_and_draw(float *scratch, const float *logits, int64_t ld, int M, int Mp, int V, float temperature, float top_p,
-                            uint64_t seed, const int32_t *d_step, const int32_t *row_active, hipStream_t st);
+                            uint64_t seed, DrawIds ids, const int32_t *row_active, hipStream_t st);
 void fast_sample_combine(int32_t *tok, float *lp, const float *part, int n_parts, int M, int Mp, const int32_t *row_active, hipStream_t st);
 // lm_head writing fp32 logits [Mp][ld] row-major (debug / unfused sampler).
 void fast_lmhead_logits(float *logits, int64_t ld, const void *Xp, const void *Wp, int Mp, int Np, int Kp, int V,

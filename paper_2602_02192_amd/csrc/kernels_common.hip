@@ -25,17 +25,19 @@ void launch_rope_table(float *cs, const int32_t *pos, int M, int hd, float base,
 
 // One block.  Records the token sampled at generation step *d_step for every active sequence, chooses the
 // token fed back (forced or sampled), applies the stop rules and prepares the rows of the next decode pass.
-__global__ void bookkeeping_kernel(int N, int max_new, int32_t *d_step, const int32_t *samp_tok, const float *samp_lp,
+// per_row: the sequences of the batch did not start together, a row's generation step is its gen_len.
+__global__ void bookkeeping_kernel(int N, int max_new, int per_row, int32_t *d_step, const int32_t *samp_tok, const float *samp_lp,
                                    const int32_t *forced, const int32_t *limit, int eos, int64_t version,
                                    const int32_t *prompt_len, int32_t *gen_len, RowState rows, int32_t *out_tok,
                                    float *out_lp, int64_t *out_ver, int32_t *n_active) {
   __shared__ int cnt;
   if (threadIdx.x == 0) cnt = 0;
   __syncthreads();
-  int s = *d_step;
+  const int s0 = *d_step;
   int mine = 0;
   for (int n = threadIdx.x; n < N; n += blockDim.x) {
     if (!rows.active[n]) continue;
+    const int s = per_row ? gen_len[n] : s0;
     int tok = samp_tok[n];
     int64_t o = (int64_t)n * max_new + s;
     out_tok[o] = tok;
@@ -52,14 +54,14 @@ __global__ void bookkeeping_kernel(int N, int max_new, int32_t *d_step, const in
   }
   if (mine) atomicAdd(&cnt, mine);
   __syncthreads();
-  if (threadIdx.x == 0) { *d_step = s + 1; *n_active = cnt; }
+  if (threadIdx.x == 0) { *d_step = s0 + 1; *n_active = cnt; }
 }
 
-void launch_bookkeeping(int N, int max_new, int32_t *d_step, const int32_t *samp_tok, const float *samp_lp,
+void launch_bookkeeping(int N, int max_new, int per_row, int32_t *d_step, const int32_t *samp_tok, const float *samp_lp,
                         const int32_t *forced, const int32_t *limit, int eos, int64_t version,
                         const int32_t *prompt_len, int32_t *gen_len, RowState rows, int32_t *out_tok, float *out_lp,
                         int64_t *out_ver, int32_t *n_active, hipStream_t st) {
-  hipLaunchKernelGGL(bookkeeping_kernel, dim3(1), dim3(256), 0, st, N, max_new, d_step, samp_tok, samp_lp, forced,
+  hipLaunchKernelGGL(bookkeeping_kernel, dim3(1), dim3(256), 0, st, N, max_new, per_row, d_step, samp_tok, samp_lp, forced,
                      limit, eos, version, prompt_len, gen_len, rows, out_tok, out_lp, out_ver, n_active);
 }
 

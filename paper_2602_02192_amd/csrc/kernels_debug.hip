@@ -162,15 +162,15 @@ void dbg_swiglu(float *ff, const float *gu, int M, int F, hipStream_t st) {
 
 // One block of 256 threads per row: Gumbel-max token and log softmax(z)[token] from materialised logits.
 __global__ void dbg_sample_kernel(int32_t *tok, float *lp, const float *logits, int64_t ld, int V, float temperature,
-                                  uint64_t seed, const int32_t *d_step, const int32_t *row_active) {
+                                  uint64_t seed, DrawIds ids, const int32_t *row_active) {
   __shared__ SampleAcc sh[4];
   int m = blockIdx.x;
   if (row_active && !row_active[m]) return;
-  uint32_t s = (uint32_t)*d_step;
+  const uint32_t s = draw_step(ids, m), stream = draw_stream(ids, m);
   SampleAcc a = sample_acc_init();
   const float *lg = logits + (int64_t)m * ld;
   for (int i4 = threadIdx.x; i4 * 4 < V; i4 += blockDim.x) {
-    u32x4 r = draw4(seed, (uint32_t)m, s, (uint32_t)i4);
+    u32x4 r = draw4(seed, stream, s, (uint32_t)i4);
     uint32_t w[4] = {r.x, r.y, r.z, r.w};
     for (int e = 0; e < 4; ++e) {
       int i = i4 * 4 + e;
@@ -190,8 +190,8 @@ __global__ void dbg_sample_kernel(int32_t *tok, float *lp, const float *logits, 
 }
 
 void dbg_sample(int32_t *tok, float *lp, const float *logits, int64_t ld, int M, int V, float temperature, uint64_t seed,
-                const int32_t *d_step, const int32_t *row_active, hipStream_t st) {
-  hipLaunchKernelGGL(dbg_sample_kernel, dim3(M), dim3(256), 0, st, tok, lp, logits, ld, V, temperature, seed, d_step,
+                DrawIds ids, const int32_t *row_active, hipStream_t st) {
+  hipLaunchKernelGGL(dbg_sample_kernel, dim3(M), dim3(256), 0, st, tok, lp, logits, ld, V, temperature, seed, ids,
                      row_active);
 }
 

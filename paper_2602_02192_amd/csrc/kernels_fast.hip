@@ -291,17 +291,17 @@ __global__ __launch_bounds__(TOPP_THREADS) void topp_cut_kernel(uint32_t *cut_ke
 
 // grid (TOPP_CHUNKS, M), block 256: slice c of row m.
 __global__ void topp_draw_kernel(float *part, int Mp, const uint32_t *cut_key, const int32_t *cut_last, const float *logits, int64_t ld,
-                                 int V, float temperature, uint64_t seed, const int32_t *d_step, const int32_t *row_active) {
+                                 int V, float temperature, uint64_t seed, DrawIds ids, const int32_t *row_active) {
   __shared__ SampleAcc sh[4];
   const int c = blockIdx.x, m = blockIdx.y;
   if (row_active && !row_active[m]) return;
-  const uint32_t step = (uint32_t)*d_step, cut = cut_key[m];
+  const uint32_t step = draw_step(ids, m), stream = draw_stream(ids, m), cut = cut_key[m];
   const int last = cut_last[m];
   const int v4 = (V + 3) / 4, per = (v4 + TOPP_CHUNKS - 1) / TOPP_CHUNKS, b4 = c * per, e4 = min(v4, b4 + per);
   const float *lg = logits + (int64_t)m * ld;
   SampleAcc a = sample_acc_init();
   for (int i4 = b4 + threadIdx.x; i4 < e4; i4 += blockDim.x) {
-    u32x4 r = draw4(seed, (uint32_t)m, step, (uint32_t)i4);
+    u32x4 r = draw4(seed, stream, step, (uint32_t)i4);
     uint32_t w[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -333,13 +333,13 @@ __global__ void topp_draw_kernel(float *part, int Mp, const uint32_t *cut_key, c
 size_t fast_topp_scratch_floats(int Mp) { return (size_t)5 * TOPP_CHUNKS * Mp + 2 * (size_t)Mp; }
 
 void fast_topp_cut_and_draw(float *scratch, const float *logits, int64_t ld, int M, int Mp, int V, float temperature, float top_p,
-                            uint64_t seed, const int32_t *d_step, const int32_t *row_active, hipStream_t st) {
+                            uint64_t seed, DrawIds ids, const int32_t *row_active, hipStream_t st) {
   if (M <= 0) return;
   uint32_t *cut_key = (uint32_t *)(scratch + (size_t)5 * TOPP_CHUNKS * Mp);
   int32_t *cut_last = (int32_t *)cut_key + Mp;
   hipLaunchKernelGGL(topp_cut_kernel, dim3(M), dim3(TOPP_THREADS), 0, st, cut_key, cut_last, logits, ld, V, temperature, top_p, row_active);
   hipLaunchKernelGGL(topp_draw_kernel, dim3(TOPP_CHUNKS, M), dim3(256), 0, st, scratch, Mp, cut_key, cut_last, logits, ld, V, temperature,
-                     seed, d_step, row_active);
+                     seed, ids, row_active);
 }
 
 }  // namespace echo

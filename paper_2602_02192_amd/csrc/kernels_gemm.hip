@@ -769,14 +769,13 @@ template <int MB> struct LmLds {   // epilogue of the 256-row kernel: accumulato
 template <int MB, int NSTAGE, bool LOGITS>
 __global__ __launch_bounds__(256) void lmhead_kernel(const u32x4v *__restrict__ Xp, const h16x8 *__restrict__ Wp, int Mp,
                                                      int Np, int Kp, int V, float temperature, uint64_t seed,
-                                                     const int32_t *d_step, const int32_t *target, float *target_z,
+                                                     DrawIds ids, const int32_t *target, float *target_z,
                                                      float *part, int n_wg, float *logits, int64_t ld) {
   extern __shared__ __attribute__((aligned(16))) char lds_raw[];
   using L = GemmLds<MB, LM_WN>;
   int w = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
   const int nblocks = Np >> 5, mrow0 = blockIdx.z * 32 * MB;
   const int nb_own = blockIdx.x * LM_WN + w, nb = min(nb_own, nblocks - 1);
-  uint32_t step = LOGITS ? 0u : (uint32_t)*d_step;
   f32x16 acc[MB];
   gemm_lds_mainloop<MB, LM_WN, NSTAGE>(acc, lds_raw, Xp, Wp, Mp, Np, Kp, nb, 0, (Kp >> 4) / L::KC, mrow0);
   // One logit: temperature, running (max, sum-exp), perturbed-score argmax, the target's z.
@@ -794,12 +793,12 @@ __global__ __launch_bounds__(256) void lmhead_kernel(const u32x4v *__restrict__ 
       if (v == tgt) target_z[m] = z;
     }
   };
-  auto fold4 = [&](SampleAcc &sa, f32x4 a, int v0, int m, int tgt) {
+  auto fold4 = [&](SampleAcc &sa, f32x4 a, int v0, int m, int tgt, uint32_t stream, uint32_t step) {
     if (target) {   // scoring: only the target's log-prob is wanted, so no noise is drawn (the token output is the plain argmax)
       fold_plain(sa, a[0], v0, m, tgt); fold_plain(sa, a[1], v0 + 1, m, tgt);
       fold_plain(sa, a[2], v0 + 2, m, tgt); fold_plain(sa, a[3], v0 + 3, m, tgt);
     } else {
-      u32x4 r = draw4(seed, (uint32_t)m, step, (uint32_t)(v0 >> 2));
+      u32x4 r = draw4(seed, stream, step, (uint32_t)(v0 >> 2));
       fold(sa, a[0], r.x, v0, m, tgt); fold(sa, a[1], r.y, v0 + 1, m, tgt);
       fold(sa, a[2], r.z, v0 + 2, m, tgt); fold(sa, a[3], r.w, v0 + 3, m, tgt);
     }
@@ -842,8 +841,9 @@ __global__ __launch_bounds__(256) void lmhead_kernel(const u32x4v *__restrict__ 
       SampleAcc sa = sample_acc_init();
       if (nb_own < nblocks) {
         int m = mrow0 + j * 32 + col, tgt = target ? target[m] : -1;
+        const uint32_t stream = draw_stream(ids, m), step = target ? 0u : draw_step(ids, m);
 #pragma unroll
-        for (int g = 0; g < 4; ++g) fold4(sa, dump[(j * 4 + g) * 64], nb * 32 + 8 * g + 4 * half, m, tgt);
+        for (int g = 0; g < 4; ++g) fold4(sa, dump[(j * 4 + g) * 64], nb * 32 + 8 * g + 4 * half, m, tgt, stream, step);
       }
       SampleAcc o = sample_acc_shfl_xor(sa, 32);
       sample_acc_merge(sa, o);
@@ -866,9 +866,11 @@ __global__ __launch_bounds__(256) void lmhead_kernel(const u32x4v *__restrict__ 
 #pragma unroll
       for (int j = 0; j < MB; ++j) {
         int m = mrow0 + j * 32 + col, tgt = target ? target[m] : -1;
+        const uint32_t stream = draw_stream(ids, m), step = target ? 0u : draw_step(ids, m);
 #pragma unroll
         for (int g = 0; g < 4; ++g)
-          fold4(sa[j], f32x4{acc[j][4 * g], acc[j][4 * g + 1], acc[j][4 * g + 2], acc[j][4 * g + 3]}, nb * 32 + 8 * g + 4 * half, m, tgt);
+          fold4(sa[j], f32x4{acc[j][4 * g], acc[j][4 * g + 1], acc[j][4 * g + 2], acc[j][4 * g + 3]}, nb * 32 + 8 * g + 4 * half, m, tgt,
+                stream, step);
       }
     }
     // lanes l and l^32 hold the same batch row; then fold the four wavefronts in wavefront order
@@ -920,7 +922,7 @@ size_t fast_lmhead_partial_floats(int Np, int Mp) { return (size_t)5 * lm_wgs(Np
 
 template <int MB, int NSTAGE, bool LOGITS>
 static void lmhead_launch(const void *Xp, const void *Wp, int Mp, int Np, int Kp, int V, float temperature, uint64_t seed,
-                          const int32_t *d_step, const int32_t *target, float *target_z, float *part, float *logits, int64_t ld,
+                          DrawIds ids, const int32_t *target, float *target_z, float *part, float *logits, int64_t ld,
                           hipStream_t st) {
   using L = GemmLds<MB, LM_WN>;
   constexpr int SH = (MB >= 8 && !LOGITS) ? LmLds<MB>::BYTES : 3 * MB * 32 * (int)sizeof(SampleAcc);
@@ -933,15 +935,15 @@ static void lmhead_launch(const void *Xp, const void *Wp, int Mp, int Np, int Kp
   int n_wg = lm_wgs(Np);
   dim3 grid(n_wg, 1, Mp / (32 * MB)), block(256);
   hipLaunchKernelGGL((lmhead_kernel<MB, NSTAGE, LOGITS>), grid, block, BYTES, st, (const u32x4v *)Xp, (const h16x8 *)Wp, Mp, Np, Kp, V,
-                     temperature, seed, d_step, target, target_z, part, n_wg, logits, ld);
+                     temperature, seed, ids, target, target_z, part, n_wg, logits, ld);
 }
 
 template <bool LOGITS>
 static void lmhead_dispatch(const void *Xp, const void *Wp, int Mp, int Np, int Kp, int V, float temperature, uint64_t seed,
-                            const int32_t *d_step, const int32_t *target, float *target_z, float *part, float *logits,
+                            DrawIds ids, const int32_t *target, float *target_z, float *part, float *logits,
                             int64_t ld, hipStream_t st) {
   int mbt = Mp / 32;
-#define LM_ARGS Xp, Wp, Mp, Np, Kp, V, temperature, seed, d_step, target, target_z, part, logits, ld, st
+#define LM_ARGS Xp, Wp, Mp, Np, Kp, V, temperature, seed, ids, target, target_z, part, logits, ld, st
   if (mbt >= 8) lmhead_launch<8, 2, LOGITS>(LM_ARGS);
   else if (mbt == 4) lmhead_launch<4, 3, LOGITS>(LM_ARGS);
   else if (mbt == 2) lmhead_launch<2, 3, LOGITS>(LM_ARGS);
@@ -950,11 +952,11 @@ static void lmhead_dispatch(const void *Xp, const void *Wp, int Mp, int Np, int 
 }
 
 void fast_lmhead_sample(int32_t *tok, float *lp, float *target_lp, const void *Xp, const void *Wp, int Mp, int M, int V,
-                        int Np, int Kp, float temperature, uint64_t seed, const int32_t *d_step, const int32_t *row_active,
+                        int Np, int Kp, float temperature, uint64_t seed, DrawIds ids, const int32_t *row_active,
                         const int32_t *target, float *partials, hipStream_t st) {
   int n_wg = lm_wgs(Np);
   float *target_z = partials + (size_t)5 * n_wg * Mp;
-  lmhead_dispatch<false>(Xp, Wp, Mp, Np, Kp, V, temperature, seed, d_step, target, target_z, partials, nullptr, 0, st);
+  lmhead_dispatch<false>(Xp, Wp, Mp, Np, Kp, V, temperature, seed, ids, target, target_z, partials, nullptr, 0, st);
   hipLaunchKernelGGL(sample_combine_kernel, dim3(M), dim3(256), 0, st, tok, lp, target_lp, partials, n_wg, Mp, row_active,
                      target, target_z);
 }
@@ -966,7 +968,7 @@ void fast_sample_combine(int32_t *tok, float *lp, const float *part, int n_parts
 
 void fast_lmhead_logits(float *logits, int64_t ld, const void *Xp, const void *Wp, int Mp, int Np, int Kp, int V,
                         hipStream_t st) {
-  lmhead_dispatch<true>(Xp, Wp, Mp, Np, Kp, V, 1.0f, 0, nullptr, nullptr, nullptr, nullptr, logits, ld, st);
+  lmhead_dispatch<true>(Xp, Wp, Mp, Np, Kp, V, 1.0f, 0, DrawIds{nullptr, nullptr, nullptr}, nullptr, nullptr, nullptr, logits, ld, st);
 }
 
 }  // namespace echo

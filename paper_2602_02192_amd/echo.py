@@ -49,7 +49,7 @@ class Stats(C.Structure):
 
 
 EXPORTS = ["echo_arena_bytes", "echo_blob_bytes", "echo_init", "echo_load_policy", "echo_load_policy_begin",
-           "echo_load_policy_chunk", "echo_load_policy_commit", "echo_load_policy_abort", "echo_rollout",
+           "echo_load_policy_chunk", "echo_load_policy_commit", "echo_load_policy_abort", "echo_rollout", "echo_rollout_continuous",
            "echo_logprobs", "echo_grpo_tensors", "echo_debug_draw_bits", "echo_stats", "echo_last_error", "echo_destroy"]
 
 lib.echo_arena_bytes.restype = C.c_size_t
@@ -66,6 +66,7 @@ lib.echo_load_policy_abort.argtypes = [C.c_void_p]
 lib.echo_rollout.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                              C.c_float, C.c_uint64, C.POINTER(RolloutOpts), C.c_void_p, C.c_void_p, C.c_void_p,
                              C.c_void_p]
+lib.echo_rollout_continuous.argtypes = lib.echo_rollout.argtypes
 lib.echo_logprobs.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_float, C.c_void_p]
 lib.echo_grpo_tensors.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                   C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -193,7 +194,7 @@ class Context:
     def rollout(self, prompts, prompt_lens, G: int, max_new: int, temperature: float, seed: int,
                 stop_lens=None, eos_id: int = -1, top_p: float = 1.0, swap_at_step: Sequence[int] = (),
                 swap_timeout_ms: int = 0, forced=None, want_logits: bool = False, unfused_sampler: bool = False,
-                no_graph: bool = False, time_kernels: bool = False) -> dict:
+                no_graph: bool = False, time_kernels: bool = False, continuous: bool = False) -> dict:
         prompts = np.ascontiguousarray(prompts, np.int32)
         prompt_lens = np.ascontiguousarray(prompt_lens, np.int32)
         P = prompts.shape[0]
@@ -225,8 +226,9 @@ class Context:
         lps = np.empty((N, max_new), np.float32)
         lens = np.empty(N, np.int32)
         vers = np.empty((N, max_new), np.int64)
-        self._chk(lib.echo_rollout(self.h, _ptr(prompts), prompts.shape[1], _ptr(prompt_lens), P, G, max_new,
-                                   temperature, seed, C.byref(o), _ptr(toks), _ptr(lps), _ptr(lens), _ptr(vers)))
+        fn = lib.echo_rollout_continuous if continuous else lib.echo_rollout
+        self._chk(fn(self.h, _ptr(prompts), prompts.shape[1], _ptr(prompt_lens), P, G, max_new,
+                     temperature, seed, C.byref(o), _ptr(toks), _ptr(lps), _ptr(lens), _ptr(vers)))
         return dict(tokens=toks, logprobs=lps, lens=lens, versions=vers, logits=logits)
 
     def logprobs(self, tokens, lens, temperature: float = 1.0) -> np.ndarray:
