@@ -49,16 +49,25 @@ WORKLOADS = {
     "dense4b-64x512+1024-top_p0.95": dict(shape="DENSE_4B", P=8, G=8, plen=512, max_new=1024, top_p=0.95),
     "dense4b-kvheavy-256x1024+4096": dict(shape="DENSE_4B", P=32, G=8, plen=1024, max_new=4096, stop=(512, 4096)),
     "dense8b-128x512+2048-swap256": dict(shape="DENSE_8B", P=16, G=8, plen=512, max_new=2048, swap_every=256),
+    # config 3's lengths with four times the prompts than the cache holds at once: finished groups are replaced by
+    # waiting prompts (echo_rollout_continuous), 256 sequences decode together throughout
+    "dense4b-kvheavy-512x1024+4096-continuous256": dict(shape="DENSE_4B", P=64, G=8, plen=1024, max_new=4096, stop=(512, 4096),
+                                                        slots=256, continuous=True),
+    # eight cache-fuls of shorter sequences, and one cache-ful of the same length mix through the ordinary rollout
+    "dense4b-2048x512+1024-continuous256": dict(shape="DENSE_4B", P=256, G=8, plen=512, max_new=1024, stop=(128, 1024),
+                                                slots=256, continuous=True),
+    "dense4b-256x512+1024-ragged": dict(shape="DENSE_4B", P=32, G=8, plen=512, max_new=1024, stop=(128, 1024)),
     "dense32b-64x1024+4096-score": dict(shape="DENSE_32B", P=8, G=8, plen=1024, max_new=4096, score=True),
 }
 
 
-def algorithmic_bytes(shape, gen_lens, prompt_len, group=1):
+def algorithmic_bytes(shape, gen_lens, prompt_len, group=1, first_step=1):
     """HBM bytes the decode steps must move: all decode-read weights once per step, the K/V of every active
     sequence once per step, and the new K/V written.  gen_lens: tokens generated per sequence (prompt-major,
     `group` sequences per prompt).  The whole 32-key tiles of a prompt are read from one copy per group by the
     decode attention kernel, so they count once per group that still has an active sequence; group=1 gives the
-    per-sequence figure (every sequence reads its own copy of everything)."""
+    per-sequence figure (every sequence reads its own copy of everything).  first_step=0: the first token, too, comes
+    out of a decode step (continuous rollouts); the K/V terms depend on each sequence's own steps only, not on when it ran."""
     e = 2 if shape.dtype == "bf16" else 4
     hd, H = shape.head_dim, shape.hidden
     per_layer = H * (shape.n_q_heads + 2 * shape.n_kv_heads) * hd + shape.n_q_heads * hd * H + 3 * H * shape.ffn
@@ -68,9 +77,9 @@ def algorithmic_bytes(shape, gen_lens, prompt_len, group=1):
     steps = int(gen.max())
     shared = (prompt_len // 32) * 32 if group > 1 else 0
     group_len = gen.reshape(-1, group).max(axis=1)
-    s_idx = np.arange(1, steps, dtype=np.int64)
-    active = np.array([(gen > s).sum() for s in range(1, steps)], np.int64)   # decode pass s serves sequences with gen > s
-    groups = np.array([(group_len > s).sum() for s in range(1, steps)], np.int64)
+    s_idx = np.arange(first_step, steps, dtype=np.int64)
+    active = np.array([(gen > s).sum() for s in range(first_step, steps)], np.int64)   # decode pass s serves sequences with gen > s
+    groups = np.array([(group_len > s).sum() for s in range(first_step, steps)], np.int64)
     kv_read = groups * shared + active * (prompt_len - shared + s_idx)
     total = int((w_dec + kv_read * kvb + active * kvb).sum())
     return total, w_dec, kvb
@@ -142,7 +151,10 @@ def main():
     prompts, lens = synth.make_prompts(shape.vocab, P, plen, seed=1)
     stop = synth.make_stop_lens(N, wl["stop"][0], wl["stop"][1], seed=3) if wl.get("stop") else None
     swaps = list(range(swap_every, max_new, swap_every)) if swap_every else []
-    ctx = echo.Context(echo.desc_from_shape(shape, N, plen + max_new + a.ctx_pad, n_weight_slots=2 if swap_every else 1))
+    continuous = bool(wl.get("continuous"))
+    if continuous:
+        a.no_kernel_timing = True    # the continuous entry point takes no per-kernel event timing
+    ctx = echo.Context(echo.desc_from_shape(shape, wl.get("slots", N), plen + max_new + a.ctx_pad, n_weight_slots=2 if swap_every else 1))
     t0 = time.perf_counter()
     ctx.load_policy(0, blob)
     load_s = time.perf_counter() - t0
@@ -158,7 +170,7 @@ def main():
         sets) as soon as the previous one has been switched in, as a worker's receiver thread would."""
         kw.setdefault("top_p", wl.get("top_p", 1.0))
         if not swaps:
-            return ctx.rollout(prompts, lens, G, max_new, 1.0, seed, stop_lens=stop, no_graph=a.no_graph, **kw)
+            return ctx.rollout(prompts, lens, G, max_new, 1.0, seed, stop_lens=stop, no_graph=a.no_graph, continuous=continuous, **kw)
         import threading
         done = threading.Event()
 
@@ -191,7 +203,7 @@ def main():
         rollout(2)
         progress("warm-up rollout done")
     torch.cuda.synchronize()
-    times, toks, decode_ms, prefill_ms, swap_wait_ms = [], 0, [], [], []
+    times, toks, decode_ms, prefill_ms, swap_wait_ms, steps_run = [], 0, [], [], [], []
     t_all = time.perf_counter()
     for k in range(a.steps):
         t0 = time.perf_counter()
@@ -202,6 +214,7 @@ def main():
         decode_ms.append(st.decode_ms)
         prefill_ms.append(st.prefill_ms)
         swap_wait_ms.append(st.swap_wait_ms)
+        steps_run.append(st.decode_steps)
         progress(f"timed rollout {k + 1} of {a.steps} done")
     torch.cuda.synchronize()
     total_s = time.perf_counter() - t_all
@@ -212,6 +225,13 @@ def main():
     bytes_per_seq = algorithmic_bytes(shape, out["lens"], plen, 1)[0]   # every sequence reading a prompt copy of its own
     step_frac_per_seq = bytes_per_seq / (np.mean(decode_ms) * 1e-3) / (HBM_PEAK_GBS * 1e9)
     n_decode_steps = max(1, int(out["lens"].max()) - 1)
+    if continuous:     # weights once per step actually run; every token, the first included, comes out of a decode step
+        n_decode_steps = int(np.mean(steps_run))
+        longest = int(out["lens"].max())
+        bytes_decode = algorithmic_bytes(shape, out["lens"], plen, G, first_step=0)[0] + w_dec * (n_decode_steps - longest)
+        bytes_per_seq = algorithmic_bytes(shape, out["lens"], plen, 1, first_step=0)[0] + w_dec * (n_decode_steps - longest)
+        step_frac = bytes_decode / (np.mean(decode_ms) * 1e-3) / (HBM_PEAK_GBS * 1e9)
+        step_frac_per_seq = bytes_per_seq / (np.mean(decode_ms) * 1e-3) / (HBM_PEAK_GBS * 1e9)
 
     score = None
     if wl.get("score"):       # teacher-forced log-probs of every generated string (prompt + response) under the active snapshot
@@ -267,7 +287,8 @@ def main():
         "dtype": "f16 MFMA operands, f32 accumulate (bf16 weights)" if shape.dtype == "bf16" else "f32", "data": "synthetic (random N(0,0.02) weights, uniform random prompt tokens)",
         "config": {"workload": a.workload, "model": name, "sequences": N, "prompts": P, "group": G,
                    "prompt_len": plen, "max_new": max_new, "temperature": 1.0, "top_p": wl.get("top_p", 1.0),
-                   "stop_lens": list(wl["stop"]) if wl.get("stop") else None},
+                   "stop_lens": list(wl["stop"]) if wl.get("stop") else None,
+                   "sequences_decoding_together": wl.get("slots", N), "continuous": continuous},
         "decode_step": {"mean_ms": float(np.mean(decode_ms)) / n_decode_steps,
                         "hbm_frac_of_8TBps": step_frac, "algorithmic_bytes_per_rollout": bytes_decode,
                         "hbm_frac_if_every_sequence_read_its_own_prompt_copy": step_frac_per_seq,

@@ -1001,10 +1001,12 @@ int echo_rollout_continuous(echo_ctx *c, const int32_t *prompt_tokens, int32_t p
   const bool use_graph = !o.no_graph;
   const bool share_prefix = p.fast && !env_flag("ECHO_NO_PREFIX_SHARING") && !env_flag("ECHO_ATTN_SIMPLE");
   const bool splitk = !env_flag("ECHO_ATTN_SIMPLE");
-  const int B = std::min(P, c->d.max_seqs / G), R = B * G;   // group slots and rows of the batch
+  const int R = std::min(N, c->d.max_seqs);   // rows of the batch = cache slots in use
   // host mirrors of the per-row state; token, pos, active and gen are read back at every check
   std::vector<int32_t> tok(R, 0), pos(R, 0), act(R, 0), slot(R), pslot(R, 0), ptiles(R, 0), plen(R, 1), gen(R, 0), lim(R, 1), stream(R, 0);
-  std::vector<int> group_prompt(B, -1);
+  std::vector<int> row_seq(R, -1);      // the sequence a row is generating, -1: none
+  std::vector<int> row_holds(R, -1);    // the prompt whose shared key tiles live in this row's cache slot, -1: none
+  std::vector<int> group_left(P, 0);    // sequences of a prompt that have not ended yet
   for (int r = 0; r < R; ++r) slot[r] = r;
   int32_t *d_forced = o.forced_tokens ? at<int32_t>(c, p.o_forced) : nullptr;
   int32_t *d_out_tok = at<int32_t>(c, p.o_out_tok);
@@ -1017,13 +1019,17 @@ int echo_rollout_continuous(echo_ctx *c, const int32_t *prompt_tokens, int32_t p
     for (auto &x : cp) HIPCHK(c, hipMemcpyAsync(x.dst, x.src->data(), (size_t)R * 4, hipMemcpyHostToDevice, st));
     return 0;
   };
+  auto limit_of = [&](int n) { return o.stop_lens ? std::max(1, std::min(max_new, o.stop_lens[n])) : max_new; };
   launch_fill_i32(c->d_step, 0, 1, st);
   c->ids = DrawIds{c->d_step, c->d_gen_len, c->d_stream};
 
-  int cur = c->active, next_prompt = 0, done_prompts = 0, decode_steps = 0, until_check = 0;
+  int cur = c->active, next_prompt = 0, done_seqs = 0, decode_steps = 0, until_check = 0;
   bool have_graph = false, first = true;
   double admit_ms = 0, swap_wait = 0;
   int rc;
+  std::vector<int> free_rows;
+  std::vector<int32_t> quads;
+  const int max_quads = 2 * c->p.Mcap / 4;   // the two row maps serve as the copy list
   for (;;) {
     if (until_check <= 0) {
       if (!first) {
@@ -1034,71 +1040,90 @@ int echo_rollout_continuous(echo_ctx *c, const int32_t *prompt_tokens, int32_t p
         HIPCHK(c, hipStreamSynchronize(st));
       }
       first = false;
-      // groups whose sequences have all ended hand their records over and free their slots
-      for (int b = 0; b < B; ++b) {
-        if (group_prompt[b] < 0) continue;
-        bool busy = false;
-        for (int g = 0; g < G; ++g) busy |= act[b * G + g] != 0;
-        if (busy) continue;
-        int64_t r0 = (int64_t)b * G * max_new, n0 = (int64_t)group_prompt[b] * G * max_new, cells = (int64_t)G * max_new;
-        HIPCHK(c, hipMemcpyAsync(out_tokens + n0, d_out_tok + r0, cells * 4, hipMemcpyDeviceToHost, st));
-        HIPCHK(c, hipMemcpyAsync(out_logprobs + n0, d_out_lp + r0, cells * 4, hipMemcpyDeviceToHost, st));
-        if (out_versions) HIPCHK(c, hipMemcpyAsync(out_versions + n0, d_out_ver + r0, cells * 8, hipMemcpyDeviceToHost, st));
-        for (int g = 0; g < G; ++g) out_lens[group_prompt[b] * G + g] = gen[b * G + g];
-        group_prompt[b] = -1;
-        ++done_prompts;
+      // a sequence that has ended hands its record over
+      for (int r = 0; r < R; ++r) {
+        int n = row_seq[r];
+        if (n < 0 || act[r]) continue;
+        int64_t r0 = (int64_t)r * max_new, n0 = (int64_t)n * max_new;
+        HIPCHK(c, hipMemcpyAsync(out_tokens + n0, d_out_tok + r0, (size_t)max_new * 4, hipMemcpyDeviceToHost, st));
+        HIPCHK(c, hipMemcpyAsync(out_logprobs + n0, d_out_lp + r0, (size_t)max_new * 4, hipMemcpyDeviceToHost, st));
+        if (out_versions) HIPCHK(c, hipMemcpyAsync(out_versions + n0, d_out_ver + r0, (size_t)max_new * 8, hipMemcpyDeviceToHost, st));
+        out_lens[n] = gen[r];
+        row_seq[r] = -1;
+        --group_left[n / G];
+        ++done_seqs;
       }
-      if (done_prompts == P) break;
-      // waiting prompts take the free group slots
-      std::vector<int> admitted;
-      for (int b = 0; b < B && next_prompt < P; ++b)
-        if (group_prompt[b] < 0) { group_prompt[b] = next_prompt++; admitted.push_back(b); }
+      if (done_seqs == N) break;
+      // its row is free again, unless the cache slot still holds the prompt tiles that running siblings read
+      free_rows.clear();
+      for (int r = 0; r < R; ++r) {
+        if (row_seq[r] >= 0) continue;
+        if (row_holds[r] >= 0 && group_left[row_holds[r]] > 0) continue;
+        row_holds[r] = -1;
+        free_rows.push_back(r);
+      }
+      // waiting prompts take G free rows each
+      struct Admit { int prompt; std::vector<int> rows; };
+      std::vector<Admit> admitted;
+      while (next_prompt < P && (int)free_rows.size() >= G) {
+        Admit ad{next_prompt++, {}};
+        ad.rows.assign(free_rows.end() - G, free_rows.end());
+        free_rows.resize(free_rows.size() - G);
+        admitted.push_back(ad);
+      }
       if (!admitted.empty()) {
         auto a0 = std::chrono::steady_clock::now();
-        // all of a prompt but its last token goes through the causal-block pass into the group's first slot; the
-        // last token is the group's first decode input, so the first sampled token comes out of an ordinary step
+        // All of a prompt but its last token goes through the causal-block pass into one of the group's cache slots
+        // (the holder); the last token is every member's first decode input, so the first sampled token comes out of
+        // an ordinary step.  The holder is the member that will run longest when that is known (stop lengths only).
         std::vector<ChunkSeq> seqs;
-        std::vector<int32_t> plen_b(B, 0);
-        for (int b : admitted) {
-          int pp = group_prompt[b], L = prompt_lens[pp];
-          if (L > 1) seqs.push_back({prompt_tokens + (int64_t)pp * prompt_stride, L - 1, b * G});
-          plen_b[b] = L - 1;
-        }
-        if (!seqs.empty()) {
-          if ((rc = run_chunk_seqs(c, c->slots[cur], seqs, [&](const ChunkRow *, int) { return 0; }))) return rc;
-          HIPCHK(c, hipMemcpyAsync(c->d_plen_p, plen_b.data(), (size_t)B * 4, hipMemcpyHostToDevice, st));
-          launch_kv_replicate(c->kv, c->d_plen_p, B, G, st);
-        }
-        for (int b : admitted) {
-          int pp = group_prompt[b], L = prompt_lens[pp];
+        quads.clear();
+        for (Admit &ad : admitted) {
+          int pp = ad.prompt, L = prompt_lens[pp], hold = 0;
+          for (int g = 1; g < G; ++g) if (limit_of(pp * G + g) > limit_of(pp * G + hold)) hold = g;
+          std::swap(ad.rows[0], ad.rows[hold]);   // member `hold` gets rows[hold], which now is the holder row
+          int hr = ad.rows[hold];
+          if (L > 1) seqs.push_back({prompt_tokens + (int64_t)pp * prompt_stride, L - 1, hr});
+          int shared = share_prefix ? (L - 1) / 32 : 0;
+          int begin = c->kv.tiled ? shared : 0, end = c->kv.tiled ? (L - 1 + 31) / 32 : L - 1;
           for (int g = 0; g < G; ++g) {
-            int r = b * G + g, n = pp * G + g;
+            int r = ad.rows[g], n = pp * G + g;
+            if (r != hr && end > begin) { quads.push_back(hr); quads.push_back(r); quads.push_back(begin); quads.push_back(end); }
             tok[r] = prompt_tokens[(int64_t)pp * prompt_stride + L - 1];
-            pos[r] = L - 1; act[r] = 1; pslot[r] = b * G; ptiles[r] = share_prefix ? (L - 1) / 32 : 0;
-            plen[r] = L; gen[r] = 0; stream[r] = n;
-            lim[r] = o.stop_lens ? std::max(1, std::min(max_new, o.stop_lens[n])) : max_new;
+            pos[r] = L - 1; act[r] = 1; pslot[r] = hr; ptiles[r] = shared;
+            plen[r] = L; gen[r] = 0; stream[r] = n; lim[r] = limit_of(n);
+            row_seq[r] = n;
           }
-          int64_t r0 = (int64_t)b * G * max_new, cells = (int64_t)G * max_new;
-          launch_fill_i32(d_out_tok + r0, -1, cells, st);
-          launch_fill_i32((int32_t *)(d_out_lp + r0), 0, cells, st);
-          launch_fill_i32((int32_t *)(d_out_ver + r0), -1, cells * 2, st);
-          if (d_forced)
-            HIPCHK(c, hipMemcpyAsync(d_forced + r0, o.forced_tokens + (int64_t)pp * G * max_new, cells * 4, hipMemcpyHostToDevice, st));
+          row_holds[hr] = pp;
+          group_left[pp] = G;
         }
+        if (!seqs.empty() && (rc = run_chunk_seqs(c, c->slots[cur], seqs, [&](const ChunkRow *, int) { return 0; }))) return rc;
+        for (size_t q0 = 0; q0 < quads.size() / 4; q0 += max_quads) {
+          int nq = (int)std::min<size_t>(max_quads, quads.size() / 4 - q0);
+          HIPCHK(c, hipMemcpyAsync(c->d_map_a, quads.data() + 4 * q0, (size_t)nq * 16, hipMemcpyHostToDevice, st));
+          launch_kv_copy_ranges(c->kv, c->d_map_a, nq, st);
+          HIPCHK(c, hipStreamSynchronize(st));   // the list is rewritten by the next round
+        }
+        for (Admit &ad : admitted)
+          for (int g = 0; g < G; ++g) {
+            int64_t r0 = (int64_t)ad.rows[g] * max_new;
+            launch_fill_i32(d_out_tok + r0, -1, max_new, st);
+            launch_fill_i32((int32_t *)(d_out_lp + r0), 0, max_new, st);
+            launch_fill_i32((int32_t *)(d_out_ver + r0), -1, (int64_t)max_new * 2, st);
+            if (d_forced)
+              HIPCHK(c, hipMemcpyAsync(d_forced + r0, o.forced_tokens + (int64_t)(ad.prompt * G + g) * max_new, (size_t)max_new * 4,
+                                       hipMemcpyHostToDevice, st));
+          }
         if ((rc = upload_rows())) return rc;   // also restores the rows the prefill pass used as its own
         HIPCHK(c, hipStreamSynchronize(st));
         admit_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - a0).count();
       }
-      // the next event: with stop lengths only, the step at which the first group runs out is known
+      // the next event: with stop lengths only, the step at which the next sequence ends is known
       until_check = 8;
       if (o.eos_id < 0) {
         int soonest = INT32_MAX;
-        for (int b = 0; b < B; ++b) {
-          if (group_prompt[b] < 0) continue;
-          int longest = 0;
-          for (int g = 0; g < G; ++g) if (act[b * G + g]) longest = std::max(longest, lim[b * G + g] - gen[b * G + g]);
-          soonest = std::min(soonest, std::max(longest, 1));
-        }
+        for (int r = 0; r < R; ++r)
+          if (row_seq[r] >= 0 && act[r]) soonest = std::min(soonest, std::max(lim[r] - gen[r], 1));
         until_check = soonest;
       }
     }

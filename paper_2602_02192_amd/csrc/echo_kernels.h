@@ -59,6 +59,9 @@ void launch_bookkeeping(int N, int max_new, int per_row /*1: a row's step is its
                         float *out_lp, int64_t *out_ver, int32_t *n_active, hipStream_t st);
 void launch_kv_replicate(KvGeom kv, const int32_t *prompt_len /*[P]*/, int P, int G, hipStream_t st);
 void launch_draw_bits(uint32_t *out, uint64_t seed, uint32_t n, uint32_t s, uint32_t i0, int count, hipStream_t st);
+// quads: device [n_quads][4] = (src slot, dst slot, begin, end); copies keys [begin, end) (plain cache) or whole tiles
+// of 32 keys [begin, end) (tiled cache) of every layer and head from the source slot to the destination slot.
+void launch_kv_copy_ranges(KvGeom kv, const int32_t *quads, int n_quads, hipStream_t st);
 void launch_fill_i32(int32_t *p, int32_t v, int64_t n, hipStream_t st);
 // Which draw of the generator a row takes (the step and stream words of its counter).  In a rollout whose sequences
 // all start together every row sits at the step *d_step and row m is stream m; with row_step / row_stream set the

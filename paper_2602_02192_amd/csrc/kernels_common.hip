@@ -86,6 +86,28 @@ void launch_kv_replicate(KvGeom kv, const int32_t *prompt_len, int P, int G, hip
   hipLaunchKernelGGL(kv_replicate_kernel, dim3(8, regions, P * (G - 1)), dim3(256), 0, st, kv, prompt_len, G);
 }
 
+// Copy part of one cache slot's prompt into another slot, for a list of (src slot, dst slot, begin, end) quadruples.
+// grid = (chunks, regions per slot, pairs).  Plain form: a region is one head's K or V plane and [begin, end) are rows
+// (keys); tiled form: a region is one head's K and V tiles and [begin, end) are tiles of 32 keys.
+__global__ void kv_copy_range_kernel(KvGeom kv, const int32_t *quads) {
+  const int32_t *q = quads + 4 * blockIdx.z;
+  int64_t unit_bytes = (kv.tiled ? 64 : 1) * (int64_t)kv.head_dim * kv.elt_bytes;
+  int64_t region_bytes = kv.head_stride() * kv.elt_bytes * (kv.tiled ? 2 : 1);
+  int64_t off = (int64_t)q[2] * unit_bytes, bytes = (int64_t)(q[3] - q[2]) * unit_bytes;
+  if (bytes <= 0) return;
+  const char *src = (const char *)kv.base + (int64_t)q[0] * kv.slot_stride() * kv.elt_bytes + blockIdx.y * region_bytes + off;
+  char *dst = (char *)kv.base + (int64_t)q[1] * kv.slot_stride() * kv.elt_bytes + blockIdx.y * region_bytes + off;
+  int64_t n16 = bytes / 16;  // head_dim * elt_bytes is a multiple of 16
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (int64_t)gridDim.x * blockDim.x)
+    ((uint4 *)dst)[i] = ((const uint4 *)src)[i];
+}
+
+void launch_kv_copy_ranges(KvGeom kv, const int32_t *quads, int n_quads, hipStream_t st) {
+  if (n_quads <= 0) return;
+  int regions = kv.n_layers * kv.n_kv_heads * (kv.tiled ? 1 : 2);
+  hipLaunchKernelGGL(kv_copy_range_kernel, dim3(8, regions, n_quads), dim3(256), 0, st, kv, quads);
+}
+
 __global__ void draw_bits_kernel(uint32_t *out, uint64_t seed, uint32_t n, uint32_t s, uint32_t i0, int count) {
   int j = blockIdx.x * blockDim.x + threadIdx.x;
   if (j >= count) return;
