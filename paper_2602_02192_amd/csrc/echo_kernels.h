@@ -112,6 +112,7 @@ constexpr int REDUCE_MAX_SPLIT = 12;   // most grid splits over K whose partials
 constexpr int GEMM_K_PAD = 128;   // packed weights and K8 activations pad K to this (whole LDS chunks of 8 k-steps)
 void fast_gemm(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, GemmShape g, GemmEpilogue epi,
                hipStream_t st);
+int fast_gemm_even_split(int Kp, int nsplit);
 void fast_gemm_pick(int Np, int Kp, int Mp, int full_k, GemmShape *g);
 void fast_qkv_post(const float *partials, int nsplit, int Np, int Mp, void *q_h16 /*[M][Hq][hd]*/,
                    const void *q_gain, const void *k_gain, int qk_norm, float eps, const float *rope_cs,

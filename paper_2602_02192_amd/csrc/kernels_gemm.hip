@@ -503,12 +503,15 @@ __global__ __launch_bounds__(WN * 64) void gemm_lds_kernel(void *out, const u32x
 // directions.  Four wavefronts, each with two weight blocks (64 output columns) against 256 batch rows: every
 // activation operand read from LDS feeds two MFMAs, which halves the LDS traffic of the one-block kernel (that one
 // runs at the LDS limit).  The 256 accumulator registers per lane live in the accumulation half of the register file.
-struct GemmWide {
-  static constexpr int MB = 8, WN = 4, NBW = 2, NSTAGE = 8, ROWS = 32 * MB, T = WN * 64;
+// WR = 2 arranges the four wavefronts as two row halves x two column pairs (tile 256 x 128, 128 accumulator registers per
+// lane): for batches of exactly a few hundred rows, where 256 x 256 tiles are too few to fill the chip.
+template <int WRv> struct GemmWideT {
+  static constexpr int WR = WRv, MB = 8 / WR, WN = 4, WC = WN / WR, NBW = 2, NSTAGE = 8, ROWS = 256, T = WN * 64;
   static constexpr int CHUNK_UNITS = 2 * ROWS, XL = CHUNK_UNITS / T;   // a chunk is one k-step
   static constexpr int X_BYTES = 2 * CHUNK_UNITS * 16, TILE_STRIDE = 33, EPI_BYTES = WN * 32 * TILE_STRIDE * 4;
   static constexpr int BYTES = X_BYTES > EPI_BYTES ? X_BYTES : EPI_BYTES;
 };
+using GemmWide = GemmWideT<1>;
 
 // One k-step per chunk, operands requested seven chunks ahead: with one wavefront per SIMD only the depth of the
 // register pipeline hides the load latency, and measured throughput kept rising with it.  Kp is a multiple of
@@ -517,18 +520,21 @@ struct GemmWide {
 // are clamped to the last k-step, loaded again and never used.
 // ZFAST: the row blocks of one weight strip are neighbours in launch order, so a strip is fetched from HBM once and
 // found in cache by the other row blocks; pays when the weight matrix is far larger than the last-level cache.
-template <int EPI, bool ZFAST>
+// blockIdx.y splits K in runs of `groups_per_split` groups of eight k-steps (EPI_PARTIAL only: split y writes the
+// partial plane y of out).
+template <int EPI, bool ZFAST, int WR>
 __global__ __launch_bounds__(256) void gemm_wide_kernel(void *out, const u32x4v *__restrict__ Xp, const h16x8 *__restrict__ Wp, int Mp,
-                                                        int Np, int Kp) {
+                                                        int Np, int Kp, int groups_per_split) {
   extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-  using L = GemmWide;
+  using L = GemmWideT<WR>;
   constexpr int MB = L::MB, NBW = L::NBW, T = L::T, XU = L::CHUNK_UNITS, XL = L::XL, ROWS = L::ROWS, NSTAGE = L::NSTAGE;
   static_assert((GEMM_K_PAD / 16) % NSTAGE == 0, "k-step count must be a multiple of the stage count");
   u32x4v *xs = (u32x4v *)lds_raw;
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, tid = threadIdx.x;
-  const int nblocks = Np >> 5, nchunks = Kp >> 4, nz = Mp / ROWS;
+  const int nblocks = Np >> 5, nz = Mp / ROWS;
+  const int c_lo = blockIdx.y * groups_per_split * NSTAGE, nchunks = min(Kp >> 4, c_lo + groups_per_split * NSTAGE);
   const int bx = ZFAST ? blockIdx.x / nz : blockIdx.x, bz = ZFAST ? blockIdx.x % nz : blockIdx.z;
-  const int nb0 = (bx * L::WN + w) * NBW, mrow0 = bz * ROWS;
+  const int nb0 = (bx * L::WC + w % L::WC) * NBW, mrow0 = bz * ROWS, wrow = (w / L::WC) * 32 * MB;
   const int64_t a_step = w_kstep_stride(Np);
   const h16x8 *a_ptr[NBW];
 #pragma unroll
@@ -559,7 +565,7 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(void *out, const u32x4v 
     for (int i = 0; i < XL; ++i) xs[buf * XU + i * T + tid] = xr[st][i];
   };
   auto compute = [&](int st, int buf) {
-    const u32x4v *bp = xs + buf * XU + (lane >> 5) * ROWS + (lane & 31);
+    const u32x4v *bp = xs + buf * XU + (lane >> 5) * ROWS + wrow + (lane & 31);
     u32x4v b[MB];
 #pragma unroll
     for (int j = 0; j < MB; ++j) b[j] = bp[j * 32];
@@ -569,17 +575,17 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(void *out, const u32x4v 
       for (int n = 0; n < NBW; ++n) acc[n][j] = mfma_h16(a[st][n], __builtin_bit_cast(h16x8, b[j]), acc[n][j]);
   };
 #pragma unroll
-  for (int s = 0; s < NSTAGE - 1; ++s) { load_x(s, s); load_a(s, s); }
+  for (int s = 0; s < NSTAGE - 1; ++s) { load_x(s, min(c_lo + s, nchunks - 1)); load_a(s, min(c_lo + s, nchunks - 1)); }
   store_x(0, 0);
   __syncthreads();
-  for (int c0 = 0; c0 < nchunks; c0 += NSTAGE) {
+  for (int c0 = c_lo; c0 < nchunks; c0 += NSTAGE) {
 #pragma unroll
     for (int s = 0; s < NSTAGE; ++s) {
       const int c = c0 + s, cn = min(c + NSTAGE - 1, nchunks - 1);
       load_x((s + NSTAGE - 1) % NSTAGE, cn);
       load_a((s + NSTAGE - 1) % NSTAGE, cn);
-      compute(s, c & 1);
-      store_x((s + 1) % NSTAGE, (c + 1) & 1);
+      compute(s, s & 1);
+      store_x((s + 1) % NSTAGE, (s + 1) & 1);
       __syncthreads();
     }
   }
@@ -588,7 +594,7 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(void *out, const u32x4v 
     float *tile = (float *)lds_raw + (size_t)w * 32 * L::TILE_STRIDE;
 #pragma unroll
     for (int n = 0; n < NBW; ++n) {
-      float *P = (float *)out + (int64_t)mrow0 * Np + (nb0 + n) * 32;
+      float *P = (float *)out + ((int64_t)blockIdx.y * Mp + mrow0 + wrow) * Np + (nb0 + n) * 32;
 #pragma unroll
       for (int j = 0; j < MB; ++j) {
 #pragma unroll
@@ -625,37 +631,60 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(void *out, const u32x4v 
         uint32_t give0 = half ? pk[0] : pk[2], give1 = half ? pk[1] : pk[3];
         uint32_t got0 = __shfl_xor(give0, 32, 64), got1 = __shfl_xor(give1, 32, 64);
         u32x4v o = half ? u32x4v{got0, pk[2], got1, pk[3]} : u32x4v{pk[0], got0, pk[1], got1};
-        int m = mrow0 + j * 32 + col;
+        int m = mrow0 + wrow + j * 32 + col;
         *(u32x4v *)(O + (((int64_t)((nb0 + n) * 2 + half) * Mp + m) * 4)) = o;
       }
     }
   }
 }
 
-template <int EPI, bool ZFAST>
-static void gemm_wide_launch(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, hipStream_t st) {
-  using L = GemmWide;
+template <int EPI, bool ZFAST, int WR = 1>
+static void gemm_wide_launch(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, hipStream_t st, int nsplit = 1) {
+  using L = GemmWideT<WR>;
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void *)gemm_wide_kernel<EPI, ZFAST>, hipFuncAttributeMaxDynamicSharedMemorySize, L::BYTES);
+    (void)hipFuncSetAttribute((const void *)gemm_wide_kernel<EPI, ZFAST, WR>, hipFuncAttributeMaxDynamicSharedMemorySize, L::BYTES);
     attr_set = true;
   }
-  int nblocks = Np / 32, per_wg = L::WN * L::NBW, strips = (nblocks + per_wg - 1) / per_wg, nz = Mp / L::ROWS;
-  dim3 grid = ZFAST ? dim3(strips * nz, 1, 1) : dim3(strips, 1, nz);
-  hipLaunchKernelGGL((gemm_wide_kernel<EPI, ZFAST>), grid, dim3(L::T), L::BYTES, st, out, (const u32x4v *)Xp, (const h16x8 *)Wp, Mp, Np,
-                     Kp);
+  int nblocks = Np / 32, per_wg = L::WC * L::NBW, strips = (nblocks + per_wg - 1) / per_wg, nz = Mp / L::ROWS;
+  int groups = (Kp / 16) / L::NSTAGE, gps = (groups + nsplit - 1) / nsplit, ny = (groups + gps - 1) / gps;
+  dim3 grid = ZFAST ? dim3(strips * nz, ny, 1) : dim3(strips, ny, nz);
+  hipLaunchKernelGGL((gemm_wide_kernel<EPI, ZFAST, WR>), grid, dim3(L::T), L::BYTES, st, out, (const u32x4v *)Xp, (const h16x8 *)Wp, Mp,
+                     Np, Kp, gps);
 }
 
 // Launch shape.  Up to 128 batch rows the LDS-staged kernel runs: three or four weight blocks per workgroup, and a
 // grid split over K that brings the launch to about one workgroup per compute unit (partials cost HBM writes, so
 // no more than that); a GEMM whose epilogue needs the whole K (SwiGLU) is not split.  Larger batches keep the
 // register-streaming kernel: waves_k wavefronts of a workgroup share a block's k-steps and are summed in LDS.
+// The largest split count <= nsplit that the 256 x 128-tile kernel realises exactly: it cuts K into runs of
+// ceil(groups / nsplit) groups of eight k-steps, which may come to fewer runs than asked for.
+int fast_gemm_even_split(int Kp, int nsplit) {
+  int groups = Kp / 16 / 8;
+  for (;;) {
+    int gps = (groups + nsplit - 1) / nsplit, ny = (groups + gps - 1) / gps;
+    if (ny == nsplit) return nsplit;
+    nsplit = ny;
+  }
+}
+
 void fast_gemm_pick(int Np, int Kp, int Mp, int full_k, GemmShape *g) {
   int nblocks = Np / 32, ksteps = Kp / 16, mb = Mp / 32 > 8 ? 8 : Mp / 32;
   int zblocks = Mp / (32 * mb);
   g->lds = 0; g->stages = 0;
   if (Kp % GEMM_K_PAD == 0 && Mp % 256 == 0 && (nblocks + 7) / 8 * (Mp / 256) >= 128) {   // 256 x 256 tiles fill the chip
     g->lds = 2; g->nbw = 2; g->waves_k = 1; g->waves_n = 4; g->stages = 8; g->nsplit = 1;
+    return;
+  }
+  if (Kp % GEMM_K_PAD == 0 && Mp % 256 == 0) {
+    // 256 x 128 tiles (two row halves x two column pairs of wavefronts), K split until the launch has about one
+    // workgroup per compute unit; a split keeps at least four groups of eight k-steps
+    int strips = (nblocks + 3) / 4 * (Mp / 256), groups = ksteps / 8;
+    int ns = full_k ? 1 : (240 + strips / 2) / strips;
+    if (ns > groups / 4) ns = groups / 4;
+    if (ns > 12) ns = 12;
+    if (ns < 1) ns = 1;
+    g->lds = 3; g->nbw = 2; g->waves_k = 1; g->waves_n = 4; g->stages = 8; g->nsplit = fast_gemm_even_split(Kp, ns);
     return;
   }
   if (Kp % (16 * GEMM_KC_SMALL) == 0 && (Mp <= 128 || Mp % 256 == 0)) {
@@ -723,6 +752,7 @@ static void gemm_dispatch(void *out, const void *Xp, const void *Wp, int Mp, int
     else gemm_wide_launch<EPI, false>(out, Xp, Wp, Mp, Np, Kp, st);
     return;
   }
+  if (g.lds == 3) { gemm_wide_launch<EPI, false, 2>(out, Xp, Wp, Mp, Np, Kp, st, g.nsplit); return; }
   if (g.lds) { gemm_lds_dispatch<EPI>(out, Xp, Wp, Mp, Np, Kp, g, st); return; }
   int mbt = Mp / 32;
   int MB = mbt >= 8 ? 8 : mbt;
