@@ -53,6 +53,9 @@ WORKLOADS = {
     # waiting prompts (echo_rollout_continuous), 256 sequences decode together throughout
     "dense4b-kvheavy-512x1024+4096-continuous256": dict(shape="DENSE_4B", P=64, G=8, plen=1024, max_new=4096, stop=(512, 4096),
                                                         slots=256, continuous=True),
+    # the paper's own sampling setting (Sec. 5.1: Qwen3-8B-class policy, 16 samples per prompt, temperature 1.0, top-p 0.95,
+    # up to 8192 generated tokens); stop lengths stand in for EOS
+    "dense8b-paper-128x1024+8192-top_p0.95": dict(shape="DENSE_8B", P=8, G=16, plen=1024, max_new=8192, top_p=0.95, stop=(1024, 8192)),
     # eight cache-fuls of shorter sequences, and one cache-ful of the same length mix through the ordinary rollout
     "dense4b-2048x512+1024-continuous256": dict(shape="DENSE_4B", P=256, G=8, plen=512, max_new=1024, stop=(128, 1024),
                                                 slots=256, continuous=True),
