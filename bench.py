@@ -121,6 +121,9 @@ def main():
                     help="keep the host copy of the weights in pageable memory (a counter-collecting profiler crashed on the pinned copy)")
     ap.add_argument("--install-chunk-mb", type=int, default=0,
                     help="snapshot swaps inside a rollout hand the blob over in pieces of this size (0 = one call)")
+    ap.add_argument("--continuous", action="store_true",
+                    help="run the workload through echo_rollout_continuous (refill does not apply when everything fits the cache; "
+                         "the rows of a draining batch are compacted)")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch decode steps kernel by kernel (counter collection cannot follow graph replays)")
     a = ap.parse_args()
@@ -154,7 +157,7 @@ def main():
     prompts, lens = synth.make_prompts(shape.vocab, P, plen, seed=1)
     stop = synth.make_stop_lens(N, wl["stop"][0], wl["stop"][1], seed=3) if wl.get("stop") else None
     swaps = list(range(swap_every, max_new, swap_every)) if swap_every else []
-    continuous = bool(wl.get("continuous"))
+    continuous = bool(wl.get("continuous")) or a.continuous
     if continuous:
         a.no_kernel_timing = True    # the continuous entry point takes no per-kernel event timing
     ctx = echo.Context(echo.desc_from_shape(shape, wl.get("slots", N), plen + max_new + a.ctx_pad, n_weight_slots=2 if swap_every else 1))

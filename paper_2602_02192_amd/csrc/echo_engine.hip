@@ -1002,7 +1002,8 @@ int echo_rollout_continuous(echo_ctx *c, const int32_t *prompt_tokens, int32_t p
   const bool use_graph = !o.no_graph;
   const bool share_prefix = p.fast && !env_flag("ECHO_NO_PREFIX_SHARING") && !env_flag("ECHO_ATTN_SIMPLE");
   const bool splitk = !env_flag("ECHO_ATTN_SIMPLE");
-  const int R = std::min(N, c->d.max_seqs);   // rows of the batch = cache slots in use
+  const int R = std::min(N, c->d.max_seqs);   // cache slots in use; rows of the batch until the rows are compacted
+  int Rc = R;                                 // rows of the batch now
   // host mirrors of the per-row state; token, pos, active and gen are read back at every check
   std::vector<int32_t> tok(R, 0), pos(R, 0), act(R, 0), slot(R), pslot(R, 0), ptiles(R, 0), plen(R, 1), gen(R, 0), lim(R, 1), stream(R, 0);
   std::vector<int> row_seq(R, -1);      // the sequence a row is generating, -1: none
@@ -1017,7 +1018,7 @@ int echo_rollout_continuous(echo_ctx *c, const int32_t *prompt_tokens, int32_t p
     struct { int32_t *dst; std::vector<int32_t> *src; } cp[] = {
         {c->rows.token, &tok}, {c->rows.pos, &pos}, {c->rows.active, &act}, {c->rows.slot, &slot}, {c->rows.pslot, &pslot},
         {c->rows.ptiles, &ptiles}, {c->d_prompt_len_seq, &plen}, {c->d_gen_len, &gen}, {c->d_limit, &lim}, {c->d_stream, &stream}};
-    for (auto &x : cp) HIPCHK(c, hipMemcpyAsync(x.dst, x.src->data(), (size_t)R * 4, hipMemcpyHostToDevice, st));
+    for (auto &x : cp) HIPCHK(c, hipMemcpyAsync(x.dst, x.src->data(), (size_t)R * 4, hipMemcpyHostToDevice, st));   // R: also the rows given up
     return 0;
   };
   auto limit_of = [&](int n) { return o.stop_lens ? std::max(1, std::min(max_new, o.stop_lens[n])) : max_new; };
@@ -1034,18 +1035,18 @@ int echo_rollout_continuous(echo_ctx *c, const int32_t *prompt_tokens, int32_t p
   for (;;) {
     if (until_check <= 0) {
       if (!first) {
-        HIPCHK(c, hipMemcpyAsync(tok.data(), c->rows.token, (size_t)R * 4, hipMemcpyDeviceToHost, st));
-        HIPCHK(c, hipMemcpyAsync(pos.data(), c->rows.pos, (size_t)R * 4, hipMemcpyDeviceToHost, st));
-        HIPCHK(c, hipMemcpyAsync(act.data(), c->rows.active, (size_t)R * 4, hipMemcpyDeviceToHost, st));
-        HIPCHK(c, hipMemcpyAsync(gen.data(), c->d_gen_len, (size_t)R * 4, hipMemcpyDeviceToHost, st));
+        HIPCHK(c, hipMemcpyAsync(tok.data(), c->rows.token, (size_t)Rc * 4, hipMemcpyDeviceToHost, st));
+        HIPCHK(c, hipMemcpyAsync(pos.data(), c->rows.pos, (size_t)Rc * 4, hipMemcpyDeviceToHost, st));
+        HIPCHK(c, hipMemcpyAsync(act.data(), c->rows.active, (size_t)Rc * 4, hipMemcpyDeviceToHost, st));
+        HIPCHK(c, hipMemcpyAsync(gen.data(), c->d_gen_len, (size_t)Rc * 4, hipMemcpyDeviceToHost, st));
         HIPCHK(c, hipStreamSynchronize(st));
       }
       first = false;
       // a sequence that has ended hands its record over
-      for (int r = 0; r < R; ++r) {
+      for (int r = 0; r < Rc; ++r) {
         int n = row_seq[r];
         if (n < 0 || act[r]) continue;
-        int64_t r0 = (int64_t)r * max_new, n0 = (int64_t)n * max_new;
+        int64_t r0 = (int64_t)slot[r] * max_new, n0 = (int64_t)n * max_new;
         HIPCHK(c, hipMemcpyAsync(out_tokens + n0, d_out_tok + r0, (size_t)max_new * 4, hipMemcpyDeviceToHost, st));
         HIPCHK(c, hipMemcpyAsync(out_logprobs + n0, d_out_lp + r0, (size_t)max_new * 4, hipMemcpyDeviceToHost, st));
         if (out_versions) HIPCHK(c, hipMemcpyAsync(out_versions + n0, d_out_ver + r0, (size_t)max_new * 8, hipMemcpyDeviceToHost, st));
@@ -1057,7 +1058,7 @@ int echo_rollout_continuous(echo_ctx *c, const int32_t *prompt_tokens, int32_t p
       if (done_seqs == N) break;
       // its row is free again, unless the cache slot still holds the prompt tiles that running siblings read
       free_rows.clear();
-      for (int r = 0; r < R; ++r) {
+      for (int r = 0; r < Rc && next_prompt < P; ++r) {
         if (row_seq[r] >= 0) continue;
         if (row_holds[r] >= 0 && group_left[row_holds[r]] > 0) continue;
         row_holds[r] = -1;
@@ -1107,7 +1108,7 @@ int echo_rollout_continuous(echo_ctx *c, const int32_t *prompt_tokens, int32_t p
         }
         for (Admit &ad : admitted)
           for (int g = 0; g < G; ++g) {
-            int64_t r0 = (int64_t)ad.rows[g] * max_new;
+            int64_t r0 = (int64_t)slot[ad.rows[g]] * max_new;
             launch_fill_i32(d_out_tok + r0, -1, max_new, st);
             launch_fill_i32((int32_t *)(d_out_lp + r0), 0, max_new, st);
             launch_fill_i32((int32_t *)(d_out_ver + r0), -1, (int64_t)max_new * 2, st);
@@ -1119,11 +1120,31 @@ int echo_rollout_continuous(echo_ctx *c, const int32_t *prompt_tokens, int32_t p
         HIPCHK(c, hipStreamSynchronize(st));
         admit_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - a0).count();
       }
+      // No prompt is waiting any more: once the live rows fit a smaller padded batch they are moved to the front (their
+      // cache slots and records stay where they are) and the step is captured again for fewer rows.
+      if (next_prompt == P) {
+        int live = 0;
+        for (int r = 0; r < Rc; ++r) live += row_seq[r] >= 0;
+        if (live > 0 && pad_rows(live) < pad_rows(Rc)) {
+          int w = 0;
+          for (int r = 0; r < Rc; ++r) {
+            if (row_seq[r] < 0) continue;
+            tok[w] = tok[r]; pos[w] = pos[r]; act[w] = act[r]; slot[w] = slot[r]; pslot[w] = pslot[r]; ptiles[w] = ptiles[r];
+            plen[w] = plen[r]; gen[w] = gen[r]; lim[w] = lim[r]; stream[w] = stream[r]; row_seq[w] = row_seq[r];
+            ++w;
+          }
+          for (int r = w; r < Rc; ++r) { act[r] = 0; row_seq[r] = -1; }
+          Rc = w;
+          if ((rc = upload_rows())) return rc;
+          HIPCHK(c, hipStreamSynchronize(st));
+          have_graph = false;
+        }
+      }
       // the next event: with stop lengths only, the step at which the next sequence ends is known
       until_check = 8;
       if (o.eos_id < 0) {
         int soonest = INT32_MAX;
-        for (int r = 0; r < R; ++r)
+        for (int r = 0; r < Rc; ++r)
           if (row_seq[r] >= 0 && act[r]) soonest = std::min(soonest, std::max(lim[r] - gen[r], 1));
         until_check = soonest;
       }
@@ -1142,14 +1163,14 @@ int echo_rollout_continuous(echo_ctx *c, const int32_t *prompt_tokens, int32_t p
     }
     if (use_graph) {
       if (!have_graph) {
-        if ((rc = capture_step(c, c->slots[cur], R, max_new, temperature, seed, unfused, d_forced, o.eos_id, o.top_p, 1))) return rc;
+        if ((rc = capture_step(c, c->slots[cur], Rc, max_new, temperature, seed, unfused, d_forced, o.eos_id, o.top_p, 1))) return rc;
         have_graph = true;
       }
       HIPCHK(c, hipGraphLaunch(c->graph, st));
     } else {
-      forward_layers(c, c->slots[cur], R, splitk);
-      sample_rows(c, c->slots[cur], R, temperature, seed, unfused, nullptr, o.top_p);
-      launch_bookkeeping(R, max_new, 1, c->d_step, c->d_samp_tok, c->d_samp_lp, d_forced, c->d_limit, o.eos_id, c->slots[cur].version,
+      forward_layers(c, c->slots[cur], Rc, splitk);
+      sample_rows(c, c->slots[cur], Rc, temperature, seed, unfused, nullptr, o.top_p);
+      launch_bookkeeping(Rc, max_new, 1, c->d_step, c->d_samp_tok, c->d_samp_lp, d_forced, c->d_limit, o.eos_id, c->slots[cur].version,
                          c->d_prompt_len_seq, c->d_gen_len, c->rows, d_out_tok, d_out_lp, d_out_ver, c->d_n_active, st);
     }
     ++decode_steps;

@@ -39,7 +39,7 @@ __global__ void bookkeeping_kernel(int N, int max_new, int per_row, int32_t *d_s
     if (!rows.active[n]) continue;
     const int s = per_row ? gen_len[n] : s0;
     int tok = samp_tok[n];
-    int64_t o = (int64_t)n * max_new + s;
+    int64_t o = (int64_t)rows.slot[n] * max_new + s;   // records are kept per cache slot (= row unless rows were compacted)
     out_tok[o] = tok;
     out_lp[o] = samp_lp[n];
     out_ver[o] = version;

@@ -15,7 +15,9 @@ pytestmark = pytest.mark.gpu
 MID = synth.ModelShape(2, 512, 8, 2, 128, 1024, 2048, dtype="bf16")
 
 
-@pytest.mark.parametrize("P,G,max_seqs,no_graph", [(7, 2, 4, False), (5, 3, 8, True), (3, 4, 4, False), (2, 2, 16, False)])
+# the last two cases leave more than 32 rows in flight when the prompts run out, so the draining batch is compacted
+@pytest.mark.parametrize("P,G,max_seqs,no_graph", [(7, 2, 4, False), (5, 3, 8, True), (3, 4, 4, False), (2, 2, 16, False),
+                                                   (30, 2, 40, False), (12, 5, 70, True)])
 def test_fp32_free_running_matches_the_oracle_sequence_by_sequence(P, G, max_seqs, no_graph):
     shape = synth.TINY
     blob = synth.make_weights(shape, 0)
@@ -54,18 +56,19 @@ def test_fp32_free_running_matches_the_oracle_sequence_by_sequence(P, G, max_seq
     ctx.close()
 
 
-def test_bf16_path_against_the_oracle_and_against_rollouts_that_fit():
+@pytest.mark.parametrize("P,max_seqs", [(9, 12), (20, 48)], ids=["three-groups", "compacted-while-draining"])
+def test_bf16_path_against_the_oracle_and_against_rollouts_that_fit(P, max_seqs):
     shape = MID
     blob = synth.make_weights(shape, 0)
     blob32 = synth.widen_to_f32(blob)
-    P, G, max_new = 9, 4, 10
+    G, max_new = 4, 10
     prompts, lens = synth.make_prompts(shape.vocab, P, 70, seed=4, ragged=True)
     lens[2] = 65                                           # two whole shared key tiles, then the decode input
     prompts[2, :65] = (np.arange(65) * 7) % shape.vocab
     stop = synth.make_stop_lens(P * G, 2, max_new, seed=6)
     ref = oracle_rollout(shape, blob32, prompts, lens, G=G, max_new=max_new, temperature=1.0, seed=2, stop_lens=stop)
     forced = ref["tokens"].clip(0)
-    ctx = make_ctx(shape, 12, 96, blob)                    # three groups at a time
+    ctx = make_ctx(shape, max_seqs, 96, blob)
     out = ctx.rollout(prompts, lens, G, max_new, 1.0, 2, stop_lens=stop, continuous=True, forced=forced)
     m = valid_mask(stop, max_new)
     assert np.array_equal(out["lens"], stop)
