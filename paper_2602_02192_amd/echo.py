@@ -259,3 +259,63 @@ class Context:
         st = Stats()
         self._chk(lib.echo_stats(self.h, C.byref(st)))
         return st
+
+
+# ---- pool capacity and dissemination arithmetic (include/echo_capacity.h; host only) -------------------------
+CAPACITY_EXPORTS = ["echo_mu_min", "echo_overlap_holds", "echo_staleness_bound", "echo_greedy_activate", "echo_peer_score",
+                    "echo_n_chains", "echo_chain_assign"]
+lib.echo_mu_min.restype = C.c_double
+lib.echo_mu_min.argtypes = [C.c_double] * 4
+lib.echo_overlap_holds.restype = C.c_int32
+lib.echo_overlap_holds.argtypes = [C.c_double] * 5
+lib.echo_staleness_bound.restype = C.c_int32
+lib.echo_staleness_bound.argtypes = [C.c_int32, C.c_double, C.c_double, C.c_double, C.c_double]
+lib.echo_greedy_activate.restype = C.c_int32
+lib.echo_greedy_activate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_double, C.c_void_p, C.c_void_p, C.c_void_p]
+lib.echo_peer_score.restype = C.c_double
+lib.echo_peer_score.argtypes = [C.c_double, C.c_double, C.c_int32, C.c_int32, C.c_double]
+lib.echo_n_chains.restype = C.c_int32
+lib.echo_n_chains.argtypes = [C.c_double, C.c_double]
+lib.echo_chain_assign.restype = C.c_int32
+lib.echo_chain_assign.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+
+
+def mu_min(kappa, R, T_train, T_bcast) -> float:
+    return lib.echo_mu_min(kappa, R, T_train, T_bcast)
+
+
+def overlap_holds(kappa, R, T_train, T_bcast, mu_pool) -> int:
+    return lib.echo_overlap_holds(kappa, R, T_train, T_bcast, mu_pool)
+
+
+def staleness_bound(kappa: int, R, T_train, T_bcast, mu_pool) -> int:
+    return lib.echo_staleness_bound(kappa, R, T_train, T_bcast, mu_pool)
+
+
+def greedy_activate(mu, cost, mu_target, available=None):
+    """(active flags, activated throughput, activated cost, return code of echo_greedy_activate)."""
+    mu = np.ascontiguousarray(mu, np.float64)
+    cost = np.ascontiguousarray(cost, np.float64)
+    av = np.ascontiguousarray(available, np.int32) if available is not None else None
+    active = np.zeros(mu.size, np.int32)
+    got, paid = C.c_double(), C.c_double()
+    rc = lib.echo_greedy_activate(_ptr(mu), _ptr(cost), _ptr(av), mu.size, mu_target, _ptr(active), C.addressof(got), C.addressof(paid))
+    return active, got.value, paid.value, rc
+
+
+def peer_score(avg_speed, success_rate, consecutive_failures: int, succ_count: int, elapsed_s) -> float:
+    return lib.echo_peer_score(avg_speed, success_rate, consecutive_failures, succ_count, elapsed_s)
+
+
+def n_chains(B0, Bw) -> int:
+    return lib.echo_n_chains(B0, Bw)
+
+
+def chain_assign(score, chains: int):
+    score = np.ascontiguousarray(score, np.float64)
+    chain = np.zeros(score.size, np.int32)
+    hop = np.zeros(score.size, np.int32)
+    rc = lib.echo_chain_assign(_ptr(score), score.size, chains, _ptr(chain), _ptr(hop))
+    if rc != 0:
+        raise ValueError("echo_chain_assign: bad arguments")
+    return chain, hop

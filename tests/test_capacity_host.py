@@ -1,0 +1,74 @@
+"""The library's pool-capacity and dissemination arithmetic (host code behind include/echo_capacity.h) against
+its oracle, and the header's symbols against the library's exports.  No GPU is touched."""
+import math
+import os
+import random
+import re
+
+import numpy as np
+import pytest
+
+from oracle import capacity as cap
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def echo():
+    from paper_2602_02192_amd import echo as e
+    return e
+
+
+def test_every_declared_symbol_is_exported(echo):
+    text = open(os.path.join(ROOT, "include", "echo_capacity.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = sorted(set(re.findall(r"\b(echo_[a-z_]+)\s*\(", text)))
+    assert names == sorted(echo.CAPACITY_EXPORTS) and len(names) == 7
+    for n in names:
+        assert hasattr(echo.lib, n)
+
+
+def test_capacity_formulas_match_the_oracle(echo):
+    rng = random.Random(0)
+    for _ in range(500):
+        kappa = rng.randint(1, 9)
+        R, T = rng.uniform(1, 5000), rng.uniform(1, 3000)
+        Tb = rng.uniform(0, 0.99 * kappa * T)
+        mu = rng.uniform(0.01, 50.0)
+        assert echo.mu_min(kappa, R, T, Tb) == pytest.approx(cap.mu_min(kappa, R, T, Tb), rel=1e-14)
+        assert echo.overlap_holds(kappa, R, T, Tb, mu) == int(cap.overlap_holds(kappa, R, T, Tb, mu))
+        assert echo.staleness_bound(kappa, R, T, Tb, mu) == cap.staleness_bound(kappa, R, T, Tb, mu)
+    assert math.isnan(echo.mu_min(2, 100.0, 10.0, 20.0)) and math.isnan(echo.mu_min(0, 100.0, 10.0, 1.0))
+    assert echo.overlap_holds(2, 100.0, 10.0, 1.0, 0.0) == -1 and echo.staleness_bound(0, 1.0, 1.0, 0.0, 1.0) == -1
+
+
+def test_peer_scores_and_chains_match_the_oracle(echo):
+    rng = random.Random(1)
+    for _ in range(500):
+        args = (10 ** rng.uniform(2, 9), rng.random(), rng.randint(0, 6), rng.randint(0, 20), rng.uniform(0, 900))
+        assert echo.peer_score(*args) == pytest.approx(cap.peer_score(*args), rel=1e-13, abs=1e-12)
+    assert math.isnan(echo.peer_score(0.0, 0.5, 0, 0, 0.0)) and math.isnan(echo.peer_score(1e6, 1.5, 0, 0, 0.0))
+    for b0, bw in ((300, 100), (650.5, 100), (99, 100), (1e9, 1)):
+        assert echo.n_chains(b0, bw) == cap.n_chains(b0, bw)
+    assert echo.n_chains(0, 100) == -1 and echo.n_chains(1e12, 1) == 2 ** 31 - 1      # saturates at the int32 range
+    for n, chains in ((0, 1), (1, 3), (23, 4), (64, 8), (10, 10)):
+        score = [round(rng.random(), 1) for _ in range(n)]          # rounded: ties are part of the case
+        chain, hop = echo.chain_assign(score, chains)
+        want_chain, want_hop = cap.chain_assign(score, chains)
+        assert chain.tolist() == want_chain and hop.tolist() == want_hop
+
+
+def test_greedy_activation_matches_the_oracle(echo):
+    rng = random.Random(2)
+    for _ in range(300):
+        n = rng.randint(0, 40)
+        mu = [round(rng.uniform(0.1, 5.0), 1) for _ in range(n)]
+        cost = [round(rng.uniform(0.0, 5.0), 1) for _ in range(n)]
+        av = [int(rng.random() < 0.8) for _ in range(n)] if rng.random() < 0.5 else None
+        target = rng.uniform(0.0, 1.2 * (sum(mu) + 0.1))
+        active, got, paid, rc = echo.greedy_activate(mu, cost, target, av)
+        want, wgot, wpaid, reached = cap.greedy_activate(mu, cost, target, av)
+        assert active.tolist() == want
+        assert got == pytest.approx(wgot, rel=1e-13) and paid == pytest.approx(wpaid, rel=1e-13)
+        assert rc == (sum(want) if reached else -sum(want) - 1)
+    assert echo.greedy_activate([1.0, -1.0], [1.0, 1.0], 1.0)[3] == -2 ** 31
