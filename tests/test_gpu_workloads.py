@@ -392,6 +392,23 @@ def test_dense4b_shape_in_the_benchmark_launch_configuration():
     # rows of the 64-row batch equal the same sequences run in a batch of two (batch invariance, bf16 path)
     assert np.abs(lg["logprobs"][0] - out["logprobs"][0])[lg["tokens"][0] == out["tokens"][0]].max() < 2e-3
 
+    # -- the continuous entry point on the same shape: 16 prompts through the 64 cache slots, so the second eight are
+    # admitted as the first finish; sequence 0 against the oracle, the first 64 against the ordinary rollout above
+    prompts16 = np.concatenate([prompts, synth.make_prompts(shape.vocab, P, 12, seed=5)[0]])
+    lens16 = np.concatenate([lens, lens])
+    forced16 = np.concatenate([forced, forced[::-1]])
+    stop16 = synth.make_stop_lens(2 * N, 3, max_new, seed=7)
+    stop16[0] = max_new
+    cont = ctx.rollout(prompts16, lens16, G, max_new, 1.0, 2, forced=forced16, stop_lens=stop16, continuous=True)
+    assert np.array_equal(cont["lens"], stop16)
+    same = cont["tokens"][0] == refs[0]["tokens"][0]
+    assert same.mean() >= 0.8 and np.abs(cont["logprobs"][0] - refs[0]["logprobs"][0])[same].max() < BF16_LOGPROB_TOL
+    m64 = valid_mask(stop16[:N], max_new)
+    agree = (cont["tokens"][:N] == out["tokens"]) & m64
+    assert agree[m64].mean() > 0.97                                   # same streams, same forced inputs: near-ties aside
+    assert np.abs(cont["logprobs"][:N] - out["logprobs"])[agree].max() < 2 * BF16_LOGPROB_TOL
+    assert (cont["tokens"][N:][valid_mask(stop16[N:], max_new)] >= 0).all() and np.isfinite(cont["logprobs"]).all()
+
     # -- the benchmark's own configuration: prompt 512, 1024 new tokens, graph replay
     prompts, lens = synth.make_prompts(shape.vocab, P, 512, seed=1)
     big = ctx.rollout(prompts, lens, G, 1024, 1.0, 2)
