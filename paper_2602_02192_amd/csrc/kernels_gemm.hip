@@ -532,9 +532,12 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(void *out, const u32x4v 
   u32x4v *xs = (u32x4v *)lds_raw;
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, tid = threadIdx.x;
   const int nblocks = Np >> 5, nz = Mp / ROWS;
-  const int c_lo = blockIdx.y * groups_per_split * NSTAGE, nchunks = min(Kp >> 4, c_lo + groups_per_split * NSTAGE);
+  // (the 256 x 256 form is never split: constants there keep its loop as it was measured)
+  const int c_lo = WR == 1 ? 0 : blockIdx.y * groups_per_split * NSTAGE;
+  const int nchunks = WR == 1 ? Kp >> 4 : min(Kp >> 4, c_lo + groups_per_split * NSTAGE);
+  const int plane = WR == 1 ? 0 : blockIdx.y;
   const int bx = ZFAST ? blockIdx.x / nz : blockIdx.x, bz = ZFAST ? blockIdx.x % nz : blockIdx.z;
-  const int nb0 = (bx * L::WC + w % L::WC) * NBW, mrow0 = bz * ROWS, wrow = (w / L::WC) * 32 * MB;
+  const int nb0 = (bx * L::WC + (WR == 1 ? w : w % L::WC)) * NBW, mrow0 = bz * ROWS, wrow = WR == 1 ? 0 : (w / L::WC) * 32 * MB;
   const int64_t a_step = w_kstep_stride(Np);
   const h16x8 *a_ptr[NBW];
 #pragma unroll
@@ -575,7 +578,7 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(void *out, const u32x4v 
       for (int n = 0; n < NBW; ++n) acc[n][j] = mfma_h16(a[st][n], __builtin_bit_cast(h16x8, b[j]), acc[n][j]);
   };
 #pragma unroll
-  for (int s = 0; s < NSTAGE - 1; ++s) { load_x(s, min(c_lo + s, nchunks - 1)); load_a(s, min(c_lo + s, nchunks - 1)); }
+  for (int s = 0; s < NSTAGE - 1; ++s) { load_x(s, c_lo + s); load_a(s, c_lo + s); }   // a run has at least eight k-steps
   store_x(0, 0);
   __syncthreads();
   for (int c0 = c_lo; c0 < nchunks; c0 += NSTAGE) {
@@ -594,7 +597,7 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(void *out, const u32x4v 
     float *tile = (float *)lds_raw + (size_t)w * 32 * L::TILE_STRIDE;
 #pragma unroll
     for (int n = 0; n < NBW; ++n) {
-      float *P = (float *)out + ((int64_t)blockIdx.y * Mp + mrow0 + wrow) * Np + (nb0 + n) * 32;
+      float *P = (float *)out + ((int64_t)plane * Mp + mrow0 + wrow) * Np + (nb0 + n) * 32;
 #pragma unroll
       for (int j = 0; j < MB; ++j) {
 #pragma unroll
@@ -647,7 +650,7 @@ static void gemm_wide_launch(void *out, const void *Xp, const void *Wp, int Mp, 
     attr_set = true;
   }
   int nblocks = Np / 32, per_wg = L::WC * L::NBW, strips = (nblocks + per_wg - 1) / per_wg, nz = Mp / L::ROWS;
-  int groups = (Kp / 16) / L::NSTAGE, gps = (groups + nsplit - 1) / nsplit, ny = (groups + gps - 1) / gps;
+  int groups = (Kp / 16) / L::NSTAGE, gps = (groups + nsplit - 1) / nsplit, ny = WR == 1 ? 1 : (groups + gps - 1) / gps;
   dim3 grid = ZFAST ? dim3(strips * nz, ny, 1) : dim3(strips, ny, nz);
   hipLaunchKernelGGL((gemm_wide_kernel<EPI, ZFAST, WR>), grid, dim3(L::T), L::BYTES, st, out, (const u32x4v *)Xp, (const h16x8 *)Wp, Mp,
                      Np, Kp, gps);
