@@ -576,6 +576,57 @@ double drain_events(std::vector<std::pair<hipEvent_t, hipEvent_t>> &v, int64_t *
   return ms;
 }
 
+// Argument checks shared by the two rollout entry points; o receives the options (defaults when opts is NULL).
+int check_rollout_args(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_stride, const int32_t *prompt_lens, int32_t P, int32_t G,
+                       int32_t max_new, float temperature, const echo_rollout_opts *opts, const int32_t *out_tokens,
+                       const float *out_logprobs, const int32_t *out_lens, echo_rollout_opts *o) {
+  memset(o, 0, sizeof *o);
+  o->eos_id = -1; o->top_p = 1.0f;
+  if (opts) *o = *opts;
+  if (!prompt_tokens || !prompt_lens || !out_tokens || !out_logprobs || !out_lens) return fail(c, ECHO_EINVAL, "NULL argument");
+  if (P < 1 || G < 1 || max_new < 1 || prompt_stride < 1) return fail(c, ECHO_EINVAL, "n_prompts, G, max_new and prompt_stride must be positive");
+  if (!(temperature > 0.f)) return fail(c, ECHO_EINVAL, "temperature must be positive");
+  if (!(o->top_p > 0.f) || o->top_p > 1.0f) return fail(c, ECHO_EINVAL, "top_p must be in (0, 1]");
+  if ((int64_t)P * G * max_new > INT32_MAX) return fail(c, ECHO_EINVAL, "n_prompts * G * max_new exceeds 2^31 - 1");
+  int max_pl = 0;
+  for (int p = 0; p < P; ++p) {
+    if (prompt_lens[p] < 1 || prompt_lens[p] > prompt_stride) return fail(c, ECHO_EINVAL, "prompt_lens[%d] = %d out of range", p, prompt_lens[p]);
+    max_pl = std::max(max_pl, prompt_lens[p]);
+    for (int t = 0; t < prompt_lens[p]; ++t) {
+      int tk = prompt_tokens[(int64_t)p * prompt_stride + t];
+      if (tk < 0 || tk >= c->d.vocab) return fail(c, ECHO_EINVAL, "prompt token %d of prompt %d is outside the vocabulary", t, p);
+    }
+  }
+  if ((int64_t)max_pl + max_new > c->d.max_ctx) return fail(c, ECHO_ENOMEM, "prompt %d + max_new %d exceeds max_ctx = %d", max_pl, max_new, c->d.max_ctx);
+  if (o->forced_tokens)
+    for (int64_t i = 0; i < (int64_t)P * G * max_new; ++i)
+      if (o->forced_tokens[i] < 0 || o->forced_tokens[i] >= c->d.vocab) return fail(c, ECHO_EINVAL, "forced token outside the vocabulary");
+  return ECHO_OK;
+}
+
+// Marks the context as running a rollout for the lifetime of the object; begin() fails when it cannot start.  When the
+// rollout ends a staged snapshot becomes the active one and the samplers' draw ids return to their default.
+struct RolloutGuard {
+  echo_ctx *c;
+  bool held = false;
+  explicit RolloutGuard(echo_ctx *c_) : c(c_) {}
+  int begin() {
+    std::lock_guard<std::mutex> lk(c->mu);
+    if (c->active < 0) return fail(c, ECHO_ESTATE, "no policy snapshot installed");
+    if (c->load.open && c->load.target == c->active) return fail(c, ECHO_ESTATE, "a snapshot is arriving in the only weight slot");
+    if (c->rollout_running) return fail(c, ECHO_ESTATE, "a rollout is already running on this context");
+    c->rollout_running = held = true;
+    return ECHO_OK;
+  }
+  ~RolloutGuard() {
+    if (!held) return;
+    std::lock_guard<std::mutex> lk(c->mu);
+    c->rollout_running = false;
+    c->ids = DrawIds{c->d_step, nullptr, nullptr};
+    if (c->staged >= 0) { c->active = c->staged; c->staged = -1; c->st.active_version = c->slots[c->active].version; c->st.staged_version = -1; }
+  }
+};
+
 }  // namespace
 
 // =================================================================================================== C ABI
@@ -742,44 +793,17 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
                  float *out_logprobs, int32_t *out_lens, int64_t *out_versions) {
   if (!c) return ECHO_EINVAL;
   echo_rollout_opts o;
-  memset(&o, 0, sizeof o);
-  o.eos_id = -1; o.top_p = 1.0f;
-  if (opts) o = *opts;
-  if (!prompt_tokens || !prompt_lens || !out_tokens || !out_logprobs || !out_lens) return fail(c, ECHO_EINVAL, "NULL argument");
-  if (P < 1 || G < 1 || max_new < 1 || prompt_stride < 1) return fail(c, ECHO_EINVAL, "n_prompts, G, max_new and prompt_stride must be positive");
-  if (!(temperature > 0.f)) return fail(c, ECHO_EINVAL, "temperature must be positive");
-  if (!(o.top_p > 0.f) || o.top_p > 1.0f) return fail(c, ECHO_EINVAL, "top_p must be in (0, 1]");
-  int64_t N64 = (int64_t)P * G;
-  if (N64 > c->d.max_seqs) return fail(c, ECHO_ENOMEM, "%lld sequences exceed max_seqs = %d", (long long)N64, c->d.max_seqs);
-  int N = (int)N64, max_pl = 0;
-  for (int p = 0; p < P; ++p) {
-    if (prompt_lens[p] < 1 || prompt_lens[p] > prompt_stride) return fail(c, ECHO_EINVAL, "prompt_lens[%d] = %d out of range", p, prompt_lens[p]);
-    max_pl = std::max(max_pl, prompt_lens[p]);
-    for (int t = 0; t < prompt_lens[p]; ++t) {
-      int tk = prompt_tokens[(int64_t)p * prompt_stride + t];
-      if (tk < 0 || tk >= c->d.vocab) return fail(c, ECHO_EINVAL, "prompt token %d of prompt %d is outside the vocabulary", t, p);
-    }
-  }
-  if ((int64_t)max_pl + max_new > c->d.max_ctx) return fail(c, ECHO_ENOMEM, "prompt %d + max_new %d exceeds max_ctx = %d", max_pl, max_new, c->d.max_ctx);
+  int rc = check_rollout_args(c, prompt_tokens, prompt_stride, prompt_lens, P, G, max_new, temperature, opts, out_tokens, out_logprobs,
+                              out_lens, &o);
+  if (rc) return rc;
+  if ((int64_t)P * G > c->d.max_seqs) return fail(c, ECHO_ENOMEM, "%lld sequences exceed max_seqs = %d", (long long)P * G, c->d.max_seqs);
+  const int N = P * G;
   if (o.n_swaps < 0 || (o.n_swaps > 0 && !o.swap_at_step)) return fail(c, ECHO_EINVAL, "bad swap schedule");
   for (int j = 0; j < o.n_swaps; ++j)
     if (o.swap_at_step[j] < 1 || (j && o.swap_at_step[j] <= o.swap_at_step[j - 1])) return fail(c, ECHO_EINVAL, "swap_at_step must be ascending and >= 1");
   if (o.n_swaps > 0 && c->d.n_weight_slots < 2) return fail(c, ECHO_ESTATE, "snapshot swaps inside a rollout need n_weight_slots = 2");
-  if (o.forced_tokens)
-    for (int64_t i = 0; i < (int64_t)N * max_new; ++i)
-      if (o.forced_tokens[i] < 0 || o.forced_tokens[i] >= c->d.vocab) return fail(c, ECHO_EINVAL, "forced token outside the vocabulary");
-  {
-    std::lock_guard<std::mutex> lk(c->mu);
-    if (c->active < 0) return fail(c, ECHO_ESTATE, "no policy snapshot installed");
-    if (c->load.open && c->load.target == c->active) return fail(c, ECHO_ESTATE, "a snapshot is arriving in the only weight slot");
-    if (c->rollout_running) return fail(c, ECHO_ESTATE, "a rollout is already running on this context");
-    c->rollout_running = true;
-  }
-  struct Done { echo_ctx *c; ~Done() {
-    std::lock_guard<std::mutex> lk(c->mu);
-    c->rollout_running = false;
-    if (c->staged >= 0) { c->active = c->staged; c->staged = -1; c->st.active_version = c->slots[c->active].version; c->st.staged_version = -1; }
-  } } done{c};
+  RolloutGuard guard(c);
+  if ((rc = guard.begin())) return rc;
 
   HIPCHK(c, hipSetDevice(c->device));
   const Plan &p = c->p;
@@ -821,7 +845,7 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
   std::vector<int> lens(prompt_lens, prompt_lens + P);
   std::vector<int32_t> map(std::max(P, N));
   float *first_h = at<float>(c, p.o_first_h);
-  int rc = run_chunks(c, c->slots[cur], prompt_tokens, prompt_stride, lens, G, [&](const ChunkRow *rows, int M) -> int {
+  rc = run_chunks(c, c->slots[cur], prompt_tokens, prompt_stride, lens, G, [&](const ChunkRow *rows, int M) -> int {
     std::fill(map.begin(), map.begin() + P, -1);
     bool any = false;
     for (int i = 0; i < M; ++i) {
@@ -955,44 +979,15 @@ int echo_rollout_continuous(echo_ctx *c, const int32_t *prompt_tokens, int32_t p
                             int32_t *out_tokens, float *out_logprobs, int32_t *out_lens, int64_t *out_versions) {
   if (!c) return ECHO_EINVAL;
   echo_rollout_opts o;
-  memset(&o, 0, sizeof o);
-  o.eos_id = -1; o.top_p = 1.0f;
-  if (opts) o = *opts;
-  if (!prompt_tokens || !prompt_lens || !out_tokens || !out_logprobs || !out_lens) return fail(c, ECHO_EINVAL, "NULL argument");
-  if (P < 1 || G < 1 || max_new < 1 || prompt_stride < 1) return fail(c, ECHO_EINVAL, "n_prompts, G, max_new and prompt_stride must be positive");
-  if (!(temperature > 0.f)) return fail(c, ECHO_EINVAL, "temperature must be positive");
-  if (!(o.top_p > 0.f) || o.top_p > 1.0f) return fail(c, ECHO_EINVAL, "top_p must be in (0, 1]");
+  int rc = check_rollout_args(c, prompt_tokens, prompt_stride, prompt_lens, P, G, max_new, temperature, opts, out_tokens, out_logprobs,
+                              out_lens, &o);
+  if (rc) return rc;
   if (o.n_swaps || o.debug_logits || o.time_kernels)
     return fail(c, ECHO_EINVAL, "a continuous rollout takes no pinned swaps (it switches when a snapshot is staged), no debug_logits and no time_kernels");
   if (G > c->d.max_seqs) return fail(c, ECHO_ENOMEM, "one group of %d sequences exceeds max_seqs = %d", G, c->d.max_seqs);
-  if ((int64_t)P * G * max_new > INT32_MAX) return fail(c, ECHO_EINVAL, "n_prompts * G * max_new exceeds 2^31 - 1");
-  int max_pl = 0;
-  for (int p = 0; p < P; ++p) {
-    if (prompt_lens[p] < 1 || prompt_lens[p] > prompt_stride) return fail(c, ECHO_EINVAL, "prompt_lens[%d] = %d out of range", p, prompt_lens[p]);
-    max_pl = std::max(max_pl, prompt_lens[p]);
-    for (int t = 0; t < prompt_lens[p]; ++t) {
-      int tk = prompt_tokens[(int64_t)p * prompt_stride + t];
-      if (tk < 0 || tk >= c->d.vocab) return fail(c, ECHO_EINVAL, "prompt token %d of prompt %d is outside the vocabulary", t, p);
-    }
-  }
-  if ((int64_t)max_pl + max_new > c->d.max_ctx) return fail(c, ECHO_ENOMEM, "prompt %d + max_new %d exceeds max_ctx = %d", max_pl, max_new, c->d.max_ctx);
   const int N = P * G;
-  if (o.forced_tokens)
-    for (int64_t i = 0; i < (int64_t)N * max_new; ++i)
-      if (o.forced_tokens[i] < 0 || o.forced_tokens[i] >= c->d.vocab) return fail(c, ECHO_EINVAL, "forced token outside the vocabulary");
-  {
-    std::lock_guard<std::mutex> lk(c->mu);
-    if (c->active < 0) return fail(c, ECHO_ESTATE, "no policy snapshot installed");
-    if (c->load.open && c->load.target == c->active) return fail(c, ECHO_ESTATE, "a snapshot is arriving in the only weight slot");
-    if (c->rollout_running) return fail(c, ECHO_ESTATE, "a rollout is already running on this context");
-    c->rollout_running = true;
-  }
-  struct Done { echo_ctx *c; ~Done() {
-    std::lock_guard<std::mutex> lk(c->mu);
-    c->rollout_running = false;
-    c->ids = DrawIds{c->d_step, nullptr, nullptr};
-    if (c->staged >= 0) { c->active = c->staged; c->staged = -1; c->st.active_version = c->slots[c->active].version; c->st.staged_version = -1; }
-  } } done{c};
+  RolloutGuard guard(c);
+  if ((rc = guard.begin())) return rc;
 
   HIPCHK(c, hipSetDevice(c->device));
   const Plan &p = c->p;
@@ -1028,7 +1023,6 @@ int echo_rollout_continuous(echo_ctx *c, const int32_t *prompt_tokens, int32_t p
   int cur = c->active, next_prompt = 0, done_seqs = 0, decode_steps = 0, until_check = 0;
   bool have_graph = false, first = true;
   double admit_ms = 0, swap_wait = 0;
-  int rc;
   std::vector<int> free_rows;
   std::vector<int32_t> quads;
   const int max_quads = 2 * c->p.Mcap / 4;   // the two row maps serve as the copy list
