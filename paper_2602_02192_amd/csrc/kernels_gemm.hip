@@ -506,8 +506,9 @@ __global__ __launch_bounds__(WN * 64) void gemm_lds_kernel(void *out, const u32x
 // WR = 2 arranges the four wavefronts as two row halves x two column pairs (tile 256 x 128, 128 accumulator registers per
 // lane): for batches of exactly a few hundred rows, where 256 x 256 tiles are too few to fill the chip.
 template <int WRv> struct GemmWideT {
-  static constexpr int WR = WRv, MB = 8 / WR, WN = 4, WC = WN / WR, NBW = 2, NSTAGE = 8, ROWS = 256, T = WN * 64;
-  static constexpr int CHUNK_UNITS = 2 * ROWS, XL = CHUNK_UNITS / T;   // a chunk is one k-step
+  static constexpr int WR = WRv, MB = 8 / WR, WN = 4, WC = WN / WR, NBW = 2, ROWS = 256, T = WN * 64;
+  static constexpr int CK = 1, NSTAGE = 8 / CK;   // k-steps per chunk (one barrier each), chunks in flight; CK = 2 measured 1-2 % slower
+  static constexpr int CHUNK_UNITS = CK * 2 * ROWS, XL = CHUNK_UNITS / T;
   static constexpr int X_BYTES = 2 * CHUNK_UNITS * 16, TILE_STRIDE = 33, EPI_BYTES = WN * 32 * TILE_STRIDE * 4;
   static constexpr int BYTES = X_BYTES > EPI_BYTES ? X_BYTES : EPI_BYTES;
 };
@@ -527,14 +528,14 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(void *out, const u32x4v 
                                                         int Np, int Kp, int groups_per_split) {
   extern __shared__ __attribute__((aligned(16))) char lds_raw[];
   using L = GemmWideT<WR>;
-  constexpr int MB = L::MB, NBW = L::NBW, T = L::T, XU = L::CHUNK_UNITS, XL = L::XL, ROWS = L::ROWS, NSTAGE = L::NSTAGE;
-  static_assert((GEMM_K_PAD / 16) % NSTAGE == 0, "k-step count must be a multiple of the stage count");
+  constexpr int MB = L::MB, NBW = L::NBW, T = L::T, XU = L::CHUNK_UNITS, XL = L::XL, ROWS = L::ROWS, NSTAGE = L::NSTAGE, CK = L::CK;
+  static_assert((GEMM_K_PAD / 16) % (NSTAGE * CK) == 0, "k-step count must be a multiple of the k-steps in flight");
   u32x4v *xs = (u32x4v *)lds_raw;
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, tid = threadIdx.x;
   const int nblocks = Np >> 5, nz = Mp / ROWS;
-  // (the 256 x 256 form is never split: constants there keep its loop as it was measured)
+  // chunk range of this workgroup (the 256 x 256 form is never split: constants there keep its loop as it was measured)
   const int c_lo = WR == 1 ? 0 : blockIdx.y * groups_per_split * NSTAGE;
-  const int nchunks = WR == 1 ? Kp >> 4 : min(Kp >> 4, c_lo + groups_per_split * NSTAGE);
+  const int nchunks = WR == 1 ? (Kp >> 4) / CK : min((Kp >> 4) / CK, c_lo + groups_per_split * NSTAGE);
   const int plane = WR == 1 ? 0 : blockIdx.y;
   const int bx = ZFAST ? blockIdx.x / nz : blockIdx.x, bz = ZFAST ? blockIdx.x % nz : blockIdx.z;
   const int nb0 = (bx * L::WC + (WR == 1 ? w : w % L::WC)) * NBW, mrow0 = bz * ROWS, wrow = WR == 1 ? 0 : (w / L::WC) * 32 * MB;
@@ -550,17 +551,19 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(void *out, const u32x4v 
     for (int j = 0; j < MB; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[n][j][r] = 0.f;
-  h16x8 a[NSTAGE][NBW];
+  h16x8 a[NSTAGE][CK][NBW];
   u32x4v xr[NSTAGE][XL];
   auto load_a = [&](int st, int c) {
 #pragma unroll
-    for (int n = 0; n < NBW; ++n) a[st][n] = __builtin_nontemporal_load(a_ptr[n] + (int64_t)c * a_step);
+    for (int u = 0; u < CK; ++u)
+#pragma unroll
+      for (int n = 0; n < NBW; ++n) a[st][u][n] = __builtin_nontemporal_load(a_ptr[n] + (int64_t)(c * CK + u) * a_step);
   };
-  auto load_x = [&](int st, int c) {   // unit i of a k-step: k8 group i / ROWS, batch row i % ROWS
+  auto load_x = [&](int st, int c) {   // unit i of a chunk: k8 group i / ROWS (two per k-step), batch row i % ROWS
 #pragma unroll
     for (int i = 0; i < XL; ++i) {
       int idx = i * T + tid;
-      xr[st][i] = Xp[(int64_t)(c * 2 + idx / ROWS) * Mp + mrow0 + idx % ROWS];
+      xr[st][i] = Xp[(int64_t)(c * CK * 2 + idx / ROWS) * Mp + mrow0 + idx % ROWS];
     }
   };
   auto store_x = [&](int st, int buf) {
@@ -569,16 +572,20 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(void *out, const u32x4v 
   };
   auto compute = [&](int st, int buf) {
     const u32x4v *bp = xs + buf * XU + (lane >> 5) * ROWS + wrow + (lane & 31);
-    u32x4v b[MB];
+    u32x4v b[CK][MB];
 #pragma unroll
-    for (int j = 0; j < MB; ++j) b[j] = bp[j * 32];
+    for (int u = 0; u < CK; ++u)
 #pragma unroll
-    for (int j = 0; j < MB; ++j)
+      for (int j = 0; j < MB; ++j) b[u][j] = bp[u * 2 * ROWS + j * 32];
 #pragma unroll
-      for (int n = 0; n < NBW; ++n) acc[n][j] = mfma_h16(a[st][n], __builtin_bit_cast(h16x8, b[j]), acc[n][j]);
+    for (int u = 0; u < CK; ++u)
+#pragma unroll
+      for (int j = 0; j < MB; ++j)
+#pragma unroll
+        for (int n = 0; n < NBW; ++n) acc[n][j] = mfma_h16(a[st][u][n], __builtin_bit_cast(h16x8, b[u][j]), acc[n][j]);
   };
 #pragma unroll
-  for (int s = 0; s < NSTAGE - 1; ++s) { load_x(s, c_lo + s); load_a(s, c_lo + s); }   // a run has at least eight k-steps
+  for (int s = 0; s < NSTAGE - 1; ++s) { load_x(s, c_lo + s); load_a(s, c_lo + s); }   // a run has at least NSTAGE chunks
   store_x(0, 0);
   __syncthreads();
   for (int c0 = c_lo; c0 < nchunks; c0 += NSTAGE) {
@@ -650,7 +657,7 @@ static void gemm_wide_launch(void *out, const void *Xp, const void *Wp, int Mp, 
     attr_set = true;
   }
   int nblocks = Np / 32, per_wg = L::WC * L::NBW, strips = (nblocks + per_wg - 1) / per_wg, nz = Mp / L::ROWS;
-  int groups = (Kp / 16) / L::NSTAGE, gps = (groups + nsplit - 1) / nsplit, ny = WR == 1 ? 1 : (groups + gps - 1) / gps;
+  int groups = (Kp / 16) / (L::NSTAGE * L::CK), gps = (groups + nsplit - 1) / nsplit, ny = WR == 1 ? 1 : (groups + gps - 1) / gps;
   dim3 grid = ZFAST ? dim3(strips * nz, ny, 1) : dim3(strips, ny, nz);
   hipLaunchKernelGGL((gemm_wide_kernel<EPI, ZFAST, WR>), grid, dim3(L::T), L::BYTES, st, out, (const u32x4v *)Xp, (const h16x8 *)Wp, Mp,
                      Np, Kp, gps);
