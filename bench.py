@@ -21,13 +21,14 @@ HBM_PEAK_GBS = 8000.0
 # counters on a plain 256 MiB copy: KiB fetched + written per launch over the KiB of the K/V tiles the launch touches
 # (shared prompt tiles once per group, a sequence's last tile whole).  Taken at the same kernel and grid on a 2-layer
 # model generating 64 tokens (the profiler crashes on the 36-layer process); set to None whenever attn_splitk_kernel changes.
-ATTN_TRAFFIC_OVER_TILE_BYTES = (29291.0 + 512.0) / (28608.0 + 512.0)
+ATTN_TRAFFIC_OVER_TILE_BYTES = (29307.0 + 512.0) / (28608.0 + 512.0)
 
 
-def attn_kv_bytes_per_launch(shape, gen_lens, prompt_len, group, steps, whole_tiles):
+def attn_kv_bytes_per_launch(shape, gen_lens, prompt_len, group, steps, whole_tiles, shared_elsewhere=False):
     """K/V bytes one decode-attention launch (one layer) reads, averaged over the decode passes `steps`: the whole
     32-key tiles of a prompt once per group with an active sequence, everything else per active sequence.
-    whole_tiles: count the tiles the kernel touches (a sequence's last tile is fetched whole) instead of the keys."""
+    whole_tiles: count the tiles the kernel touches (a sequence's last tile is fetched whole) instead of the keys.
+    shared_elsewhere: the groups' whole prompt tiles are attended by attn_prefix_kernel, not by this kernel."""
     gen = np.asarray(gen_lens, np.int64)
     shared = (prompt_len // 32) * 32 if group > 1 else 0
     group_len = gen.reshape(-1, group).max(axis=1)
@@ -37,7 +38,7 @@ def attn_kv_bytes_per_launch(shape, gen_lens, prompt_len, group, steps, whole_ti
         own = prompt_len - shared + st
         if whole_tiles:
             own = -(-own // 32) * 32
-        tot += (int((group_len > st).sum()) * shared + int((gen > st).sum()) * own) * per_key
+        tot += (int((group_len > st).sum()) * (0 if shared_elsewhere else shared) + int((gen > st).sum()) * own) * per_key
     return tot / max(1, len(steps))
 
 WORKLOADS = {
@@ -266,14 +267,21 @@ def main():
             per_launch_s = st.attn_ms * 1e-3 / st.attn_launches
             ach = per_launch_bytes / per_launch_s / 1e9
             timed = [t for t in range(1, int(out["lens"].max())) if t % 16 == 1]   # the passes the library times
-            model = attn_kv_bytes_per_launch(shape, out["lens"], plen, G, timed, whole_tiles=False)
+            # which accounting the library used tells whether the shared prompt tiles went through the prefix kernel
+            models = {se: attn_kv_bytes_per_launch(shape, out["lens"], plen, G, timed, whole_tiles=False, shared_elsewhere=se)
+                      for se in (True, False)}
+            prefix_kernel = abs(models[True] - per_launch_bytes) < abs(models[False] - per_launch_bytes)
             traffic = None
-            if ATTN_TRAFFIC_OVER_TILE_BYTES and abs(model - per_launch_bytes) <= 1e-3 * per_launch_bytes:
-                traffic = attn_kv_bytes_per_launch(shape, out["lens"], plen, G, timed, whole_tiles=True) * ATTN_TRAFFIC_OVER_TILE_BYTES
-            roofline = {"bound": "hbm", "kernel": "attn_splitk_kernel (decode attention, one launch per layer)",
+            # (the counters were taken with the kernel reading its shared tiles itself; with the prefix kernel it also reads
+            # that kernel's partials, which the factor does not cover)
+            if ATTN_TRAFFIC_OVER_TILE_BYTES and not prefix_kernel and abs(models[False] - per_launch_bytes) <= 1e-3 * per_launch_bytes:
+                traffic = attn_kv_bytes_per_launch(shape, out["lens"], plen, G, timed, whole_tiles=True,
+                                                   shared_elsewhere=prefix_kernel) * ATTN_TRAFFIC_OVER_TILE_BYTES
+            roofline = {"bound": "hbm", "kernel": "attn_splitk_kernel (decode attention, one launch per layer" +
+                                  ("; the groups' shared prompt tiles are attended by attn_prefix_kernel before it)" if prefix_kernel else ")"),
                         "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
                         "traffic": traffic,
-                        "traffic_unit": "bytes per launch: whole K/V tiles of the timed launches x 1.0235 (FETCH_SIZE + WRITE_SIZE over "
+                        "traffic_unit": "bytes per launch: whole K/V tiles of the timed launches x 1.0240 (FETCH_SIZE + WRITE_SIZE over "
                                         "whole-tile bytes, same kernel and grid, profiles/pmc_traffic_*.md)",
                         "launches_timed": int(st.attn_launches),
                         "avg_launch_us": per_launch_s * 1e6, "bytes_per_launch": per_launch_bytes}

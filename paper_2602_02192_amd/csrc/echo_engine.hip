@@ -43,7 +43,7 @@ struct Plan {
   int Np_qkv, Np_d, Np_gu, Np_v, Kp_d, Kp_q, Kp_f;
   size_t slot_bytes, o_slot[2], o_kv, kv_bytes;
   size_t o_h, o_x, o_qkv, o_att, o_gu, o_ff, o_logits, o_q16, o_xa, o_xatt, o_xff, o_part, o_rope, o_lmpart;
-  size_t o_attn_o, o_attn_ml, o_topp;
+  size_t o_attn_o, o_attn_ml, o_topp, o_pjobs;
   size_t o_blocks, o_rows, o_seq, o_samp, o_out_tok, o_out_lp, o_out_ver, o_forced, o_scal, o_first_h, o_stage, o_maps;
   size_t stage_bytes, part_floats, logit_rows = 0, total;
   int attn_chunk, attn_max_splits;
@@ -143,6 +143,7 @@ Plan make_plan(const echo_model_desc *d) {
   }
   p.o_blocks = b.take(M * sizeof(PrefillBlock));   // at worst every row of a pass is a block of its own
   p.o_topp = b.take(fast_topp_scratch_floats((int)pad_rows(d->max_seqs)) * 4);
+  p.o_pjobs = b.take((pad_rows(d->max_seqs) / 2 + 1) * sizeof(PrefixJob));   // a job has at least two rows
   p.o_rows = b.take(6 * M * 4);
   p.o_maps = b.take(2 * M * 4 + (size_t)d->max_seqs * 4);
   p.o_seq = b.take(4 * (size_t)pad_rows(d->max_seqs) * 4);   // samplers read the step and stream of padding rows too
@@ -206,6 +207,7 @@ struct echo_ctx {
   float *d_samp_lp, *d_target_lp;
   int32_t *d_stream;  // per-row stream ids of a continuous rollout
   DrawIds ids{nullptr, nullptr, nullptr};
+  PrefixPlan px{nullptr, 0, 0, 1};       // shared-prompt attention jobs of the running rollout (n_jobs = 0: none)
   hipGraphExec_t graph = nullptr;
   // kernel timing (time_kernels)
   std::vector<std::pair<hipEvent_t, hipEvent_t>> ev_attn, ev_gemm;
@@ -425,13 +427,15 @@ void forward_layers(echo_ctx *c, const Slot &S, int M, bool use_splitk_attn, int
     const LayerW &L = S.layers[l];
     gemm_fast(c, part, xa, L.wqkv, Mp, p.Np_qkv, p.Kp_d, EPI_PARTIAL, &ns);
     fast_qkv_post(part, ns, p.Np_qkv, Mp, q16, L.q_norm, L.k_norm, d.qk_norm, d.rms_eps, rope, c->rows, c->kv, l, M, Hq, Hkv, st);
+    if (n_prefill_blocks == 0 && use_splitk_attn)   // the groups' shared prompt tiles, once per group (outside the timed launch)
+      fast_attention_prefix(q16, c->kv, l, Hq, Hkv, at<float>(c, p.o_attn_o), at<float>(c, p.o_attn_ml), c->px, st);
     {
       TimerScope t(c, &c->ev_attn);
       if (n_prefill_blocks > 0)
         fast_attention_prefill(xatt, q16, at<PrefillBlock>(c, p.o_blocks), n_prefill_blocks, c->kv, l, Mp, Hq, Hkv, st);
       else if (use_splitk_attn)
         fast_attention(xatt, q16, c->rows, c->kv, l, M, Mp, Hq, Hkv, fast_attention_splits(M, Hkv, p.attn_max_splits),
-                       at<float>(c, p.o_attn_o), at<float>(c, p.o_attn_ml), st);
+                       at<float>(c, p.o_attn_o), at<float>(c, p.o_attn_ml), c->px, st);
       else
         fast_attention_simple(xatt, q16, c->rows, c->kv, l, M, Mp, Hq, Hkv, st);
     }
@@ -576,6 +580,67 @@ double drain_events(std::vector<std::pair<hipEvent_t, hipEvent_t>> &v, int64_t *
   return ms;
 }
 
+// Plans the shared-prompt attention of a decode batch of R rows.  Rows that read whole prompt tiles from a common cache slot
+// (ptiles >= 1) and are still generating are grouped by that slot; every group of two or more is cut into jobs of up to
+// 32 / grp rows, whose rows get ATT_PREFIX_DONE in ptiles (host copy: the caller uploads it).  max_ptiles fixes the chunking
+// for the whole rollout and grid_jobs the launch's job count (unused job slots are empty), so a captured step stays valid
+// when the list is rebuilt.  Leaves c->px.n_jobs = 0 when there is nothing to share or the decode kernel splits keys.
+int plan_prefix_jobs(echo_ctx *c, std::vector<int32_t> &ptiles, const std::vector<int32_t> &pslot, const std::vector<int32_t> &live, int R,
+                     int max_ptiles, int grid_jobs) {
+  const int grp = c->d.n_q_heads / c->d.n_kv_heads, per_job = std::max(1, 32 / grp);
+  const int cap = pad_rows(c->d.max_seqs) / 2 + 1;
+  c->px = PrefixPlan{at<PrefixJob>(c, c->p.o_pjobs), 0, 0, 1};
+  for (int r = 0; r < R; ++r) ptiles[r] &= ~ATT_PREFIX_DONE;
+  if (!c->p.fast || max_ptiles < 1 || fast_attention_splits(R, c->d.n_kv_heads, c->p.attn_max_splits) != 1 || env_flag("ECHO_NO_PREFIX_KERNEL")) return 0;
+  std::vector<PrefixJob> jobs;
+  std::vector<int> order(R);
+  for (int r = 0; r < R; ++r) order[r] = r;
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return pslot[a] < pslot[b]; });
+  for (int i = 0; i < R;) {
+    int j = i;
+    std::vector<int> members;
+    while (j < R && pslot[order[j]] == pslot[order[i]]) {
+      if (live[order[j]] && ptiles[order[j]] >= 1) members.push_back(order[j]);
+      ++j;
+    }
+    if (members.size() >= 2) {
+      for (size_t k = 0; k < members.size(); k += per_job) {
+        size_t n = std::min<size_t>(per_job, members.size() - k);
+        if (n < 2 && k > 0) break;   // a lone last row reads its prompt tiles itself
+        PrefixJob jb;
+        memset(&jb, 0, sizeof jb);
+        jb.pslot = pslot[members[k]]; jb.ptiles = ptiles[members[k]]; jb.nrows = (int)n;
+        for (size_t q = 0; q < n; ++q) { jb.rows[q] = members[k + q]; ptiles[members[k + q]] |= ATT_PREFIX_DONE; }
+        jobs.push_back(jb);
+      }
+    }
+    i = j;
+  }
+  // The extra launch costs about as much as it saves at 64 rows x 16 tiles (measured: -7 % there, +1 % at 256 x 16,
+  // +5 % at 256 x 32), so small batches with short prompts keep reading their shared tiles in the decode kernel.
+  int64_t covered = 0, min_covered = 4096;
+  for (const PrefixJob &jb : jobs) covered += (int64_t)jb.nrows * jb.ptiles;
+  if (const char *v = getenv("ECHO_PREFIX_KERNEL_MIN")) min_covered = atoll(v);
+  if (jobs.empty() || (int)jobs.size() > cap || covered < min_covered) {
+    for (int r = 0; r < R; ++r) ptiles[r] &= ~ATT_PREFIX_DONE;
+    return 0;
+  }
+  int n_grid = std::max(grid_jobs, (int)jobs.size());
+  if (n_grid > cap) n_grid = cap;
+  PrefixJob empty;
+  memset(&empty, 0, sizeof empty);
+  jobs.resize(n_grid, empty);
+  int est = grid_jobs > 0 ? std::max(1, R / per_job) : (int)jobs.size();
+  int np = (256 + est * c->d.n_kv_heads - 1) / (est * c->d.n_kv_heads);
+  np = std::max(1, std::min({np, c->p.attn_max_splits, max_ptiles}));
+  int tpc = (max_ptiles + np - 1) / np;
+  np = (max_ptiles + tpc - 1) / tpc;
+  HIPCHK(c, hipMemcpyAsync(at<PrefixJob>(c, c->p.o_pjobs), jobs.data(), jobs.size() * sizeof(PrefixJob), hipMemcpyHostToDevice, c->cs));
+  HIPCHK(c, hipStreamSynchronize(c->cs));   // the host list goes out of scope
+  c->px = PrefixPlan{at<PrefixJob>(c, c->p.o_pjobs), n_grid, np, tpc};
+  return 0;
+}
+
 // Argument checks shared by the two rollout entry points; o receives the options (defaults when opts is NULL).
 int check_rollout_args(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_stride, const int32_t *prompt_lens, int32_t P, int32_t G,
                        int32_t max_new, float temperature, const echo_rollout_opts *opts, const int32_t *out_tokens,
@@ -623,6 +688,7 @@ struct RolloutGuard {
     std::lock_guard<std::mutex> lk(c->mu);
     c->rollout_running = false;
     c->ids = DrawIds{c->d_step, nullptr, nullptr};
+    c->px.n_jobs = 0;
     if (c->staged >= 0) { c->active = c->staged; c->staged = -1; c->st.active_version = c->slots[c->active].version; c->st.staged_version = -1; }
   }
 };
@@ -867,8 +933,14 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
   for (int n = 0; n < N; ++n) map[n] = n;
   HIPCHK(c, hipMemcpyAsync(c->rows.slot, map.data(), N * 4, hipMemcpyHostToDevice, st));
   {   // decode attention reads the whole tiles of a group's prompt from the group's first slot
-    std::vector<int32_t> pslot(N), ptiles(N);
-    for (int n = 0; n < N; ++n) { pslot[n] = n / G * G; ptiles[n] = share_prefix ? prompt_lens[n / G] / 32 : 0; }
+    std::vector<int32_t> pslot(N), ptiles(N), live(N, 1);
+    int max_ptiles = 0;
+    for (int n = 0; n < N; ++n) {
+      pslot[n] = n / G * G;
+      ptiles[n] = share_prefix ? prompt_lens[n / G] / 32 : 0;
+      max_ptiles = std::max(max_ptiles, ptiles[n]);
+    }
+    if ((rc = plan_prefix_jobs(c, ptiles, pslot, live, N, max_ptiles, 0))) return rc;
     HIPCHK(c, hipMemcpyAsync(c->rows.pslot, pslot.data(), N * 4, hipMemcpyHostToDevice, st));
     HIPCHK(c, hipMemcpyAsync(c->rows.ptiles, ptiles.data(), N * 4, hipMemcpyHostToDevice, st));
     HIPCHK(c, hipStreamSynchronize(st));   // the host vectors go out of scope
@@ -923,13 +995,14 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
     bool time_this = c->timing;
     if (c->timing) {
       c->timing = (s % 16) == 1;
-      // K/V bytes one attention launch has to read: a group's whole prompt tiles once, the rest per active sequence
+      // K/V bytes one launch of the decode attention kernel has to read: the rest of every active sequence, and (when it
+      // reads them itself) a group's whole prompt tiles once
       double keys = 0;
       for (int g0 = 0; g0 < N; g0 += G) {
         int shared = share_prefix ? plen_seq[g0] / 32 * 32 : 0;
         bool any = false;
         for (int n = g0; n < g0 + G; ++n) if (s < limit[n]) { keys += plen_seq[n] - shared + s; any = true; }
-        if (any) keys += shared;
+        if (any && c->px.n_jobs == 0) keys += shared;   // with the prefix kernel the shared tiles are not this kernel's to read
       }
       c->cur_attn_bytes = keys * 2 * c->d.n_kv_heads * c->d.head_dim * 2;
     }
@@ -986,6 +1059,8 @@ int echo_rollout_continuous(echo_ctx *c, const int32_t *prompt_tokens, int32_t p
     return fail(c, ECHO_EINVAL, "a continuous rollout takes no pinned swaps (it switches when a snapshot is staged), no debug_logits and no time_kernels");
   if (G > c->d.max_seqs) return fail(c, ECHO_ENOMEM, "one group of %d sequences exceeds max_seqs = %d", G, c->d.max_seqs);
   const int N = P * G;
+  int max_pl = 0;
+  for (int p = 0; p < P; ++p) max_pl = std::max(max_pl, prompt_lens[p]);
   RolloutGuard guard(c);
   if ((rc = guard.begin())) return rc;
 
@@ -1021,7 +1096,7 @@ int echo_rollout_continuous(echo_ctx *c, const int32_t *prompt_tokens, int32_t p
   c->ids = DrawIds{c->d_step, c->d_gen_len, c->d_stream};
 
   int cur = c->active, next_prompt = 0, done_seqs = 0, decode_steps = 0, until_check = 0;
-  bool have_graph = false, first = true;
+  bool have_graph = false, first = true, dirty = false;
   double admit_ms = 0, swap_wait = 0;
   std::vector<int> free_rows;
   std::vector<int32_t> quads;
@@ -1110,8 +1185,7 @@ int echo_rollout_continuous(echo_ctx *c, const int32_t *prompt_tokens, int32_t p
               HIPCHK(c, hipMemcpyAsync(d_forced + r0, o.forced_tokens + (int64_t)(ad.prompt * G + g) * max_new, (size_t)max_new * 4,
                                        hipMemcpyHostToDevice, st));
           }
-        if ((rc = upload_rows())) return rc;   // also restores the rows the prefill pass used as its own
-        HIPCHK(c, hipStreamSynchronize(st));
+        dirty = true;   // the upload below also restores the rows the prefill pass used as its own
         admit_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - a0).count();
       }
       // No prompt is waiting any more: once the live rows fit a smaller padded batch they are moved to the front (their
@@ -1129,10 +1203,19 @@ int echo_rollout_continuous(echo_ctx *c, const int32_t *prompt_tokens, int32_t p
           }
           for (int r = w; r < Rc; ++r) { act[r] = 0; row_seq[r] = -1; }
           Rc = w;
-          if ((rc = upload_rows())) return rc;
-          HIPCHK(c, hipStreamSynchronize(st));
+          dirty = true;
           have_graph = false;
         }
+      }
+      if (dirty) {   // the rows changed: plan the shared-prompt attention for them, then put the row state on the device
+        std::vector<int32_t> live(R, 0);
+        for (int r = 0; r < Rc; ++r) live[r] = row_seq[r] >= 0 && act[r];
+        const PrefixPlan was = c->px;
+        if ((rc = plan_prefix_jobs(c, ptiles, pslot, live, Rc, share_prefix ? (max_pl - 1) / 32 : 0, Rc / 2 + 1))) return rc;
+        if (was.n_jobs != c->px.n_jobs || was.np != c->px.np || was.tiles_per_chunk != c->px.tiles_per_chunk) have_graph = false;
+        if ((rc = upload_rows())) return rc;
+        HIPCHK(c, hipStreamSynchronize(st));
+        dirty = false;
       }
       // the next event: with stop lengths only, the step at which the next sequence ends is known
       until_check = 8;

@@ -121,9 +121,20 @@ void fast_qkv_post(const float *partials, int nsplit, int Np, int Mp, void *q_h1
 void fast_attention_simple(void *Xp_out, const void *q_h16, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq,
                            int Hkv, hipStream_t st);
 // Split-K decode attention over the half-precision KV cache + combine; writes Xp (half K8 [Mp][Hq*hd]).
-// nsplit = fast_attention_splits(M, Hkv, capacity); partial buffers hold M*Hq*nsplit*(hd + 2) floats.
+// The shared prompt of a group is attended once for all its sequences by a kernel of its own: a job is up to 32 / (Hq/Hkv)
+// rows of one group (rows with RowState.ptiles >= 1 that read the prompt tiles of cache slot pslot).  Rows covered by a
+// job carry ATT_PREFIX_DONE in RowState.ptiles; the decode kernel then starts after the shared tiles and folds the job's
+// partials in.  np chunk slots per (row, head) in the partial buffers, tiles_per_chunk whole tiles per chunk
+// (np * tiles_per_chunk >= the longest job's ptiles); n_jobs = 0: no such kernel, every row reads its shared tiles itself.
+constexpr int ATT_PREFIX_DONE = 0x40000000;
+struct PrefixJob { int32_t pslot, ptiles, nrows; int32_t rows[32]; };
+struct PrefixPlan { const PrefixJob *jobs; int n_jobs, np, tiles_per_chunk; };
+// nsplit = fast_attention_splits(M, Hkv, capacity); partial buffers hold M*Hq*max(nsplit, px.np)*(hd + 2) floats.
+// With px.n_jobs > 0 and nsplit == 1, fast_attention_prefix must have run first on the same stream, partial buffers and q.
 void fast_attention(void *Xp_out, const void *q_h16, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq,
-                    int Hkv, int nsplit, float *part_o, float *part_ml, hipStream_t st);
+                    int Hkv, int nsplit, float *part_o, float *part_ml, PrefixPlan px, hipStream_t st);
+void fast_attention_prefix(const void *q_h16, KvGeom kv, int layer, int Hq, int Hkv, float *part_o, float *part_ml, PrefixPlan px,
+                           hipStream_t st);
 int fast_attention_splits(int M, int Hkv, int max_splits);
 // Causal attention for runs of consecutive positions (prefill, teacher-forced scoring).  A block is up to
 // ATT_PREFILL_WAVES * ATT_PREFILL_COLS / (Hq/Hkv) rows m0 .. m0 + nrows - 1 holding positions pos0 .. of one cache

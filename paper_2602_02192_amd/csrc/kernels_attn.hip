@@ -99,10 +99,13 @@ __device__ __forceinline__ void att_issue_v(v4u (&rv)[HD / 16], const v4u *__res
 
 // grid (nsplit, Hkv, M).  Every row's keys are cut into nsplit equal chunks of that row's own length.  DIRECT
 // (nsplit == 1): the workgroup normalises and writes the half-precision output itself and no partials exist.
+// DIRECT with np > 0: rows whose ptiles carry ATT_PREFIX_DONE skip their group's shared prompt tiles and fold in the
+// partials attn_prefix_kernel left for them (np chunk slots per (row, head), prefix_tpc tiles per chunk).
 template <int HD, bool DIRECT>
 __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__ part_o, float *__restrict__ part_ml,
                                                           uint16_t *__restrict__ Xp, int Mp, const uint16_t *__restrict__ q_h16,
-                                                          RowState rows, KvGeom kv, int layer, int Hq, int Hkv, int nsplit) {
+                                                          RowState rows, KvGeom kv, int layer, int Hq, int Hkv, int nsplit,
+                                                          int np, int prefix_tpc) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   using L = AttLds<HD>;
   constexpr int KS = HD / 16;          // k-steps of K Q^T; also 1 KiB loads per K (or V) tile
@@ -123,7 +126,8 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
   // one slot, so the tiles reach HBM once per group and the other sequences find them in L2 (workgroups of one KV head
   // land on one XCD, i.e. behind one L2).
   const v4u *head_sh = (const v4u *)((const uint16_t *)kv.base + kv.tiled_head_off(rows.pslot[m], layer, kvh));
-  const int ptiles = rows.ptiles[m];
+  const int ptiles_raw = rows.ptiles[m], ptiles = ptiles_raw & ~ATT_PREFIX_DONE;
+  const bool pre = DIRECT && np > 0 && (ptiles_raw & ATT_PREFIX_DONE);
 
   // One K and one V register tile per wavefront.  The next tile's K is requested as soon as K Q^T has consumed the
   // current one, the next V as soon as V^T P^T has; loads return in order, so waiting for V leaves the next K in flight.
@@ -131,7 +135,7 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
   // (streaming loads for the shared tiles too: measured faster than cached loads, the concurrent misses of a group merge)
   auto issue_k = [&](int t) { att_issue_k<HD, true>(rk, t < ptiles ? head_sh : head, t, lane); };
   auto issue_v = [&](int t) { att_issue_v<HD, true>(rv, t < ptiles ? head_sh : head, t, lane); };
-  int tile = w;
+  int tile = (pre ? ptiles : 0) + w;
   if (tile < ntiles) { issue_k(tile0 + tile); issue_v(tile0 + tile); }
 
   // the group's queries as B operands in LDS: unit (ks*2 + half)*8 + head holds dims ks*16 + half*8 .. +8 of one head
@@ -237,6 +241,10 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
     float mw[ATT_WAVES], M = -INFINITY;
 #pragma unroll
     for (int ww = 0; ww < ATT_WAVES; ++ww) { mw[ww] = ((float *)(lds + ww * L::MERGE_PER_WAVE))[8 * HD + r]; M = fmaxf(M, mw[ww]); }
+    // the chunks of the shared prompt, computed once for the whole group
+    const int npc = pre ? (ptiles + prefix_tpc - 1) / prefix_tpc : 0;
+    const int64_t ppi = ((int64_t)m * Hq + kvh * grp + r) * np;
+    for (int pc = 0; pc < npc; ++pc) M = fmaxf(M, part_ml[(ppi + pc) * 2]);
     float acc = 0.f, lsum = 0.f;
 #pragma unroll
     for (int ww = 0; ww < ATT_WAVES; ++ww) {
@@ -245,6 +253,11 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
       acc += mo[r * HD + dd] * f;
       lsum += mo[8 * HD + 8 + r] * f;
     }
+    for (int pc = 0; pc < npc; ++pc) {
+      float f = __expf(part_ml[(ppi + pc) * 2] - M);
+      acc += part_o[(ppi + pc) * HD + dd] * f;
+      lsum += part_ml[(ppi + pc) * 2 + 1] * f;
+    }
     if (DIRECT) {
       Xp[k8_index(m, (kvh * grp + r) * HD + dd, Mp)] = f32_to_h16_bits(acc / lsum);
     } else {
@@ -252,6 +265,136 @@ __global__ __launch_bounds__(256, 2) void attn_splitk_kernel(float *__restrict__
       part_o[pi * HD + dd] = acc;
       if (dd == 0) { part_ml[pi * 2] = M; part_ml[pi * 2 + 1] = lsum; }
     }
+  }
+}
+
+// ---- the shared prompt of a group, once for all its sequences ---------------------------------------------------
+// grid (chunks, Hkv, jobs).  A job is up to 32 / grp sequences of one group: the MFMA column side, which the kernel above
+// fills with one sequence's grp query heads, here carries (sequence, head) pairs of the whole job, so a prompt tile is
+// loaded and multiplied once per job instead of once per sequence.  Chunk c covers the whole prompt tiles
+// c * tiles_per_chunk .. of the job's prompt slot (no masking: every key of a whole tile is a prompt key).  The result is
+// the partial (max, sum, acc) of every (row, head) for that chunk, in slot c of the row's np chunk slots.
+template <int HD> struct AttPxLds {
+  static constexpr int MERGE_PER_WAVE = 32 * HD * 4 + 256;   // O columns of 32 (sequence, head) pairs + m[32], l[32]
+  static constexpr int Q_BYTES = 32 * HD * 2;
+  static constexpr int TOTAL = ATT_WAVES * MERGE_PER_WAVE + Q_BYTES;
+};
+
+template <int HD>
+__global__ __launch_bounds__(256, 2) void attn_prefix_kernel(float *__restrict__ part_o, float *__restrict__ part_ml,
+                                                          const uint16_t *__restrict__ q_h16, const PrefixJob *__restrict__ jobs,
+                                                          KvGeom kv, int layer, int Hq, int Hkv, int tiles_per_chunk, int np) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  using L = AttPxLds<HD>;
+  constexpr int KS = HD / 16, NE = HD / 32;
+  const int c = blockIdx.x, kvh = blockIdx.y;
+  const PrefixJob *job = jobs + blockIdx.z;
+  const int nrows = job->nrows, t0 = c * tiles_per_chunk, t1 = min(job->ptiles, t0 + tiles_per_chunk);
+  if (nrows <= 0 || t0 >= t1) return;
+  const int grp = Hq / Hkv;
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
+  const v4u *head = (const v4u *)((const uint16_t *)kv.base + kv.tiled_head_off(job->pslot, layer, kvh));
+  v4u rk[KS], rv[KS];
+  // cached loads: the jobs of a large group (more than 32 / grp sequences) read the same tiles
+  auto issue_k = [&](int t) { att_issue_k<HD, false>(rk, head, t, lane); };
+  auto issue_v = [&](int t) { att_issue_v<HD, false>(rv, head, t, lane); };
+  int tile = t0 + w;
+  if (tile < t1) { issue_k(tile); issue_v(tile); }
+
+  // queries as B operands: unit (ks*2 + half)*32 + column holds dims ks*16 + half*8 .. +8 of column = sequence*grp + head
+  v4u *qs = (v4u *)(lds + ATT_WAVES * L::MERGE_PER_WAVE);
+  for (int idx = threadIdx.x; idx < 32 * (HD / 8); idx += 256) {
+    int cc = idx & 31, d8 = idx >> 5, si = cc / grp, hq = cc - si * grp;
+    v4u v = v4u{0u, 0u, 0u, 0u};
+    if (si < nrows) v = *(const v4u *)(q_h16 + ((int64_t)job->rows[si] * Hq + kvh * grp + hq) * HD + d8 * 8);
+    qs[idx] = v;
+  }
+  __syncthreads();
+
+  const float scale = 1.0f / sqrtf((float)HD);
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x16 o[NE];
+#pragma unroll
+  for (int e = 0; e < NE; ++e)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[e][r] = 0.f;
+
+  auto step = [&](auto more_tag) {
+    constexpr bool more = decltype(more_tag)::value;
+    f32x16 s;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+      s = mfma_h16(__builtin_bit_cast(h16x8, rk[ks]), __builtin_bit_cast(h16x8, qs[(ks * 2 + half) * 32 + col]), s);
+    if (more) issue_k(tile + ATT_WAVES);
+    float tm = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { s[r] *= scale; tm = fmaxf(tm, s[r]); }
+    tm = fmaxf(tm, __shfl_xor(tm, 32, 64));
+    const float mn = fmaxf(m_run, tm);
+    const float alpha = __expf(m_run - mn);
+    m_run = mn;
+    float ls = 0.f;
+    uint32_t pk[8];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+      for (int i = 0; i < 4; i += 2) {
+        float p0 = __expf(s[4 * g + i] - mn), p1 = __expf(s[4 * g + i + 1] - mn);
+        ls += p0 + p1;
+        pk[2 * g + (i >> 1)] = (uint32_t)f32_to_h16_bits(p0) | ((uint32_t)f32_to_h16_bits(p1) << 16);
+      }
+    l_run = l_run * alpha + ls;
+    if (__any(alpha != 1.0f)) {
+#pragma unroll
+      for (int e = 0; e < NE; ++e)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[e][r] *= alpha;
+    }
+#pragma unroll
+    for (int ks2 = 0; ks2 < 2; ++ks2) {   // the P^T hand-over between the two lanes of a column, as in the kernel above
+      const int ga = 2 * ks2, gb = 2 * ks2 + 1;
+      uint32_t s0 = half ? pk[2 * ga] : pk[2 * gb], s1 = half ? pk[2 * ga + 1] : pk[2 * gb + 1];
+      uint32_t r0 = __shfl_xor(s0, 32, 64), r1 = __shfl_xor(s1, 32, 64);
+      uint32_t m0 = half ? pk[2 * gb] : pk[2 * ga], m1 = half ? pk[2 * gb + 1] : pk[2 * ga + 1];
+      v4u pb = half ? v4u{r0, r1, m0, m1} : v4u{m0, m1, r0, r1};
+#pragma unroll
+      for (int e = 0; e < NE; ++e)
+        o[e] = mfma_h16(__builtin_bit_cast(h16x8, rv[ks2 * NE + e]), __builtin_bit_cast(h16x8, pb), o[e]);
+    }
+    if (more) issue_v(tile + ATT_WAVES);
+  };
+  for (; tile + ATT_WAVES < t1; tile += ATT_WAVES) step(std::true_type{});
+  if (tile < t1) step(std::false_type{});
+  l_run += __shfl_xor(l_run, 32, 64);
+  {
+    float *mo = (float *)(lds + w * L::MERGE_PER_WAVE);      // [32][HD] then m[32], l[32]
+#pragma unroll
+    for (int e = 0; e < NE; ++e)
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mo[col * HD + 32 * e + 8 * g + 4 * half + i] = o[e][4 * g + i];
+    if (half == 0) { mo[32 * HD + col] = m_run; mo[32 * HD + 32 + col] = l_run; }
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < nrows * grp * HD; idx += 256) {
+    int cc = idx / HD, dd = idx % HD, si = cc / grp, hq = cc - si * grp;
+    float mw[ATT_WAVES], M = -INFINITY;
+#pragma unroll
+    for (int ww = 0; ww < ATT_WAVES; ++ww) { mw[ww] = ((float *)(lds + ww * L::MERGE_PER_WAVE))[32 * HD + cc]; M = fmaxf(M, mw[ww]); }
+    float acc = 0.f, lsum = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < ATT_WAVES; ++ww) {
+      const float *mo = (const float *)(lds + ww * L::MERGE_PER_WAVE);
+      float f = __expf(mw[ww] - M);
+      acc += mo[cc * HD + dd] * f;
+      lsum += mo[32 * HD + 32 + cc] * f;
+    }
+    int64_t pi = ((int64_t)job->rows[si] * Hq + kvh * grp + hq) * np + c;
+    part_o[pi * HD + dd] = acc;
+    if (dd == 0) { part_ml[pi * 2] = M; part_ml[pi * 2 + 1] = lsum; }
   }
 }
 
@@ -285,14 +428,15 @@ int fast_attention_splits(int M, int Hkv, int max_splits) {
 
 template <int HD>
 static void attention_launch(void *Xp_out, const void *q_h16, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq, int Hkv,
-                             int nsplit, float *part_o, float *part_ml, hipStream_t st) {
+                             int nsplit, float *part_o, float *part_ml, PrefixPlan px, hipStream_t st) {
   dim3 grid(nsplit, Hkv, M);
   if (nsplit == 1) {
+    const bool pre = px.n_jobs > 0 && px.np > 0;
     hipLaunchKernelGGL((attn_splitk_kernel<HD, true>), grid, dim3(256), AttLds<HD>::TOTAL, st, part_o, part_ml, (uint16_t *)Xp_out,
-                       Mp, (const uint16_t *)q_h16, rows, kv, layer, Hq, Hkv, nsplit);
+                       Mp, (const uint16_t *)q_h16, rows, kv, layer, Hq, Hkv, nsplit, pre ? px.np : 0, px.tiles_per_chunk);
   } else {
     hipLaunchKernelGGL((attn_splitk_kernel<HD, false>), grid, dim3(256), AttLds<HD>::TOTAL, st, part_o, part_ml, (uint16_t *)Xp_out,
-                       Mp, (const uint16_t *)q_h16, rows, kv, layer, Hq, Hkv, nsplit);
+                       Mp, (const uint16_t *)q_h16, rows, kv, layer, Hq, Hkv, nsplit, 0, 1);
     hipLaunchKernelGGL(attn_combine_kernel<HD>, dim3(M, Hq), dim3(HD), 0, st, (uint16_t *)Xp_out, part_o, part_ml, rows, Mp, Hq,
                        nsplit);
   }
@@ -498,10 +642,29 @@ void fast_attention_prefill(void *Xp_out, const void *q_h16, const PrefillBlock 
   else attention_prefill_launch<64>(Xp_out, q_h16, blocks, nblocks, kv, layer, Mp, Hq, Hkv, st);
 }
 
+template <int HD>
+static void prefix_launch(const void *q_h16, KvGeom kv, int layer, int Hq, int Hkv, float *part_o, float *part_ml, PrefixPlan px,
+                          hipStream_t st) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void *)attn_prefix_kernel<HD>, hipFuncAttributeMaxDynamicSharedMemorySize, AttPxLds<HD>::TOTAL);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(attn_prefix_kernel<HD>, dim3(px.np, Hkv, px.n_jobs), dim3(256), AttPxLds<HD>::TOTAL, st, part_o, part_ml,
+                     (const uint16_t *)q_h16, px.jobs, kv, layer, Hq, Hkv, px.tiles_per_chunk, px.np);
+}
+
+void fast_attention_prefix(const void *q_h16, KvGeom kv, int layer, int Hq, int Hkv, float *part_o, float *part_ml, PrefixPlan px,
+                           hipStream_t st) {
+  if (px.n_jobs <= 0 || px.np <= 0) return;
+  if (kv.head_dim == 128) prefix_launch<128>(q_h16, kv, layer, Hq, Hkv, part_o, part_ml, px, st);
+  else prefix_launch<64>(q_h16, kv, layer, Hq, Hkv, part_o, part_ml, px, st);
+}
+
 void fast_attention(void *Xp_out, const void *q_h16, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq, int Hkv,
-                    int nsplit, float *part_o, float *part_ml, hipStream_t st) {
-  if (kv.head_dim == 128) attention_launch<128>(Xp_out, q_h16, rows, kv, layer, M, Mp, Hq, Hkv, nsplit, part_o, part_ml, st);
-  else attention_launch<64>(Xp_out, q_h16, rows, kv, layer, M, Mp, Hq, Hkv, nsplit, part_o, part_ml, st);
+                    int nsplit, float *part_o, float *part_ml, PrefixPlan px, hipStream_t st) {
+  if (kv.head_dim == 128) attention_launch<128>(Xp_out, q_h16, rows, kv, layer, M, Mp, Hq, Hkv, nsplit, part_o, part_ml, px, st);
+  else attention_launch<64>(Xp_out, q_h16, rows, kv, layer, M, Mp, Hq, Hkv, nsplit, part_o, part_ml, px, st);
 }
 
 }  // namespace echo

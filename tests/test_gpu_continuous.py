@@ -142,3 +142,26 @@ def test_a_staged_snapshot_is_switched_in_between_steps_and_errors():
             bad()
         assert e.value.code == code
     ctx.close()
+
+
+def test_refill_and_compaction_with_the_groups_prompts_attended_once_per_group(monkeypatch):
+    """Enough rows that a row's keys stay in one workgroup, so the shared prompt tiles can go through the prefix kernel
+    (forced on: at this size it would not pay): its job list is rebuilt as groups are admitted, finish and are
+    compacted.  Teacher-forced against the oracle."""
+    monkeypatch.setenv("ECHO_PREFIX_KERNEL_MIN", "0")
+    shape = MID
+    blob = synth.make_weights(shape, 0)
+    blob32 = synth.widen_to_f32(blob)
+    P, G, max_new = 30, 8, 12
+    prompts, lens = synth.make_prompts(shape.vocab, P, 100, seed=12)
+    lens[:] = np.resize(np.array([33, 64, 100, 65, 97, 40, 32], np.int32), P)     # 32: one whole tile minus the decode input
+    stop = synth.make_stop_lens(P * G, 1, max_new, seed=13)
+    ref = oracle_rollout(shape, blob32, prompts, lens, G=G, max_new=max_new, temperature=1.0, seed=2, stop_lens=stop)
+    ctx = make_ctx(shape, 168, 128, blob)
+    out = ctx.rollout(prompts, lens, G, max_new, 1.0, 2, stop_lens=stop, continuous=True, forced=ref["tokens"].clip(0))
+    m = valid_mask(stop, max_new)
+    assert np.array_equal(out["lens"], stop)
+    same = (out["tokens"] == ref["tokens"]) & m
+    assert same[m].mean() > 0.9
+    assert np.abs(out["logprobs"] - ref["logprobs"])[same].max() < BF16_LOGPROB_TOL
+    ctx.close()

@@ -202,7 +202,9 @@ def test_group_shared_prompt_tiles(monkeypatch, shape, G, P):
     N, max_new = P * G, 40
     stop = np.resize(np.array([3, 40, 17, 29, 40, 1, 36, 22], np.int32), N)
     ctx = make_ctx(shape, N, 160, blob)
-    # 1. every row reading the group's copy of the prompt tiles against every row reading its own replicated copy: bit for bit
+    # 1. every row reading the group's copy of the prompt tiles itself against every row reading its own replicated copy:
+    # bit for bit (same kernel, same order of operations, other addresses)
+    monkeypatch.setenv("ECHO_NO_PREFIX_KERNEL", "1")
     a = ctx.rollout(prompts, lens, G, max_new, 1.0, 11, stop_lens=stop)
     monkeypatch.setenv("ECHO_NO_PREFIX_SHARING", "1")
     b = ctx.rollout(prompts, lens, G, max_new, 1.0, 11, stop_lens=stop)
@@ -210,6 +212,18 @@ def test_group_shared_prompt_tiles(monkeypatch, shape, G, P):
     assert np.array_equal(a["lens"], stop) and np.array_equal(b["lens"], stop)
     assert np.array_equal(a["tokens"], b["tokens"])
     assert np.array_equal(a["logprobs"], b["logprobs"])
+    # 1b. the shared tiles attended once per group by the prefix kernel (the default where a row's keys stay in one
+    # workgroup): the same sums in another order, so equal up to rounding -- fed the same tokens, the same tokens come out
+    # (near-ties aside) with log-probs a rounding apart
+    forced = np.maximum(a["tokens"], 0)
+    af = ctx.rollout(prompts, lens, G, max_new, 1.0, 11, stop_lens=stop, forced=forced)
+    monkeypatch.delenv("ECHO_NO_PREFIX_KERNEL")
+    monkeypatch.setenv("ECHO_PREFIX_KERNEL_MIN", "0")      # also for batches this small, where it does not pay
+    pf = ctx.rollout(prompts, lens, G, max_new, 1.0, 11, stop_lens=stop, forced=forced)
+    m = valid_mask(stop, max_new)
+    same = (pf["tokens"] == af["tokens"]) & m
+    assert same[m].mean() > 0.995, same[m].mean()
+    assert np.abs(pf["logprobs"] - af["logprobs"])[same].max() < 2e-3
     # 2. against the oracle, teacher-forced on the oracle's tokens, for three prompts spread over the batch
     blob32 = synth.widen_to_f32(blob)
     pick = [0, P // 2, P - 1]
@@ -347,7 +361,7 @@ def test_edge_cases_and_errors():
     ctx.close()
 
 
-def test_dense4b_shape_in_the_benchmark_launch_configuration():
+def test_dense4b_shape_in_the_benchmark_launch_configuration(monkeypatch):
     """The 4B-class decoder (36 layers, full width, vocabulary 151936), 8 prompts x G = 8 = 64 sequences as the
     benchmark launches it.  The oracle is affordable for two whole sequences with a short prompt; the long
     configuration (prompt 512 + 1024 new tokens) is checked through properties and self-consistency."""
@@ -429,6 +443,15 @@ def test_dense4b_shape_in_the_benchmark_launch_configuration():
         # two paths (decode kernels, causal block kernels) that each sit within the tolerance of the exact value
         assert np.abs(got - lp[n]).max() < 2 * BF16_LOGPROB_TOL
         assert np.abs(got - lp[n]).mean() < 0.3 * BF16_LOGPROB_TOL
+    # the groups' 512-token prompts attended once per group by the prefix kernel (forced on; off by default at this size):
+    # the same tokens fed in, the same tokens out (near-ties aside), log-probs a rounding apart
+    monkeypatch.setenv("ECHO_PREFIX_KERNEL_MIN", "0")
+    px = ctx.rollout(prompts, lens, G, 64, 1.0, 2, forced=big["tokens"][:, :64])
+    monkeypatch.delenv("ECHO_PREFIX_KERNEL_MIN")
+    same = px["tokens"] == big["tokens"][:, :64]
+    dlp = np.abs(px["logprobs"] - big["logprobs"][:, :64])[same]
+    # two paths that each sit within the tolerance of the exact value (36 layers amplify the other summation order)
+    assert same.mean() > 0.995 and dlp.max() < 2 * BF16_LOGPROB_TOL and dlp.mean() < 0.3 * BF16_LOGPROB_TOL, (dlp.max(), dlp.mean())
     # kernel-by-kernel launches reproduce the graph replay bit for bit (same kernels, same order)
     ng = ctx.rollout(prompts, lens, G, 64, 1.0, 2, no_graph=True)
     assert np.array_equal(ng["tokens"], big["tokens"][:, :64]) and np.array_equal(ng["logprobs"], big["logprobs"][:, :64])
