@@ -616,9 +616,10 @@ int plan_prefix_jobs(echo_ctx *c, std::vector<int32_t> &ptiles, const std::vecto
     }
     i = j;
   }
-  // The extra launch costs about as much as it saves at 64 rows x 16 tiles (measured: -7 % there, +1 % at 256 x 16,
-  // +5 % at 256 x 32), so small batches with short prompts keep reading their shared tiles in the decode kernel.
-  int64_t covered = 0, min_covered = 4096;
+  // The extra launch costs more than it saves at 64 rows x 16 tiles (measured: -7 % there; +1 % at 256 x 16, -2 % at a
+  // draining 128 x 32, +5 % at 256 x 32), so small batches with short prompts keep reading their shared tiles in the
+  // decode kernel.
+  int64_t covered = 0, min_covered = 6144;
   for (const PrefixJob &jb : jobs) covered += (int64_t)jb.nrows * jb.ptiles;
   if (const char *v = getenv("ECHO_PREFIX_KERNEL_MIN")) min_covered = atoll(v);
   if (jobs.empty() || (int)jobs.size() > cap || covered < min_covered) {
