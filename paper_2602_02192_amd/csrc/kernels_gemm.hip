@@ -932,6 +932,170 @@ __global__ __launch_bounds__(256) void lmhead_kernel(const u32x4v *__restrict__ 
   }
 }
 
+// ---- lm_head on 256 x 256 tiles (batches of 256 rows and more: scoring passes, wide decode batches) -----------------
+// The main loop of gemm_wide_kernel (four wavefronts, two weight blocks each, 256 rows, operands eight k-steps ahead),
+// then the sampler of the kernel above over the 2 x 8 accumulator tiles of a wavefront: parked in LDS one weight block
+// at a time (static indices, so the accumulators stay registers during the main loop) and folded in a rolled loop.
+// grid: ceil(Np/256) column strips x Mp/256 row blocks, the row blocks of a strip neighbours in launch order (the
+// vocabulary matrix is far larger than the caches); one partial per (row, strip).
+struct LmWideLds {
+  static constexpr int DUMP_PER_WAVE = 8 * 16 * 64 * 4;   // one weight block's eight accumulator tiles
+  static constexpr int BYTES = LM_WN * DUMP_PER_WAVE + LM_WN * 8 * 32 * (int)sizeof(SampleAcc);
+};
+
+// SCORE (teacher-forced scoring, target set): only the log-sum-exp of the row and the target's z are wanted, so a
+// lane takes the 16 logits of an accumulator tile at once -- their maximum, then 16 hardware exp2 of the differences
+// -- instead of the sampler's per-logit running update (which costs more than the main loop at this tile size).
+template <bool SCORE>
+__global__ __launch_bounds__(256) void lmhead_wide_kernel(const u32x4v *__restrict__ Xp, const h16x8 *__restrict__ Wp, int Mp, int Np,
+                                                          int Kp, int V, float temperature, uint64_t seed, DrawIds ids,
+                                                          const int32_t *target, float *target_z, float *part, int n_wg) {
+  extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+  using L = GemmWide;
+  constexpr int MB = L::MB, NBW = L::NBW, T = L::T, XU = L::CHUNK_UNITS, XL = L::XL, ROWS = L::ROWS, NSTAGE = L::NSTAGE;
+  u32x4v *xs = (u32x4v *)lds_raw;
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, tid = threadIdx.x, half = lane >> 5, col = lane & 31;
+  const int nblocks = Np >> 5, nchunks = Kp >> 4, nz = Mp / ROWS;
+  const int bx = blockIdx.x / nz, bz = blockIdx.x % nz;
+  const int nb0 = (bx * L::WN + w) * NBW, mrow0 = bz * ROWS;
+  const int64_t a_step = w_kstep_stride(Np);
+  const h16x8 *a_ptr[NBW];
+#pragma unroll
+  for (int n = 0; n < NBW; ++n) a_ptr[n] = Wp + w_block_base(min(nb0 + n, nblocks - 1), Kp) + (lane >> 5) * 32 + (lane & 31);
+  f32x16 acc[NBW][MB];
+#pragma unroll
+  for (int n = 0; n < NBW; ++n)
+#pragma unroll
+    for (int j = 0; j < MB; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[n][j][r] = 0.f;
+  h16x8 a[NSTAGE][NBW];
+  u32x4v xr[NSTAGE][XL];
+  auto load_a = [&](int st, int c) {
+#pragma unroll
+    for (int n = 0; n < NBW; ++n) a[st][n] = __builtin_nontemporal_load(a_ptr[n] + (int64_t)c * a_step);
+  };
+  auto load_x = [&](int st, int c) {
+#pragma unroll
+    for (int i = 0; i < XL; ++i) {
+      int idx = i * T + tid;
+      xr[st][i] = Xp[(int64_t)(c * 2 + idx / ROWS) * Mp + mrow0 + idx % ROWS];
+    }
+  };
+  auto store_x = [&](int st, int buf) {
+#pragma unroll
+    for (int i = 0; i < XL; ++i) xs[buf * XU + i * T + tid] = xr[st][i];
+  };
+  auto compute = [&](int st, int buf) {
+    const u32x4v *bp = xs + buf * XU + (lane >> 5) * ROWS + (lane & 31);
+    u32x4v b[MB];
+#pragma unroll
+    for (int j = 0; j < MB; ++j) b[j] = bp[j * 32];
+#pragma unroll
+    for (int j = 0; j < MB; ++j)
+#pragma unroll
+      for (int n = 0; n < NBW; ++n) acc[n][j] = mfma_h16(a[st][n], __builtin_bit_cast(h16x8, b[j]), acc[n][j]);
+  };
+#pragma unroll
+  for (int s = 0; s < NSTAGE - 1; ++s) { load_x(s, s); load_a(s, s); }
+  store_x(0, 0);
+  __syncthreads();
+  for (int c0 = 0; c0 < nchunks; c0 += NSTAGE) {
+#pragma unroll
+    for (int s = 0; s < NSTAGE; ++s) {
+      const int c = c0 + s, cn = min(c + NSTAGE - 1, nchunks - 1);
+      load_x((s + NSTAGE - 1) % NSTAGE, cn);
+      load_a((s + NSTAGE - 1) % NSTAGE, cn);
+      compute(s, s & 1);
+      store_x((s + 1) % NSTAGE, (s + 1) & 1);
+      __syncthreads();
+    }
+  }
+  // ---- sampler epilogue
+  auto fold4 = [&](SampleAcc &sa, f32x4 av, int v0, int m, int tgt, uint32_t stream, uint32_t step) {
+    u32x4 r = {0u, 0u, 0u, 0u};
+    if (!target) r = draw4(seed, stream, step, (uint32_t)(v0 >> 2));
+    const uint32_t bits[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int v = v0 + i;
+      if (v < V) {
+        float z = av[i] * W_UNSCALE / temperature;
+        sample_acc_add(sa, z, target ? z : z + gumbel_from_bits(bits[i]), v);   // scoring draws no noise
+        if (v == tgt) target_z[m] = z;
+      }
+    }
+  };
+  f32x4 *dump = (f32x4 *)(lds_raw + w * LmWideLds::DUMP_PER_WAVE) + lane;
+  SampleAcc (*sh)[MB][32] = (SampleAcc (*)[MB][32])(lds_raw + LM_WN * LmWideLds::DUMP_PER_WAVE);   // [4][MB][32]
+#pragma unroll
+  for (int n = 0; n < NBW; ++n) {
+    // (the loop above ended with a barrier: its buffers are free; between the two blocks each lane re-reads only its own dump)
+#pragma unroll
+    for (int j = 0; j < MB; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) dump[(j * 4 + g) * 64] = f32x4{acc[n][j][4 * g], acc[n][j][4 * g + 1], acc[n][j][4 * g + 2], acc[n][j][4 * g + 3]};
+    const int nb = nb0 + n;
+#pragma unroll 1
+    for (int j = 0; j < MB; ++j) {
+      SampleAcc sa = sample_acc_init();
+      if (nb < nblocks) {
+        int m = mrow0 + j * 32 + col, tgt = target ? target[m] : -1;
+        if (SCORE) {
+          const float c2 = W_UNSCALE / temperature * 1.44269504088896341f;   // logits in log2 units
+          float z2[16], bm = -INFINITY;
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            f32x4 av = dump[(j * 4 + g) * 64];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              int v = nb * 32 + 8 * g + 4 * half + i;
+              z2[4 * g + i] = v < V ? av[i] * c2 : -INFINITY;
+              bm = fmaxf(bm, z2[4 * g + i]);
+              if (v == tgt) target_z[m] = av[i] * W_UNSCALE / temperature;
+            }
+          }
+          if (bm > -INFINITY) {
+            float sum = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(z2[i] - bm);
+            sa.zmax = bm * 0.693147180559945309f;   // back to natural units: exp(z - zmax) = exp2(z2 - bm)
+            sa.zsum = sum;
+          }
+        } else {
+          const uint32_t stream = draw_stream(ids, m), step = target ? 0u : draw_step(ids, m);
+#pragma unroll
+          for (int g = 0; g < 4; ++g) fold4(sa, dump[(j * 4 + g) * 64], nb * 32 + 8 * g + 4 * half, m, tgt, stream, step);
+        }
+      }
+      SampleAcc o = sample_acc_shfl_xor(sa, 32);
+      sample_acc_merge(sa, o);
+      if (half == 0) {
+        if (n > 0) { SampleAcc prev = sh[w][j][col]; sample_acc_merge(prev, sa); sa = prev; }   // block order: lower indices first
+        sh[w][j][col] = sa;
+      }
+    }
+  }
+  __syncthreads();
+  if (w == 0 && half == 0) {
+#pragma unroll 1
+    for (int j = 0; j < MB; ++j) {
+      SampleAcc sa = sh[0][j][col];
+      for (int ww = 1; ww < LM_WN; ++ww) sample_acc_merge(sa, sh[ww][j][col]);
+      int m = mrow0 + j * 32 + col;
+      int64_t o = (int64_t)bx * Mp + m, plane = (int64_t)n_wg * Mp;
+      part[o] = sa.zmax;
+      part[plane + o] = sa.zsum;
+      part[2 * plane + o] = sa.best;
+      part[3 * plane + o] = sa.zbest;
+      part[4 * plane + o] = __int_as_float(sa.idx);
+    }
+  }
+}
+
+static int lm_wide_wgs(int Np) { return (Np / 32 + 7) / 8; }
+static bool lm_use_wide(int Mp, int Kp) { return Mp % 256 == 0 && Kp % GEMM_K_PAD == 0; }
+
 // grid M rows, block 256: fold the per-workgroup partials of one row in workgroup order.
 __global__ void sample_combine_kernel(int32_t *tok, float *lp, float *target_lp, const float *part, int n_wg, int Mp,
                                       const int32_t *row_active, const int32_t *target, const float *target_z) {
@@ -994,9 +1158,26 @@ static void lmhead_dispatch(const void *Xp, const void *Wp, int Mp, int Np, int 
 void fast_lmhead_sample(int32_t *tok, float *lp, float *target_lp, const void *Xp, const void *Wp, int Mp, int M, int V,
                         int Np, int Kp, float temperature, uint64_t seed, DrawIds ids, const int32_t *row_active,
                         const int32_t *target, float *partials, hipStream_t st) {
-  int n_wg = lm_wgs(Np);
-  float *target_z = partials + (size_t)5 * n_wg * Mp;
-  lmhead_dispatch<false>(Xp, Wp, Mp, Np, Kp, V, temperature, seed, ids, target, target_z, partials, nullptr, 0, st);
+  const bool wide = lm_use_wide(Mp, Kp);
+  int n_wg = wide ? lm_wide_wgs(Np) : lm_wgs(Np);
+  float *target_z = partials + (size_t)5 * lm_wgs(Np) * Mp;   // behind the partials of either form
+  if (wide) {
+    static bool attr_set = false;
+    constexpr int BYTES = LmWideLds::BYTES > GemmWide::BYTES ? LmWideLds::BYTES : GemmWide::BYTES;
+    if (!attr_set) {
+      (void)hipFuncSetAttribute((const void *)lmhead_wide_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, BYTES);
+      (void)hipFuncSetAttribute((const void *)lmhead_wide_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, BYTES);
+      attr_set = true;
+    }
+    if (target)
+      hipLaunchKernelGGL(lmhead_wide_kernel<true>, dim3(n_wg * (Mp / 256)), dim3(256), BYTES, st, (const u32x4v *)Xp, (const h16x8 *)Wp, Mp,
+                         Np, Kp, V, temperature, seed, ids, target, target_z, partials, n_wg);
+    else
+      hipLaunchKernelGGL(lmhead_wide_kernel<false>, dim3(n_wg * (Mp / 256)), dim3(256), BYTES, st, (const u32x4v *)Xp, (const h16x8 *)Wp, Mp,
+                         Np, Kp, V, temperature, seed, ids, target, target_z, partials, n_wg);
+  } else {
+    lmhead_dispatch<false>(Xp, Wp, Mp, Np, Kp, V, temperature, seed, ids, target, target_z, partials, nullptr, 0, st);
+  }
   hipLaunchKernelGGL(sample_combine_kernel, dim3(M), dim3(256), 0, st, tok, lp, target_lp, partials, n_wg, Mp, row_active,
                      target, target_z);
 }
