@@ -58,6 +58,17 @@ def test_peer_scores_and_chains_match_the_oracle(echo):
         assert chain.tolist() == want_chain and hop.tolist() == want_hop
 
 
+def test_values_the_paper_states(echo):
+    from test_oracle_capacity import stated_values
+    for name, args, want in stated_values():
+        if name == "n_chains":
+            assert echo.n_chains(*args) == want
+        elif name == "speed_term":
+            assert echo.peer_score(args[0], 0.0, 4, 0, 0.0) == pytest.approx(0.5 * want, abs=1e-12)
+        elif name == "stale_bound":
+            assert echo.staleness_bound(int(args[0]), *args[1:]) == want
+
+
 def test_greedy_activation_matches_the_oracle(echo):
     rng = random.Random(2)
     for _ in range(300):

@@ -63,6 +63,29 @@ def test_peer_score_components():
     assert cap.peer_score(1e7, 0.0, 4, 0, 0.0) - cap.peer_score(1e6, 0.0, 4, 0, 0.0) == pytest.approx(10.0, abs=1e-12)
 
 
+def stated_values():
+    import os
+    rows = []
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "paper_stated_values.txt")):
+        line = line.split("#")[0].split()
+        if line:
+            rows.append((line[0], [float(x) for x in line[1:-1]], float(line[-1])))
+    return rows
+
+
+def test_values_the_paper_states():
+    seen = set()
+    for name, args, want in stated_values():
+        seen.add(name)
+        if name == "n_chains":
+            assert cap.n_chains(*args) == want
+        elif name == "speed_term":      # the score with nothing but the speed term, undecayed: 0.5 * Speed
+            assert cap.peer_score(args[0], 0.0, 4, 0, 0.0) == pytest.approx(0.5 * want, abs=1e-12)
+        elif name == "stale_bound":
+            assert cap.staleness_bound(int(args[0]), *args[1:]) == want
+    assert seen == {"n_chains", "speed_term", "stale_bound"}
+
+
 def test_chains():
     assert [cap.n_chains(b, 100.0) for b in (300.0, 600.0, 700.0, 800.0)] == [3, 6, 7, 8]   # the paper's uplink budgets
     assert cap.n_chains(250.0, 100.0) == 2 and cap.n_chains(50.0, 100.0) == 1
