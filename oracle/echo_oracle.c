@@ -26,7 +26,8 @@
  *
  * Pins (tests/test_oracle_*.py): incremental decode == full recompute, softmax
  * rows sum to 1, RoPE(pos 0) = identity and relative-position property,
- * single-key attention returns V, a closed-form 1-layer example, Philox
+ * single-key attention returns V, closed-form 1-layer examples (one of them
+ * for the per-head q/k norm: before the rotation, each with its own gains), Philox
  * known-answer vectors, Gumbel-max frequencies vs softmax (chi-square), silu
  * closed forms, batch/seed independence.  No function is "parity unpinned".
  */

@@ -109,6 +109,59 @@ def test_cached_decode_equals_full_recompute(orc, orc32, qk_norm):
     assert np.allclose(a32, a, rtol=1e-4, atol=2e-4)            # the fp32 build tracks the fp64 build
 
 
+def test_worked_example_qk_norm_per_head_before_rotation_with_its_own_gains(orc):
+    # d = 2, two query heads over one key/value head, hd = 2 (a single rotary pair, theta_0 = 1), eps = 0, tokens [0, 1].
+    # E = 2I, so a0 = sqrt2 e0 and a1 = sqrt2 e1 and a projection of a_t is sqrt2 times column t of its matrix.
+    #   Wq columns:  head 0: (*, *), (3, 4);   head 1: (*, *), (0, 10)      (only position 1 queries are looked at)
+    #   Wk columns:  (4, 3) for token 0, (-3, 4) for token 1;  Wv = 3I;  Wo = [I | I] (adds the two heads);  Wd = 0
+    #   gains: q_norm = (2, 1/2), k_norm = (1/2, 3): unequal inside the pair, so norm-then-rotate != rotate-then-norm,
+    #   and q and k gains differ, so swapping them shows; two heads of different length, so one norm over the whole
+    #   q vector shows; values are three times too long for a norm applied to them to go unnoticed.
+    sh = synth.ModelShape(1, 2, 2, 1, 2, 2, 2, rms_eps=0.0, dtype="fp32", qk_norm=True)
+    I = np.eye(2)
+    wq = np.array([[1.0, 3.0], [2.0, 4.0], [5.0, 0.0], [1.0, 10.0]])
+    wk = np.array([[4.0, -3.0], [3.0, 4.0]])
+    gq, gk = np.array([2.0, 0.5]), np.array([0.5, 3.0])
+    blob = _blob(sh, embed=2 * I, layers__0__wq=wq, layers__0__wk=wk, layers__0__wv=3 * I, layers__0__wo=np.hstack([I, I]),
+                 layers__0__q_norm=gq, layers__0__k_norm=gk, lm_head=I)
+    lg = orc.forward_cached(oracle.desc_from_shape(sh), blob, [0, 1])[1]
+    r2, c1, s1 = np.sqrt(2.0), np.cos(1.0), np.sin(1.0)
+    rot = lambda v: np.array([v[0] * c1 - v[1] * s1, v[0] * s1 + v[1] * c1])
+    # per-head unit-RMS vectors times the gain, written out: |(3,4)| = 5 -> rms 5/sqrt2 * sqrt2 ... = (0.6, 0.8) sqrt2
+    q0 = rot(r2 * np.array([0.6, 0.8]) * gq)            # = rot(sqrt2 (1.2, 0.4))
+    q1 = rot(r2 * np.array([0.0, 1.0]) * gq)            # = rot(sqrt2 (0, 0.5))
+    k0 = r2 * np.array([0.8, 0.6]) * gk                  # position 0: no rotation; = sqrt2 (0.4, 1.8)
+    k1 = rot(r2 * np.array([-0.6, 0.8]) * gk)           # = rot(sqrt2 (-0.3, 2.4))
+    assert np.allclose(q0, rot(r2 * np.array([1.2, 0.4]))) and np.allclose(k0, r2 * np.array([0.4, 1.8]))
+    v0, v1 = 3 * r2 * np.array([1.0, 0.0]), 3 * r2 * np.array([0.0, 1.0])
+    h = np.array([0.0, 2.0])
+    for q in (q0, q1):
+        s = np.array([q @ k0, q @ k1]) / np.sqrt(2.0)
+        w = np.exp(s - s.max())
+        w /= w.sum()
+        h = h + w[0] * v0 + w[1] * v1
+    want = h / np.sqrt(np.mean(h * h))
+    assert np.allclose(lg, want, atol=1e-12)
+    # the plausible mistakes move the answer by far more than the tolerance above
+    def variant(q_vecs, k_vecs):
+        hh = np.array([0.0, 2.0])
+        for q in q_vecs:
+            s = np.array([q @ k_vecs[0], q @ k_vecs[1]]) / np.sqrt(2.0)
+            w = np.exp(s - s.max())
+            w /= w.sum()
+            hh = hh + w[0] * v0 + w[1] * v1
+        return hh / np.sqrt(np.mean(hh * hh))
+    rotate_then_norm = variant([gq * rot(r2 * np.array([0.6, 0.8])), gq * rot(r2 * np.array([0.0, 1.0]))],
+                               [k0, gk * rot(r2 * np.array([-0.6, 0.8]))])
+    swapped_gains = variant([rot(r2 * np.array([0.6, 0.8]) * gk), rot(r2 * np.array([0.0, 1.0]) * gk)],
+                            [r2 * np.array([0.8, 0.6]) * gq, rot(r2 * np.array([-0.6, 0.8]) * gq)])
+    qall = np.array([3.0, 4.0, 0.0, 10.0])
+    qall = qall / np.sqrt(np.mean(qall * qall))        # one norm over both heads
+    whole_vector = variant([rot(qall[:2] * gq), rot(qall[2:] * gq)], [k0, k1])
+    for wrong in (rotate_then_norm, swapped_gains, whole_vector):
+        assert np.abs(wrong - want).max() > 1e-3
+
+
 def test_qk_norm_changes_the_result_and_gains_matter(orc):
     d0, d1 = oracle.desc_from_shape(SMALL), oracle.desc_from_shape(SMALL.replace(qk_norm=True))
     toks = np.arange(6, dtype=np.int32)
