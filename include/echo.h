@@ -75,6 +75,14 @@ typedef struct {
   int32_t no_graph;            /* 1: launch decode steps kernel by kernel instead of replaying a HIP graph */
   int32_t time_kernels;        /* 1: bracket decode-attention and GEMM launches with HIP events (implies
                                   no_graph); durations are read back with echo_stats */
+  /* Cross-check switches (0 = the default path; results differ from it by rounding order at most, see each): */
+  int32_t attn_plain;          /* 1: decode and prompt attention by the plain kernel (one wavefront per (row, head), two
+                                  passes, no key splitting, no sharing of prompt tiles) instead of the MFMA kernels */
+  int32_t own_prompt_copy;     /* 1: every sequence reads its own replicated copy of its group's prompt K/V instead of
+                                  the copy in the group's first cache slot (bit-identical results) */
+  int32_t prefix_kernel;       /* who attends a group's shared whole prompt tiles: 0 = the planner decides by batch size,
+                                  1 = always each row in the decode kernel, 2 = always the once-per-group kernel where it
+                                  applies (a row's keys not split over workgroups); the two differ by summation order */
 } echo_rollout_opts;
 
 typedef struct {

@@ -33,6 +33,7 @@
  */
 #include <math.h>
 #include <stdint.h>
+#include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
 #ifdef _OPENMP
@@ -61,6 +62,21 @@ typedef struct {
 } orc_model;
 
 int orc_real_bytes(void) { return (int)sizeof(real); }
+
+/* Progress notes of the long calls (a line every 32 tokens of a string), appended to a file when one is set:
+ * a caller that is watched for signs of life can show that a minutes-long call is moving.  No arithmetic here. */
+static char progress_path[1024];
+void orc_set_progress_file(const char *path) {
+  progress_path[0] = 0;
+  if (path && strlen(path) < sizeof progress_path) strcpy(progress_path, path);
+}
+static void progress_note(const char *what, int seq, int done, int total) {
+  if (!progress_path[0] || (done & 31) != 0) return;
+  FILE *f = fopen(progress_path, "a");
+  if (!f) return;
+  fprintf(f, "[oracle] %s: sequence %d, token %d of %d\n", what, seq, done, total);
+  fclose(f);
+}
 
 void orc_set_threads(int n) {
 #ifdef _OPENMP
@@ -479,7 +495,10 @@ int orc_rollout_top_p(const orc_desc *d, int n_models, const float *const *blobs
       out_versions[(int64_t)n * max_new + s] = -1;
     }
     orc_seq *sq = seq_new(d, pl + max_new + 1);
-    for (int t = 0; t < pl; ++t) decode_token(ms[0], sq, prompts[(int64_t)p * prompt_stride + t], t == pl - 1 ? lg : NULL);
+    for (int t = 0; t < pl; ++t) {
+      decode_token(ms[0], sq, prompts[(int64_t)p * prompt_stride + t], t == pl - 1 ? lg : NULL);
+      progress_note("rollout, prompt", n, t + 1, pl);
+    }
     int len = 0, cur = 0;
     for (int s = 0; s < limit; ++s) {
       while (cur + 1 < n_models && swap_at_step[cur] <= s) ++cur;
@@ -564,6 +583,7 @@ int orc_logprobs(const orc_desc *d, const float *blob, const int32_t *tokens, in
     decode_token(m, s, tokens[t], lg);
     orc_log_softmax(ls, lg, d->vocab, temperature);
     out[t + 1] = (double)ls[tokens[t + 1]];
+    progress_note("scoring", 0, t + 1, T - 1);
   }
   free(lg); free(ls); seq_free(s); model_free(m);
   return 0;

@@ -58,6 +58,7 @@ class Oracle:
                                    C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_float)]
         L.orc_rollout.restype = C.c_int
         L.orc_set_threads.argtypes = [C.c_int]
+        L.orc_set_progress_file.argtypes = [C.c_char_p]
         L.orc_get_threads.restype = C.c_int
 
     # -- primitives -------------------------------------------------------------------
@@ -210,6 +211,10 @@ class Oracle:
         if rc != 0:
             raise ValueError("orc_grpo_tensors: bad arguments")
         return mask, adv, adv_tok
+
+    def set_progress_file(self, path: Optional[str]) -> None:
+        """Long calls append a line every 32 tokens to this file (None: off)."""
+        self.lib.orc_set_progress_file(path.encode() if path else None)
 
     def set_threads(self, n: int) -> None:
         self.lib.orc_set_threads(n)

@@ -38,6 +38,8 @@ int echo_init(const echo_model_desc *desc, int device, void *dev_arena, size_t a
   if (!c->cs) { if ((e = hipStreamCreateWithFlags(&c->cs, hipStreamNonBlocking)) != hipSuccess) return bail("hipStreamCreate", e); c->own_cs = true; }
   if (!c->ks) { if ((e = hipStreamCreateWithFlags(&c->ks, hipStreamNonBlocking)) != hipSuccess) return bail("hipStreamCreate", e); c->own_ks = true; }
   if ((e = hipEventCreateWithFlags(&c->staged_ev, hipEventDisableTiming)) != hipSuccess) return bail("hipEventCreate", e);
+  for (int s = 0; s < 2; ++s)
+    if ((e = hipEventCreateWithFlags(&c->vacated_ev[s], hipEventDisableTiming)) != hipSuccess) return bail("hipEventCreate", e);
   for (int s = 0; s < desc->n_weight_slots; ++s) bind_slot(c, s);
   int32_t *r = at<int32_t>(c, p.o_rows);
   size_t M = p.Mcap;
@@ -180,7 +182,9 @@ void echo_destroy(echo_ctx *c) {
   hipStreamSynchronize(c->cs);
   hipStreamSynchronize(c->ks);
   if (c->graph) hipGraphExecDestroy(c->graph);
+  for (hipGraphExec_t g : c->retired_graphs) hipGraphExecDestroy(g);
   if (c->staged_ev) hipEventDestroy(c->staged_ev);
+  for (int s = 0; s < 2; ++s) if (c->vacated_ev[s]) hipEventDestroy(c->vacated_ev[s]);
   if (c->own_cs) hipStreamDestroy(c->cs);
   if (c->own_ks) hipStreamDestroy(c->ks);
   delete c;

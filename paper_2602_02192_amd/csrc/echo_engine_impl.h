@@ -195,6 +195,7 @@ struct echo_ctx {
   Slot slots[2];
   int active = -1, staged = -1;
   hipEvent_t staged_ev = nullptr;
+  hipEvent_t vacated_ev[2] = {nullptr, nullptr};   // recorded on the compute stream behind the last launch that reads a slot a rollout has left
   Loading load;
   int64_t newest_version = -1;
   int stage_flip = 0;
@@ -212,9 +213,11 @@ struct echo_ctx {
   DrawIds ids{nullptr, nullptr, nullptr};
   PrefixPlan px{nullptr, 0, 0, 1};       // shared-prompt attention jobs of the running rollout (n_jobs = 0: none)
   hipGraphExec_t graph = nullptr;
+  std::vector<hipGraphExec_t> retired_graphs;   // replaced while replays of them may still be queued; destroyed once the stream is idle
   // kernel timing (time_kernels)
   std::vector<std::pair<hipEvent_t, hipEvent_t>> ev_attn, ev_gemm;
   bool timing = false;
+  bool attn_plain = false;   // cross-check switch of the running rollout (echo_rollout_opts.attn_plain)
   double t_attn_bytes = 0, t_gemm_bytes = 0, cur_attn_bytes = 0;
 };
 
@@ -237,6 +240,17 @@ int fail(echo_ctx *c, int code, const char *fmt, ...) {
   } while (0)
 
 template <typename T> T *at(echo_ctx *c, size_t off) { return (T *)(c->arena + off); }
+
+// The rollout stops using weight slot `s` (call with c->mu held, outside stream capture): decode steps that read the slot
+// may still be queued on the compute stream, so whatever the copy stream does from now on -- the next install writes
+// into this slot -- starts behind them.  The wait is placed here, by the rollout's thread, and not by the installing
+// thread: the runtime refuses a cross-stream wait on an event of a stream that is capturing at that moment, and the
+// rollout captures its next step graph right after a switch.
+hipError_t leave_slot(echo_ctx *c, int s) {
+  hipError_t e = hipEventRecord(c->vacated_ev[s], c->cs);
+  if (e == hipSuccess) e = hipStreamWaitEvent(c->ks, c->vacated_ev[s], 0);
+  return e;
+}
 
 void bind_slot(echo_ctx *c, int s) {
   const echo_model_desc &d = c->d;
@@ -415,8 +429,6 @@ void norm_only(echo_ctx *c, const Slot &S, int M) {
                        d.hidden, d.rms_eps, c->cs);
 }
 
-bool env_flag(const char *name) { const char *v = getenv(name); return v && v[0] && v[0] != '0'; }
-
 struct ChunkRow { int32_t token, slot, pos; };
 
 // Feed the token strings (one per cache slot slot0 + q*slot_step) through the decoder in chunks of rows.
@@ -432,7 +444,7 @@ int run_chunk_seqs(echo_ctx *c, const Slot &S, const std::vector<ChunkSeq> &seqs
   std::vector<int32_t> tok(R), slot(R), pos(R), act(R);
   std::vector<PrefillBlock> blocks;
   const int block_rows = ATT_PREFILL_WAVES * ATT_PREFILL_COLS / (c->d.n_q_heads / c->d.n_kv_heads);
-  bool splitk = !env_flag("ECHO_ATTN_SIMPLE"), causal_blocks = c->p.fast && splitk;
+  bool splitk = !c->attn_plain, causal_blocks = c->p.fast && splitk;
   for (size_t a = 0; a < all.size(); a += R) {
     int M = (int)std::min<size_t>(R, all.size() - a);
     for (int i = 0; i < M; ++i) { tok[i] = all[a + i].token; slot[i] = all[a + i].slot; pos[i] = all[a + i].pos; act[i] = 1; }

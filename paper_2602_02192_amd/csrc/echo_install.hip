@@ -118,6 +118,8 @@ int echo_load_policy_begin(echo_ctx *c, int64_t version, size_t nbytes) {
   if (hipSetDevice(c->device) != hipSuccess) return undo(fail(c, ECHO_EHIP, "hipSetDevice failed"));
   if (!running && hipStreamSynchronize(c->cs) != hipSuccess) return undo(fail(c, ECHO_EHIP, "hipStreamSynchronize failed"));
   c->load.segs = blob_segments(c, target);
+  // (A rollout that has just switched away from the target slot may still have decode steps queued that read it; the
+  // rollout made the copy stream wait for them when it switched, see leave_slot.)
   // zero rows and columns of padding in the packed weights
   if (c->p.fast && hipMemsetAsync(c->slots[target].base, 0, c->p.slot_bytes, c->ks) != hipSuccess) return undo(fail(c, ECHO_EHIP, "hipMemsetAsync failed"));
   return ECHO_OK;

@@ -7,10 +7,10 @@ namespace {
 
 int capture_step(echo_ctx *c, const Slot &S, int N, int max_new, float temperature, uint64_t seed, bool unfused, const int32_t *forced,
                  int eos, float top_p, int per_row = 0) {
-  if (c->graph) { hipGraphExecDestroy(c->graph); c->graph = nullptr; }
+  if (c->graph) { c->retired_graphs.push_back(c->graph); c->graph = nullptr; }
   hipGraph_t g = nullptr;
   HIPCHK(c, hipStreamBeginCapture(c->cs, hipStreamCaptureModeThreadLocal));
-  forward_layers(c, S, N, !env_flag("ECHO_ATTN_SIMPLE"));
+  forward_layers(c, S, N, !c->attn_plain);
   sample_rows(c, S, N, temperature, seed, unfused, nullptr, top_p);
   launch_bookkeeping(N, max_new, per_row, c->d_step, c->d_samp_tok, c->d_samp_lp, forced, c->d_limit, eos, S.version, c->d_prompt_len_seq,
                      c->d_gen_len, c->rows, at<int32_t>(c, c->p.o_out_tok), at<float>(c, c->p.o_out_lp), at<int64_t>(c, c->p.o_out_ver),
@@ -40,12 +40,12 @@ double drain_events(std::vector<std::pair<hipEvent_t, hipEvent_t>> &v, int64_t *
 // for the whole rollout and grid_jobs the launch's job count (unused job slots are empty), so a captured step stays valid
 // when the list is rebuilt.  Leaves c->px.n_jobs = 0 when there is nothing to share or the decode kernel splits keys.
 int plan_prefix_jobs(echo_ctx *c, std::vector<int32_t> &ptiles, const std::vector<int32_t> &pslot, const std::vector<int32_t> &live, int R,
-                     int max_ptiles, int grid_jobs) {
+                     int max_ptiles, int grid_jobs, int prefix_kernel /* echo_rollout_opts.prefix_kernel */) {
   const int grp = c->d.n_q_heads / c->d.n_kv_heads, per_job = std::max(1, 32 / grp);
   const int cap = pad_rows(c->d.max_seqs) / 2 + 1;
   c->px = PrefixPlan{at<PrefixJob>(c, c->p.o_pjobs), 0, 0, 1};
   for (int r = 0; r < R; ++r) ptiles[r] &= ~ATT_PREFIX_DONE;
-  if (!c->p.fast || max_ptiles < 1 || fast_attention_splits(R, c->d.n_kv_heads, c->p.attn_max_splits) != 1 || env_flag("ECHO_NO_PREFIX_KERNEL")) return 0;
+  if (!c->p.fast || max_ptiles < 1 || fast_attention_splits(R, c->d.n_kv_heads, c->p.attn_max_splits) != 1 || prefix_kernel == 1) return 0;
   std::vector<PrefixJob> jobs;
   std::vector<int> order(R);
   for (int r = 0; r < R; ++r) order[r] = r;
@@ -73,9 +73,8 @@ int plan_prefix_jobs(echo_ctx *c, std::vector<int32_t> &ptiles, const std::vecto
   // The extra launch costs more than it saves at 64 rows x 16 tiles (measured: -7 % there; +1 % at 256 x 16, -2 % at a
   // draining 128 x 32, +5 % at 256 x 32), so small batches with short prompts keep reading their shared tiles in the
   // decode kernel.
-  int64_t covered = 0, min_covered = 6144;
+  int64_t covered = 0, min_covered = prefix_kernel == 2 ? 0 : 6144;
   for (const PrefixJob &jb : jobs) covered += (int64_t)jb.nrows * jb.ptiles;
-  if (const char *v = getenv("ECHO_PREFIX_KERNEL_MIN")) min_covered = atoll(v);
   if (jobs.empty() || (int)jobs.size() > cap || covered < min_covered) {
     for (int r = 0; r < R; ++r) ptiles[r] &= ~ATT_PREFIX_DONE;
     return 0;
@@ -107,6 +106,7 @@ int check_rollout_args(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt
   if (P < 1 || G < 1 || max_new < 1 || prompt_stride < 1) return fail(c, ECHO_EINVAL, "n_prompts, G, max_new and prompt_stride must be positive");
   if (!(temperature > 0.f)) return fail(c, ECHO_EINVAL, "temperature must be positive");
   if (!(o->top_p > 0.f) || o->top_p > 1.0f) return fail(c, ECHO_EINVAL, "top_p must be in (0, 1]");
+  if (o->prefix_kernel < 0 || o->prefix_kernel > 2) return fail(c, ECHO_EINVAL, "prefix_kernel must be 0, 1 or 2");
   if ((int64_t)P * G * max_new > INT32_MAX) return fail(c, ECHO_EINVAL, "n_prompts * G * max_new exceeds 2^31 - 1");
   int max_pl = 0;
   for (int p = 0; p < P; ++p) {
@@ -140,11 +140,20 @@ struct RolloutGuard {
   }
   ~RolloutGuard() {
     if (!held) return;
+    if (!c->retired_graphs.empty()) {   // step graphs replaced at a snapshot switch or a compaction
+      hipStreamSynchronize(c->cs);
+      for (hipGraphExec_t g : c->retired_graphs) hipGraphExecDestroy(g);
+      c->retired_graphs.clear();
+    }
     std::lock_guard<std::mutex> lk(c->mu);
     c->rollout_running = false;
+    c->attn_plain = false;
     c->ids = DrawIds{c->d_step, nullptr, nullptr};
     c->px.n_jobs = 0;
-    if (c->staged >= 0) { c->active = c->staged; c->staged = -1; c->st.active_version = c->slots[c->active].version; c->st.staged_version = -1; }
+    if (c->staged >= 0) {   // (a rollout that failed half-way may have left work queued on the old slot)
+      leave_slot(c, c->active);
+      c->active = c->staged; c->staged = -1; c->st.active_version = c->slots[c->active].version; c->st.staged_version = -1;
+    }
   }
 };
 
@@ -205,7 +214,8 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
   HIPCHK(c, hipStreamSynchronize(st));
 
   int cur = c->active;
-  const bool share_prefix = p.fast && !env_flag("ECHO_NO_PREFIX_SHARING") && !env_flag("ECHO_ATTN_SIMPLE");
+  c->attn_plain = o.attn_plain != 0;
+  const bool share_prefix = p.fast && !o.own_prompt_copy && !o.attn_plain;
   // ---- prefill the P unique prompts into cache slots p*G, keep each prompt's last hidden state
   std::vector<int> lens(prompt_lens, prompt_lens + P);
   std::vector<int32_t> map(std::max(P, N));
@@ -239,7 +249,7 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
       ptiles[n] = share_prefix ? prompt_lens[n / G] / 32 : 0;
       max_ptiles = std::max(max_ptiles, ptiles[n]);
     }
-    if ((rc = plan_prefix_jobs(c, ptiles, pslot, live, N, max_ptiles, 0))) return rc;
+    if ((rc = plan_prefix_jobs(c, ptiles, pslot, live, N, max_ptiles, 0, o.prefix_kernel))) return rc;
     HIPCHK(c, hipMemcpyAsync(c->rows.pslot, pslot.data(), N * 4, hipMemcpyHostToDevice, st));
     HIPCHK(c, hipMemcpyAsync(c->rows.ptiles, ptiles.data(), N * 4, hipMemcpyHostToDevice, st));
     HIPCHK(c, hipStreamSynchronize(st));   // the host vectors go out of scope
@@ -269,7 +279,7 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
   double swap_wait = 0;
   int next_swap = 0, decode_steps = 0;
   bool have_graph = false;
-  bool splitk = !env_flag("ECHO_ATTN_SIMPLE");
+  bool splitk = !o.attn_plain;
   for (int s = 1; s < steps; ++s) {
     if (next_swap < o.n_swaps && o.swap_at_step[next_swap] == s) {
       auto w0 = std::chrono::steady_clock::now();
@@ -277,6 +287,7 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
       int tmo = o.swap_timeout_ms > 0 ? o.swap_timeout_ms : 10000;
       if (!c->cv.wait_for(lk, std::chrono::milliseconds(tmo), [&] { return c->staged >= 0; }))
         return fail(c, ECHO_ESTATE, "no snapshot was staged for the swap at step %d within %d ms", s, tmo);
+      HIPCHK(c, leave_slot(c, cur));   // before the lock is released: an install that finds the old slot free starts behind its readers
       cur = c->staged; c->active = cur; c->staged = -1;
       c->st.active_version = c->slots[cur].version; c->st.staged_version = -1;
       lk.unlock();
@@ -369,8 +380,9 @@ int echo_rollout_continuous(echo_ctx *c, const int32_t *prompt_tokens, int32_t p
   auto t0 = std::chrono::steady_clock::now();
   const bool unfused = o.unfused_sampler || o.top_p < 1.0f;
   const bool use_graph = !o.no_graph;
-  const bool share_prefix = p.fast && !env_flag("ECHO_NO_PREFIX_SHARING") && !env_flag("ECHO_ATTN_SIMPLE");
-  const bool splitk = !env_flag("ECHO_ATTN_SIMPLE");
+  c->attn_plain = o.attn_plain != 0;
+  const bool share_prefix = p.fast && !o.own_prompt_copy && !o.attn_plain;
+  const bool splitk = !o.attn_plain;
   const int R = std::min(N, c->d.max_seqs);   // cache slots in use; rows of the batch until the rows are compacted
   int Rc = R;                                 // rows of the batch now
   // host mirrors of the per-row state; token, pos, active and gen are read back at every check
@@ -510,7 +522,7 @@ int echo_rollout_continuous(echo_ctx *c, const int32_t *prompt_tokens, int32_t p
         std::vector<int32_t> live(R, 0);
         for (int r = 0; r < Rc; ++r) live[r] = row_seq[r] >= 0 && act[r];
         const PrefixPlan was = c->px;
-        if ((rc = plan_prefix_jobs(c, ptiles, pslot, live, Rc, share_prefix ? (max_pl - 1) / 32 : 0, Rc / 2 + 1))) return rc;
+        if ((rc = plan_prefix_jobs(c, ptiles, pslot, live, Rc, share_prefix ? (max_pl - 1) / 32 : 0, Rc / 2 + 1, o.prefix_kernel))) return rc;
         if (was.n_jobs != c->px.n_jobs || was.np != c->px.np || was.tiles_per_chunk != c->px.tiles_per_chunk) have_graph = false;
         if ((rc = upload_rows())) return rc;
         HIPCHK(c, hipStreamSynchronize(st));
@@ -529,6 +541,7 @@ int echo_rollout_continuous(echo_ctx *c, const int32_t *prompt_tokens, int32_t p
       std::unique_lock<std::mutex> lk(c->mu);
       if (c->staged >= 0) {
         auto w0 = std::chrono::steady_clock::now();
+        HIPCHK(c, leave_slot(c, cur));   // the steps queued so far still read the old slot
         cur = c->staged; c->active = cur; c->staged = -1;
         c->st.active_version = c->slots[cur].version; c->st.staged_version = -1;
         lk.unlock();

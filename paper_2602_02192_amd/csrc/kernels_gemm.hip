@@ -12,16 +12,9 @@
 
 namespace echo {
 
-// Packed weight addressing, in units of 16 bytes (8 halves).  ECHO_W_KSMAJOR = 0: one 32-row block is contiguous
-// over K.  ECHO_W_KSMAJOR = 1: k-step major -- all row blocks of one k-step are contiguous, so wavefronts that
-// advance together sweep HBM like one streaming copy.
-#ifndef ECHO_W_KSMAJOR
-#define ECHO_W_KSMAJOR 0
-#endif
-__host__ __device__ __forceinline__ int64_t w_block_base(int nb, int Kp) {
-  return ECHO_W_KSMAJOR ? (int64_t)nb * 64 : (int64_t)nb * (Kp >> 3) * 32;
-}
-__host__ __device__ __forceinline__ int64_t w_kstep_stride(int Np) { return ECHO_W_KSMAJOR ? (int64_t)(Np >> 5) * 64 : 64; }
+// Packed weight addressing, in units of 16 bytes (8 halves): one 32-row block is contiguous over K, a k-step of it is 64 units.
+__host__ __device__ __forceinline__ int64_t w_block_base(int nb, int Kp) { return (int64_t)nb * (Kp >> 3) * 32; }
+__host__ __device__ __forceinline__ int64_t w_kstep_stride(int) { return 64; }
 
 // ---- weight repacking --------------------------------------------------------------------------------
 // src: row-major bf16 [n_rows][K]; destination row of source row i is dst_row0 + i*dst_row_stride.

@@ -12,6 +12,16 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+@pytest.fixture(scope="session", autouse=True)
+def _oracle_progress_notes():
+    """Where a run is watched through the files under gpurun_out/, the oracle's minutes-long calls leave notes there."""
+    out = os.path.join(ROOT, "gpurun_out")
+    if os.path.isdir(out):
+        from oracle import oracle
+        oracle.load("f64").set_progress_file(os.path.join(out, "oracle_progress.log"))
+    yield
+
+
 @pytest.fixture(scope="session")
 def orc():
     from oracle import oracle

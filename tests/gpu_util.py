@@ -50,3 +50,16 @@ def argmax_agreement(gpu_logits, ref_logits, mask, tol):
     clear = gap > 2 * tol
     rate_clear = float((ga[clear] == ra[clear]).mean()) if clear.any() else 1.0
     return rate_clear, float((ga == ra).mean()), int(clear.sum())
+
+
+def check_argmax(gpu_logits, ref_logits, mask, tol, label=""):
+    """The stated argmax bound, asserted on the raw rate wherever there are enough positions for 99.5 % to mean
+    something (at least 200); the rate over clearly separated positions follows from the logit bound and must be 1.
+    Prints both rates."""
+    rate_clear, raw, n_clear = argmax_agreement(gpu_logits, ref_logits, mask, tol)
+    n = int(np.asarray(mask).sum())
+    print(f"[argmax {label}] raw agreement {raw:.4f} over {n} positions, {rate_clear:.4f} over the {n_clear} with a top-2 gap > {2 * tol}")
+    assert rate_clear == 1.0, (label, rate_clear, n_clear)
+    if n >= 200:
+        assert raw >= BF16_ARGMAX_RATE, (label, raw, n)
+    return raw

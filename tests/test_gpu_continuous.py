@@ -84,7 +84,7 @@ def test_bf16_path_against_the_oracle_and_against_rollouts_that_fit(P, max_seqs)
     ctx.close()
 
 
-def test_shared_prompt_tiles_do_not_change_a_continuous_rollout(monkeypatch):
+def test_shared_prompt_tiles_do_not_change_a_continuous_rollout():
     shape = MID
     blob = synth.make_weights(shape, 0)
     P, G, max_new = 6, 4, 8
@@ -93,13 +93,11 @@ def test_shared_prompt_tiles_do_not_change_a_continuous_rollout(monkeypatch):
     stop = synth.make_stop_lens(P * G, 1, max_new, seed=9)
     ctx = make_ctx(shape, 8, 128, blob)
     a = ctx.rollout(prompts, lens, G, max_new, 1.0, 3, stop_lens=stop, continuous=True)
-    monkeypatch.setenv("ECHO_NO_PREFIX_SHARING", "1")
-    b = ctx.rollout(prompts, lens, G, max_new, 1.0, 3, stop_lens=stop, continuous=True)
+    b = ctx.rollout(prompts, lens, G, max_new, 1.0, 3, stop_lens=stop, continuous=True, own_prompt_copy=True)
     for k in ("tokens", "logprobs", "lens"):
         assert np.array_equal(a[k], b[k]), k
     # what shares the batch with a sequence does not change its record beyond rounding (another batch size splits the
     # keys and the GEMMs differently): capacity for all groups at once, fed a's tokens, reproduces a
-    monkeypatch.delenv("ECHO_NO_PREFIX_SHARING")
     ctx.close()
     big = make_ctx(shape, 24, 128, blob)
     c = big.rollout(prompts, lens, G, max_new, 1.0, 3, stop_lens=stop, continuous=True, forced=a["tokens"].clip(0))
@@ -144,11 +142,10 @@ def test_a_staged_snapshot_is_switched_in_between_steps_and_errors():
     ctx.close()
 
 
-def test_refill_and_compaction_with_the_groups_prompts_attended_once_per_group(monkeypatch):
+def test_refill_and_compaction_with_the_groups_prompts_attended_once_per_group():
     """Enough rows that a row's keys stay in one workgroup, so the shared prompt tiles can go through the prefix kernel
     (forced on: at this size it would not pay): its job list is rebuilt as groups are admitted, finish and are
     compacted.  Teacher-forced against the oracle."""
-    monkeypatch.setenv("ECHO_PREFIX_KERNEL_MIN", "0")
     shape = MID
     blob = synth.make_weights(shape, 0)
     blob32 = synth.widen_to_f32(blob)
@@ -158,7 +155,7 @@ def test_refill_and_compaction_with_the_groups_prompts_attended_once_per_group(m
     stop = synth.make_stop_lens(P * G, 1, max_new, seed=13)
     ref = oracle_rollout(shape, blob32, prompts, lens, G=G, max_new=max_new, temperature=1.0, seed=2, stop_lens=stop)
     ctx = make_ctx(shape, 168, 128, blob)
-    out = ctx.rollout(prompts, lens, G, max_new, 1.0, 2, stop_lens=stop, continuous=True, forced=ref["tokens"].clip(0))
+    out = ctx.rollout(prompts, lens, G, max_new, 1.0, 2, stop_lens=stop, continuous=True, forced=ref["tokens"].clip(0), prefix_kernel=2)
     m = valid_mask(stop, max_new)
     assert np.array_equal(out["lens"], stop)
     same = (out["tokens"] == ref["tokens"]) & m
