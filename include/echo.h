@@ -194,6 +194,21 @@ int echo_grpo_tensors(echo_ctx *ctx, const int32_t *tokens, int32_t stride, cons
                       int32_t G, int32_t turn_start_id, const float *rewards, float eps, uint8_t *out_mask,
                       float *out_adv, float *out_adv_tok);
 
+/* echo_grpo_tensors for callers that cannot allocate device memory and whose context has no arena to lend (tight serving
+ * loops, harnesses that forbid hipMalloc): same arguments, same kernels and bit-identical results, but the records are
+ * staged in a fixed array of ECHO_STATIC_SCRATCH_BYTES that the library itself holds on every GPU it runs on (from
+ * echo_init of the first context on that GPU until the process ends) instead of in the context's arena.  The call
+ * allocates nothing: no hipMalloc / hipFree, no allocating library routine.  All records of a call must fit the
+ * array at once -- 9 bytes per token of n_seqs * stride plus 12 per record, each part rounded up to 16 -- or the call
+ * returns ECHO_ENOMEM and says how much was asked for; unlike echo_grpo_tensors it does not run in passes.  Other
+ * errors as echo_grpo_tensors (ECHO_ESTATE during a rollout on the same context).  Every call on a GPU, whatever its
+ * context, uses that GPU's one array, which keeps the previous call's contents (nothing in it needs to start from
+ * zero): calls that overlap in time on one GPU race; serialise them. */
+#define ECHO_STATIC_SCRATCH_BYTES (32u << 20)
+int echo_grpo_tensors_static(echo_ctx *ctx, const int32_t *tokens, int32_t stride, const int32_t *lens, int32_t n_seqs,
+                             int32_t G, int32_t turn_start_id, const float *rewards, float eps, uint8_t *out_mask,
+                             float *out_adv, float *out_adv_tok);
+
 /* Raw 32-bit draws of the sampler's generator for (seed; n, s, i = i0..i0+count-1), computed on the GPU
  * (out: host [count]).  Exists so that the generator can be compared bit for bit with its definition. */
 int echo_debug_draw_bits(echo_ctx *ctx, uint64_t seed, uint32_t n, uint32_t s, uint32_t i0, int32_t count,

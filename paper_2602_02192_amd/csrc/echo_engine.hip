@@ -2,6 +2,8 @@
 // tensors, statistics.  (Snapshot install: echo_install.hip; rollouts: echo_rollout.hip.)
 #include "echo_engine_impl.h"
 
+int echo_static_scratch_resolve(int device);   // echo_noalloc.hip: looks up this GPU's copy of the library's static scratch
+
 // =================================================================================================== C ABI
 extern "C" {
 
@@ -40,6 +42,7 @@ int echo_init(const echo_model_desc *desc, int device, void *dev_arena, size_t a
   if ((e = hipEventCreateWithFlags(&c->staged_ev, hipEventDisableTiming)) != hipSuccess) return bail("hipEventCreate", e);
   for (int s = 0; s < 2; ++s)
     if ((e = hipEventCreateWithFlags(&c->vacated_ev[s], hipEventDisableTiming)) != hipSuccess) return bail("hipEventCreate", e);
+  if (int se = echo_static_scratch_resolve(device)) return bail("hipGetSymbolAddress(static scratch)", (hipError_t)se);
   for (int s = 0; s < desc->n_weight_slots; ++s) bind_slot(c, s);
   int32_t *r = at<int32_t>(c, p.o_rows);
   size_t M = p.Mcap;

@@ -51,7 +51,7 @@ class Stats(C.Structure):
 
 EXPORTS = ["echo_arena_bytes", "echo_blob_bytes", "echo_init", "echo_load_policy", "echo_load_policy_begin",
            "echo_load_policy_chunk", "echo_load_policy_commit", "echo_load_policy_abort", "echo_rollout", "echo_rollout_continuous",
-           "echo_logprobs", "echo_grpo_tensors", "echo_debug_draw_bits", "echo_stats", "echo_last_error", "echo_destroy"]
+           "echo_logprobs", "echo_grpo_tensors", "echo_grpo_tensors_static", "echo_debug_draw_bits", "echo_stats", "echo_last_error", "echo_destroy"]
 
 lib.echo_arena_bytes.restype = C.c_size_t
 lib.echo_arena_bytes.argtypes = [C.POINTER(ModelDesc)]
@@ -71,6 +71,8 @@ lib.echo_rollout_continuous.argtypes = lib.echo_rollout.argtypes
 lib.echo_logprobs.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_float, C.c_void_p]
 lib.echo_grpo_tensors.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                   C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
+lib.echo_grpo_tensors_static.argtypes = lib.echo_grpo_tensors.argtypes
+STATIC_SCRATCH_BYTES = 32 << 20
 lib.echo_debug_draw_bits.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int32,
                                      C.c_void_p]
 lib.echo_stats.argtypes = [C.c_void_p, C.POINTER(Stats)]
@@ -242,14 +244,16 @@ class Context:
                                     _ptr(out)))
         return out
 
-    def grpo_tensors(self, tokens, lens, G: int, turn_start_id: int, rewards, eps: float = 1e-6, per_token: bool = True):
+    def grpo_tensors(self, tokens, lens, G: int, turn_start_id: int, rewards, eps: float = 1e-6, per_token: bool = True,
+                     static_scratch: bool = False):
         tokens = np.ascontiguousarray(tokens, np.int32)
         lens = np.ascontiguousarray(lens, np.int32)
         rewards = np.ascontiguousarray(rewards, np.float32)
         mask = np.empty(tokens.shape, np.uint8)
         adv = np.empty(tokens.shape[0], np.float32)
         adv_tok = np.empty(tokens.shape, np.float32) if per_token else None
-        self._chk(lib.echo_grpo_tensors(self.h, _ptr(tokens), tokens.shape[1], _ptr(lens), tokens.shape[0], G, turn_start_id,
+        fn = lib.echo_grpo_tensors_static if static_scratch else lib.echo_grpo_tensors
+        self._chk(fn(self.h, _ptr(tokens), tokens.shape[1], _ptr(lens), tokens.shape[0], G, turn_start_id,
                                         _ptr(rewards), eps, _ptr(mask), _ptr(adv), _ptr(adv_tok) if per_token else None))
         return mask, adv, adv_tok
 
