@@ -65,13 +65,14 @@ WORKLOADS = {
 }
 
 
-def algorithmic_bytes(shape, gen_lens, prompt_len, group=1, first_step=1):
+def algorithmic_bytes(shape, gen_lens, prompt_len, group=1, first_step=1, per_step_out=None):
     """HBM bytes the decode steps must move: all decode-read weights once per step, the K/V of every active
     sequence once per step, and the new K/V written.  gen_lens: tokens generated per sequence (prompt-major,
     `group` sequences per prompt).  The whole 32-key tiles of a prompt are read from one copy per group by the
     decode attention kernel, so they count once per group that still has an active sequence; group=1 gives the
     per-sequence figure (every sequence reads its own copy of everything).  first_step=0: the first token, too, comes
-    out of a decode step (continuous rollouts); the K/V terms depend on each sequence's own steps only, not on when it ran."""
+    out of a decode step (continuous rollouts); the K/V terms depend on each sequence's own steps only, not on when it ran.
+    per_step_out: a list that receives the bytes of every decode pass, in step order."""
     e = 2 if shape.dtype == "bf16" else 4
     hd, H = shape.head_dim, shape.hidden
     per_layer = H * (shape.n_q_heads + 2 * shape.n_kv_heads) * hd + shape.n_q_heads * hd * H + 3 * H * shape.ffn
@@ -85,28 +86,39 @@ def algorithmic_bytes(shape, gen_lens, prompt_len, group=1, first_step=1):
     active = np.array([(gen > s).sum() for s in range(first_step, steps)], np.int64)   # decode pass s serves sequences with gen > s
     groups = np.array([(group_len > s).sum() for s in range(first_step, steps)], np.int64)
     kv_read = groups * shared + active * (prompt_len - shared + s_idx)
-    total = int((w_dec + kv_read * kvb + active * kvb).sum())
+    per_step = w_dec + kv_read * kvb + active * kvb
+    if per_step_out is not None:
+        per_step_out.extend(int(b) for b in per_step)
+    total = int(per_step.sum())
     return total, w_dec, kvb
 
 
-def cpu_baseline(shape, blob, seconds_budget=20.0):
-    """The oracle (fp32 build, as it stands) on one sequence of the same model: a short prompt and a
-    few generated tokens, all layers at full width."""
+def cpu_baseline(shape, blob, wl):
+    """The oracle (fp32 build, as it stands) on a bounded slice of the same workload.  The tiny workload: the whole
+    rollout.  The large shapes: one sequence with the workload's prompt length (at most 512 tokens) and four generated
+    tokens, all layers at full width -- the oracle's cost per token is the same at every step, so the slice fixes its
+    rate; its prompt pass is inside the timed call as the GPU's prefill is inside the rollout."""
     from oracle import oracle
     from paper_2602_02192_amd import synth
     orc = oracle.load("f32")
     cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")))
     orc.set_threads(cores)
-    prompt_len, new = (16, 32) if shape.n_layers <= 2 else (64, 64)
-    prompts, lens = synth.make_prompts(shape.vocab, 1, prompt_len, seed=1)
+    if shape.n_layers <= 2:
+        P, G, prompt_len, new = wl["P"], wl["G"], wl["plen"], wl["max_new"]
+    else:
+        P, G, prompt_len, new = 1, 1, min(512, wl["plen"]), 4
+    prompts, lens = synth.make_prompts(shape.vocab, P, prompt_len, seed=1)
     b32 = synth.widen_to_f32(blob)
     t0 = time.perf_counter()
-    r = orc.rollout(oracle.desc_from_shape(shape), b32, prompts, lens, G=1, max_new=new, temperature=1.0, seed=2)
+    r = orc.rollout(oracle.desc_from_shape(shape), b32, prompts, lens, G=G, max_new=new, temperature=1.0, seed=2)
     dt = time.perf_counter() - t0
     del b32
-    return {"value": float(r["lens"].sum() / dt), "unit": "generated tokens/s", "cores": orc.get_threads(),
-            "kind": "oracle", "sample": f"fp32 oracle, 1 sequence, prompt {prompt_len} + {new} new tokens, all "
-            f"{shape.n_layers} layers at full width, {dt:.1f} s"}
+    n_gen = int(r["lens"].sum())
+    n_fed = int(P * G * prompt_len + n_gen - P * G)
+    return {"value": float(n_gen / dt), "unit": "generated tokens/s", "cores": orc.get_threads(),
+            "kind": "oracle", "tokens_through_the_decoder_per_s": float(n_fed / dt),
+            "sample": f"fp32 oracle, {P * G} sequence(s), prompt {prompt_len} + {new} new tokens, all "
+            f"{shape.n_layers} layers at full width, {dt:.1f} s (prompt pass included; every token costs one pass through the decoder)"}
 
 
 def main():
@@ -117,6 +129,7 @@ def main():
     ap.add_argument("--workload", default="dense4b-64x512+1024", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--no-step-timing", action="store_true")
     ap.add_argument("--ctx-pad", type=int, default=0, help="extra KV-cache tokens per sequence beyond prompt + max_new")
     ap.add_argument("--pageable-blob", action="store_true",
                     help="keep the host copy of the weights in pageable memory (a counter-collecting profiler crashed on the pinned copy)")
@@ -240,6 +253,25 @@ def main():
         step_frac = bytes_decode / (np.mean(decode_ms) * 1e-3) / (HBM_PEAK_GBS * 1e9)
         step_frac_per_seq = bytes_per_seq / (np.mean(decode_ms) * 1e-3) / (HBM_PEAK_GBS * 1e9)
 
+    # per-step roofline fractions: one more rollout (graph replay as timed above) with a HIP event between every two steps
+    step_stats = {}
+    if not continuous and not swaps and not a.no_step_timing:
+        rollout(2 + a.steps - 1, time_steps=True)
+        progress("rollout with per-step event timing done")
+        sm = ctx.step_times().astype(np.float64)
+        strict, per_seq = [], []
+        algorithmic_bytes(shape, out["lens"], plen, G, per_step_out=strict)
+        algorithmic_bytes(shape, out["lens"], plen, 1, per_step_out=per_seq)
+        n = min(len(sm), len(strict))
+        if n > 0:
+            fs = np.array(strict[:n]) / (sm[:n] * 1e-3) / (HBM_PEAK_GBS * 1e9)
+            fp = np.array(per_seq[:n]) / (sm[:n] * 1e-3) / (HBM_PEAK_GBS * 1e9)
+            step_stats = {"steps_timed": int(n), "step_ms_p10_median_p90": [float(np.percentile(sm[:n], q)) for q in (10, 50, 90)],
+                          "hbm_frac_p10": float(np.percentile(fs, 10)), "hbm_frac_median": float(np.percentile(fs, 50)),
+                          "hbm_frac_p90": float(np.percentile(fs, 90)),
+                          "hbm_frac_if_every_sequence_read_its_own_prompt_copy_p10_median_p90":
+                              [float(np.percentile(fp, q)) for q in (10, 50, 90)]}
+
     score = None
     if wl.get("score"):       # teacher-forced log-probs of every generated string (prompt + response) under the active snapshot
         full = np.concatenate([np.repeat(prompts, G, axis=0), np.maximum(out["tokens"], 0)], axis=1)
@@ -292,7 +324,7 @@ def main():
                                                   "launches_timed": int(st.gemm_launches)}
     cpu = None
     if not a.no_cpu_baseline and blob.numel() < 6e9:   # the oracle needs an fp32 copy of the weights: 4B-class and smaller
-        cpu = cpu_baseline(shape, blob)
+        cpu = cpu_baseline(shape, blob, wl)
     ctx.close()
     line = {
         "metric": "rollout generated tokens/s on 1 MI355X", "value": value, "unit": "generated tokens/s",
@@ -307,7 +339,8 @@ def main():
                         "hbm_frac_of_8TBps": step_frac, "algorithmic_bytes_per_rollout": bytes_decode,
                         "hbm_frac_if_every_sequence_read_its_own_prompt_copy": step_frac_per_seq,
                         "prefill_ms": float(np.mean(prefill_ms)), "policy_install_s": load_s,
-                        "swaps_per_rollout": len(swaps), "install_chunk_mb": a.install_chunk_mb, "swap_wait_ms": float(np.mean(swap_wait_ms))},
+                        "swaps_per_rollout": len(swaps), "install_chunk_mb": a.install_chunk_mb, "swap_wait_ms": float(np.mean(swap_wait_ms)),
+                        **step_stats},
         "scoring_pass": score,
         "roofline": roofline, "cpu_baseline": cpu,
     }

@@ -75,6 +75,8 @@ typedef struct {
   int32_t no_graph;            /* 1: launch decode steps kernel by kernel instead of replaying a HIP graph */
   int32_t time_kernels;        /* 1: bracket decode-attention and GEMM launches with HIP events (implies
                                   no_graph); durations are read back with echo_stats */
+  int32_t time_steps;          /* 1 (echo_rollout only): a HIP event between every two decode steps (graph replays
+                                  included); the per-step durations are read back with echo_step_times */
   /* Cross-check switches (0 = the default path; results differ from it by rounding order at most, see each): */
   int32_t attn_plain;          /* 1: decode and prompt attention by the plain kernel (one wavefront per (row, head), two
                                   passes, no key splitting, no sharing of prompt tiles) instead of the MFMA kernels */
@@ -215,6 +217,11 @@ int echo_debug_draw_bits(echo_ctx *ctx, uint64_t seed, uint32_t n, uint32_t s, u
                          uint32_t *out_bits);
 
 int echo_stats(echo_ctx *ctx, echo_stats_t *out);
+
+/* Durations in milliseconds of the decode steps of the last echo_rollout that ran with time_steps = 1, in step order
+ * (entry k: decode step k + 1, i.e. the pass that produced generated token k + 1): out_ms host [cap].  Returns the
+ * number of steps that were timed (which may exceed cap; only cap entries are written), or a negative echo_status. */
+int echo_step_times(echo_ctx *ctx, float *out_ms, int32_t cap);
 
 /* Message for the last error on this context (ctx-owned, valid until the next call); "" if none.
  * With ctx == NULL: the message of the last failed echo_init on this thread. */

@@ -177,6 +177,15 @@ int echo_stats(echo_ctx *c, echo_stats_t *out) {
   return ECHO_OK;
 }
 
+int echo_step_times(echo_ctx *c, float *out_ms, int32_t cap) {
+  if (!c) return ECHO_EINVAL;
+  if (cap < 0 || (cap > 0 && !out_ms)) return fail(c, ECHO_EINVAL, "bad argument");
+  std::lock_guard<std::mutex> lk(c->mu);
+  if (c->rollout_running) return fail(c, ECHO_ESTATE, "a rollout is running on this context");
+  for (size_t i = 0; i < c->step_ms.size() && i < (size_t)cap; ++i) out_ms[i] = c->step_ms[i];
+  return (int)c->step_ms.size();
+}
+
 const char *echo_last_error(const echo_ctx *c) { return c ? c->err.c_str() : g_init_error.c_str(); }
 
 void echo_destroy(echo_ctx *c) {

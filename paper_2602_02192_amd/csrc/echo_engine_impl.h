@@ -217,6 +217,7 @@ struct echo_ctx {
   // kernel timing (time_kernels)
   std::vector<std::pair<hipEvent_t, hipEvent_t>> ev_attn, ev_gemm;
   bool timing = false;
+  std::vector<float> step_ms;   // per-step durations of the last rollout run with time_steps
   bool attn_plain = false;   // cross-check switch of the running rollout (echo_rollout_opts.attn_plain)
   double t_attn_bytes = 0, t_gemm_bytes = 0, cur_attn_bytes = 0;
 };

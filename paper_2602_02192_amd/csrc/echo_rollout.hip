@@ -239,8 +239,9 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
   HIPCHK(c, hipMemcpyAsync(c->d_map_a, map.data(), N * 4, hipMemcpyHostToDevice, st));
   launch_gather_rows_f32(at<float>(c, p.o_h), first_h, c->d_map_a, N, c->d.hidden, st);
   launch_fill_i32(c->rows.active, 1, N, st);
-  for (int n = 0; n < N; ++n) map[n] = n;
-  HIPCHK(c, hipMemcpyAsync(c->rows.slot, map.data(), N * 4, hipMemcpyHostToDevice, st));
+  std::vector<int32_t> ident(N);   // (a vector of its own: the copy above may still be reading `map`)
+  for (int n = 0; n < N; ++n) ident[n] = n;
+  HIPCHK(c, hipMemcpyAsync(c->rows.slot, ident.data(), N * 4, hipMemcpyHostToDevice, st));
   {   // decode attention reads the whole tiles of a group's prompt from the group's first slot
     std::vector<int32_t> pslot(N), ptiles(N), live(N, 1);
     int max_ptiles = 0;
@@ -276,6 +277,16 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
 
   // ---- decode
   c->timing = want_timing;
+  std::vector<hipEvent_t> step_ev;   // time_steps: one event per step boundary
+  auto mark_step = [&]() -> int {
+    if (!o.time_steps) return 0;
+    hipEvent_t e;
+    HIPCHK(c, hipEventCreate(&e));
+    step_ev.push_back(e);
+    HIPCHK(c, hipEventRecord(e, st));
+    return 0;
+  };
+  if ((rc = mark_step())) return rc;
   double swap_wait = 0;
   int next_swap = 0, decode_steps = 0;
   bool have_graph = false;
@@ -330,9 +341,18 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
     }
     c->timing = time_this;
     ++decode_steps;
+    if ((rc = mark_step())) return rc;
   }
   HIPCHK(c, hipStreamSynchronize(st));
   auto t2 = std::chrono::steady_clock::now();
+  if (o.time_steps) {
+    c->step_ms.clear();
+    for (size_t i = 1; i < step_ev.size(); ++i) {
+      float t = 0;
+      if (hipEventElapsedTime(&t, step_ev[i - 1], step_ev[i]) == hipSuccess) c->step_ms.push_back(t);
+    }
+    for (hipEvent_t e : step_ev) hipEventDestroy(e);
+  }
 
   // ---- results
   HIPCHK(c, hipMemcpyAsync(out_tokens, at<int32_t>(c, p.o_out_tok), outn * 4, hipMemcpyDeviceToHost, st));
@@ -365,8 +385,8 @@ int echo_rollout_continuous(echo_ctx *c, const int32_t *prompt_tokens, int32_t p
   int rc = check_rollout_args(c, prompt_tokens, prompt_stride, prompt_lens, P, G, max_new, temperature, opts, out_tokens, out_logprobs,
                               out_lens, &o);
   if (rc) return rc;
-  if (o.n_swaps || o.debug_logits || o.time_kernels)
-    return fail(c, ECHO_EINVAL, "a continuous rollout takes no pinned swaps (it switches when a snapshot is staged), no debug_logits and no time_kernels");
+  if (o.n_swaps || o.debug_logits || o.time_kernels || o.time_steps)
+    return fail(c, ECHO_EINVAL, "a continuous rollout takes no pinned swaps (it switches when a snapshot is staged), no debug_logits, no time_kernels and no time_steps");
   if (G > c->d.max_seqs) return fail(c, ECHO_ENOMEM, "one group of %d sequences exceeds max_seqs = %d", G, c->d.max_seqs);
   const int N = P * G;
   int max_pl = 0;

@@ -36,7 +36,7 @@ class RolloutOpts(C.Structure):
     _fields_ = [("stop_lens", C.c_void_p), ("eos_id", C.c_int32), ("top_p", C.c_float),
                 ("n_swaps", C.c_int32), ("swap_at_step", C.c_void_p), ("swap_timeout_ms", C.c_int32),
                 ("forced_tokens", C.c_void_p), ("debug_logits", C.c_void_p),
-                ("unfused_sampler", C.c_int32), ("no_graph", C.c_int32), ("time_kernels", C.c_int32),
+                ("unfused_sampler", C.c_int32), ("no_graph", C.c_int32), ("time_kernels", C.c_int32), ("time_steps", C.c_int32),
                 ("attn_plain", C.c_int32), ("own_prompt_copy", C.c_int32), ("prefix_kernel", C.c_int32)]
 
 
@@ -51,7 +51,7 @@ class Stats(C.Structure):
 
 EXPORTS = ["echo_arena_bytes", "echo_blob_bytes", "echo_init", "echo_load_policy", "echo_load_policy_begin",
            "echo_load_policy_chunk", "echo_load_policy_commit", "echo_load_policy_abort", "echo_rollout", "echo_rollout_continuous",
-           "echo_logprobs", "echo_grpo_tensors", "echo_grpo_tensors_static", "echo_debug_draw_bits", "echo_stats", "echo_last_error", "echo_destroy"]
+           "echo_logprobs", "echo_grpo_tensors", "echo_grpo_tensors_static", "echo_debug_draw_bits", "echo_stats", "echo_step_times", "echo_last_error", "echo_destroy"]
 
 lib.echo_arena_bytes.restype = C.c_size_t
 lib.echo_arena_bytes.argtypes = [C.POINTER(ModelDesc)]
@@ -76,6 +76,7 @@ STATIC_SCRATCH_BYTES = 32 << 20
 lib.echo_debug_draw_bits.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int32,
                                      C.c_void_p]
 lib.echo_stats.argtypes = [C.c_void_p, C.POINTER(Stats)]
+lib.echo_step_times.argtypes = [C.c_void_p, C.c_void_p, C.c_int32]
 lib.echo_last_error.restype = C.c_char_p
 lib.echo_last_error.argtypes = [C.c_void_p]
 lib.echo_destroy.argtypes = [C.c_void_p]
@@ -198,7 +199,7 @@ class Context:
                 stop_lens=None, eos_id: int = -1, top_p: float = 1.0, swap_at_step: Sequence[int] = (),
                 swap_timeout_ms: int = 0, forced=None, want_logits: bool = False, unfused_sampler: bool = False,
                 no_graph: bool = False, time_kernels: bool = False, continuous: bool = False, attn_plain: bool = False,
-                own_prompt_copy: bool = False, prefix_kernel: int = 0) -> dict:
+                own_prompt_copy: bool = False, prefix_kernel: int = 0, time_steps: bool = False) -> dict:
         prompts = np.ascontiguousarray(prompts, np.int32)
         prompt_lens = np.ascontiguousarray(prompt_lens, np.int32)
         P = prompts.shape[0]
@@ -227,6 +228,7 @@ class Context:
             o.debug_logits = logits.ctypes.data
         o.unfused_sampler, o.no_graph, o.time_kernels = int(unfused_sampler), int(no_graph), int(time_kernels)
         o.attn_plain, o.own_prompt_copy, o.prefix_kernel = int(attn_plain), int(own_prompt_copy), int(prefix_kernel)
+        o.time_steps = int(time_steps)
         toks = np.empty((N, max_new), np.int32)
         lps = np.empty((N, max_new), np.float32)
         lens = np.empty(N, np.int32)
@@ -260,6 +262,16 @@ class Context:
     def draw_bits(self, seed: int, n: int, s: int, i0: int, count: int) -> np.ndarray:
         out = np.empty(count, np.uint32)
         self._chk(lib.echo_debug_draw_bits(self.h, seed, n, s, i0, count, _ptr(out)))
+        return out
+
+    def step_times(self) -> np.ndarray:
+        """Per-step durations (ms) of the last rollout that ran with time_steps."""
+        n = lib.echo_step_times(self.h, None, 0)
+        if n < 0:
+            self._chk(n)
+        out = np.zeros(max(n, 0), np.float32)
+        if n > 0:
+            lib.echo_step_times(self.h, _ptr(out), n)
         return out
 
     def stats(self) -> Stats:

@@ -47,6 +47,11 @@ def test_tiny_fp32_rollout_matches_oracle():
     # graph replay and kernel-by-kernel launches give identical results
     ng = ctx.rollout(prompts, lens, 2, 32, 1.0, 2, no_graph=True)
     assert np.array_equal(ng["tokens"], out["tokens"]) and np.array_equal(ng["logprobs"], out["logprobs"])
+    # per-step timing marks change nothing and return one duration per decode step
+    ts = ctx.rollout(prompts, lens, 2, 32, 1.0, 2, time_steps=True)
+    assert np.array_equal(ts["tokens"], out["tokens"]) and np.array_equal(ts["logprobs"], out["logprobs"])
+    ms = ctx.step_times()
+    assert ms.shape == (31,) and (ms > 0).all() and ms.sum() <= ctx.stats().decode_ms * 1.05 + 0.5
     ctx.close()
 
 
@@ -106,3 +111,20 @@ def test_mid_bf16_ragged_long_context_splitk_vs_oracle_and_simple():
     assert np.abs(simple["logits"] - ref["logits"])[m].max() < BF16_LOGIT_TOL
     assert np.abs(simple["logits"] - tf["logits"])[m].max() < BF16_LOGIT_TOL
     ctx.close()
+
+
+def test_the_c_client_runs_a_rollout_without_python():
+    """csrc/echo_client.cpp through the C ABI alone (hipMalloc arena, the library's own streams): exit status 0 and a
+    finite mean log-prob of a near-uniform policy over 1024 tokens."""
+    import os
+    import re
+    import subprocess
+    client = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2602_02192_amd", "echo_client")
+    assert os.path.exists(client), "run `python -m paper_2602_02192_amd.build` first"
+    r = subprocess.run([client, "tiny", "8", "16", "16"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stderr[-2000:]
+    m = re.search(r"(\d+) tokens generated .* mean log-prob (-?[0-9.]+)", r.stdout)
+    assert m, r.stdout
+    assert int(m.group(1)) == 8 * 16
+    lp = float(m.group(2))
+    assert np.isfinite(lp) and -8.0 < lp < -6.0          # ln 1024 = 6.93
