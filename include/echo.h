@@ -77,6 +77,8 @@ typedef struct {
                                   no_graph); durations are read back with echo_stats */
   int32_t time_steps;          /* 1 (echo_rollout only): a HIP event between every two decode steps (graph replays
                                   included); the per-step durations are read back with echo_step_times */
+  int32_t no_compaction;       /* 1 (echo_rollout only): rows of sequences that have ended stay in the batch as inactive
+                                  rows until the call ends, instead of the rows of a drained batch being moved together */
   /* Cross-check switches (0 = the default path; results differ from it by rounding order at most, see each): */
   int32_t attn_plain;          /* 1: decode and prompt attention by the plain kernel (one wavefront per (row, head), two
                                   passes, no key splitting, no sharing of prompt tiles) instead of the MFMA kernels */

@@ -33,7 +33,11 @@ _i64p = np.ctypeslib.ndpointer(np.int64, flags="C_CONTIGUOUS")
 class Oracle:
     def __init__(self, precision: str = "f64"):
         path = _build.lib_path(precision)
-        if not os.path.exists(path):
+        if os.environ.get("ORACLE_SANITIZE") == "1":     # the ASan + UBSan builds (oracle/build.py: build_sanitized)
+            path = os.path.join(os.path.dirname(path), f"liboracle_{precision}_san.so")
+            if not os.path.exists(path):
+                raise RuntimeError(f"ORACLE_SANITIZE=1 needs {path} (oracle/build.py: build_sanitized)")
+        elif not os.path.exists(path):
             _build.build(force=False)
         self.lib = L = C.CDLL(path)
         self.precision = precision

@@ -242,19 +242,24 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
   std::vector<int32_t> ident(N);   // (a vector of its own: the copy above may still be reading `map`)
   for (int n = 0; n < N; ++n) ident[n] = n;
   HIPCHK(c, hipMemcpyAsync(c->rows.slot, ident.data(), N * 4, hipMemcpyHostToDevice, st));
-  {   // decode attention reads the whole tiles of a group's prompt from the group's first slot
-    std::vector<int32_t> pslot(N), ptiles(N), live(N, 1);
-    int max_ptiles = 0;
+  // decode attention reads the whole tiles of a group's prompt from the group's first slot
+  std::vector<int32_t> pslot(N), ptiles(N), stream(N);
+  int max_ptiles = 0;
+  {
+    std::vector<int32_t> live(N, 1);
     for (int n = 0; n < N; ++n) {
       pslot[n] = n / G * G;
       ptiles[n] = share_prefix ? prompt_lens[n / G] / 32 : 0;
       max_ptiles = std::max(max_ptiles, ptiles[n]);
+      stream[n] = n;
     }
     if ((rc = plan_prefix_jobs(c, ptiles, pslot, live, N, max_ptiles, 0, o.prefix_kernel))) return rc;
     HIPCHK(c, hipMemcpyAsync(c->rows.pslot, pslot.data(), N * 4, hipMemcpyHostToDevice, st));
     HIPCHK(c, hipMemcpyAsync(c->rows.ptiles, ptiles.data(), N * 4, hipMemcpyHostToDevice, st));
-    HIPCHK(c, hipStreamSynchronize(st));   // the host vectors go out of scope
+    HIPCHK(c, hipMemcpyAsync(c->d_stream, stream.data(), N * 4, hipMemcpyHostToDevice, st));
+    HIPCHK(c, hipStreamSynchronize(st));
   }
+  c->ids = DrawIds{c->d_step, nullptr, c->d_stream};   // a row's draws are keyed by its sequence, wherever the row moves
   norm_only(c, c->slots[cur], N);
   sample_rows(c, c->slots[cur], N, temperature, seed, unfused, nullptr, o.top_p);
   auto grab_logits = [&](int s) -> int {
@@ -265,8 +270,12 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
     return 0;
   };
   if ((rc = grab_logits(0))) return rc;
+  int Rc = N;   // rows of the batch now (row r serves sequence row_seq[r]; rows are moved up when the batch has drained enough)
+  std::vector<int> row_seq(N);
+  for (int n = 0; n < N; ++n) row_seq[n] = n;
+  std::vector<int32_t> lens_host(N, 0);
   auto book = [&](int slot) {
-    launch_bookkeeping(N, max_new, 0, c->d_step, c->d_samp_tok, c->d_samp_lp, d_forced, c->d_limit, o.eos_id, c->slots[slot].version,
+    launch_bookkeeping(Rc, max_new, 0, c->d_step, c->d_samp_tok, c->d_samp_lp, d_forced, c->d_limit, o.eos_id, c->slots[slot].version,
                        c->d_prompt_len_seq, c->d_gen_len, c->rows, at<int32_t>(c, p.o_out_tok), at<float>(c, p.o_out_lp),
                        at<int64_t>(c, p.o_out_ver), c->d_n_active, st);
   };
@@ -291,6 +300,7 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
   int next_swap = 0, decode_steps = 0;
   bool have_graph = false;
   bool splitk = !o.attn_plain;
+  const bool may_compact = !o.debug_logits && !o.no_compaction;   // (returned logits are in sequence order)
   for (int s = 1; s < steps; ++s) {
     if (next_swap < o.n_swaps && o.swap_at_step[next_swap] == s) {
       auto w0 = std::chrono::steady_clock::now();
@@ -307,11 +317,51 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
       have_graph = false;
       ++next_swap;
     }
-    if (o.eos_id >= 0 && (s % 16) == 0) {  // sequences may have ended early: look at the active count
-      int32_t na = 0;
-      HIPCHK(c, hipMemcpyAsync(&na, c->d_n_active, 4, hipMemcpyDeviceToHost, st));
+    int live_now = Rc;   // sequences that take part in pass s, as far as the host knows
+    if (o.eos_id >= 0) {
+      if ((s % 16) == 0) {  // sequences may have ended early: look at the active count
+        int32_t na = 0;
+        HIPCHK(c, hipMemcpyAsync(&na, c->d_n_active, 4, hipMemcpyDeviceToHost, st));
+        HIPCHK(c, hipStreamSynchronize(st));
+        if (na == 0) break;
+        live_now = na;
+      }
+    } else {
+      live_now = 0;
+      for (int r = 0; r < Rc; ++r) live_now += limit[row_seq[r]] > s;
+    }
+    // A draining batch: once the sequences still generating fit a smaller padded batch their rows are moved to the
+    // front (cache slots and records stay where they are) and the step is captured again for fewer rows.  With stop
+    // lengths only, the host knows who is still generating; with an end-of-sequence token it looks every 16 steps.
+    if (may_compact && pad_rows(std::max(1, live_now)) < pad_rows(Rc) && live_now > 0) {
+      std::vector<int32_t> tok(Rc), pos(Rc), act(Rc), gen(Rc);
+      HIPCHK(c, hipMemcpyAsync(tok.data(), c->rows.token, (size_t)Rc * 4, hipMemcpyDeviceToHost, st));
+      HIPCHK(c, hipMemcpyAsync(pos.data(), c->rows.pos, (size_t)Rc * 4, hipMemcpyDeviceToHost, st));
+      HIPCHK(c, hipMemcpyAsync(act.data(), c->rows.active, (size_t)Rc * 4, hipMemcpyDeviceToHost, st));
+      HIPCHK(c, hipMemcpyAsync(gen.data(), c->d_gen_len, (size_t)Rc * 4, hipMemcpyDeviceToHost, st));
       HIPCHK(c, hipStreamSynchronize(st));
-      if (na == 0) break;
+      std::vector<int32_t> slot2, pslot2, ptiles2, plen2, lim2, stream2, tok2, pos2, act2, gen2, live2;
+      std::vector<int> seq2;
+      for (int r = 0; r < Rc; ++r) {
+        const int n = row_seq[r];
+        if (!act[r]) { lens_host[n] = gen[r]; continue; }
+        tok2.push_back(tok[r]); pos2.push_back(pos[r]); act2.push_back(1); gen2.push_back(gen[r]); slot2.push_back(n);
+        pslot2.push_back(pslot[r]); ptiles2.push_back(ptiles[r]); plen2.push_back(plen_seq[n]); lim2.push_back(limit[n]);
+        stream2.push_back(n); seq2.push_back(n); live2.push_back(1);
+      }
+      const int w = (int)seq2.size();
+      if (w > 0 && pad_rows(w) < pad_rows(Rc)) {
+        if ((rc = plan_prefix_jobs(c, ptiles2, pslot2, live2, w, max_ptiles, 0, o.prefix_kernel))) return rc;
+        struct { int32_t *dst; std::vector<int32_t> *src; } cp[] = {
+            {c->rows.token, &tok2}, {c->rows.pos, &pos2}, {c->rows.active, &act2}, {c->rows.slot, &slot2}, {c->rows.pslot, &pslot2},
+            {c->rows.ptiles, &ptiles2}, {c->d_prompt_len_seq, &plen2}, {c->d_gen_len, &gen2}, {c->d_limit, &lim2}, {c->d_stream, &stream2}};
+        for (auto &x : cp) HIPCHK(c, hipMemcpyAsync(x.dst, x.src->data(), (size_t)w * 4, hipMemcpyHostToDevice, st));
+        launch_fill_i32(c->rows.active + w, 0, Rc - w, st);   // the rows given up
+        HIPCHK(c, hipStreamSynchronize(st));
+        pslot = pslot2; ptiles = ptiles2; row_seq = seq2;
+        Rc = w;
+        have_graph = false;
+      }
     }
     bool time_this = c->timing;
     if (c->timing) {
@@ -329,13 +379,13 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
     }
     if (use_graph) {
       if (!have_graph) {
-        if ((rc = capture_step(c, c->slots[cur], N, max_new, temperature, seed, unfused, d_forced, o.eos_id, o.top_p))) return rc;
+        if ((rc = capture_step(c, c->slots[cur], Rc, max_new, temperature, seed, unfused, d_forced, o.eos_id, o.top_p))) return rc;
         have_graph = true;
       }
       HIPCHK(c, hipGraphLaunch(c->graph, st));
     } else {
-      forward_layers(c, c->slots[cur], N, splitk);
-      sample_rows(c, c->slots[cur], N, temperature, seed, unfused, nullptr, o.top_p);
+      forward_layers(c, c->slots[cur], Rc, splitk);
+      sample_rows(c, c->slots[cur], Rc, temperature, seed, unfused, nullptr, o.top_p);
       if ((rc = grab_logits(s))) return rc;
       book(cur);
     }
@@ -358,8 +408,13 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
   HIPCHK(c, hipMemcpyAsync(out_tokens, at<int32_t>(c, p.o_out_tok), outn * 4, hipMemcpyDeviceToHost, st));
   HIPCHK(c, hipMemcpyAsync(out_logprobs, at<float>(c, p.o_out_lp), outn * 4, hipMemcpyDeviceToHost, st));
   if (out_versions) HIPCHK(c, hipMemcpyAsync(out_versions, at<int64_t>(c, p.o_out_ver), outn * 8, hipMemcpyDeviceToHost, st));
-  HIPCHK(c, hipMemcpyAsync(out_lens, c->d_gen_len, N * 4, hipMemcpyDeviceToHost, st));
-  HIPCHK(c, hipStreamSynchronize(st));
+  {
+    std::vector<int32_t> gen(Rc);
+    HIPCHK(c, hipMemcpyAsync(gen.data(), c->d_gen_len, (size_t)Rc * 4, hipMemcpyDeviceToHost, st));
+    HIPCHK(c, hipStreamSynchronize(st));
+    for (int r = 0; r < Rc; ++r) lens_host[row_seq[r]] = gen[r];
+    memcpy(out_lens, lens_host.data(), (size_t)N * 4);
+  }
   auto t3 = std::chrono::steady_clock::now();
   c->st.decode_steps = decode_steps;
   c->st.prefill_ms = std::chrono::duration<float, std::milli>(t1 - t0).count();

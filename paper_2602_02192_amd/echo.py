@@ -36,7 +36,7 @@ class RolloutOpts(C.Structure):
     _fields_ = [("stop_lens", C.c_void_p), ("eos_id", C.c_int32), ("top_p", C.c_float),
                 ("n_swaps", C.c_int32), ("swap_at_step", C.c_void_p), ("swap_timeout_ms", C.c_int32),
                 ("forced_tokens", C.c_void_p), ("debug_logits", C.c_void_p),
-                ("unfused_sampler", C.c_int32), ("no_graph", C.c_int32), ("time_kernels", C.c_int32), ("time_steps", C.c_int32),
+                ("unfused_sampler", C.c_int32), ("no_graph", C.c_int32), ("time_kernels", C.c_int32), ("time_steps", C.c_int32), ("no_compaction", C.c_int32),
                 ("attn_plain", C.c_int32), ("own_prompt_copy", C.c_int32), ("prefix_kernel", C.c_int32)]
 
 
@@ -199,7 +199,8 @@ class Context:
                 stop_lens=None, eos_id: int = -1, top_p: float = 1.0, swap_at_step: Sequence[int] = (),
                 swap_timeout_ms: int = 0, forced=None, want_logits: bool = False, unfused_sampler: bool = False,
                 no_graph: bool = False, time_kernels: bool = False, continuous: bool = False, attn_plain: bool = False,
-                own_prompt_copy: bool = False, prefix_kernel: int = 0, time_steps: bool = False) -> dict:
+                own_prompt_copy: bool = False, prefix_kernel: int = 0, time_steps: bool = False,
+                no_compaction: bool = False) -> dict:
         prompts = np.ascontiguousarray(prompts, np.int32)
         prompt_lens = np.ascontiguousarray(prompt_lens, np.int32)
         P = prompts.shape[0]
@@ -228,7 +229,7 @@ class Context:
             o.debug_logits = logits.ctypes.data
         o.unfused_sampler, o.no_graph, o.time_kernels = int(unfused_sampler), int(no_graph), int(time_kernels)
         o.attn_plain, o.own_prompt_copy, o.prefix_kernel = int(attn_plain), int(own_prompt_copy), int(prefix_kernel)
-        o.time_steps = int(time_steps)
+        o.time_steps, o.no_compaction = int(time_steps), int(no_compaction)
         toks = np.empty((N, max_new), np.int32)
         lps = np.empty((N, max_new), np.float32)
         lens = np.empty(N, np.int32)
