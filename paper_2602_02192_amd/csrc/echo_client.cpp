@@ -2,7 +2,9 @@
 // and runs one rollout through include/echo.h.  It exists to show the boundary in use from plain C/C++ and to give
 // profilers a small host process to attach to (rocprofv3 counter collection on this program:
 //   rocprofv3 --pmc FETCH_SIZE -- paper_2602_02192_amd/echo_client 4b 64 512 64).
-// usage: echo_client <tiny|4b|4b:LAYERS> <sequences (multiple of 8)> <prompt_len> <max_new>
+// usage: echo_client <tiny|4b|8b|32b>[:LAYERS] <sequences (multiple of 8)> <prompt_len> <max_new> [score]
+//   (":LAYERS" keeps a model's width and cuts its depth; "score" adds a teacher-forced echo_logprobs pass over every
+//   prompt + generated string, i.e. the 4096-row GEMM and causal-attention kernels)
 #include <hip/hip_runtime.h>
 
 #include <chrono>
@@ -37,9 +39,17 @@ int main(int argc, char **argv) {
   int N = argc > 2 ? atoi(argv[2]) : 8, plen = argc > 3 ? atoi(argv[3]) : 16, max_new = argc > 4 ? atoi(argv[4]) : 16;
   echo_model_desc d;
   memset(&d, 0, sizeof d);
-  if (!strncmp(model, "4b", 2)) { d.n_layers = model[2] == ':' ? atoi(model + 3) : 36;   // "4b:L" keeps the width, L layers
-    d.hidden = 2560; d.n_q_heads = 32; d.n_kv_heads = 8; d.head_dim = 128; d.ffn = 9728; d.vocab = 151936; }
-  else { d.n_layers = 2; d.hidden = 256; d.n_q_heads = 4; d.n_kv_heads = 2; d.head_dim = 64; d.ffn = 704; d.vocab = 1024; }
+  const char *colon = strchr(model, ':');
+  const size_t name_len = colon ? (size_t)(colon - model) : strlen(model);
+  auto is = [&](const char *n) { return strlen(n) == name_len && !strncmp(model, n, name_len); };
+  if (is("4b")) { d.n_layers = 36; d.hidden = 2560; d.n_q_heads = 32; d.n_kv_heads = 8; d.head_dim = 128; d.ffn = 9728; d.vocab = 151936; }
+  else if (is("8b")) { d.n_layers = 36; d.hidden = 4096; d.n_q_heads = 32; d.n_kv_heads = 8; d.head_dim = 128; d.ffn = 12288; d.vocab = 151936; }
+  else if (is("32b")) { d.n_layers = 64; d.hidden = 5120; d.n_q_heads = 64; d.n_kv_heads = 8; d.head_dim = 128; d.ffn = 25600; d.vocab = 151936; }
+  else if (is("tiny")) { d.n_layers = 2; d.hidden = 256; d.n_q_heads = 4; d.n_kv_heads = 2; d.head_dim = 64; d.ffn = 704; d.vocab = 1024; }
+  else { fprintf(stderr, "unknown model %s\n", model); return 2; }
+  if (colon) d.n_layers = atoi(colon + 1);
+  if (d.n_layers < 1) { fprintf(stderr, "bad layer count\n"); return 2; }
+  const bool score = argc > 5 && !strcmp(argv[5], "score");
   d.rms_eps = 1e-6f; d.rope_base = 1e4f; d.dtype = ECHO_BF16; d.max_seqs = N; d.max_ctx = plen + max_new; d.n_weight_slots = 1;
   const int G = 8, P = N / G;
   if (P < 1 || N % G || plen < 1 || max_new < 1) { fprintf(stderr, "sequences must be a positive multiple of %d\n", G); return 2; }
@@ -90,6 +100,32 @@ int main(int argc, char **argv) {
   for (int n = 0; n < N; ++n) { total += out_lens[n]; for (int t = 0; t < out_lens[n]; ++t) lp += lps[(size_t)n * max_new + t]; }
   printf("%s: %d sequences, prompt %d, %ld tokens generated in %.3f s (%.0f tokens/s), mean log-prob %.3f\n", model, N, plen, total, s,
          total / s, lp / total);
+  if (score) {   // every string (prompt + generated tokens) through echo_logprobs
+    const int stride = plen + max_new;
+    std::vector<int32_t> full((size_t)N * stride), flen(N);
+    std::vector<float> slp((size_t)N * stride);
+    long rows = 0;
+    for (int n = 0; n < N; ++n) {
+      memcpy(&full[(size_t)n * stride], &prompts[(size_t)(n / G) * plen], (size_t)plen * 4);
+      for (int t = 0; t < out_lens[n]; ++t) full[(size_t)n * stride + plen + t] = toks[(size_t)n * max_new + t];
+      flen[n] = plen + out_lens[n];
+      rows += flen[n] - 1;
+    }
+    t0 = std::chrono::steady_clock::now();
+    rc = echo_logprobs(ctx, full.data(), stride, flen.data(), N, 1.0f, slp.data());
+    s = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+    if (rc) { fprintf(stderr, "echo_logprobs: %s\n", echo_last_error(ctx)); return 1; }
+    const double H = d.hidden, Q = (double)d.n_q_heads * d.head_dim, KV = (double)d.n_kv_heads * d.head_dim;
+    const double per_layer = H * (Q + 2 * KV) + Q * H + 3.0 * H * d.ffn, flop = 2.0 * rows * (d.n_layers * per_layer + (double)d.vocab * H);
+    double dev = 0;
+    for (int n = 0; n < N; ++n)
+      for (int t = 0; t < out_lens[n]; ++t) {
+        double e = slp[(size_t)n * stride + plen + t] - lps[(size_t)n * max_new + t];
+        dev = e < 0 ? (-e > dev ? -e : dev) : (e > dev ? e : dev);
+      }
+    printf("scoring: %ld rows in %.3f s, %.1f TFLOP/s in the GEMMs (%.1f %% of 2.5 PFLOP/s); max |scored - sampled log-prob| %.4f\n", rows, s,
+           flop / s / 1e12, 100.0 * flop / s / 2.5e15, dev);
+  }
   echo_destroy(ctx);
   (void)hipFree(arena);
   return 0;

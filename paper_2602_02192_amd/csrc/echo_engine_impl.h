@@ -313,7 +313,7 @@ void gemm_fast(echo_ctx *c, void *out, const void *Xp, const void *Wp, int Mp, i
     int room = (int)(c->p.part_floats / ((size_t)Np * Mp));
     if (g.nsplit > room) g.nsplit = room;
   }
-  if (g.lds == 3) g.nsplit = fast_gemm_even_split(Kp, g.nsplit);
+  if (g.lds == 3 || g.lds == 2) g.nsplit = fast_gemm_even_split(Kp, g.nsplit);
   {
     TimerScope t(c, &c->ev_gemm);
     fast_gemm(out, Xp, Wp, Mp, Np, Kp, g, epi, c->cs);

@@ -490,16 +490,17 @@ __global__ __launch_bounds__(WN * 64) void gemm_lds_kernel(void *out, const u32x
   }
 }
 
-// ---- 256 x 256 tiles for batches of 256 rows and more ------------------------------------------------------
+// ---- 256-row tiles for batches of 256 rows and more ------------------------------------------------------------
 // Prefill and scoring are bound by the matrix cores, and what a compute unit can pull from L2 per cycle caps them:
 // a workgroup that computes Tn x Tm outputs per k loads Tn + Tm operand rows, so the tile has to be large in both
-// directions.  Four wavefronts, each with two weight blocks (64 output columns) against 256 batch rows: every
-// activation operand read from LDS feeds two MFMAs, which halves the LDS traffic of the one-block kernel (that one
-// runs at the LDS limit).  The 256 accumulator registers per lane live in the accumulation half of the register file.
-// WR = 2 arranges the four wavefronts as two row halves x two column pairs (tile 256 x 128, 128 accumulator registers per
-// lane): for batches of exactly a few hundred rows, where 256 x 256 tiles are too few to fill the chip.
-template <int WRv> struct GemmWideT {
-  static constexpr int WR = WRv, MB = 8 / WR, WN = 4, WC = WN / WR, NBW = 2, ROWS = 256, T = WN * 64;
+// directions.  Every wavefront owns two weight blocks (64 output columns), streamed from global memory straight into
+// A-operand registers, against MB blocks of 32 batch rows whose operands come through LDS; every activation operand read
+// from LDS feeds two MFMAs, which halves the LDS traffic of the one-block kernel (that one runs at the LDS limit).
+// Two forms: WN = 8 wavefronts (two per SIMD) as two row halves x four column pairs on a 256 x 256 tile, 128
+// accumulator registers per lane: the form for 512 rows and more; WN = 4 as two row halves x two column pairs on a
+// 256 x 128 tile: for batches of exactly a few hundred rows, where 256 x 256 tiles are too few to fill the chip.
+template <int WRv, int WNv = 4> struct GemmWideT {
+  static constexpr int WR = WRv, MB = 8 / WR, WN = WNv, WC = WN / WR, NBW = 2, ROWS = 256, T = WN * 64;
   static constexpr int CK = 1, NSTAGE = 8 / CK;   // k-steps per chunk (one barrier each), chunks in flight; CK = 2 measured 1-2 % slower
   static constexpr int CHUNK_UNITS = CK * 2 * ROWS, XL = CHUNK_UNITS / T;
   static constexpr int X_BYTES = 2 * CHUNK_UNITS * 16, TILE_STRIDE = 33, EPI_BYTES = WN * 32 * TILE_STRIDE * 4;
@@ -507,8 +508,8 @@ template <int WRv> struct GemmWideT {
 };
 using GemmWide = GemmWideT<1>;
 
-// One k-step per chunk, operands requested seven chunks ahead: with one wavefront per SIMD only the depth of the
-// register pipeline hides the load latency, and measured throughput kept rising with it.  Kp is a multiple of
+// One k-step per chunk, operands requested seven chunks ahead: the depth of the register pipeline hides most of the
+// load latency (measured throughput kept rising with it), a second wavefront on the SIMD the rest.  Kp is a multiple of
 // GEMM_K_PAD, so the k-step count is a multiple of the eight stages and the loop needs neither tails nor conditions
 // (a load behind a condition makes the compiler's wait counts drain the queue): the prefetches of the last trips
 // are clamped to the last k-step, loaded again and never used.
@@ -516,22 +517,22 @@ using GemmWide = GemmWideT<1>;
 // found in cache by the other row blocks; pays when the weight matrix is far larger than the last-level cache.
 // blockIdx.y splits K in runs of `groups_per_split` groups of eight k-steps (EPI_PARTIAL only: split y writes the
 // partial plane y of out).
-template <int EPI, bool ZFAST, int WR>
-__global__ __launch_bounds__(256) void gemm_wide_kernel(void *out, const u32x4v *__restrict__ Xp, const h16x8 *__restrict__ Wp, int Mp,
+template <int EPI, bool ZFAST, int WR, int WN>
+__global__ __launch_bounds__(WN * 64) void gemm_wide_kernel(void *out, const u32x4v *__restrict__ Xp, const h16x8 *__restrict__ Wp, int Mp,
                                                         int Np, int Kp, int groups_per_split) {
   extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-  using L = GemmWideT<WR>;
+  using L = GemmWideT<WR, WN>;
   constexpr int MB = L::MB, NBW = L::NBW, T = L::T, XU = L::CHUNK_UNITS, XL = L::XL, ROWS = L::ROWS, NSTAGE = L::NSTAGE, CK = L::CK;
   static_assert((GEMM_K_PAD / 16) % (NSTAGE * CK) == 0, "k-step count must be a multiple of the k-steps in flight");
   u32x4v *xs = (u32x4v *)lds_raw;
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, tid = threadIdx.x;
   const int nblocks = Np >> 5, nz = Mp / ROWS;
-  // chunk range of this workgroup (the 256 x 256 form is never split: constants there keep its loop as it was measured)
-  const int c_lo = WR == 1 ? 0 : blockIdx.y * groups_per_split * NSTAGE;
-  const int nchunks = WR == 1 ? (Kp >> 4) / CK : min((Kp >> 4) / CK, c_lo + groups_per_split * NSTAGE);
-  const int plane = WR == 1 ? 0 : blockIdx.y;
+  // chunk range of this workgroup
+  const int c_lo = blockIdx.y * groups_per_split * NSTAGE;
+  const int nchunks = min((Kp >> 4) / CK, c_lo + groups_per_split * NSTAGE);
+  const int plane = blockIdx.y;
   const int bx = ZFAST ? blockIdx.x / nz : blockIdx.x, bz = ZFAST ? blockIdx.x % nz : blockIdx.z;
-  const int nb0 = (bx * L::WC + (WR == 1 ? w : w % L::WC)) * NBW, mrow0 = bz * ROWS, wrow = WR == 1 ? 0 : (w / L::WC) * 32 * MB;
+  const int nb0 = (bx * L::WC + w % L::WC) * NBW, mrow0 = bz * ROWS, wrow = (w / L::WC) * 32 * MB;
   const int64_t a_step = w_kstep_stride(Np);
   const h16x8 *a_ptr[NBW];
 #pragma unroll
@@ -641,18 +642,18 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(void *out, const u32x4v 
   }
 }
 
-template <int EPI, bool ZFAST, int WR = 1>
+template <int EPI, bool ZFAST, int WR = 1, int WN = 4>
 static void gemm_wide_launch(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, hipStream_t st, int nsplit = 1) {
-  using L = GemmWideT<WR>;
+  using L = GemmWideT<WR, WN>;
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void *)gemm_wide_kernel<EPI, ZFAST, WR>, hipFuncAttributeMaxDynamicSharedMemorySize, L::BYTES);
+    (void)hipFuncSetAttribute((const void *)gemm_wide_kernel<EPI, ZFAST, WR, WN>, hipFuncAttributeMaxDynamicSharedMemorySize, L::BYTES);
     attr_set = true;
   }
   int nblocks = Np / 32, per_wg = L::WC * L::NBW, strips = (nblocks + per_wg - 1) / per_wg, nz = Mp / L::ROWS;
-  int groups = (Kp / 16) / (L::NSTAGE * L::CK), gps = (groups + nsplit - 1) / nsplit, ny = WR == 1 ? 1 : (groups + gps - 1) / gps;
+  int groups = (Kp / 16) / (L::NSTAGE * L::CK), gps = (groups + nsplit - 1) / nsplit, ny = (groups + gps - 1) / gps;
   dim3 grid = ZFAST ? dim3(strips * nz, ny, 1) : dim3(strips, ny, nz);
-  hipLaunchKernelGGL((gemm_wide_kernel<EPI, ZFAST, WR>), grid, dim3(L::T), L::BYTES, st, out, (const u32x4v *)Xp, (const h16x8 *)Wp, Mp,
+  hipLaunchKernelGGL((gemm_wide_kernel<EPI, ZFAST, WR, WN>), grid, dim3(L::T), L::BYTES, st, out, (const u32x4v *)Xp, (const h16x8 *)Wp, Mp,
                      Np, Kp, gps);
 }
 
@@ -677,6 +678,15 @@ void fast_gemm_pick(int Np, int Kp, int Mp, int full_k, GemmShape *g) {
   g->lds = 0; g->stages = 0;
   if (Kp % GEMM_K_PAD == 0 && Mp % 256 == 0 && (nblocks + 7) / 8 * (Mp / 256) >= 128) {   // 256 x 256 tiles fill the chip
     g->lds = 2; g->nbw = 2; g->waves_k = 1; g->waves_n = 4; g->stages = 8; g->nsplit = 1;
+    // One tile per compute unit at a time, so a tile count just above a multiple of 256 leaves most of the chip idle in
+    // the last round (320 tiles take two rounds).  Splitting K in two runs makes the units of work half as long and the
+    // rounds fill up (320 tiles: 1.5 rounds' worth), at the price of a second plane of fp32 partials written and read
+    // again -- which pays once K is long (measured at 4096 rows: N 5120, K 8192: 411 -> 340 us, K 25600: 1228 -> 1011 us,
+    // for about 34 us of extra plane traffic; at K 4096 the plane costs more than the split saves).
+    if (!full_k && Kp >= 6144) {
+      const int tiles = (nblocks + 7) / 8 * (Mp / 256);
+      if ((2 * tiles + 255) / 256 * 0.5 <= 0.8 * ((tiles + 255) / 256)) g->nsplit = 2;
+    }
     return;
   }
   if (Kp % GEMM_K_PAD == 0 && Mp % 256 == 0) {
@@ -750,9 +760,12 @@ static void gemm_lds_dispatch(void *out, const void *Xp, const void *Wp, int Mp,
 
 template <int EPI>
 static void gemm_dispatch(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, GemmShape g, hipStream_t st) {
-  if (g.lds == 2) {   // row blocks fastest once the weights are far larger than the last-level cache
-    if ((size_t)Np * Kp * 2 >= ((size_t)256 << 20)) gemm_wide_launch<EPI, true>(out, Xp, Wp, Mp, Np, Kp, st);
-    else gemm_wide_launch<EPI, false>(out, Xp, Wp, Mp, Np, Kp, st);
+  if (g.lds == 2) {
+    // Eight wavefronts (two per SIMD) on the 256 x 256 tile: at 4096 rows 3 .. 10 % faster than four wavefronts with
+    // twice the accumulators each on all the projection shapes of the 4B, 8B and 32B models.  Row blocks fastest once
+    // the weights are far larger than the last-level cache.
+    if ((size_t)Np * Kp * 2 >= ((size_t)256 << 20)) gemm_wide_launch<EPI, true, 2, 8>(out, Xp, Wp, Mp, Np, Kp, st, g.nsplit);
+    else gemm_wide_launch<EPI, false, 2, 8>(out, Xp, Wp, Mp, Np, Kp, st, g.nsplit);
     return;
   }
   if (g.lds == 3) { gemm_wide_launch<EPI, false, 2>(out, Xp, Wp, Mp, Np, Kp, st, g.nsplit); return; }
