@@ -147,6 +147,21 @@ int echo_load_policy_chunk(echo_ctx *ctx, const void *data, size_t nbytes);
 int echo_load_policy_commit(echo_ctx *ctx);
 int echo_load_policy_abort(echo_ctx *ctx);
 
+/* Install snapshot `version` as a delta against the newest installed snapshot (Sec. 4.2 ships whole snapshots in chunks;
+ * the "Limitations and Future Work" section names delta updates as the way to cut that traffic): the new blob is the
+ * blob of base_version with n_ranges byte ranges replaced.
+ *   offsets, sizes  host [n_ranges]: byte ranges of the blob, ascending and non-overlapping, whole elements of the model
+ *                   dtype (they may start and end anywhere inside a tensor or a matrix row, and span tensors)
+ *   host_data       host: the new bytes of all ranges, concatenated in range order
+ * With n_weight_slots = 2 the inactive slot first becomes a device-side copy of the base snapshot, then the ranges are
+ * copied in and re-packed on the copy stream, while a rollout may keep decoding; with one slot the active snapshot is
+ * patched in place (no rollout may be running).  The result is bit for bit the snapshot a full echo_load_policy of the
+ * patched blob leaves, and it becomes active or staged exactly as there.  ECHO_ESTATE if base_version is not the
+ * newest installed snapshot, if version does not advance, if another load is open or a staged snapshot is waiting;
+ * ECHO_EINVAL for a bad range list.  After a failure half-way a slot that was patched in place holds no snapshot. */
+int echo_load_policy_delta(echo_ctx *ctx, int64_t base_version, int64_t version, int32_t n_ranges, const uint64_t *offsets,
+                           const uint64_t *sizes, const void *host_data);
+
 /* Generate G samples for each of n_prompts prompts (sequence n = p*G + g) by ancestral sampling from
  * softmax(logits / temperature) (Algorithm 1, "sample and generate y ~ pi(.|x)"), up to max_new tokens each.
  * The draw for vocabulary entry i of sequence n at step s is the Gumbel-max rule on a counter-based uniform

@@ -92,10 +92,112 @@ int feed_segments(echo_ctx *c, std::vector<BlobSeg> &segs, const char *data, siz
   return 0;
 }
 
+// Bytes [lo, lo + n) of the blob are replaced by `data` in a slot that already holds a whole snapshot: plain ranges are
+// copied over, spans of a matrix go through the staging buffer and are re-packed element by element.
+int patch_segments(echo_ctx *c, std::vector<BlobSeg> &segs, const char *data, size_t lo, size_t n) {
+  const size_t hi = lo + n, elt = c->p.elt;
+  for (BlobSeg &g : segs) {
+    size_t a = std::max(lo, g.off), b = std::min(hi, g.off + g.bytes);
+    if (a >= b) continue;
+    const char *src = data + (a - lo);
+    if (g.rows == 0) {
+      HIPCHK(c, hipMemcpyAsync(g.dst + (a - g.off), src, b - a, hipMemcpyHostToDevice, c->ks));
+      continue;
+    }
+    const int Np = (int)round_up(g.rows * g.stride, 32), Kp = (int)round_up(g.K, GEMM_K_PAD);
+    const size_t half_stage = c->p.stage_bytes / 2;
+    for (size_t o = a; o < b; o += half_stage) {
+      const size_t len = std::min(half_stage, b - o);
+      char *stg = c->arena + c->p.o_stage + (c->stage_flip ? half_stage : 0);
+      c->stage_flip ^= 1;
+      HIPCHK(c, hipMemcpyAsync(stg, data + (o - lo), len, hipMemcpyHostToDevice, c->ks));
+      fast_pack_span(g.dst, stg, (int64_t)((o - g.off) / elt), (int64_t)(len / elt), g.dst_row0, g.stride, g.K, Kp, Np, c->ks);
+    }
+  }
+  return 0;
+}
+
+// The snapshot in slot `target` is complete on the copy stream: make it the active or the staged one.
+int commit_slot(echo_ctx *c, int target, int64_t version) {
+  HIPCHK(c, hipEventRecord(c->staged_ev, c->ks));
+  HIPCHK(c, hipStreamSynchronize(c->ks));
+  std::lock_guard<std::mutex> lk(c->mu);
+  c->slots[target].version = version;
+  c->newest_version = version;
+  if (c->rollout_running) {
+    c->staged = target;
+    c->st.staged_version = version;
+  } else {
+    c->active = target;
+    c->st.active_version = version;
+  }
+  c->load.open = false;
+  c->load.segs.clear();
+  c->cv.notify_all();
+  return ECHO_OK;
+}
+
 }  // namespace
 
 // =================================================================================================== C ABI
 extern "C" {
+
+int echo_load_policy_delta(echo_ctx *c, int64_t base_version, int64_t version, int32_t n_ranges, const uint64_t *offsets,
+                           const uint64_t *sizes, const void *host_data) {
+  if (!c) return ECHO_EINVAL;
+  if (n_ranges < 0 || (n_ranges > 0 && (!offsets || !sizes || !host_data))) return fail(c, ECHO_EINVAL, "bad argument");
+  const size_t blob = echo_blob_bytes(&c->d), elt = c->p.elt;
+  size_t total = 0, prev_end = 0;
+  for (int i = 0; i < n_ranges; ++i) {
+    if (sizes[i] == 0 || offsets[i] % elt || sizes[i] % elt) return fail(c, ECHO_EINVAL, "range %d is empty or not a whole number of %zu-byte elements", i, elt);
+    if (offsets[i] < prev_end || offsets[i] > blob || sizes[i] > blob - offsets[i])
+      return fail(c, ECHO_EINVAL, "range %d overlaps its predecessor, is out of order or runs past the blob of %zu bytes", i, blob);
+    prev_end = offsets[i] + sizes[i];
+    total += sizes[i];
+  }
+  std::unique_lock<std::mutex> lk(c->mu);
+  if (c->load.open) return fail(c, ECHO_ESTATE, "snapshot %lld is still arriving (commit or abort it first)", (long long)c->load.version);
+  if (c->staged >= 0) return fail(c, ECHO_ESTATE, "a staged snapshot is still waiting to be switched in");
+  if (c->active < 0 || base_version != c->newest_version)
+    return fail(c, ECHO_ESTATE, "the delta is against version %lld, the newest installed snapshot is %lld", (long long)base_version, (long long)c->newest_version);
+  if (version <= c->newest_version) return fail(c, ECHO_ESTATE, "version %lld does not advance past %lld", (long long)version, (long long)c->newest_version);
+  const bool running = c->rollout_running;
+  const int base = c->active;
+  int target;
+  if (c->d.n_weight_slots == 2) target = 1 - base;
+  else if (!running) target = base;   // patched in place: nothing reads the only slot
+  else return fail(c, ECHO_ESTATE, "installing during a rollout needs n_weight_slots = 2");
+  c->load.open = true;
+  c->load.version = version; c->load.target = target; c->load.received = 0; c->load.total = total;
+  lk.unlock();
+  auto undo = [&](int rc) {   // the target may hold part of two snapshots now
+    hipStreamSynchronize(c->ks);
+    std::lock_guard<std::mutex> g(c->mu);
+    c->load.open = false;
+    c->load.segs.clear();
+    if (target == c->active) { c->active = -1; c->st.active_version = -1; }
+    return rc;
+  };
+  if (hipSetDevice(c->device) != hipSuccess) return undo(fail(c, ECHO_EHIP, "hipSetDevice failed"));
+  if (!running && hipStreamSynchronize(c->cs) != hipSuccess) return undo(fail(c, ECHO_EHIP, "hipStreamSynchronize failed"));
+  if (target != base) {   // the other slot becomes a copy of the base first (behind whatever still reads it, see leave_slot)
+    for (size_t o = 0; o < c->p.slot_bytes; o += (size_t)1 << 30) {
+      size_t len = std::min((size_t)1 << 30, c->p.slot_bytes - o);
+      if (hipMemcpyAsync(c->slots[target].base + o, c->slots[base].base + o, len, hipMemcpyDeviceToDevice, c->ks) != hipSuccess)
+        return undo(fail(c, ECHO_EHIP, "copying the base snapshot failed"));
+    }
+  }
+  c->load.segs = blob_segments(c, target);
+  const char *data = (const char *)host_data;
+  for (int i = 0; i < n_ranges; ++i) {
+    int rc = patch_segments(c, c->load.segs, data, (size_t)offsets[i], (size_t)sizes[i]);
+    if (rc) return undo(rc);
+    data += sizes[i];
+    if (hipStreamSynchronize(c->ks) != hipSuccess) return undo(fail(c, ECHO_EHIP, "hipStreamSynchronize failed"));   // staging halves are reused
+  }
+  int rc = commit_slot(c, target, version);
+  return rc ? undo(rc) : ECHO_OK;
+}
 
 int echo_load_policy_begin(echo_ctx *c, int64_t version, size_t nbytes) {
   if (!c) return ECHO_EINVAL;
@@ -150,23 +252,7 @@ int echo_load_policy_commit(echo_ctx *c) {
     if (c->load.received != c->load.total) return fail(c, ECHO_ESTATE, "%zu of %zu bytes have arrived", c->load.received, c->load.total);
   }
   HIPCHK(c, hipSetDevice(c->device));
-  HIPCHK(c, hipEventRecord(c->staged_ev, c->ks));
-  HIPCHK(c, hipStreamSynchronize(c->ks));
-  std::lock_guard<std::mutex> lk(c->mu);
-  int target = c->load.target;
-  c->slots[target].version = c->load.version;
-  c->newest_version = c->load.version;
-  if (c->rollout_running) {
-    c->staged = target;
-    c->st.staged_version = c->load.version;
-  } else {
-    c->active = target;
-    c->st.active_version = c->load.version;
-  }
-  c->load.open = false;
-  c->load.segs.clear();
-  c->cv.notify_all();
-  return ECHO_OK;
+  return commit_slot(c, c->load.target, c->load.version);
 }
 
 int echo_load_policy_abort(echo_ctx *c) {

@@ -42,6 +42,32 @@ void fast_pack_weight(void *dst, const void *src, int64_t dst_row0, int dst_row_
                      (const uint4 *)src, dst_row0, dst_row_stride, n_rows, K / 8, Kp / 8, Np);
 }
 
+// Re-pack a span of a matrix: elements [e0, e0 + n) of the row-major bf16 matrix [rows][K] (src holds just those n
+// values) replace their places in the packed weight; source row i lives in destination row dst_row0 + i * stride.
+// One thread per destination unit of 8 k that the span touches; a unit covered only in part keeps its other values.
+__global__ void pack_span_kernel(uint16_t *dst, const uint16_t *src, int64_t e0, int64_t n, int64_t dst_row0, int dst_row_stride, int K,
+                                 int Kp8, int Np) {
+  const int64_t u0 = e0 >> 3, u = u0 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // K % 8 == 0: units never straddle rows
+  if (u * 8 >= e0 + n) return;
+  const int K8 = K >> 3;
+  const int64_t i = u / K8, r = dst_row0 + i * dst_row_stride;
+  const int k8 = (int)(u % K8);
+  uint16_t *d = dst + (w_block_base((int)(r >> 5), Kp8 * 8) + (k8 >> 1) * w_kstep_stride(Np) + (k8 & 1) * 32 + (r & 31)) * 8;
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    const int64_t e = u * 8 + q;
+    if (e >= e0 && e < e0 + n) d[q] = f32_to_h16_bits(bf16_bits_to_f32(src[e - e0]) * W_SCALE);
+  }
+}
+
+void fast_pack_span(void *dst, const void *src, int64_t e0, int64_t n, int64_t dst_row0, int dst_row_stride, int K, int Kp, int Np,
+                    hipStream_t st) {
+  if (n <= 0) return;
+  const int64_t units = ((e0 + n + 7) >> 3) - (e0 >> 3);
+  hipLaunchKernelGGL(pack_span_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, st, (uint16_t *)dst, (const uint16_t *)src, e0, n,
+                     dst_row0, dst_row_stride, K, Kp / 8, Np);
+}
+
 // ---- the MFMA inner loop -------------------------------------------------------------------------------
 // A wavefront owns NBW consecutive 32-row weight blocks and all MB 32-row batch blocks of its launch slice:
 // per k-step it reads NBW KiB of weights and MB KiB of activations, so activation traffic from L2 per weight

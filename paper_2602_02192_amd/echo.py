@@ -50,7 +50,7 @@ class Stats(C.Structure):
 
 
 EXPORTS = ["echo_arena_bytes", "echo_blob_bytes", "echo_init", "echo_load_policy", "echo_load_policy_begin",
-           "echo_load_policy_chunk", "echo_load_policy_commit", "echo_load_policy_abort", "echo_rollout", "echo_rollout_continuous",
+           "echo_load_policy_chunk", "echo_load_policy_commit", "echo_load_policy_abort", "echo_load_policy_delta", "echo_rollout", "echo_rollout_continuous",
            "echo_logprobs", "echo_grpo_tensors", "echo_grpo_tensors_static", "echo_debug_draw_bits", "echo_stats", "echo_step_times", "echo_last_error", "echo_destroy"]
 
 lib.echo_arena_bytes.restype = C.c_size_t
@@ -64,6 +64,7 @@ lib.echo_load_policy_begin.argtypes = [C.c_void_p, C.c_int64, C.c_size_t]
 lib.echo_load_policy_chunk.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
 lib.echo_load_policy_commit.argtypes = [C.c_void_p]
 lib.echo_load_policy_abort.argtypes = [C.c_void_p]
+lib.echo_load_policy_delta.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
 lib.echo_rollout.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                              C.c_float, C.c_uint64, C.POINTER(RolloutOpts), C.c_void_p, C.c_void_p, C.c_void_p,
                              C.c_void_p]
@@ -181,6 +182,14 @@ class Context:
         except Exception:
             lib.echo_load_policy_abort(self.h)
             raise
+
+    def load_policy_delta(self, base_version: int, version: int, offsets, sizes, data) -> None:
+        """data: the new bytes of the ranges, concatenated (numpy uint8 array or bytes)."""
+        offsets = np.ascontiguousarray(offsets, np.uint64)
+        sizes = np.ascontiguousarray(sizes, np.uint64)
+        data = np.ascontiguousarray(np.frombuffer(data, np.uint8) if isinstance(data, (bytes, bytearray)) else data, np.uint8)
+        assert offsets.shape == sizes.shape and data.size == int(sizes.sum())
+        self._chk(lib.echo_load_policy_delta(self.h, base_version, version, offsets.size, _ptr(offsets), _ptr(sizes), _ptr(data)))
 
     def load_policy_begin(self, version: int, nbytes: int) -> None:
         self._chk(lib.echo_load_policy_begin(self.h, version, nbytes))
