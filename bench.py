@@ -22,6 +22,11 @@ HBM_PEAK_GBS = 8000.0
 # (shared prompt tiles once per group, a sequence's last tile whole).  Taken at the same kernel and grid on a 2-layer
 # model generating 64 tokens (the profiler crashes on the 36-layer process); set to None whenever attn_splitk_kernel changes.
 ATTN_TRAFFIC_OVER_TILE_BYTES = (29307.0 + 512.0) / (28608.0 + 512.0)
+# The same kernel timed by rocprofv3 --kernel-trace inside the graph replays of this very command (config 2), in microseconds
+# per launch (profiles/kernel_trace_dense4b-64x512+1024.md): the HIP events of the timed run bracket launches that are issued
+# one by one and include the launch gap, so both figures go into the line.  None for any other workload, and whenever the
+# kernel changes.
+ATTN_KERNEL_TRACE_US = {"dense4b-64x512+1024": 34.64}
 
 
 def attn_kv_bytes_per_launch(shape, gen_lens, prompt_len, group, steps, whole_tiles, shared_elsewhere=False):
@@ -317,6 +322,12 @@ def main():
                                         "whole-tile bytes, same kernel and grid, profiles/pmc_traffic_*.md)",
                         "launches_timed": int(st.attn_launches),
                         "avg_launch_us": per_launch_s * 1e6, "bytes_per_launch": per_launch_bytes}
+            if ATTN_KERNEL_TRACE_US.get(a.workload) and not prefix_kernel:
+                t_us = ATTN_KERNEL_TRACE_US[a.workload]
+                mean_bytes = attn_kv_bytes_per_launch(shape, out["lens"], plen, G, range(1, int(out["lens"].max())), whole_tiles=False)
+                roofline["kernel_trace"] = {"avg_launch_us": t_us, "bytes_per_launch": mean_bytes, "achieved": mean_bytes / t_us / 1e3,
+                                            "frac": mean_bytes / t_us / 1e3 / HBM_PEAK_GBS,
+                                            "source": "profiles/kernel_trace_dense4b-64x512+1024.md (rocprofv3 --kernel-trace of this command, all decode steps, inside graph replays)"}
             if st.gemm_launches:
                 g = st.gemm_bytes / (st.gemm_ms * 1e-3) / 1e9
                 roofline["gemm_weight_stream"] = {"achieved": g, "frac": g / HBM_PEAK_GBS,

@@ -42,7 +42,12 @@ enum { ECHO_F32 = 0, ECHO_BF16 = 1 };
  * ECHO_BF16 (weights are bf16 values) runs the MFMA kernels: half-precision operands -- the weights converted
  * exactly, activations and the KV cache rounded to half -- fp32 accumulation, fp32 residual stream;
  * ECHO_F32 runs the all-fp32 debug kernels.  debug_naive = 1 with ECHO_BF16 keeps bf16
- * weights but runs the debug kernels on them (fp32 activations and KV cache). */
+ * weights but runs the debug kernels on them (fp32 activations and KV cache).
+ * Range of the half-precision operands (ECHO_BF16 without debug_naive): a value that is rounded to half -- a normed
+ * activation, a query, a cached key or value, a SwiGLU output -- saturates at the largest finite half, +-65504, instead
+ * of becoming infinite, so everything downstream stays finite (and differs from an unbounded evaluation from there on);
+ * weights are held as halves of 256 times their value, exact for every bf16 weight of magnitude 2^-22 .. 255 and
+ * saturating beyond (smaller magnitudes flush towards zero); accumulation and the residual stream are fp32. */
 typedef struct {
   int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
   float rms_eps, rope_base;
