@@ -479,3 +479,35 @@ def test_dense4b_shape_in_the_benchmark_launch_configuration():
     ng = ctx.rollout(prompts, lens, G, 64, 1.0, 2, no_graph=True)
     assert np.array_equal(ng["tokens"], big["tokens"][:, :64]) and np.array_equal(ng["logprobs"], big["logprobs"][:, :64])
     ctx.close()
+
+
+@pytest.mark.parametrize("no_graph", [False, True])
+def test_draining_batch_with_eos_and_stop_lengths_is_compacted_and_matches_the_oracle(no_graph):
+    """40 sequences on the all-fp32 path, ended by stop lengths and by an end-of-sequence token: the batch drains below 32
+    rows (the host learns of EOS endings every 16 steps), rows are moved together, and every sequence still draws the
+    oracle's tokens (its draws are keyed by its sequence index wherever its row has moved)."""
+    shape = synth.TINY
+    blob = synth.make_weights(shape, 0)
+    blob32 = synth.widen_to_f32(blob)
+    P, G, max_new = 10, 4, 96
+    prompts, lens = synth.make_prompts(shape.vocab, P, 12, seed=3)
+    stop = synth.make_stop_lens(P * G, 1, max_new, seed=4)
+    stop[:6] = max_new                                    # some run to the end
+    probe = oracle_rollout(shape, blob32, prompts, lens, G=G, max_new=max_new, temperature=1.0, seed=9, stop_lens=stop)
+    vals, counts = np.unique(probe["tokens"][probe["tokens"] >= 0], return_counts=True)
+    eos = int(vals[counts.argmax()])                      # a token that does occur
+    ref = oracle_rollout(shape, blob32, prompts, lens, G=G, max_new=max_new, temperature=1.0, seed=9, stop_lens=stop, eos_id=eos)
+    assert (ref["lens"] < stop).any()                     # EOS does end sequences early
+    ctx = make_ctx(shape, P * G, 12 + max_new, blob)
+    got = ctx.rollout(prompts, lens, G, max_new, 1.0, 9, stop_lens=stop, eos_id=eos, no_graph=no_graph)
+    keep = ctx.rollout(prompts, lens, G, max_new, 1.0, 9, stop_lens=stop, eos_id=eos, no_graph=no_graph, no_compaction=True)
+    for k in ("tokens", "lens", "versions"):              # fp32 debug kernels: row position does not change a row's arithmetic
+        assert np.array_equal(got[k], keep[k]), k
+    assert np.array_equal(got["logprobs"], keep["logprobs"])
+    m = valid_mask(np.minimum(got["lens"], ref["lens"]), max_new)
+    if check_tokens_fp32_sampler(got["tokens"], ref, mask=m) == 0:
+        assert np.array_equal(got["lens"], ref["lens"])
+        assert np.abs(got["logprobs"] - ref["logprobs"])[m].max() < F32_LOGPROB_TOL
+    mm = valid_mask(got["lens"], max_new)
+    assert (got["tokens"][~mm] == -1).all() and (got["logprobs"][~mm] == 0).all() and (got["versions"][~mm] == -1).all()
+    ctx.close()
