@@ -517,16 +517,15 @@ __global__ __launch_bounds__(WN * 64) void gemm_lds_kernel(void *out, const u32x
 }
 
 // ---- 256-row tiles for batches of 256 rows and more ------------------------------------------------------------
-// Prefill and scoring are bound by the matrix cores, and what a compute unit can pull from L2 per cycle caps them:
-// a workgroup that computes Tn x Tm outputs per k loads Tn + Tm operand rows, so the tile has to be large in both
-// directions.  Every wavefront owns two weight blocks (64 output columns), streamed from global memory straight into
-// A-operand registers, against MB blocks of 32 batch rows whose operands come through LDS; every activation operand read
-// from LDS feeds two MFMAs, which halves the LDS traffic of the one-block kernel (that one runs at the LDS limit).
-// Two forms: WN = 8 wavefronts (two per SIMD) as two row halves x four column pairs on a 256 x 256 tile, 128
-// accumulator registers per lane: the form for 512 rows and more; WN = 4 as two row halves x two column pairs on a
-// 256 x 128 tile: for batches of exactly a few hundred rows, where 256 x 256 tiles are too few to fill the chip.
-template <int WRv, int WNv = 4> struct GemmWideT {
-  static constexpr int WR = WRv, MB = 8 / WR, WN = WNv, WC = WN / WR, NBW = 2, ROWS = 256, T = WN * 64;
+// Register-streaming form, four wavefronts.  Every wavefront owns two weight blocks (64 output columns), streamed from
+// global memory straight into A-operand registers, against MB blocks of 32 batch rows whose operands come through LDS;
+// every activation operand read from LDS feeds two MFMAs, which halves the LDS traffic of the one-block kernel (that
+// one runs at the LDS limit).  WR = 1: one row of four wavefronts on a 256 x 256 tile (the lm_head kernels below
+// share this layout); WR = 2: two row halves x two column pairs on a 256 x 128 tile, for batches of exactly a few
+// hundred rows, where 256 x 256 tiles are too few to fill the chip.  Batches of 512 rows and more take
+// gemm_ring_kernel further down.
+template <int WRv> struct GemmWideT {
+  static constexpr int WR = WRv, MB = 8 / WR, WN = 4, WC = WN / WR, NBW = 2, ROWS = 256, T = WN * 64;
   static constexpr int CK = 1, NSTAGE = 8 / CK;   // k-steps per chunk (one barrier each), chunks in flight; CK = 2 measured 1-2 % slower
   static constexpr int CHUNK_UNITS = CK * 2 * ROWS, XL = CHUNK_UNITS / T;
   static constexpr int X_BYTES = 2 * CHUNK_UNITS * 16, TILE_STRIDE = 33, EPI_BYTES = WN * 32 * TILE_STRIDE * 4;
@@ -535,7 +534,7 @@ template <int WRv, int WNv = 4> struct GemmWideT {
 using GemmWide = GemmWideT<1>;
 
 // One k-step per chunk, operands requested seven chunks ahead: the depth of the register pipeline hides most of the
-// load latency (measured throughput kept rising with it), a second wavefront on the SIMD the rest.  Kp is a multiple of
+// load latency (measured throughput kept rising with it).  Kp is a multiple of
 // GEMM_K_PAD, so the k-step count is a multiple of the eight stages and the loop needs neither tails nor conditions
 // (a load behind a condition makes the compiler's wait counts drain the queue): the prefetches of the last trips
 // are clamped to the last k-step, loaded again and never used.
@@ -543,11 +542,11 @@ using GemmWide = GemmWideT<1>;
 // found in cache by the other row blocks; pays when the weight matrix is far larger than the last-level cache.
 // blockIdx.y splits K in runs of `groups_per_split` groups of eight k-steps (EPI_PARTIAL only: split y writes the
 // partial plane y of out).
-template <int EPI, bool ZFAST, int WR, int WN>
-__global__ __launch_bounds__(WN * 64) void gemm_wide_kernel(void *out, const u32x4v *__restrict__ Xp, const h16x8 *__restrict__ Wp, int Mp,
+template <int EPI, bool ZFAST, int WR>
+__global__ __launch_bounds__(256) void gemm_wide_kernel(void *out, const u32x4v *__restrict__ Xp, const h16x8 *__restrict__ Wp, int Mp,
                                                         int Np, int Kp, int groups_per_split) {
   extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-  using L = GemmWideT<WR, WN>;
+  using L = GemmWideT<WR>;
   constexpr int MB = L::MB, NBW = L::NBW, T = L::T, XU = L::CHUNK_UNITS, XL = L::XL, ROWS = L::ROWS, NSTAGE = L::NSTAGE, CK = L::CK;
   static_assert((GEMM_K_PAD / 16) % (NSTAGE * CK) == 0, "k-step count must be a multiple of the k-steps in flight");
   u32x4v *xs = (u32x4v *)lds_raw;
@@ -668,19 +667,164 @@ __global__ __launch_bounds__(WN * 64) void gemm_wide_kernel(void *out, const u32
   }
 }
 
-template <int EPI, bool ZFAST, int WR = 1, int WN = 4>
+template <int EPI, bool ZFAST, int WR = 1>
 static void gemm_wide_launch(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, hipStream_t st, int nsplit = 1) {
-  using L = GemmWideT<WR, WN>;
+  using L = GemmWideT<WR>;
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void *)gemm_wide_kernel<EPI, ZFAST, WR, WN>, hipFuncAttributeMaxDynamicSharedMemorySize, L::BYTES);
+    (void)hipFuncSetAttribute((const void *)gemm_wide_kernel<EPI, ZFAST, WR>, hipFuncAttributeMaxDynamicSharedMemorySize, L::BYTES);
     attr_set = true;
   }
   int nblocks = Np / 32, per_wg = L::WC * L::NBW, strips = (nblocks + per_wg - 1) / per_wg, nz = Mp / L::ROWS;
   int groups = (Kp / 16) / (L::NSTAGE * L::CK), gps = (groups + nsplit - 1) / nsplit, ny = (groups + gps - 1) / gps;
   dim3 grid = ZFAST ? dim3(strips * nz, ny, 1) : dim3(strips, ny, nz);
-  hipLaunchKernelGGL((gemm_wide_kernel<EPI, ZFAST, WR, WN>), grid, dim3(L::T), L::BYTES, st, out, (const u32x4v *)Xp, (const h16x8 *)Wp, Mp,
+  hipLaunchKernelGGL((gemm_wide_kernel<EPI, ZFAST, WR>), grid, dim3(L::T), L::BYTES, st, out, (const u32x4v *)Xp, (const h16x8 *)Wp, Mp,
                      Np, Kp, gps);
+}
+
+// ---- 256 x 256 tiles with both operands in an LDS ring: batches of 512 rows and more --------------------------
+// What caps a large-tile GEMM here is what a compute unit can take in per cycle through its vector memory path, so a
+// workgroup must fetch every operand byte once: 256 weight columns and 256 batch rows per k-step are 16 KB for 2 MFLOP.
+// (The register-streaming form above fetches every weight block once per row half, 24 KB per k-step, and measured
+// 12 - 25 % slower at 4096 rows.)  Eight wavefronts, two per SIMD, as two row halves x four column pairs; wavefront w
+// fetches weight block w of the tile's eight and an eighth of the activation chunk, each as one 1 KB load that lands
+// in LDS without passing through registers (global_load_lds, the data of lane l at 16 l); a stage of the ring is one
+// k-step: [8 blocks x 64 units of A operands][2 k8 groups x 256 rows of B operands], 16 KB, eight stages.  Step c
+// issues the loads of k-step c + LA, reads its two A and four B operands from stage c and runs eight MFMAs; before the
+// barrier that ends the step a wavefront waits until its own loads of k-step c + 1 have landed (loads retire in
+// order: all but the 2 (LA - 1) youngest), so after the barrier the whole stage c + 1 is there.  The stage that
+// step c's loads overwrite held k-step c + LA - 8, whose readers passed the barrier of step c + LA - 8 <= c - 1.
+// The wait is written by hand, together with the barrier: the compiler's own barrier sequence would wait for every
+// outstanding load and empty the ring.  Sums run in the same order as in the other kernels (k ascending in one
+// accumulator), so results are bit-identical.
+struct GemmRing {
+  static constexpr int WR = 2, WC = 4, WN = 8, MB = 4, NBW = 2, ROWS = 256, T = WN * 64;
+  static constexpr int NS = 8, LA = 6, SU = 1024;   // stages, k-steps ahead (< NS), 16-byte units per stage
+  static constexpr int TILE_STRIDE = 33, BYTES = NS * SU * 16;   // 128 KB; the epilogue's 8 x 32 x 33 floats reuse it
+};
+
+__device__ __forceinline__ void load_to_lds(const void *g, void *l) {   // 16 bytes per lane; l is the wavefront's base, lane l lands at l + 16 l
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g, (__attribute__((address_space(3))) void *)l, 16, 0, 0);
+}
+
+template <int EPI, bool ZFAST>
+__global__ __launch_bounds__(GemmRing::T) void gemm_ring_kernel(void *out, const u32x4v *__restrict__ Xp, const h16x8 *__restrict__ Wp, int Mp,
+                                                                int Np, int Kp, int groups_per_split) {
+  extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+  using L = GemmRing;
+  constexpr int MB = L::MB, NBW = L::NBW, ROWS = L::ROWS, NS = L::NS, LA = L::LA, SU = L::SU, WC = L::WC;
+  static_assert((GEMM_K_PAD / 16) % NS == 0 && LA < NS && LA >= 1, "a run of k-steps is a whole number of trips round the ring");
+  u32x4v *ring = (u32x4v *)lds_raw;
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int nblocks = Np >> 5, nz = Mp / ROWS;
+  const int c_lo = blockIdx.y * groups_per_split * NS;
+  const int nchunks = min(Kp >> 4, c_lo + groups_per_split * NS), last = nchunks - 1;
+  const int plane = blockIdx.y;
+  const int bx = ZFAST ? blockIdx.x / nz : blockIdx.x, bz = ZFAST ? blockIdx.x % nz : blockIdx.z;
+  const int nbw = bx * WC * NBW, nb0 = nbw + (w % WC) * NBW, mrow0 = bz * ROWS, wrow = (w / WC) * 32 * MB;
+  const int64_t a_step = w_kstep_stride(Np);
+  // what this wavefront fetches: weight block nbw + w (past the end: the last one again, never stored) and units
+  // 64 w .. of the activation chunk (unit i: k8 group i / ROWS of the k-step, batch row i % ROWS)
+  const h16x8 *a_src = Wp + w_block_base(min(nbw + w, nblocks - 1), Kp) + (lane >> 5) * 32 + (lane & 31);
+  const int xi = w * 64 + lane;
+  const u32x4v *x_src = Xp + (int64_t)(xi / ROWS) * Mp + mrow0 + xi % ROWS;
+  auto fetch = [&](int st, int c) {
+    load_to_lds(x_src + (int64_t)(c * 2) * Mp, ring + st * SU + 512 + w * 64);
+    load_to_lds(a_src + (int64_t)c * a_step, ring + st * SU + w * 64);
+  };
+  // what it reads: its two weight blocks, and the rows of its row half
+  const u32x4v *a_lds = ring + (w % WC) * NBW * 64 + lane;
+  const u32x4v *b_lds = ring + 512 + (lane >> 5) * ROWS + wrow + (lane & 31);
+  f32x16 acc[NBW][MB];
+#pragma unroll
+  for (int n = 0; n < NBW; ++n)
+#pragma unroll
+    for (int j = 0; j < MB; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[n][j][r] = 0.f;
+#pragma unroll
+  for (int j = 0; j < LA; ++j) fetch(j, min(c_lo + j, last));   // a run has at least NS k-steps
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * (LA - 1)) : "memory");
+  __syncthreads();
+  for (int c0 = c_lo; c0 < nchunks; c0 += NS) {
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      fetch((s + LA) % NS, min(c0 + s + LA, last));   // past the end: the last k-step again, never read
+      u32x4v a[NBW], b[MB];
+#pragma unroll
+      for (int n = 0; n < NBW; ++n) a[n] = a_lds[s * SU + n * 64];
+#pragma unroll
+      for (int j = 0; j < MB; ++j) b[j] = b_lds[s * SU + j * 32];
+#pragma unroll
+      for (int j = 0; j < MB; ++j)
+#pragma unroll
+        for (int n = 0; n < NBW; ++n) acc[n][j] = mfma_h16(__builtin_bit_cast(h16x8, a[n]), __builtin_bit_cast(h16x8, b[j]), acc[n][j]);
+      asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * (LA - 1)) : "memory");
+    }
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the loads past the end have landed before the ring is reused
+  __syncthreads();
+  const int half = lane >> 5, col = lane & 31;
+  if (EPI == EPI_PARTIAL) {   // 32 x 32 tiles transposed through LDS so that every store is a whole 128-byte row segment
+    float *tile = (float *)lds_raw + (size_t)w * 32 * L::TILE_STRIDE;
+#pragma unroll
+    for (int n = 0; n < NBW; ++n) {
+      float *P = (float *)out + ((int64_t)plane * Mp + mrow0 + wrow) * Np + (nb0 + n) * 32;
+#pragma unroll
+      for (int j = 0; j < MB; ++j) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) tile[col * L::TILE_STRIDE + 8 * g + 4 * half + i] = acc[n][j][4 * g + i] * W_UNSCALE;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        if (nb0 + n < nblocks) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            int r = q * 8 + (lane >> 3), n4 = (lane & 7) * 4;
+            const float *t = tile + r * L::TILE_STRIDE + n4;
+            f32x4 v = {t[0], t[1], t[2], t[3]};
+            *(f32x4 *)(P + (int64_t)(j * 32 + r) * Np + n4) = v;
+          }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      }
+    }
+  } else {  // EPI_SWIGLU, as in the kernels above
+    uint32_t *O = (uint32_t *)out;
+#pragma unroll
+    for (int n = 0; n < NBW; ++n) {
+      if (nb0 + n >= nblocks) break;
+#pragma unroll
+      for (int j = 0; j < MB; ++j) {
+        uint32_t pk[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          float v0 = silu_f(acc[n][j][4 * g] * W_UNSCALE) * (acc[n][j][4 * g + 1] * W_UNSCALE);
+          float v1 = silu_f(acc[n][j][4 * g + 2] * W_UNSCALE) * (acc[n][j][4 * g + 3] * W_UNSCALE);
+          pk[g] = (uint32_t)f32_to_h16_bits(v0) | ((uint32_t)f32_to_h16_bits(v1) << 16);
+        }
+        uint32_t give0 = half ? pk[0] : pk[2], give1 = half ? pk[1] : pk[3];
+        uint32_t got0 = __shfl_xor(give0, 32, 64), got1 = __shfl_xor(give1, 32, 64);
+        u32x4v o = half ? u32x4v{got0, pk[2], got1, pk[3]} : u32x4v{pk[0], got0, pk[1], got1};
+        int m = mrow0 + wrow + j * 32 + col;
+        *(u32x4v *)(O + (((int64_t)((nb0 + n) * 2 + half) * Mp + m) * 4)) = o;
+      }
+    }
+  }
+}
+
+template <int EPI, bool ZFAST>
+static void gemm_ring_launch(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, hipStream_t st, int nsplit = 1) {
+  using L = GemmRing;
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void *)gemm_ring_kernel<EPI, ZFAST>, hipFuncAttributeMaxDynamicSharedMemorySize, L::BYTES);
+    attr_set = true;
+  }
+  int nblocks = Np / 32, per_wg = L::WC * L::NBW, strips = (nblocks + per_wg - 1) / per_wg, nz = Mp / L::ROWS;
+  int groups = (Kp / 16) / L::NS, gps = (groups + nsplit - 1) / nsplit, ny = (groups + gps - 1) / gps;
+  dim3 grid = ZFAST ? dim3(strips * nz, ny, 1) : dim3(strips, ny, nz);
+  hipLaunchKernelGGL((gemm_ring_kernel<EPI, ZFAST>), grid, dim3(L::T), L::BYTES, st, out, (const u32x4v *)Xp, (const h16x8 *)Wp, Mp, Np, Kp, gps);
 }
 
 // Launch shape.  Up to 128 batch rows the LDS-staged kernel runs: three or four weight blocks per workgroup, and a
@@ -786,12 +930,9 @@ static void gemm_lds_dispatch(void *out, const void *Xp, const void *Wp, int Mp,
 
 template <int EPI>
 static void gemm_dispatch(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, GemmShape g, hipStream_t st) {
-  if (g.lds == 2) {
-    // Eight wavefronts (two per SIMD) on the 256 x 256 tile: at 4096 rows 3 .. 10 % faster than four wavefronts with
-    // twice the accumulators each on all the projection shapes of the 4B, 8B and 32B models.  Row blocks fastest once
-    // the weights are far larger than the last-level cache.
-    if ((size_t)Np * Kp * 2 >= ((size_t)256 << 20)) gemm_wide_launch<EPI, true, 2, 8>(out, Xp, Wp, Mp, Np, Kp, st, g.nsplit);
-    else gemm_wide_launch<EPI, false, 2, 8>(out, Xp, Wp, Mp, Np, Kp, st, g.nsplit);
+  if (g.lds == 2) {   // row blocks fastest once the weights are far larger than the last-level cache
+    if ((size_t)Np * Kp * 2 >= ((size_t)256 << 20)) gemm_ring_launch<EPI, true>(out, Xp, Wp, Mp, Np, Kp, st, g.nsplit);
+    else gemm_ring_launch<EPI, false>(out, Xp, Wp, Mp, Np, Kp, st, g.nsplit);
     return;
   }
   if (g.lds == 3) { gemm_wide_launch<EPI, false, 2>(out, Xp, Wp, Mp, Np, Kp, st, g.nsplit); return; }
