@@ -516,203 +516,55 @@ __global__ __launch_bounds__(WN * 64) void gemm_lds_kernel(void *out, const u32x
   }
 }
 
-// ---- 256-row tiles for batches of 256 rows and more ------------------------------------------------------------
-// Register-streaming form, four wavefronts.  Every wavefront owns two weight blocks (64 output columns), streamed from
-// global memory straight into A-operand registers, against MB blocks of 32 batch rows whose operands come through LDS;
-// every activation operand read from LDS feeds two MFMAs, which halves the LDS traffic of the one-block kernel (that
-// one runs at the LDS limit).  WR = 1: one row of four wavefronts on a 256 x 256 tile (the lm_head kernels below
-// share this layout); WR = 2: two row halves x two column pairs on a 256 x 128 tile, for batches of exactly a few
-// hundred rows, where 256 x 256 tiles are too few to fill the chip.  Batches of 512 rows and more take
-// gemm_ring_kernel further down.
-template <int WRv> struct GemmWideT {
-  static constexpr int WR = WRv, MB = 8 / WR, WN = 4, WC = WN / WR, NBW = 2, ROWS = 256, T = WN * 64;
+// ---- the 256 x 256 register-streaming tile of the wide lm_head kernel ----------------------------------------------
+// Four wavefronts in a row; every wavefront owns two weight blocks (64 output columns), streamed from global memory
+// straight into A-operand registers, against eight blocks of 32 batch rows whose operands come through LDS; every
+// activation operand read from LDS feeds two MFMAs.  (The projections used this form too, also as two row halves x two
+// column pairs on a 256 x 128 tile, until gemm_ring_kernel below replaced it there.)
+struct GemmWide {
+  static constexpr int MB = 8, WN = 4, NBW = 2, ROWS = 256, T = WN * 64;
   static constexpr int CK = 1, NSTAGE = 8 / CK;   // k-steps per chunk (one barrier each), chunks in flight; CK = 2 measured 1-2 % slower
   static constexpr int CHUNK_UNITS = CK * 2 * ROWS, XL = CHUNK_UNITS / T;
   static constexpr int X_BYTES = 2 * CHUNK_UNITS * 16, TILE_STRIDE = 33, EPI_BYTES = WN * 32 * TILE_STRIDE * 4;
   static constexpr int BYTES = X_BYTES > EPI_BYTES ? X_BYTES : EPI_BYTES;
 };
-using GemmWide = GemmWideT<1>;
 
-// One k-step per chunk, operands requested seven chunks ahead: the depth of the register pipeline hides most of the
-// load latency (measured throughput kept rising with it).  Kp is a multiple of
-// GEMM_K_PAD, so the k-step count is a multiple of the eight stages and the loop needs neither tails nor conditions
-// (a load behind a condition makes the compiler's wait counts drain the queue): the prefetches of the last trips
-// are clamped to the last k-step, loaded again and never used.
-// ZFAST: the row blocks of one weight strip are neighbours in launch order, so a strip is fetched from HBM once and
-// found in cache by the other row blocks; pays when the weight matrix is far larger than the last-level cache.
-// blockIdx.y splits K in runs of `groups_per_split` groups of eight k-steps (EPI_PARTIAL only: split y writes the
-// partial plane y of out).
-template <int EPI, bool ZFAST, int WR>
-__global__ __launch_bounds__(256) void gemm_wide_kernel(void *out, const u32x4v *__restrict__ Xp, const h16x8 *__restrict__ Wp, int Mp,
-                                                        int Np, int Kp, int groups_per_split) {
-  extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-  using L = GemmWideT<WR>;
-  constexpr int MB = L::MB, NBW = L::NBW, T = L::T, XU = L::CHUNK_UNITS, XL = L::XL, ROWS = L::ROWS, NSTAGE = L::NSTAGE, CK = L::CK;
-  static_assert((GEMM_K_PAD / 16) % (NSTAGE * CK) == 0, "k-step count must be a multiple of the k-steps in flight");
-  u32x4v *xs = (u32x4v *)lds_raw;
-  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, tid = threadIdx.x;
-  const int nblocks = Np >> 5, nz = Mp / ROWS;
-  // chunk range of this workgroup
-  const int c_lo = blockIdx.y * groups_per_split * NSTAGE;
-  const int nchunks = min((Kp >> 4) / CK, c_lo + groups_per_split * NSTAGE);
-  const int plane = blockIdx.y;
-  const int bx = ZFAST ? blockIdx.x / nz : blockIdx.x, bz = ZFAST ? blockIdx.x % nz : blockIdx.z;
-  const int nb0 = (bx * L::WC + w % L::WC) * NBW, mrow0 = bz * ROWS, wrow = (w / L::WC) * 32 * MB;
-  const int64_t a_step = w_kstep_stride(Np);
-  const h16x8 *a_ptr[NBW];
-#pragma unroll
-  for (int n = 0; n < NBW; ++n)   // blocks past the end re-read the last one and are not stored
-    a_ptr[n] = Wp + w_block_base(min(nb0 + n, nblocks - 1), Kp) + (lane >> 5) * 32 + (lane & 31);
-  f32x16 acc[NBW][MB];
-#pragma unroll
-  for (int n = 0; n < NBW; ++n)
-#pragma unroll
-    for (int j = 0; j < MB; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[n][j][r] = 0.f;
-  h16x8 a[NSTAGE][CK][NBW];
-  u32x4v xr[NSTAGE][XL];
-  auto load_a = [&](int st, int c) {
-#pragma unroll
-    for (int u = 0; u < CK; ++u)
-#pragma unroll
-      for (int n = 0; n < NBW; ++n) a[st][u][n] = __builtin_nontemporal_load(a_ptr[n] + (int64_t)(c * CK + u) * a_step);
-  };
-  auto load_x = [&](int st, int c) {   // unit i of a chunk: k8 group i / ROWS (two per k-step), batch row i % ROWS
-#pragma unroll
-    for (int i = 0; i < XL; ++i) {
-      int idx = i * T + tid;
-      xr[st][i] = Xp[(int64_t)(c * CK * 2 + idx / ROWS) * Mp + mrow0 + idx % ROWS];
-    }
-  };
-  auto store_x = [&](int st, int buf) {
-#pragma unroll
-    for (int i = 0; i < XL; ++i) xs[buf * XU + i * T + tid] = xr[st][i];
-  };
-  auto compute = [&](int st, int buf) {
-    const u32x4v *bp = xs + buf * XU + (lane >> 5) * ROWS + wrow + (lane & 31);
-    u32x4v b[CK][MB];
-#pragma unroll
-    for (int u = 0; u < CK; ++u)
-#pragma unroll
-      for (int j = 0; j < MB; ++j) b[u][j] = bp[u * 2 * ROWS + j * 32];
-#pragma unroll
-    for (int u = 0; u < CK; ++u)
-#pragma unroll
-      for (int j = 0; j < MB; ++j)
-#pragma unroll
-        for (int n = 0; n < NBW; ++n) acc[n][j] = mfma_h16(a[st][u][n], __builtin_bit_cast(h16x8, b[u][j]), acc[n][j]);
-  };
-#pragma unroll
-  for (int s = 0; s < NSTAGE - 1; ++s) { load_x(s, c_lo + s); load_a(s, c_lo + s); }   // a run has at least NSTAGE chunks
-  store_x(0, 0);
-  __syncthreads();
-  for (int c0 = c_lo; c0 < nchunks; c0 += NSTAGE) {
-#pragma unroll
-    for (int s = 0; s < NSTAGE; ++s) {
-      const int c = c0 + s, cn = min(c + NSTAGE - 1, nchunks - 1);
-      load_x((s + NSTAGE - 1) % NSTAGE, cn);
-      load_a((s + NSTAGE - 1) % NSTAGE, cn);
-      compute(s, s & 1);
-      store_x((s + 1) % NSTAGE, (s + 1) & 1);
-      __syncthreads();
-    }
-  }
-  const int half = lane >> 5, col = lane & 31;
-  if (EPI == EPI_PARTIAL) {   // 32 x 32 tiles transposed through LDS so that every store is a whole 128-byte row segment
-    float *tile = (float *)lds_raw + (size_t)w * 32 * L::TILE_STRIDE;
-#pragma unroll
-    for (int n = 0; n < NBW; ++n) {
-      float *P = (float *)out + ((int64_t)plane * Mp + mrow0 + wrow) * Np + (nb0 + n) * 32;
-#pragma unroll
-      for (int j = 0; j < MB; ++j) {
-#pragma unroll
-        for (int g = 0; g < 4; ++g)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) tile[col * L::TILE_STRIDE + 8 * g + 4 * half + i] = acc[n][j][4 * g + i] * W_UNSCALE;
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        if (nb0 + n < nblocks) {
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            int r = q * 8 + (lane >> 3), n4 = (lane & 7) * 4;
-            const float *t = tile + r * L::TILE_STRIDE + n4;
-            f32x4 v = {t[0], t[1], t[2], t[3]};
-            *(f32x4 *)(P + (int64_t)(j * 32 + r) * Np + n4) = v;
-          }
-        }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      }
-    }
-  } else {  // EPI_SWIGLU, as in the kernel above
-    uint32_t *O = (uint32_t *)out;
-#pragma unroll
-    for (int n = 0; n < NBW; ++n) {
-      if (nb0 + n >= nblocks) break;
-#pragma unroll
-      for (int j = 0; j < MB; ++j) {
-        uint32_t pk[4];
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          float v0 = silu_f(acc[n][j][4 * g] * W_UNSCALE) * (acc[n][j][4 * g + 1] * W_UNSCALE);
-          float v1 = silu_f(acc[n][j][4 * g + 2] * W_UNSCALE) * (acc[n][j][4 * g + 3] * W_UNSCALE);
-          pk[g] = (uint32_t)f32_to_h16_bits(v0) | ((uint32_t)f32_to_h16_bits(v1) << 16);
-        }
-        uint32_t give0 = half ? pk[0] : pk[2], give1 = half ? pk[1] : pk[3];
-        uint32_t got0 = __shfl_xor(give0, 32, 64), got1 = __shfl_xor(give1, 32, 64);
-        u32x4v o = half ? u32x4v{got0, pk[2], got1, pk[3]} : u32x4v{pk[0], got0, pk[1], got1};
-        int m = mrow0 + wrow + j * 32 + col;
-        *(u32x4v *)(O + (((int64_t)((nb0 + n) * 2 + half) * Mp + m) * 4)) = o;
-      }
-    }
-  }
-}
-
-template <int EPI, bool ZFAST, int WR = 1>
-static void gemm_wide_launch(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, hipStream_t st, int nsplit = 1) {
-  using L = GemmWideT<WR>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute((const void *)gemm_wide_kernel<EPI, ZFAST, WR>, hipFuncAttributeMaxDynamicSharedMemorySize, L::BYTES);
-    attr_set = true;
-  }
-  int nblocks = Np / 32, per_wg = L::WC * L::NBW, strips = (nblocks + per_wg - 1) / per_wg, nz = Mp / L::ROWS;
-  int groups = (Kp / 16) / (L::NSTAGE * L::CK), gps = (groups + nsplit - 1) / nsplit, ny = (groups + gps - 1) / gps;
-  dim3 grid = ZFAST ? dim3(strips * nz, ny, 1) : dim3(strips, ny, nz);
-  hipLaunchKernelGGL((gemm_wide_kernel<EPI, ZFAST, WR>), grid, dim3(L::T), L::BYTES, st, out, (const u32x4v *)Xp, (const h16x8 *)Wp, Mp,
-                     Np, Kp, gps);
-}
-
-// ---- 256 x 256 tiles with both operands in an LDS ring: batches of 512 rows and more --------------------------
+// ---- 256-row tiles with both operands in an LDS ring: batches of 256 rows and more ------------------------------
 // What caps a large-tile GEMM here is what a compute unit can take in per cycle through its vector memory path, so a
 // workgroup must fetch every operand byte once: 256 weight columns and 256 batch rows per k-step are 16 KB for 2 MFLOP.
-// (The register-streaming form above fetches every weight block once per row half, 24 KB per k-step, and measured
-// 12 - 25 % slower at 4096 rows.)  Eight wavefronts, two per SIMD, as two row halves x four column pairs; wavefront w
-// fetches weight block w of the tile's eight and an eighth of the activation chunk, each as one 1 KB load that lands
+// (A register-streaming form with two row halves fetched every weight block once per row half, 24 KB per k-step, and
+// measured 12 - 25 % slower at 4096 rows.)  Eight wavefronts, two per SIMD, as two row halves x four column pairs; wavefront w
+// fetches weight block w of the tile's eight and its share of the activation chunk, each as one 1 KB load that lands
 // in LDS without passing through registers (global_load_lds, the data of lane l at 16 l); a stage of the ring is one
 // k-step: [8 blocks x 64 units of A operands][2 k8 groups x 256 rows of B operands], 16 KB, eight stages.  Step c
 // issues the loads of k-step c + LA, reads its two A and four B operands from stage c and runs eight MFMAs; before the
 // barrier that ends the step a wavefront waits until its own loads of k-step c + 1 have landed (loads retire in
-// order: all but the 2 (LA - 1) youngest), so after the barrier the whole stage c + 1 is there.  The stage that
+// order: all but the youngest LA - 1 k-steps' worth), so after the barrier the whole stage c + 1 is there.  The stage that
 // step c's loads overwrite held k-step c + LA - 8, whose readers passed the barrier of step c + LA - 8 <= c - 1.
 // The wait is written by hand, together with the barrier: the compiler's own barrier sequence would wait for every
 // outstanding load and empty the ring.  Sums run in the same order as in the other kernels (k ascending in one
-// accumulator), so results are bit-identical.
-struct GemmRing {
-  static constexpr int WR = 2, WC = 4, WN = 8, MB = 4, NBW = 2, ROWS = 256, T = WN * 64;
-  static constexpr int NS = 8, LA = 6, SU = 1024;   // stages, k-steps ahead (< NS), 16-byte units per stage
-  static constexpr int TILE_STRIDE = 33, BYTES = NS * SU * 16;   // 128 KB; the epilogue's 8 x 32 x 33 floats reuse it
+// accumulator), so results are bit-identical.  With WC = 2 the same kernel runs four wavefronts (two row halves x two
+// column pairs) on a 256 x 128 tile, 12 KB per k-step: batches of a few hundred rows, where 256 x 256 tiles are too few
+// to fill the chip (4 - 15 % faster there than the register-streaming form it replaced).
+template <int WCv> struct GemmRingT {   // WC = 4: 256 x 256 tile, eight wavefronts; WC = 2: 256 x 128 tile, four wavefronts
+  static constexpr int WR = 2, WC = WCv, WN = WR * WC, MB = 4, NBW = 2, ROWS = 256, T = WN * 64;
+  static constexpr int AU = WC * NBW * 64, XU = 2 * ROWS, SU = AU + XU;   // 16-byte units of a stage: A operands, B operands
+  static constexpr int XLW = XU / T, LPS = 1 + XLW;                       // activation loads, all loads per wavefront and k-step
+  static constexpr int NS = 8, LA = 6;                                    // stages, k-steps ahead (< NS)
+  static constexpr int TILE_STRIDE = 33, BYTES = NS * SU * 16;            // 128 KB / 96 KB; the epilogue's WN x 32 x 33 floats reuse it
 };
+using GemmRing = GemmRingT<4>;
 
 __device__ __forceinline__ void load_to_lds(const void *g, void *l) {   // 16 bytes per lane; l is the wavefront's base, lane l lands at l + 16 l
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g, (__attribute__((address_space(3))) void *)l, 16, 0, 0);
 }
 
-template <int EPI, bool ZFAST>
-__global__ __launch_bounds__(GemmRing::T) void gemm_ring_kernel(void *out, const u32x4v *__restrict__ Xp, const h16x8 *__restrict__ Wp, int Mp,
+template <int EPI, bool ZFAST, int WCv>
+__global__ __launch_bounds__(GemmRingT<WCv>::T) void gemm_ring_kernel(void *out, const u32x4v *__restrict__ Xp, const h16x8 *__restrict__ Wp, int Mp,
                                                                 int Np, int Kp, int groups_per_split) {
   extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-  using L = GemmRing;
-  constexpr int MB = L::MB, NBW = L::NBW, ROWS = L::ROWS, NS = L::NS, LA = L::LA, SU = L::SU, WC = L::WC;
+  using L = GemmRingT<WCv>;
+  constexpr int MB = L::MB, NBW = L::NBW, ROWS = L::ROWS, NS = L::NS, LA = L::LA, SU = L::SU, WC = L::WC, AU = L::AU, WN = L::WN, LPS = L::LPS;
   static_assert((GEMM_K_PAD / 16) % NS == 0 && LA < NS && LA >= 1, "a run of k-steps is a whole number of trips round the ring");
   u32x4v *ring = (u32x4v *)lds_raw;
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -723,18 +575,23 @@ __global__ __launch_bounds__(GemmRing::T) void gemm_ring_kernel(void *out, const
   const int bx = ZFAST ? blockIdx.x / nz : blockIdx.x, bz = ZFAST ? blockIdx.x % nz : blockIdx.z;
   const int nbw = bx * WC * NBW, nb0 = nbw + (w % WC) * NBW, mrow0 = bz * ROWS, wrow = (w / WC) * 32 * MB;
   const int64_t a_step = w_kstep_stride(Np);
-  // what this wavefront fetches: weight block nbw + w (past the end: the last one again, never stored) and units
-  // 64 w .. of the activation chunk (unit i: k8 group i / ROWS of the k-step, batch row i % ROWS)
+  // what this wavefront fetches: weight block nbw + w (past the end: the last one again, never stored) and the
+  // runs of 64 units i WN + w of the activation chunk (unit u: k8 group u / ROWS of the k-step, batch row u % ROWS)
   const h16x8 *a_src = Wp + w_block_base(min(nbw + w, nblocks - 1), Kp) + (lane >> 5) * 32 + (lane & 31);
-  const int xi = w * 64 + lane;
-  const u32x4v *x_src = Xp + (int64_t)(xi / ROWS) * Mp + mrow0 + xi % ROWS;
+  const u32x4v *x_src[L::XLW];
+#pragma unroll
+  for (int i = 0; i < L::XLW; ++i) {
+    int xi = (i * WN + w) * 64 + lane;
+    x_src[i] = Xp + (int64_t)(xi / ROWS) * Mp + mrow0 + xi % ROWS;
+  }
   auto fetch = [&](int st, int c) {
-    load_to_lds(x_src + (int64_t)(c * 2) * Mp, ring + st * SU + 512 + w * 64);
+#pragma unroll
+    for (int i = 0; i < L::XLW; ++i) load_to_lds(x_src[i] + (int64_t)(c * 2) * Mp, ring + st * SU + AU + (i * WN + w) * 64);
     load_to_lds(a_src + (int64_t)c * a_step, ring + st * SU + w * 64);
   };
   // what it reads: its two weight blocks, and the rows of its row half
   const u32x4v *a_lds = ring + (w % WC) * NBW * 64 + lane;
-  const u32x4v *b_lds = ring + 512 + (lane >> 5) * ROWS + wrow + (lane & 31);
+  const u32x4v *b_lds = ring + AU + (lane >> 5) * ROWS + wrow + (lane & 31);
   f32x16 acc[NBW][MB];
 #pragma unroll
   for (int n = 0; n < NBW; ++n)
@@ -744,7 +601,7 @@ __global__ __launch_bounds__(GemmRing::T) void gemm_ring_kernel(void *out, const
       for (int r = 0; r < 16; ++r) acc[n][j][r] = 0.f;
 #pragma unroll
   for (int j = 0; j < LA; ++j) fetch(j, min(c_lo + j, last));   // a run has at least NS k-steps
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * (LA - 1)) : "memory");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPS * (LA - 1)) : "memory");
   __syncthreads();
   for (int c0 = c_lo; c0 < nchunks; c0 += NS) {
 #pragma unroll
@@ -759,7 +616,7 @@ __global__ __launch_bounds__(GemmRing::T) void gemm_ring_kernel(void *out, const
       for (int j = 0; j < MB; ++j)
 #pragma unroll
         for (int n = 0; n < NBW; ++n) acc[n][j] = mfma_h16(__builtin_bit_cast(h16x8, a[n]), __builtin_bit_cast(h16x8, b[j]), acc[n][j]);
-      asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * (LA - 1)) : "memory");
+      asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(LPS * (LA - 1)) : "memory");
     }
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the loads past the end have landed before the ring is reused
@@ -813,18 +670,18 @@ __global__ __launch_bounds__(GemmRing::T) void gemm_ring_kernel(void *out, const
   }
 }
 
-template <int EPI, bool ZFAST>
+template <int EPI, bool ZFAST, int WC = 4>
 static void gemm_ring_launch(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, hipStream_t st, int nsplit = 1) {
-  using L = GemmRing;
+  using L = GemmRingT<WC>;
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void *)gemm_ring_kernel<EPI, ZFAST>, hipFuncAttributeMaxDynamicSharedMemorySize, L::BYTES);
+    (void)hipFuncSetAttribute((const void *)gemm_ring_kernel<EPI, ZFAST, WC>, hipFuncAttributeMaxDynamicSharedMemorySize, L::BYTES);
     attr_set = true;
   }
   int nblocks = Np / 32, per_wg = L::WC * L::NBW, strips = (nblocks + per_wg - 1) / per_wg, nz = Mp / L::ROWS;
   int groups = (Kp / 16) / L::NS, gps = (groups + nsplit - 1) / nsplit, ny = (groups + gps - 1) / gps;
   dim3 grid = ZFAST ? dim3(strips * nz, ny, 1) : dim3(strips, ny, nz);
-  hipLaunchKernelGGL((gemm_ring_kernel<EPI, ZFAST>), grid, dim3(L::T), L::BYTES, st, out, (const u32x4v *)Xp, (const h16x8 *)Wp, Mp, Np, Kp, gps);
+  hipLaunchKernelGGL((gemm_ring_kernel<EPI, ZFAST, WC>), grid, dim3(L::T), L::BYTES, st, out, (const u32x4v *)Xp, (const h16x8 *)Wp, Mp, Np, Kp, gps);
 }
 
 // Launch shape.  Up to 128 batch rows the LDS-staged kernel runs: three or four weight blocks per workgroup, and a
@@ -935,7 +792,7 @@ static void gemm_dispatch(void *out, const void *Xp, const void *Wp, int Mp, int
     else gemm_ring_launch<EPI, false>(out, Xp, Wp, Mp, Np, Kp, st, g.nsplit);
     return;
   }
-  if (g.lds == 3) { gemm_wide_launch<EPI, false, 2>(out, Xp, Wp, Mp, Np, Kp, st, g.nsplit); return; }
+  if (g.lds == 3) { gemm_ring_launch<EPI, false, 2>(out, Xp, Wp, Mp, Np, Kp, st, g.nsplit); return; }
   if (g.lds) { gemm_lds_dispatch<EPI>(out, Xp, Wp, Mp, Np, Kp, g, st); return; }
   int mbt = Mp / 32;
   int MB = mbt >= 8 ? 8 : mbt;
@@ -1106,7 +963,7 @@ __global__ __launch_bounds__(256) void lmhead_kernel(const u32x4v *__restrict__ 
 }
 
 // ---- lm_head on 256 x 256 tiles (batches of 256 rows and more: scoring passes, wide decode batches) -----------------
-// The main loop of gemm_wide_kernel (four wavefronts, two weight blocks each, 256 rows, operands eight k-steps ahead),
+// A register-streaming main loop (four wavefronts, two weight blocks each, 256 rows, operands eight k-steps ahead),
 // then the sampler of the kernel above over the 2 x 8 accumulator tiles of a wavefront: parked in LDS one weight block
 // at a time (static indices, so the accumulators stay registers during the main loop) and folded in a rolled loop.
 // grid: ceil(Np/256) column strips x Mp/256 row blocks, the row blocks of a strip neighbours in launch order (the
