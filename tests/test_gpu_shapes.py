@@ -93,6 +93,41 @@ def test_decode_prefill_and_scoring_at_workload_width_and_depth(name, rows):
     ctx.close()
 
 
+# 10 weight blocks of 32 rows in the output and down projections, 74 in the gate/up projection, K = 320 and 1184 (padded to
+# 384 and 1280): no tile of the 256-row GEMMs (four or eight blocks wide) and no padded k-range divides these evenly
+RAGGED = synth.ModelShape(2, 320, 4, 2, 64, 1184, 1000)
+
+
+def test_ragged_tile_edges_of_the_256_row_gemms():
+    """Weight-block counts that are no multiple of the tile width and hidden / feed-forward widths that are no multiple of
+    the k padding, at the two row counts that take the 256-row tiles: 4096 rows in a scoring pass (256 x 256 tiles on the
+    gate/up projection, 256 x 128 on the others) and a 256-row decode step."""
+    shape = RAGGED
+    blob = _pinned_blob(shape, 5)
+    blob32 = synth.widen_to_f32(blob)
+    orc = oracle.load("f64")
+    d = oracle.desc_from_shape(shape)
+    # scoring: 8 strings of 512 tokens = one pass of 4096 rows; the oracle scores the first and the last
+    toks = np.random.default_rng(11).integers(0, shape.vocab, size=(8, 512)).astype(np.int32)
+    ctx = make_ctx(shape, 256, 512, blob)
+    got = ctx.logprobs(toks, np.full(8, 512, np.int32), 1.0)
+    for i in (0, 7):
+        want = orc.logprobs(d, blob32, toks[i], 1.0)
+        err = float(np.abs(got[i] - want).max())
+        assert err < BF16_LOGPROB_TOL, (i, err)
+    # decode: 32 prompts x 8 = 256 rows, teacher-forced; the oracle follows the first and the last sequence
+    G, P, plen, new = 8, 32, 24, 5
+    prompts, lens = synth.make_prompts(shape.vocab, P, plen, seed=6)
+    forced = np.random.default_rng(7).integers(0, shape.vocab, size=(P * G, new)).astype(np.int32)
+    tf = ctx.rollout(prompts, lens, G, new, 1.0, 2, forced=forced, want_logits=True)
+    for n, pidx in ((0, 0), (P * G - 1, P - 1)):
+        ref = orc.rollout(d, blob32, prompts[pidx:pidx + 1], lens[pidx:pidx + 1], G=1, max_new=new, temperature=1.0, seed=2,
+                          want_logits=True, forced=forced[n:n + 1])
+        err = float(np.abs(tf["logits"][n] - ref["logits"][0]).max())
+        assert err < BF16_LOGIT_TOL, (n, err)
+    ctx.close()
+
+
 @pytest.mark.parametrize("hd", [64, 128])
 def test_tied_embeddings_and_qk_norm_on_the_decode_path(hd):
     """Gains drawn away from 1 (a dropped or misplaced gain shows), lm_head = embedding table, per-head q/k norm; ragged
