@@ -836,8 +836,16 @@ template <int MB> struct LmLds {   // epilogue of the 256-row kernel: accumulato
   static constexpr int BYTES = LM_WN * DUMP_PER_WAVE + LM_WN * MB * 32 * (int)sizeof(SampleAcc);
 };
 
+// The vocabulary takes several rounds of workgroups (1187 for 151936 rows on 256 compute units), and a workgroup's
+// sampler epilogue moves no weights.  With two workgroups resident per compute unit one's epilogue and first loads run
+// under the other's weight stream: 64 rows 199 -> 146 us, 32 rows 158 -> 133 us, 128 rows (sampler) 306 -> 280 us.  That
+// needs the kernel inside 256 registers per lane, which a two-chunk weight pipeline allows (three chunks in flight
+// fit only at 32 rows; the 128-row forms spill a little, and the 128-row logits form, which has no long epilogue to
+// hide, is faster alone on the unit with its three-chunk pipeline).
+template <int MB, bool LOGITS> constexpr int lm_wgs_per_cu() { return MB <= 2 || (MB == 4 && !LOGITS) ? 2 : 1; }
+
 template <int MB, int NSTAGE, bool LOGITS>
-__global__ __launch_bounds__(256) void lmhead_kernel(const u32x4v *__restrict__ Xp, const h16x8 *__restrict__ Wp, int Mp,
+__global__ __launch_bounds__(256, (lm_wgs_per_cu<MB, LOGITS>())) void lmhead_kernel(const u32x4v *__restrict__ Xp, const h16x8 *__restrict__ Wp, int Mp,
                                                      int Np, int Kp, int V, float temperature, uint64_t seed,
                                                      DrawIds ids, const int32_t *target, float *target_z,
                                                      float *part, int n_wg, float *logits, int64_t ld) {
@@ -1179,8 +1187,8 @@ static void lmhead_dispatch(const void *Xp, const void *Wp, int Mp, int Np, int 
   int mbt = Mp / 32;
 #define LM_ARGS Xp, Wp, Mp, Np, Kp, V, temperature, seed, ids, target, target_z, part, logits, ld, st
   if (mbt >= 8) lmhead_launch<8, 2, LOGITS>(LM_ARGS);
-  else if (mbt == 4) lmhead_launch<4, 3, LOGITS>(LM_ARGS);
-  else if (mbt == 2) lmhead_launch<2, 3, LOGITS>(LM_ARGS);
+  else if (mbt == 4) lmhead_launch<4, LOGITS ? 3 : 2, LOGITS>(LM_ARGS);
+  else if (mbt == 2) lmhead_launch<2, 2, LOGITS>(LM_ARGS);
   else lmhead_launch<1, 3, LOGITS>(LM_ARGS);
 #undef LM_ARGS
 }
