@@ -731,7 +731,20 @@ void fast_gemm_pick(int Np, int Kp, int Mp, int full_k, GemmShape *g) {
     const bool wide = Mp > 128;   // 256 batch rows per workgroup, Mp/256 workgroups per weight strip
     int total_chunks = ksteps / (wide ? GEMM_KC_WIDE : GEMM_KC_SMALL);
     g->lds = 1; g->nbw = 1; g->waves_k = 1;
-    if (full_k && !wide) { g->waves_n = 3; g->stages = 3; g->nsplit = 1; return; }
+    if (full_k && !wide) {
+      // No split over K (the SwiGLU epilogue needs whole sums), one workgroup per compute unit at a time: the launch takes
+      // rounds x width, rounds = ceil(workgroups / 256).  The width with the smallest product wins, the wider one on a
+      // tie (fewer rounds, fewer re-reads of the activations).  Measured at 64 rows: 608 blocks (4B) width 3, 203
+      // workgroups, 21 us (width 4: 23); 768 blocks (8B) width 3, 256 workgroups, 34 us; 1600 blocks (32B) width 7,
+      // 229 workgroups, 81 us -- width 3 (534 workgroups, three rounds) took 109 us there, width 4 (two rounds) 90.
+      int best = 3, best_cost = 1 << 30;
+      for (int wn = 3; wn <= 8; ++wn) {
+        int wgs = (nblocks + wn - 1) / wn, cost = (wgs + 255) / 256 * wn;
+        if (cost <= best_cost) { best = wn; best_cost = cost; }
+      }
+      g->waves_n = best; g->stages = best == 3 ? 3 : 2; g->nsplit = 1;
+      return;
+    }
     g->waves_n = wide || nblocks % 4 == 0 || nblocks > 96 ? 4 : 3;
     g->stages = 2;   // deeper register pipelines measured no faster once the wait counts are exact
     int strips = (nblocks + g->waves_n - 1) / g->waves_n * (wide ? Mp / 256 : 1);
@@ -778,7 +791,11 @@ static void gemm_lds_dispatch(void *out, const void *Xp, const void *Wp, int Mp,
   if (mb >= 8) { gemm_lds_launch<8, 4, 2, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st); return; }
 #define LDS_CASE(MBV)                                                                                              \
   if (g.waves_n == 3) gemm_lds_launch<MBV, 3, 3, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st);                      \
-  else gemm_lds_launch<MBV, 4, 2, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st)
+  else if (g.waves_n == 4 || EPI == EPI_PARTIAL) gemm_lds_launch<MBV, 4, 2, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st);  \
+  else if (g.waves_n == 5) gemm_lds_launch<MBV, 5, 2, EPI_SWIGLU>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st);         \
+  else if (g.waves_n == 6) gemm_lds_launch<MBV, 6, 2, EPI_SWIGLU>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st);         \
+  else if (g.waves_n == 7) gemm_lds_launch<MBV, 7, 2, EPI_SWIGLU>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st);         \
+  else gemm_lds_launch<MBV, 8, 2, EPI_SWIGLU>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st)
   if (mb == 1) { LDS_CASE(1); }
   else if (mb == 2) { LDS_CASE(2); }
   else { LDS_CASE(4); }
