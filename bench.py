@@ -26,7 +26,7 @@ ATTN_TRAFFIC_OVER_TILE_BYTES = (29307.0 + 512.0) / (28608.0 + 512.0)
 # per launch (profiles/kernel_trace_dense4b-64x512+1024.md): the HIP events of the timed run bracket launches that are issued
 # one by one and include the launch gap, so both figures go into the line.  None for any other workload, and whenever the
 # kernel changes.
-ATTN_KERNEL_TRACE_US = {"dense4b-64x512+1024": 34.86}
+ATTN_KERNEL_TRACE_US = {"dense4b-64x512+1024": 34.71}
 
 
 def attn_kv_bytes_per_launch(shape, gen_lens, prompt_len, group, steps, whole_tiles, shared_elsewhere=False):
