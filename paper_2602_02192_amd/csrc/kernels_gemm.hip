@@ -744,7 +744,8 @@ void fast_gemm_pick(int Np, int Kp, int Mp, int full_k, GemmShape *g) {
       // workgroups, 21 us (width 4: 23); 768 blocks (8B) width 3, 256 workgroups, 34 us; 1600 blocks (32B) width 7,
       // 229 workgroups, 81 us -- width 3 (534 workgroups, three rounds) took 109 us there, width 4 (two rounds) 90.
       int best = 3, best_cost = 1 << 30;
-      for (int wn = 3; wn <= 8; ++wn) {
+      const int wn_max = Mp <= 64 ? 8 : 4;   // 128 rows: more than four wavefronts would not fit their registers
+      for (int wn = 3; wn <= wn_max; ++wn) {
         int wgs = (nblocks + wn - 1) / wn, cost = (wgs + 255) / 256 * wn;
         if (cost <= best_cost) { best = wn; best_cost = cost; }
       }
@@ -791,22 +792,31 @@ static void gemm_lds_launch(void *out, const void *Xp, const void *Wp, int Mp, i
                      Np, Kp, cps);
 }
 
+// The instantiated forms: three blocks with the three-chunk weight pipeline (two chunks at 64 rows), four blocks with two
+// chunks, and for the full-K projection at up to 64 rows five to eight blocks with two chunks (see fast_gemm_pick).
+template <int MB, int EPI>
+static void gemm_lds_dispatch_rows(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, GemmShape g, hipStream_t st) {
+  if (g.waves_n == 3 && g.stages == 2) { gemm_lds_launch<MB, 3, 2, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st); return; }
+  if (g.waves_n == 3) { gemm_lds_launch<MB, 3, 3, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st); return; }
+  if constexpr (EPI == EPI_SWIGLU && MB <= 2) {
+    switch (g.waves_n) {
+      case 5: gemm_lds_launch<MB, 5, 2, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st); return;
+      case 6: gemm_lds_launch<MB, 6, 2, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st); return;
+      case 7: gemm_lds_launch<MB, 7, 2, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st); return;
+      case 8: gemm_lds_launch<MB, 8, 2, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st); return;
+      default: break;
+    }
+  }
+  gemm_lds_launch<MB, 4, 2, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st);
+}
+
 template <int EPI>
 static void gemm_lds_dispatch(void *out, const void *Xp, const void *Wp, int Mp, int Np, int Kp, GemmShape g, hipStream_t st) {
   int mb = Mp / 32;   // 1, 2, 4 or a multiple of 8
-  if (mb >= 8) { gemm_lds_launch<8, 4, 2, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st); return; }
-#define LDS_CASE(MBV)                                                                                              \
-  if (g.waves_n == 3 && g.stages == 2) gemm_lds_launch<MBV, 3, 2, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st);     \
-  else if (g.waves_n == 3) gemm_lds_launch<MBV, 3, 3, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st);                 \
-  else if (g.waves_n == 4 || EPI == EPI_PARTIAL) gemm_lds_launch<MBV, 4, 2, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st);  \
-  else if (g.waves_n == 5) gemm_lds_launch<MBV, 5, 2, EPI_SWIGLU>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st);         \
-  else if (g.waves_n == 6) gemm_lds_launch<MBV, 6, 2, EPI_SWIGLU>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st);         \
-  else if (g.waves_n == 7) gemm_lds_launch<MBV, 7, 2, EPI_SWIGLU>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st);         \
-  else gemm_lds_launch<MBV, 8, 2, EPI_SWIGLU>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st)
-  if (mb == 1) { LDS_CASE(1); }
-  else if (mb == 2) { LDS_CASE(2); }
-  else { LDS_CASE(4); }
-#undef LDS_CASE
+  if (mb >= 8) gemm_lds_launch<8, 4, 2, EPI>(out, Xp, Wp, Mp, Np, Kp, g.nsplit, st);
+  else if (mb == 1) gemm_lds_dispatch_rows<1, EPI>(out, Xp, Wp, Mp, Np, Kp, g, st);
+  else if (mb == 2) gemm_lds_dispatch_rows<2, EPI>(out, Xp, Wp, Mp, Np, Kp, g, st);
+  else gemm_lds_dispatch_rows<4, EPI>(out, Xp, Wp, Mp, Np, Kp, g, st);
 }
 
 template <int EPI>
