@@ -3,7 +3,8 @@
 The oracle cannot afford the 8B- and 32B-class models whole, so each is cut one way at a time: full width (hidden size,
 head grouping, feed-forward width, vocabulary 151936) at two layers, and full depth (64 layers) on a narrow model with
 the 32B-class head grouping (8 query heads per key/value head, head_dim 128) and the full vocabulary.  Every case runs
-in the batch sizes of its workload (64 and 128 rows); the oracle computes the first and the last sequence of the batch.
+in the batch sizes of its workload (64 and 128 rows; the 32B width also at 32 rows, where the gate/up projection takes its
+widest workgroups); the oracle computes the first and the last sequence of the batch.
 Also here: tied embeddings and per-head q/k norm on the decode path, operands beyond the half-precision range, and
 snapshots installed back to back while a rollout keeps switching."""
 import functools
@@ -56,7 +57,7 @@ def _case(name):
     return shape, blob, prompts, lens, refs, scores
 
 
-@pytest.mark.parametrize("name,rows", [("8b", 64), ("8b", 128), ("32b", 64), ("32b", 128), ("deep", 64)])
+@pytest.mark.parametrize("name,rows", [("8b", 64), ("8b", 128), ("32b", 64), ("32b", 128), ("32b", 32), ("deep", 64)])
 def test_decode_prefill_and_scoring_at_workload_width_and_depth(name, rows):
     shape, blob, prompts16, lens16, refs, scores = _case(name)
     G, P = 8, rows // 8
