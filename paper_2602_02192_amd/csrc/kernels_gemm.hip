@@ -692,8 +692,11 @@ static void gemm_ring_launch(void *out, const void *Xp, const void *Wp, int Mp, 
 
 // Launch shape.  Up to 128 batch rows the LDS-staged kernel runs: three or four weight blocks per workgroup, and a
 // grid split over K that brings the launch to about one workgroup per compute unit (partials cost HBM writes, so
-// no more than that); a GEMM whose epilogue needs the whole K (SwiGLU) is not split.  Larger batches keep the
-// register-streaming kernel: waves_k wavefronts of a workgroup share a block's k-steps and are summed in LDS.
+// no more than that); a GEMM whose epilogue needs the whole K (SwiGLU) is not split and takes the workgroup width
+// (three to eight blocks) that needs the fewest rounds of the chip.  Batches that are a multiple of 256 rows take the
+// LDS-ring kernel (256 x 256 tiles when those fill the chip, 256 x 128 tiles with a split over K otherwise).  Shapes
+// that fit neither (K not padded, odd row counts) keep the plain register-streaming kernel: waves_k wavefronts of a
+// workgroup share a block's k-steps and are summed in LDS.
 // The largest split count <= nsplit that the 256 x 128-tile kernel realises exactly: it cuts K into runs of
 // ceil(groups / nsplit) groups of eight k-steps, which may come to fewer runs than asked for.
 int fast_gemm_even_split(int Kp, int nsplit) {
