@@ -559,7 +559,6 @@ template <int WCv> struct GemmRingT {   // WC = 4: 256 x 256 tile, eight wavefro
   static constexpr int NS = 8, LA = 6;                                    // stages, k-steps ahead (< NS)
   static constexpr int TILE_STRIDE = 33, BYTES = NS * SU * 16;            // 128 KB / 96 KB; the epilogue's WN x 32 x 33 floats reuse it
 };
-using GemmRing = GemmRingT<4>;
 
 __device__ __forceinline__ void load_to_lds(const void *g, void *l) {   // 16 bytes per lane; l is the wavefront's base, lane l lands at l + 16 l
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g, (__attribute__((address_space(3))) void *)l, 16, 0, 0);
