@@ -129,6 +129,26 @@ def test_ragged_tile_edges_of_the_256_row_gemms():
     ctx.close()
 
 
+# 17 strips of 256 columns in the output and down projections with K = 6144: at 4096 rows that is 272 tiles of 256 x 256 on
+# 256 compute units, the case in which the GEMM splits K in two runs and the reducing kernel sums two planes
+KSPLIT = synth.ModelShape(1, 4352, 48, 12, 128, 6144, 2048)
+
+
+def test_k_split_of_the_4096_row_gemm():
+    shape = KSPLIT
+    blob = _pinned_blob(shape, 8)
+    blob32 = synth.widen_to_f32(blob)
+    orc = oracle.load("f64")
+    d = oracle.desc_from_shape(shape)
+    toks = np.random.default_rng(12).integers(0, shape.vocab, size=(8, 512)).astype(np.int32)
+    ctx = make_ctx(shape, 8, 512, blob)
+    got = ctx.logprobs(toks, np.full(8, 512, np.int32), 1.0)
+    want = orc.logprobs(d, blob32, toks[5], 1.0)
+    err = float(np.abs(got[5] - want).max())
+    assert err < BF16_LOGPROB_TOL, err
+    ctx.close()
+
+
 @pytest.mark.parametrize("hd", [64, 128])
 def test_tied_embeddings_and_qk_norm_on_the_decode_path(hd):
     """Gains drawn away from 1 (a dropped or misplaced gain shows), lm_head = embedding table, per-head q/k norm; ragged
