@@ -149,6 +149,27 @@ def test_k_split_of_the_4096_row_gemm():
     ctx.close()
 
 
+def test_k_split_of_the_256_row_gemm():
+    """A 256-row decode step whose projections are few 256 x 128 tiles with K = 2048: the launch splits K in four runs and
+    the reducing kernels sum four planes."""
+    shape = synth.ModelShape(1, 2048, 16, 4, 128, 2048, 2048)
+    blob = _pinned_blob(shape, 9)
+    blob32 = synth.widen_to_f32(blob)
+    orc = oracle.load("f64")
+    d = oracle.desc_from_shape(shape)
+    G, P, plen, new = 8, 32, 40, 4
+    prompts, lens = synth.make_prompts(shape.vocab, P, plen, seed=10)
+    forced = np.random.default_rng(13).integers(0, shape.vocab, size=(P * G, new)).astype(np.int32)
+    ctx = make_ctx(shape, P * G, plen + new + 20, blob)
+    tf = ctx.rollout(prompts, lens, G, new, 1.0, 2, forced=forced, want_logits=True)
+    for n, pidx in ((0, 0), (P * G - 1, P - 1)):
+        ref = orc.rollout(d, blob32, prompts[pidx:pidx + 1], lens[pidx:pidx + 1], G=1, max_new=new, temperature=1.0, seed=2,
+                          want_logits=True, forced=forced[n:n + 1])
+        err = float(np.abs(tf["logits"][n] - ref["logits"][0]).max())
+        assert err < BF16_LOGIT_TOL, (n, err)
+    ctx.close()
+
+
 @pytest.mark.parametrize("hd", [64, 128])
 def test_tied_embeddings_and_qk_norm_on_the_decode_path(hd):
     """Gains drawn away from 1 (a dropped or misplaced gain shows), lm_head = embedding table, per-head q/k norm; ragged
