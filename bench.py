@@ -145,6 +145,8 @@ def main():
                          "the rows of a draining batch are compacted)")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch decode steps kernel by kernel (counter collection cannot follow graph replays)")
+    ap.add_argument("--prefix-kernel", type=int, default=0, choices=[0, 1, 2, 3],
+                    help="echo_rollout_opts.prefix_kernel: who attends a group's shared prompt tiles (0 = the planner decides)")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py measures one GPU: rollout workers are independent (data parallel over prompts) and "
@@ -194,6 +196,7 @@ def main():
         """One rollout; with a swap schedule a second thread installs the next snapshot (alternating two weight
         sets) as soon as the previous one has been switched in, as a worker's receiver thread would."""
         kw.setdefault("top_p", wl.get("top_p", 1.0))
+        kw.setdefault("prefix_kernel", a.prefix_kernel)
         if not swaps:
             return ctx.rollout(prompts, lens, G, max_new, 1.0, seed, stop_lens=stop, no_graph=a.no_graph, continuous=continuous, **kw)
         import threading

@@ -90,8 +90,10 @@ typedef struct {
   int32_t own_prompt_copy;     /* 1: every sequence reads its own replicated copy of its group's prompt K/V instead of
                                   the copy in the group's first cache slot (bit-identical results) */
   int32_t prefix_kernel;       /* who attends a group's shared whole prompt tiles: 0 = the planner decides by batch size,
-                                  1 = always each row in the decode kernel, 2 = always the once-per-group kernel where it
-                                  applies (a row's keys not split over workgroups); the two differ by summation order */
+                                  1 = always each row on its own in the decode kernel, 2 = always the once-per-group kernel
+                                  where it applies (a row's keys not split over workgroups), 3 = always decode workgroups
+                                  that take several neighbouring rows and their common prompt tiles once; the forms differ
+                                  by summation order */
 } echo_rollout_opts;
 
 typedef struct {

@@ -46,7 +46,7 @@ struct Plan {
   int Np_qkv, Np_d, Np_gu, Np_v, Kp_d, Kp_q, Kp_f;
   size_t slot_bytes, o_slot[2], o_kv, kv_bytes;
   size_t o_h, o_x, o_qkv, o_att, o_gu, o_ff, o_logits, o_q16, o_xa, o_xatt, o_xff, o_part, o_rope, o_lmpart;
-  size_t o_attn_o, o_attn_ml, o_topp, o_pjobs;
+  size_t o_attn_o, o_attn_ml, o_topp, o_pjobs, o_aplan;
   size_t o_blocks, o_rows, o_seq, o_samp, o_out_tok, o_out_lp, o_out_ver, o_forced, o_scal, o_first_h, o_stage, o_maps;
   size_t stage_bytes, part_floats, logit_rows = 0, total;
   int attn_chunk, attn_max_splits;
@@ -147,6 +147,7 @@ Plan make_plan(const echo_model_desc *d) {
   p.o_blocks = b.take(M * sizeof(PrefillBlock));   // at worst every row of a pass is a block of its own
   p.o_topp = b.take(fast_topp_scratch_floats((int)pad_rows(d->max_seqs)) * 4);
   p.o_pjobs = b.take((pad_rows(d->max_seqs) / 2 + 1) * sizeof(PrefixJob));   // a job has at least two rows
+  p.o_aplan = b.take(fast_attention_plan_ints(pad_rows(d->max_seqs)) * 4);   // tile lists of the several-rows decode attention
   p.o_rows = b.take(6 * M * 4);
   p.o_maps = b.take(2 * M * 4 + (size_t)d->max_seqs * 4);
   p.o_seq = b.take(4 * (size_t)pad_rows(d->max_seqs) * 4);   // samplers read the step and stream of padding rows too
@@ -219,6 +220,7 @@ struct echo_ctx {
   bool timing = false;
   std::vector<float> step_ms;   // per-step durations of the last rollout run with time_steps
   bool attn_plain = false;   // cross-check switch of the running rollout (echo_rollout_opts.attn_plain)
+  int attn_mode = 0;         // echo_rollout_opts.prefix_kernel of the running rollout
   double t_attn_bytes = 0, t_gemm_bytes = 0, cur_attn_bytes = 0;
 };
 
@@ -353,6 +355,9 @@ void forward_layers(echo_ctx *c, const Slot &S, int M, bool use_splitk_attn, int
   void *xa = at<void>(c, p.o_xa), *xatt = at<void>(c, p.o_xatt), *xff = at<void>(c, p.o_xff), *q16 = at<void>(c, p.o_q16);
   float *part = at<float>(c, p.o_part);
   fast_resid_norm(h, S.embed, c->rows.token, nullptr, 0, p.Np_d, xa, S.layers[0].attn_norm, M, Mp, H, d.rms_eps, st);
+  // decode attention over several rows per workgroup: the tile lists are the same for every layer
+  const int att_rows = n_prefill_blocks == 0 && use_splitk_attn && c->px.n_jobs == 0 ? fast_attention_rows_per_group(M, Hq, Hkv, c->attn_mode) : 1;
+  if (att_rows > 1) fast_attention_rows_plan(at<int32_t>(c, p.o_aplan), c->rows, M, Hq, Hkv, att_rows, st);
   for (int l = 0; l < d.n_layers; ++l) {
     const LayerW &L = S.layers[l];
     gemm_fast(c, part, xa, L.wqkv, Mp, p.Np_qkv, p.Kp_d, EPI_PARTIAL, &ns);
@@ -363,6 +368,8 @@ void forward_layers(echo_ctx *c, const Slot &S, int M, bool use_splitk_attn, int
       TimerScope t(c, &c->ev_attn);
       if (n_prefill_blocks > 0)
         fast_attention_prefill(xatt, q16, at<PrefillBlock>(c, p.o_blocks), n_prefill_blocks, c->kv, l, Mp, Hq, Hkv, st);
+      else if (att_rows > 1)
+        fast_attention_rows(xatt, q16, at<int32_t>(c, p.o_aplan), c->kv, l, M, Mp, Hq, Hkv, att_rows, st);
       else if (use_splitk_attn)
         fast_attention(xatt, q16, c->rows, c->kv, l, M, Mp, Hq, Hkv, fast_attention_splits(M, Hkv, p.attn_max_splits),
                        at<float>(c, p.o_attn_o), at<float>(c, p.o_attn_ml), c->px, st);

@@ -46,6 +46,7 @@ int plan_prefix_jobs(echo_ctx *c, std::vector<int32_t> &ptiles, const std::vecto
   c->px = PrefixPlan{at<PrefixJob>(c, c->p.o_pjobs), 0, 0, 1};
   for (int r = 0; r < R; ++r) ptiles[r] &= ~ATT_PREFIX_DONE;
   if (!c->p.fast || max_ptiles < 1 || fast_attention_splits(R, c->d.n_kv_heads, c->p.attn_max_splits) != 1 || prefix_kernel == 1) return 0;
+  if (fast_attention_rows_per_group(R, c->d.n_q_heads, c->d.n_kv_heads, c->attn_mode) > 1) return 0;   // the decode kernel shares the tiles itself
   std::vector<PrefixJob> jobs;
   std::vector<int> order(R);
   for (int r = 0; r < R; ++r) order[r] = r;
@@ -70,10 +71,10 @@ int plan_prefix_jobs(echo_ctx *c, std::vector<int32_t> &ptiles, const std::vecto
     }
     i = j;
   }
-  // The extra launch costs more than it saves at 64 rows x 16 tiles (measured: -7 % there; +1 % at 256 x 16, -2 % at a
-  // draining 128 x 32, +5 % at 256 x 32), so small batches with short prompts keep reading their shared tiles in the
-  // decode kernel.
-  int64_t covered = 0, min_covered = prefix_kernel == 2 ? 0 : 6144;
+  // The extra launch costs more than it saves at 64 rows x 16 tiles (measured: -7 % there; -2 % at a draining 128 x 32,
+  // +5 % at 256 x 32), so small batches with short prompts keep reading their shared tiles in the decode kernel.  A
+  // batch that is refilled as sequences end (grid_jobs > 0) keeps 256 rows of unequal lengths in flight: +9 % at 256 x 16.
+  int64_t covered = 0, min_covered = prefix_kernel == 2 ? 0 : grid_jobs > 0 ? 4096 : 6144;
   for (const PrefixJob &jb : jobs) covered += (int64_t)jb.nrows * jb.ptiles;
   if (jobs.empty() || (int)jobs.size() > cap || covered < min_covered) {
     for (int r = 0; r < R; ++r) ptiles[r] &= ~ATT_PREFIX_DONE;
@@ -106,7 +107,7 @@ int check_rollout_args(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt
   if (P < 1 || G < 1 || max_new < 1 || prompt_stride < 1) return fail(c, ECHO_EINVAL, "n_prompts, G, max_new and prompt_stride must be positive");
   if (!(temperature > 0.f)) return fail(c, ECHO_EINVAL, "temperature must be positive");
   if (!(o->top_p > 0.f) || o->top_p > 1.0f) return fail(c, ECHO_EINVAL, "top_p must be in (0, 1]");
-  if (o->prefix_kernel < 0 || o->prefix_kernel > 2) return fail(c, ECHO_EINVAL, "prefix_kernel must be 0, 1 or 2");
+  if (o->prefix_kernel < 0 || o->prefix_kernel > 3) return fail(c, ECHO_EINVAL, "prefix_kernel must be 0, 1, 2 or 3");
   if ((int64_t)P * G * max_new > INT32_MAX) return fail(c, ECHO_EINVAL, "n_prompts * G * max_new exceeds 2^31 - 1");
   int max_pl = 0;
   for (int p = 0; p < P; ++p) {
@@ -148,6 +149,7 @@ struct RolloutGuard {
     std::lock_guard<std::mutex> lk(c->mu);
     c->rollout_running = false;
     c->attn_plain = false;
+    c->attn_mode = 0;
     c->ids = DrawIds{c->d_step, nullptr, nullptr};
     c->px.n_jobs = 0;
     if (c->staged >= 0) {   // (a rollout that failed half-way may have left work queued on the old slot)
@@ -215,6 +217,7 @@ int echo_rollout(echo_ctx *c, const int32_t *prompt_tokens, int32_t prompt_strid
 
   int cur = c->active;
   c->attn_plain = o.attn_plain != 0;
+  c->attn_mode = o.prefix_kernel;
   const bool share_prefix = p.fast && !o.own_prompt_copy && !o.attn_plain;
   // ---- prefill the P unique prompts into cache slots p*G, keep each prompt's last hidden state
   std::vector<int> lens(prompt_lens, prompt_lens + P);
@@ -456,6 +459,9 @@ int echo_rollout_continuous(echo_ctx *c, const int32_t *prompt_tokens, int32_t p
   const bool unfused = o.unfused_sampler || o.top_p < 1.0f;
   const bool use_graph = !o.no_graph;
   c->attn_plain = o.attn_plain != 0;
+  // rows of unequal lengths: workgroups of several rows, one per compute unit, would finish at very different times
+  // (measured 22.7 k tokens/s against 25.5 k with the once-per-group kernel at 256 rows), so only on request
+  c->attn_mode = o.prefix_kernel == 0 ? 1 : o.prefix_kernel;
   const bool share_prefix = p.fast && !o.own_prompt_copy && !o.attn_plain;
   const bool splitk = !o.attn_plain;
   const int R = std::min(N, c->d.max_seqs);   // cache slots in use; rows of the batch until the rows are compacted

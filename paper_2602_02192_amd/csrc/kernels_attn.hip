@@ -442,6 +442,278 @@ static void attention_launch(void *Xp_out, const void *q_h16, RowState rows, KvG
   }
 }
 
+// ---- several rows of the batch per workgroup ---------------------------------------------------------------------
+// A decode batch with more (row, KV head) pairs than the chip has room for at once gives every compute unit several of them
+// anyway; a workgroup of eight wavefronts that takes R consecutive rows (R * grp <= 32 MFMA columns, column = row * grp +
+// head) can then take the whole prompt tiles that rows of one group have in common once for all of them: the tile is
+// loaded and multiplied once, every column keeps its own softmax state.  A row's remaining tiles follow with the other
+// rows' columns masked.  What a workgroup walks is a list of segments of whole tiles (cache slot, first tile, columns,
+// number of valid keys) that attn_rows_plan_kernel writes once per decode step from the row state -- the list is the
+// same for every layer and KV head.  Lane i of every wavefront holds segment i, so finding the segment of a tile is a
+// ballot and a few lane reads, with no memory access on the way to the tile's address.  The wavefronts take the
+// workgroup's tiles in turn, one K and one V register tile each, exactly as in attn_splitk_kernel.
+constexpr int ATT_ROWS_MAX = 8;            // rows per workgroup at most
+constexpr int ATT_ROWS_WAVES = 8;
+constexpr int ATT_SEG_MAX = 24;            // runs of rows with a common prompt (<= R/2) + two segments per row
+constexpr int ATT_SEG_INTS = 8;            // cache slot, first tile, first and end position in the workgroup's tile list, first and end column, valid keys, tiles in all
+constexpr int ATT_PLAN_INTS = ATT_SEG_MAX * ATT_SEG_INTS;
+
+// grid (workgroups of the attention launch), block 64.
+__global__ void attn_rows_plan_kernel(int32_t *__restrict__ plan, RowState rows, int M, int grp, int R) {
+  __shared__ int32_t f[ATT_ROWS_MAX][5];   // active, prompt slot, whole prompt tiles, keys, slot
+  const int gi = blockIdx.x, m0 = gi * R, t = threadIdx.x;
+  if (t < R) {
+    const int m = m0 + t;
+    const bool val = m < M && rows.active[m] != 0;
+    f[t][0] = val;
+    f[t][1] = val ? rows.pslot[m] : 0;
+    f[t][2] = val ? (rows.ptiles[m] & ~ATT_PREFIX_DONE) : 0;
+    f[t][3] = val ? rows.pos[m] + 1 : 0;
+    f[t][4] = val ? rows.slot[m] : 0;
+  }
+  __syncthreads();
+  if (t != 0) return;
+  int32_t *seg = plan + (int64_t)gi * ATT_PLAN_INTS;
+  int ns = 0, v = 0;
+  auto emit = [&](int slot, int tile0, int n, int c0, int c1, int keys) {
+    int32_t *s = seg + ns * ATT_SEG_INTS;
+    s[0] = slot; s[1] = tile0; s[2] = v; s[3] = v + n; s[4] = c0; s[5] = c1; s[6] = keys; s[7] = 0;
+    v += n;
+    ++ns;
+  };
+  for (int r = 0; r < R;) {
+    if (!f[r][0]) { ++r; continue; }
+    const int ps = f[r][1], pt = f[r][2];
+    int r2 = r + 1, full = f[r][3] / ATT_TILE;
+    while (r2 < R && f[r2][0] && f[r2][1] == ps && f[r2][2] == pt) { full = min(full, f[r2][3] / ATT_TILE); ++r2; }
+    const int sh = r2 - r >= 2 ? min(pt, full) : 0;   // whole tiles that every row of the run reads from the same slot
+    if (sh > 0) emit(ps, 0, sh, r * grp, r2 * grp, 0x7fffffff);
+    for (int rr = r; rr < r2; ++rr) {
+      const int nk = f[rr][3], nt = (nk + ATT_TILE - 1) / ATT_TILE;
+      int a = sh;
+      const int b = min(pt, nt);
+      if (b > a) { emit(ps, a, b - a, rr * grp, (rr + 1) * grp, nk); a = b; }   // prompt tiles the row reads alone
+      if (nt > a) emit(f[rr][4], a, nt - a, rr * grp, (rr + 1) * grp, nk);
+    }
+    r = r2;
+  }
+  for (int i = ns; i < ATT_SEG_MAX; ++i) {   // unused entries lie beyond every tile
+    int32_t *s = seg + i * ATT_SEG_INTS;
+    s[0] = 0; s[1] = 0; s[2] = 0x7fffffff; s[3] = 0x7fffffff; s[4] = 0; s[5] = 0; s[6] = 0; s[7] = 0;
+  }
+  seg[7] = v;   // tiles of the workgroup in all
+}
+
+template <int HD> struct AttRowsLds {
+  static constexpr int Q_BYTES = 32 * HD * 2;
+  // per wavefront: O^T of its columns as [head dim][ncols + 1] floats (the odd stride spreads a store over the banks), then m[32], l[32]
+  __host__ __device__ static int merge_per_wave(int ncols) { return HD * (ncols + 1) * 4 + 256; }
+  __host__ __device__ static int total(int ncols) { return Q_BYTES + ATT_ROWS_WAVES * merge_per_wave(ncols); }
+};
+
+// grid (1, Hkv, ceil(M / R)), block 512.
+template <int HD>
+__global__ __launch_bounds__(ATT_ROWS_WAVES * 64) void attn_rows_kernel(uint16_t *__restrict__ Xp, int Mp, const uint16_t *__restrict__ q_h16,
+                                                                       const int32_t *__restrict__ plan, KvGeom kv, int layer, int Hq, int Hkv,
+                                                                       int M, int R) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  using L = AttRowsLds<HD>;
+  constexpr int KS = HD / 16, NE = HD / 32, NW = ATT_ROWS_WAVES;
+  const int kvh = blockIdx.y, gi = blockIdx.z, m0 = gi * R, grp = Hq / Hkv, ncols = R * grp;
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
+
+  // lane i holds segment i of the workgroup's list
+  int sg_slot = 0, sg_tile0 = 0, sg_v0 = 0x7fffffff, sg_v1 = 0x7fffffff, sg_c0 = 0, sg_c1 = 0, sg_keys = 0, sg_total = 0;
+  if (lane < ATT_SEG_MAX) {
+    const int4 *sp = (const int4 *)(plan + ((int64_t)gi * ATT_SEG_MAX + lane) * ATT_SEG_INTS);
+    const int4 a = sp[0], b = sp[1];
+    sg_slot = a.x; sg_tile0 = a.y; sg_v0 = a.z; sg_v1 = a.w; sg_c0 = b.x; sg_c1 = b.y; sg_keys = b.z; sg_total = b.w;
+  }
+  const int V = __builtin_amdgcn_readfirstlane(sg_total);
+  const int64_t head_units = (int64_t)HD * 8;   // 16-byte units per tile (K then V)
+  const v4u *cache = (const v4u *)kv.base;
+  const int64_t lk_off = ((int64_t)layer * kv.layer_stride() + (int64_t)kvh * 2 * kv.head_stride()) / 8;   // in 16-byte units
+  const int64_t slot_units = kv.slot_stride() / 8;
+
+  struct Loc { const v4u *tile; int tile_idx, c0, c1, keys; };
+  auto locate = [&](int v) {
+    const int s = __popcll(__ballot(sg_v1 <= v));   // segments that end at or before v: the index of v's segment
+    Loc l;
+    const int slot = __builtin_amdgcn_readlane(sg_slot, s);
+    l.tile_idx = __builtin_amdgcn_readlane(sg_tile0, s) + v - __builtin_amdgcn_readlane(sg_v0, s);
+    l.c0 = __builtin_amdgcn_readlane(sg_c0, s);
+    l.c1 = __builtin_amdgcn_readlane(sg_c1, s);
+    l.keys = __builtin_amdgcn_readlane(sg_keys, s);
+    l.tile = cache + (int64_t)slot * slot_units + lk_off + (int64_t)l.tile_idx * head_units + lane;
+    return l;
+  };
+  v4u rk[KS], rv[KS];
+  auto issue_k = [&](const Loc &l) {
+#pragma unroll
+    for (int i = 0; i < KS; ++i) rk[i] = __builtin_nontemporal_load(l.tile + i * 64);
+  };
+  auto issue_v = [&](const Loc &l) {
+#pragma unroll
+    for (int i = 0; i < KS; ++i) rv[i] = __builtin_nontemporal_load(l.tile + HD * 4 + i * 64);
+  };
+  int v = w;
+  Loc cur = locate(v < V ? v : 0), nxt = cur;
+  if (v < V) {
+    // in the order the loop issues them (K then V, each in k-step order): the wait counts of the loop are the merge of
+    // this path and the loop's own, and a first tile requested in another order would make every trip wait for more
+#pragma unroll
+    for (int i = 0; i < KS; ++i) { rk[i] = __builtin_nontemporal_load(cur.tile + i * 64); __builtin_amdgcn_sched_barrier(0); }
+#pragma unroll
+    for (int i = 0; i < KS; ++i) { rv[i] = __builtin_nontemporal_load(cur.tile + HD * 4 + i * 64); __builtin_amdgcn_sched_barrier(0); }
+  }
+
+  // the queries of all columns as B operands: unit (ks*2 + half)*32 + column holds dims ks*16 + half*8 .. +8
+  v4u *qs = (v4u *)lds;
+  for (int idx = threadIdx.x; idx < 32 * (HD / 8); idx += NW * 64) {
+    const int cc = idx & 31, d8 = idx >> 5, r = cc / grp, hq = cc - r * grp;
+    v4u q = v4u{0u, 0u, 0u, 0u};
+    if (cc < ncols && m0 + r < M) q = *(const v4u *)(q_h16 + ((int64_t)(m0 + r) * Hq + kvh * grp + hq) * HD + d8 * 8);
+    qs[idx] = q;
+  }
+  __syncthreads();
+
+  const float scale = 1.0f / sqrtf((float)HD);
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x16 o[NE];
+#pragma unroll
+  for (int e = 0; e < NE; ++e)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[e][r] = 0.f;
+
+  auto step = [&](auto more_tag) {
+    constexpr bool more = decltype(more_tag)::value;
+    if (more) nxt = locate(v + NW);
+    f32x16 s;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+      s = mfma_h16(__builtin_bit_cast(h16x8, rk[ks]), __builtin_bit_cast(h16x8, qs[(ks * 2 + half) * 32 + col]), s);
+    if (more) issue_k(nxt);
+    // a column outside the segment's rows sees no key of this tile
+    const int klim = (col >= cur.c0 && col < cur.c1) ? cur.keys : 0;
+    const int kbase = cur.tile_idx * ATT_TILE + 4 * half;
+    float tm = -INFINITY;
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float sv = (kbase + 8 * g + i < klim) ? s[4 * g + i] * scale : -INFINITY;
+        s[4 * g + i] = sv;
+        tm = fmaxf(tm, sv);
+      }
+    tm = fmaxf(tm, __shfl_xor(tm, 32, 64));
+    const float mn = fmaxf(m_run, tm);
+    const float mref = mn == -INFINITY ? 0.f : mn;             // a column that has seen no key yet: every p is exp(-inf) = 0
+    const float alpha = m_run == mn ? 1.0f : __expf(m_run - mref);
+    m_run = mn;
+    float ls = 0.f;
+    uint32_t pk[8];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+      for (int i = 0; i < 4; i += 2) {
+        float p0 = __expf(s[4 * g + i] - mref), p1 = __expf(s[4 * g + i + 1] - mref);
+        ls += p0 + p1;
+        pk[2 * g + (i >> 1)] = (uint32_t)f32_to_h16_bits(p0) | ((uint32_t)f32_to_h16_bits(p1) << 16);
+      }
+    l_run = l_run * alpha + ls;
+    if (__any(alpha != 1.0f)) {
+#pragma unroll
+      for (int e = 0; e < NE; ++e)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[e][r] *= alpha;
+    }
+#pragma unroll
+    for (int ks2 = 0; ks2 < 2; ++ks2) {   // the P^T hand-over between the two lanes of a column, as in attn_splitk_kernel
+      const int ga = 2 * ks2, gb = 2 * ks2 + 1;
+      uint32_t s0 = half ? pk[2 * ga] : pk[2 * gb], s1 = half ? pk[2 * ga + 1] : pk[2 * gb + 1];
+      uint32_t r0 = __shfl_xor(s0, 32, 64), r1 = __shfl_xor(s1, 32, 64);
+      uint32_t m0_ = half ? pk[2 * gb] : pk[2 * ga], m1_ = half ? pk[2 * gb + 1] : pk[2 * ga + 1];
+      v4u pb = half ? v4u{r0, r1, m0_, m1_} : v4u{m0_, m1_, r0, r1};
+#pragma unroll
+      for (int e = 0; e < NE; ++e)
+        o[e] = mfma_h16(__builtin_bit_cast(h16x8, rv[ks2 * NE + e]), __builtin_bit_cast(h16x8, pb), o[e]);
+    }
+    if (more) { issue_v(nxt); cur = nxt; }
+  };
+  for (; v + NW < V; v += NW) step(std::true_type{});
+  if (v < V) step(std::false_type{});
+
+  // ---- the two lanes of a column add their sums; then the wavefronts are folded in wavefront order
+  l_run += __shfl_xor(l_run, 32, 64);
+  const int ncp = ncols + 1, mpw = L::merge_per_wave(ncols);
+  char *mg = lds + L::Q_BYTES;
+  if (col < ncols) {
+    float *mo = (float *)(mg + w * mpw);
+#pragma unroll
+    for (int e = 0; e < NE; ++e)
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mo[(32 * e + 8 * g + 4 * half + i) * ncp + col] = o[e][4 * g + i];
+    if (half == 0) { mo[HD * ncp + col] = m_run; mo[HD * ncp + 32 + col] = l_run; }
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < ncols * HD; idx += NW * 64) {
+    const int cc = idx / HD, dd = idx % HD, r = cc / grp, hq = cc - r * grp;
+    if (m0 + r >= M) continue;
+    float mw[NW], Mx = -INFINITY;
+#pragma unroll
+    for (int ww = 0; ww < NW; ++ww) { mw[ww] = ((const float *)(mg + ww * mpw))[HD * ncp + cc]; Mx = fmaxf(Mx, mw[ww]); }
+    float acc = 0.f, lsum = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < NW; ++ww) {
+      const float *mo = (const float *)(mg + ww * mpw);
+      const float f = mw[ww] == -INFINITY ? 0.f : __expf(mw[ww] - Mx);   // a wavefront that saw no key of the column
+      acc += mo[dd * ncp + cc] * f;
+      lsum += mo[HD * ncp + 32 + cc] * f;
+    }
+    // a row that is not generating has no segment: its columns saw no key and its output is zero
+    Xp[k8_index(m0 + r, (kvh * grp + hq) * HD + dd, Mp)] = Mx == -INFINITY ? (uint16_t)0 : f32_to_h16_bits(acc / lsum);
+  }
+}
+
+int fast_attention_rows_per_group(int M, int Hq, int Hkv, int mode) {
+  const int grp = Hq / Hkv;
+  int rmax = 32 / grp < ATT_ROWS_MAX ? 32 / grp : ATT_ROWS_MAX;
+  if (mode == 1 || mode == 2 || rmax < 2 || M < 2) return 1;
+  if (mode == 3) return rmax;
+  // as many rows as still leave one workgroup for every compute unit
+  int R = rmax;
+  while (R >= 2 && (int64_t)((M + R - 1) / R) * Hkv < 256) R /= 2;
+  return R >= 2 ? R : 1;
+}
+
+size_t fast_attention_plan_ints(int max_rows) { return (size_t)(max_rows / 2 + 1) * ATT_PLAN_INTS; }
+
+void fast_attention_rows_plan(int32_t *plan, RowState rows, int M, int Hq, int Hkv, int R, hipStream_t st) {
+  hipLaunchKernelGGL(attn_rows_plan_kernel, dim3((M + R - 1) / R), dim3(64), 0, st, plan, rows, M, Hq / Hkv, R);
+}
+
+template <int HD>
+static void attention_rows_launch(void *Xp_out, const void *q_h16, const int32_t *plan, KvGeom kv, int layer, int M, int Mp, int Hq, int Hkv,
+                                  int R, hipStream_t st) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void *)attn_rows_kernel<HD>, hipFuncAttributeMaxDynamicSharedMemorySize, AttRowsLds<HD>::total(32));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(attn_rows_kernel<HD>, dim3(1, Hkv, (M + R - 1) / R), dim3(ATT_ROWS_WAVES * 64), AttRowsLds<HD>::total(R * (Hq / Hkv)), st,
+                     (uint16_t *)Xp_out, Mp, (const uint16_t *)q_h16, plan, kv, layer, Hq, Hkv, M, R);
+}
+
+void fast_attention_rows(void *Xp_out, const void *q_h16, const int32_t *plan, KvGeom kv, int layer, int M, int Mp, int Hq, int Hkv, int R,
+                         hipStream_t st) {
+  if (kv.head_dim == 128) attention_rows_launch<128>(Xp_out, q_h16, plan, kv, layer, M, Mp, Hq, Hkv, R, st);
+  else attention_rows_launch<64>(Xp_out, q_h16, plan, kv, layer, M, Mp, Hq, Hkv, R, st);
+}
+
 // ---- causal kernel for runs of consecutive positions ---------------------------------------------------
 // grid (blocks, Hkv), eight wavefronts per workgroup (two per SIMD, so one's MFMAs run under the other's softmax).
 // A block is up to 8 * 32 / grp consecutive rows of one cache slot; wavefront w carries rows w * 32/grp .. as one tile

@@ -142,10 +142,13 @@ def test_a_staged_snapshot_is_switched_in_between_steps_and_errors():
     ctx.close()
 
 
-def test_refill_and_compaction_with_the_groups_prompts_attended_once_per_group():
+@pytest.mark.parametrize("prefix_kernel", [2, 3], ids=["once-per-group-kernel", "several-rows-per-decode-workgroup"])
+def test_refill_and_compaction_with_the_groups_prompts_attended_once_per_group(prefix_kernel):
     """Enough rows that a row's keys stay in one workgroup, so the shared prompt tiles can go through the prefix kernel
     (forced on: at this size it would not pay): its job list is rebuilt as groups are admitted, finish and are
-    compacted.  Teacher-forced against the oracle."""
+    compacted.  The same with decode workgroups that take eight neighbouring rows -- rows at different positions, of
+    different groups once rows have moved, idle rows between them -- and the prompt tiles that neighbours of one group have
+    in common once.  Teacher-forced against the oracle."""
     shape = MID
     blob = synth.make_weights(shape, 0)
     blob32 = synth.widen_to_f32(blob)
@@ -155,7 +158,7 @@ def test_refill_and_compaction_with_the_groups_prompts_attended_once_per_group()
     stop = synth.make_stop_lens(P * G, 1, max_new, seed=13)
     ref = oracle_rollout(shape, blob32, prompts, lens, G=G, max_new=max_new, temperature=1.0, seed=2, stop_lens=stop)
     ctx = make_ctx(shape, 168, 128, blob)
-    out = ctx.rollout(prompts, lens, G, max_new, 1.0, 2, stop_lens=stop, continuous=True, forced=ref["tokens"].clip(0), prefix_kernel=2)
+    out = ctx.rollout(prompts, lens, G, max_new, 1.0, 2, stop_lens=stop, continuous=True, forced=ref["tokens"].clip(0), prefix_kernel=prefix_kernel)
     m = valid_mask(stop, max_new)
     assert np.array_equal(out["lens"], stop)
     same = (out["tokens"] == ref["tokens"]) & m

@@ -231,6 +231,16 @@ def test_group_shared_prompt_tiles(shape, G, P):
     same = (pf["tokens"] == af["tokens"]) & m
     assert same[m].mean() > 0.995, same[m].mean()
     assert np.abs(pf["logprobs"] - af["logprobs"])[same].max() < 2e-3
+    # 1c. decode workgroups that take several neighbouring rows and the prompt tiles those have in common once (the default
+    # for batches that leave every compute unit a workgroup that way): groups of 3 straddle the workgroups' rows, a batch
+    # that is no multiple of the rows per workgroup leaves the last one partly empty, and without compaction the
+    # sequences that have stopped stay behind as idle rows between the others
+    for nc in (False, True):
+        rf = ctx.rollout(prompts, lens, G, max_new, 1.0, 11, stop_lens=stop, forced=forced, prefix_kernel=3, no_compaction=nc)
+        assert np.array_equal(rf["lens"], stop)
+        same = (rf["tokens"] == af["tokens"]) & m
+        assert same[m].mean() > 0.995, same[m].mean()
+        assert np.abs(rf["logprobs"] - af["logprobs"])[same].max() < 2e-3
     # 2. against the oracle, teacher-forced on the oracle's tokens, for three prompts spread over the batch
     blob32 = synth.widen_to_f32(blob)
     pick = [0, P // 2, P - 1]
@@ -239,9 +249,10 @@ def test_group_shared_prompt_tiles(shape, G, P):
     for p in pick:
         refs[p] = oracle_rollout(shape, blob32, prompts[p:p + 1], lens[p:p + 1], G=G, max_new=12, temperature=1.0, seed=11, want_logits=True)
         forced12[p * G:(p + 1) * G] = np.maximum(refs[p]["tokens"], 0)
-    tf = ctx.rollout(prompts, lens, G, 12, 1.0, 11, forced=forced12, want_logits=True, prefix_kernel=2)
-    for p in pick:
-        assert np.abs(tf["logits"][p * G:(p + 1) * G] - refs[p]["logits"]).max() < BF16_LOGIT_TOL, p
+    for pk in (2, 3):
+        tf = ctx.rollout(prompts, lens, G, 12, 1.0, 11, forced=forced12, want_logits=True, prefix_kernel=pk)
+        for p in pick:
+            assert np.abs(tf["logits"][p * G:(p + 1) * G] - refs[p]["logits"]).max() < BF16_LOGIT_TOL, (pk, p)
     ctx.close()
 
 
@@ -431,12 +442,13 @@ def test_dense4b_shape_in_the_benchmark_launch_configuration():
 
     # -- the benchmark's prompt length against the oracle, inside the 64-row batch: sequence 0 with its 512-token prompt
     # and 8 teacher-forced steps (the oracle's stream id 0 is the batch's, so tokens and log-probs compare too); once with
-    # every row reading the group's 16 shared prompt tiles itself, once with the once-per-group kernel attending them
+    # every row reading the group's 16 shared prompt tiles itself, once with the once-per-group kernel attending them, once
+    # the way the benchmark runs (0: two neighbouring rows and their common prompt tiles per decode workgroup)
     prompts, lens = synth.make_prompts(shape.vocab, P, 512, seed=1)
     ref512 = oracle_rollout(shape, blob32, prompts[0:1], lens[0:1], G=1, max_new=8, temperature=1.0, seed=2, want_logits=True)
     forced8 = rng.integers(0, shape.vocab, size=(N, 8)).astype(np.int32)
     forced8[0] = ref512["tokens"][0]
-    for pk in (1, 2):
+    for pk in (0, 1, 2):
         tf = ctx.rollout(prompts, lens, G, 8, 1.0, 2, forced=forced8, want_logits=True, prefix_kernel=pk)
         err = float(np.abs(tf["logits"][0] - ref512["logits"][0]).max())
         print(f"[dense4b, 512-token prompt, prefix_kernel={pk}] max |dlogit| = {err:.4f}")
