@@ -20,13 +20,13 @@ HBM_PEAK_GBS = 8000.0
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of the decode-attention kernel (profiles/pmc_traffic_*.md), scaled by the same
 # counters on a plain 256 MiB copy: KiB fetched + written per launch over the KiB of the K/V tiles the launch touches
 # (shared prompt tiles once per group, a sequence's last tile whole).  Taken at the same kernel and grid on a 2-layer
-# model generating 64 tokens (the profiler crashes on the 36-layer process); set to None whenever attn_splitk_kernel changes.
-ATTN_TRAFFIC_OVER_TILE_BYTES = (29307.0 + 512.0) / (28608.0 + 512.0)
+# model generating 64 tokens (the profiler crashes on the 36-layer process); set to None whenever attn_rows_kernel changes.
+ATTN_TRAFFIC_OVER_TILE_BYTES = (29503.6 + 512.0) / (28608.0 + 512.0)
 # The same kernel timed by rocprofv3 --kernel-trace inside the graph replays of this very command (config 2), in microseconds
 # per launch (profiles/kernel_trace_dense4b-64x512+1024.md): the HIP events of the timed run bracket launches that are issued
 # one by one and include the launch gap, so both figures go into the line.  None for any other workload, and whenever the
 # kernel changes.
-ATTN_KERNEL_TRACE_US = {"dense4b-64x512+1024": 34.71}
+ATTN_KERNEL_TRACE_US = {"dense4b-64x512+1024": 31.44}
 
 
 def attn_kv_bytes_per_launch(shape, gen_lens, prompt_len, group, steps, whole_tiles, shared_elsewhere=False):
@@ -313,15 +313,20 @@ def main():
             prefix_kernel = abs(models[True] - per_launch_bytes) < abs(models[False] - per_launch_bytes)
             traffic = None
             # (the counters were taken with the kernel reading its shared tiles itself; with the prefix kernel it also reads
-            # that kernel's partials, which the factor does not cover)
-            if ATTN_TRAFFIC_OVER_TILE_BYTES and not prefix_kernel and abs(models[False] - per_launch_bytes) <= 1e-3 * per_launch_bytes:
+            # that kernel's partials, which the factor does not cover; they were taken on the two-rows-per-workgroup form)
+            rows_per_wg = int(st.attn_rows_per_workgroup)
+            if (ATTN_TRAFFIC_OVER_TILE_BYTES and not prefix_kernel and rows_per_wg == 2
+                    and abs(models[False] - per_launch_bytes) <= 1e-3 * per_launch_bytes):
                 traffic = attn_kv_bytes_per_launch(shape, out["lens"], plen, G, timed, whole_tiles=True,
                                                    shared_elsewhere=prefix_kernel) * ATTN_TRAFFIC_OVER_TILE_BYTES
-            roofline = {"bound": "hbm", "kernel": "attn_splitk_kernel (decode attention, one launch per layer" +
-                                  ("; the groups' shared prompt tiles are attended by attn_prefix_kernel before it)" if prefix_kernel else ")"),
+            kname = (f"attn_rows_kernel (decode attention, one launch per layer, {rows_per_wg} neighbouring rows and their common prompt tiles per workgroup)"
+                     if rows_per_wg > 1 else
+                     "attn_splitk_kernel (decode attention, one launch per layer" +
+                     ("; the groups' shared prompt tiles are attended by attn_prefix_kernel before it)" if prefix_kernel else ")"))
+            roofline = {"bound": "hbm", "kernel": kname,
                         "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
                         "traffic": traffic,
-                        "traffic_unit": "bytes per launch: whole K/V tiles of the timed launches x 1.0240 (FETCH_SIZE + WRITE_SIZE over "
+                        "traffic_unit": "bytes per launch: whole K/V tiles of the timed launches x 1.0308 (FETCH_SIZE + WRITE_SIZE over "
                                         "whole-tile bytes, same kernel and grid, profiles/pmc_traffic_*.md)",
                         "launches_timed": int(st.attn_launches),
                         "avg_launch_us": per_launch_s * 1e6, "bytes_per_launch": per_launch_bytes}

@@ -108,6 +108,9 @@ typedef struct {
   double gemm_ms, gemm_bytes; /* weight-streaming GEMMs: HIP-event time, weight bytes read */
   int32_t rollout_running;    /* 1 while echo_rollout is inside its loop on another thread (a snapshot installed
                                  now is staged, not activated) */
+  int32_t attn_rows_per_workgroup; /* rows of the batch that one workgroup of the decode attention took in the last decode
+                                 step that was launched or captured (1: a workgroup per row and KV head; see prefix_kernel) */
+  int32_t attn_prefix_jobs;   /* jobs of the once-per-group prompt kernel in that step (0: the kernel did not run) */
 } echo_stats_t;
 
 /* Bytes of device memory a context of this shape needs (weights x slots, KV cache, activations);

@@ -357,6 +357,7 @@ void forward_layers(echo_ctx *c, const Slot &S, int M, bool use_splitk_attn, int
   fast_resid_norm(h, S.embed, c->rows.token, nullptr, 0, p.Np_d, xa, S.layers[0].attn_norm, M, Mp, H, d.rms_eps, st);
   // decode attention over several rows per workgroup: the tile lists are the same for every layer
   const int att_rows = n_prefill_blocks == 0 && use_splitk_attn && c->px.n_jobs == 0 ? fast_attention_rows_per_group(M, Hq, Hkv, c->attn_mode) : 1;
+  if (n_prefill_blocks == 0 && use_splitk_attn) { c->st.attn_rows_per_workgroup = att_rows; c->st.attn_prefix_jobs = c->px.n_jobs; }
   if (att_rows > 1) fast_attention_rows_plan(at<int32_t>(c, p.o_aplan), c->rows, M, Hq, Hkv, att_rows, st);
   for (int l = 0; l < d.n_layers; ++l) {
     const LayerW &L = S.layers[l];

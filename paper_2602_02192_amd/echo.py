@@ -46,7 +46,7 @@ class Stats(C.Structure):
                 ("total_ms", C.c_float), ("swap_wait_ms", C.c_float),
                 ("attn_launches", C.c_int64), ("attn_ms", C.c_double), ("attn_bytes", C.c_double),
                 ("gemm_launches", C.c_int64), ("gemm_ms", C.c_double), ("gemm_bytes", C.c_double),
-                ("rollout_running", C.c_int32)]
+                ("rollout_running", C.c_int32), ("attn_rows_per_workgroup", C.c_int32), ("attn_prefix_jobs", C.c_int32)]
 
 
 EXPORTS = ["echo_arena_bytes", "echo_blob_bytes", "echo_init", "echo_load_policy", "echo_load_policy_begin",
