@@ -358,7 +358,7 @@ void forward_layers(echo_ctx *c, const Slot &S, int M, bool use_splitk_attn, int
   // decode attention over several rows per workgroup: the tile lists are the same for every layer
   const int att_rows = n_prefill_blocks == 0 && use_splitk_attn && c->px.n_jobs == 0 ? fast_attention_rows_per_group(M, Hq, Hkv, c->attn_mode) : 1;
   if (n_prefill_blocks == 0 && use_splitk_attn) { c->st.attn_rows_per_workgroup = att_rows; c->st.attn_prefix_jobs = c->px.n_jobs; }
-  if (att_rows > 1) fast_attention_rows_plan(at<int32_t>(c, p.o_aplan), c->rows, M, Hq, Hkv, att_rows, st);
+  if (att_rows > 1) fast_attention_rows_plan(at<int32_t>(c, p.o_aplan), c->rows, M, Hq, Hkv, c->attn_mode, st);
   for (int l = 0; l < d.n_layers; ++l) {
     const LayerW &L = S.layers[l];
     gemm_fast(c, part, xa, L.wqkv, Mp, p.Np_qkv, p.Kp_d, EPI_PARTIAL, &ns);
@@ -370,7 +370,7 @@ void forward_layers(echo_ctx *c, const Slot &S, int M, bool use_splitk_attn, int
       if (n_prefill_blocks > 0)
         fast_attention_prefill(xatt, q16, at<PrefillBlock>(c, p.o_blocks), n_prefill_blocks, c->kv, l, Mp, Hq, Hkv, st);
       else if (att_rows > 1)
-        fast_attention_rows(xatt, q16, at<int32_t>(c, p.o_aplan), c->kv, l, M, Mp, Hq, Hkv, att_rows, st);
+        fast_attention_rows(xatt, q16, at<int32_t>(c, p.o_aplan), c->rows, c->kv, l, M, Mp, Hq, Hkv, c->attn_mode, st);
       else if (use_splitk_attn)
         fast_attention(xatt, q16, c->rows, c->kv, l, M, Mp, Hq, Hkv, fast_attention_splits(M, Hkv, p.attn_max_splits),
                        at<float>(c, p.o_attn_o), at<float>(c, p.o_attn_ml), c->px, st);

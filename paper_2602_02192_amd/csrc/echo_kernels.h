@@ -139,17 +139,18 @@ void fast_attention(void *Xp_out, const void *q_h16, RowState rows, KvGeom kv, i
 void fast_attention_prefix(const void *q_h16, KvGeom kv, int layer, int Hq, int Hkv, float *part_o, float *part_ml, PrefixPlan px,
                            hipStream_t st);
 int fast_attention_splits(int M, int Hkv, int max_splits);
-// Decode attention with R consecutive rows of the batch per workgroup (R * Hq/Hkv <= 32): the whole prompt tiles that rows
-// of one group have in common are loaded and multiplied once per workgroup.  No key splitting and no partial buffers.
-// fast_attention_rows_per_group picks R (1: use fast_attention) -- mode 0: as many rows as still leave a workgroup for
-// every compute unit; 1, 2: never; 3: as many as the MFMA columns hold.  fast_attention_rows_plan writes every
-// workgroup's tile list (fast_attention_plan_ints(rows of the largest batch) ints) from the row state, once per decode
-// step and before the first fast_attention_rows of that step on the same stream.
+// Decode attention with several rows of the batch per workgroup (at most R, R * Hq/Hkv <= 32): the whole prompt tiles
+// that neighbouring rows of one group have in common are loaded and multiplied once per workgroup.  No key splitting and no
+// partial buffers.  fast_attention_rows_per_group gives R (1: use fast_attention) -- mode 0: a workgroup for every compute
+// unit, and at least two rows for each; 1, 2: never; 3: as many rows as the MFMA columns hold.  fast_attention_rows_plan
+// deals the generating rows to the workgroups and writes every workgroup's tile list (fast_attention_plan_ints(rows of
+// the largest batch) ints) from the row state, once per decode step and before the first fast_attention_rows of that
+// step on the same stream, with the same M and mode.
 int fast_attention_rows_per_group(int M, int Hq, int Hkv, int mode);
 size_t fast_attention_plan_ints(int max_rows);
-void fast_attention_rows_plan(int32_t *plan, RowState rows, int M, int Hq, int Hkv, int R, hipStream_t st);
-void fast_attention_rows(void *Xp_out, const void *q_h16, const int32_t *plan, KvGeom kv, int layer, int M, int Mp, int Hq, int Hkv, int R,
-                         hipStream_t st);
+void fast_attention_rows_plan(int32_t *plan, RowState rows, int M, int Hq, int Hkv, int mode, hipStream_t st);
+void fast_attention_rows(void *Xp_out, const void *q_h16, const int32_t *plan, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq,
+                         int Hkv, int mode, hipStream_t st);
 // Causal attention for runs of consecutive positions (prefill, teacher-forced scoring).  A block is up to
 // ATT_PREFILL_WAVES * ATT_PREFILL_COLS / (Hq/Hkv) rows m0 .. m0 + nrows - 1 holding positions pos0 .. of one cache
 // slot, whose keys and values (positions 0 .. pos0 + nrows - 1) are already in the cache.  The blocks must cover

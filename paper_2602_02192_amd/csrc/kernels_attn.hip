@@ -444,36 +444,43 @@ static void attention_launch(void *Xp_out, const void *q_h16, RowState rows, KvG
 
 // ---- several rows of the batch per workgroup ---------------------------------------------------------------------
 // A decode batch with more (row, KV head) pairs than the chip has room for at once gives every compute unit several of them
-// anyway; a workgroup of eight wavefronts that takes R consecutive rows (R * grp <= 32 MFMA columns, column = row * grp +
-// head) can then take the whole prompt tiles that rows of one group have in common once for all of them: the tile is
-// loaded and multiplied once, every column keeps its own softmax state.  A row's remaining tiles follow with the other
-// rows' columns masked.  What a workgroup walks is a list of segments of whole tiles (cache slot, first tile, columns,
-// number of valid keys) that attn_rows_plan_kernel writes once per decode step from the row state -- the list is the
-// same for every layer and KV head.  Lane i of every wavefront holds segment i, so finding the segment of a tile is a
-// ballot and a few lane reads, with no memory access on the way to the tile's address.  The wavefronts take the
-// workgroup's tiles in turn, one K and one V register tile each, exactly as in attn_splitk_kernel.
+// anyway; a workgroup of eight wavefronts that takes up to R rows (R * grp <= 32 MFMA columns, column = row * grp + head)
+// can then take the whole prompt tiles that rows of one group have in common once for all of them: the tile is loaded
+// and multiplied once, every column keeps its own softmax state.  A row's remaining tiles follow with the other rows'
+// columns masked.  attn_rows_plan_kernel, once per decode step, deals the rows that are still generating to the launch's
+// NG row sets in order and evenly (so a batch that has partly drained still gives every workgroup the same number of rows,
+// to within one), and writes for every set its rows and a list of segments of whole tiles (cache slot, first tile,
+// columns, number of valid keys) -- the same for every layer and KV head.  Lane i of every wavefront holds segment i, so
+// finding the segment of a tile is a ballot and a few lane reads, with no memory access on the way to the tile's
+// address.  The wavefronts take the workgroup's tiles in turn, one K and one V register tile each, exactly as in
+// attn_splitk_kernel.
 constexpr int ATT_ROWS_MAX = 8;            // rows per workgroup at most
 constexpr int ATT_ROWS_WAVES = 8;
+constexpr int ATT_ROWS_BATCH_MAX = 1024;   // rows of a batch that the plan kernel (one workgroup) deals
 constexpr int ATT_SEG_MAX = 24;            // runs of rows with a common prompt (<= R/2) + two segments per row
-constexpr int ATT_SEG_INTS = 8;            // cache slot, first tile, first and end position in the workgroup's tile list, first and end column, valid keys, tiles in all
-constexpr int ATT_PLAN_INTS = ATT_SEG_MAX * ATT_SEG_INTS;
+constexpr int ATT_SEG_INTS = 8;            // cache slot, first tile, first and end position in the workgroup's tile list, first and end column, valid keys
+constexpr int ATT_HDR_INTS = 16;           // number of rows, tiles in all, the rows
+constexpr int ATT_PLAN_INTS = ATT_HDR_INTS + ATT_SEG_MAX * ATT_SEG_INTS;
 
-// grid (workgroups of the attention launch), block 64.
-__global__ void attn_rows_plan_kernel(int32_t *__restrict__ plan, RowState rows, int M, int grp, int R) {
-  __shared__ int32_t f[ATT_ROWS_MAX][5];   // active, prompt slot, whole prompt tiles, keys, slot
-  const int gi = blockIdx.x, m0 = gi * R, t = threadIdx.x;
-  if (t < R) {
-    const int m = m0 + t;
-    const bool val = m < M && rows.active[m] != 0;
-    f[t][0] = val;
-    f[t][1] = val ? rows.pslot[m] : 0;
-    f[t][2] = val ? (rows.ptiles[m] & ~ATT_PREFIX_DONE) : 0;
-    f[t][3] = val ? rows.pos[m] + 1 : 0;
-    f[t][4] = val ? rows.slot[m] : 0;
-  }
+// One workgroup of ATT_ROWS_BATCH_MAX threads, thread m for row m; NG row sets, each of at most R rows (NG * R >= M).
+__global__ __launch_bounds__(ATT_ROWS_BATCH_MAX) void attn_rows_plan_kernel(int32_t *__restrict__ plan, RowState rows, int M, int grp, int NG, int R) {
+  __shared__ int32_t f[ATT_ROWS_BATCH_MAX][4];   // prompt slot, whole prompt tiles, keys, slot
+  __shared__ int32_t order[ATT_ROWS_BATCH_MAX];  // the rows that are generating, in row order
+  __shared__ int32_t wtot[ATT_ROWS_BATCH_MAX / 64 + 1];
+  const int t = threadIdx.x, w = t >> 6, lane = t & 63;
+  const bool val = t < M && rows.active[t] != 0;
+  if (val) { f[t][0] = rows.pslot[t]; f[t][1] = rows.ptiles[t] & ~ATT_PREFIX_DONE; f[t][2] = rows.pos[t] + 1; f[t][3] = rows.slot[t]; }
+  const uint64_t bal = __ballot(val);
+  if (lane == 0) wtot[w] = __popcll(bal);
   __syncthreads();
-  if (t != 0) return;
-  int32_t *seg = plan + (int64_t)gi * ATT_PLAN_INTS;
+  int rank = __popcll(bal & ((1ull << lane) - 1)), n_act = 0;
+  for (int i = 0; i < ATT_ROWS_BATCH_MAX / 64; ++i) { if (i < w) rank += wtot[i]; n_act += wtot[i]; }
+  if (val) order[rank] = t;
+  __syncthreads();
+  if (t >= NG) return;
+  // set t takes the generating rows of rank ceil(t n / NG) .. ceil((t + 1) n / NG) - 1: at most ceil(n / NG) <= R of them
+  const int first = (int)(((int64_t)t * n_act + NG - 1) / NG), end = (int)(((int64_t)(t + 1) * n_act + NG - 1) / NG), nr = end - first;
+  int32_t *hdr = plan + (int64_t)t * ATT_PLAN_INTS, *seg = hdr + ATT_HDR_INTS;
   int ns = 0, v = 0;
   auto emit = [&](int slot, int tile0, int n, int c0, int c1, int keys) {
     int32_t *s = seg + ns * ATT_SEG_INTS;
@@ -481,19 +488,25 @@ __global__ void attn_rows_plan_kernel(int32_t *__restrict__ plan, RowState rows,
     v += n;
     ++ns;
   };
-  for (int r = 0; r < R;) {
-    if (!f[r][0]) { ++r; continue; }
-    const int ps = f[r][1], pt = f[r][2];
-    int r2 = r + 1, full = f[r][3] / ATT_TILE;
-    while (r2 < R && f[r2][0] && f[r2][1] == ps && f[r2][2] == pt) { full = min(full, f[r2][3] / ATT_TILE); ++r2; }
+  for (int r = 0; r < nr;) {
+    const int32_t *a = f[order[first + r]];
+    const int ps = a[0], pt = a[1];
+    int r2 = r + 1, full = a[2] / ATT_TILE;
+    while (r2 < nr) {
+      const int32_t *b = f[order[first + r2]];
+      if (b[0] != ps || b[1] != pt) break;
+      full = min(full, b[2] / ATT_TILE);
+      ++r2;
+    }
     const int sh = r2 - r >= 2 ? min(pt, full) : 0;   // whole tiles that every row of the run reads from the same slot
     if (sh > 0) emit(ps, 0, sh, r * grp, r2 * grp, 0x7fffffff);
     for (int rr = r; rr < r2; ++rr) {
-      const int nk = f[rr][3], nt = (nk + ATT_TILE - 1) / ATT_TILE;
-      int a = sh;
-      const int b = min(pt, nt);
-      if (b > a) { emit(ps, a, b - a, rr * grp, (rr + 1) * grp, nk); a = b; }   // prompt tiles the row reads alone
-      if (nt > a) emit(f[rr][4], a, nt - a, rr * grp, (rr + 1) * grp, nk);
+      const int32_t *b = f[order[first + rr]];
+      const int nk = b[2], nt = (nk + ATT_TILE - 1) / ATT_TILE;
+      int a0 = sh;
+      const int e0 = min(pt, nt);
+      if (e0 > a0) { emit(ps, a0, e0 - a0, rr * grp, (rr + 1) * grp, nk); a0 = e0; }   // prompt tiles the row reads alone
+      if (nt > a0) emit(b[3], a0, nt - a0, rr * grp, (rr + 1) * grp, nk);
     }
     r = r2;
   }
@@ -501,7 +514,8 @@ __global__ void attn_rows_plan_kernel(int32_t *__restrict__ plan, RowState rows,
     int32_t *s = seg + i * ATT_SEG_INTS;
     s[0] = 0; s[1] = 0; s[2] = 0x7fffffff; s[3] = 0x7fffffff; s[4] = 0; s[5] = 0; s[6] = 0; s[7] = 0;
   }
-  seg[7] = v;   // tiles of the workgroup in all
+  hdr[0] = nr; hdr[1] = v;
+  for (int r = 0; r < ATT_ROWS_MAX; ++r) hdr[2 + r] = r < nr ? order[first + r] : -1;
 }
 
 template <int HD> struct AttRowsLds {
@@ -511,25 +525,28 @@ template <int HD> struct AttRowsLds {
   __host__ __device__ static int total(int ncols) { return Q_BYTES + ATT_ROWS_WAVES * merge_per_wave(ncols); }
 };
 
-// grid (1, Hkv, ceil(M / R)), block 512.
+// grid (1, Hkv, NG), block 512; R = the most rows a set can hold (NG * R >= M).
 template <int HD>
 __global__ __launch_bounds__(ATT_ROWS_WAVES * 64) void attn_rows_kernel(uint16_t *__restrict__ Xp, int Mp, const uint16_t *__restrict__ q_h16,
-                                                                       const int32_t *__restrict__ plan, KvGeom kv, int layer, int Hq, int Hkv,
-                                                                       int M, int R) {
+                                                                       const int32_t *__restrict__ plan, const int32_t *__restrict__ row_active,
+                                                                       KvGeom kv, int layer, int Hq, int Hkv, int M, int R) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   using L = AttRowsLds<HD>;
   constexpr int KS = HD / 16, NE = HD / 32, NW = ATT_ROWS_WAVES;
-  const int kvh = blockIdx.y, gi = blockIdx.z, m0 = gi * R, grp = Hq / Hkv, ncols = R * grp;
+  const int kvh = blockIdx.y, gi = blockIdx.z, NG = gridDim.z, grp = Hq / Hkv, ncols = R * grp;
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
+  const int32_t *hdr = plan + (int64_t)gi * ATT_PLAN_INTS;
 
-  // lane i holds segment i of the workgroup's list
-  int sg_slot = 0, sg_tile0 = 0, sg_v0 = 0x7fffffff, sg_v1 = 0x7fffffff, sg_c0 = 0, sg_c1 = 0, sg_keys = 0, sg_total = 0;
+  // lane i holds segment i of the workgroup's list; lanes 32 .. 47 the header (number of rows, tiles in all, the rows)
+  int sg_slot = 0, sg_tile0 = 0, sg_v0 = 0x7fffffff, sg_v1 = 0x7fffffff, sg_c0 = 0, sg_c1 = 0, sg_keys = 0, hd_word = 0;
   if (lane < ATT_SEG_MAX) {
-    const int4 *sp = (const int4 *)(plan + ((int64_t)gi * ATT_SEG_MAX + lane) * ATT_SEG_INTS);
+    const int4 *sp = (const int4 *)(hdr + ATT_HDR_INTS + lane * ATT_SEG_INTS);
     const int4 a = sp[0], b = sp[1];
-    sg_slot = a.x; sg_tile0 = a.y; sg_v0 = a.z; sg_v1 = a.w; sg_c0 = b.x; sg_c1 = b.y; sg_keys = b.z; sg_total = b.w;
+    sg_slot = a.x; sg_tile0 = a.y; sg_v0 = a.z; sg_v1 = a.w; sg_c0 = b.x; sg_c1 = b.y; sg_keys = b.z;
+  } else if (lane >= 32 && lane < 32 + ATT_HDR_INTS) {
+    hd_word = hdr[lane - 32];
   }
-  const int V = __builtin_amdgcn_readfirstlane(sg_total);
+  const int nrows = __builtin_amdgcn_readlane(hd_word, 32), V = __builtin_amdgcn_readlane(hd_word, 33);
   const int64_t head_units = (int64_t)HD * 8;   // 16-byte units per tile (K then V)
   const v4u *cache = (const v4u *)kv.base;
   const int64_t lk_off = ((int64_t)layer * kv.layer_stride() + (int64_t)kvh * 2 * kv.head_stride()) / 8;   // in 16-byte units
@@ -572,7 +589,7 @@ __global__ __launch_bounds__(ATT_ROWS_WAVES * 64) void attn_rows_kernel(uint16_t
   for (int idx = threadIdx.x; idx < 32 * (HD / 8); idx += NW * 64) {
     const int cc = idx & 31, d8 = idx >> 5, r = cc / grp, hq = cc - r * grp;
     v4u q = v4u{0u, 0u, 0u, 0u};
-    if (cc < ncols && m0 + r < M) q = *(const v4u *)(q_h16 + ((int64_t)(m0 + r) * Hq + kvh * grp + hq) * HD + d8 * 8);
+    if (r < nrows) q = *(const v4u *)(q_h16 + ((int64_t)hdr[2 + r] * Hq + kvh * grp + hq) * HD + d8 * 8);
     qs[idx] = q;
   }
   __syncthreads();
@@ -660,9 +677,8 @@ __global__ __launch_bounds__(ATT_ROWS_WAVES * 64) void attn_rows_kernel(uint16_t
     if (half == 0) { mo[HD * ncp + col] = m_run; mo[HD * ncp + 32 + col] = l_run; }
   }
   __syncthreads();
-  for (int idx = threadIdx.x; idx < ncols * HD; idx += NW * 64) {
+  for (int idx = threadIdx.x; idx < nrows * grp * HD; idx += NW * 64) {
     const int cc = idx / HD, dd = idx % HD, r = cc / grp, hq = cc - r * grp;
-    if (m0 + r >= M) continue;
     float mw[NW], Mx = -INFINITY;
 #pragma unroll
     for (int ww = 0; ww < NW; ++ww) { mw[ww] = ((const float *)(mg + ww * mpw))[HD * ncp + cc]; Mx = fmaxf(Mx, mw[ww]); }
@@ -674,44 +690,55 @@ __global__ __launch_bounds__(ATT_ROWS_WAVES * 64) void attn_rows_kernel(uint16_t
       acc += mo[dd * ncp + cc] * f;
       lsum += mo[HD * ncp + 32 + cc] * f;
     }
-    // a row that is not generating has no segment: its columns saw no key and its output is zero
-    Xp[k8_index(m0 + r, (kvh * grp + hq) * HD + dd, Mp)] = Mx == -INFINITY ? (uint16_t)0 : f32_to_h16_bits(acc / lsum);
+    Xp[k8_index(hdr[2 + r], (kvh * grp + hq) * HD + dd, Mp)] = f32_to_h16_bits(acc / lsum);
   }
+  // rows that are not generating belong to no set: their outputs are zero; workgroup gi clears rows gi, gi + NG, ..
+  for (int m = gi; m < M; m += NG) {
+    if (row_active[m]) continue;
+    for (int idx = threadIdx.x; idx < grp * HD; idx += NW * 64) Xp[k8_index(m, kvh * grp * HD + idx, Mp)] = 0;
+  }
+}
+
+// Row sets of a launch over M rows: one workgroup per compute unit where the batch allows (sets x KV heads >= 256), more
+// when a set would otherwise need more rows than the MFMA columns hold.  mode 3: as few sets as the columns allow.
+static int attention_row_sets(int M, int Hq, int Hkv, int mode) {
+  const int grp = Hq / Hkv, rmax = 32 / grp < ATT_ROWS_MAX ? 32 / grp : ATT_ROWS_MAX;
+  const int need = (M + rmax - 1) / rmax, fill = mode == 3 ? 1 : (256 + Hkv - 1) / Hkv;
+  return need > fill ? need : fill;
 }
 
 int fast_attention_rows_per_group(int M, int Hq, int Hkv, int mode) {
   const int grp = Hq / Hkv;
-  int rmax = 32 / grp < ATT_ROWS_MAX ? 32 / grp : ATT_ROWS_MAX;
-  if (mode == 1 || mode == 2 || rmax < 2 || M < 2) return 1;
-  if (mode == 3) return rmax;
-  // as many rows as still leave one workgroup for every compute unit
-  int R = rmax;
-  while (R >= 2 && (int64_t)((M + R - 1) / R) * Hkv < 256) R /= 2;
-  return R >= 2 ? R : 1;
+  if (mode == 1 || mode == 2 || 32 / grp < 2 || M < 2 || M > ATT_ROWS_BATCH_MAX) return 1;
+  const int NG = attention_row_sets(M, Hq, Hkv, mode);
+  if (mode != 3 && M < 2 * NG) return 1;   // fewer than two rows per compute unit: one row per workgroup, keys split where it pays
+  return (M + NG - 1) / NG;
 }
 
-size_t fast_attention_plan_ints(int max_rows) { return (size_t)(max_rows / 2 + 1) * ATT_PLAN_INTS; }
+size_t fast_attention_plan_ints(int max_rows) { return (size_t)(max_rows < ATT_ROWS_BATCH_MAX ? max_rows : ATT_ROWS_BATCH_MAX) * ATT_PLAN_INTS; }
 
-void fast_attention_rows_plan(int32_t *plan, RowState rows, int M, int Hq, int Hkv, int R, hipStream_t st) {
-  hipLaunchKernelGGL(attn_rows_plan_kernel, dim3((M + R - 1) / R), dim3(64), 0, st, plan, rows, M, Hq / Hkv, R);
+void fast_attention_rows_plan(int32_t *plan, RowState rows, int M, int Hq, int Hkv, int mode, hipStream_t st) {
+  const int NG = attention_row_sets(M, Hq, Hkv, mode);
+  hipLaunchKernelGGL(attn_rows_plan_kernel, dim3(1), dim3(ATT_ROWS_BATCH_MAX), 0, st, plan, rows, M, Hq / Hkv, NG, (M + NG - 1) / NG);
 }
 
 template <int HD>
-static void attention_rows_launch(void *Xp_out, const void *q_h16, const int32_t *plan, KvGeom kv, int layer, int M, int Mp, int Hq, int Hkv,
-                                  int R, hipStream_t st) {
+static void attention_rows_launch(void *Xp_out, const void *q_h16, const int32_t *plan, RowState rows, KvGeom kv, int layer, int M, int Mp,
+                                  int Hq, int Hkv, int mode, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
     (void)hipFuncSetAttribute((const void *)attn_rows_kernel<HD>, hipFuncAttributeMaxDynamicSharedMemorySize, AttRowsLds<HD>::total(32));
     attr_set = true;
   }
-  hipLaunchKernelGGL(attn_rows_kernel<HD>, dim3(1, Hkv, (M + R - 1) / R), dim3(ATT_ROWS_WAVES * 64), AttRowsLds<HD>::total(R * (Hq / Hkv)), st,
-                     (uint16_t *)Xp_out, Mp, (const uint16_t *)q_h16, plan, kv, layer, Hq, Hkv, M, R);
+  const int NG = attention_row_sets(M, Hq, Hkv, mode), R = (M + NG - 1) / NG;
+  hipLaunchKernelGGL(attn_rows_kernel<HD>, dim3(1, Hkv, NG), dim3(ATT_ROWS_WAVES * 64), AttRowsLds<HD>::total(R * (Hq / Hkv)), st,
+                     (uint16_t *)Xp_out, Mp, (const uint16_t *)q_h16, plan, rows.active, kv, layer, Hq, Hkv, M, R);
 }
 
-void fast_attention_rows(void *Xp_out, const void *q_h16, const int32_t *plan, KvGeom kv, int layer, int M, int Mp, int Hq, int Hkv, int R,
-                         hipStream_t st) {
-  if (kv.head_dim == 128) attention_rows_launch<128>(Xp_out, q_h16, plan, kv, layer, M, Mp, Hq, Hkv, R, st);
-  else attention_rows_launch<64>(Xp_out, q_h16, plan, kv, layer, M, Mp, Hq, Hkv, R, st);
+void fast_attention_rows(void *Xp_out, const void *q_h16, const int32_t *plan, RowState rows, KvGeom kv, int layer, int M, int Mp, int Hq,
+                         int Hkv, int mode, hipStream_t st) {
+  if (kv.head_dim == 128) attention_rows_launch<128>(Xp_out, q_h16, plan, rows, kv, layer, M, Mp, Hq, Hkv, mode, st);
+  else attention_rows_launch<64>(Xp_out, q_h16, plan, rows, kv, layer, M, Mp, Hq, Hkv, mode, st);
 }
 
 // ---- causal kernel for runs of consecutive positions ---------------------------------------------------
