@@ -477,10 +477,19 @@ __global__ __launch_bounds__(ATT_ROWS_BATCH_MAX) void attn_rows_plan_kernel(int3
   for (int i = 0; i < ATT_ROWS_BATCH_MAX / 64; ++i) { if (i < w) rank += wtot[i]; n_act += wtot[i]; }
   if (val) order[rank] = t;
   __syncthreads();
-  if (t >= NG) return;
   // set t takes the generating rows of rank ceil(t n / NG) .. ceil((t + 1) n / NG) - 1: at most ceil(n / NG) <= R of them
-  const int first = (int)(((int64_t)t * n_act + NG - 1) / NG), end = (int)(((int64_t)(t + 1) * n_act + NG - 1) / NG), nr = end - first;
-  int32_t *hdr = plan + (int64_t)t * ATT_PLAN_INTS, *seg = hdr + ATT_HDR_INTS;
+  const int first = (int)(((int64_t)t * n_act + NG - 1) / NG), end = (int)(((int64_t)(t + 1) * n_act + NG - 1) / NG), nr = t < NG ? end - first : 0;
+  // The sets go into the list longest first (by tiles, shared ones counted per row): workgroups start in list order, so
+  // when a launch has more workgroups than the chip holds at once the short ones fill in behind the long ones.
+  int mine = 0;
+  for (int r = 0; r < nr; ++r) mine += (f[order[first + r]][2] + ATT_TILE - 1) / ATT_TILE;
+  __shared__ int32_t tot[ATT_ROWS_BATCH_MAX];
+  if (t < NG) tot[t] = mine;
+  __syncthreads();
+  if (t >= NG) return;
+  int place = 0;
+  for (int u = 0; u < NG; ++u) place += tot[u] > mine || (tot[u] == mine && u < t);
+  int32_t *hdr = plan + (int64_t)place * ATT_PLAN_INTS, *seg = hdr + ATT_HDR_INTS;
   int ns = 0, v = 0;
   auto emit = [&](int slot, int tile0, int n, int c0, int c1, int keys) {
     int32_t *s = seg + ns * ATT_SEG_INTS;
