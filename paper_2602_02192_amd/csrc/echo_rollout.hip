@@ -73,8 +73,8 @@ int plan_prefix_jobs(echo_ctx *c, std::vector<int32_t> &ptiles, const std::vecto
   }
   // The extra launch costs more than it saves at 64 rows x 16 tiles (measured: -7 % there; -2 % at a draining 128 x 32,
   // +5 % at 256 x 32), so small batches with short prompts keep reading their shared tiles in the decode kernel.  A
-  // batch that is refilled as sequences end (grid_jobs > 0) keeps 256 rows of unequal lengths in flight: +9 % at 256 x 16.
-  int64_t covered = 0, min_covered = prefix_kernel == 2 ? 0 : grid_jobs > 0 ? 4096 : 6144;
+  // batch that is refilled as sequences end (grid_jobs > 0) keeps 256 rows of unequal lengths in flight: +9 % at 256 x 15.
+  int64_t covered = 0, min_covered = prefix_kernel == 2 ? 0 : grid_jobs > 0 ? 3584 : 6144;
   for (const PrefixJob &jb : jobs) covered += (int64_t)jb.nrows * jb.ptiles;
   if (jobs.empty() || (int)jobs.size() > cap || covered < min_covered) {
     for (int r = 0; r < R; ++r) ptiles[r] &= ~ATT_PREFIX_DONE;
