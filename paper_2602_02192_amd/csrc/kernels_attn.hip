@@ -10,6 +10,10 @@
 //   whose state lives in the lanes of each query-head column.  Per-wavefront and per-split partial (max, sum,
 //   acc) are merged in a fixed order (no atomics): by the workgroup through LDS, by attn_combine_kernel across
 //   splits.
+// attn_rows_kernel: the same loop with several rows of the batch per workgroup, for batches that give every compute unit
+//   two rows and more: the prompt tiles that neighbouring rows of one group share are loaded and multiplied once.
+// attn_prefix_kernel: a group's shared prompt tiles once for all its rows, as partials that attn_splitk_kernel folds in.
+// attn_prefill_kernel: causal attention over runs of consecutive positions (prefill, teacher-forced scoring).
 #include <type_traits>
 
 #include "echo_device.h"

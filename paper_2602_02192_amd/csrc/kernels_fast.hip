@@ -150,7 +150,7 @@ __global__ __launch_bounds__(TOPP_THREADS) void topp_cut_kernel(uint32_t *cut_ke
   __shared__ unsigned long long sh_u64[TOPP_THREADS / 64];
   __shared__ float sh_f[TOPP_THREADS / 64];
   __shared__ int sh_i[TOPP_THREADS / 64];
-  __shared__ unsigned long long sel_above;
+  __shared__ unsigned long long sel_above, sel_mass;
   __shared__ uint32_t sel_digit;
   const int m = blockIdx.x, tid = threadIdx.x, wv = tid >> 6;
   if (row_active && !row_active[m]) return;
@@ -229,28 +229,18 @@ __global__ __launch_bounds__(TOPP_THREADS) void topp_cut_kernel(uint32_t *cut_ke
     if (tid < 256) {
       for (int w = 0; w < wv; ++w) incl += hist[w];
       const unsigned long long at = above + incl, before = at - h;
-      if ((at >= target && before < target) || (tid == 255 && at < target)) { sel_digit = (uint32_t)(255 - tid); sel_above = before; }
+      if ((at >= target && before < target) || (tid == 255 && at < target)) { sel_digit = (uint32_t)(255 - tid); sel_above = before; sel_mass = h; }
     }
     __syncthreads();
     prefix = (prefix << 8) | sel_digit;
     above = sel_above;
   }
   const uint32_t cut = prefix;
-  // keys equal to the cut share one mass; the first `take` of them in index order are kept
-  int ties = 0;
-  unsigned long long q_cut = 0;
-  visit([&](float v) { if (float_order_key(v) == cut) { ++ties; q_cut = mass(v); } });
-  for (int o = 32; o > 0; o >>= 1) {
-    ties += __shfl_xor(ties, o, 64);
-    unsigned long long v = __shfl_xor(q_cut, o, 64);
-    q_cut = q_cut > v ? q_cut : v;
-  }
-  __syncthreads();
-  if ((tid & 63) == 0) { sh_i[wv] = ties; sh_u64[wv] = q_cut; }
-  __syncthreads();
-  int n_ties = 0;
-  unsigned long long qc = 0;
-  for (int w = 0; w < TOPP_THREADS / 64; ++w) { n_ties += sh_i[w]; qc = qc > sh_u64[w] ? qc : sh_u64[w]; }
+  // Keys equal to the cut share one mass, so the last round's bin of the cut -- whose keys are exactly those -- holds
+  // their number times that mass; the first `take` of them in index order are kept.  (A mass of zero, far below the
+  // maximum: every such key is kept, and their number does not matter.)
+  const unsigned long long qc = mass(__uint_as_float((cut & 0x80000000u) ? cut ^ 0x80000000u : ~cut));
+  const long long n_ties = qc ? (long long)(sel_mass / qc) : 0;
   const unsigned long long need = target - above;   // > 0: mass still missing once every key above the cut is kept
   const long long take = qc ? (long long)((need + qc - 1) / qc) : (long long)V;   // >= 1
   if (tid == 0) { cut_key[m] = cut; cut_last[m] = V; }   // V: every key equal to the cut is kept
