@@ -143,6 +143,10 @@ __device__ __forceinline__ uint32_t float_order_key(float f) {   // a < b  <=>  
   uint32_t u = __float_as_uint(f);
   return u ^ ((u >> 31) ? 0xffffffffu : 0x80000000u);
 }
+__device__ __forceinline__ float order_key_float(uint32_t key) {   // the float whose key this is
+  return __uint_as_float((key & 0x80000000u) ? key ^ 0x80000000u : ~key);
+}
+constexpr int TOPP_CAND = 1024;   // keys the last round can take from the list (more: it walks the row like the others)
 __global__ __launch_bounds__(TOPP_THREADS) void topp_cut_kernel(uint32_t *cut_key, int32_t *cut_last, const float *logits, int64_t ld,
                                                                  int V, float temperature, float top_p, const int32_t *row_active) {
   __shared__ unsigned long long hist[4];        // mass of the bins of each of the first four wavefronts
@@ -203,18 +207,37 @@ __global__ __launch_bounds__(TOPP_THREADS) void topp_cut_kernel(uint32_t *cut_ke
   // radix select of the cut key: the largest key K with mass{key >= K} >= target
   uint32_t prefix = 0;
   unsigned long long above = 0;   // mass of the keys above the current prefix range
+  // The third round notes the keys it histograms (those that share the cut's upper 16 bits: a few hundred of a row of
+  // N(0, 1)-like logits); if they fit the list the last round walks the list instead of the row.
+  __shared__ uint32_t cand[TOPP_CAND];
+  __shared__ int cand_n;
+  if (tid == 0) cand_n = 0;
   for (int round = 0; round < 4; ++round) {
     const int shift = 24 - 8 * round;
     __syncthreads();
     for (int j = tid; j < 16 * 256; j += TOPP_THREADS) (&sub[0][0])[j] = 0;
     __syncthreads();
-    visit([&](float v) {
-      uint32_t key = float_order_key(v);
-      if (round == 0 || (key >> (shift + 8)) == prefix) {
-        unsigned long long q = mass(v);
-        if (q) atomicAdd(&sub[tid & 15][(key >> shift) & 255u], q);
+    if (round == 3 && cand_n <= TOPP_CAND) {
+      for (int j = tid; j < cand_n; j += TOPP_THREADS) {
+        const uint32_t key = cand[j];
+        if ((key >> 8) == prefix) {
+          unsigned long long q = mass(order_key_float(key));
+          if (q) atomicAdd(&sub[tid & 15][key & 255u], q);
+        }
       }
-    });
+    } else {
+      visit([&](float v) {
+        uint32_t key = float_order_key(v);
+        if (round == 0 || (key >> (shift + 8)) == prefix) {
+          unsigned long long q = mass(v);
+          if (q) atomicAdd(&sub[tid & 15][(key >> shift) & 255u], q);
+          if (round == 2) {
+            const int k = atomicAdd(&cand_n, 1);
+            if (k < TOPP_CAND) cand[k] = key;
+          }
+        }
+      });
+    }
     __syncthreads();
     // walk the bins from the top: thread t of the first four wavefronts owns bin 255 - t, so an inclusive prefix sum
     // over t is the mass of the bins at or above its own; exactly one bin takes the running mass across the target
@@ -239,7 +262,7 @@ __global__ __launch_bounds__(TOPP_THREADS) void topp_cut_kernel(uint32_t *cut_ke
   // Keys equal to the cut share one mass, so the last round's bin of the cut -- whose keys are exactly those -- holds
   // their number times that mass; the first `take` of them in index order are kept.  (A mass of zero, far below the
   // maximum: every such key is kept, and their number does not matter.)
-  const unsigned long long qc = mass(__uint_as_float((cut & 0x80000000u) ? cut ^ 0x80000000u : ~cut));
+  const unsigned long long qc = mass(order_key_float(cut));
   const long long n_ties = qc ? (long long)(sel_mass / qc) : 0;
   const unsigned long long need = target - above;   // > 0: mass still missing once every key above the cut is kept
   const long long take = qc ? (long long)((need + qc - 1) / qc) : (long long)V;   // >= 1

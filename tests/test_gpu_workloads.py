@@ -315,7 +315,8 @@ def test_nucleus_cut_inside_exact_ties(shape):
     """A zero lm_head makes every logit exactly 0: all V tokens tie, the kept set is the lowest ceil(top_p * V) indices
     (lower index first among equals), every kept token has probability 1/k, and the token is the kept index with the
     largest uniform draw -- the oracle and the GPU must agree on every token.  V = 1024 resolves the ties through the
-    index list, V = 2048 through the scan over contiguous runs."""
+    index list, V = 2048 through the scan over contiguous runs; the cut's last radix round takes its 1024 keys from the
+    candidate list that the round before filled (exactly full), and with 2048 candidates walks the row instead."""
     blob = synth.make_weights(shape, 4)
     off, shp = synth.blob_offsets(shape)["lm_head"]
     blob[off:off + int(np.prod(shp))] = 0
