@@ -754,16 +754,30 @@ void fast_gemm_pick(int Np, int Kp, int Mp, int full_k, GemmShape *g) {
       g->waves_n = best; g->stages = best == 3 && Mp != 64 ? 3 : 2; g->nsplit = 1;   // 64 rows: see gemm_lds_min_wgs
       return;
     }
-    g->waves_n = wide || nblocks % 4 == 0 || nblocks > 96 ? 4 : 3;
     g->stages = 2;   // deeper register pipelines measured no faster once the wait counts are exact
-    int strips = (nblocks + g->waves_n - 1) / g->waves_n * (wide ? Mp / 256 : 1);
-    if (full_k) { g->nsplit = 1; return; }
-    int ns = (240 + strips / 2) / strips;
-    if (ns > total_chunks / 2) ns = total_chunks / 2;
-    if (ns > 10) ns = 10;
-    if (ns < 1) ns = 1;
-    int cps = (total_chunks + ns - 1) / ns;
-    g->nsplit = (total_chunks + cps - 1) / cps;
+    // workgroups of a launch with wn weight blocks per workgroup once K is split to about one workgroup per compute unit
+    auto split_for = [&](int wn, int *wgs) {
+      int strips = (nblocks + wn - 1) / wn * (wide ? Mp / 256 : 1);
+      int ns = full_k ? 1 : (240 + strips / 2) / strips;
+      if (ns > total_chunks / 2) ns = total_chunks / 2;
+      if (ns > 10) ns = 10;
+      if (ns < 1) ns = 1;
+      int cps = (total_chunks + ns - 1) / ns;
+      ns = (total_chunks + cps - 1) / cps;
+      *wgs = strips * ns;
+      return ns;
+    };
+    g->waves_n = wide || nblocks % 4 == 0 || nblocks > 96 ? 4 : 3;
+    int wgs = 0;
+    g->nsplit = split_for(g->waves_n, &wgs);
+    // A narrow output with four blocks per workgroup can leave a third of the chip without a workgroup however K is split
+    // (2560 columns: 20 strips x 8 runs = 160); three blocks give 27 strips and 216 workgroups (measured at 64 rows on the
+    // 4B shape, output and down projection together: decode step 3.764 -> 3.741 ms; where the gain in workgroups is small --
+    // 6144 columns, 240 -> 256 -- nothing moves).  Never past one workgroup per compute unit.
+    if (!full_k && !wide && Mp <= 64 && g->waves_n == 4) {
+      int wgs3 = 0, ns3 = split_for(3, &wgs3);
+      if (wgs3 <= 256 && wgs3 * 20 >= wgs * 23) { g->waves_n = 3; g->nsplit = ns3; }
+    }
     return;
   }
   g->nbw = 1;
