@@ -21,12 +21,12 @@ HBM_PEAK_GBS = 8000.0
 # counters on a plain 256 MiB copy: KiB fetched + written per launch over the KiB of the K/V tiles the launch touches
 # (shared prompt tiles once per group, a sequence's last tile whole).  Taken at the same kernel and grid on a 2-layer
 # model generating 64 tokens (the profiler crashes on the 36-layer process); set to None whenever attn_rows_kernel changes.
-ATTN_TRAFFIC_OVER_TILE_BYTES = (29521.6 + 512.0) / (28608.0 + 512.0)
+ATTN_TRAFFIC_OVER_TILE_BYTES = (29524.2 + 512.0) / (28608.0 + 512.0)
 # The same kernel timed by rocprofv3 --kernel-trace inside the graph replays of this very command (config 2), in microseconds
 # per launch (profiles/kernel_trace_dense4b-64x512+1024.md): the HIP events of the timed run bracket launches that are issued
 # one by one and include the launch gap, so both figures go into the line.  None for any other workload, and whenever the
 # kernel changes.
-ATTN_KERNEL_TRACE_US = {"dense4b-64x512+1024": 31.45}
+ATTN_KERNEL_TRACE_US = {"dense4b-64x512+1024": 31.39}
 
 
 def attn_kv_bytes_per_launch(shape, gen_lens, prompt_len, group, steps, whole_tiles, shared_elsewhere=False):
@@ -326,7 +326,7 @@ def main():
             roofline = {"bound": "hbm", "kernel": kname,
                         "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
                         "traffic": traffic,
-                        "traffic_unit": "bytes per launch: whole K/V tiles of the timed launches x 1.0314 (FETCH_SIZE + WRITE_SIZE over "
+                        "traffic_unit": "bytes per launch: whole K/V tiles of the timed launches x 1.0315 (FETCH_SIZE + WRITE_SIZE over "
                                         "whole-tile bytes, same kernel and grid, profiles/pmc_traffic_*.md)",
                         "launches_timed": int(st.attn_launches),
                         "avg_launch_us": per_launch_s * 1e6, "bytes_per_launch": per_launch_bytes}
