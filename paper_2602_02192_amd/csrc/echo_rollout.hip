@@ -460,7 +460,8 @@ int echo_rollout_continuous(echo_ctx *c, const int32_t *prompt_tokens, int32_t p
   const bool use_graph = !o.no_graph;
   c->attn_plain = o.attn_plain != 0;
   // rows of unequal lengths: workgroups of several rows, one per compute unit, would finish at very different times
-  // (measured 22.7 k tokens/s against 25.5 k with the once-per-group kernel at 256 rows), so only on request
+  // (measured 22.7 k tokens/s against 25.5 k with the once-per-group kernel at 256 rows), so unless asked for that form is
+  // taken only while the live rows sit at about the same position (decided whenever the rows change, below)
   c->attn_mode = o.prefix_kernel == 0 ? 1 : o.prefix_kernel;
   const bool share_prefix = p.fast && !o.own_prompt_copy && !o.attn_plain;
   const bool splitk = !o.attn_plain;
@@ -601,7 +602,15 @@ int echo_rollout_continuous(echo_ctx *c, const int32_t *prompt_tokens, int32_t p
       }
       if (dirty) {   // the rows changed: plan the shared-prompt attention for them, then put the row state on the device
         std::vector<int32_t> live(R, 0);
-        for (int r = 0; r < Rc; ++r) live[r] = row_seq[r] >= 0 && act[r];
+        int pos_lo = INT32_MAX, pos_hi = 0;
+        for (int r = 0; r < Rc; ++r) {
+          live[r] = row_seq[r] >= 0 && act[r];
+          if (live[r]) { pos_lo = std::min(pos_lo, pos[r]); pos_hi = std::max(pos_hi, pos[r]); }
+        }
+        if (o.prefix_kernel == 0) {   // several rows per decode-attention workgroup only while their lengths are within an eighth
+          const int mode = pos_hi >= pos_lo && (pos_hi - pos_lo) * 8 <= pos_hi ? 0 : 1;
+          if (mode != c->attn_mode) { c->attn_mode = mode; have_graph = false; }
+        }
         const PrefixPlan was = c->px;
         if ((rc = plan_prefix_jobs(c, ptiles, pslot, live, Rc, share_prefix ? (max_pl - 1) / 32 : 0, Rc / 2 + 1, o.prefix_kernel))) return rc;
         if (was.n_jobs != c->px.n_jobs || was.np != c->px.np || was.tiles_per_chunk != c->px.tiles_per_chunk) have_graph = false;
