@@ -116,9 +116,91 @@ __global__ void qkv_post_kernel(const float *partials, int nsplit, int Np, int M
   }
 }
 
+// The same for batches of hundreds of rows and more (prefill, scoring, wide decode steps), where the kernel above is a
+// launch of millions of threads that move 14 bytes each: here a thread takes four consecutive dims of the head's first half
+// and their four rotation partners, with 16-byte loads of the partials and of the rotation table and 8-byte stores of q and
+// of the key tile (a value tile holds eight keys of one dim per unit, so values still leave as single halves).  Same sums in
+// the same order: bit-identical to the kernel above.  grid (M, ceil((Hq + 2*Hkv) / QPW_HEADS)), block QPW_HEADS * hd/8.
+constexpr int QPW_HEADS = 16;
+__global__ void qkv_post_wide_kernel(const float *partials, int nsplit, int Np, int Mp, uint16_t *q_out, const uint16_t *q_gain,
+                                     const uint16_t *k_gain, int qk_norm, float eps, const float2 *rope_cs, RowState rows,
+                                     KvGeom kv, int layer, int Hq, int Hkv) {
+  const int hd = kv.head_dim, half = hd / 2, per_head = half / 4;
+  const int m = blockIdx.x, j = blockIdx.y * QPW_HEADS + threadIdx.x / per_head, i = (threadIdx.x % per_head) * 4;
+  if (j >= Hq + 2 * Hkv) return;
+  const bool is_q = j < Hq, is_k = !is_q && j < Hq + Hkv;
+  if (!is_q && !rows.active[m]) return;
+  const int n0 = j * hd + i, n1 = n0 + half;
+  f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f}, pa[REDUCE_MAX_SPLIT], pb[REDUCE_MAX_SPLIT];
+#pragma unroll
+  for (int s = 0; s < REDUCE_MAX_SPLIT; ++s) {   // all loads issued before the sums
+    const float *row = partials + ((int64_t)s * Mp + m) * Np;
+    pa[s] = s < nsplit ? *(const f32x4 *)(row + n0) : f32x4{0.f, 0.f, 0.f, 0.f};
+    pb[s] = s < nsplit ? *(const f32x4 *)(row + n1) : f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+#pragma unroll
+  for (int s = 0; s < REDUCE_MAX_SPLIT; ++s) { a += pa[s]; b += pb[s]; }
+  if (is_q || is_k) {
+    if (qk_norm) {
+      // Summed in the order of the one-pair-per-lane kernel, whose tree adds lane i ^ off to lane i for off = half/2 .. 1:
+      // its lanes 4q .. 4q+3 sit in this thread, so its offsets >= 4 are shuffles over the head's threads, element by
+      // element, and its offsets 2 and 1 are the local sums at the end.
+      float t[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) t[e] = a[e] * a[e] + b[e] * b[e];
+      for (int off = per_head >> 1; off > 0; off >>= 1) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t[e] += __shfl_xor(t[e], off);
+      }
+      const float ss = (t[0] + t[2]) + (t[1] + t[3]);
+      float inv = 1.0f / sqrtf(ss / (float)hd + eps);
+      const uint16_t *g = is_q ? q_gain : k_gain;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { a[e] = a[e] * inv * bf16_bits_to_f32(g[i + e]); b[e] = b[e] * inv * bf16_bits_to_f32(g[i + e + half]); }
+    }
+    const f32x4 *cs = (const f32x4 *)(rope_cs + (int64_t)m * half + i);
+    const f32x4 c01 = cs[0], c23 = cs[1];
+    const float cx[4] = {c01[0], c01[2], c23[0], c23[2]}, sy[4] = {c01[1], c01[3], c23[1], c23[3]};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float ra = a[e] * cx[e] - b[e] * sy[e], rb = a[e] * sy[e] + b[e] * cx[e];
+      a[e] = ra; b[e] = rb;
+    }
+  }
+  uint2 ha, hb;
+  ha.x = (uint32_t)f32_to_h16_bits(a[0]) | ((uint32_t)f32_to_h16_bits(a[1]) << 16);
+  ha.y = (uint32_t)f32_to_h16_bits(a[2]) | ((uint32_t)f32_to_h16_bits(a[3]) << 16);
+  hb.x = (uint32_t)f32_to_h16_bits(b[0]) | ((uint32_t)f32_to_h16_bits(b[1]) << 16);
+  hb.y = (uint32_t)f32_to_h16_bits(b[2]) | ((uint32_t)f32_to_h16_bits(b[3]) << 16);
+  if (is_q) {
+    uint16_t *dst = q_out + ((int64_t)m * Hq + j) * hd;
+    *(uint2 *)(dst + i) = ha;
+    *(uint2 *)(dst + i + half) = hb;
+  } else {
+    const int kvh = is_k ? j - Hq : j - Hq - Hkv, pos = rows.pos[m];
+    uint16_t *head = (uint16_t *)kv.base + kv.tiled_head_off(rows.slot[m], layer, kvh);
+    if (is_k) {   // four dims of one 8-dim unit of the key
+      *(uint2 *)(head + kv.tiled_k_off(pos, i)) = ha;
+      *(uint2 *)(head + kv.tiled_k_off(pos, i + half)) = hb;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        head[kv.tiled_v_off(pos, i + e)] = f32_to_h16_bits(a[e]);
+        head[kv.tiled_v_off(pos, i + e + half)] = f32_to_h16_bits(b[e]);
+      }
+    }
+  }
+}
+
 void fast_qkv_post(const float *partials, int nsplit, int Np, int Mp, void *q_h16, const void *q_gain, const void *k_gain,
                    int qk_norm, float eps, const float *rope_cs, RowState rows, KvGeom kv, int layer, int M, int Hq, int Hkv,
                    hipStream_t st) {
+  if (M >= 256) {
+    hipLaunchKernelGGL(qkv_post_wide_kernel, dim3(M, (Hq + 2 * Hkv + QPW_HEADS - 1) / QPW_HEADS), dim3(QPW_HEADS * kv.head_dim / 8), 0, st, partials,
+                       nsplit, Np, Mp, (uint16_t *)q_h16, (const uint16_t *)q_gain, (const uint16_t *)k_gain, qk_norm, eps,
+                       (const float2 *)rope_cs, rows, kv, layer, Hq, Hkv);
+    return;
+  }
   hipLaunchKernelGGL(qkv_post_kernel, dim3(M, (Hq + 2 * Hkv + QP_HEADS - 1) / QP_HEADS), dim3(QP_HEADS * kv.head_dim / 2), 0, st, partials, nsplit, Np, Mp,
                      (uint16_t *)q_h16, (const uint16_t *)q_gain, (const uint16_t *)k_gain, qk_norm, eps,
                      (const float2 *)rope_cs, rows, kv, layer, Hq, Hkv);
