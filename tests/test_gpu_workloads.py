@@ -18,10 +18,12 @@ pytestmark = pytest.mark.gpu
 MID = synth.ModelShape(2, 512, 8, 2, 128, 1024, 2048, dtype="bf16")
 
 
-@pytest.mark.parametrize("n_prompts,G", [(16, 8), (32, 8), (5, 3)])
+@pytest.mark.parametrize("n_prompts,G", [(16, 8), (32, 8), (5, 3), (40, 8)])
 def test_wide_batches_with_ragged_stops_match_oracle(n_prompts, G):
-    """128 and 256 sequences (the row counts of the 8B and the KV-heavy workloads) and an odd 15: ragged
-    prompts, per-sequence stop lengths, finished rows dropping out while the others go on."""
+    """128 and 256 sequences (the row counts of the 8B and the KV-heavy workloads), an odd 15 and 320: ragged
+    prompts, per-sequence stop lengths, finished rows dropping out while the others go on.  With this shape's two KV
+    heads the decode attention takes several rows per workgroup from 256 rows on: two at 256, and at 320 sets of two and
+    three rows that straddle the groups of eight, re-dealt every step as sequences stop."""
     shape = MID
     N = n_prompts * G
     blob = synth.make_weights(shape, 3)
