@@ -184,3 +184,27 @@ def make_turn_records(n_seqs: int, stride: int, vocab: int, turn_start_id: int, 
     else:
         rewards = rng.normal(3.0, 40.0, n_seqs).astype(np.float32)
     return toks.astype(np.int32), lens, rewards
+
+
+def make_q8_weights(s: ModelShape, seed: int) -> np.ndarray:
+    """A quantised snapshot blob (uint8) for a bf16 shape, in the layout of echo_load_policy_q8: tensors in blob order,
+    gains as bf16 ones, every matrix [rows, K] as rows fp32 scales followed by rows * K int8 codes.  Codes are
+    round(N(0, 42^2)) clipped to [-127, 127] and scales uniform in [0.5, 1.5] * 0.02 / 42, so the weights they stand for
+    look like the N(0, 0.02^2) weights of the other generators.  Random bytes only: what the codes mean is the
+    library's and the oracle's business."""
+    assert s.dtype == "bf16"
+    rng = np.random.default_rng(seed)
+    parts = []
+    for _, shape, is_gain in tensor_table(s):
+        if len(shape) == 1:
+            assert is_gain
+            parts.append(np.full(shape[0], 0x3F80, "<u2").view(np.uint8))
+            continue
+        rows, k = shape
+        parts.append(((0.5 + rng.random(rows)) * (0.02 / 42.0)).astype("<f4").view(np.uint8))
+        step = max(1, (1 << 26) // k)
+        for a in range(0, rows, step):
+            b = min(rows, a + step)
+            c = np.clip(np.rint(rng.standard_normal((b - a, k), np.float32) * 42.0), -127, 127).astype(np.int8)
+            parts.append(c.reshape(-1).view(np.uint8))
+    return np.concatenate(parts)
