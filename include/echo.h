@@ -172,6 +172,19 @@ int echo_load_policy_abort(echo_ctx *ctx);
 int echo_load_policy_delta(echo_ctx *ctx, int64_t base_version, int64_t version, int32_t n_ranges, const uint64_t *offsets,
                            const uint64_t *sizes, const void *host_data);
 
+/* Install snapshot `version` from a quantised blob (the "Limitations and Future Work" section names quantised updates,
+ * next to delta updates, as the way to cut snapshot traffic; it gives no format, this is the library's): the tensors of
+ * the echo_load_policy blob in the same order; a vector (norm gain) as bf16, unchanged; a matrix [rows, K] as `rows`
+ * little-endian fp32 scales followed by rows * K int8 codes, row-major.  The weight a code stands for is the bf16 value
+ * nearest (ties to even) to float(code) * scale of its row, one fp32 product.  host_blob (host, nbytes =
+ * echo_q8_blob_bytes: about half the bf16 blob) may be freed when the call returns.  Codes and scales are copied to the
+ * GPU as they are, turned into bf16 rows and packed on the copy stream, so the PCIe traffic is that of the quantised
+ * blob; the result is bit for bit the snapshot echo_load_policy leaves for the dequantised bf16 blob, and it becomes
+ * active or staged exactly as there, with the same errors.  Needs dtype = ECHO_BF16 without debug_naive (ECHO_EINVAL
+ * otherwise, and for a wrong size); echo_q8_blob_bytes returns 0 for an invalid shape or another dtype. */
+size_t echo_q8_blob_bytes(const echo_model_desc *desc);
+int echo_load_policy_q8(echo_ctx *ctx, int64_t version, const void *host_blob, size_t nbytes);
+
 /* Generate G samples for each of n_prompts prompts (sequence n = p*G + g) by ancestral sampling from
  * softmax(logits / temperature) (Algorithm 1, "sample and generate y ~ pi(.|x)"), up to max_new tokens each.
  * The draw for vocabulary entry i of sequence n at step s is the Gumbel-max rule on a counter-based uniform

@@ -117,6 +117,41 @@ int patch_segments(echo_ctx *c, std::vector<BlobSeg> &segs, const char *data, si
   return 0;
 }
 
+// Bytes [lo, lo + n) of the bf16 blob sit at device address `dev` (whole rows of every matrix they touch): copy or pack
+// them into every segment they cover, on the copy stream.
+int feed_device(echo_ctx *c, std::vector<BlobSeg> &segs, const char *dev, size_t lo, size_t n) {
+  const size_t hi = lo + n;
+  for (BlobSeg &g : segs) {
+    size_t a = std::max(lo, g.off), b = std::min(hi, g.off + g.bytes);
+    if (a >= b) continue;
+    const char *src = dev + (a - lo);
+    if (g.rows == 0) {
+      HIPCHK(c, hipMemcpyAsync(g.dst + (a - g.off), src, b - a, hipMemcpyDeviceToDevice, c->ks));
+      continue;
+    }
+    const size_t row_bytes = (size_t)g.K * 2;
+    if ((a - g.off) % row_bytes || (b - a) % row_bytes) return fail(c, ECHO_EINVAL, "internal: a device piece cuts a matrix row");
+    const int Np = (int)round_up(g.rows * g.stride, 32), Kp = (int)round_up(g.K, GEMM_K_PAD);
+    fast_pack_weight(g.dst, src, g.dst_row0 + (int64_t)((a - g.off) / row_bytes) * g.stride, g.stride, (int64_t)((b - a) / row_bytes), g.K, Kp, Np, c->ks);
+  }
+  return 0;
+}
+
+// The tensors of a blob in order: (rows, K), rows == 0 for a vector of K elements.
+std::vector<std::pair<int64_t, int64_t>> blob_tensors(const echo_model_desc &d) {
+  const int64_t H = d.hidden, hd = d.head_dim, Q = (int64_t)d.n_q_heads * hd, KV = (int64_t)d.n_kv_heads * hd, F = d.ffn, V = d.vocab;
+  std::vector<std::pair<int64_t, int64_t>> t;
+  t.push_back({V, H});
+  for (int l = 0; l < d.n_layers; ++l) {
+    t.push_back({0, H}); t.push_back({Q, H}); t.push_back({KV, H}); t.push_back({KV, H});
+    if (d.qk_norm) { t.push_back({0, hd}); t.push_back({0, hd}); }
+    t.push_back({H, Q}); t.push_back({0, H}); t.push_back({F, H}); t.push_back({F, H}); t.push_back({H, F});
+  }
+  t.push_back({0, H});
+  if (!d.tie_embeddings) t.push_back({V, H});
+  return t;
+}
+
 // The snapshot in slot `target` is complete on the copy stream: make it the active or the staged one.
 int commit_slot(echo_ctx *c, int target, int64_t version) {
   HIPCHK(c, hipEventRecord(c->staged_ev, c->ks));
@@ -197,6 +232,63 @@ int echo_load_policy_delta(echo_ctx *c, int64_t base_version, int64_t version, i
   }
   int rc = commit_slot(c, target, version);
   return rc ? undo(rc) : ECHO_OK;
+}
+
+size_t echo_q8_blob_bytes(const echo_model_desc *desc) {
+  if (!valid_desc(desc, nullptr) || desc->dtype != ECHO_BF16) return 0;
+  size_t n = 0;
+  for (auto &t : blob_tensors(*desc)) n += t.first == 0 ? (size_t)t.second * 2 : (size_t)t.first * 4 + (size_t)t.first * t.second;
+  return n;
+}
+
+int echo_load_policy_q8(echo_ctx *c, int64_t version, const void *host_blob, size_t nbytes) {
+  if (!c) return ECHO_EINVAL;
+  if (!host_blob) return fail(c, ECHO_EINVAL, "host_blob is NULL");
+  if (!c->p.fast) return fail(c, ECHO_EINVAL, "a quantised snapshot stands for bf16 weights and is unpacked through the MFMA path's staging buffer: the model dtype must be ECHO_BF16, without debug_naive");
+  if (nbytes != echo_q8_blob_bytes(&c->d)) return fail(c, ECHO_EINVAL, "quantised blob has %zu bytes, this shape needs %zu", nbytes, echo_q8_blob_bytes(&c->d));
+  int rc = echo_load_policy_begin(c, version, echo_blob_bytes(&c->d));
+  if (rc) return rc;
+  auto run = [&]() -> int {
+    HIPCHK(c, hipSetDevice(c->device));
+    const char *src = (const char *)host_blob;
+    size_t bf_off = 0;   // where the tensor starts in the bf16 blob it stands for
+    const size_t half = c->p.stage_bytes / 2;
+    auto stage = [&]() { char *p = c->arena + c->p.o_stage + (c->stage_flip ? half : 0); c->stage_flip ^= 1; return p; };
+    // The copy stream runs in order, so a half of the staging buffer is free again by the time the copy that refills it
+    // is reached; only the host blob must stay until the end, which the commit waits for.
+    for (auto &t : blob_tensors(c->d)) {
+      const int64_t rows = t.first, K = t.second;
+      if (rows == 0) {
+        char *stg = stage();
+        HIPCHK(c, hipMemcpyAsync(stg, src, (size_t)K * 2, hipMemcpyHostToDevice, c->ks));
+        if ((rc = feed_device(c, c->load.segs, stg, bf_off, (size_t)K * 2))) return rc;
+        src += K * 2; bf_off += (size_t)K * 2;
+        continue;
+      }
+      // per batch of rows: [bf16 rows out | scales | codes] in one half of the staging buffer
+      const int64_t per = std::max<int64_t>(1, (int64_t)((half - 512) / (size_t)(3 * K + 4)));
+      const char *scales = src, *codes = src + rows * 4;
+      for (int64_t r = 0; r < rows; r += per) {
+        const int64_t n = std::min(per, rows - r);
+        char *stg = stage();
+        char *d_scales = stg + round_up(n * K * 2, 256), *d_codes = d_scales + round_up(n * 4, 256);
+        HIPCHK(c, hipMemcpyAsync(d_scales, scales + r * 4, (size_t)n * 4, hipMemcpyHostToDevice, c->ks));
+        HIPCHK(c, hipMemcpyAsync(d_codes, codes + r * K, (size_t)(n * K), hipMemcpyHostToDevice, c->ks));
+        fast_dequant_q8(stg, d_codes, d_scales, n, (int)K, c->ks);
+        if ((rc = feed_device(c, c->load.segs, stg, bf_off + (size_t)(r * K * 2), (size_t)(n * K * 2)))) return rc;
+      }
+      src += rows * 4 + rows * K; bf_off += (size_t)(rows * K * 2);
+    }
+    HIPCHK(c, hipStreamSynchronize(c->ks));
+    c->load.received = c->load.total;
+    return echo_load_policy_commit(c);
+  };
+  if ((rc = run())) {
+    std::string msg = c->err;
+    echo_load_policy_abort(c);
+    c->err = msg;
+  }
+  return rc;
 }
 
 int echo_load_policy_begin(echo_ctx *c, int64_t version, size_t nbytes) {

@@ -104,6 +104,8 @@ void fast_pack_weight(void *dst, const void *src, int64_t dst_row0, int dst_row_
 // The same for a span of elements [e0, e0 + n) of the row-major matrix (src holds those n values only): a delta install.
 void fast_pack_span(void *dst, const void *src, int64_t e0, int64_t n, int64_t dst_row0, int dst_row_stride, int K, int Kp, int Np,
                     hipStream_t st);
+// rows x K int8 codes with one fp32 scale per row -> row-major bf16 [rows][K] (any path; out, codes, scales on the device).
+void fast_dequant_q8(void *out_bf16, const void *codes, const void *scales, int64_t rows, int K, hipStream_t st);
 // h = embed[token] (first layer) or h += sum_s P[s] (+0); then x = rmsnorm(h)*gain -> Xp (half K8).
 void fast_resid_norm(float *h, const void *embed_bf16, const int32_t *token, const float *partials, int nsplit,
                      int Np, void *Xp, const void *gain_bf16, int M, int Mp, int d, float eps, hipStream_t st);

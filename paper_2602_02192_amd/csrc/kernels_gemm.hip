@@ -68,6 +68,22 @@ void fast_pack_span(void *dst, const void *src, int64_t e0, int64_t n, int64_t d
                      dst_row0, dst_row_stride, K, Kp / 8, Np);
 }
 
+// A quantised matrix (per-row fp32 scale, int8 codes) back to row-major bf16: the bf16 value nearest to float(code) * scale,
+// computed as one fp32 product, ties to even.  One thread per code.
+__global__ void dequant_q8_kernel(uint16_t *__restrict__ out, const int8_t *__restrict__ codes, const float *__restrict__ scales,
+                                  int64_t n, int K) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  out[i] = f32_to_bf16_bits(__fmul_rn((float)codes[i], scales[i / K]));
+}
+
+void fast_dequant_q8(void *out_bf16, const void *codes, const void *scales, int64_t rows, int K, hipStream_t st) {
+  const int64_t n = rows * K;
+  if (n <= 0) return;
+  hipLaunchKernelGGL(dequant_q8_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (uint16_t *)out_bf16, (const int8_t *)codes,
+                     (const float *)scales, n, K);
+}
+
 // ---- the MFMA inner loop -------------------------------------------------------------------------------
 // A wavefront owns NBW consecutive 32-row weight blocks and all MB 32-row batch blocks of its launch slice:
 // per k-step it reads NBW KiB of weights and MB KiB of activations, so activation traffic from L2 per weight

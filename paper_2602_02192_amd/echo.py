@@ -50,7 +50,7 @@ class Stats(C.Structure):
 
 
 EXPORTS = ["echo_arena_bytes", "echo_blob_bytes", "echo_init", "echo_load_policy", "echo_load_policy_begin",
-           "echo_load_policy_chunk", "echo_load_policy_commit", "echo_load_policy_abort", "echo_load_policy_delta", "echo_rollout", "echo_rollout_continuous",
+           "echo_load_policy_chunk", "echo_load_policy_commit", "echo_load_policy_abort", "echo_load_policy_delta", "echo_q8_blob_bytes", "echo_load_policy_q8", "echo_rollout", "echo_rollout_continuous",
            "echo_logprobs", "echo_grpo_tensors", "echo_grpo_tensors_static", "echo_debug_draw_bits", "echo_stats", "echo_step_times", "echo_last_error", "echo_destroy"]
 
 lib.echo_arena_bytes.restype = C.c_size_t
@@ -64,6 +64,9 @@ lib.echo_load_policy_begin.argtypes = [C.c_void_p, C.c_int64, C.c_size_t]
 lib.echo_load_policy_chunk.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
 lib.echo_load_policy_commit.argtypes = [C.c_void_p]
 lib.echo_load_policy_abort.argtypes = [C.c_void_p]
+lib.echo_q8_blob_bytes.restype = C.c_size_t
+lib.echo_q8_blob_bytes.argtypes = [C.POINTER(ModelDesc)]
+lib.echo_load_policy_q8.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t]
 lib.echo_load_policy_delta.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
 lib.echo_rollout.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                              C.c_float, C.c_uint64, C.POINTER(RolloutOpts), C.c_void_p, C.c_void_p, C.c_void_p,
@@ -103,6 +106,10 @@ def arena_bytes(desc: ModelDesc) -> int:
 
 def blob_bytes(desc: ModelDesc) -> int:
     return int(lib.echo_blob_bytes(C.byref(desc)))
+
+
+def q8_blob_bytes(desc: ModelDesc) -> int:
+    return int(lib.echo_q8_blob_bytes(C.byref(desc)))
 
 
 def _ptr(a: Optional[np.ndarray]):
@@ -190,6 +197,11 @@ class Context:
         data = np.ascontiguousarray(np.frombuffer(data, np.uint8) if isinstance(data, (bytes, bytearray)) else data, np.uint8)
         assert offsets.shape == sizes.shape and data.size == int(sizes.sum())
         self._chk(lib.echo_load_policy_delta(self.h, base_version, version, offsets.size, _ptr(offsets), _ptr(sizes), _ptr(data)))
+
+    def load_policy_q8(self, version: int, blob) -> None:
+        """blob: numpy uint8 array in the quantised layout (per-row fp32 scales and int8 codes for every matrix)."""
+        blob = np.ascontiguousarray(blob, np.uint8)
+        self._chk(lib.echo_load_policy_q8(self.h, version, C.c_void_p(blob.ctypes.data), blob.nbytes))
 
     def load_policy_begin(self, version: int, nbytes: int) -> None:
         self._chk(lib.echo_load_policy_begin(self.h, version, nbytes))

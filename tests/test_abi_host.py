@@ -20,7 +20,7 @@ def echo():
 def _declared():
     text = open(os.path.join(ROOT, "include", "echo.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(echo_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(echo_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_entry_point(echo):
