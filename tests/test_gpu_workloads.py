@@ -202,10 +202,12 @@ def test_full_4096_row_pass_with_wide_tiles_and_a_pass_boundary_matches_the_orac
 
 
 GRP8 = synth.ModelShape(2, 512, 16, 2, 64, 1024, 2048, dtype="bf16")
+GRP1 = synth.ModelShape(2, 256, 4, 4, 64, 512, 1024, dtype="bf16")      # one query head per KV head
+GRP2 = synth.ModelShape(2, 512, 4, 2, 128, 1024, 1024, dtype="bf16")
 
 
-@pytest.mark.parametrize("shape,G,P", [(MID, 8, 21), (GRP8, 8, 21), (MID, 3, 54), (MID, 4, 5)],
-                         ids=["grp4-G8", "grp8-G8", "grp4-G3", "grp4-G4-keys-split-over-workgroups"])
+@pytest.mark.parametrize("shape,G,P", [(MID, 8, 21), (GRP8, 8, 21), (MID, 3, 54), (MID, 4, 5), (GRP1, 5, 13), (GRP2, 8, 9)],
+                         ids=["grp4-G8", "grp8-G8", "grp4-G3", "grp4-G4-keys-split-over-workgroups", "grp1-G5", "grp2-G8"])
 def test_group_shared_prompt_tiles(shape, G, P):
     """Decode attention reads the whole 32-key tiles of a prompt from the group's first cache slot (three cases with
     enough rows that every row's keys stay in one workgroup, one small batch whose keys are split over workgroups).  Prompt lengths below, at and between tile boundaries;
