@@ -184,6 +184,11 @@ int echo_load_policy_delta(echo_ctx *ctx, int64_t base_version, int64_t version,
  * otherwise, and for a wrong size); echo_q8_blob_bytes returns 0 for an invalid shape or another dtype. */
 size_t echo_q8_blob_bytes(const echo_model_desc *desc);
 int echo_load_policy_q8(echo_ctx *ctx, int64_t version, const void *host_blob, size_t nbytes);
+/* The same for a quantised blob that arrives in pieces (Sec. 4.2): echo_load_policy_q8_begin opens the load (nbytes =
+ * echo_q8_blob_bytes; checks, slot choice and errors as echo_load_policy_begin), then echo_load_policy_chunk takes the
+ * bytes of the quantised blob in order, in pieces of any size cut at any byte, and echo_load_policy_commit /
+ * echo_load_policy_abort end the load as for a bf16 blob.  Bit for bit the snapshot of the one-call form. */
+int echo_load_policy_q8_begin(echo_ctx *ctx, int64_t version, size_t nbytes);
 
 /* Generate G samples for each of n_prompts prompts (sequence n = p*G + g) by ancestral sampling from
  * softmax(logits / temperature) (Algorithm 1, "sample and generate y ~ pi(.|x)"), up to max_new tokens each.

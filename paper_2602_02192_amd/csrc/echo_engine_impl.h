@@ -47,7 +47,7 @@ struct Plan {
   size_t slot_bytes, o_slot[2], o_kv, kv_bytes;
   size_t o_h, o_x, o_qkv, o_att, o_gu, o_ff, o_logits, o_q16, o_xa, o_xatt, o_xff, o_part, o_rope, o_lmpart;
   size_t o_attn_o, o_attn_ml, o_topp, o_pjobs, o_aplan;
-  size_t o_blocks, o_rows, o_seq, o_samp, o_out_tok, o_out_lp, o_out_ver, o_forced, o_scal, o_first_h, o_stage, o_maps;
+  size_t o_blocks, o_rows, o_seq, o_samp, o_out_tok, o_out_lp, o_out_ver, o_forced, o_scal, o_first_h, o_stage, o_maps, o_qscales;
   size_t stage_bytes, part_floats, logit_rows = 0, total;
   int attn_chunk, attn_max_splits;
 };
@@ -137,6 +137,7 @@ Plan make_plan(const echo_model_desc *d) {
     p.o_attn_ml = b.take(Md * d->n_q_heads * (size_t)p.attn_max_splits * 2 * 4);
     p.stage_bytes = STAGE_BYTES;
     p.o_stage = b.take(p.stage_bytes);
+    p.o_qscales = b.take((size_t)std::max<int64_t>({V, Q + 2 * KV, 2 * F, H}) * 4);   // the row scales of the matrix a quantised load is in
   } else {
     p.o_x = b.take(M * H * 4);
     p.o_qkv = b.take(M * (Q + 2 * KV) * 4);
@@ -184,6 +185,11 @@ struct Loading {
   int target = -1;
   size_t received = 0, total = 0;
   std::vector<BlobSeg> segs;
+  // a quantised blob (echo_load_policy_q8_begin): where its byte stream stands
+  bool q8 = false;
+  std::vector<std::pair<int64_t, int64_t>> tensors;   // (rows, K) in blob order, rows == 0: a vector
+  size_t ti = 0, tb = 0, bf_off = 0;                  // tensor, byte inside its quantised form, its start in the bf16 blob
+  std::vector<char> carry;                            // a vector or a row of codes cut by the end of a piece
 };
 
 struct echo_ctx {

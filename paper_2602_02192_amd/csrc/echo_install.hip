@@ -152,6 +152,78 @@ std::vector<std::pair<int64_t, int64_t>> blob_tensors(const echo_model_desc &d) 
   return t;
 }
 
+// The next n bytes of a quantised blob have arrived at `data` (host).  Vectors and rows of codes move whole: what a piece
+// cuts waits in the carry buffer.  A matrix's scales go to their device buffer as they come; its codes are staged in batches
+// of rows, turned into bf16 rows next to them and fed on as the bytes of the bf16 blob they stand for.  Everything runs on
+// the copy stream, which is in order: a half of the staging buffer is free again when the copy that refills it is reached.
+int feed_q8(echo_ctx *c, const char *data, size_t n) {
+  Loading &L = c->load;
+  const size_t half = c->p.stage_bytes / 2;
+  auto stage = [&]() { char *p = c->arena + c->p.o_stage + (c->stage_flip ? half : 0); c->stage_flip ^= 1; return p; };
+  char *d_scales = c->arena + c->p.o_qscales;
+  // rows r0 .. r0 + nr - 1 of the current matrix, their codes at host address src
+  auto rows_in = [&](const char *src, int64_t r0, int64_t nr, int64_t K) -> int {
+    const int64_t per = std::max<int64_t>(1, (int64_t)((half - 256) / (size_t)(3 * K)));
+    for (int64_t r = 0; r < nr; r += per) {
+      const int64_t m = std::min(per, nr - r);
+      char *stg = stage(), *d_codes = stg + round_up(m * K * 2, 256);
+      HIPCHK(c, hipMemcpyAsync(d_codes, src + r * K, (size_t)(m * K), hipMemcpyHostToDevice, c->ks));
+      fast_dequant_q8(stg, d_codes, d_scales + (r0 + r) * 4, m, (int)K, c->ks);
+      int rc = feed_device(c, L.segs, stg, L.bf_off + (size_t)((r0 + r) * K * 2), (size_t)(m * K * 2));
+      if (rc) return rc;
+    }
+    return 0;
+  };
+  while (n > 0) {
+    if (L.ti >= L.tensors.size()) return fail(c, ECHO_EINVAL, "bytes past the end of the quantised blob");
+    const int64_t rows = L.tensors[L.ti].first, K = L.tensors[L.ti].second;
+    const size_t q_bytes = rows == 0 ? (size_t)K * 2 : (size_t)rows * 4 + (size_t)rows * K;
+    size_t take = 0;
+    if (rows == 0) {   // a vector: whole, through the carry buffer
+      take = std::min(n, q_bytes - L.tb);
+      L.carry.insert(L.carry.end(), data, data + take);
+      if (L.carry.size() == q_bytes) {
+        char *stg = stage();
+        HIPCHK(c, hipMemcpyAsync(stg, L.carry.data(), q_bytes, hipMemcpyHostToDevice, c->ks));
+        int rc = feed_device(c, L.segs, stg, L.bf_off, q_bytes);
+        if (rc) return rc;
+        HIPCHK(c, hipStreamSynchronize(c->ks));   // the carry buffer is reused
+        L.carry.clear();
+      }
+    } else if (L.tb < (size_t)rows * 4) {   // scales, cut anywhere
+      take = std::min(n, (size_t)rows * 4 - L.tb);
+      HIPCHK(c, hipMemcpyAsync(d_scales + L.tb, data, take, hipMemcpyHostToDevice, c->ks));
+    } else {   // codes
+      const size_t cb = L.tb - (size_t)rows * 4;   // position inside the codes; a partial row is in the carry buffer
+      if (!L.carry.empty()) {
+        take = std::min(n, (size_t)K - L.carry.size());
+        L.carry.insert(L.carry.end(), data, data + take);
+        if ((int64_t)L.carry.size() == K) {
+          int rc = rows_in(L.carry.data(), (int64_t)((cb - (L.carry.size() - take)) / K), 1, K);
+          if (rc) return rc;
+          HIPCHK(c, hipStreamSynchronize(c->ks));
+          L.carry.clear();
+        }
+      } else {
+        take = std::min(n, q_bytes - L.tb);
+        const int64_t whole = (int64_t)(take / K);
+        if (whole) {
+          int rc = rows_in(data, (int64_t)(cb / K), whole, K);
+          if (rc) return rc;
+        }
+        L.carry.assign(data + whole * K, data + take);
+      }
+    }
+    data += take; n -= take; L.tb += take;
+    if (L.tb == q_bytes) {   // the tensor is complete
+      L.bf_off += rows == 0 ? (size_t)K * 2 : (size_t)(rows * K * 2);
+      L.tb = 0;
+      ++L.ti;
+    }
+  }
+  return 0;
+}
+
 // The snapshot in slot `target` is complete on the copy stream: make it the active or the staged one.
 int commit_slot(echo_ctx *c, int target, int64_t version) {
   HIPCHK(c, hipEventRecord(c->staged_ev, c->ks));
@@ -241,49 +313,27 @@ size_t echo_q8_blob_bytes(const echo_model_desc *desc) {
   return n;
 }
 
-int echo_load_policy_q8(echo_ctx *c, int64_t version, const void *host_blob, size_t nbytes) {
+int echo_load_policy_q8_begin(echo_ctx *c, int64_t version, size_t nbytes) {
   if (!c) return ECHO_EINVAL;
-  if (!host_blob) return fail(c, ECHO_EINVAL, "host_blob is NULL");
   if (!c->p.fast) return fail(c, ECHO_EINVAL, "a quantised snapshot stands for bf16 weights and is unpacked through the MFMA path's staging buffer: the model dtype must be ECHO_BF16, without debug_naive");
   if (nbytes != echo_q8_blob_bytes(&c->d)) return fail(c, ECHO_EINVAL, "quantised blob has %zu bytes, this shape needs %zu", nbytes, echo_q8_blob_bytes(&c->d));
   int rc = echo_load_policy_begin(c, version, echo_blob_bytes(&c->d));
   if (rc) return rc;
-  auto run = [&]() -> int {
-    HIPCHK(c, hipSetDevice(c->device));
-    const char *src = (const char *)host_blob;
-    size_t bf_off = 0;   // where the tensor starts in the bf16 blob it stands for
-    const size_t half = c->p.stage_bytes / 2;
-    auto stage = [&]() { char *p = c->arena + c->p.o_stage + (c->stage_flip ? half : 0); c->stage_flip ^= 1; return p; };
-    // The copy stream runs in order, so a half of the staging buffer is free again by the time the copy that refills it
-    // is reached; only the host blob must stay until the end, which the commit waits for.
-    for (auto &t : blob_tensors(c->d)) {
-      const int64_t rows = t.first, K = t.second;
-      if (rows == 0) {
-        char *stg = stage();
-        HIPCHK(c, hipMemcpyAsync(stg, src, (size_t)K * 2, hipMemcpyHostToDevice, c->ks));
-        if ((rc = feed_device(c, c->load.segs, stg, bf_off, (size_t)K * 2))) return rc;
-        src += K * 2; bf_off += (size_t)K * 2;
-        continue;
-      }
-      // per batch of rows: [bf16 rows out | scales | codes] in one half of the staging buffer
-      const int64_t per = std::max<int64_t>(1, (int64_t)((half - 512) / (size_t)(3 * K + 4)));
-      const char *scales = src, *codes = src + rows * 4;
-      for (int64_t r = 0; r < rows; r += per) {
-        const int64_t n = std::min(per, rows - r);
-        char *stg = stage();
-        char *d_scales = stg + round_up(n * K * 2, 256), *d_codes = d_scales + round_up(n * 4, 256);
-        HIPCHK(c, hipMemcpyAsync(d_scales, scales + r * 4, (size_t)n * 4, hipMemcpyHostToDevice, c->ks));
-        HIPCHK(c, hipMemcpyAsync(d_codes, codes + r * K, (size_t)(n * K), hipMemcpyHostToDevice, c->ks));
-        fast_dequant_q8(stg, d_codes, d_scales, n, (int)K, c->ks);
-        if ((rc = feed_device(c, c->load.segs, stg, bf_off + (size_t)(r * K * 2), (size_t)(n * K * 2)))) return rc;
-      }
-      src += rows * 4 + rows * K; bf_off += (size_t)(rows * K * 2);
-    }
-    HIPCHK(c, hipStreamSynchronize(c->ks));
-    c->load.received = c->load.total;
-    return echo_load_policy_commit(c);
-  };
-  if ((rc = run())) {
+  Loading &L = c->load;   // open: this thread's until commit or abort
+  L.q8 = true;
+  L.total = nbytes;
+  L.tensors = blob_tensors(c->d);
+  L.ti = 0; L.tb = 0; L.bf_off = 0;
+  L.carry.clear();
+  return ECHO_OK;
+}
+
+int echo_load_policy_q8(echo_ctx *c, int64_t version, const void *host_blob, size_t nbytes) {
+  if (!c) return ECHO_EINVAL;
+  if (!host_blob) return fail(c, ECHO_EINVAL, "host_blob is NULL");
+  int rc = echo_load_policy_q8_begin(c, version, nbytes);
+  if (rc) return rc;
+  if ((rc = echo_load_policy_chunk(c, host_blob, nbytes)) || (rc = echo_load_policy_commit(c))) {
     std::string msg = c->err;
     echo_load_policy_abort(c);
     c->err = msg;
@@ -307,6 +357,7 @@ int echo_load_policy_begin(echo_ctx *c, int64_t version, size_t nbytes) {
   else return fail(c, ECHO_ESTATE, "installing during a rollout needs n_weight_slots = 2");
   c->load.open = true;  // from here on a rollout cannot start on the target slot
   c->load.version = version; c->load.target = target; c->load.received = 0; c->load.total = nbytes;
+  c->load.q8 = false;
   lk.unlock();
   auto undo = [&](int rc) { lk.lock(); c->load.open = false; if (target == c->active) { c->active = -1; c->st.active_version = -1; } return rc; };
   if (hipSetDevice(c->device) != hipSuccess) return undo(fail(c, ECHO_EHIP, "hipSetDevice failed"));
@@ -329,7 +380,7 @@ int echo_load_policy_chunk(echo_ctx *c, const void *data, size_t nbytes) {
       return fail(c, ECHO_EINVAL, "%zu bytes after %zu overrun the blob of %zu", nbytes, c->load.received, c->load.total);
   }
   HIPCHK(c, hipSetDevice(c->device));
-  int rc = feed_segments(c, c->load.segs, (const char *)data, c->load.received, nbytes);
+  int rc = c->load.q8 ? feed_q8(c, (const char *)data, nbytes) : feed_segments(c, c->load.segs, (const char *)data, c->load.received, nbytes);
   if (rc) return rc;
   HIPCHK(c, hipStreamSynchronize(c->ks));  // the piece may be freed when this call returns
   c->load.received += nbytes;

@@ -50,7 +50,7 @@ class Stats(C.Structure):
 
 
 EXPORTS = ["echo_arena_bytes", "echo_blob_bytes", "echo_init", "echo_load_policy", "echo_load_policy_begin",
-           "echo_load_policy_chunk", "echo_load_policy_commit", "echo_load_policy_abort", "echo_load_policy_delta", "echo_q8_blob_bytes", "echo_load_policy_q8", "echo_rollout", "echo_rollout_continuous",
+           "echo_load_policy_chunk", "echo_load_policy_commit", "echo_load_policy_abort", "echo_load_policy_delta", "echo_q8_blob_bytes", "echo_load_policy_q8", "echo_load_policy_q8_begin", "echo_rollout", "echo_rollout_continuous",
            "echo_logprobs", "echo_grpo_tensors", "echo_grpo_tensors_static", "echo_debug_draw_bits", "echo_stats", "echo_step_times", "echo_last_error", "echo_destroy"]
 
 lib.echo_arena_bytes.restype = C.c_size_t
@@ -67,6 +67,7 @@ lib.echo_load_policy_abort.argtypes = [C.c_void_p]
 lib.echo_q8_blob_bytes.restype = C.c_size_t
 lib.echo_q8_blob_bytes.argtypes = [C.POINTER(ModelDesc)]
 lib.echo_load_policy_q8.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t]
+lib.echo_load_policy_q8_begin.argtypes = [C.c_void_p, C.c_int64, C.c_size_t]
 lib.echo_load_policy_delta.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
 lib.echo_rollout.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                              C.c_float, C.c_uint64, C.POINTER(RolloutOpts), C.c_void_p, C.c_void_p, C.c_void_p,
@@ -202,6 +203,22 @@ class Context:
         """blob: numpy uint8 array in the quantised layout (per-row fp32 scales and int8 codes for every matrix)."""
         blob = np.ascontiguousarray(blob, np.uint8)
         self._chk(lib.echo_load_policy_q8(self.h, version, C.c_void_p(blob.ctypes.data), blob.nbytes))
+
+    def load_policy_q8_chunked(self, version: int, blob, chunk_sizes) -> None:
+        """The quantised blob handed over in pieces of the given byte sizes (cycled until the blob ends)."""
+        blob = np.ascontiguousarray(blob, np.uint8)
+        self._chk(lib.echo_load_policy_q8_begin(self.h, version, blob.nbytes))
+        try:
+            off, k = 0, 0
+            while off < blob.nbytes:
+                n = min(int(chunk_sizes[k % len(chunk_sizes)]), blob.nbytes - off)
+                self._chk(lib.echo_load_policy_chunk(self.h, C.c_void_p(blob.ctypes.data + off), n))
+                off += n
+                k += 1
+            self._chk(lib.echo_load_policy_commit(self.h))
+        except Exception:
+            lib.echo_load_policy_abort(self.h)
+            raise
 
     def load_policy_begin(self, version: int, nbytes: int) -> None:
         self._chk(lib.echo_load_policy_begin(self.h, version, nbytes))

@@ -69,6 +69,36 @@ def test_q8_install_equals_the_install_of_the_dequantised_blob(shape):
     b.close()
 
 
+@pytest.mark.parametrize("shape", [MID.replace(qk_norm=True), ODD, BIGV], ids=["mid-qknorm", "odd-sizes", "matrices-larger-than-the-staging-buffer"])
+def test_q8_blob_in_pieces_equals_the_one_call_install(shape):
+    """The quantised blob through echo_load_policy_q8_begin / _chunk / _commit with cuts inside scales, inside rows of
+    codes, inside gains and across several tensors: the same logits, bit for bit, as the one-call install; an aborted load
+    leaves the old snapshot in place (two weight slots) and its version can be offered again."""
+    from paper_2602_02192_amd import echo
+    q8 = synth.make_q8_weights(shape, 21)
+    a = make_ctx(shape, 6, 32)
+    a.load_policy_q8(0, q8)
+    ref = roll(a, shape)
+    a.close()
+    b = make_ctx(shape, 6, 32, slots=2)
+    for v, cuts in enumerate(([1, 2, 3, 997, 40001, 5, 262147], [q8.size // 3 + 1], [7], [1 << 20])):
+        if cuts == [7] and q8.size > 4e6:
+            continue                                  # seven-byte pieces of the large blob would take minutes
+        b.load_policy_q8_chunked(v, q8, cuts)
+        assert np.array_equal(roll(b, shape)["logits"], ref["logits"]), cuts
+    other = synth.make_q8_weights(shape, 22)
+    b.load_policy_begin(10, echo.blob_bytes(b.desc))   # a bf16 load opened and dropped, then a quantised one dropped half-way
+    b.load_policy_abort()
+    assert echo.lib.echo_load_policy_q8_begin(b.h, 10, other.size) == 0
+    assert echo.lib.echo_load_policy_chunk(b.h, other.ctypes.data, other.size // 2) == 0
+    assert echo.lib.echo_load_policy_commit(b.h) == echo.ECHO_ESTATE          # not all bytes are in
+    assert echo.lib.echo_load_policy_abort(b.h) == 0
+    assert np.array_equal(roll(b, shape)["logits"], ref["logits"])
+    b.load_policy_q8_chunked(10, other, [123457])
+    assert not np.array_equal(roll(b, shape)["logits"], ref["logits"])
+    b.close()
+
+
 def test_q8_install_during_a_rollout_is_staged_and_switched_in():
     """Two weight slots: the quantised snapshot is installed from another thread while the rollout runs and is switched in
     at the pinned step; the tokens after the switch carry its version."""
