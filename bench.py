@@ -350,7 +350,7 @@ def main():
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": 1e3 * total_s / a.steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16 MFMA operands, f32 accumulate (bf16 weights)" if shape.dtype == "bf16" else "f32", "data": "synthetic (random N(0,0.02) weights, uniform random prompt tokens)",
-        "config": {"workload": a.workload, "model": name, "sequences": N, "prompts": P, "group": G,
+        "config": {"workload": a.workload, "decoder_shape": name, "sequences": N, "prompts": P, "group": G,
                    "prompt_len": plen, "max_new": max_new, "temperature": 1.0, "top_p": wl.get("top_p", 1.0),
                    "stop_lens": list(wl["stop"]) if wl.get("stop") else None,
                    "sequences_decoding_together": wl.get("slots", N), "continuous": continuous},
